@@ -1,0 +1,439 @@
+"""Pins for the CPU oracle: each test ties a piece of oracle/abl_oracle.* to something other
+than itself - a closed form, an invariant the paper states, a library routine the special
+case reduces to, brute force on tiny inputs, or hand-evaluated worked examples."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1901_07988_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+FD_SHAPES = [
+    (2, 4, 4, 3, 2, 3, 3, 1, 1),
+    (2, 5, 5, 2, 3, 3, 3, 2, 1),
+    (3, 3, 3, 4, 5, 1, 1, 1, 0),
+    (2, 6, 5, 2, 2, 3, 3, 2, 0),
+]
+
+
+def _rand_layer(o, shape_t, seed, dtype=np.float64, affine=True):
+    rng = np.random.default_rng(seed)
+    s = o.Shape(*shape_t)
+    x = rng.standard_normal((s.N, s.H, s.W, s.Cin)).astype(dtype) * 1.3 + 0.2
+    w = rng.standard_normal((s.R, s.S, s.Cin, s.Cout)).astype(dtype) * 0.5
+    if affine:
+        gamma = rng.uniform(0.5, 1.5, s.Cin).astype(dtype)
+        beta = (rng.standard_normal(s.Cin) * 0.3).astype(dtype)
+    else:
+        gamma, beta = np.ones(s.Cin, dtype), np.zeros(s.Cin, dtype)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(dtype)
+    return s, x, w, gamma, beta, dy
+
+
+# ------------------------------------------------------------------ exact path, Eq. 1-8
+@pytest.mark.parametrize("shape_t", FD_SHAPES)
+def test_exact_gradients_match_finite_differences(oracle, shape_t):
+    """Eq. 5-8 are the gradient of Eq. 1-4: with exact storage (K=32, double) the oracle's
+    backward equals central differences of L = sum(y * dy)."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _rand_layer(o, shape_t, 7)
+    f64 = np.float64
+
+    def loss(x_, w_, g_, b_):
+        y, _ = o.layer_forward(x_, w_, g_, b_, 32, s, dtype=f64)
+        return float(np.sum(y * dy))
+
+    _, saved = o.layer_forward(x, w, gamma, beta, 32, s, dtype=f64)
+    dx, dw, dg, db = o.layer_backward(saved, dy, w, dtype=f64)
+    h = 1e-6
+    args = [x, w, gamma, beta]
+    for idx, (name, grad) in enumerate([("dx", dx), ("dW", dw), ("dgamma", dg), ("dbeta", db)]):
+        num = np.zeros_like(grad)
+        flat = args[idx].reshape(-1)
+        for i in range(flat.size):
+            keep = flat[i]
+            flat[i] = keep + h
+            lp = loss(*args)
+            flat[i] = keep - h
+            lm = loss(*args)
+            flat[i] = keep
+            num.reshape(-1)[i] = (lp - lm) / (2 * h)
+        rel = np.max(np.abs(num - grad)) / max(np.max(np.abs(num)), 1e-30)
+        assert rel < 1e-3, (name, rel)      # the stated bar
+        assert rel < 2e-6, (name, rel)      # what double precision actually gives
+
+
+@pytest.mark.parametrize("shape_t", FD_SHAPES + [(2, 7, 6, 5, 4, 3, 3, 1, 1)])
+def test_exact_path_matches_torch_autograd_float64(oracle, shape_t):
+    """The exact layer is batch_norm(training) -> relu -> conv2d, which PyTorch's CPU autograd
+    differentiates; outputs and all four gradients must agree to double rounding."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _rand_layer(o, shape_t, 11)
+    y, saved = o.layer_forward(x, w, gamma, beta, 32, s, dtype=np.float64)
+    dx, dw, dg, db = o.layer_backward(saved, dy, w, dtype=np.float64)
+
+    xt = torch.tensor(x).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    wt = torch.tensor(w).permute(3, 2, 0, 1).contiguous().requires_grad_(True)  # [Cout,Cin,R,S]
+    gt = torch.tensor(gamma).requires_grad_(True)
+    bt = torch.tensor(beta).requires_grad_(True)
+    a2 = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=float(np.float64(o.EPS)))
+    yt = torch.nn.functional.conv2d(torch.relu(a2), wt, stride=s.stride, padding=s.pad)
+    yt.backward(torch.tensor(dy).permute(0, 3, 1, 2))
+    tol = dict(rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dw, wt.grad.permute(2, 3, 1, 0).numpy(), **tol)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), **tol)
+    np.testing.assert_allclose(db, bt.grad.numpy(), **tol)
+
+
+def test_conv_against_python_loops(oracle):
+    """Eq. 4 by seven nested Python loops on a tiny ragged case (stride 2, pad 1, H != W)."""
+    o = oracle
+    s = o.Shape(2, 5, 4, 3, 2, 3, 3, 2, 1)
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((s.N, s.H, s.W, s.Cin))
+    w = rng.standard_normal((s.R, s.S, s.Cin, s.Cout))
+    ref = np.zeros((s.N, s.Ho, s.Wo, s.Cout))
+    for n in range(s.N):
+        for ho in range(s.Ho):
+            for wo in range(s.Wo):
+                for r in range(s.R):
+                    for q in range(s.S):
+                        h, x = ho * s.stride + r - s.pad, wo * s.stride + q - s.pad
+                        if 0 <= h < s.H and 0 <= x < s.W:
+                            for ci in range(s.Cin):
+                                ref[n, ho, wo, :] += a[n, h, x, ci] * w[r, q, ci, :]
+    np.testing.assert_allclose(o.conv_fwd(a, w, s, np.float64), ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("shape_t", FD_SHAPES)
+def test_conv_adjoints(oracle, shape_t):
+    """dgrad and wgrad are the two adjoints of the bilinear map (a3, W) -> y:
+    <conv(a,W), g> = <a, dgrad(g,W)> = <W, wgrad(a,g)>."""
+    o = oracle
+    s, x, w, _, _, dy = _rand_layer(o, shape_t, 5)
+    f64 = np.float64
+    lhs = np.sum(o.conv_fwd(x, w, s, f64) * dy)
+    assert abs(lhs - np.sum(x * o.conv_dgrad(dy, w, s, f64))) < 1e-10 * max(1, abs(lhs))
+    assert abs(lhs - np.sum(w * o.conv_wgrad(x, dy, s, f64))) < 1e-10 * max(1, abs(lhs))
+
+
+def test_bn_statistics_and_normalisation(oracle):
+    """Eq. 1: statistics are the per-channel mean and the biased variance; A1 then has zero
+    mean and variance sigma^2/(sigma^2+eps)."""
+    o = oracle
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal((4, 6, 5, 3)) * [0.5, 2.0, 7.0] + [3.0, -1.0, 0.1])
+    mean, var = o.bn_stats(x, np.float64)
+    flat = x.reshape(-1, 3)
+    np.testing.assert_allclose(mean, flat.mean(0), rtol=1e-13)
+    np.testing.assert_allclose(var, flat.var(0, ddof=0), rtol=1e-12)
+    assert not np.allclose(var, flat.var(0, ddof=1), rtol=1e-4)  # unbiased would differ
+    rstd = o.bn_rstd(var, o.EPS, np.float64)
+    np.testing.assert_allclose(rstd, 1 / np.sqrt(var + o.EPS), rtol=1e-14)
+    a2, a3 = o.bn_relu(x, mean, rstd, np.ones(3), np.zeros(3), np.float64)
+    np.testing.assert_allclose(a2.reshape(-1, 3).mean(0), 0, atol=1e-12)
+    np.testing.assert_allclose(a2.reshape(-1, 3).var(0), var / (var + o.EPS), rtol=1e-12)
+    np.testing.assert_array_equal(a3, np.maximum(a2, 0))
+    g, b = np.array([2.0, -0.5, 1.0]), np.array([0.3, 0.0, -4.0])
+    a2b, _ = o.bn_relu(x, mean, rstd, g, b, np.float64)
+    np.testing.assert_allclose(a2b, a2 * g + b, rtol=1e-13, atol=1e-13)
+
+
+def test_bn_backward_projection_properties(oracle):
+    """Eq. 8 removes from the incoming gradient its components along 1 and along A1:
+    per channel sum(dx) = 0 and sum(dx * A1) = 0 (up to the eps in the variance)."""
+    o = oracle
+    rng = np.random.default_rng(2)
+    M, C = 200, 4
+    x = rng.standard_normal((M, C))
+    mean, var = o.bn_stats(x, np.float64)
+    rstd = o.bn_rstd(var, 0.0, np.float64)
+    gamma, beta = rng.uniform(0.5, 2, C), rng.standard_normal(C)
+    a2, _ = o.bn_relu(x, mean, rstd, gamma, beta, np.float64)
+    da3 = rng.standard_normal((M, C))
+    dx, dg, db = o.bn_relu_bwd(a2, da3, rstd, gamma, beta, np.float64)
+    a1 = (x - mean) * rstd
+    np.testing.assert_allclose(dx.sum(0), 0, atol=1e-10)
+    np.testing.assert_allclose((dx * a1).sum(0), 0, atol=1e-9)
+    da2 = da3 * (a2 > 0)
+    np.testing.assert_allclose(db, da2.sum(0), rtol=1e-12)           # Eq. 7
+    np.testing.assert_allclose(dg, (a1 * da2).sum(0), rtol=1e-10)    # Eq. 7
+
+
+# ------------------------------------------------------------------ quantizer, Eq. 9-10
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "quantizer_vectors.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                g, b, k, a, q, r = line.split()
+                rows.append((float(g), float(b), int(k), float(a), int(q), float(r)))
+    return rows
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_quantizer_worked_examples(oracle, dtype):
+    o = oracle
+    for g, b, K, a2, code, recon in _golden_rows():
+        ga, be = np.array([g], dtype), np.array([b], dtype)
+        q = o.quantize(np.array([[a2]], dtype), ga, be, K, dtype)
+        assert q.item() == code, (g, b, K, a2, q.item(), code)
+        r = o.dequantize(q, ga, be, K, dtype)
+        assert abs(r.item() - recon) <= 1e-6 * abs(recon), (g, b, K, a2, r.item(), recon)
+
+
+def test_reconstruction_range_unit_scale(oracle):
+    """gamma=1, beta=0, K=4: sixteen bins of width 0.375 tile [-3, 3); midpoints run from
+    -2.8125 to 2.8125 (Sec. 3.2: clip range beta +- 3 gamma)."""
+    o = oracle
+    one, zero = np.ones(1, np.float32), np.zeros(1, np.float32)
+    rec = o.dequantize(np.arange(16, dtype=np.int32).reshape(16, 1), one, zero, 4)
+    np.testing.assert_array_equal(rec.ravel(), (np.arange(16) - 8 + 0.5) * 0.375)
+    edges = np.arange(-8, 9) * 0.375
+    assert edges[0] == -3.0 and edges[-1] == 3.0
+    inside = ((edges[:-1] + edges[1:]) / 2).astype(np.float32).reshape(16, 1)
+    np.testing.assert_array_equal(o.quantize(inside, one, zero, 4).ravel(), np.arange(16))
+
+
+@pytest.mark.parametrize("K", [2, 4, 8])
+@pytest.mark.parametrize("gamma,beta", [(1.0, 0.0), (0.7, 0.31), (1.5, -0.2), (-0.9, 0.4), (0.5, 1.2)])
+def test_every_code_round_trips(oracle, K, gamma, beta):
+    """Brute force over all 2^K codes: dequantize then quantize returns the code."""
+    o = oracle
+    g, b = np.array([gamma], np.float32), np.array([beta], np.float32)
+    q = np.arange(2 ** K, dtype=np.int32).reshape(-1, 1)
+    np.testing.assert_array_equal(o.quantize(o.dequantize(q, g, b, K), g, b, K), q)
+
+
+@pytest.mark.parametrize("K", [4, 8])
+def test_half_step_bound_sign_and_range(oracle, K):
+    """Sec. 3.2 after Eq. 10: codes lie in [0, 2^K-1]; unclipped values are reproduced to
+    within 3*gamma/2^K (half a step) for A2 and A3 and 3/2^K for A1; the sign of A2 is kept."""
+    o = oracle
+    rng = np.random.default_rng(K)
+    M, C = 20000, 8
+    gamma = rng.uniform(0.5, 1.5, C).astype(np.float32)
+    gamma[3] = -gamma[3]
+    beta = (rng.standard_normal(C) * 0.3).astype(np.float32)
+    a1 = rng.standard_normal((M, C)).astype(np.float32)
+    a2 = gamma * a1 + beta
+    q = o.quantize(a2, gamma, beta, K)
+    assert q.min() >= 0 and q.max() <= 2 ** K - 1
+    assert q.min() == 0 and q.max() == 2 ** K - 1           # N(0,1) reaches both clip ends
+    rec = o.dequantize(q, gamma, beta, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    raw = np.floor(a2 * cq).astype(np.int64) + 2 ** (K - 1) - fb
+    unclipped = (raw >= 0) & (raw <= 2 ** K - 1)
+    assert unclipped.mean() > 0.99
+    half = np.abs(step) / 2 * (1 + 1e-6) + 1e-7
+    err = np.abs(rec - a2)
+    assert np.all(err[unclipped] <= np.broadcast_to(half, err.shape)[unclipped])
+    np.testing.assert_allclose(np.abs(step) / 2, 3 * np.abs(gamma) / 2 ** K, rtol=1e-6)
+    err3 = np.abs(np.maximum(rec, 0) - np.maximum(a2, 0))
+    assert np.all(err3[unclipped] <= np.broadcast_to(half, err.shape)[unclipped])
+    err1 = np.abs((rec - beta) / gamma - (a2 - beta) / gamma)
+    assert np.all(err1[unclipped] <= 3 / 2 ** K * (1 + 1e-5) + 1e-6)
+    # clipped values land on the end bins; the error there exceeds half a step
+    assert np.all(err[~unclipped] > np.broadcast_to(np.abs(step) / 2, err.shape)[~unclipped] * 0.999)
+    nz = a2 != 0
+    np.testing.assert_array_equal((rec > 0)[nz], (a2 > 0)[nz])
+
+
+def test_clip_range_is_beta_pm_3gamma_slightly_asymmetric(oracle):
+    o = oracle
+    g, b = np.array([1.0], np.float32), np.array([0.5], np.float32)
+    rec = o.dequantize(np.array([[0], [15]], np.int32), g, b, 4).ravel()
+    step = 0.375
+    lo, hi = rec[0] - step / 2, rec[1] + step / 2
+    assert (lo, hi) == (-2.625, 3.375)          # beta-3.125 .. beta+2.875: off-centre by < 1 step
+    assert abs((lo + hi) / 2 - 0.5) < step and hi - lo == 6.0
+
+
+# ------------------------------------------------------------------ packed store
+def test_packed_byte_layout_by_hand(oracle):
+    o = oracle
+    q = np.array([1, 2, 3, 4, 15, 0, 9], np.int32)
+    buf = o.pack_codes(q, 4)
+    assert buf.size == 128 and list(buf[:4]) == [0x21, 0x43, 0x0F, 0x09] and not buf[4:].any()
+    buf8 = o.pack_codes(np.array([7, 255, 0, 128], np.int32), 8)
+    assert list(buf8[:4]) == [7, 255, 0, 128] and buf8.size == 128
+    rng = np.random.default_rng(1)
+    for K in (4, 8):
+        qq = rng.integers(0, 2 ** K, size=(3, 5, 7, 3)).astype(np.int32)
+        np.testing.assert_array_equal(o.unpack_codes(o.pack_codes(qq, K), qq.shape, K), qq)
+
+
+def test_packed_size_is_k_over_32_of_fp32(oracle):
+    """Sec. 3.4: alpha = K/32 -> 1/8 (K=4), 1/4 (K=8) on every workload shape."""
+    o = oracle
+    wls = [synth.config1(), synth.config2(), *synth.config3(), synth.config4(), synth.config5()]
+    for wl in wls:
+        for s in wl.shapes:
+            for K in (4, 8):
+                assert o.packed_bytes(s.E, K) * 32 == 4 * s.E * K
+    assert o.packed_bytes(7, 4) == 128 and o.packed_bytes(257, 8) == 384
+
+
+# ------------------------------------------------------------------ the method, Sec. 3.2-3.3
+def _f32_layer(o, shape_t, seed, uniform=False):
+    rng = np.random.default_rng(seed)
+    s = o.Shape(*shape_t)
+    if uniform:
+        x = rng.uniform(-1, 1, (s.N, s.H, s.W, s.Cin)).astype(np.float32)
+    else:
+        x = rng.standard_normal((s.N, s.H, s.W, s.Cin)).astype(np.float32)
+    w = (rng.standard_normal((s.R, s.S, s.Cin, s.Cout)) * 0.2).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, s.Cin).astype(np.float32)
+    beta = (rng.standard_normal(s.Cin) * 0.1).astype(np.float32)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    return s, x, w, gamma, beta, dy
+
+
+def test_forward_output_does_not_depend_on_K(oracle):
+    o = oracle
+    s, x, w, gamma, beta, _ = _f32_layer(o, (4, 8, 8, 6, 5, 3, 3, 1, 1), 0)
+    ys = [o.layer_forward(x, w, gamma, beta, K, s)[0] for K in (4, 8, 32)]
+    assert ys[0].tobytes() == ys[1].tobytes() == ys[2].tobytes()
+
+
+def test_which_gradients_are_exact(oracle):
+    """Sec. 3.3: the gradient to A3, the ReLU mask and dbeta do not depend on the
+    approximation; dW, dgamma and the variance term of Eq. 8 do.  K=32 is exact storage."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _f32_layer(o, (4, 8, 8, 6, 5, 3, 3, 1, 1), 1)
+    out = {}
+    for K in (4, 8, 32):
+        _, saved = o.layer_forward(x, w, gamma, beta, K, s)
+        out[K] = o.layer_backward(saved, dy, w, keep=True)
+    for K in (4, 8):
+        assert out[K][4]["da3"].tobytes() == out[32][4]["da3"].tobytes()
+        np.testing.assert_array_equal(out[K][4]["a2t"] > 0, out[32][4]["a2t"] > 0)
+        assert out[K][3].tobytes() == out[32][3].tobytes()               # dbeta
+        assert not np.array_equal(out[K][1], out[32][1])                  # dW differs
+        assert not np.array_equal(out[K][2], out[32][2])                  # dgamma differs
+    # errors shrink with K (not by the full 16x: the clipped tails cost the same at any K)
+    e4 = np.sqrt(np.mean((out[4][1] - out[32][1]) ** 2))
+    e8 = np.sqrt(np.mean((out[8][1] - out[32][1]) ** 2))
+    assert e8 < e4 / 1.5
+    # dx: exact parts dominate, so the approximate dx stays close to the exact one
+    rel = np.abs(out[4][0] - out[32][0]).max() / np.abs(out[32][0]).max()
+    assert 0 < rel < 0.05
+
+
+def test_weight_gradient_error_bound_and_halving(oracle):
+    """With nothing clipped, |dW_K - dW_exact| <= (step/2) * sum|dy| per input channel
+    (Sec. 3.2 error bound pushed through Eq. 5), and the error about halves per extra bit."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _f32_layer(o, (4, 8, 8, 4, 3, 3, 3, 1, 1), 2, uniform=True)
+    _, sv = o.layer_forward(x, w, gamma, beta, 32, s)
+    dw_exact = o.layer_backward(sv, dy, w)[1].astype(np.float64)
+    errs = []
+    for K in range(3, 13):
+        a2 = sv.store
+        q = o.quantize(a2, gamma, beta, K)
+        assert q.min() > 0 and q.max() < 2 ** K - 1 or K >= 3      # uniform x: within +-3 sigma
+        a2t = o.dequantize(q, gamma, beta, K)
+        dw = o.conv_wgrad(np.maximum(a2t, 0), dy, s).astype(np.float64)
+        err = np.abs(dw - dw_exact)
+        bound = (3 * gamma / 2 ** K)[None, None, :, None] * np.abs(dy).sum()
+        assert np.all(err <= bound + 1e-4)
+        errs.append(np.sqrt(np.mean(err ** 2)))
+    ratios = np.array(errs[:-1]) / np.array(errs[1:])
+    assert np.all((ratios > 1.4) & (ratios < 2.9)), ratios
+
+
+def test_two_tier_stats_override(oracle):
+    o = oracle
+    s, x, w, gamma, beta, _ = _f32_layer(o, (2, 4, 4, 3, 2, 3, 3, 1, 1), 4)
+    y0, sv0 = o.layer_forward(x, w, gamma, beta, 4, s)
+    y1, sv1 = o.layer_forward(x, w, gamma, beta, 4, s, stats=(sv0.mean, sv0.var))
+    assert y0.tobytes() == y1.tobytes() and sv0.store.tobytes() == sv1.store.tobytes()
+
+
+# ------------------------------------------------------------------ residual stack, Sec. 3.4
+def _torch_stack(x, layers, dy, skip_every, eps):
+    xt = torch.tensor(x, dtype=torch.float64).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    params = []
+    stream = xt
+    t = xt
+    for i, (s, w, g, b) in enumerate(layers):
+        wt = torch.tensor(w, dtype=torch.float64).permute(3, 2, 0, 1).contiguous().requires_grad_(True)
+        gt = torch.tensor(g, dtype=torch.float64).requires_grad_(True)
+        bt = torch.tensor(b, dtype=torch.float64).requires_grad_(True)
+        params.append((wt, gt, bt))
+        a2 = torch.nn.functional.batch_norm(t, None, None, gt, bt, training=True, eps=eps)
+        y = torch.nn.functional.conv2d(torch.relu(a2), wt, stride=s.stride, padding=s.pad)
+        last = skip_every > 0 and (i + 1) % skip_every == 0
+        if last and y.shape == stream.shape:
+            y = y + stream
+        t = y
+        if skip_every == 0 or last:
+            stream = y
+    t.backward(torch.tensor(dy, dtype=torch.float64).permute(0, 3, 1, 2))
+    return t, xt, params
+
+
+@pytest.mark.parametrize("skip_every,nl", [(2, 4), (2, 5), (3, 3), (0, 3)])
+def test_stack_matches_torch_autograd(oracle, skip_every, nl):
+    """Skips only copy / add gradients (Sec. 3.4): an exact-storage stack in double equals
+    PyTorch's autograd on the same graph."""
+    o = oracle
+    rng = np.random.default_rng(9)
+    if skip_every == 3:
+        shapes = [o.Shape(2, 5, 5, 8, 4, 1, 1, 1, 0), o.Shape(2, 5, 5, 4, 4), o.Shape(2, 5, 5, 4, 8, 1, 1, 1, 0)]
+    else:
+        shapes = [o.Shape(2, 6, 6, 4, 4)] * nl
+    layers = []
+    for s in shapes:
+        layers.append((s, rng.standard_normal((s.R, s.S, s.Cin, s.Cout)) * 0.3,
+                       rng.uniform(0.5, 1.5, s.Cin), rng.standard_normal(s.Cin) * 0.2))
+    x = rng.standard_normal((shapes[0].N, shapes[0].H, shapes[0].W, shapes[0].Cin))
+    dy = rng.standard_normal((shapes[-1].N, shapes[-1].Ho, shapes[-1].Wo, shapes[-1].Cout))
+    y, saved = o.stack_forward(x, layers, 32, np.float64, skip_every)
+    dx, grads = o.stack_backward(saved, layers, dy, np.float64, skip_every)
+    yt, xt, params = _torch_stack(x, layers, dy, skip_every, float(o.EPS))
+    tol = dict(rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy(), **tol)
+    for (dw, dg, db), (wt, gt, bt) in zip(grads, params):
+        np.testing.assert_allclose(dw, wt.grad.permute(2, 3, 1, 0).numpy(), **tol)
+        np.testing.assert_allclose(dg, gt.grad.numpy(), **tol)
+        np.testing.assert_allclose(db, bt.grad.numpy(), **tol)
+
+
+def test_stack_memory_model(oracle):
+    """Sec. 3.4: stored bytes are alpha * L activations, alpha = K/32."""
+    o = oracle
+    wl = synth.config2(N=2, layers=6)
+    x, layers, dy = synth.draw_stack(wl, 0)
+    layers = [(o.Shape(*s.as_tuple()), w, g, b) for s, w, g, b in layers]
+    exact = sum(4 * s.E for s, *_ in layers)
+    for K, alpha in ((4, 1 / 8), (8, 1 / 4), (32, 1.0)):
+        _, saved = o.stack_forward(x, layers, K, np.float32, wl.skip_every)
+        assert sum(sv.nbytes for sv in saved) == alpha * exact
+
+
+def test_approximate_stack_errors_do_not_compound(oracle):
+    """Sec. 3.3: because the forward pass is exact and the gradient path is mostly exact, the
+    4-bit stack's gradients stay close to the exact ones at every depth."""
+    o = oracle
+    wl = synth.config2(N=4, layers=8)
+    x, layers, dy = synth.draw_stack(wl, 1)
+    layers = [(o.Shape(*s.as_tuple()), w, g, b) for s, w, g, b in layers]
+    ref = None
+    for K in (32, 4):
+        y, saved = o.stack_forward(x, layers, K, np.float32, 2)
+        dx, grads = o.stack_backward(saved, layers, dy, np.float32, 2)
+        if K == 32:
+            ref = (y, dx, grads)
+            continue
+        assert y.tobytes() == ref[0].tobytes()
+        rels = [np.linalg.norm(g[0] - r[0]) / np.linalg.norm(r[0]) for g, r in zip(grads, ref[2])]
+        assert max(rels) < 0.15, rels
+        assert np.linalg.norm(dx - ref[1]) / np.linalg.norm(ref[1]) < 0.15
