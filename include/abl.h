@@ -1,0 +1,178 @@
+/* abl - approximate-activation backprop layer for AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Backprop with Approximate Activations for
+ * Memory-efficient Network Training" (Chakrabarti & Moseley, arXiv 1901.07988):
+ * one pre-activation layer  BatchNorm -> scale & bias -> ReLU -> convolution
+ * (Sec. 3.1, Eq. 1-4) whose forward pass is exact and keeps only a K-bit copy of
+ * the pre-ReLU activation A2 plus per-channel vectors (Sec. 3.2, Eq. 9), and whose
+ * backward pass (Eq. 5-8) is computed from that copy alone (Eq. 10).
+ *
+ * General rules, valid for every entry point unless it says otherwise:
+ *   - every tensor pointer is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned; the library allocates nothing, keeps no state, enqueues its
+ *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and never synchronises.  Shapes and sizes are host values.
+ *   - activations are fp32, NHWC ("first dim = sample, last dim = channel",
+ *     Sec. 3.1); conv weights are fp32 [R][S][Cin][Cout]; the linear transform of
+ *     Eq. 4 is a zero-padded cross-correlation without bias.
+ *   - the BN tensor of a layer is its input: M = N*H*W rows of Cin channels,
+ *     E = M*Cin elements.  Batch statistics use the biased variance, eps = 1e-5.
+ *   - K is 4 or 8.
+ *   - return value: ABL_OK or an ABL_ERR_* code; on error nothing was enqueued
+ *     (ABL_ERR_HIP: a launch failed, earlier launches of the call may have run).
+ *   - preconditions that are NOT checked: finite inputs, gamma != 0.
+ *
+ * Packed store (opaque to callers, specified because parity is on bytes):
+ * codes in flat NHWC element order; K=8: byte e = code e; K=4: byte e/2 holds
+ * code 2j in bits 0-3 and code 2j+1 in bits 4-7; zero padded to a multiple of
+ * 128 bytes.  `stats` = 8 planes of Cin 4-byte values:
+ * mean, var, rstd, gamma, beta, cq = 2^K/(6 gamma), step = 6 gamma/2^K (fp32) and
+ * fb = floor(beta*cq) (int32).
+ */
+#ifndef ABL_H_
+#define ABL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct abl_shape {
+  int32_t N, H, W;      /* input batch, height, width                        */
+  int32_t Cin, Cout;    /* input (= BN) channels, output channels            */
+  int32_t R, S;         /* filter height, width                              */
+  int32_t stride, pad;  /* same in both spatial dims; Ho=(H+2pad-R)/stride+1 */
+} abl_shape;
+
+enum {
+  ABL_OK = 0,
+  ABL_ERR_ARG = 1,      /* null / misaligned pointer, K not in {4,8}, bad flag      */
+  ABL_ERR_SHAPE = 2,    /* non-positive dim, empty output, more than 2^31-1 elements */
+  ABL_ERR_SCRATCH = 3,  /* scratch buffer smaller than abl_scratch_bytes            */
+  ABL_ERR_HIP = 4       /* kernel launch failed                                     */
+};
+
+enum {
+  ABL_ACCUM_DX = 1u << 0 /* abl_backward / abl_bn_bwd: dx += result (residual-stream gradient, Sec. 3.4) */
+};
+
+#define ABL_BN_EPS 1e-5f
+#define ABL_STATS_PLANES 8
+
+const char* abl_error_string(int code);
+
+/* Bytes of the K-bit store of one layer's A2 (Sec. 3.4: alpha = K/32 of the fp32
+ * tensor): ceil(E*K/8) rounded up to 128.  0 on invalid arguments. */
+size_t abl_packed_bytes(const abl_shape* shape, int K);
+/* Bytes of the per-channel vectors kept with the store (Sec. 3.2): 32*Cin. */
+size_t abl_stats_bytes(const abl_shape* shape);
+/* Bytes of reusable workspace that abl_forward / abl_backward need for this
+ * shape: one fp32 tensor for A3 (forward) or its gradient (backward) - the
+ * "+1" buffer of Sec. 3.4 - plus reduction partials. */
+size_t abl_scratch_bytes(const abl_shape* shape, int K);
+
+/* Forward of one layer (Sec. 3.2; Eq. 1-4 and Eq. 9).
+ *   x      [N,H,W,Cin]      in
+ *   W      [R,S,Cin,Cout]   in
+ *   gamma, beta [Cin]       in
+ *   skip   [N,Ho,Wo,Cout]   in, may be NULL; y = conv(...) + skip (identity
+ *                           shortcut, Sec. 3.4).  May alias y.
+ *   y      [N,Ho,Wo,Cout]   out.  May alias x (x is consumed before y is written).
+ *   packed abl_packed_bytes out: K-bit codes of A2
+ *   stats  abl_stats_bytes  out
+ *   scratch                 workspace, contents undefined afterwards
+ * y is computed from the full-precision A3 and does not depend on K. */
+int abl_forward(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                const float* x, const float* W, const float* gamma, const float* beta,
+                const float* skip, void* scratch, size_t scratch_bytes,
+                float* y, void* packed, void* stats);
+
+/* Backward of one layer from the stored copy only (Sec. 3.2; Eq. 10, Eq. 5-8).
+ *   packed, stats           in, as written by abl_forward (gamma and beta are
+ *                           taken from the snapshot in `stats`)
+ *   dy     [N,Ho,Wo,Cout]   in
+ *   W      [R,S,Cin,Cout]   in
+ *   dx     [N,H,W,Cin]      out (or accumulated into with ABL_ACCUM_DX).  May alias dy.
+ *   dW     [R,S,Cin,Cout]   out: approximate (uses the dequantized A3)
+ *   dgamma, dbeta [Cin]     out: dgamma approximate, dbeta exact (Sec. 3.3) */
+int abl_backward(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                 const void* packed, const void* stats, const float* dy, const float* W,
+                 void* scratch, size_t scratch_bytes,
+                 float* dx, float* dW, float* dgamma, float* dbeta);
+
+/* ---- stage-level entry points (the steps the two calls above are made of) ---- */
+
+/* Eq. 1 statistics of x [M,C] and the per-channel constants of Eq. 9/10 -> stats.
+ * scratch: abl_bn_scratch_bytes(M, C). */
+size_t abl_bn_scratch_bytes(int64_t M, int32_t C);
+int abl_bn_stats(void* stream, const float* x, int64_t M, int32_t C, const float* gamma,
+                 const float* beta, int K, void* scratch, size_t scratch_bytes, void* stats);
+/* Eq. 1-3 and Eq. 9 in one pass over x: writes A3 = max(0, A2) (fp32 [M,C]) and the
+ * packed codes of A2.  a3 may alias x. */
+int abl_bn_relu_pack(void* stream, const float* x, int64_t M, int32_t C, int K,
+                     const void* stats, float* a3, void* packed);
+/* Eq. 9 alone: a2 fp32 [M,C] -> packed codes (gamma, beta, cq, fb from stats). */
+int abl_pack(void* stream, const float* a2, int64_t M, int32_t C, int K, const void* stats,
+             void* packed);
+/* Eq. 10 alone: packed codes -> fp32 [M,C] reconstruction of A2. */
+int abl_unpack(void* stream, const void* packed, int64_t M, int32_t C, int K,
+               const void* stats, float* a2t);
+/* Eq. 6-8 from the packed copy: da3 [M,C] -> dx [M,C] (+= with ABL_ACCUM_DX), dgamma, dbeta.
+ * dx may alias da3.  scratch: abl_bn_scratch_bytes(M, C). */
+int abl_bn_bwd(void* stream, const void* packed, const void* stats, const float* da3,
+               int64_t M, int32_t C, int K, uint32_t flags, void* scratch, size_t scratch_bytes,
+               float* dx, float* dgamma, float* dbeta);
+/* Eq. 4: y = a3 (*) W (+ skip).  skip may be NULL or alias y. */
+int abl_conv_fwd(void* stream, const abl_shape* shape, const float* a3, const float* W,
+                 const float* skip, float* y);
+/* Eq. 5, gradient to the conv input: da3 [N,H,W,Cin] from dy [N,Ho,Wo,Cout]. */
+int abl_conv_dgrad(void* stream, const abl_shape* shape, const float* dy, const float* W,
+                   float* da3);
+/* Eq. 5, gradient to the weights, with A3 rebuilt on the fly from the packed codes
+ * (Eq. 10 then Eq. 3); no full-precision copy of the activation is written to memory.
+ * scratch: abl_wgrad_scratch_bytes(shape). */
+size_t abl_wgrad_scratch_bytes(const abl_shape* shape);
+int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, const void* packed,
+                          const void* stats, const float* dy, void* scratch,
+                          size_t scratch_bytes, float* dW);
+
+/* ---- residual stack (Sec. 3.4; Fig. 2; Sec. 4 first paragraph) ----
+ * A chain of layers with an identity shortcut around every group of `skip_every`
+ * layers whose input and output shapes agree (0: plain chain).  Two caller-owned
+ * fp32 buffers hold the residual stream and the straight path; they are reused for
+ * the gradients in the backward pass.  Each must hold the largest layer input or
+ * output of the stack.  Per layer the caller provides parameters, the packed store
+ * and stats (written by the forward, read by the backward) and gradient outputs. */
+typedef struct abl_layer {
+  abl_shape shape;
+  const float* W;
+  const float* gamma;
+  const float* beta;
+  void* packed;   /* abl_packed_bytes(&shape, K) */
+  void* stats;    /* abl_stats_bytes(&shape)     */
+  float* dW;      /* backward outputs            */
+  float* dgamma;
+  float* dbeta;
+} abl_layer;
+
+/* Largest abl_scratch_bytes over the layers / largest activation in bytes. */
+size_t abl_stack_scratch_bytes(const abl_layer* layers, int32_t L, int K);
+size_t abl_stack_buffer_bytes(const abl_layer* layers, int32_t L);
+/* Forward: the input batch must already be in buf_s.  On return the stack output is
+ * in buf_s. */
+int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                      int32_t skip_every, float* buf_s, float* buf_t,
+                      void* scratch, size_t scratch_bytes);
+/* Backward: the gradient of the stack output must already be in buf_s.  On return
+ * the gradient of the stack input is in buf_s and every layer's dW, dgamma, dbeta
+ * are written. */
+int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                       int32_t skip_every, float* buf_s, float* buf_t,
+                       void* scratch, size_t scratch_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABL_H_ */

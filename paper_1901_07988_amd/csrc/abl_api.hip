@@ -1,0 +1,334 @@
+// C ABI of libabl: argument validation, workspace carving and the order in which the
+// kernels of one layer step (and of a residual stack) are enqueued.  No device code here.
+
+#include "abl_internal.h"
+
+using namespace abl;
+
+namespace {
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool bad_ptr(const void* p) { return p == nullptr || !aligned16(p); }
+
+int check_k(int K) { return (K == 4 || K == 8) ? ABL_OK : ABL_ERR_ARG; }
+
+int check_shape(const abl_shape* s) {
+  if (s == nullptr) return ABL_ERR_ARG;
+  if (s->N < 1 || s->H < 1 || s->W < 1 || s->Cin < 1 || s->Cout < 1 || s->R < 1 || s->S < 1 ||
+      s->stride < 1 || s->pad < 0)
+    return ABL_ERR_SHAPE;
+  if (s->H + 2 * s->pad < s->R || s->W + 2 * s->pad < s->S) return ABL_ERR_SHAPE;
+  const int64_t lim = 2147483647LL;
+  const int64_t e_in = (int64_t)s->N * s->H * s->W * s->Cin;
+  const int64_t e_out = (int64_t)s->N * out_dim(s->H, s->pad, s->R, s->stride) *
+                        out_dim(s->W, s->pad, s->S, s->stride) * s->Cout;
+  const int64_t e_w = (int64_t)s->R * s->S * s->Cin * s->Cout;
+  if (e_in > lim || e_out > lim || e_w > lim) return ABL_ERR_SHAPE;
+  return ABL_OK;
+}
+
+int check_mc(int64_t M, int32_t C) {
+  if (M < 1 || C < 1) return ABL_ERR_SHAPE;
+  if (M * C > 2147483647LL) return ABL_ERR_SHAPE;
+  return ABL_OK;
+}
+
+inline int64_t rows_of(const abl_shape& s) { return (int64_t)s.N * s.H * s.W; }
+
+size_t packed_bytes_of(int64_t E, int K) { return (size_t)(((E * K + 7) / 8 + 127) / 128 * 128); }
+
+}  // namespace
+
+extern "C" {
+
+const char* abl_error_string(int code) {
+  switch (code) {
+    case ABL_OK: return "ok";
+    case ABL_ERR_ARG: return "invalid argument (null or misaligned pointer, unsupported K or flag)";
+    case ABL_ERR_SHAPE: return "invalid shape";
+    case ABL_ERR_SCRATCH: return "scratch buffer too small";
+    case ABL_ERR_HIP: return "HIP launch failure";
+    default: return "unknown error";
+  }
+}
+
+size_t abl_packed_bytes(const abl_shape* s, int K) {
+  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  return packed_bytes_of(rows_of(*s) * s->Cin, K);
+}
+
+size_t abl_stats_bytes(const abl_shape* s) {
+  if (check_shape(s) != ABL_OK) return 0;
+  return (size_t)ABL_STATS_PLANES * 4 * (size_t)s->Cin;
+}
+
+size_t abl_bn_scratch_bytes(int64_t M, int32_t C) {
+  if (check_mc(M, C) != ABL_OK) return 0;
+  return bn_partial_bytes(M, C);
+}
+
+size_t abl_wgrad_scratch_bytes(const abl_shape* s) {
+  if (check_shape(s) != ABL_OK) return 0;
+  return wgrad_partial_bytes(*s);
+}
+
+size_t abl_scratch_bytes(const abl_shape* s, int K) {
+  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  const size_t act = up256((size_t)rows_of(*s) * s->Cin * sizeof(float));
+  return act + up256(bn_partial_bytes(rows_of(*s), s->Cin)) + wgrad_partial_bytes(*s);
+}
+
+int abl_bn_stats(void* stream, const float* x, int64_t M, int32_t C, const float* gamma,
+                 const float* beta, int K, void* scratch, size_t scratch_bytes, void* stats) {
+  if (int e = check_k(K)) return e;
+  if (int e = check_mc(M, C)) return e;
+  if (bad_ptr(x) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(stats)) return ABL_ERR_ARG;
+  if (scratch_bytes < bn_partial_bytes(M, C)) return ABL_ERR_SCRATCH;
+  return launch_bn_stats((hipStream_t)stream, x, M, C, gamma, beta, K, scratch, stats);
+}
+
+int abl_bn_relu_pack(void* stream, const float* x, int64_t M, int32_t C, int K, const void* stats,
+                     float* a3, void* packed) {
+  if (int e = check_k(K)) return e;
+  if (int e = check_mc(M, C)) return e;
+  if (bad_ptr(x) || bad_ptr(stats) || bad_ptr(a3) || bad_ptr(packed)) return ABL_ERR_ARG;
+  return launch_bn_relu_pack((hipStream_t)stream, x, M, C, K, stats, a3, packed);
+}
+
+int abl_pack(void* stream, const float* a2, int64_t M, int32_t C, int K, const void* stats,
+             void* packed) {
+  if (int e = check_k(K)) return e;
+  if (int e = check_mc(M, C)) return e;
+  if (bad_ptr(a2) || bad_ptr(stats) || bad_ptr(packed)) return ABL_ERR_ARG;
+  return launch_pack((hipStream_t)stream, a2, M, C, K, stats, packed);
+}
+
+int abl_unpack(void* stream, const void* packed, int64_t M, int32_t C, int K, const void* stats,
+               float* a2t) {
+  if (int e = check_k(K)) return e;
+  if (int e = check_mc(M, C)) return e;
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(a2t)) return ABL_ERR_ARG;
+  return launch_unpack((hipStream_t)stream, packed, M, C, K, stats, a2t);
+}
+
+int abl_bn_bwd(void* stream, const void* packed, const void* stats, const float* da3, int64_t M,
+               int32_t C, int K, uint32_t flags, void* scratch, size_t scratch_bytes, float* dx,
+               float* dgamma, float* dbeta) {
+  if (int e = check_k(K)) return e;
+  if (int e = check_mc(M, C)) return e;
+  if (flags & ~(uint32_t)ABL_ACCUM_DX) return ABL_ERR_ARG;
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(da3) || bad_ptr(scratch) || bad_ptr(dx) ||
+      bad_ptr(dgamma) || bad_ptr(dbeta))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < bn_partial_bytes(M, C)) return ABL_ERR_SCRATCH;
+  return launch_bn_bwd((hipStream_t)stream, packed, stats, da3, M, C, K, (flags & ABL_ACCUM_DX) != 0,
+                       scratch, dx, dgamma, dbeta);
+}
+
+int abl_conv_fwd(void* stream, const abl_shape* s, const float* a3, const float* W, const float* skip,
+                 float* y) {
+  if (int e = check_shape(s)) return e;
+  if (bad_ptr(a3) || bad_ptr(W) || bad_ptr(y) || (skip != nullptr && !aligned16(skip))) return ABL_ERR_ARG;
+  return launch_conv_fwd((hipStream_t)stream, *s, a3, W, skip, y);
+}
+
+int abl_conv_dgrad(void* stream, const abl_shape* s, const float* dy, const float* W, float* da3) {
+  if (int e = check_shape(s)) return e;
+  if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(da3)) return ABL_ERR_ARG;
+  return launch_conv_dgrad((hipStream_t)stream, *s, dy, W, da3);
+}
+
+int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, const void* packed, const void* stats,
+                          const float* dy, void* scratch, size_t scratch_bytes, float* dW) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(scratch) || bad_ptr(dW)) return ABL_ERR_ARG;
+  if (scratch_bytes < wgrad_partial_bytes(*s)) return ABL_ERR_SCRATCH;
+  return launch_conv_wgrad_packed((hipStream_t)stream, *s, K, packed, stats, dy, scratch, dW);
+}
+
+// Forward: statistics -> (normalise, ReLU, quantize, pack) -> convolution.  A3 lives in the
+// workspace only until the convolution has read it (Sec. 3.2: full-precision intermediates
+// are overwritten as soon as they have been used).
+int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const float* W,
+                const float* gamma, const float* beta, const float* skip, void* scratch,
+                size_t scratch_bytes, float* y, void* packed, void* stats) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags != 0) return ABL_ERR_ARG;
+  if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
+      bad_ptr(packed) || bad_ptr(stats) || (skip != nullptr && !aligned16(skip)))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t M = rows_of(*s);
+  const size_t act = up256((size_t)M * s->Cin * sizeof(float));
+  float* a3 = static_cast<float*>(scratch);
+  void* red = static_cast<char*>(scratch) + act;
+  if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
+  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
+  return launch_conv_fwd(st, *s, a3, W, skip, y);
+}
+
+// Backward: dgrad (exact) and wgrad (from the packed copy) consume dy; then the BN/ReLU
+// backward turns dA3 into dx.  dx may alias dy because dy is dead once both contractions
+// have been enqueued ahead of the kernel that writes dx.
+int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const void* packed,
+                 const void* stats, const float* dy, const float* W, void* scratch, size_t scratch_bytes,
+                 float* dx, float* dW, float* dgamma, float* dbeta) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)ABL_ACCUM_DX) return ABL_ERR_ARG;
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(W) || bad_ptr(scratch) || bad_ptr(dx) ||
+      bad_ptr(dW) || bad_ptr(dgamma) || bad_ptr(dbeta))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t M = rows_of(*s);
+  const size_t act = up256((size_t)M * s->Cin * sizeof(float));
+  const size_t redb = up256(bn_partial_bytes(M, s->Cin));
+  float* da3 = static_cast<float*>(scratch);
+  void* red = static_cast<char*>(scratch) + act;
+  void* wpart = static_cast<char*>(scratch) + act + redb;
+  if (int e = launch_conv_dgrad(st, *s, dy, W, da3)) return e;
+  if (int e = launch_conv_wgrad_packed(st, *s, K, packed, stats, dy, wpart, dW)) return e;
+  return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, (flags & ABL_ACCUM_DX) != 0, red, dx, dgamma,
+                       dbeta);
+}
+
+// ---- residual stack ---------------------------------------------------------------------
+
+size_t abl_stack_scratch_bytes(const abl_layer* layers, int32_t L, int K) {
+  if (layers == nullptr || L < 1) return 0;
+  size_t m = 0;
+  for (int i = 0; i < L; ++i) {
+    const size_t b = abl_scratch_bytes(&layers[i].shape, K);
+    if (b == 0) return 0;
+    if (b > m) m = b;
+  }
+  return m;
+}
+
+size_t abl_stack_buffer_bytes(const abl_layer* layers, int32_t L) {
+  if (layers == nullptr || L < 1) return 0;
+  size_t m = 0;
+  for (int i = 0; i < L; ++i) {
+    const abl_shape& s = layers[i].shape;
+    if (check_shape(&s) != ABL_OK) return 0;
+    const size_t in = (size_t)rows_of(s) * s.Cin * sizeof(float);
+    const size_t out = (size_t)s.N * out_dim(s.H, s.pad, s.R, s.stride) * out_dim(s.W, s.pad, s.S, s.stride) *
+                       s.Cout * sizeof(float);
+    if (in > m) m = in;
+    if (out > m) m = out;
+  }
+  return up256(m);
+}
+
+}  // extern "C"
+
+namespace {
+
+// A group is `skip_every` consecutive layers; the shortcut is taken when the group's output
+// shape equals its input shape.  Layers after the last complete group form a plain chain.
+struct GroupInfo {
+  bool in_group;  // layer belongs to a complete group
+  bool first, last;
+  bool shortcut;  // group has an identity shortcut
+};
+
+GroupInfo group_info(const abl_layer* layers, int L, int skip_every, int i) {
+  GroupInfo gi{false, false, false, false};
+  if (skip_every <= 0) return gi;
+  const int g0 = (i / skip_every) * skip_every;
+  if (g0 + skip_every > L) return gi;
+  gi.in_group = true;
+  gi.first = i == g0;
+  gi.last = i == g0 + skip_every - 1;
+  const abl_shape& a = layers[g0].shape;
+  const abl_shape& b = layers[g0 + skip_every - 1].shape;
+  gi.shortcut = a.N == b.N && a.H == out_dim(b.H, b.pad, b.R, b.stride) &&
+                a.W == out_dim(b.W, b.pad, b.S, b.stride) && a.Cin == b.Cout;
+  return gi;
+}
+
+int check_stack(const abl_layer* layers, int L, int K, int skip_every, const float* s, const float* t,
+                void* scratch, size_t scratch_bytes) {
+  if (layers == nullptr || L < 1 || skip_every < 0) return ABL_ERR_ARG;
+  if (int e = check_k(K)) return e;
+  if (bad_ptr(s) || bad_ptr(t) || bad_ptr(scratch)) return ABL_ERR_ARG;
+  for (int i = 0; i < L; ++i) {
+    if (int e = check_shape(&layers[i].shape)) return e;
+    if (i > 0) {  // layer i consumes layer i-1's output
+      const abl_shape& p = layers[i - 1].shape;
+      const abl_shape& c = layers[i].shape;
+      if (c.N != p.N || c.H != out_dim(p.H, p.pad, p.R, p.stride) ||
+          c.W != out_dim(p.W, p.pad, p.S, p.stride) || c.Cin != p.Cout)
+        return ABL_ERR_SHAPE;
+    }
+  }
+  if (scratch_bytes < abl_stack_scratch_bytes(layers, L, K)) return ABL_ERR_SCRATCH;
+  return ABL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Buffer plan (Fig. 2): S holds the residual stream, T the straight path.  The first layer
+// of a group reads S and writes T, middle layers run in place on T (a layer's input is dead
+// once A3 is in the workspace), the last layer writes S = conv + S.
+int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                      int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                      size_t scratch_bytes) {
+  if (flags != 0) return ABL_ERR_ARG;
+  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  for (int i = 0; i < L; ++i) {
+    const abl_layer& l = layers[i];
+    const GroupInfo gi = group_info(layers, L, skip_every, i);
+    const float* x = buf_s;
+    float* y = buf_s;
+    const float* skip = nullptr;
+    if (gi.in_group) {
+      x = gi.first ? buf_s : buf_t;
+      y = gi.last ? buf_s : buf_t;
+      if (gi.last && gi.shortcut) skip = buf_s;
+    }
+    if (int e = abl_forward(stream, &l.shape, K, 0, x, l.W, l.gamma, l.beta, skip, scratch, scratch_bytes, y,
+                            l.packed, l.stats))
+      return e;
+  }
+  return ABL_OK;
+}
+
+// Mirror image: S holds the gradient of the residual stream.  The last layer of a group reads
+// S and writes T, middle layers run in place on T, the first layer adds its dx into S
+// (gradients through a shortcut are copied and added, Sec. 3.4).  Without a shortcut the
+// first layer overwrites S.
+int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                       size_t scratch_bytes) {
+  if (flags != 0) return ABL_ERR_ARG;
+  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  for (int i = L - 1; i >= 0; --i) {
+    const abl_layer& l = layers[i];
+    if (bad_ptr(l.dW) || bad_ptr(l.dgamma) || bad_ptr(l.dbeta)) return ABL_ERR_ARG;
+    const GroupInfo gi = group_info(layers, L, skip_every, i);
+    const float* dy = buf_s;
+    float* dx = buf_s;
+    uint32_t f = 0;
+    if (gi.in_group) {
+      dy = gi.last ? buf_s : buf_t;
+      dx = gi.first ? buf_s : buf_t;
+      if (gi.first && gi.shortcut) f = ABL_ACCUM_DX;
+    }
+    if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W, scratch, scratch_bytes, dx,
+                             l.dW, l.dgamma, l.dbeta))
+      return e;
+  }
+  return ABL_OK;
+}
+
+}  // extern "C"

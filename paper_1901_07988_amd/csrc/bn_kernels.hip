@@ -1,0 +1,782 @@
+// Batch-norm / quantizer kernels of the approximate-activation layer for gfx950.
+//
+//   bn_stats      Eq. 1 statistics (Sec. 3.1) + per-channel constants of Eq. 9/10 (Sec. 3.2)
+//   bn_relu_pack  Eq. 1-3 and Eq. 9 fused: one read of x, writes A3 (fp32) and the K-bit codes
+//   pack/unpack   Eq. 9 / Eq. 10 alone
+//   bn_bwd        Eq. 6-8 from the K-bit codes: reduce pass, then apply pass
+//
+// All of them stream [M,C] row-major tensors once and are HBM-bound.  A block is a
+// TX x TY arrangement of 256 threads: a thread owns VEC consecutive channels (so its
+// per-channel constants live in registers) and walks rows ty, ty+TY, ...; a wave
+// therefore touches whole contiguous rows.  Reductions are two-pass with a fixed order
+// (no atomics), so every result is reproducible bit for bit.
+//
+// The codes must equal those of a CPU evaluation of Eq. 9 in IEEE fp32, so the
+// quantizer arithmetic is written one rounded operation at a time and this file is
+// compiled with floating-point contraction off.
+
+#include "abl_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace abl {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+struct RowGeom {
+  int CV;     // channel groups per row (C / VEC)
+  int TX;     // channel groups per block
+  int TY;     // rows per block pass
+  int gridX;  // blocks across channel groups
+  int gridY;  // blocks across rows
+  int rpt;    // rows per thread
+};
+
+// reduce == true bounds gridY (partials) and keeps >= 64 rows per block so that the
+// partial sums stay below 1/16 of the tensor's bytes.
+RowGeom make_geom(int64_t M, int C, int VEC, bool reduce) {
+  RowGeom g;
+  g.CV = C / VEC;
+  g.TX = g.CV < 64 ? g.CV : 64;
+  g.TY = kThreads / g.TX;
+  g.gridX = (g.CV + g.TX - 1) / g.TX;
+  const int64_t passes = (M + g.TY - 1) / g.TY;  // rows / TY
+  int64_t want = 2048 / g.gridX;                 // blocks across rows we would like
+  if (want < 1) want = 1;
+  int64_t rpt = (passes + want - 1) / want;
+  if (reduce) {
+    const int64_t min_rpt = (64 + g.TY - 1) / g.TY;
+    if (rpt < min_rpt) rpt = min_rpt;
+    const int64_t cap = (passes + kMaxPartialBlocks - 1) / kMaxPartialBlocks;
+    if (rpt < cap) rpt = cap;
+  } else {
+    if (rpt > 8) rpt = 8;
+  }
+  if (rpt < 1) rpt = 1;
+  g.rpt = (int)rpt;
+  g.gridY = (int)((passes + rpt - 1) / rpt);
+  if (g.gridY < 1) g.gridY = 1;
+  return g;
+}
+
+template <int VEC>
+__device__ inline void load_vec(const float* __restrict__ p, float (&v)[VEC]) {
+  if constexpr (VEC % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC / 4; ++i) {
+      const float4 t = reinterpret_cast<const float4*>(p)[i];
+      v[4 * i + 0] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = p[i];
+  }
+}
+
+template <int VEC>
+__device__ inline void load_vec_i(const int32_t* __restrict__ p, int32_t (&v)[VEC]) {
+  if constexpr (VEC % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC / 4; ++i) {
+      const int4 t = reinterpret_cast<const int4*>(p)[i];
+      v[4 * i + 0] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = p[i];
+  }
+}
+
+template <int VEC>
+__device__ inline void store_vec(float* __restrict__ p, const float (&v)[VEC]) {
+  if constexpr (VEC % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC / 4; ++i)
+      reinterpret_cast<float4*>(p)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) p[i] = v[i];
+  }
+}
+
+// floor() limited to +-2^24 so that the integer conversion is defined for any input.
+__device__ inline float limit_floor(float u) {
+  const float lim = 16777216.0f;
+  u = floorf(u);
+  u = (u >= -lim) ? u : -lim;  // NaN -> -lim
+  u = (u > lim) ? lim : u;
+  return u;
+}
+
+// Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).
+template <int K>
+__device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
+  const float u = limit_floor(a2 * cq);
+  int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
+  v = v < 0 ? 0 : v;
+  v = v > (1 << K) - 1 ? (1 << K) - 1 : v;
+  return (uint32_t)v;
+}
+
+// Eq. 10 for one code.
+template <int K>
+__device__ inline float dequant(uint32_t q, float step, int32_t fb) {
+  const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
+  const float t = (float)j + 0.5f;
+  return step * t;
+}
+
+// Packed word of VEC codes: K*VEC bits (32 or 16).
+template <int K, int VEC>
+struct PackedWord {
+  static_assert(K * VEC == 32 || K * VEC == 16, "unsupported packing");
+  using type = typename std::conditional<K * VEC == 32, uint32_t, uint16_t>::type;
+};
+
+struct ThreadPos {
+  int tx, ty;
+  int c0;       // first channel of this thread
+  bool active;
+};
+
+template <int VEC>
+__device__ inline ThreadPos thread_pos(const RowGeom& g) {
+  ThreadPos p;
+  p.tx = threadIdx.x % g.TX;
+  p.ty = threadIdx.x / g.TX;
+  const int cg = blockIdx.x * g.TX + p.tx;
+  p.active = p.ty < g.TY && cg < g.CV;
+  p.c0 = p.active ? cg * VEC : 0;
+  return p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 1 statistics, pass 1: per-block sums of (x - k) and (x - k)^2 in fp64, k = first row
+// (a per-channel shift that keeps E[x^2] - E[x]^2 well conditioned when |mean| >> sigma).
+// partial layout: [gridY][2][C] doubles.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __restrict__ x, int64_t M,
+                                                                 int C, RowGeom g,
+                                                                 double* __restrict__ partial) {
+  __shared__ double red[kThreads][2 * VEC];
+  const ThreadPos p = thread_pos<VEC>(g);
+  double s[VEC], ss[VEC];
+  float k[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) s[v] = ss[v] = 0.0;
+  load_vec<VEC>(x + p.c0, k);
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; i += kUnroll) {
+    float xv[kUnroll][VEC];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+      ok[j] = p.active && (i + j) < g.rpt && r < M;
+      load_vec<VEC>(x + (ok[j] ? r : 0) * C + p.c0, xv[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (ok[j]) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          const double d = (double)xv[j][v] - (double)k[v];
+          s[v] += d;
+          ss[v] += d * d;
+        }
+      }
+  }
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    red[threadIdx.x][v] = s[v];
+    red[threadIdx.x][VEC + v] = ss[v];
+  }
+  __syncthreads();
+  // tree over ty (threads tx + TX*ty), fixed order
+  int span = 1;
+  while (span < g.TY) span <<= 1;
+  for (int h = span >> 1; h >= 1; h >>= 1) {
+    if (p.ty < h && p.ty + h < g.TY) {
+#pragma unroll
+      for (int v = 0; v < 2 * VEC; ++v) red[threadIdx.x][v] += red[threadIdx.x + h * g.TX][v];
+    }
+    __syncthreads();
+  }
+  if (p.active && p.ty == 0) {
+    double* out = partial + (int64_t)blockIdx.y * 2 * C + p.c0;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      out[v] = red[threadIdx.x][v];
+      out[C + v] = red[threadIdx.x][VEC + v];
+    }
+  }
+}
+
+// Sums `nb` partial rows of two per-channel quantities in a fixed order.
+// 256 threads: 64 channels x 4 interleaved parts.
+__device__ inline void reduce_partials(const double* __restrict__ partial, int nb, int C, int c,
+                                       double (&out)[2], double (*sm)[64][2]) {
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  double a = 0.0, b = 0.0;
+  if (c < C) {
+    for (int i = part; i < nb; i += 4) {
+      a += partial[(int64_t)i * 2 * C + c];
+      b += partial[(int64_t)i * 2 * C + C + c];
+    }
+  }
+  sm[part][lane][0] = a;
+  sm[part][lane][1] = b;
+  __syncthreads();
+  out[0] = ((sm[0][lane][0] + sm[1][lane][0]) + sm[2][lane][0]) + sm[3][lane][0];
+  out[1] = ((sm[0][lane][1] + sm[1][lane][1]) + sm[2][lane][1]) + sm[3][lane][1];
+}
+
+// Eq. 1 statistics, pass 2, and the per-channel constants of Eq. 9/10.
+__global__ __launch_bounds__(kThreads) void stats_finalize_kernel(const double* __restrict__ partial, int nb,
+                                                                  const float* __restrict__ x, int64_t M,
+                                                                  int C, const float* __restrict__ gamma,
+                                                                  const float* __restrict__ beta, int K,
+                                                                  float* __restrict__ stats) {
+  __shared__ double sm[4][64][2];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  double t[2];
+  reduce_partials(partial, nb, C, c, t, sm);
+  if (c >= C || threadIdx.x >= 64) return;
+  const double k = (double)x[c];
+  const double mk = t[0] / (double)M;
+  double var = t[1] / (double)M - mk * mk;
+  var = var > 0.0 ? var : 0.0;
+  const float mean_f = (float)(k + mk);
+  const float var_f = (float)var;
+  const float rstd = (float)(1.0 / sqrt((double)var_f + (double)ABL_BN_EPS));
+  const float gm = gamma[c], bt = beta[c];
+  const float two_k = (float)(1 << K);
+  const float six_g = 6.0f * gm;
+  // double division then one rounding == correctly rounded fp32 division
+  const float cq = (float)((double)two_k / (double)six_g);
+  const float step = (float)((double)six_g / (double)two_k);
+  const int32_t fb = (int32_t)limit_floor(bt * cq);
+  stats[P_MEAN * C + c] = mean_f;
+  stats[P_VAR * C + c] = var_f;
+  stats[P_RSTD * C + c] = rstd;
+  stats[P_GAMMA * C + c] = gm;
+  stats[P_BETA * C + c] = bt;
+  stats[P_CQ * C + c] = cq;
+  stats[P_STEP * C + c] = step;
+  reinterpret_cast<int32_t*>(stats)[P_FB * C + c] = fb;
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward elementwise pass.  MODE 0: x -> A3 and codes (Eq. 1-3, 9).  MODE 1: a2 -> codes (Eq. 9).
+template <int K, int VEC, int MODE>
+__global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __restrict__ in, int64_t M, int C,
+                                                              RowGeom g, const float* __restrict__ stats,
+                                                              float* __restrict__ a3,
+                                                              void* __restrict__ packed, int pad_bytes) {
+  using word_t = typename PackedWord<K, VEC>::type;
+  const ThreadPos p = thread_pos<VEC>(g);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < pad_bytes)  // zero the 128-byte row tail
+    reinterpret_cast<uint8_t*>(packed)[(M * C * K) / 8 + threadIdx.x] = 0;
+  if (!p.active) return;
+  float mean[VEC], rstd[VEC], gm[VEC], bt[VEC], cq[VEC];
+  int32_t fb[VEC];
+  if constexpr (MODE == 0) {
+    load_vec<VEC>(stats + P_MEAN * C + p.c0, mean);
+    load_vec<VEC>(stats + P_RSTD * C + p.c0, rstd);
+    load_vec<VEC>(stats + P_GAMMA * C + p.c0, gm);
+    load_vec<VEC>(stats + P_BETA * C + p.c0, bt);
+  }
+  load_vec<VEC>(stats + P_CQ * C + p.c0, cq);
+  load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
+  word_t* __restrict__ pw = reinterpret_cast<word_t*>(packed);
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; i += kUnroll) {
+    float xv[kUnroll][VEC];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+      ok[j] = (i + j) < g.rpt && r < M;
+      load_vec<VEC>(in + (ok[j] ? r : 0) * C + p.c0, xv[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (ok[j]) {
+        const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+        uint32_t word = 0;
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          float a2;
+          if constexpr (MODE == 0) {
+            const float d = xv[j][v] - mean[v];
+            const float a1 = d * rstd[v];   // Eq. 1
+            const float t = gm[v] * a1;
+            a2 = t + bt[v];                 // Eq. 2
+            out[v] = a2 > 0.0f ? a2 : 0.0f; // Eq. 3
+          } else {
+            a2 = xv[j][v];
+          }
+          word |= quant_code<K>(a2, cq[v], fb[v]) << (K * v);
+        }
+        const int64_t e = r * C + p.c0;
+        if constexpr (MODE == 0) store_vec<VEC>(a3 + e, out);
+        pw[e / VEC] = (word_t)word;
+      }
+  }
+}
+
+// Eq. 10: codes -> fp32.
+template <int K, int VEC>
+__global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict__ packed, int64_t M, int C,
+                                                          RowGeom g, const float* __restrict__ stats,
+                                                          float* __restrict__ a2t) {
+  using word_t = typename PackedWord<K, VEC>::type;
+  const ThreadPos p = thread_pos<VEC>(g);
+  if (!p.active) return;
+  float step[VEC];
+  int32_t fb[VEC];
+  load_vec<VEC>(stats + P_STEP * C + p.c0, step);
+  load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
+  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; i += kUnroll) {
+    uint32_t w[kUnroll];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+      ok[j] = (i + j) < g.rpt && r < M;
+      w[j] = pw[((ok[j] ? r : 0) * C + p.c0) / VEC];
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (ok[j]) {
+        const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+          out[v] = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+        store_vec<VEC>(a2t + r * C + p.c0, out);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward, pass 1 (Eq. 6-7): per-block sums of dA2 and A1~ * dA2, fp64, [gridY][2][C].
+template <int K, int VEC>
+__global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __restrict__ packed,
+                                                              const float* __restrict__ da3, int64_t M, int C,
+                                                              RowGeom g, const float* __restrict__ stats,
+                                                              double* __restrict__ partial) {
+  using word_t = typename PackedWord<K, VEC>::type;
+  __shared__ double red[kThreads][2 * VEC];
+  const ThreadPos p = thread_pos<VEC>(g);
+  float step[VEC], bt[VEC], ig[VEC];
+  int32_t fb[VEC];
+  load_vec<VEC>(stats + P_STEP * C + p.c0, step);
+  load_vec<VEC>(stats + P_BETA * C + p.c0, bt);
+  load_vec<VEC>(stats + P_GAMMA * C + p.c0, ig);
+  load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
+  double s1[VEC], s2[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    ig[v] = 1.0f / ig[v];
+    s1[v] = s2[v] = 0.0;
+  }
+  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; i += kUnroll) {
+    float gv[kUnroll][VEC];
+    uint32_t w[kUnroll];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+      ok[j] = p.active && (i + j) < g.rpt && r < M;
+      const int64_t e = (ok[j] ? r : 0) * C + p.c0;
+      load_vec<VEC>(da3 + e, gv[j]);
+      w[j] = pw[e / VEC];
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (ok[j]) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          const float da2 = a2t > 0.0f ? gv[j][v] : 0.0f;  // Eq. 6
+          const float a1t = (a2t - bt[v]) * ig[v];          // inverse of Eq. 2
+          s1[v] += (double)da2;
+          s2[v] += (double)a1t * (double)da2;
+        }
+      }
+  }
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    red[threadIdx.x][v] = s1[v];
+    red[threadIdx.x][VEC + v] = s2[v];
+  }
+  __syncthreads();
+  int span = 1;
+  while (span < g.TY) span <<= 1;
+  for (int h = span >> 1; h >= 1; h >>= 1) {
+    if (p.ty < h && p.ty + h < g.TY) {
+#pragma unroll
+      for (int v = 0; v < 2 * VEC; ++v) red[threadIdx.x][v] += red[threadIdx.x + h * g.TX][v];
+    }
+    __syncthreads();
+  }
+  if (p.active && p.ty == 0) {
+    double* out = partial + (int64_t)blockIdx.y * 2 * C + p.c0;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      out[v] = red[threadIdx.x][v];
+      out[C + v] = red[threadIdx.x][VEC + v];
+    }
+  }
+}
+
+// Backward, pass 1b: dbeta, dgamma (Eq. 7) and the two per-channel means of Eq. 8.
+// means layout: [2][C] floats = Mean(dA1), Mean(A1~ * dA1) with dA1 = gamma * dA2.
+__global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(const double* __restrict__ partial, int nb,
+                                                                int64_t M, int C,
+                                                                const float* __restrict__ stats,
+                                                                float* __restrict__ dgamma,
+                                                                float* __restrict__ dbeta,
+                                                                float* __restrict__ means) {
+  __shared__ double sm[4][64][2];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  double t[2];
+  reduce_partials(partial, nb, C, c, t, sm);
+  if (c >= C || threadIdx.x >= 64) return;
+  const double gm = (double)stats[P_GAMMA * C + c];
+  dbeta[c] = (float)t[0];
+  dgamma[c] = (float)t[1];
+  means[c] = (float)(gm * t[0] / (double)M);
+  means[C + c] = (float)(gm * t[1] / (double)M);
+}
+
+// Backward, pass 2 (Eq. 8): dx = rstd * (dA1 - Mean(dA1) - A1~ * Mean(A1~ * dA1)).
+template <int K, int VEC, bool ACCUM>
+__global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restrict__ packed,
+                                                             const float* da3, int64_t M, int C, RowGeom g,
+                                                             const float* __restrict__ stats,
+                                                             const float* __restrict__ means, float* dx) {
+  using word_t = typename PackedWord<K, VEC>::type;
+  const ThreadPos p = thread_pos<VEC>(g);
+  if (!p.active) return;
+  float step[VEC], bt[VEC], gm[VEC], ig[VEC], rstd[VEC], m1[VEC], m2[VEC];
+  int32_t fb[VEC];
+  load_vec<VEC>(stats + P_STEP * C + p.c0, step);
+  load_vec<VEC>(stats + P_BETA * C + p.c0, bt);
+  load_vec<VEC>(stats + P_GAMMA * C + p.c0, gm);
+  load_vec<VEC>(stats + P_RSTD * C + p.c0, rstd);
+  load_vec<VEC>(means + p.c0, m1);
+  load_vec<VEC>(means + C + p.c0, m2);
+  load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) ig[v] = 1.0f / gm[v];
+  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; i += kUnroll) {
+    float gv[kUnroll][VEC], acc[kUnroll][VEC];
+    uint32_t w[kUnroll];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+      ok[j] = (i + j) < g.rpt && r < M;
+      const int64_t e = (ok[j] ? r : 0) * C + p.c0;
+      load_vec<VEC>(da3 + e, gv[j]);
+      if constexpr (ACCUM) load_vec<VEC>(dx + e, acc[j]);
+      w[j] = pw[e / VEC];
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (ok[j]) {
+        const int64_t r = row0 + (int64_t)(i + j) * g.TY;
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          const float da2 = a2t > 0.0f ? gv[j][v] : 0.0f;  // Eq. 6
+          const float a1t = (a2t - bt[v]) * ig[v];
+          const float da1 = gm[v] * da2;                    // Eq. 7
+          const float t = (da1 - m1[v]) - a1t * m2[v];
+          out[v] = rstd[v] * t;                             // Eq. 8
+          if constexpr (ACCUM) out[v] = acc[j][v] + out[v];
+        }
+        store_vec<VEC>(dx + r * C + p.c0, out);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Any-C fallbacks: flat element order, 8 elements per thread, per-element channel lookup.
+// They cover the zero-padded tail of the packed store as well.
+template <int K, int MODE>  // MODE 0: bn+relu+pack, 1: pack only
+__global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* __restrict__ in, int64_t E,
+                                                                   int C, int64_t packed_bytes,
+                                                                   const float* __restrict__ stats,
+                                                                   float* __restrict__ a3,
+                                                                   uint8_t* __restrict__ packed) {
+  const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t e0 = t * 8;
+  if (e0 * K / 8 >= packed_bytes) return;
+  const int32_t* fbp = reinterpret_cast<const int32_t*>(stats) + P_FB * C;
+  uint32_t codes[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t e = e0 + i;
+    codes[i] = 0;
+    if (e < E) {
+      const int c = (int)(e % C);
+      float a2 = in[e];
+      if constexpr (MODE == 0) {
+        const float d = a2 - stats[P_MEAN * C + c];
+        const float a1 = d * stats[P_RSTD * C + c];
+        const float g = stats[P_GAMMA * C + c] * a1;
+        a2 = g + stats[P_BETA * C + c];
+        a3[e] = a2 > 0.0f ? a2 : 0.0f;
+      }
+      codes[i] = quant_code<K>(a2, stats[P_CQ * C + c], fbp[c]);
+    }
+  }
+  if constexpr (K == 4) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) packed[e0 / 2 + b] = (uint8_t)(codes[2 * b] | (codes[2 * b + 1] << 4));
+  } else {
+#pragma unroll
+    for (int b = 0; b < 8; ++b) packed[e0 + b] = (uint8_t)codes[b];
+  }
+}
+
+template <int K>
+__device__ inline uint32_t flat_code(const uint8_t* __restrict__ packed, int64_t e) {
+  if constexpr (K == 4) return (packed[e >> 1] >> ((e & 1) * 4)) & 15u;
+  return packed[e];
+}
+
+template <int K>
+__global__ __launch_bounds__(kThreads) void flat_unpack_kernel(const uint8_t* __restrict__ packed, int64_t E,
+                                                               int C, const float* __restrict__ stats,
+                                                               float* __restrict__ a2t) {
+  const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (e >= E) return;
+  const int c = (int)(e % C);
+  a2t[e] = dequant<K>(flat_code<K>(packed, e), stats[P_STEP * C + c],
+                      reinterpret_cast<const int32_t*>(stats)[P_FB * C + c]);
+}
+
+// Reduce pass for any C: one thread per channel per block pass (VEC = 1 geometry).
+template <int K>
+__global__ __launch_bounds__(kThreads) void flat_bwd_reduce_kernel(const uint8_t* __restrict__ packed,
+                                                                   const float* __restrict__ da3, int64_t M,
+                                                                   int C, RowGeom g,
+                                                                   const float* __restrict__ stats,
+                                                                   double* __restrict__ partial) {
+  __shared__ double red[kThreads][2];
+  const ThreadPos p = thread_pos<1>(g);
+  const int c = p.c0;
+  const float step = stats[P_STEP * C + c], bt = stats[P_BETA * C + c];
+  const float ig = 1.0f / stats[P_GAMMA * C + c];
+  const int32_t fb = reinterpret_cast<const int32_t*>(stats)[P_FB * C + c];
+  double s1 = 0.0, s2 = 0.0;
+  const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
+  for (int i = 0; i < g.rpt; ++i) {
+    const int64_t r = row0 + (int64_t)i * g.TY;
+    if (p.active && r < M) {
+      const int64_t e = r * C + c;
+      const float a2t = dequant<K>(flat_code<K>(packed, e), step, fb);
+      const float da2 = a2t > 0.0f ? da3[e] : 0.0f;
+      const float a1t = (a2t - bt) * ig;
+      s1 += (double)da2;
+      s2 += (double)a1t * (double)da2;
+    }
+  }
+  red[threadIdx.x][0] = s1;
+  red[threadIdx.x][1] = s2;
+  __syncthreads();
+  int span = 1;
+  while (span < g.TY) span <<= 1;
+  for (int h = span >> 1; h >= 1; h >>= 1) {
+    if (p.ty < h && p.ty + h < g.TY) {
+      red[threadIdx.x][0] += red[threadIdx.x + h * g.TX][0];
+      red[threadIdx.x][1] += red[threadIdx.x + h * g.TX][1];
+    }
+    __syncthreads();
+  }
+  if (p.active && p.ty == 0) {
+    partial[(int64_t)blockIdx.y * 2 * C + c] = red[threadIdx.x][0];
+    partial[(int64_t)blockIdx.y * 2 * C + C + c] = red[threadIdx.x][1];
+  }
+}
+
+template <int K, bool ACCUM>
+__global__ __launch_bounds__(kThreads) void flat_bwd_apply_kernel(const uint8_t* __restrict__ packed,
+                                                                  const float* da3, int64_t E, int C,
+                                                                  const float* __restrict__ stats,
+                                                                  const float* __restrict__ means, float* dx) {
+  const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (e >= E) return;
+  const int c = (int)(e % C);
+  const float gm = stats[P_GAMMA * C + c];
+  const float a2t = dequant<K>(flat_code<K>(packed, e), stats[P_STEP * C + c],
+                               reinterpret_cast<const int32_t*>(stats)[P_FB * C + c]);
+  const float da2 = a2t > 0.0f ? da3[e] : 0.0f;
+  const float a1t = (a2t - stats[P_BETA * C + c]) * (1.0f / gm);
+  const float da1 = gm * da2;
+  const float t = (da1 - means[c]) - a1t * means[C + c];
+  float out = stats[P_RSTD * C + c] * t;
+  if constexpr (ACCUM) out = dx[e] + out;
+  dx[e] = out;
+}
+
+// VEC used by the fast path for (K, C); 0 = use the flat fallback.
+int fast_vec(int K, int C) {
+  if (K == 4) return C % 8 == 0 ? 8 : (C % 4 == 0 ? 4 : 0);
+  return C % 4 == 0 ? 4 : 0;
+}
+
+inline dim3 grid_of(const RowGeom& g) { return dim3(g.gridX, g.gridY, 1); }
+
+}  // namespace
+
+size_t bn_partial_bytes(int64_t M, int C) {
+  int gy = 1;
+  for (int vec : {1, 4, 8}) {
+    if (C % vec) continue;
+    const RowGeom g = make_geom(M, C, vec, true);
+    if (g.gridY > gy) gy = g.gridY;
+  }
+  const size_t partial = (size_t)gy * 2 * (size_t)C * sizeof(double);
+  const size_t means = ((size_t)2 * C * sizeof(float) + 255) / 256 * 256;
+  return (partial + 255) / 256 * 256 + means;
+}
+
+int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const float* gamma,
+                    const float* beta, int K, void* scratch, void* stats) {
+  double* partial = static_cast<double*>(scratch);
+  const int vec = C % 4 == 0 ? 4 : 1;
+  const RowGeom g = make_geom(M, C, vec, true);
+  if (vec == 4)
+    stats_partial_kernel<4><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
+  else
+    stats_partial_kernel<1><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
+  stats_finalize_kernel<<<(C + 63) / 64, kThreads, 0, st>>>(partial, g.gridY, x, M, C, gamma, beta, K,
+                                                            static_cast<float*>(stats));
+  return hip_status();
+}
+
+template <int MODE>
+static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, int K, const void* stats,
+                             float* a3, void* packed) {
+  const float* sp = static_cast<const float*>(stats);
+  const int64_t E = M * C;
+  const int64_t raw = (E * K + 7) / 8;
+  const int64_t pbytes = (raw + 127) / 128 * 128;
+  const int vec = fast_vec(K, C);
+  if (vec == 0) {
+    const int64_t threads = pbytes * 8 / K / 8;
+    const unsigned blocks = (unsigned)((threads + kThreads - 1) / kThreads);
+    uint8_t* pk = static_cast<uint8_t*>(packed);
+    if (K == 4)
+      flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+    else
+      flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+    return hip_status();
+  }
+  const RowGeom g = make_geom(M, C, vec, false);
+  const int pad = (int)(pbytes - raw);
+  if (K == 4 && vec == 8)
+    quant_pack_kernel<4, 8, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
+  else if (K == 4)
+    quant_pack_kernel<4, 4, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
+  else
+    quant_pack_kernel<8, 4, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
+  return hip_status();
+}
+
+int launch_bn_relu_pack(hipStream_t st, const float* x, int64_t M, int C, int K, const void* stats,
+                        float* a3, void* packed) {
+  return launch_quant_pack<0>(st, x, M, C, K, stats, a3, packed);
+}
+
+int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const void* stats,
+                void* packed) {
+  return launch_quant_pack<1>(st, a2, M, C, K, stats, nullptr, packed);
+}
+
+int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, const void* stats,
+                  float* a2t) {
+  const float* sp = static_cast<const float*>(stats);
+  const int vec = fast_vec(K, C);
+  if (vec == 0) {
+    const int64_t E = M * C;
+    const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
+    const uint8_t* pk = static_cast<const uint8_t*>(packed);
+    if (K == 4)
+      flat_unpack_kernel<4><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+    else
+      flat_unpack_kernel<8><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+    return hip_status();
+  }
+  const RowGeom g = make_geom(M, C, vec, false);
+  if (K == 4 && vec == 8)
+    unpack_kernel<4, 8><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
+  else if (K == 4)
+    unpack_kernel<4, 4><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
+  else
+    unpack_kernel<8, 4><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
+  return hip_status();
+}
+
+int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
+                  int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta) {
+  const float* sp = static_cast<const float*>(stats);
+  double* partial = static_cast<double*>(scratch);
+  const int vec = fast_vec(K, C);
+  const RowGeom gr = make_geom(M, C, vec ? vec : 1, true);
+  const size_t partial_bytes = ((size_t)gr.gridY * 2 * C * sizeof(double) + 255) / 256 * 256;
+  float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + partial_bytes);
+  const uint8_t* pk = static_cast<const uint8_t*>(packed);
+  if (vec == 0) {
+    if (K == 4)
+      flat_bwd_reduce_kernel<4><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+    else
+      flat_bwd_reduce_kernel<8><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+  } else if (K == 4 && vec == 8) {
+    bwd_reduce_kernel<4, 8><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+  } else if (K == 4) {
+    bwd_reduce_kernel<4, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+  } else {
+    bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+  }
+  bwd_finalize_kernel<<<(C + 63) / 64, kThreads, 0, st>>>(partial, gr.gridY, M, C, sp, dgamma, dbeta, means);
+  if (vec == 0) {
+    const int64_t E = M * C;
+    const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
+    if (K == 4 && accum) flat_bwd_apply_kernel<4, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else if (K == 4) flat_bwd_apply_kernel<4, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else if (accum) flat_bwd_apply_kernel<8, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else flat_bwd_apply_kernel<8, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    return hip_status();
+  }
+  const RowGeom ga = make_geom(M, C, vec, false);
+#define ABL_APPLY(KK, VV)                                                                               \
+  do {                                                                                                  \
+    if (accum)                                                                                          \
+      bwd_apply_kernel<KK, VV, true><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
+    else                                                                                                \
+      bwd_apply_kernel<KK, VV, false><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
+  } while (0)
+  if (K == 4 && vec == 8) ABL_APPLY(4, 8);
+  else if (K == 4) ABL_APPLY(4, 4);
+  else ABL_APPLY(8, 4);
+#undef ABL_APPLY
+  return hip_status();
+}
+
+}  // namespace abl

@@ -1,0 +1,587 @@
+// Convolution contractions of the approximate-activation layer for gfx950 (CDNA4):
+//   conv_fwd     Eq. 4            y   = A3 (*) W            (+ identity shortcut, Sec. 3.4)
+//   conv_dgrad   Eq. 5, 2nd half  dA3 = dy (*)^T W          (exact: does not touch activations)
+//   conv_wgrad   Eq. 5, 1st half  dW  = A3~^T (*) dy        with A3~ = max(0, dequant(codes))
+//                                 rebuilt in registers on the way to LDS (Eq. 10, Eq. 3)
+//
+// All three are implicit GEMMs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32,
+// 64-lane wavefronts): operand tiles are staged in LDS with the contraction index
+// contiguous, so a lane fetches four consecutive k of its row with one ds_read_b128 and
+// feeds four MFMAs from it.  NHWC activations, [R][S][Cin][Cout] weights.
+
+#include "abl_internal.h"
+
+namespace abl {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+struct ConvGeom {
+  int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
+};
+
+ConvGeom geom_of(const abl_shape& s) {
+  ConvGeom g;
+  g.N = s.N; g.H = s.H; g.W = s.W; g.Cin = s.Cin; g.Cout = s.Cout;
+  g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
+  g.Ho = out_dim(s.H, s.pad, s.R, s.stride);
+  g.Wo = out_dim(s.W, s.pad, s.S, s.stride);
+  return g;
+}
+
+__device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// Implicit GEMM  Out[p][n] = sum_{tap,c} A[p][(tap,c)] * B[(tap,c)][n]
+//   MODE 0 (forward): p = (n,ho,wo), A = a3[n, ho*st+r-pad, wo*st+s-pad, c], c < Cin,
+//                     B = W[r][s][c][n], n < Cout
+//   MODE 1 (dgrad):   p = (n,h,w),   A = dy[n, (h+pad-r)/st, (w+pad-s)/st, c], c < Cout,
+//                     (only where the division is exact and lands inside dy)
+//                     B = W[r][s][n][c], n < Cin
+// Block tile BM x BN, K chunk 16 channels of one filter tap, 4 waves of 64 x WN.
+template <int BM, int BN, int WN, int MODE>
+__global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict__ in,
+                                                         const float* __restrict__ wgt,
+                                                         const float* skip, float* out, ConvGeom g) {
+  constexpr int BK = 16, LDK = BK + 4;
+  constexpr int WM = 64;
+  constexpr int WAVES_N = BN / WN, WAVES_M = 4 / WAVES_N;
+  static_assert(BM == WAVES_M * WM, "tile/wave mismatch");
+  constexpr int MT = WM / 16, NT = WN / 16;
+  constexpr int A_PASSES = BM / 64;
+  constexpr int B_F4 = BK * BN / 4;                        // float4 per B chunk
+  constexpr int B_PASSES = (B_F4 + kThreads - 1) / kThreads;
+
+  __shared__ __attribute__((aligned(16))) float As[BM * LDK];
+  __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+
+  // A-operand tensor dims, output pixel grid, GEMM extents
+  const int Hi = MODE == 0 ? g.H : g.Ho, Wi = MODE == 0 ? g.W : g.Wo;
+  const int Hq = MODE == 0 ? g.Ho : g.H, Wq = MODE == 0 ? g.Wo : g.W;
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const int64_t Mg = (int64_t)g.N * Hq * Wq;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int64_t m0 = (int64_t)blockIdx.x * BM;
+  const int n0 = blockIdx.y * BN;
+
+  // rows of the A tile this thread fetches (one float4 = 4 channels per row and pass)
+  const int a_kq = tid & 3, a_row = tid >> 2;
+  int a_n[A_PASSES], a_h[A_PASSES], a_w[A_PASSES];
+  bool a_ok[A_PASSES];
+#pragma unroll
+  for (int i = 0; i < A_PASSES; ++i) {
+    const int64_t p = m0 + a_row + 64 * i;
+    a_ok[i] = p < Mg;
+    const int64_t pp = a_ok[i] ? p : 0;
+    const int wq = (int)(pp % Wq);
+    const int64_t t = pp / Wq;
+    const int hq = (int)(t % Hq);
+    a_n[i] = (int)(t / Hq);
+    if (MODE == 0) {
+      a_h[i] = hq * g.stride - g.pad;
+      a_w[i] = wq * g.stride - g.pad;
+    } else {
+      a_h[i] = hq + g.pad;
+      a_w[i] = wq + g.pad;
+    }
+  }
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int cchunks = (Cg + BK - 1) / BK;
+  const int iters = g.R * g.S * cchunks;
+  float4 ra[A_PASSES], rb[B_PASSES];
+
+  auto fetch = [&](int it) {
+    const int tap = it / cchunks, c0 = (it - tap * cchunks) * BK;
+    const int r = tap / g.S, s = tap - r * g.S;
+    const int c = c0 + 4 * a_kq;
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i) {
+      int hi, wi;
+      bool ok = a_ok[i] && c < Cg;
+      if (MODE == 0) {
+        hi = a_h[i] + r;
+        wi = a_w[i] + s;
+      } else {
+        const int hh = a_h[i] - r, ww = a_w[i] - s;
+        hi = hh / g.stride;
+        wi = ww / g.stride;
+        ok = ok && hh >= 0 && ww >= 0 && hi * g.stride == hh && wi * g.stride == ww;
+      }
+      ok = ok && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi;
+      ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ok) ra[i] = *reinterpret_cast<const float4*>(in + (((int64_t)a_n[i] * Hi + hi) * Wi + wi) * Cg + c);
+    }
+#pragma unroll
+    for (int j = 0; j < B_PASSES; ++j) {
+      const int idx = tid + kThreads * j;
+      rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (idx < B_F4) {
+        if (MODE == 0) {  // rows k, float4 along n
+          const int kk = idx / (BN / 4), n = n0 + 4 * (idx % (BN / 4));
+          if (c0 + kk < Cg && n < Ng)
+            rb[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + c0 + kk) * g.Cout + n);
+        } else {          // rows n, float4 along k
+          const int nn = n0 + idx / 4, kq = idx % 4;
+          if (nn < Ng && c0 + 4 * kq < Cg)
+            rb[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + nn) * g.Cout + c0 + 4 * kq);
+        }
+      }
+    }
+  };
+
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i)
+      *reinterpret_cast<float4*>(&As[(a_row + 64 * i) * LDK + 4 * a_kq]) = ra[i];
+#pragma unroll
+    for (int j = 0; j < B_PASSES; ++j) {
+      const int idx = tid + kThreads * j;
+      if (idx < B_F4) {
+        if (MODE == 0) {
+          const int kk = idx / (BN / 4), nl = 4 * (idx % (BN / 4));
+          Bs[(nl + 0) * LDK + kk] = rb[j].x;
+          Bs[(nl + 1) * LDK + kk] = rb[j].y;
+          Bs[(nl + 2) * LDK + kk] = rb[j].z;
+          Bs[(nl + 3) * LDK + kk] = rb[j].w;
+        } else {
+          *reinterpret_cast<float4*>(&Bs[(idx / 4) * LDK + 4 * (idx % 4)]) = rb[j];
+        }
+      }
+    }
+  };
+
+  const int li = lane & 15, lk = lane >> 4;
+  fetch(0);
+  for (int it = 0; it < iters; ++it) {
+    stage();
+    __syncthreads();
+    if (it + 1 < iters) fetch(it + 1);
+    float4 af[MT], bf[NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+      af[i] = *reinterpret_cast<const float4*>(&As[(wm0 + 16 * i + li) * LDK + 4 * lk]);
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      bf[j] = *reinterpret_cast<const float4*>(&Bs[(wn0 + 16 * j + li) * LDK + 4 * lk]);
+    // k-step outermost: consecutive MFMAs write different accumulators
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds rows 4*lk + r, column li of each 16x16 tile
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t p = m0 + wm0 + 16 * i + 4 * lk + r;
+      if (p >= Mg) continue;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int n = n0 + wn0 + 16 * j + li;
+        if (n >= Ng) continue;
+        float v = acc[i][j][r];
+        if (skip != nullptr) v += skip[p * Ng + n];
+        out[p * Ng + n] = v;
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight gradient from the packed activation.  One block = one filter tap x TM input
+// channels x TN output channels x one slice of the output pixels; a chunk of 64 pixels is
+// staged in LDS (activations dequantized + ReLU'd to fp32 on the way in), each wave
+// contracts 16 of them into its own accumulators, the four waves are summed in a fixed
+// order at the end.  partial layout: [split][R][S][Cin][Cout].
+template <int TM, int TN, int K>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restrict__ packed,
+                                                         const float* __restrict__ stats,
+                                                         const float* __restrict__ dy,
+                                                         float* __restrict__ partial, ConvGeom g,
+                                                         int chunks_per_split) {
+  constexpr int CH = 64;                                  // pixels per chunk
+  constexpr int LDA = (TM % 32 == 0) ? TM + 16 : TM;
+  constexpr int LDB = (TN % 32 == 0) ? TN + 16 : TN;
+  constexpr int CPW = 32 / K;                             // codes per 32-bit word
+  constexpr int GA = TM / CPW;                            // words per pixel of the A tile
+  constexpr int A_PASSES = (CH * GA + kThreads - 1) / kThreads;
+  constexpr int GB = TN / 4;                              // float4 per pixel of the B tile
+  constexpr int B_PASSES = (CH * GB + kThreads - 1) / kThreads;
+  constexpr int MT = TM / 16, NT = TN / 16;
+  constexpr int SM_AB = CH * (LDA + LDB), SM_RED = TM * TN;
+  __shared__ __attribute__((aligned(16))) float sm[SM_AB > SM_RED ? SM_AB : SM_RED];
+  float* As = sm;
+  float* Bs = sm + CH * LDA;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tiles_m = (g.Cin + TM - 1) / TM, tiles_n = (g.Cout + TN - 1) / TN;
+  int t = blockIdx.x;
+  const int tn = t % tiles_n; t /= tiles_n;
+  const int tm = t % tiles_m; t /= tiles_m;
+  const int tap = t;
+  const int r = tap / g.S, s = tap - r * g.S;
+  const int ci0 = tm * TM, co0 = tn * TN;
+  const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
+  const int64_t p_begin = (int64_t)blockIdx.y * chunks_per_split * CH;
+  int64_t p_end = p_begin + (int64_t)chunks_per_split * CH;
+  if (p_end > Mg) p_end = Mg;
+
+  // per-thread dequantization constants: the thread's channel group is the same in every pass
+  const int a_cg = tid % GA;
+  float step[CPW];
+  int32_t fb[CPW];
+#pragma unroll
+  for (int v = 0; v < CPW; ++v) {
+    const int c = ci0 + a_cg * CPW + v;
+    const bool ok = c < g.Cin;
+    step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
+    fb[v] = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
+  }
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int li = lane & 15, lk = lane >> 4;
+  for (int64_t pc = p_begin; pc < p_end; pc += CH) {
+    uint32_t wa[A_PASSES];
+    bool oka[A_PASSES];
+    float4 rb[B_PASSES];
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i) {
+      const int idx = tid + kThreads * i;
+      const int pl = idx / GA;
+      const int64_t p = pc + pl;
+      oka[i] = idx < CH * GA && p < p_end && (ci0 + a_cg * CPW) < g.Cin;
+      wa[i] = 0;
+      if (oka[i]) {
+        const int wo = (int)(p % g.Wo);
+        const int64_t q = p / g.Wo;
+        const int ho = (int)(q % g.Ho), n = (int)(q / g.Ho);
+        const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s - g.pad;
+        oka[i] = hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+        if (oka[i])
+          wa[i] = packed[((((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci0) / CPW + a_cg];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_PASSES; ++j) {
+      const int idx = tid + kThreads * j;
+      const int pl = idx / GB, c = co0 + 4 * (idx % GB);
+      const int64_t p = pc + pl;
+      rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (idx < CH * GB && p < p_end && c < g.Cout)
+        rb[j] = *reinterpret_cast<const float4*>(dy + p * g.Cout + c);
+    }
+    __syncthreads();  // previous chunk fully consumed
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i) {
+      const int idx = tid + kThreads * i;
+      if (idx < CH * GA) {
+        float* dst = &As[(idx / GA) * LDA + a_cg * CPW];
+#pragma unroll
+        for (int v = 0; v < CPW; ++v) {
+          const int32_t j = (int32_t)((wa[i] >> (K * v)) & ((1u << K) - 1)) - (1 << (K - 1)) + fb[v];
+          const float a2t = step[v] * ((float)j + 0.5f);          // Eq. 10
+          dst[v] = (oka[i] && a2t > 0.f) ? a2t : 0.f;             // Eq. 3
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_PASSES; ++j) {
+      const int idx = tid + kThreads * j;
+      if (idx < CH * GB) *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = rb[j];
+    }
+    __syncthreads();
+    // wave w contracts pixels [16w, 16w+16) of the chunk: 4 MFMA k-steps of 4 pixels
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int row = 16 * wave + 4 * ks + lk;
+      float af[MT], bf[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[i] = As[row * LDA + 16 * i + li];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) bf[j] = Bs[row * LDB + 16 * j + li];
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i], bf[j], acc[i][j]);
+    }
+  }
+
+  // sum the four waves in order 0,1,2,3 through LDS, then write the tile
+  for (int w = 0; w < 4; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            float* d = &sm[(16 * i + 4 * lk + rr) * TN + 16 * j + li];
+            *d = (w == 0) ? acc[i][j][rr] : *d + acc[i][j][rr];
+          }
+    }
+  }
+  __syncthreads();
+  float* dst = partial + (int64_t)blockIdx.y * g.R * g.S * g.Cin * g.Cout;
+  for (int idx = tid; idx < TM * TN / 4; idx += kThreads) {
+    const int i = idx / (TN / 4), j = 4 * (idx % (TN / 4));
+    const int ci = ci0 + i, co = co0 + j;
+    if (ci < g.Cin && co < g.Cout)
+      *reinterpret_cast<float4*>(dst + ((int64_t)tap * g.Cin + ci) * g.Cout + co) =
+          *reinterpret_cast<const float4*>(&sm[i * TN + j]);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const float* __restrict__ partial, int split,
+                                                                int64_t n, float* __restrict__ dw) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int k = 0; k < split; ++k) s += partial[(int64_t)k * n + i];
+  dw[i] = s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fallbacks for channel counts that are not multiples of 16: one thread per output element.
+__global__ __launch_bounds__(kThreads) void naive_fwd_kernel(const float* __restrict__ a3,
+                                                             const float* __restrict__ w, const float* skip,
+                                                             float* out, ConvGeom g) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t total = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
+  if (i >= total) return;
+  const int co = (int)(i % g.Cout);
+  int64_t p = i / g.Cout;
+  const int wo = (int)(p % g.Wo); p /= g.Wo;
+  const int ho = (int)(p % g.Ho);
+  const int n = (int)(p / g.Ho);
+  float acc = 0.f;
+  for (int r = 0; r < g.R; ++r) {
+    const int h = ho * g.stride + r - g.pad;
+    if (h < 0 || h >= g.H) continue;
+    for (int s = 0; s < g.S; ++s) {
+      const int x = wo * g.stride + s - g.pad;
+      if (x < 0 || x >= g.W) continue;
+      const float* ap = a3 + (((int64_t)n * g.H + h) * g.W + x) * g.Cin;
+      const float* wp = w + ((int64_t)(r * g.S + s) * g.Cin) * g.Cout + co;
+      for (int ci = 0; ci < g.Cin; ++ci) acc += ap[ci] * wp[(int64_t)ci * g.Cout];
+    }
+  }
+  if (skip != nullptr) acc += skip[i];
+  out[i] = acc;
+}
+
+__global__ __launch_bounds__(kThreads) void naive_dgrad_kernel(const float* __restrict__ dy,
+                                                               const float* __restrict__ w,
+                                                               float* __restrict__ da3, ConvGeom g) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t total = (int64_t)g.N * g.H * g.W * g.Cin;
+  if (i >= total) return;
+  const int ci = (int)(i % g.Cin);
+  int64_t p = i / g.Cin;
+  const int x = (int)(p % g.W); p /= g.W;
+  const int h = (int)(p % g.H);
+  const int n = (int)(p / g.H);
+  float acc = 0.f;
+  for (int r = 0; r < g.R; ++r) {
+    const int hh = h + g.pad - r;
+    if (hh < 0 || hh % g.stride) continue;
+    const int ho = hh / g.stride;
+    if (ho >= g.Ho) continue;
+    for (int s = 0; s < g.S; ++s) {
+      const int ww = x + g.pad - s;
+      if (ww < 0 || ww % g.stride) continue;
+      const int wo = ww / g.stride;
+      if (wo >= g.Wo) continue;
+      const float* gp = dy + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout;
+      const float* wp = w + ((int64_t)(r * g.S + s) * g.Cin + ci) * g.Cout;
+      for (int co = 0; co < g.Cout; ++co) acc += gp[co] * wp[co];
+    }
+  }
+  da3[i] = acc;
+}
+
+// One block per dW element; the 256 threads stride over the output pixels, fixed-order tree.
+template <int K>
+__global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __restrict__ packed,
+                                                               const float* __restrict__ stats,
+                                                               const float* __restrict__ dy,
+                                                               float* __restrict__ dw, ConvGeom g) {
+  __shared__ float red[kThreads];
+  int t = blockIdx.x;
+  const int co = t % g.Cout; t /= g.Cout;
+  const int ci = t % g.Cin; t /= g.Cin;
+  const int s = t % g.S, r = t / g.S;
+  const float step = stats[P_STEP * g.Cin + ci];
+  const int32_t fb = reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci];
+  const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
+  float acc = 0.f;
+  for (int64_t p = threadIdx.x; p < Mg; p += kThreads) {
+    const int wo = (int)(p % g.Wo);
+    const int64_t q = p / g.Wo;
+    const int ho = (int)(q % g.Ho), n = (int)(q / g.Ho);
+    const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s - g.pad;
+    if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) continue;
+    const int64_t e = (((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci;
+    uint32_t code;
+    if (K == 4) code = (packed[e >> 1] >> ((e & 1) * 4)) & 15u;
+    else code = packed[e];
+    const int32_t j = (int32_t)code - (1 << (K - 1)) + fb;
+    const float a2t = step * ((float)j + 0.5f);
+    if (a2t > 0.f) acc += a2t * dy[p * g.Cout + co];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int h = kThreads / 2; h >= 1; h >>= 1) {
+    if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) dw[blockIdx.x] = red[0];
+}
+
+inline bool mfma_ok(const ConvGeom& g) { return g.Cin % 16 == 0 && g.Cout % 16 == 0; }
+
+template <int MODE>
+int launch_igemm(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip,
+                 float* out) {
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
+  if (Ng > 64) {
+    dim3 grid((unsigned)((Mg + 127) / 128), (Ng + 127) / 128);
+    igemm_kernel<128, 128, 64, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+  } else if (Ng > 32) {
+    dim3 grid((unsigned)((Mg + 255) / 256), (Ng + 63) / 64);
+    igemm_kernel<256, 64, 64, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+  } else if (Ng > 16) {
+    dim3 grid((unsigned)((Mg + 255) / 256), 1);
+    igemm_kernel<256, 32, 32, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+  } else {
+    dim3 grid((unsigned)((Mg + 255) / 256), 1);
+    igemm_kernel<256, 16, 16, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+  }
+  return hip_status();
+}
+
+struct WgradPlan {
+  int tm, tn, tiles, split, chunks_per_split;
+};
+
+WgradPlan wgrad_plan(const ConvGeom& g) {
+  WgradPlan p;
+  p.tm = g.Cin >= 64 ? 64 : (g.Cin >= 32 ? 32 : 16);
+  p.tn = g.Cout >= 64 ? 64 : (g.Cout >= 32 ? 32 : 16);
+  p.tiles = g.R * g.S * ((g.Cin + p.tm - 1) / p.tm) * ((g.Cout + p.tn - 1) / p.tn);
+  const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
+  const int64_t chunks = (Mg + 63) / 64;
+  int64_t split = 1024 / p.tiles;
+  if (split < 1) split = 1;
+  if (split > chunks) split = chunks;
+  p.chunks_per_split = (int)((chunks + split - 1) / split);
+  p.split = (int)((chunks + p.chunks_per_split - 1) / p.chunks_per_split);
+  return p;
+}
+
+}  // namespace
+
+size_t wgrad_partial_bytes(const abl_shape& s) {
+  const ConvGeom g = geom_of(s);
+  if (!mfma_ok(g)) return 256;
+  const WgradPlan p = wgrad_plan(g);
+  const size_t n = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
+  return ((size_t)p.split * n + 255) / 256 * 256;
+}
+
+int launch_conv_fwd(hipStream_t st, const abl_shape& s, const float* a3, const float* w,
+                    const float* skip, float* y) {
+  const ConvGeom g = geom_of(s);
+  if (!mfma_ok(g)) {
+    const int64_t total = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
+    naive_fwd_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(a3, w, skip, y, g);
+    return hip_status();
+  }
+  return launch_igemm<0>(st, g, a3, w, skip, y);
+}
+
+int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const float* w,
+                      float* da3) {
+  const ConvGeom g = geom_of(s);
+  if (!mfma_ok(g)) {
+    const int64_t total = (int64_t)g.N * g.H * g.W * g.Cin;
+    naive_dgrad_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(dy, w, da3, g);
+    return hip_status();
+  }
+  return launch_igemm<1>(st, g, dy, w, nullptr, da3);
+}
+
+template <int TM, int TN>
+static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K,
+                              const void* packed, const float* stats, const float* dy, float* dst) {
+  dim3 grid(p.tiles, p.split);
+  const uint32_t* pk = static_cast<const uint32_t*>(packed);
+  if (K == 4)
+    wgrad_kernel<TM, TN, 4><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split);
+  else
+    wgrad_kernel<TM, TN, 8><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split);
+}
+
+int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const void* packed,
+                             const void* stats, const float* dy, void* scratch, float* dw) {
+  const ConvGeom g = geom_of(s);
+  const float* sp = static_cast<const float*>(stats);
+  if (!mfma_ok(g)) {
+    const unsigned blocks = (unsigned)(g.R * g.S * g.Cin * g.Cout);
+    const uint8_t* pk = static_cast<const uint8_t*>(packed);
+    if (K == 4) naive_wgrad_kernel<4><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
+    else naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
+    return hip_status();
+  }
+  const WgradPlan p = wgrad_plan(g);
+  float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
+  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 32) launch_wgrad_tile<32, 32>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 16) launch_wgrad_tile<32, 16>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, packed, sp, dy, dst);
+  else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, packed, sp, dy, dst);
+  else launch_wgrad_tile<16, 16>(st, g, p, K, packed, sp, dy, dst);
+  if (p.split > 1) {
+    const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
+    wgrad_reduce_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, st>>>(dst, p.split, n, dw);
+  }
+  return hip_status();
+}
+
+}  // namespace abl

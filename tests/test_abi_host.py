@@ -1,0 +1,76 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol that
+include/abl.h declares, and its size queries and argument validation behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1901_07988_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    lib = os.path.join(ROOT, "paper_1901_07988_amd", "libabl.so")
+    if not os.path.exists(lib):
+        from paper_1901_07988_amd import build
+        build.build(verbose=False)
+    from paper_1901_07988_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "abl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(abl_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = declared_symbols()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(B.lib, n), n
+    assert set(names) == set(B.EXPORTS)
+
+
+def test_packed_and_stats_sizes(B, oracle):
+    wls = [synth.config1(), synth.config2(), *synth.config3(), synth.config4(), synth.config5()]
+    for wl in wls:
+        for s in wl.shapes:
+            for K in (4, 8):
+                pb = B.abl_packed_bytes(s.as_tuple(), K)
+                assert pb == oracle.packed_bytes(s.E, K) == 4 * s.E * K // 32       # alpha = K/32
+                meta = B.abl_stats_bytes(s.as_tuple())
+                assert meta == 32 * s.Cin
+                assert pb + meta <= (K / 32 + 0.01) * 4 * s.E
+                assert B.abl_scratch_bytes(s.as_tuple(), K) >= 4 * s.E
+    assert B.abl_packed_bytes((1, 1, 1, 3, 4, 1, 1, 1, 0), 4) == 128      # ragged tail is padded
+    assert B.abl_packed_bytes((1, 3, 3, 43, 4, 1, 1, 1, 0), 8) == 512
+
+
+def test_invalid_arguments_are_rejected_before_any_launch(B):
+    s = B.shape_struct((2, 8, 8, 16, 16, 3, 3, 1, 1))
+    ref = ctypes.byref(s)
+    assert B.lib.abl_packed_bytes(ref, 5) == 0
+    assert B.lib.abl_packed_bytes(None, 4) == 0
+    bad = B.shape_struct((2, 2, 2, 16, 16, 5, 5, 1, 0))                   # filter larger than input
+    assert B.lib.abl_packed_bytes(ctypes.byref(bad), 4) == 0
+    assert B.lib.abl_forward(None, ref, 4, 0, None, None, None, None, None, None, 0, None, None, None) == B.ABL_ERR_ARG
+    assert B.lib.abl_forward(None, ref, 3, 0, 16, 16, 16, 16, None, 16, 0, 16, 16, 16) == B.ABL_ERR_ARG
+    assert B.lib.abl_forward(None, ref, 4, 0, 16, 16, 16, 16, None, 16, 0, 16, 16, 16) == B.ABL_ERR_SCRATCH
+    assert B.lib.abl_forward(None, ref, 4, 0, 20, 16, 16, 16, None, 16, 1 << 30, 16, 16, 16) == B.ABL_ERR_ARG
+    assert B.lib.abl_backward(None, ctypes.byref(bad), 4, 0, 16, 16, 16, 16, 16, 1 << 30, 16, 16, 16, 16) == B.ABL_ERR_SHAPE
+    assert B.lib.abl_bn_stats(None, 16, 0, 16, 16, 16, 4, 16, 1 << 20, 16) == B.ABL_ERR_SHAPE
+    assert B.lib.abl_bn_bwd(None, 16, 16, 16, 10, 16, 4, 8, 16, 1 << 20, 16, 16, 16) == B.ABL_ERR_ARG  # unknown flag
+    assert b"scratch" in B.lib.abl_error_string(B.ABL_ERR_SCRATCH)
+
+
+def test_stack_plan_validation(B):
+    mk = lambda t: dict(shape=t)
+    ok = B.make_layers([mk((2, 8, 8, 16, 32, 3, 3, 2, 1)), mk((2, 4, 4, 32, 32, 3, 3, 1, 1))])
+    assert B.abl_stack_buffer_bytes(ok) == 2 * 8 * 8 * 16 * 4
+    assert B.abl_stack_scratch_bytes(ok, 4) >= 2 * 8 * 8 * 16 * 4
+    broken = B.make_layers([mk((2, 8, 8, 16, 32, 3, 3, 2, 1)), mk((2, 8, 8, 32, 32, 3, 3, 1, 1))])
+    assert B.lib.abl_stack_forward(None, broken, 2, 4, 0, 0, 16, 32, 48, 1 << 30) == B.ABL_ERR_SHAPE

@@ -1,0 +1,322 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: K-bit codes, packed bytes and every integer are bit-exact; fp32 tensors are within
+1e-4 of the oracle, measured per tensor as max|a-b| / max|b|.  A3 and the dequantized A2 are
+the same chain of individually rounded fp32 operations on both sides, so they are compared
+bit for bit as well."""
+import numpy as np
+import pytest
+
+from paper_1901_07988_amd import synth
+from paper_1901_07988_amd.synth import LayerShape
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def G():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_util
+    return gpu_util
+
+
+def rel(a, b):
+    return float(np.max(np.abs(a.astype(np.float64) - b.astype(np.float64))) / max(float(np.max(np.abs(b))), 1e-30))
+
+
+def oshape(o, s):
+    return o.Shape(*s.as_tuple())
+
+
+def rand_affine(rng, C):
+    return rng.uniform(0.5, 1.5, C).astype(np.float32), (rng.standard_normal(C) * 0.2).astype(np.float32)
+
+
+# (M, C): several row tiles with ragged tails; C = 16/64/256/1024 take the vector path,
+# 12/20 the 4-wide path, 7/3 the any-C fallback
+BN_CASES = [(8192, 16), (1000, 16), (4099, 64), (777, 256), (131, 1024), (515, 12), (333, 20), (513, 7),
+            (1, 16), (3, 3), (100, 1)]
+
+
+@pytest.mark.parametrize("M,C", BN_CASES)
+@pytest.mark.parametrize("K", [4, 8])
+def test_stats_codes_and_a3(G, oracle, M, C, K):
+    o = oracle
+    print("case bn M=%d C=%d K=%d" % (M, C, K), flush=True)
+    rng = np.random.default_rng(1000 * M + C + K)
+    x = (rng.standard_normal((M, C)) * rng.uniform(0.5, 3, C) + rng.standard_normal(C)).astype(np.float32)
+    gamma, beta = rand_affine(rng, C)
+    if C > 2:
+        gamma[1] = -gamma[1]                      # a negative scale reverses the bins
+    st = G.run_bn_stats(x, gamma, beta, K)
+    sd = G.stats_to_dict(st, C)
+    mean, var = o.bn_stats(x)
+    rstd = o.bn_rstd(var)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    # tier 2: the statistics themselves (fp64 accumulation on both sides -> same fp32 values)
+    for name, ref in (("mean", mean), ("var", var), ("rstd", rstd)):
+        ulp = np.abs(sd[name].view(np.int32).astype(np.int64) - ref.view(np.int32).astype(np.int64))
+        assert ulp.max() <= 1, (name, ulp.max())
+    np.testing.assert_array_equal(sd["gamma"], gamma)
+    np.testing.assert_array_equal(sd["beta"], beta)
+    np.testing.assert_array_equal(sd["cq"], cq)
+    np.testing.assert_array_equal(sd["step"], step)
+    np.testing.assert_array_equal(sd["fb"], fb)
+    # tier 1: codes and A3 with the GPU's statistics fed to the oracle -> bit-exact
+    a3, packed = G.run_bn_relu_pack(x, st, K)
+    rstd_g = o.bn_rstd(sd["var"])
+    np.testing.assert_array_equal(rstd_g, sd["rstd"])
+    a2_ref, a3_ref = o.bn_relu(x, sd["mean"], sd["rstd"], gamma, beta)
+    packed_ref = o.pack_codes(o.quantize(a2_ref, gamma, beta, K), K)
+    assert a3.tobytes() == a3_ref.tobytes()
+    assert packed.tobytes() == packed_ref.tobytes()
+    # and against the oracle's own statistics
+    _, a3_own = o.bn_relu(x, mean, rstd, gamma, beta)
+    a2_own, _ = o.bn_relu(x, mean, rstd, gamma, beta)
+    own = o.pack_codes(o.quantize(a2_own, gamma, beta, K), K)
+    assert int(np.count_nonzero(own != packed)) == 0
+    assert a3.tobytes() == a3_own.tobytes()
+
+
+@pytest.mark.parametrize("M,C", BN_CASES)
+@pytest.mark.parametrize("K", [4, 8])
+def test_pack_unpack_round_trip(G, oracle, M, C, K):
+    o = oracle
+    print("case pack M=%d C=%d K=%d" % (M, C, K), flush=True)
+    rng = np.random.default_rng(7 * M + C + K)
+    gamma, beta = rand_affine(rng, C)
+    a2 = (gamma * rng.standard_normal((M, C)) * 1.2 + beta).astype(np.float32)
+    a2.reshape(-1)[:: max(1, a2.size // 50)] *= 40          # some far outside the clip range
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    z = np.zeros(C, np.float32)
+    st = G.stats_from_arrays(z, z + 1, z + 1, gamma, beta, cq, step, fb)
+    q_ref = o.quantize(a2, gamma, beta, K)
+    packed = G.run_pack(a2, st, K)
+    assert packed.tobytes() == o.pack_codes(q_ref, K).tobytes()
+    a2t = G.run_unpack(packed, a2.shape, st, K)
+    assert a2t.tobytes() == o.dequantize(q_ref, gamma, beta, K).tobytes()
+    # pack -> unpack -> pack leaves the store unchanged, unpack again gives the same tensor
+    packed2 = G.run_pack(a2t, st, K)
+    assert packed2.tobytes() == packed.tobytes()
+    assert G.run_unpack(packed2, a2.shape, st, K).tobytes() == a2t.tobytes()
+
+
+@pytest.mark.parametrize("M,C", BN_CASES)
+@pytest.mark.parametrize("K", [4, 8])
+def test_bn_backward(G, oracle, M, C, K):
+    o = oracle
+    print("case bnbwd M=%d C=%d K=%d" % (M, C, K), flush=True)
+    rng = np.random.default_rng(13 * M + C + K)
+    x = rng.standard_normal((M, C)).astype(np.float32)
+    gamma, beta = rand_affine(rng, C)
+    mean, var = o.bn_stats(x)
+    rstd = o.bn_rstd(var)
+    a2, _ = o.bn_relu(x, mean, rstd, gamma, beta)
+    q = o.quantize(a2, gamma, beta, K)
+    packed = o.pack_codes(q, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    st = G.stats_from_arrays(mean, var, rstd, gamma, beta, cq, step, fb)
+    da3 = rng.standard_normal((M, C)).astype(np.float32)
+    dx_ref, dg_ref, db_ref = o.bn_relu_bwd(o.dequantize(q, gamma, beta, K), da3, rstd, gamma, beta)
+    dx, dg, db = G.run_bn_bwd(packed, st, da3, K)
+    scale = max(1.0, float(np.abs(da3).sum(0).max()))
+    assert rel(dx, dx_ref) < TOL
+    assert np.max(np.abs(dg - dg_ref)) < TOL * scale and np.max(np.abs(db - db_ref)) < TOL * scale
+    # in place (dx aliases da3) and accumulate
+    dx2, _, _ = G.run_bn_bwd(packed, st, da3, K, alias=True)
+    assert dx2.tobytes() == dx.tobytes()
+    base = rng.standard_normal((M, C)).astype(np.float32)
+    dx3, _, _ = G.run_bn_bwd(packed, st, da3, K, accum_into=base)
+    assert rel(dx3, base + dx_ref) < TOL
+
+
+CONV_CASES = [
+    LayerShape(2, 32, 32, 16, 16),                     # config-1/2 layer, small batch
+    LayerShape(3, 9, 7, 16, 16),                       # ragged pixel tail
+    LayerShape(2, 16, 16, 32, 32),
+    LayerShape(2, 8, 8, 64, 64),
+    LayerShape(2, 32, 32, 16, 32, stride=2),           # config-3 transitions
+    LayerShape(2, 16, 16, 32, 64, stride=2),
+    LayerShape(2, 14, 14, 256, 64, 1, 1, 1, 0),        # bottleneck 1x1s
+    LayerShape(1, 14, 14, 64, 256, 1, 1, 1, 0),
+    LayerShape(1, 7, 7, 1024, 256, 1, 1, 1, 0),
+    LayerShape(1, 14, 14, 256, 256),
+    LayerShape(2, 12, 12, 64, 64),
+    LayerShape(1, 10, 10, 48, 80),                     # channel counts that are not tile multiples
+    LayerShape(2, 9, 9, 96, 144, stride=2),
+    LayerShape(2, 7, 6, 5, 3),                         # fallback kernels (channels not multiple of 16)
+    LayerShape(1, 6, 6, 8, 12, 3, 3, 2, 0),
+    LayerShape(1, 5, 5, 16, 16, 5, 5, 1, 2),           # 5x5 filter
+]
+
+
+@pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
+def test_conv_forward_and_dgrad(G, oracle, s):
+    o = oracle
+    print("case conv", s.as_tuple(), flush=True)
+    rng = np.random.default_rng(sum(s.as_tuple()))
+    a3 = np.maximum(rng.standard_normal((s.N, s.H, s.W, s.Cin)), 0).astype(np.float32)
+    w = synth.he_normal(rng, s)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    y_ref = o.conv_fwd(a3, w, oshape(o, s))
+    assert rel(G.run_conv_fwd(s, a3, w), y_ref) < TOL
+    skip = rng.standard_normal(y_ref.shape).astype(np.float32)
+    assert rel(G.run_conv_fwd(s, a3, w, skip), y_ref + skip) < TOL
+    assert rel(G.run_conv_fwd(s, a3, w, skip, alias_skip=True), y_ref + skip) < TOL
+    assert rel(G.run_conv_dgrad(s, dy, w), o.conv_dgrad(dy, w, oshape(o, s))) < TOL
+
+
+@pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_conv_wgrad_from_packed(G, oracle, s, K):
+    o = oracle
+    print("case wgrad", s.as_tuple(), K, flush=True)
+    rng = np.random.default_rng(sum(s.as_tuple()) + K)
+    gamma, beta = rand_affine(rng, s.Cin)
+    a2 = (gamma * rng.standard_normal((s.N, s.H, s.W, s.Cin)) + beta).astype(np.float32)
+    q = o.quantize(a2, gamma, beta, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    z = np.zeros(s.Cin, np.float32)
+    st = G.stats_from_arrays(z, z + 1, z + 1, gamma, beta, cq, step, fb)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    a3t = np.maximum(o.dequantize(q, gamma, beta, K), 0)
+    dw_ref = o.conv_wgrad(a3t, dy, oshape(o, s))
+    dw = G.run_conv_wgrad(s, K, o.pack_codes(q, K), st, dy)
+    assert rel(dw, dw_ref) < TOL
+
+
+LAYER_CASES = [
+    (synth.config1().shapes[0], "normal", "unit"),             # BASELINE config 1 as is
+    (LayerShape(4, 32, 32, 16, 16), "normal", "random"),
+    (LayerShape(4, 16, 16, 32, 32), "normal", "random"),
+    (LayerShape(4, 32, 32, 16, 32, stride=2), "normal", "random"),
+    (LayerShape(2, 14, 14, 256, 64, 1, 1, 1, 0), "relu_normal", "unit"),
+    (LayerShape(2, 14, 14, 64, 64), "relu_normal", "unit"),
+    (LayerShape(2, 14, 14, 64, 256, 1, 1, 1, 0), "relu_normal", "unit"),
+    (LayerShape(2, 7, 7, 256, 256), "normal", "random"),
+    (LayerShape(3, 7, 5, 6, 10), "normal", "random"),          # fallback path end to end
+]
+
+
+@pytest.mark.parametrize("case", LAYER_CASES, ids=lambda c: "x".join(map(str, c[0].as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_layer_forward_backward(G, oracle, case, K):
+    o = oracle
+    s, xd, aff = case
+    print("case layer", s.as_tuple(), K, flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, synth.DEFAULT_SEED, xd, aff)
+    run = G.LayerRun(s, K)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+    sd = G.stats_to_dict(run.stats, s.Cin)
+    np.testing.assert_array_equal(sd["mean"], saved.mean)
+    np.testing.assert_array_equal(sd["var"], saved.var)
+    np.testing.assert_array_equal(sd["rstd"], saved.rstd)
+    assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+    assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+
+
+def test_layer_forward_is_independent_of_K_and_repeatable(G):
+    s = LayerShape(4, 32, 32, 16, 16)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 1, "normal", "random")
+    outs = []
+    for K in (4, 8, 4):
+        run = G.LayerRun(s, K)
+        y = run.forward(x, w, gamma, beta)
+        outs.append((y, run.backward(dy, w), run.packed.cpu().numpy()))
+    assert outs[0][0].tobytes() == outs[1][0].tobytes()             # y does not see the codes
+    assert outs[0][1][3].tobytes() == outs[1][1][3].tobytes()       # dbeta is exact (Sec. 3.3)
+    assert outs[0][0].tobytes() == outs[2][0].tobytes()             # run twice: identical bits
+    assert outs[0][2].tobytes() == outs[2][2].tobytes()
+    for a, b in zip(outs[0][1], outs[2][1]):
+        assert a.tobytes() == b.tobytes()
+
+
+def test_layer_skip_inplace_and_accumulate(G, oracle):
+    o = oracle
+    s = LayerShape(4, 16, 16, 32, 32)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 2, "normal", "random")
+    rng = np.random.default_rng(5)
+    skip = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    run = G.LayerRun(s, 4)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, 4, oshape(o, s), skip=skip)
+    assert rel(run.forward(x, w, gamma, beta, skip=skip), y_ref) < TOL
+    y_plain, _ = o.layer_forward(x, w, gamma, beta, 4, oshape(o, s))
+    assert rel(run.forward(x, w, gamma, beta, in_place=True), y_plain) < TOL
+    base = rng.standard_normal(x.shape).astype(np.float32)
+    dx, *_ = run.backward(dy, w, accum_into=base)
+    dx_ref, *_ = o.layer_backward(saved, dy, w)
+    assert rel(dx, base + dx_ref) < TOL
+
+
+def _shrunk_stacks():
+    c2 = synth.config2(N=8, layers=6)
+    c3a, c3b = synth.config3(N=4, per_stage=4)
+    c4 = synth.config4(N=2, HW=14)
+    c5 = synth.config5(N=2, blocks=2, HW=7)
+    odd = synth.Workload("chain of 5, skip/2 (trailing layer runs as a plain chain)",
+                         [LayerShape(2, 8, 8, 16, 16)] * 5, 2, "normal", "random")
+    return [c2, c3a, c3b, c4, c5, odd]
+
+
+@pytest.mark.parametrize("wl", _shrunk_stacks(), ids=lambda w: w.name.split(":")[0])
+@pytest.mark.parametrize("K", [4, 8])
+def test_stack_forward_backward(G, oracle, wl, K):
+    """The five workloads at reduced batch / depth / resolution, same structure."""
+    o = oracle
+    print("case stack", wl.name, K, flush=True)
+    x, layers, dy = synth.draw_stack(wl, synth.DEFAULT_SEED)
+    run = G.StackRun(layers, K, wl.skip_every)
+    run.load(x)
+    run.forward()
+    y = run.output()
+    olayers = [(oshape(o, s), w, g, b) for s, w, g, b in layers]
+    y_ref, saved = o.stack_forward(x, olayers, K, np.float32, wl.skip_every)
+    assert rel(y, y_ref) < TOL
+    # the first layer's codes depend on x only: bit-exact; deeper layers quantize activations
+    # that already differ by rounding between the two conv implementations
+    assert run.descs[0]["packed"].cpu().numpy()[: saved[0].store.size].tobytes() == saved[0].store.tobytes()
+    for d, sv in zip(run.descs, saved):
+        got = d["packed"].cpu().numpy()[: sv.store.size]
+        assert np.count_nonzero(got != sv.store) <= max(2, sv.store.size // 2000)
+    run.load(dy)
+    run.backward()
+    dx = run.input_grad()
+    dx_ref, grads = o.stack_backward(saved, olayers, dy, np.float32, wl.skip_every)
+    assert rel(dx, dx_ref) < 20 * TOL
+    for d, (dw, dg, db) in zip(run.descs, grads):
+        assert rel(d["dW"].cpu().numpy(), dw) < 20 * TOL
+        assert rel(d["dgamma"].cpu().numpy(), dg) < 20 * TOL
+        assert rel(d["dbeta"].cpu().numpy(), db) < 20 * TOL
+    exact = sum(4 * s.E for s, *_ in layers)
+    assert run.stored_bytes() <= (K / 32 + 0.01) * exact or exact < 1 << 20
+
+
+def test_error_codes(G):
+    from paper_1901_07988_amd import binding as B
+    import torch
+    s = (2, 8, 8, 16, 16, 3, 3, 1, 1)
+    t = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    small = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.AblError) as e:
+        B.abl_forward(s, 5, t, t, t, t, None, t, t, t, t)
+    assert e.value.code == B.ABL_ERR_ARG
+    with pytest.raises(B.AblError) as e:
+        B.abl_forward((2, 8, 8, 0, 16, 3, 3, 1, 1), 4, t, t, t, t, None, t, t, t, t)
+    assert e.value.code == B.ABL_ERR_SHAPE
+    with pytest.raises(B.AblError) as e:
+        B.abl_forward(s, 4, t, t, t, t, None, small, t, t, t)
+    assert e.value.code == B.ABL_ERR_SCRATCH
+    with pytest.raises(B.AblError) as e:
+        B.abl_forward(s, 4, t.view(-1)[1:], t, t, t, None, t, t, t, t)     # 4-byte aligned only
+    assert e.value.code == B.ABL_ERR_ARG
+    assert B.abl_packed_bytes((2, 1, 1, 3, 16, 1, 1, 1, 0), 4) == 128
+    assert B.abl_packed_bytes(s, 3) == 0
