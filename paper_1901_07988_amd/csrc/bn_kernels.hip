@@ -160,7 +160,7 @@ template <int VEC>
 __global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __restrict__ x, int64_t M,
                                                                  int C, RowGeom g,
                                                                  double* __restrict__ partial) {
-  __shared__ double red[kThreads][2 * VEC];
+  __shared__ double red[2 * VEC][kThreads];  // [value][thread]: conflict-free
   const ThreadPos p = thread_pos<VEC>(g);
   double s[VEC], ss[VEC];
   float k[VEC];
@@ -190,8 +190,8 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __
   }
 #pragma unroll
   for (int v = 0; v < VEC; ++v) {
-    red[threadIdx.x][v] = s[v];
-    red[threadIdx.x][VEC + v] = ss[v];
+    red[v][threadIdx.x] = s[v];
+    red[VEC + v][threadIdx.x] = ss[v];
   }
   __syncthreads();
   // tree over ty (threads tx + TX*ty), fixed order
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __
   for (int h = span >> 1; h >= 1; h >>= 1) {
     if (p.ty < h && p.ty + h < g.TY) {
 #pragma unroll
-      for (int v = 0; v < 2 * VEC; ++v) red[threadIdx.x][v] += red[threadIdx.x + h * g.TX][v];
+      for (int v = 0; v < 2 * VEC; ++v) red[v][threadIdx.x] += red[v][threadIdx.x + h * g.TX];
     }
     __syncthreads();
   }
@@ -208,42 +208,48 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __
     double* out = partial + (int64_t)blockIdx.y * 2 * C + p.c0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      out[v] = red[threadIdx.x][v];
-      out[C + v] = red[threadIdx.x][VEC + v];
+      out[v] = red[v][threadIdx.x];
+      out[C + v] = red[VEC + v][threadIdx.x];
     }
   }
 }
 
-// Sums `nb` partial rows of two per-channel quantities in a fixed order.
-// 256 threads: 64 channels x 4 interleaved parts.
-__device__ inline void reduce_partials(const double* __restrict__ partial, int nb, int C, int c,
-                                       double (&out)[2], double (*sm)[64][2]) {
-  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
-  double a = 0.0, b = 0.0;
+// Sums `nb` partial rows of two per-channel quantities in a fixed order.  A block of 1024
+// threads covers 16 channels: thread = (part 0..31, quantity 0..1, channel 0..15); every thread
+// adds up its interleaved share of the rows, then the 32 parts are combined by a tree in LDS.
+// Returns the two totals of channel blockIdx.x*16 + (threadIdx.x & 15) to threads < 16.
+constexpr int kFinThreads = 1024;
+__device__ inline void reduce_partials(const double* __restrict__ partial, int nb, int C,
+                                       double (&out)[2], double (*sm)[32]) {
+  const int v = threadIdx.x & 31, part = threadIdx.x >> 5;
+  const int c = blockIdx.x * 16 + (v & 15), q = v >> 4;
+  double a = 0.0;
   if (c < C) {
-    for (int i = part; i < nb; i += 4) {
-      a += partial[(int64_t)i * 2 * C + c];
-      b += partial[(int64_t)i * 2 * C + C + c];
-    }
+    const double* src = partial + (int64_t)q * C + c;
+#pragma unroll 8
+    for (int i = part; i < nb; i += 32) a += src[(int64_t)i * 2 * C];
   }
-  sm[part][lane][0] = a;
-  sm[part][lane][1] = b;
+  sm[part][v] = a;
   __syncthreads();
-  out[0] = ((sm[0][lane][0] + sm[1][lane][0]) + sm[2][lane][0]) + sm[3][lane][0];
-  out[1] = ((sm[0][lane][1] + sm[1][lane][1]) + sm[2][lane][1]) + sm[3][lane][1];
+  for (int h = 16; h >= 1; h >>= 1) {
+    if (part < h) sm[part][v] += sm[part + h][v];
+    __syncthreads();
+  }
+  out[0] = sm[0][threadIdx.x & 15];
+  out[1] = sm[0][16 + (threadIdx.x & 15)];
 }
 
 // Eq. 1 statistics, pass 2, and the per-channel constants of Eq. 9/10.
-__global__ __launch_bounds__(kThreads) void stats_finalize_kernel(const double* __restrict__ partial, int nb,
+__global__ __launch_bounds__(kFinThreads) void stats_finalize_kernel(const double* __restrict__ partial, int nb,
                                                                   const float* __restrict__ x, int64_t M,
                                                                   int C, const float* __restrict__ gamma,
                                                                   const float* __restrict__ beta, int K,
                                                                   float* __restrict__ stats) {
-  __shared__ double sm[4][64][2];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  __shared__ double sm[32][32];
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15);
   double t[2];
-  reduce_partials(partial, nb, C, c, t, sm);
-  if (c >= C || threadIdx.x >= 64) return;
+  reduce_partials(partial, nb, C, t, sm);
+  if (c >= C || threadIdx.x >= 16) return;
   const double k = (double)x[c];
   const double mk = t[0] / (double)M;
   double var = t[1] / (double)M - mk * mk;
@@ -372,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
                                                               RowGeom g, const float* __restrict__ stats,
                                                               double* __restrict__ partial) {
   using word_t = typename PackedWord<K, VEC>::type;
-  __shared__ double red[kThreads][2 * VEC];
+  __shared__ double red[2 * VEC][kThreads];  // [value][thread]: conflict-free
   const ThreadPos p = thread_pos<VEC>(g);
   float step[VEC], bt[VEC], ig[VEC];
   int32_t fb[VEC];
@@ -415,8 +421,8 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
   }
 #pragma unroll
   for (int v = 0; v < VEC; ++v) {
-    red[threadIdx.x][v] = s1[v];
-    red[threadIdx.x][VEC + v] = s2[v];
+    red[v][threadIdx.x] = s1[v];
+    red[VEC + v][threadIdx.x] = s2[v];
   }
   __syncthreads();
   int span = 1;
@@ -424,7 +430,7 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
   for (int h = span >> 1; h >= 1; h >>= 1) {
     if (p.ty < h && p.ty + h < g.TY) {
 #pragma unroll
-      for (int v = 0; v < 2 * VEC; ++v) red[threadIdx.x][v] += red[threadIdx.x + h * g.TX][v];
+      for (int v = 0; v < 2 * VEC; ++v) red[v][threadIdx.x] += red[v][threadIdx.x + h * g.TX];
     }
     __syncthreads();
   }
@@ -432,25 +438,25 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
     double* out = partial + (int64_t)blockIdx.y * 2 * C + p.c0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      out[v] = red[threadIdx.x][v];
-      out[C + v] = red[threadIdx.x][VEC + v];
+      out[v] = red[v][threadIdx.x];
+      out[C + v] = red[VEC + v][threadIdx.x];
     }
   }
 }
 
 // Backward, pass 1b: dbeta, dgamma (Eq. 7) and the two per-channel means of Eq. 8.
 // means layout: [2][C] floats = Mean(dA1), Mean(A1~ * dA1) with dA1 = gamma * dA2.
-__global__ __launch_bounds__(kThreads) void bwd_finalize_kernel(const double* __restrict__ partial, int nb,
+__global__ __launch_bounds__(kFinThreads) void bwd_finalize_kernel(const double* __restrict__ partial, int nb,
                                                                 int64_t M, int C,
                                                                 const float* __restrict__ stats,
                                                                 float* __restrict__ dgamma,
                                                                 float* __restrict__ dbeta,
                                                                 float* __restrict__ means) {
-  __shared__ double sm[4][64][2];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  __shared__ double sm[32][32];
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15);
   double t[2];
-  reduce_partials(partial, nb, C, c, t, sm);
-  if (c >= C || threadIdx.x >= 64) return;
+  reduce_partials(partial, nb, C, t, sm);
+  if (c >= C || threadIdx.x >= 16) return;
   const double gm = (double)stats[P_GAMMA * C + c];
   dbeta[c] = (float)t[0];
   dgamma[c] = (float)t[1];
@@ -577,7 +583,7 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_reduce_kernel(const uint8_t
                                                                    int C, RowGeom g,
                                                                    const float* __restrict__ stats,
                                                                    double* __restrict__ partial) {
-  __shared__ double red[kThreads][2];
+  __shared__ double red[2][kThreads];
   const ThreadPos p = thread_pos<1>(g);
   const int c = p.c0;
   const float step = stats[P_STEP * C + c], bt = stats[P_BETA * C + c];
@@ -596,21 +602,21 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_reduce_kernel(const uint8_t
       s2 += (double)a1t * (double)da2;
     }
   }
-  red[threadIdx.x][0] = s1;
-  red[threadIdx.x][1] = s2;
+  red[0][threadIdx.x] = s1;
+  red[1][threadIdx.x] = s2;
   __syncthreads();
   int span = 1;
   while (span < g.TY) span <<= 1;
   for (int h = span >> 1; h >= 1; h >>= 1) {
     if (p.ty < h && p.ty + h < g.TY) {
-      red[threadIdx.x][0] += red[threadIdx.x + h * g.TX][0];
-      red[threadIdx.x][1] += red[threadIdx.x + h * g.TX][1];
+      red[0][threadIdx.x] += red[0][threadIdx.x + h * g.TX];
+      red[1][threadIdx.x] += red[1][threadIdx.x + h * g.TX];
     }
     __syncthreads();
   }
   if (p.active && p.ty == 0) {
-    partial[(int64_t)blockIdx.y * 2 * C + c] = red[threadIdx.x][0];
-    partial[(int64_t)blockIdx.y * 2 * C + C + c] = red[threadIdx.x][1];
+    partial[(int64_t)blockIdx.y * 2 * C + c] = red[0][threadIdx.x];
+    partial[(int64_t)blockIdx.y * 2 * C + C + c] = red[1][threadIdx.x];
   }
 }
 
@@ -665,7 +671,7 @@ int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const floa
     stats_partial_kernel<4><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
   else
     stats_partial_kernel<1><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
-  stats_finalize_kernel<<<(C + 63) / 64, kThreads, 0, st>>>(partial, g.gridY, x, M, C, gamma, beta, K,
+  stats_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, g.gridY, x, M, C, gamma, beta, K,
                                                             static_cast<float*>(stats));
   return hip_status();
 }
@@ -754,7 +760,7 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
   } else {
     bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
   }
-  bwd_finalize_kernel<<<(C + 63) / 64, kThreads, 0, st>>>(partial, gr.gridY, M, C, sp, dgamma, dbeta, means);
+  bwd_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, gr.gridY, M, C, sp, dgamma, dbeta, means);
   if (vec == 0) {
     const int64_t E = M * C;
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);

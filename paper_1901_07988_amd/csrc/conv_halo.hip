@@ -1,0 +1,557 @@
+// Stride-1 convolutions (Eq. 4 forward, Eq. 5 gradient to the input) for filters larger than
+// 1x1 on gfx950, with the input tile staged ONCE in LDS.
+//
+// An implicit GEMM that gathers its A operand tap by tap re-reads every input pixel R*S times
+// from L2.  Here a block owns a tile of TI images x TH x TW output pixels; for each chunk of
+// 16 input channels it stages the (TH+R-1) x (TW+S-1) input patch (zero filled outside the
+// image) and the R*S*16 x BN slice of the weights, and every filter tap then reads its
+// shifted view of that patch straight from LDS as the MFMA A operand
+// (v_mfma_f32_16x16x4_f32; one ds_read_b128 = four k-steps).  An M-tile is 16 consecutive
+// output pixels of the flattened tile, so tiles of any shape fill the matrix cores.
+//
+// MODE 0 forward : out[n,h,w,co] = sum in[n, h+r-pad, w+s-pad, ci] W[r,s,ci,co]
+// MODE 1 dgrad   : out[n,h,w,ci] = sum in[n, h+pad-r, w+pad-s, co] W[r,s,ci,co]   (in = dy)
+
+#include "abl_internal.h"
+
+namespace abl {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int PS = 20;     // floats per staged pixel: 16 channels + 4 pad (conflict-free b128 reads)
+constexpr int AMAX = 8;    // float4 slots per thread for the input patch (<= 512 staged pixels)
+
+struct HaloPlan {
+  int TI, TH, TW;                 // output tile: images, rows, cols
+  int HH, HW;                     // staged patch rows, cols
+  int tiles_i, tiles_h, tiles_w;  // tiles per batch / image height / image width
+  int npix;                       // TI*TH*TW
+  int mtiles;                     // ceil(npix / 16)
+  int variant;                    // index into the instantiation table
+  int bn;                         // output channels per block
+  unsigned lds_bytes;
+};
+
+__device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// WAVES_N waves share the block's M-tiles and split its N-tiles; the other 4/WAVES_N groups
+// split the M-tiles.  MT = M-tiles per wave (upper bound, `mtiles` is the real count),
+// NT = N-tiles per wave.
+template <int MODE, int WAVES_N, int MT, int NT>
+__global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __restrict__ in,
+                                                             const float* __restrict__ wgt, const float* skip,
+                                                             float* out, ConvGeom g, HaloPlan p) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  constexpr int WAVES_M = 4 / WAVES_N;
+  constexpr int BN = WAVES_N * NT * 16;
+  const int taps = g.R * g.S;
+  const int BS = taps * 16 + 4;  // floats per staged weight row (one output channel)
+  float* tileA = lds;
+  float* tileB = lds + p.TI * p.HH * p.HW * PS;
+
+  const int Hi = MODE == 0 ? g.H : g.Ho, Wi = MODE == 0 ? g.W : g.Wo;
+  const int Hq = MODE == 0 ? g.Ho : g.H, Wq = MODE == 0 ? g.Wo : g.W;
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lk = lane >> 4;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  const int wn0 = wave_n * NT * 16;
+
+  int b = blockIdx.x;
+  const int tw_i = b % p.tiles_w; b /= p.tiles_w;
+  const int th_i = b % p.tiles_h; b /= p.tiles_h;
+  const int img0 = b * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
+  const int n0 = blockIdx.y * BN;
+  // input coordinate of patch element (0,0)
+  const int oh = h0 + (MODE == 0 ? -g.pad : g.pad - (g.R - 1));
+  const int ow = w0 + (MODE == 0 ? -g.pad : g.pad - (g.S - 1));
+
+  // global offsets (in floats, channel 0) of the patch elements this thread stages; -1 = zero fill
+  const int totalA = p.TI * p.HH * p.HW * 4;
+  int goff[AMAX];
+#pragma unroll
+  for (int j = 0; j < AMAX; ++j) {
+    const int idx = tid + kThreads * j;
+    goff[j] = -1;
+    if (idx < totalA) {
+      int pix = idx >> 2;
+      const int ww = pix % p.HW; pix /= p.HW;
+      const int hh = pix % p.HH;
+      const int ti = pix / p.HH;
+      const int n = img0 + ti, hi = oh + hh, wi = ow + ww;
+      if (n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi)
+        goff[j] = ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3);
+    }
+  }
+
+  // LDS base of this lane's pixel in each of the wave's M-tiles
+  int base[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int m = (wave_m * MT + i) * 16 + li;
+    if (m >= p.npix) m = p.npix - 1;
+    const int w = m % p.TW; m /= p.TW;
+    const int h = m % p.TH;
+    const int ti = m / p.TH;
+    base[i] = ((ti * p.HH + h) * p.HW + w) * PS + 4 * lk;
+  }
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int totalB = taps * 4 * BN;  // float4 per weight chunk
+  for (int c0 = 0; c0 < Cg; c0 += 16) {
+    __syncthreads();  // previous chunk consumed
+#pragma unroll
+    for (int j = 0; j < AMAX; ++j) {
+      const int idx = tid + kThreads * j;
+      if (idx < totalA) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (goff[j] >= 0 && c0 + 4 * (idx & 3) < Cg) v = *reinterpret_cast<const float4*>(in + goff[j] + c0);
+        *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = v;
+      }
+    }
+    for (int idx = tid; idx < totalB; idx += kThreads) {
+      if (MODE == 0) {  // W rows (tap, ci) are contiguous in co: transpose into [co][tap*16 + ci]
+        const int k = idx / (BN / 4), nl = 4 * (idx % (BN / 4));
+        const int tap = k >> 4, c = c0 + (k & 15);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < Cg && n0 + nl < Ng)
+          v = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + c) * g.Cout + n0 + nl);
+        tileB[(nl + 0) * BS + k] = v.x;
+        tileB[(nl + 1) * BS + k] = v.y;
+        tileB[(nl + 2) * BS + k] = v.z;
+        tileB[(nl + 3) * BS + k] = v.w;
+      } else {          // W rows (tap, ci) hold the contraction index co contiguously
+        const int nl = idx / (taps * 4), rem = idx % (taps * 4);
+        const int tap = rem >> 2, kq = rem & 3;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n0 + nl < Ng && c0 + 4 * kq < Cg)
+          v = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + n0 + nl) * g.Cout + c0 + 4 * kq);
+        *reinterpret_cast<float4*>(&tileB[nl * BS + tap * 16 + 4 * kq]) = v;
+      }
+    }
+    __syncthreads();
+    for (int t = 0; t < taps; ++t) {
+      const int r = t / g.S, s = t - r * g.S;
+      const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
+      const int aoff = (rr * p.HW + ss) * PS;
+      float4 af[MT], bf[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        bf[j] = *reinterpret_cast<const float4*>(&tileB[(wn0 + 16 * j + li) * BS + t * 16 + 4 * lk]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+    }
+  }
+
+  // epilogue: the lane holds pixels 4*lk .. 4*lk+3 of each M-tile, channel li of each N-tile
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int m = (wave_m * MT + i) * 16 + 4 * lk;
+    int w = m % p.TW;
+    int q = m / p.TW;
+    int h = q % p.TH;
+    int ti = q / p.TH;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
+      if (m + rr < p.npix && n < g.N && hq < Hq && wq < Wq) {
+        const int64_t pix = ((int64_t)n * Hq + hq) * Wq + wq;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int c = n0 + wn0 + 16 * j + li;
+          if (c < Ng) {
+            float v = acc[i][j][rr];
+            if (skip != nullptr) v += skip[pix * Ng + c];
+            out[pix * Ng + c] = v;
+          }
+        }
+      }
+      if (++w == p.TW) {
+        w = 0;
+        if (++h == p.TH) {
+          h = 0;
+          ++ti;
+        }
+      }
+    }
+  }
+}
+
+// ---- host side ----------------------------------------------------------------------------
+struct Variant {
+  int waves_n, mt, nt;
+};
+// instantiation table; `variant` in the plan indexes it
+constexpr Variant kVariants[] = {
+    {1, 4, 1},   // 0: 256 px x 16 ch   (16-channel CIFAR layers)
+    {1, 2, 2},   // 1: 128 px x 32 ch
+    {1, 4, 2},   // 2: 256 px x 32 ch
+    {4, 4, 1},   // 3: 64 px x 64 ch
+    {4, 8, 1},   // 4: 128 px x 64 ch
+    {4, 14, 1},  // 5: 224 px x 64 ch   (56x56 and 14x14 ImageNet layers)
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Choose the tile shape with at most `maxpix` output pixels that minimises staged patch
+// elements plus padded M-tile work over the whole image.
+void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
+  if (Hq * Wq <= maxpix) {
+    p.TH = Hq; p.TW = Wq;
+    p.TI = maxpix / (Hq * Wq);
+    if (p.TI > N) p.TI = N;
+    while (p.TI > 1 && p.TI * (Hq + R - 1) * (Wq + S - 1) * 4 > AMAX * kThreads) --p.TI;
+  } else {
+    p.TI = 1;
+    p.TH = p.TW = 0;
+    long best = -1;
+    for (int kw = 1; kw <= 16; ++kw) {
+      const int tw = cdiv(Wq, kw);
+      if (tw > maxpix) continue;
+      for (int kh = 1; kh <= Hq; ++kh) {
+        const int th = cdiv(Hq, kh);
+        if (th * tw > maxpix) continue;
+        if ((th + R - 1) * (tw + S - 1) * 4 > AMAX * kThreads) continue;
+        const long tiles = (long)cdiv(Hq, th) * cdiv(Wq, tw);
+        const long cost = tiles * ((long)(th + R - 1) * (tw + S - 1) + 2L * 16 * cdiv(th * tw, 16));
+        if (best < 0 || cost < best) {
+          best = cost;
+          p.TH = th; p.TW = tw;
+        }
+        break;  // larger kh only shrinks the tile further
+      }
+    }
+  }
+  p.HH = p.TH + R - 1;
+  p.HW = p.TW + S - 1;
+  p.tiles_i = cdiv(N, p.TI);
+  p.tiles_h = cdiv(Hq, p.TH);
+  p.tiles_w = cdiv(Wq, p.TW);
+  p.npix = p.TI * p.TH * p.TW;
+  p.mtiles = cdiv(p.npix, 16);
+}
+
+bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
+  const int Hq = mode == 0 ? g.Ho : g.H, Wq = mode == 0 ? g.Wo : g.W;
+  const int Ng = mode == 0 ? g.Cout : g.Cin;
+  int v;
+  if (Ng <= 16) v = 0;
+  else if (Ng <= 32) v = (int64_t)g.N * Hq * Wq >= 256 * 512 ? 2 : 1;
+  else {
+    const int64_t px = (int64_t)g.N * Hq * Wq * cdiv(Ng, 64);
+    v = px >= 224 * 512 ? 5 : (px >= 128 * 512 ? 4 : 3);
+  }
+  const Variant& var = kVariants[v];
+  const int waves_m = 4 / var.waves_n;
+  choose_tile(Hq, Wq, g.N, g.R, g.S, waves_m * var.mt * 16, p);
+  p.variant = v;
+  p.bn = var.waves_n * var.nt * 16;
+  const size_t fl = (size_t)p.TI * p.HH * p.HW * PS + (size_t)p.bn * (g.R * g.S * 16 + 4);
+  p.lds_bytes = (unsigned)(fl * sizeof(float));
+  return p.lds_bytes <= 64 * 1024 && p.TI * p.HH * p.HW * 4 <= AMAX * kThreads && p.TH > 0;
+}
+
+template <int MODE, int V>
+void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const float* in, const float* w,
+                    const float* skip, float* out) {
+  constexpr Variant var = kVariants[V];
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  dim3 grid(p.tiles_i * p.tiles_h * p.tiles_w, cdiv(Ng, p.bn));
+  halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
+}
+
+template <int MODE>
+void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const float* in, const float* w,
+                 const float* skip, float* out) {
+  switch (p.variant) {
+    case 0: launch_variant<MODE, 0>(st, g, p, in, w, skip, out); break;
+    case 1: launch_variant<MODE, 1>(st, g, p, in, w, skip, out); break;
+    case 2: launch_variant<MODE, 2>(st, g, p, in, w, skip, out); break;
+    case 3: launch_variant<MODE, 3>(st, g, p, in, w, skip, out); break;
+    case 4: launch_variant<MODE, 4>(st, g, p, in, w, skip, out); break;
+    default: launch_variant<MODE, 5>(st, g, p, in, w, skip, out); break;
+  }
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Weight gradient (Eq. 5) of a stride-1 RxS convolution from the packed activation, all taps
+// in one pass.  A block owns 16 input channels x 16*NT output channels and walks over pixel
+// tiles; per tile it stages the dequantized + ReLU'd activation patch (Eq. 10, Eq. 3) and the
+// dy tile in LDS once, and every group of 4 output pixels then feeds R*S MFMAs (one per tap,
+// A = activation at the shifted pixel, B = dy).  dy is read once per block instead of once per
+// tap.  The four waves take interleaved pixel groups and are summed in a fixed order at the
+// end.  partial layout: [gridDim.x][R][S][Cin][Cout].
+template <int K, int NT, int R, int S>
+__global__ __launch_bounds__(kThreads) void halo_wgrad_kernel(const uint32_t* __restrict__ packed,
+                                                              const float* __restrict__ stats,
+                                                              const float* __restrict__ dy,
+                                                              float* __restrict__ partial, ConvGeom g,
+                                                              HaloPlan p) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  constexpr int TAPS = R * S;
+  constexpr int BNW = 16 * NT;
+  constexpr int PSB = (BNW % 32 == 0) ? BNW + 16 : BNW;
+  constexpr int WPP = 16 * K / 32;  // packed 32-bit words per pixel for 16 channels
+  const int patch = p.TI * p.HH * p.HW;
+  const int npix4 = (p.npix + 3) & ~3;
+  float* tileA = lds;                       // [patch][16]
+  float* tileB = tileA + patch * 16;        // [npix4][PSB]
+  int* pixbase = reinterpret_cast<int*>(tileB + npix4 * PSB);  // [npix4] LDS offset of pixel m in tileA
+  int* pixloc = pixbase + npix4;                               // [npix4] (ti<<16)|(h<<8)|w, -1 = padding
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lk = lane >> 4;
+  const int cout_blocks = (g.Cout + BNW - 1) / BNW;
+  const int ci0 = (blockIdx.y / cout_blocks) * 16, co0 = (blockIdx.y % cout_blocks) * BNW;
+
+  for (int m = tid; m < npix4; m += kThreads) {
+    if (m < p.npix) {
+      const int w = m % p.TW, q = m / p.TW;
+      const int h = q % p.TH, ti = q / p.TH;
+      pixbase[m] = ((ti * p.HH + h) * p.HW + w) * 16;
+      pixloc[m] = (ti << 16) | (h << 8) | w;
+    } else {
+      pixbase[m] = 0;
+      pixloc[m] = -1;
+    }
+  }
+
+  float step[16];
+  int32_t fb[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    step[v] = stats[P_STEP * g.Cin + ci0 + v];
+    fb[v] = reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci0 + v];
+  }
+
+  floatx4 acc[TAPS][NT];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[t][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int ntiles = p.tiles_i * p.tiles_h * p.tiles_w;
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    int b = tile;
+    const int tw_i = b % p.tiles_w; b /= p.tiles_w;
+    const int th_i = b % p.tiles_h; b /= p.tiles_h;
+    const int img0 = b * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
+    __syncthreads();  // previous tile consumed (and the lookup tables written)
+    for (int idx = tid; idx < patch; idx += kThreads) {
+      int pix = idx;
+      const int ww = pix % p.HW; pix /= p.HW;
+      const int hh = pix % p.HH;
+      const int ti = pix / p.HH;
+      const int n = img0 + ti, hi = h0 - g.pad + hh, wi = w0 - g.pad + ww;
+      uint32_t wd[WPP];
+      const bool ok = n < g.N && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+      if (ok) {
+        const uint32_t* src = packed + ((((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci0) * K / 32;
+        if (WPP == 2) {
+          const uint2 t = *reinterpret_cast<const uint2*>(src);
+          wd[0] = t.x; wd[1] = t.y;
+        } else {
+          const uint4 t = *reinterpret_cast<const uint4*>(src);
+          wd[0] = t.x; wd[1] = t.y; wd[2 % WPP] = t.z; wd[3 % WPP] = t.w;
+        }
+      }
+      float v[16];
+#pragma unroll
+      for (int c = 0; c < 16; ++c) {
+        const uint32_t code = ok ? (wd[c * K / 32] >> ((c * K) % 32)) & ((1u << K) - 1) : 0u;
+        const int32_t j = (int32_t)code - (1 << (K - 1)) + fb[c];
+        const float a2t = step[c] * ((float)j + 0.5f);  // Eq. 10
+        v[c] = (ok && a2t > 0.f) ? a2t : 0.f;           // Eq. 3
+      }
+      float4* dst = reinterpret_cast<float4*>(&tileA[idx * 16]);
+      dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+      dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+      dst[2] = make_float4(v[8], v[9], v[10], v[11]);
+      dst[3] = make_float4(v[12], v[13], v[14], v[15]);
+    }
+    for (int idx = tid; idx < npix4 * (BNW / 4); idx += kThreads) {
+      const int m = idx / (BNW / 4), c4 = 4 * (idx % (BNW / 4));
+      const int loc = pixloc[m];
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (loc >= 0) {
+        const int n = img0 + (loc >> 16), ho = h0 + ((loc >> 8) & 255), wo = w0 + (loc & 255);
+        if (n < g.N && ho < g.Ho && wo < g.Wo && co0 + c4 < g.Cout)
+          v = *reinterpret_cast<const float4*>(dy + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout + co0 + c4);
+      }
+      *reinterpret_cast<float4*>(&tileB[m * PSB + c4]) = v;
+    }
+    __syncthreads();
+    for (int q = wave; q < npix4 / 4; q += 4) {
+      const int m = 4 * q + lk;
+      const int pb = pixbase[m] + li;
+      float bf[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) bf[j] = tileB[m * PSB + 16 * j + li];
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) {
+        const float a = tileA[pb + ((t / S) * p.HW + (t % S)) * 16];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[t][j] = mfma16(a, bf[j], acc[t][j]);
+      }
+    }
+  }
+
+  // sum the four waves in order through LDS: red[tap][ci][co]
+  float* red = lds;
+  for (int w = 0; w < 4; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            float* d = &red[(t * 16 + 4 * lk + rr) * BNW + 16 * j + li];
+            *d = (w == 0) ? acc[t][j][rr] : *d + acc[t][j][rr];
+          }
+    }
+  }
+  __syncthreads();
+  float* dst = partial + (int64_t)blockIdx.x * TAPS * g.Cin * g.Cout;
+  for (int idx = tid; idx < TAPS * 16 * (BNW / 4); idx += kThreads) {
+    const int row = idx / (BNW / 4), c4 = 4 * (idx % (BNW / 4));
+    const int t = row >> 4, ci = ci0 + (row & 15);
+    if (co0 + c4 < g.Cout)
+      *reinterpret_cast<float4*>(dst + ((int64_t)t * g.Cin + ci) * g.Cout + co0 + c4) =
+          *reinterpret_cast<const float4*>(&red[row * BNW + c4]);
+  }
+}
+
+// dW[i] = sum of nb partial copies, fixed order: 16 outputs x 16 interleaved parts per block.
+__global__ __launch_bounds__(kThreads) void partial_sum_kernel(const float* __restrict__ partial, int nb,
+                                                               int64_t n, float* __restrict__ dw) {
+  __shared__ float sm[16][17];
+  const int o = threadIdx.x & 15, part = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + o;
+  float s = 0.f;
+  if (i < n) {
+#pragma unroll 8
+    for (int k = part; k < nb; k += 16) s += partial[(int64_t)k * n + i];
+  }
+  sm[part][o] = s;
+  __syncthreads();
+  for (int h = 8; h >= 1; h >>= 1) {
+    if (part < h) sm[part][o] += sm[part + h][o];
+    __syncthreads();
+  }
+  if (part == 0 && i < n) dw[i] = sm[0][o];
+}
+
+struct WgradHaloPlan {
+  HaloPlan tile;
+  int nt;        // 16-wide output-channel tiles per block
+  int nblk;      // blocks along the pixel tiles (= number of partial copies)
+  int gridy;     // cin chunks x cout blocks
+};
+
+bool make_wgrad_plan(const ConvGeom& g, WgradHaloPlan& wp) {
+  if (g.stride != 1 || g.R != 3 || g.S != 3 || g.Cin % 16 != 0 || g.Cout % 16 != 0 || g.pad > 2) return false;
+  wp.nt = g.Cout >= 64 ? 4 : (g.Cout >= 32 ? 2 : 1);
+  HaloPlan& p = wp.tile;
+  choose_tile(g.Ho, g.Wo, g.N, g.R, g.S, 256, p);
+  if (p.TH <= 0 || p.TH > 255 || p.TW > 255) return false;
+  const int bnw = 16 * wp.nt, psb = (bnw % 32 == 0) ? bnw + 16 : bnw;
+  const int npix4 = (p.npix + 3) & ~3;
+  size_t fl = (size_t)p.TI * p.HH * p.HW * 16 + (size_t)npix4 * psb + 2 * (size_t)npix4;
+  const size_t red = (size_t)g.R * g.S * 16 * bnw;
+  if (fl < red) fl = red;
+  p.lds_bytes = (unsigned)(fl * sizeof(float));
+  if (p.lds_bytes > 64 * 1024) return false;
+  wp.gridy = (g.Cin / 16) * ((g.Cout + bnw - 1) / bnw);
+  const int ntiles = p.tiles_i * p.tiles_h * p.tiles_w;
+  int nblk = 512 / wp.gridy;
+  if (nblk < 16) nblk = 16;
+  if (nblk > ntiles) nblk = ntiles;
+  // even share of tiles per block
+  const int per = cdiv(ntiles, nblk);
+  wp.nblk = cdiv(ntiles, per);
+  return true;
+}
+
+}  // namespace
+
+bool halo_conv_supported(const ConvGeom& g) {
+  if (g.stride != 1 || g.R * g.S < 2 || g.R > 7 || g.S > 7) return false;
+  if (g.Cin % 16 != 0 || g.Cout % 16 != 0) return false;
+  if (g.pad > g.R - 1 || g.pad > g.S - 1) return false;
+  HaloPlan p;
+  return make_plan(g, 0, p) && make_plan(g, 1, p);
+}
+
+int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                     const float* skip, float* out) {
+  HaloPlan p;
+  if (!make_plan(g, mode, p)) return ABL_ERR_SHAPE;
+  if (mode == 0) launch_mode<0>(st, g, p, in, w, skip, out);
+  else launch_mode<1>(st, g, p, in, w, nullptr, out);
+  return hip_status();
+}
+
+}  // namespace abl
+
+namespace abl {
+
+size_t halo_wgrad_partial_bytes(const ConvGeom& g) {
+  WgradHaloPlan wp;
+  if (!make_wgrad_plan(g, wp)) return 0;
+  return ((size_t)wp.nblk * g.R * g.S * g.Cin * g.Cout * sizeof(float) + 255) / 256 * 256;
+}
+
+int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+                      const float* dy, void* scratch, float* dw) {
+  WgradHaloPlan wp;
+  if (!make_wgrad_plan(g, wp)) return ABL_ERR_SHAPE;
+  const uint32_t* pk = static_cast<const uint32_t*>(packed);
+  float* part = wp.nblk == 1 ? dw : static_cast<float*>(scratch);
+  dim3 grid(wp.nblk, wp.gridy);
+  const unsigned lds = wp.tile.lds_bytes;
+#define ABL_WG(KK, NN) halo_wgrad_kernel<KK, NN, 3, 3><<<grid, kThreads, lds, st>>>(pk, stats, dy, part, g, wp.tile)
+  if (K == 4) {
+    if (wp.nt == 1) ABL_WG(4, 1); else if (wp.nt == 2) ABL_WG(4, 2); else ABL_WG(4, 4);
+  } else {
+    if (wp.nt == 1) ABL_WG(8, 1); else if (wp.nt == 2) ABL_WG(8, 2); else ABL_WG(8, 4);
+  }
+#undef ABL_WG
+  if (wp.nblk > 1) {
+    const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
+    partial_sum_kernel<<<(unsigned)((n + 15) / 16), kThreads, 0, st>>>(part, wp.nblk, n, dw);
+  }
+  return hip_status();
+}
+
+}  // namespace abl

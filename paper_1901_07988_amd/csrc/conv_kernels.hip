@@ -18,19 +18,6 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 
-struct ConvGeom {
-  int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
-};
-
-ConvGeom geom_of(const abl_shape& s) {
-  ConvGeom g;
-  g.N = s.N; g.H = s.H; g.W = s.W; g.Cin = s.Cin; g.Cout = s.Cout;
-  g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
-  g.Ho = out_dim(s.H, s.pad, s.R, s.stride);
-  g.Wo = out_dim(s.W, s.pad, s.S, s.stride);
-  return g;
-}
-
 __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
@@ -364,13 +351,20 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
   }
 }
 
+// dW[i] = sum over the split-K partials, fixed order: 64 outputs x 4 interleaved parts per block.
 __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const float* __restrict__ partial, int split,
                                                                 int64_t n, float* __restrict__ dw) {
-  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= n) return;
+  __shared__ float sm[4][64];
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
   float s = 0.f;
-  for (int k = 0; k < split; ++k) s += partial[(int64_t)k * n + i];
-  dw[i] = s;
+  if (i < n) {
+#pragma unroll 8
+    for (int k = part; k < split; k += 4) s += partial[(int64_t)k * n + i];
+  }
+  sm[part][lane] = s;
+  __syncthreads();
+  if (part == 0 && i < n) dw[i] = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -505,6 +499,7 @@ WgradPlan wgrad_plan(const ConvGeom& g) {
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
   const int64_t chunks = (Mg + 63) / 64;
   int64_t split = 1024 / p.tiles;
+  if (split > 64) split = 64;
   if (split < 1) split = 1;
   if (split > chunks) split = chunks;
   p.chunks_per_split = (int)((chunks + split - 1) / split);
@@ -514,9 +509,13 @@ WgradPlan wgrad_plan(const ConvGeom& g) {
 
 }  // namespace
 
+// Shapes for which the all-taps kernel is used instead of the per-tap one.
+inline bool use_halo_wgrad(const ConvGeom& g) { return g.Cin <= 64 && halo_wgrad_partial_bytes(g) != 0; }
+
 size_t wgrad_partial_bytes(const abl_shape& s) {
   const ConvGeom g = geom_of(s);
   if (!mfma_ok(g)) return 256;
+  if (use_halo_wgrad(g)) return halo_wgrad_partial_bytes(g);
   const WgradPlan p = wgrad_plan(g);
   const size_t n = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
   return ((size_t)p.split * n + 255) / 256 * 256;
@@ -530,6 +529,7 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, const float* a3, const f
     naive_fwd_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(a3, w, skip, y, g);
     return hip_status();
   }
+  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, a3, w, skip, y);
   return launch_igemm<0>(st, g, a3, w, skip, y);
 }
 
@@ -541,6 +541,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const
     naive_dgrad_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(dy, w, da3, g);
     return hip_status();
   }
+  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, dy, w, nullptr, da3);
   return launch_igemm<1>(st, g, dy, w, nullptr, da3);
 }
 
@@ -566,6 +567,7 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const vo
     else naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
     return hip_status();
   }
+  if (use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, packed, sp, dy, scratch, dw);
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
   if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, packed, sp, dy, dst);
@@ -579,7 +581,7 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const vo
   else launch_wgrad_tile<16, 16>(st, g, p, K, packed, sp, dy, dst);
   if (p.split > 1) {
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
-    wgrad_reduce_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, st>>>(dst, p.split, n, dw);
+    wgrad_reduce_kernel<<<(unsigned)((n + 63) / 64), kThreads, 0, st>>>(dst, p.split, n, dw);
   }
   return hip_status();
 }
