@@ -360,3 +360,56 @@ def stack_backward(saved, layers, dy, dtype=np.float32, skip_every=2):
             g_stream = None
         g = dx
     return g, grads
+
+
+# --------------------------------------------------------------------------- sampled outputs
+# Eq. 4 / Eq. 5 evaluated output by output in double, for tensors too large to run the full
+# loops on in a test.  Same definitions as conv_fwd / conv_dgrad / conv_wgrad above.
+def conv_fwd_at(a3, w, s: Shape, pts):
+    """y[n, ho, wo, :] for each (n, ho, wo) in pts."""
+    out = np.zeros((len(pts), s.Cout), np.float64)
+    w64 = np.asarray(w, np.float64)
+    for i, (n, ho, wo) in enumerate(pts):
+        for r in range(s.R):
+            h = ho * s.stride + r - s.pad
+            if h < 0 or h >= s.H:
+                continue
+            for q in range(s.S):
+                x = wo * s.stride + q - s.pad
+                if x < 0 or x >= s.W:
+                    continue
+                out[i] += np.asarray(a3[n, h, x], np.float64) @ w64[r, q]
+    return out
+
+
+def conv_dgrad_at(dy, w, s: Shape, pts):
+    """da3[n, h, x, :] for each (n, h, x) in pts."""
+    out = np.zeros((len(pts), s.Cin), np.float64)
+    w64 = np.asarray(w, np.float64)
+    for i, (n, h, x) in enumerate(pts):
+        for r in range(s.R):
+            hh = h + s.pad - r
+            if hh < 0 or hh % s.stride or hh // s.stride >= s.Ho:
+                continue
+            for q in range(s.S):
+                ww = x + s.pad - q
+                if ww < 0 or ww % s.stride or ww // s.stride >= s.Wo:
+                    continue
+                out[i] += w64[r, q] @ np.asarray(dy[n, hh // s.stride, ww // s.stride], np.float64)
+    return out
+
+
+def conv_wgrad_at(a3, dy, s: Shape, entries):
+    """dW[r, q, ci, :] for each (r, q, ci) in entries."""
+    out = np.zeros((len(entries), s.Cout), np.float64)
+    for i, (r, q, ci) in enumerate(entries):
+        ho = np.arange(s.Ho)
+        wo = np.arange(s.Wo)
+        h = ho * s.stride + r - s.pad
+        x = wo * s.stride + q - s.pad
+        hv = (h >= 0) & (h < s.H)
+        xv = (x >= 0) & (x < s.W)
+        a = np.asarray(a3[:, h[hv]][:, :, x[xv], ci], np.float64)          # [N, ho', wo']
+        g = np.asarray(dy[:, ho[hv]][:, :, wo[xv], :], np.float64)         # [N, ho', wo', Cout]
+        out[i] = np.einsum("nhw,nhwc->c", a, g)
+    return out

@@ -437,3 +437,18 @@ def test_approximate_stack_errors_do_not_compound(oracle):
         rels = [np.linalg.norm(g[0] - r[0]) / np.linalg.norm(r[0]) for g, r in zip(grads, ref[2])]
         assert max(rels) < 0.15, rels
         assert np.linalg.norm(dx - ref[1]) / np.linalg.norm(ref[1]) < 0.15
+
+
+@pytest.mark.parametrize("shape_t", FD_SHAPES)
+def test_sampled_conv_evaluators_agree_with_full_loops(oracle, shape_t):
+    """The output-by-output evaluators used on full-size tensors are the same Eq. 4 / Eq. 5."""
+    o = oracle
+    s, x, w, _, _, dy = _rand_layer(o, shape_t, 21)
+    f64 = np.float64
+    y, da, dw = o.conv_fwd(x, w, s, f64), o.conv_dgrad(dy, w, s, f64), o.conv_wgrad(x, dy, s, f64)
+    pts = [(n, h, q) for n in range(s.N) for h in range(s.Ho) for q in range(s.Wo)]
+    np.testing.assert_allclose(o.conv_fwd_at(x, w, s, pts), y.reshape(-1, s.Cout), rtol=1e-12, atol=1e-12)
+    pts = [(n, h, q) for n in range(s.N) for h in range(s.H) for q in range(s.W)]
+    np.testing.assert_allclose(o.conv_dgrad_at(dy, w, s, pts), da.reshape(-1, s.Cin), rtol=1e-12, atol=1e-12)
+    ent = [(r, q, c) for r in range(s.R) for q in range(s.S) for c in range(s.Cin)]
+    np.testing.assert_allclose(o.conv_wgrad_at(x, dy, s, ent), dw.reshape(-1, s.Cout), rtol=1e-12, atol=1e-12)
