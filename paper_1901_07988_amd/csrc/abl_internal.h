@@ -66,6 +66,11 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const void* packed,
                              const void* stats, const float* dy, void* scratch, float* dw);
 
+// v where ok, zeros elsewhere - written per component so that it stays in registers
+__device__ inline float4 keep_if(bool ok, const float4& v) {
+  return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+}
+
 inline int hip_status() { return hipGetLastError() == hipSuccess ? ABL_OK : ABL_ERR_HIP; }
 
 }  // namespace abl

@@ -12,6 +12,8 @@
 // MODE 0 forward : out[n,h,w,co] = sum in[n, h+r-pad, w+s-pad, ci] W[r,s,ci,co]
 // MODE 1 dgrad   : out[n,h,w,ci] = sum in[n, h+pad-r, w+pad-s, co] W[r,s,ci,co]   (in = dy)
 
+#include <cstdlib>
+
 #include "abl_internal.h"
 
 namespace abl {
@@ -21,7 +23,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int PS = 20;     // floats per staged pixel: 16 channels + 4 pad (conflict-free b128 reads)
-constexpr int AMAX = 8;    // float4 slots per thread for the input patch (<= 512 staged pixels)
+constexpr int AMAX = 6;    // float4 slots per thread for the input patch (<= 384 staged pixels)
 
 struct HaloPlan {
   int TI, TH, TW;                 // output tile: images, rows, cols
@@ -31,7 +33,26 @@ struct HaloPlan {
   int mtiles;                     // ceil(npix / 16)
   int variant;                    // index into the instantiation table
   int bn;                         // output channels per block
+  int a_dw, a_dh;                 // 64 patch pixels further = a_dh rows + a_dw cols
+  int m_dw, m_dh;                 // 16 tile pixels further = m_dh rows + m_dw cols
   unsigned lds_bytes;
+};
+
+// (ti, h, w) position inside a tile or patch, advanced without divisions.
+struct Pos {
+  int w, h, ti;
+  __device__ inline void init(int idx, int width, int height) {
+    w = idx % width;
+    const int q = idx / width;
+    h = q % height;
+    ti = q / height;
+  }
+  __device__ inline void advance(int dw, int dh, int width, int height) {
+    w += dw;
+    h += dh;
+    if (w >= width) { w -= width; ++h; }
+    while (h >= height) { h -= height; ++ti; }
+  }
 };
 
 __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
@@ -40,8 +61,11 @@ __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
 
 // WAVES_N waves share the block's M-tiles and split its N-tiles; the other 4/WAVES_N groups
 // split the M-tiles.  MT = M-tiles per wave (upper bound, `mtiles` is the real count),
-// NT = N-tiles per wave.
-template <int MODE, int WAVES_N, int MT, int NT>
+// NT = N-tiles per wave.  The weights are not staged: each lane fetches its B fragment (four
+// consecutive k of one output channel) for the next tap straight from L2 while the current
+// tap is contracted.  With more than 16 input channels the patch buffer is doubled and the
+// next chunk's global loads are in flight during the MFMAs.
+template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS>
 __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
                                                              float* out, ConvGeom g, HaloPlan p) {
@@ -49,9 +73,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   constexpr int WAVES_M = 4 / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
   const int taps = g.R * g.S;
-  const int BS = taps * 16 + 4;  // floats per staged weight row (one output channel)
-  float* tileA = lds;
-  float* tileB = lds + p.TI * p.HH * p.HW * PS;
+  const int patch_floats = p.TI * p.HH * p.HW * PS;
 
   const int Hi = MODE == 0 ? g.H : g.Ho, Wi = MODE == 0 ? g.W : g.Wo;
   const int Hq = MODE == 0 ? g.Ho : g.H, Wq = MODE == 0 ? g.Wo : g.W;
@@ -63,11 +85,16 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int wn0 = wave_n * NT * 16;
 
-  int b = blockIdx.x;
+  // ids 8 apart share an XCD (and its L2): the blocks that contract the same pixel tile against
+  // different output-channel blocks run there back to back
+  const int nblk_n = (Ng + BN - 1) / BN;
+  const int slot = blockIdx.x >> 3;
+  int b = (slot / nblk_n) * 8 + (blockIdx.x & 7);
+  if (b >= p.tiles_i * p.tiles_h * p.tiles_w) return;
   const int tw_i = b % p.tiles_w; b /= p.tiles_w;
   const int th_i = b % p.tiles_h; b /= p.tiles_h;
   const int img0 = b * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
-  const int n0 = blockIdx.y * BN;
+  const int n0 = (slot % nblk_n) * BN;
   // input coordinate of patch element (0,0)
   const int oh = h0 + (MODE == 0 ? -g.pad : g.pad - (g.R - 1));
   const int ow = w0 + (MODE == 0 ? -g.pad : g.pad - (g.S - 1));
@@ -75,31 +102,32 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // global offsets (in floats, channel 0) of the patch elements this thread stages; -1 = zero fill
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AMAX];
+  {
+    Pos q;
+    q.init(tid >> 2, p.HW, p.HH);
 #pragma unroll
-  for (int j = 0; j < AMAX; ++j) {
-    const int idx = tid + kThreads * j;
-    goff[j] = -1;
-    if (idx < totalA) {
-      int pix = idx >> 2;
-      const int ww = pix % p.HW; pix /= p.HW;
-      const int hh = pix % p.HH;
-      const int ti = pix / p.HH;
-      const int n = img0 + ti, hi = oh + hh, wi = ow + ww;
-      if (n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi)
+    for (int j = 0; j < AMAX; ++j) {
+      const int idx = tid + kThreads * j;
+      goff[j] = -1;
+      const int n = img0 + q.ti, hi = oh + q.h, wi = ow + q.w;
+      if (idx < totalA && n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi)
         goff[j] = ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3);
+      q.advance(p.a_dw, p.a_dh, p.HW, p.HH);
     }
   }
 
   // LDS base of this lane's pixel in each of the wave's M-tiles
   int base[MT];
+  {
+    Pos q;
+    int m = wave_m * MT * 16 + li;
+    q.init(m < p.npix ? m : p.npix - 1, p.TW, p.TH);
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    int m = (wave_m * MT + i) * 16 + li;
-    if (m >= p.npix) m = p.npix - 1;
-    const int w = m % p.TW; m /= p.TW;
-    const int h = m % p.TH;
-    const int ti = m / p.TH;
-    base[i] = ((ti * p.HH + h) * p.HW + w) * PS + 4 * lk;
+    for (int i = 0; i < MT; ++i) {
+      base[i] = ((q.ti * p.HH + q.h) * p.HW + q.w) * PS + 4 * lk;
+      m += 16;
+      if (m < p.npix) q.advance(p.m_dw, p.m_dh, p.TW, p.TH);
+    }
   }
 
   floatx4 acc[MT][NT];
@@ -108,99 +136,129 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const int totalB = taps * 4 * BN;  // float4 per weight chunk
-  for (int c0 = 0; c0 < Cg; c0 += 16) {
-    __syncthreads();  // previous chunk consumed
+  float4 ra[AMAX];
+  auto fetch_a = [&](int c0) __attribute__((always_inline)) {
+    // unconditional loads (lanes outside the image read element 0 and are zeroed): no branch
+    // separates the loads, so all of them are in flight together
+#pragma unroll
+    for (int j = 0; j < AMAX; ++j) {
+      const bool ok = goff[j] >= 0;
+      const float4 v = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
+      ra[j] = keep_if(ok, v);
+    }
+  };
+  auto stage_a = [&](float* tileA) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < AMAX; ++j) {
       const int idx = tid + kThreads * j;
-      if (idx < totalA) {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (goff[j] >= 0 && c0 + 4 * (idx & 3) < Cg) v = *reinterpret_cast<const float4*>(in + goff[j] + c0);
-        *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = v;
-      }
+      if (idx < totalA) *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = ra[j];
     }
-    for (int idx = tid; idx < totalB; idx += kThreads) {
-      if (MODE == 0) {  // W rows (tap, ci) are contiguous in co: transpose into [co][tap*16 + ci]
-        const int k = idx / (BN / 4), nl = 4 * (idx % (BN / 4));
-        const int tap = k >> 4, c = c0 + (k & 15);
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c < Cg && n0 + nl < Ng)
-          v = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + c) * g.Cout + n0 + nl);
-        tileB[(nl + 0) * BS + k] = v.x;
-        tileB[(nl + 1) * BS + k] = v.y;
-        tileB[(nl + 2) * BS + k] = v.z;
-        tileB[(nl + 3) * BS + k] = v.w;
-      } else {          // W rows (tap, ci) hold the contraction index co contiguously
-        const int nl = idx / (taps * 4), rem = idx % (taps * 4);
-        const int tap = rem >> 2, kq = rem & 3;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n0 + nl < Ng && c0 + 4 * kq < Cg)
-          v = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + n0 + nl) * g.Cout + c0 + 4 * kq);
-        *reinterpret_cast<float4*>(&tileB[nl * BS + tap * 16 + 4 * kq]) = v;
+  };
+  // B fragment of this lane for chunk c0, tap t: k = c0 + 4*lk .. +3, column = its channel
+  auto fetch_b = [&](int c0, int t, float4 (&bf)[NT]) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n = n0 + wn0 + 16 * j + li, c = c0 + 4 * lk;
+      const bool ok = n < Ng;
+      float4 v;
+      if (MODE == 0) {
+        const float* src = ok ? wgt + ((int64_t)t * g.Cin + c) * g.Cout + n : wgt;
+        const int64_t ld = ok ? g.Cout : 0;
+        v = make_float4(src[0], src[ld], src[2 * ld], src[3 * ld]);
+      } else {
+        v = *reinterpret_cast<const float4*>(ok ? wgt + ((int64_t)t * g.Cin + n) * g.Cout + c : wgt);
       }
+      bf[j] = keep_if(ok, v);
     }
-    __syncthreads();
-    for (int t = 0; t < taps; ++t) {
-      const int r = t / g.S, s = t - r * g.S;
+  };
+
+  float4 bcur[NT], bnext[NT];
+  fetch_a(0);
+  fetch_b(0, 0, bcur);
+  stage_a(lds);
+  __syncthreads();
+  int buf = 0;
+  for (int c0 = 0; c0 < Cg; c0 += 16) {
+    const float* tileA = lds + buf * patch_floats;
+    const bool more = c0 + 16 < Cg;
+    if (more) fetch_a(c0 + 16);
+    auto tap_step = [&](int t, int r, int s) __attribute__((always_inline)) {
+      if (t + 1 < taps) fetch_b(c0, t + 1, bnext);
+      else if (more) fetch_b(c0 + 16, 0, bnext);
       const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
       const int aoff = (rr * p.HW + ss) * PS;
-      float4 af[MT], bf[NT];
+      float4 af[MT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
 #pragma unroll
-      for (int j = 0; j < NT; ++j)
-        bf[j] = *reinterpret_cast<const float4*>(&tileB[(wn0 + 16 * j + li) * BS + t * 16 + 4 * lk]);
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bcur[j].x, acc[i][j]);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bcur[j].y, acc[i][j]);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bcur[j].z, acc[i][j]);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bcur[j].w, acc[i][j]);
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
+      for (int j = 0; j < NT; ++j) bcur[j] = bnext[j];
+    };
+    if (UNROLL_TAPS) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+      for (int t = 0; t < 9; ++t) tap_step(t, t / 3, t % 3);
+    } else {
+      for (int t = 0; t < taps; ++t) tap_step(t, t / g.S, t % g.S);
+    }
+    if (more) {
+      stage_a(lds + (buf ^ 1) * patch_floats);
+      __syncthreads();
+      buf ^= 1;
     }
   }
 
-  // epilogue: the lane holds pixels 4*lk .. 4*lk+3 of each M-tile, channel li of each N-tile
+  // epilogue: the lane holds pixels 4*lk .. 4*lk+3 of each M-tile, channel li of each N-tile.
+  // Output offsets first, then the shortcut values in one batch, then the stores.
+  Pos e;
+  int m = wave_m * MT * 16 + 4 * lk;
+  e.init(m, p.TW, p.TH);
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    int m = (wave_m * MT + i) * 16 + 4 * lk;
-    int w = m % p.TW;
-    int q = m / p.TW;
-    int h = q % p.TH;
-    int ti = q / p.TH;
+    Pos q = e;
+    int64_t off[4];  // element offset of (pixel, channel 0 of this block), -1 = outside
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
-      const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
-      if (m + rr < p.npix && n < g.N && hq < Hq && wq < Wq) {
-        const int64_t pix = ((int64_t)n * Hq + hq) * Wq + wq;
+      const int n = img0 + q.ti, hq = h0 + q.h, wq = w0 + q.w;
+      const bool ok = m + rr < p.npix && n < g.N && hq < Hq && wq < Wq;
+      off[rr] = ok ? (((int64_t)n * Hq + hq) * Wq + wq) * Ng + n0 + wn0 + li : -1;
+      q.advance(1, 0, p.TW, p.TH);
+    }
+    if (skip != nullptr) {
+      float sv[4][NT];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-          const int c = n0 + wn0 + 16 * j + li;
-          if (c < Ng) {
-            float v = acc[i][j][rr];
-            if (skip != nullptr) v += skip[pix * Ng + c];
-            out[pix * Ng + c] = v;
-          }
+          const bool ok = off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng;
+          sv[rr][j] = skip[ok ? off[rr] + 16 * j : 0];
         }
-      }
-      if (++w == p.TW) {
-        w = 0;
-        if (++h == p.TH) {
-          h = 0;
-          ++ti;
-        }
-      }
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j][rr] += sv[rr][j];
     }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) out[off[rr] + 16 * j] = acc[i][j][rr];
+    m += 16;
+    e.advance(p.m_dw, p.m_dh, p.TW, p.TH);
   }
 }
 
@@ -216,6 +274,7 @@ constexpr Variant kVariants[] = {
     {4, 4, 1},   // 3: 64 px x 64 ch
     {4, 8, 1},   // 4: 128 px x 64 ch
     {4, 14, 1},  // 5: 224 px x 64 ch   (56x56 and 14x14 ImageNet layers)
+    {1, 2, 1},   // 6: 128 px x 16 ch
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -257,13 +316,16 @@ void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
   p.tiles_w = cdiv(Wq, p.TW);
   p.npix = p.TI * p.TH * p.TW;
   p.mtiles = cdiv(p.npix, 16);
+  p.a_dw = 64 % p.HW; p.a_dh = 64 / p.HW;
+  p.m_dw = 16 % p.TW; p.m_dh = 16 / p.TW;
 }
 
 bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   const int Hq = mode == 0 ? g.Ho : g.H, Wq = mode == 0 ? g.Wo : g.W;
   const int Ng = mode == 0 ? g.Cout : g.Cin;
   int v;
-  if (Ng <= 16) v = 0;
+  static const int tune16 = getenv("ABL_TUNE16") ? atoi(getenv("ABL_TUNE16")) : 0;
+  if (Ng <= 16) v = tune16 ? 6 : 0;
   else if (Ng <= 32) v = (int64_t)g.N * Hq * Wq >= 256 * 512 ? 2 : 1;
   else {
     const int64_t px = (int64_t)g.N * Hq * Wq * cdiv(Ng, 64);
@@ -274,7 +336,8 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   choose_tile(Hq, Wq, g.N, g.R, g.S, waves_m * var.mt * 16, p);
   p.variant = v;
   p.bn = var.waves_n * var.nt * 16;
-  const size_t fl = (size_t)p.TI * p.HH * p.HW * PS + (size_t)p.bn * (g.R * g.S * 16 + 4);
+  const int Cg = mode == 0 ? g.Cin : g.Cout;
+  const size_t fl = (size_t)p.TI * p.HH * p.HW * PS * (Cg > 16 ? 2 : 1);
   p.lds_bytes = (unsigned)(fl * sizeof(float));
   return p.lds_bytes <= 64 * 1024 && p.TI * p.HH * p.HW * 4 <= AMAX * kThreads && p.TH > 0;
 }
@@ -284,8 +347,11 @@ void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const 
                     const float* skip, float* out) {
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
-  dim3 grid(p.tiles_i * p.tiles_h * p.tiles_w, cdiv(Ng, p.bn));
-  halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
+  dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * cdiv(Ng, p.bn));
+  if (g.R == 3 && g.S == 3 && var.mt * var.nt <= 4)
+    halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
+  else
+    halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
 }
 
 template <int MODE>
@@ -297,7 +363,8 @@ void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const flo
     case 2: launch_variant<MODE, 2>(st, g, p, in, w, skip, out); break;
     case 3: launch_variant<MODE, 3>(st, g, p, in, w, skip, out); break;
     case 4: launch_variant<MODE, 4>(st, g, p, in, w, skip, out); break;
-    default: launch_variant<MODE, 5>(st, g, p, in, w, skip, out); break;
+    case 5: launch_variant<MODE, 5>(st, g, p, in, w, skip, out); break;
+    default: launch_variant<MODE, 6>(st, g, p, in, w, skip, out); break;
   }
 }
 

@@ -29,22 +29,28 @@ __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
 //   MODE 1 (dgrad):   p = (n,h,w),   A = dy[n, (h+pad-r)/st, (w+pad-s)/st, c], c < Cout,
 //                     (only where the division is exact and lands inside dy)
 //                     B = W[r][s][n][c], n < Cin
-// Block tile BM x BN, K chunk 16 channels of one filter tap, 4 waves of 64 x WN.
-template <int BM, int BN, int WN, int MODE>
+// Block tile BM x BN, K chunk 16 channels of one filter tap, 4 waves of WM x WN.  The LDS
+// tiles are double buffered: the global loads of chunk i+1 are in flight while chunk i is
+// contracted, and one barrier per chunk separates "everyone has read buffer b" from
+// "buffer b is overwritten".
+template <int BM, int BN, int WM, int WN, int BK, int MODE>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict__ in,
                                                          const float* __restrict__ wgt,
                                                          const float* skip, float* out, ConvGeom g) {
-  constexpr int BK = 16, LDK = BK + 4;
-  constexpr int WM = 64;
-  constexpr int WAVES_N = BN / WN, WAVES_M = 4 / WAVES_N;
-  static_assert(BM == WAVES_M * WM, "tile/wave mismatch");
+  constexpr int LDK = BK + 4;
+  constexpr int KQ = BK / 4;                               // float4 per tile row
+  constexpr int WAVES_N = BN / WN, WAVES_M = BM / WM;
+  static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
   constexpr int MT = WM / 16, NT = WN / 16;
-  constexpr int A_PASSES = BM / 64;
+  constexpr int ROWS = kThreads / KQ;                      // A rows staged per pass
+  static_assert(BM % ROWS == 0, "A tile rows are staged ROWS at a time");
+  constexpr int A_PASSES = BM / ROWS;
   constexpr int B_F4 = BK * BN / 4;                        // float4 per B chunk
   constexpr int B_PASSES = (B_F4 + kThreads - 1) / kThreads;
 
-  __shared__ __attribute__((aligned(16))) float As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  float* As0 = lds;                      // [2][BM * LDK]
+  float* Bs0 = lds + 2 * BM * LDK;       // [2][BN * LDK]
 
   // A-operand tensor dims, output pixel grid, GEMM extents
   const int Hi = MODE == 0 ? g.H : g.Ho, Wi = MODE == 0 ? g.W : g.Wo;
@@ -55,22 +61,28 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-  const int64_t m0 = (int64_t)blockIdx.x * BM;
-  const int n0 = blockIdx.y * BN;
+  // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The blocks that share an
+  // A tile (same pixel rows, different output channels) are therefore given ids 8 apart, so
+  // they run on one XCD back to back and the tile comes from HBM once.
+  const int nblk_n = (Ng + BN - 1) / BN;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int64_t m0 = ((int64_t)(slot / nblk_n) * 8 + xcd) * BM;
+  const int n0 = (slot % nblk_n) * BN;
+  if (m0 >= Mg) return;
 
   // rows of the A tile this thread fetches (one float4 = 4 channels per row and pass)
-  const int a_kq = tid & 3, a_row = tid >> 2;
+  const int a_kq = tid % KQ, a_row = tid / KQ;
   int a_n[A_PASSES], a_h[A_PASSES], a_w[A_PASSES];
   bool a_ok[A_PASSES];
 #pragma unroll
   for (int i = 0; i < A_PASSES; ++i) {
-    const int64_t p = m0 + a_row + 64 * i;
+    const int64_t p = m0 + a_row + ROWS * i;
     a_ok[i] = p < Mg;
-    const int64_t pp = a_ok[i] ? p : 0;
-    const int wq = (int)(pp % Wq);
-    const int64_t t = pp / Wq;
-    const int hq = (int)(t % Hq);
-    a_n[i] = (int)(t / Hq);
+    const int pp = a_ok[i] ? (int)p : 0;
+    const int wq = pp % Wq;
+    const int t = pp / Wq;
+    const int hq = t % Hq;
+    a_n[i] = t / Hq;
     if (MODE == 0) {
       a_h[i] = hq * g.stride - g.pad;
       a_w[i] = wq * g.stride - g.pad;
@@ -87,17 +99,21 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int cchunks = (Cg + BK - 1) / BK;
-  const int iters = g.R * g.S * cchunks;
+  const int taps = g.R * g.S;
+  const int iters = taps * cchunks;
   float4 ra[A_PASSES], rb[B_PASSES];
 
-  auto fetch = [&](int it) {
-    const int tap = it / cchunks, c0 = (it - tap * cchunks) * BK;
+  // Fetch state.  Chunks are fetched in order, so everything that depends on the filter tap
+  // (bounds, the division for strided dgrad, the pixel offset) is recomputed only when the tap
+  // changes; within a tap a chunk is `offset + channel`.
+  int a_off[A_PASSES];  // element offset of channel 0 of this thread's pixel for the tap, -1 = zero
+  int f_tap = 0, f_c0 = 0;
+  auto set_tap = [&](int tap) __attribute__((always_inline)) {
     const int r = tap / g.S, s = tap - r * g.S;
-    const int c = c0 + 4 * a_kq;
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       int hi, wi;
-      bool ok = a_ok[i] && c < Cg;
+      bool ok = a_ok[i];
       if (MODE == 0) {
         hi = a_h[i] + r;
         wi = a_w[i] + s;
@@ -108,95 +124,157 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
         ok = ok && hh >= 0 && ww >= 0 && hi * g.stride == hh && wi * g.stride == ww;
       }
       ok = ok && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi;
-      ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (ok) ra[i] = *reinterpret_cast<const float4*>(in + (((int64_t)a_n[i] * Hi + hi) * Wi + wi) * Cg + c);
+      a_off[i] = ok ? ((a_n[i] * Hi + hi) * Wi + wi) * Cg : -1;
     }
+  };
+  // per-thread part of the weight address
+  int b_thr[B_PASSES];
+  bool b_ok[B_PASSES];
+#pragma unroll
+  for (int j = 0; j < B_PASSES; ++j) {
+    const int idx = tid + kThreads * j;
+    if (MODE == 0) {  // column n of four consecutive k rows
+      const int n = n0 + idx % BN;
+      b_ok[j] = idx < B_F4 && n < Ng;
+      b_thr[j] = 4 * (idx / BN) * g.Cout + n;
+    } else {          // row n, float4 along k
+      const int nn = n0 + idx / KQ;
+      b_ok[j] = idx < B_F4 && nn < Ng;
+      b_thr[j] = nn * g.Cout + 4 * (idx % KQ);
+    }
+  }
+  set_tap(0);
+
+  auto fetch = [&]() __attribute__((always_inline)) {
+    // every load is issued unconditionally (out-of-range lanes read element 0 and are zeroed
+    // afterwards): no branches between the loads, so they are all in flight together
+    const int c = f_c0 + 4 * a_kq;
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i) {
+      const bool ok = a_off[i] >= 0 && c < Cg;
+      const float4 v = *reinterpret_cast<const float4*>(in + (ok ? a_off[i] + c : 0));
+      ra[i] = keep_if(ok, v);
+    }
+    const float* wb = MODE == 0 ? wgt + ((int64_t)f_tap * g.Cin + f_c0) * g.Cout
+                                : wgt + (int64_t)f_tap * g.Cin * g.Cout + f_c0;
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
-      rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (idx < B_F4) {
-        if (MODE == 0) {  // rows k, float4 along n
-          const int kk = idx / (BN / 4), n = n0 + 4 * (idx % (BN / 4));
-          if (c0 + kk < Cg && n < Ng)
-            rb[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + c0 + kk) * g.Cout + n);
-        } else {          // rows n, float4 along k
-          const int nn = n0 + idx / 4, kq = idx % 4;
-          if (nn < Ng && c0 + 4 * kq < Cg)
-            rb[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)tap * g.Cin + nn) * g.Cout + c0 + 4 * kq);
-        }
+      if (MODE == 0) {
+        const bool ok = b_ok[j] && f_c0 + 4 * (idx / BN) < Cg;
+        const float* src = ok ? wb + b_thr[j] : wgt;
+        const int64_t ld = ok ? g.Cout : 0;
+        const float4 v = make_float4(src[0], src[ld], src[2 * ld], src[3 * ld]);
+        rb[j] = keep_if(ok, v);
+      } else {
+        const bool ok = b_ok[j] && f_c0 + 4 * (idx % KQ) < Cg;
+        const float4 v = *reinterpret_cast<const float4*>(ok ? wb + b_thr[j] : wgt);
+        rb[j] = keep_if(ok, v);
       }
+    }
+    f_c0 += BK;
+    if (f_c0 >= Cg) {
+      f_c0 = 0;
+      ++f_tap;
+      if (f_tap < taps) set_tap(f_tap);
     }
   };
 
-  auto stage = [&]() {
+  auto stage = [&](int buf) __attribute__((always_inline)) {
+    float* As = As0 + buf * BM * LDK;
+    float* Bs = Bs0 + buf * BN * LDK;
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i)
-      *reinterpret_cast<float4*>(&As[(a_row + 64 * i) * LDK + 4 * a_kq]) = ra[i];
+      *reinterpret_cast<float4*>(&As[(a_row + ROWS * i) * LDK + 4 * a_kq]) = ra[i];
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
-      if (idx < B_F4) {
+      if (B_F4 % kThreads == 0 || idx < B_F4) {
         if (MODE == 0) {
-          const int kk = idx / (BN / 4), nl = 4 * (idx % (BN / 4));
-          Bs[(nl + 0) * LDK + kk] = rb[j].x;
-          Bs[(nl + 1) * LDK + kk] = rb[j].y;
-          Bs[(nl + 2) * LDK + kk] = rb[j].z;
-          Bs[(nl + 3) * LDK + kk] = rb[j].w;
+          *reinterpret_cast<float4*>(&Bs[(idx % BN) * LDK + 4 * (idx / BN)]) = rb[j];
         } else {
-          *reinterpret_cast<float4*>(&Bs[(idx / 4) * LDK + 4 * (idx % 4)]) = rb[j];
+          *reinterpret_cast<float4*>(&Bs[(idx / KQ) * LDK + 4 * (idx % KQ)]) = rb[j];
         }
       }
     }
   };
 
   const int li = lane & 15, lk = lane >> 4;
-  fetch(0);
+  auto compute = [&](int cur) __attribute__((always_inline)) {
+    const float* As = As0 + cur * BM * LDK;
+    const float* Bs = Bs0 + cur * BN * LDK;
+#pragma unroll
+    for (int kg = 0; kg < BK / 16; ++kg) {
+      float4 af[MT], bf[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        af[i] = *reinterpret_cast<const float4*>(&As[(wm0 + 16 * i + li) * LDK + 16 * kg + 4 * lk]);
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        bf[j] = *reinterpret_cast<const float4*>(&Bs[(wn0 + 16 * j + li) * LDK + 16 * kg + 4 * lk]);
+      // k-step outermost: consecutive MFMAs write different accumulators
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+    }
+  };
+  // The loads of chunk i+1 are issued before chunk i is contracted and written to the other
+  // LDS buffer afterwards; one barrier per chunk.
+  fetch();
+  stage(0);
+  __syncthreads();
   for (int it = 0; it < iters; ++it) {
-    stage();
-    __syncthreads();
-    if (it + 1 < iters) fetch(it + 1);
-    float4 af[MT], bf[NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-      af[i] = *reinterpret_cast<const float4*>(&As[(wm0 + 16 * i + li) * LDK + 4 * lk]);
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-      bf[j] = *reinterpret_cast<const float4*>(&Bs[(wn0 + 16 * j + li) * LDK + 4 * lk]);
-    // k-step outermost: consecutive MFMAs write different accumulators
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+    const int cur = it & 1;
+    if (it + 1 < iters) fetch();
+    compute(cur);
+    if (it + 1 < iters) stage(cur ^ 1);
     __syncthreads();
   }
 
-  // epilogue: lane holds rows 4*lk + r, column li of each 16x16 tile
+  // epilogue: lane holds rows 4*lk + r, column li of each 16x16 tile.  The shortcut values are
+  // loaded in one batch (clamped addresses), then added and stored.
+  const bool full = m0 + BM <= Mg && n0 + BN <= Ng;
+  if (skip != nullptr) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      float sv[4][NT];
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int64_t p = m0 + wm0 + 16 * i + 4 * lk + r;
+          const int n = n0 + wn0 + 16 * j + li;
+          const bool ok = full || (p < Mg && n < Ng);
+          sv[r][j] = skip[ok ? p * Ng + n : 0];
+        }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j][r] += sv[r][j];
+    }
+  }
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int64_t p = m0 + wm0 + 16 * i + 4 * lk + r;
-      if (p >= Mg) continue;
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int n = n0 + wn0 + 16 * j + li;
-        if (n >= Ng) continue;
-        float v = acc[i][j][r];
-        if (skip != nullptr) v += skip[p * Ng + n];
-        out[p * Ng + n] = v;
+        if (full || (p < Mg && n < Ng)) out[p * Ng + n] = acc[i][j][r];
       }
     }
 }
@@ -212,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
                                                          float* __restrict__ partial, ConvGeom g,
-                                                         int chunks_per_split) {
+                                                         int chunks_per_split, int nsplit) {
   constexpr int CH = 64;                                  // pixels per chunk
   constexpr int LDA = (TM % 32 == 0) ? TM + 16 : TM;
   constexpr int LDB = (TN % 32 == 0) ? TN + 16 : TN;
@@ -229,14 +307,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_m = (g.Cin + TM - 1) / TM, tiles_n = (g.Cout + TN - 1) / TN;
-  int t = blockIdx.x;
+  // ids 8 apart share an XCD (and its L2): all tiles of one pixel slice run there back to back
+  const int ntiles = g.R * g.S * tiles_m * tiles_n;
+  const int slot = blockIdx.x >> 3;
+  const int split_idx = (slot / ntiles) * 8 + (blockIdx.x & 7);
+  if (split_idx >= nsplit) return;
+  int t = slot % ntiles;
   const int tn = t % tiles_n; t /= tiles_n;
   const int tm = t % tiles_m; t /= tiles_m;
   const int tap = t;
   const int r = tap / g.S, s = tap - r * g.S;
   const int ci0 = tm * TM, co0 = tn * TN;
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
-  const int64_t p_begin = (int64_t)blockIdx.y * chunks_per_split * CH;
+  const int64_t p_begin = (int64_t)split_idx * chunks_per_split * CH;
   int64_t p_end = p_begin + (int64_t)chunks_per_split * CH;
   if (p_end > Mg) p_end = Mg;
 
@@ -259,10 +342,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
     for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int li = lane & 15, lk = lane >> 4;
-  for (int64_t pc = p_begin; pc < p_end; pc += CH) {
-    uint32_t wa[A_PASSES];
-    bool oka[A_PASSES];
-    float4 rb[B_PASSES];
+  uint32_t wa[A_PASSES];
+  bool oka[A_PASSES];
+  float4 rb[B_PASSES];
+  // global loads of one 64-pixel chunk into registers
+  auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       const int idx = tid + kThreads * i;
@@ -289,6 +373,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
       if (idx < CH * GB && p < p_end && c < g.Cout)
         rb[j] = *reinterpret_cast<const float4*>(dy + p * g.Cout + c);
     }
+  };
+  if (p_begin < p_end) fetch(p_begin);
+  for (int64_t pc = p_begin; pc < p_end; pc += CH) {
     __syncthreads();  // previous chunk fully consumed
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
@@ -309,6 +396,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
       if (idx < CH * GB) *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = rb[j];
     }
     __syncthreads();
+    if (pc + CH < p_end) fetch(pc + CH);  // in flight while this chunk is contracted
     // wave w contracts pixels [16w, 16w+16) of the chunk: 4 MFMA k-steps of 4 pixels
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -341,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
     }
   }
   __syncthreads();
-  float* dst = partial + (int64_t)blockIdx.y * g.R * g.S * g.Cin * g.Cout;
+  float* dst = partial + (int64_t)split_idx * g.R * g.S * g.Cin * g.Cout;
   for (int idx = tid; idx < TM * TN / 4; idx += kThreads) {
     const int i = idx / (TN / 4), j = 4 * (idx % (TN / 4));
     const int ci = ci0 + i, co = co0 + j;
@@ -466,24 +554,57 @@ __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __
 
 inline bool mfma_ok(const ConvGeom& g) { return g.Cin % 16 == 0 && g.Cout % 16 == 0; }
 
+// Tile choice: the largest tile whose grid still gives every CU about two blocks; a tile
+// that is too large for a small GEMM leaves compute units idle.
 template <int MODE>
 int launch_igemm(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip,
                  float* out) {
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
-  if (Ng > 64) {
-    dim3 grid((unsigned)((Mg + 127) / 128), (Ng + 127) / 128);
-    igemm_kernel<128, 128, 64, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+  auto blocks = [&](int bm, int bn) __attribute__((always_inline)) { return ((Mg + bm - 1) / bm) * ((Ng + bn - 1) / bn); };
+#define ABL_IGEMM(BM_, BN_, WM_, WN_, BK_)                                                     \
+  do {                                                                                         \
+    const int64_t mb8 = ((Mg + BM_ - 1) / BM_ + 7) / 8 * 8;                                   \
+    dim3 grid((unsigned)(mb8 * ((Ng + BN_ - 1) / BN_)));                                      \
+    constexpr unsigned lds = 2u * (BM_ + BN_) * (BK_ + 4) * sizeof(float);                    \
+    auto kern = igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE>;                                   \
+    if (lds > 64 * 1024) {                                                                     \
+      static const hipError_t attr = hipFuncSetAttribute(                                     \
+          reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
+      if (attr != hipSuccess) return ABL_ERR_HIP;                                              \
+    }                                                                                          \
+    kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, g);                                    \
+  } while (0)
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;
+  const int64_t want = 512;
+  if (Cg % 32 == 0) {  // 32-channel chunks: whole 128-byte lines per pixel row
+    if (Ng > 64) {
+      if (blocks(128, 128) >= want) ABL_IGEMM(128, 128, 64, 64, 32);
+      else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 32);
+      else ABL_IGEMM(64, 64, 32, 32, 32);
+    } else if (Ng > 32) {
+      if (blocks(256, 64) >= want) ABL_IGEMM(256, 64, 64, 64, 32);
+      else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 32);
+      else ABL_IGEMM(64, 64, 32, 32, 32);
+    } else if (Ng > 16) {
+      ABL_IGEMM(256, 32, 64, 32, 32);
+    } else {
+      ABL_IGEMM(256, 16, 64, 16, 32);
+    }
+  } else if (Ng > 64) {
+    if (blocks(128, 128) >= want) ABL_IGEMM(128, 128, 64, 64, 16);
+    else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 16);
+    else ABL_IGEMM(64, 64, 32, 32, 16);
   } else if (Ng > 32) {
-    dim3 grid((unsigned)((Mg + 255) / 256), (Ng + 63) / 64);
-    igemm_kernel<256, 64, 64, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+    if (blocks(256, 64) >= want) ABL_IGEMM(256, 64, 64, 64, 16);
+    else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 16);
+    else ABL_IGEMM(64, 64, 32, 32, 16);
   } else if (Ng > 16) {
-    dim3 grid((unsigned)((Mg + 255) / 256), 1);
-    igemm_kernel<256, 32, 32, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+    ABL_IGEMM(256, 32, 64, 32, 16);
   } else {
-    dim3 grid((unsigned)((Mg + 255) / 256), 1);
-    igemm_kernel<256, 16, 16, MODE><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
+    ABL_IGEMM(256, 16, 64, 16, 16);
   }
+#undef ABL_IGEMM
   return hip_status();
 }
 
@@ -548,12 +669,12 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const
 template <int TM, int TN>
 static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K,
                               const void* packed, const float* stats, const float* dy, float* dst) {
-  dim3 grid(p.tiles, p.split);
+  dim3 grid((unsigned)((p.split + 7) / 8 * 8 * p.tiles));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
   if (K == 4)
-    wgrad_kernel<TM, TN, 4><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split);
+    wgrad_kernel<TM, TN, 4><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
   else
-    wgrad_kernel<TM, TN, 8><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split);
+    wgrad_kernel<TM, TN, 8><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
 }
 
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const void* packed,
