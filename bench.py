@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 
 
 def parse():
@@ -29,6 +30,8 @@ def parse():
     ap.add_argument("--K", type=int, default=4)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3a", "config3b",
                                                               "config4", "config5"])
+    ap.add_argument("--math", default="fp32", choices=["fp32", "bf16"],
+                    help="operand type of the conv contractions (bf16 = ABL_MATH_BF16 variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=50)
     return ap.parse_args()
@@ -61,7 +64,7 @@ def time_events(fn, reps):
     return start.elapsed_time(stop) / reps
 
 
-def kernel_breakdown(G, B, s, K, reps):
+def kernel_breakdown(G, B, s, K, reps, flags=0):
     """Per-stage timing of one layer shape with HIP events on the stream the kernels run on.
     Returns {stage: dict(ms, bytes, flops, launches)} with ALGORITHMIC bytes / flops per call."""
     import numpy as np
@@ -90,9 +93,9 @@ def kernel_breakdown(G, B, s, K, reps):
     stages = {
         "bn_stats": (lambda: B.abl_bn_stats(x, M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2),
         "bn_relu_pack": (lambda: B.abl_bn_relu_pack(x, M, C, K, stats, a3, packed), 8 * E + P, 0, 1),
-        "conv_fwd": (lambda: B.abl_conv_fwd(t, a3, w, None, y), 4 * E + 4 * Eo + wbytes, flops, 1),
-        "conv_dgrad": (lambda: B.abl_conv_dgrad(t, dy, w, a3), 4 * E + 4 * Eo + wbytes, flops, 1),
-        "conv_wgrad_packed": (lambda: B.abl_conv_wgrad_packed(t, K, packed, stats, dy, scratch, dw),
+        "conv_fwd": (lambda: B.abl_conv_fwd(t, a3, w, None, y, flags=flags), 4 * E + 4 * Eo + wbytes, flops, 1),
+        "conv_dgrad": (lambda: B.abl_conv_dgrad(t, dy, w, a3, flags=flags), 4 * E + 4 * Eo + wbytes, flops, 1),
+        "conv_wgrad_packed": (lambda: B.abl_conv_wgrad_packed(t, K, packed, stats, dy, scratch, dw, flags=flags),
                               P + 4 * Eo + wbytes, flops, 2),
         "bn_bwd": (lambda: B.abl_bn_bwd(packed, stats, a3, M, C, K, scratch, dx, dg, db), 2 * P + 12 * E, 0, 3),
         "pack": (lambda: B.abl_pack(x, M, C, K, stats, packed), 4 * E + P, 0, 1),
@@ -142,7 +145,8 @@ def main():
     wl = get_workload(args.workload)
     K = args.K
     x, layers, dy = synth.draw_stack(wl)
-    run = G.StackRun(layers, K, wl.skip_every)
+    flags = B.ABL_MATH_BF16 if args.math == "bf16" else 0
+    run = G.StackRun(layers, K, wl.skip_every, flags=flags)
     xd = G.dev(x).view(-1)
     dyd = G.dev(dy).view(-1)
     n_in, n_out = xd.numel(), dyd.numel()
@@ -172,7 +176,7 @@ def main():
     per_step = {}
     breakdown = {}
     for s, count in shapes.items():
-        bd = kernel_breakdown(G, B, s, K, args.kernel_reps)
+        bd = kernel_breakdown(G, B, s, K, args.kernel_reps, flags)
         breakdown["x".join(map(str, s.as_tuple()))] = {k: round(v["ms"] * 1e3, 2) for k, v in bd.items()}
         for k, v in bd.items():
             if k in ("pack", "unpack"):
@@ -180,11 +184,12 @@ def main():
             key = (s, k)
             per_step[key] = (v["ms"] * count, v)
     (dom_shape, dom_name), (_, dom) = max(per_step.items(), key=lambda kv: kv[1][0])
-    flops_bound_ms = dom["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e9)
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if args.math == "bf16" else MFMA_FP32_PEAK_TFLOPS
+    flops_bound_ms = dom["flops"] / (mfma_peak * 1e9)
     bytes_bound_ms = dom["bytes"] / (HBM_PEAK_GBS * 1e6)
     if dom["flops"] > 0 and flops_bound_ms >= bytes_bound_ms:
-        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": dom["tflops"] / MFMA_FP32_PEAK_TFLOPS}
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": mfma_peak, "unit": "TFLOP/s",
+                "frac": dom["tflops"] / mfma_peak}
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["gbs"] / HBM_PEAK_GBS}
@@ -198,7 +203,8 @@ def main():
         "unit": "images/sec per layer step (N x layers / step time)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if args.math == "fp32" else "bf16 operands, f32 accumulate (contractions); f32 elsewhere",
+        "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "layers": L, "batch": N, "skip_every": wl.skip_every,
                    "stack_images_per_sec": N / (dt / args.steps)},
         "roofline": roof,
@@ -208,7 +214,7 @@ def main():
                              "ratio": run.stored_bytes() / exact_bytes},
     }
     s0 = max(shapes, key=shapes.get)
-    bd0 = kernel_breakdown(G, B, s0, K, args.kernel_reps)
+    bd0 = kernel_breakdown(G, B, s0, K, args.kernel_reps, flags)
     result["pack_unpack_gbs"] = {"pack": bd0["pack"]["gbs"], "unpack": bd0["unpack"]["gbs"],
                                  "bn_relu_pack": bd0["bn_relu_pack"]["gbs"]}
     if not args.no_cpu_baseline:

@@ -18,6 +18,8 @@
  *   - the BN tensor of a layer is its input: M = N*H*W rows of Cin channels,
  *     E = M*Cin elements.  Batch statistics use the biased variance, eps = 1e-5.
  *   - K is 4 or 8.
+ *   - `flags` is a bit set of the ABL_* flags an entry point documents; unknown bits are an
+ *     ABL_ERR_ARG.
  *   - return value: ABL_OK or an ABL_ERR_* code; on error nothing was enqueued
  *     (ABL_ERR_HIP: a launch failed, earlier launches of the call may have run).
  *   - preconditions that are NOT checked: finite inputs, gamma != 0.
@@ -55,7 +57,10 @@ enum {
 };
 
 enum {
-  ABL_ACCUM_DX = 1u << 0 /* abl_backward / abl_bn_bwd: dx += result (residual-stream gradient, Sec. 3.4) */
+  ABL_ACCUM_DX = 1u << 0, /* abl_backward / abl_bn_bwd: dx += result (residual-stream gradient, Sec. 3.4) */
+  ABL_MATH_BF16 = 1u << 1 /* contractions (Eq. 4, Eq. 5): operands rounded to bf16 on the way into the
+                             matrix cores, fp32 accumulation; everything else (statistics, codes,
+                             BN forward/backward) is unchanged.  Default: fp32 operands. */
 };
 
 #define ABL_BN_EPS 1e-5f
@@ -83,7 +88,7 @@ size_t abl_scratch_bytes(const abl_shape* shape, int K);
  *   packed abl_packed_bytes out: K-bit codes of A2
  *   stats  abl_stats_bytes  out
  *   scratch                 workspace, contents undefined afterwards
- * y is computed from the full-precision A3 and does not depend on K. */
+ * y is computed from the full-precision A3 and does not depend on K.  flags: ABL_MATH_BF16. */
 int abl_forward(void* stream, const abl_shape* shape, int K, uint32_t flags,
                 const float* x, const float* W, const float* gamma, const float* beta,
                 const float* skip, void* scratch, size_t scratch_bytes,
@@ -96,7 +101,8 @@ int abl_forward(void* stream, const abl_shape* shape, int K, uint32_t flags,
  *   W      [R,S,Cin,Cout]   in
  *   dx     [N,H,W,Cin]      out (or accumulated into with ABL_ACCUM_DX).  May alias dy.
  *   dW     [R,S,Cin,Cout]   out: approximate (uses the dequantized A3)
- *   dgamma, dbeta [Cin]     out: dgamma approximate, dbeta exact (Sec. 3.3) */
+ *   dgamma, dbeta [Cin]     out: dgamma approximate, dbeta exact (Sec. 3.3)
+ * flags: ABL_ACCUM_DX, ABL_MATH_BF16. */
 int abl_backward(void* stream, const abl_shape* shape, int K, uint32_t flags,
                  const void* packed, const void* stats, const float* dy, const float* W,
                  void* scratch, size_t scratch_bytes,
@@ -110,7 +116,7 @@ size_t abl_bn_scratch_bytes(int64_t M, int32_t C);
 int abl_bn_stats(void* stream, const float* x, int64_t M, int32_t C, const float* gamma,
                  const float* beta, int K, void* scratch, size_t scratch_bytes, void* stats);
 /* Eq. 1-3 and Eq. 9 in one pass over x: writes A3 = max(0, A2) (fp32 [M,C]) and the
- * packed codes of A2.  a3 may alias x. */
+ * packed codes of A2. */
 int abl_bn_relu_pack(void* stream, const float* x, int64_t M, int32_t C, int K,
                      const void* stats, float* a3, void* packed);
 /* Eq. 9 alone: a2 fp32 [M,C] -> packed codes (gamma, beta, cq, fb from stats). */
@@ -124,17 +130,17 @@ int abl_unpack(void* stream, const void* packed, int64_t M, int32_t C, int K,
 int abl_bn_bwd(void* stream, const void* packed, const void* stats, const float* da3,
                int64_t M, int32_t C, int K, uint32_t flags, void* scratch, size_t scratch_bytes,
                float* dx, float* dgamma, float* dbeta);
-/* Eq. 4: y = a3 (*) W (+ skip).  skip may be NULL or alias y. */
-int abl_conv_fwd(void* stream, const abl_shape* shape, const float* a3, const float* W,
+/* Eq. 4: y = a3 (*) W (+ skip).  skip may be NULL or alias y.  flags: ABL_MATH_BF16. */
+int abl_conv_fwd(void* stream, const abl_shape* shape, uint32_t flags, const float* a3, const float* W,
                  const float* skip, float* y);
-/* Eq. 5, gradient to the conv input: da3 [N,H,W,Cin] from dy [N,Ho,Wo,Cout]. */
-int abl_conv_dgrad(void* stream, const abl_shape* shape, const float* dy, const float* W,
+/* Eq. 5, gradient to the conv input: da3 [N,H,W,Cin] from dy [N,Ho,Wo,Cout].  flags: ABL_MATH_BF16. */
+int abl_conv_dgrad(void* stream, const abl_shape* shape, uint32_t flags, const float* dy, const float* W,
                    float* da3);
 /* Eq. 5, gradient to the weights, with A3 rebuilt on the fly from the packed codes
  * (Eq. 10 then Eq. 3); no full-precision copy of the activation is written to memory.
- * scratch: abl_wgrad_scratch_bytes(shape). */
+ * scratch: abl_wgrad_scratch_bytes(shape).  flags: ABL_MATH_BF16. */
 size_t abl_wgrad_scratch_bytes(const abl_shape* shape);
-int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, const void* packed,
+int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, uint32_t flags, const void* packed,
                           const void* stats, const float* dy, void* scratch,
                           size_t scratch_bytes, float* dW);
 

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libabl.so")
 
 ABL_OK, ABL_ERR_ARG, ABL_ERR_SHAPE, ABL_ERR_SCRATCH, ABL_ERR_HIP = range(5)
 ABL_ACCUM_DX = 1
+ABL_MATH_BF16 = 2
 STATS_PLANES = 8
 
 
@@ -55,9 +56,9 @@ _SIGS = {
     "abl_pack": (ctypes.c_int, [_vp, _vp, _i64, _i32, ctypes.c_int, _vp, _vp]),
     "abl_unpack": (ctypes.c_int, [_vp, _vp, _i64, _i32, ctypes.c_int, _vp, _vp]),
     "abl_bn_bwd": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _u32, _vp, _sz, _vp, _vp, _vp]),
-    "abl_conv_fwd": (ctypes.c_int, [_vp, _shp, _vp, _vp, _vp, _vp]),
-    "abl_conv_dgrad": (ctypes.c_int, [_vp, _shp, _vp, _vp, _vp]),
-    "abl_conv_wgrad_packed": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "abl_conv_fwd": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp, _vp]),
+    "abl_conv_dgrad": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp]),
+    "abl_conv_wgrad_packed": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "abl_stack_scratch_bytes": (_sz, [_lay, _i32, ctypes.c_int]),
     "abl_stack_buffer_bytes": (_sz, [_lay, _i32]),
     "abl_stack_forward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
@@ -160,19 +161,20 @@ def abl_bn_bwd(packed, stats, da3, M, C, K, scratch, dx, dgamma, dbeta, flags=0)
            "abl_bn_bwd")
 
 
-def abl_conv_fwd(shape, a3, W, skip, y):
+def abl_conv_fwd(shape, a3, W, skip, y, flags=0):
     s = shape_struct(shape)
-    _check(lib.abl_conv_fwd(_stream(), ctypes.byref(s), _ptr(a3), _ptr(W), _ptr(skip), _ptr(y)), "abl_conv_fwd")
+    _check(lib.abl_conv_fwd(_stream(), ctypes.byref(s), flags, _ptr(a3), _ptr(W), _ptr(skip), _ptr(y)),
+           "abl_conv_fwd")
 
 
-def abl_conv_dgrad(shape, dy, W, da3):
+def abl_conv_dgrad(shape, dy, W, da3, flags=0):
     s = shape_struct(shape)
-    _check(lib.abl_conv_dgrad(_stream(), ctypes.byref(s), _ptr(dy), _ptr(W), _ptr(da3)), "abl_conv_dgrad")
+    _check(lib.abl_conv_dgrad(_stream(), ctypes.byref(s), flags, _ptr(dy), _ptr(W), _ptr(da3)), "abl_conv_dgrad")
 
 
-def abl_conv_wgrad_packed(shape, K, packed, stats, dy, scratch, dW):
+def abl_conv_wgrad_packed(shape, K, packed, stats, dy, scratch, dW, flags=0):
     s = shape_struct(shape)
-    _check(lib.abl_conv_wgrad_packed(_stream(), ctypes.byref(s), K, _ptr(packed), _ptr(stats), _ptr(dy),
+    _check(lib.abl_conv_wgrad_packed(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy),
                                      _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dW)),
            "abl_conv_wgrad_packed")
 

@@ -128,26 +128,32 @@ int abl_bn_bwd(void* stream, const void* packed, const void* stats, const float*
                        scratch, dx, dgamma, dbeta);
 }
 
-int abl_conv_fwd(void* stream, const abl_shape* s, const float* a3, const float* W, const float* skip,
-                 float* y) {
+int abl_conv_fwd(void* stream, const abl_shape* s, uint32_t flags, const float* a3, const float* W,
+                 const float* skip, float* y) {
   if (int e = check_shape(s)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(a3) || bad_ptr(W) || bad_ptr(y) || (skip != nullptr && !aligned16(skip))) return ABL_ERR_ARG;
-  return launch_conv_fwd((hipStream_t)stream, *s, a3, W, skip, y);
+  return launch_conv_fwd((hipStream_t)stream, *s, (flags & ABL_MATH_BF16) != 0, a3, W, skip, y);
 }
 
-int abl_conv_dgrad(void* stream, const abl_shape* s, const float* dy, const float* W, float* da3) {
+int abl_conv_dgrad(void* stream, const abl_shape* s, uint32_t flags, const float* dy, const float* W,
+                   float* da3) {
   if (int e = check_shape(s)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(da3)) return ABL_ERR_ARG;
-  return launch_conv_dgrad((hipStream_t)stream, *s, dy, W, da3);
+  return launch_conv_dgrad((hipStream_t)stream, *s, (flags & ABL_MATH_BF16) != 0, dy, W, da3);
 }
 
-int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, const void* packed, const void* stats,
-                          const float* dy, void* scratch, size_t scratch_bytes, float* dW) {
+int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, uint32_t flags, const void* packed,
+                          const void* stats, const float* dy, void* scratch, size_t scratch_bytes,
+                          float* dW) {
   if (int e = check_shape(s)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (int e = check_k(K)) return e;
   if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(scratch) || bad_ptr(dW)) return ABL_ERR_ARG;
   if (scratch_bytes < wgrad_partial_bytes(*s)) return ABL_ERR_SCRATCH;
-  return launch_conv_wgrad_packed((hipStream_t)stream, *s, K, packed, stats, dy, scratch, dW);
+  return launch_conv_wgrad_packed((hipStream_t)stream, *s, K, (flags & ABL_MATH_BF16) != 0, packed, stats, dy,
+                                  scratch, dW);
 }
 
 // Forward: statistics -> (normalise, ReLU, quantize, pack) -> convolution.  A3 lives in the
@@ -158,7 +164,7 @@ int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const f
                 size_t scratch_bytes, float* y, void* packed, void* stats) {
   if (int e = check_shape(s)) return e;
   if (int e = check_k(K)) return e;
-  if (flags != 0) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
       bad_ptr(packed) || bad_ptr(stats) || (skip != nullptr && !aligned16(skip)))
     return ABL_ERR_ARG;
@@ -170,7 +176,7 @@ int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const f
   void* red = static_cast<char*>(scratch) + act;
   if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
-  return launch_conv_fwd(st, *s, a3, W, skip, y);
+  return launch_conv_fwd(st, *s, (flags & ABL_MATH_BF16) != 0, a3, W, skip, y);
 }
 
 // Backward: dgrad (exact) and wgrad (from the packed copy) consume dy; then the BN/ReLU
@@ -181,7 +187,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
                  float* dx, float* dW, float* dgamma, float* dbeta) {
   if (int e = check_shape(s)) return e;
   if (int e = check_k(K)) return e;
-  if (flags & ~(uint32_t)ABL_ACCUM_DX) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)(ABL_ACCUM_DX | ABL_MATH_BF16)) return ABL_ERR_ARG;
   if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(W) || bad_ptr(scratch) || bad_ptr(dx) ||
       bad_ptr(dW) || bad_ptr(dgamma) || bad_ptr(dbeta))
     return ABL_ERR_ARG;
@@ -193,8 +199,9 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   float* da3 = static_cast<float*>(scratch);
   void* red = static_cast<char*>(scratch) + act;
   void* wpart = static_cast<char*>(scratch) + act + redb;
-  if (int e = launch_conv_dgrad(st, *s, dy, W, da3)) return e;
-  if (int e = launch_conv_wgrad_packed(st, *s, K, packed, stats, dy, wpart, dW)) return e;
+  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
+  if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
   return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, (flags & ABL_ACCUM_DX) != 0, red, dx, dgamma,
                        dbeta);
 }
@@ -283,7 +290,7 @@ extern "C" {
 int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
                       size_t scratch_bytes) {
-  if (flags != 0) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
   for (int i = 0; i < L; ++i) {
     const abl_layer& l = layers[i];
@@ -296,7 +303,7 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
       y = gi.last ? buf_s : buf_t;
       if (gi.last && gi.shortcut) skip = buf_s;
     }
-    if (int e = abl_forward(stream, &l.shape, K, 0, x, l.W, l.gamma, l.beta, skip, scratch, scratch_bytes, y,
+    if (int e = abl_forward(stream, &l.shape, K, flags, x, l.W, l.gamma, l.beta, skip, scratch, scratch_bytes, y,
                             l.packed, l.stats))
       return e;
   }
@@ -310,7 +317,7 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
 int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
                        int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
                        size_t scratch_bytes) {
-  if (flags != 0) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
   for (int i = L - 1; i >= 0; --i) {
     const abl_layer& l = layers[i];
@@ -318,11 +325,11 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
     const GroupInfo gi = group_info(layers, L, skip_every, i);
     const float* dy = buf_s;
     float* dx = buf_s;
-    uint32_t f = 0;
+    uint32_t f = flags;
     if (gi.in_group) {
       dy = gi.last ? buf_s : buf_t;
       dx = gi.first ? buf_s : buf_t;
-      if (gi.first && gi.shortcut) f = ABL_ACCUM_DX;
+      if (gi.first && gi.shortcut) f |= ABL_ACCUM_DX;
     }
     if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W, scratch, scratch_bytes, dx,
                              l.dW, l.dgamma, l.dbeta))

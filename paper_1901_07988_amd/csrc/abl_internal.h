@@ -48,23 +48,81 @@ inline ConvGeom geom_of(const abl_shape& s) {
 // ---- stride-1 convolutions with the input tile staged once in LDS (conv_halo.hip) ----
 // mode 0: forward, mode 1: gradient to the input.
 bool halo_conv_supported(const ConvGeom& g);
-int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
                      const float* skip, float* out);
 
 // Weight gradient of stride-1 3x3 convolutions from the packed activation, all taps per pass.
 // halo_wgrad_partial_bytes returns 0 when the shape is not supported.
 size_t halo_wgrad_partial_bytes(const ConvGeom& g);
-int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                       const float* dy, void* scratch, float* dw);
 
 // ---- convolution kernels (conv_kernels.hip) ----
 size_t wgrad_partial_bytes(const abl_shape& s);
-int launch_conv_fwd(hipStream_t st, const abl_shape& s, const float* a3, const float* w,
+int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,
                     const float* skip, float* y);
-int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const float* w,
+int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float* dy, const float* w,
                       float* da3);
-int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const void* packed,
+int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
                              const void* stats, const float* dy, void* scratch, float* dw);
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+// D = A(16x4) * B(4x16) + C on the fp32 matrix cores; lane l supplies A[l%16][l/16] and
+// B[l/16][l%16] and holds D[4*(l/16) + r][l%16], r = 0..3.
+__device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ inline short bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (short)(u >> 16);
+}
+
+__device__ inline shortx4 to_bf16x4(const float4& v) {
+  return shortx4{bf16_bits(v.x), bf16_bits(v.y), bf16_bits(v.z), bf16_bits(v.w)};
+}
+
+// Contract four consecutive k (one float4 per lane and operand row) into every accumulator
+// tile.  fp32: four 16x16x4 MFMAs per tile, component e of the float4 = k-step e, the lane
+// group l/16 = k within the step.  bf16: operands rounded to bf16, ONE 16x16x16 MFMA per
+// tile, lane group l/16 supplies k = 4*(l/16) + e; accumulation stays fp32.
+template <bool BF16, int MT, int NT>
+__device__ inline void mma_k4(const float4 (&af)[MT], const float4 (&bf)[NT], floatx4 (&acc)[MT][NT]) {
+  if constexpr (BF16) {
+    shortx4 a[MT], b[NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) a[i] = to_bf16x4(af[i]);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) b[j] = to_bf16x4(bf[j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+  } else {
+    // k-step outermost: consecutive MFMAs write different accumulators
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+  }
+}
 
 // v where ok, zeros elsewhere - written per component so that it stays in registers
 __device__ inline float4 keep_if(bool ok, const float4& v) {

@@ -19,7 +19,6 @@
 namespace abl {
 namespace {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int PS = 20;     // floats per staged pixel: 16 channels + 4 pad (conflict-free b128 reads)
@@ -55,9 +54,6 @@ struct Pos {
   }
 };
 
-__device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-}
 
 // WAVES_N waves share the block's M-tiles and split its N-tiles; the other 4/WAVES_N groups
 // split the M-tiles.  MT = M-tiles per wave (upper bound, `mtiles` is the real count),
@@ -65,7 +61,7 @@ __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
 // consecutive k of one output channel) for the next tap straight from L2 while the current
 // tap is contracted.  With more than 16 input channels the patch buffer is doubled and the
 // next chunk's global loads are in flight during the MFMAs.
-template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS>
+template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16>
 __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
                                                              float* out, ConvGeom g, HaloPlan p) {
@@ -190,22 +186,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       float4 af[MT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bcur[j].x, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bcur[j].y, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bcur[j].z, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bcur[j].w, acc[i][j]);
+      mma_k4<BF16, MT, NT>(af, bcur, acc);
 #pragma unroll
       for (int j = 0; j < NT; ++j) bcur[j] = bnext[j];
     };
@@ -343,28 +324,30 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
 }
 
 template <int MODE, int V>
-void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const float* in, const float* w,
+void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
                     const float* skip, float* out) {
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * cdiv(Ng, p.bn));
-  if (g.R == 3 && g.S == 3 && var.mt * var.nt <= 4)
-    halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
-  else
-    halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false><<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
+  const bool unroll = g.R == 3 && g.S == 3 && var.mt * var.nt <= 4;
+  auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true>
+                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false>)
+                     : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true>
+                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false>);
+  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
 }
 
 template <int MODE>
-void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const float* in, const float* w,
+void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
                  const float* skip, float* out) {
   switch (p.variant) {
-    case 0: launch_variant<MODE, 0>(st, g, p, in, w, skip, out); break;
-    case 1: launch_variant<MODE, 1>(st, g, p, in, w, skip, out); break;
-    case 2: launch_variant<MODE, 2>(st, g, p, in, w, skip, out); break;
-    case 3: launch_variant<MODE, 3>(st, g, p, in, w, skip, out); break;
-    case 4: launch_variant<MODE, 4>(st, g, p, in, w, skip, out); break;
-    case 5: launch_variant<MODE, 5>(st, g, p, in, w, skip, out); break;
-    default: launch_variant<MODE, 6>(st, g, p, in, w, skip, out); break;
+    case 0: launch_variant<MODE, 0>(st, g, p, bf16, in, w, skip, out); break;
+    case 1: launch_variant<MODE, 1>(st, g, p, bf16, in, w, skip, out); break;
+    case 2: launch_variant<MODE, 2>(st, g, p, bf16, in, w, skip, out); break;
+    case 3: launch_variant<MODE, 3>(st, g, p, bf16, in, w, skip, out); break;
+    case 4: launch_variant<MODE, 4>(st, g, p, bf16, in, w, skip, out); break;
+    case 5: launch_variant<MODE, 5>(st, g, p, bf16, in, w, skip, out); break;
+    default: launch_variant<MODE, 6>(st, g, p, bf16, in, w, skip, out); break;
   }
 }
 
@@ -377,7 +360,7 @@ void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, const flo
 // A = activation at the shifted pixel, B = dy).  dy is read once per block instead of once per
 // tap.  The four waves take interleaved pixel groups and are summed in a fixed order at the
 // end.  partial layout: [gridDim.x][R][S][Cin][Cout].
-template <int K, int NT, int R, int S>
+template <int K, int NT, int R, int S, bool BF16>
 __global__ __launch_bounds__(kThreads) void halo_wgrad_kernel(const uint32_t* __restrict__ packed,
                                                               const float* __restrict__ stats,
                                                               const float* __restrict__ dy,
@@ -389,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void halo_wgrad_kernel(const uint32_t* __
   constexpr int PSB = (BNW % 32 == 0) ? BNW + 16 : BNW;
   constexpr int WPP = 16 * K / 32;  // packed 32-bit words per pixel for 16 channels
   const int patch = p.TI * p.HH * p.HW;
-  const int npix4 = (p.npix + 3) & ~3;
+  const int npix4 = (p.npix + 15) & ~15;     // pixel rows of the dy tile, padded to whole groups of 16
   float* tileA = lds;                       // [patch][16]
   float* tileB = tileA + patch * 16;        // [npix4][PSB]
   int* pixbase = reinterpret_cast<int*>(tileB + npix4 * PSB);  // [npix4] LDS offset of pixel m in tileA
@@ -477,17 +460,29 @@ __global__ __launch_bounds__(kThreads) void halo_wgrad_kernel(const uint32_t* __
       *reinterpret_cast<float4*>(&tileB[m * PSB + c4]) = v;
     }
     __syncthreads();
-    for (int q = wave; q < npix4 / 4; q += 4) {
-      const int m = 4 * q + lk;
-      const int pb = pixbase[m] + li;
-      float bf[NT];
+    // 16 pixels per step.  Component e of the operand vectors is pixel 4e + lk (fp32: k-step e,
+    // lane group = k) or 4lk + e (bf16: the lane group owns 4 consecutive k).
+    for (int q = wave; q < npix4 / 16; q += 4) {
+      int pb[4];
+      float4 bf[NT];
+      {
+        int m[4];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bf[j] = tileB[m * PSB + 16 * j + li];
+        for (int e = 0; e < 4; ++e) {
+          m[e] = 16 * q + (BF16 ? 4 * lk + e : 4 * e + lk);
+          pb[e] = pixbase[m[e]] + li;
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          bf[j] = make_float4(tileB[m[0] * PSB + 16 * j + li], tileB[m[1] * PSB + 16 * j + li],
+                              tileB[m[2] * PSB + 16 * j + li], tileB[m[3] * PSB + 16 * j + li]);
+      }
 #pragma unroll
       for (int t = 0; t < TAPS; ++t) {
-        const float a = tileA[pb + ((t / S) * p.HW + (t % S)) * 16];
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[t][j] = mfma16(a, bf[j], acc[t][j]);
+        const int toff = ((t / S) * p.HW + (t % S)) * 16;
+        float4 a[1];
+        a[0] = make_float4(tileA[pb[0] + toff], tileA[pb[1] + toff], tileA[pb[2] + toff], tileA[pb[3] + toff]);
+        mma_k4<BF16, 1, NT>(a, bf, reinterpret_cast<floatx4(&)[1][NT]>(acc[t]));
       }
     }
   }
@@ -553,7 +548,7 @@ bool make_wgrad_plan(const ConvGeom& g, WgradHaloPlan& wp) {
   choose_tile(g.Ho, g.Wo, g.N, g.R, g.S, 256, p);
   if (p.TH <= 0 || p.TH > 255 || p.TW > 255) return false;
   const int bnw = 16 * wp.nt, psb = (bnw % 32 == 0) ? bnw + 16 : bnw;
-  const int npix4 = (p.npix + 3) & ~3;
+  const int npix4 = (p.npix + 15) & ~15;
   size_t fl = (size_t)p.TI * p.HH * p.HW * 16 + (size_t)npix4 * psb + 2 * (size_t)npix4;
   const size_t red = (size_t)g.R * g.S * 16 * bnw;
   if (fl < red) fl = red;
@@ -580,12 +575,12 @@ bool halo_conv_supported(const ConvGeom& g) {
   return make_plan(g, 0, p) && make_plan(g, 1, p);
 }
 
-int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
                      const float* skip, float* out) {
   HaloPlan p;
   if (!make_plan(g, mode, p)) return ABL_ERR_SHAPE;
-  if (mode == 0) launch_mode<0>(st, g, p, in, w, skip, out);
-  else launch_mode<1>(st, g, p, in, w, nullptr, out);
+  if (mode == 0) launch_mode<0>(st, g, p, bf16, in, w, skip, out);
+  else launch_mode<1>(st, g, p, bf16, in, w, nullptr, out);
   return hip_status();
 }
 
@@ -599,7 +594,7 @@ size_t halo_wgrad_partial_bytes(const ConvGeom& g) {
   return ((size_t)wp.nblk * g.R * g.S * g.Cin * g.Cout * sizeof(float) + 255) / 256 * 256;
 }
 
-int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                       const float* dy, void* scratch, float* dw) {
   WgradHaloPlan wp;
   if (!make_wgrad_plan(g, wp)) return ABL_ERR_SHAPE;
@@ -607,7 +602,11 @@ int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* pack
   float* part = wp.nblk == 1 ? dw : static_cast<float*>(scratch);
   dim3 grid(wp.nblk, wp.gridy);
   const unsigned lds = wp.tile.lds_bytes;
-#define ABL_WG(KK, NN) halo_wgrad_kernel<KK, NN, 3, 3><<<grid, kThreads, lds, st>>>(pk, stats, dy, part, g, wp.tile)
+#define ABL_WG(KK, NN)                                                                          \
+  do {                                                                                          \
+    auto kern = bf16 ? halo_wgrad_kernel<KK, NN, 3, 3, true> : halo_wgrad_kernel<KK, NN, 3, 3, false>; \
+    kern<<<grid, kThreads, lds, st>>>(pk, stats, dy, part, g, wp.tile);                         \
+  } while (0)
   if (K == 4) {
     if (wp.nt == 1) ABL_WG(4, 1); else if (wp.nt == 2) ABL_WG(4, 2); else ABL_WG(4, 4);
   } else {

@@ -14,13 +14,9 @@
 namespace abl {
 namespace {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 
-__device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-}
 
 // ------------------------------------------------------------------------------------------
 // Implicit GEMM  Out[p][n] = sum_{tap,c} A[p][(tap,c)] * B[(tap,c)][n]
@@ -33,7 +29,7 @@ __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
 // tiles are double buffered: the global loads of chunk i+1 are in flight while chunk i is
 // contracted, and one barrier per chunk separates "everyone has read buffer b" from
 // "buffer b is overwritten".
-template <int BM, int BN, int WM, int WN, int BK, int MODE>
+template <int BM, int BN, int WM, int WN, int BK, int MODE, bool BF16>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict__ in,
                                                          const float* __restrict__ wgt,
                                                          const float* skip, float* out, ConvGeom g) {
@@ -212,23 +208,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 #pragma unroll
       for (int j = 0; j < NT; ++j)
         bf[j] = *reinterpret_cast<const float4*>(&Bs[(wn0 + 16 * j + li) * LDK + 16 * kg + 4 * lk]);
-      // k-step outermost: consecutive MFMAs write different accumulators
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+      mma_k4<BF16, MT, NT>(af, bf, acc);
     }
   };
   // The loads of chunk i+1 are issued before chunk i is contracted and written to the other
@@ -285,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 // staged in LDS (activations dequantized + ReLU'd to fp32 on the way in), each wave
 // contracts 16 of them into its own accumulators, the four waves are summed in a fixed
 // order at the end.  partial layout: [split][R][S][Cin][Cout].
-template <int TM, int TN, int K>
+template <int TM, int TN, int K, bool BF16>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
@@ -346,32 +326,44 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
   bool oka[A_PASSES];
   float4 rb[B_PASSES];
   // global loads of one 64-pixel chunk into registers
+  // Output-pixel position (n, ho, wo) of each A pass, advanced by one chunk per fetch without
+  // divisions; all loads are unconditional (clamped address, zeroed afterwards).
+  int a_wo[A_PASSES], a_ho[A_PASSES], a_n[A_PASSES];
+#pragma unroll
+  for (int i = 0; i < A_PASSES; ++i) {
+    const int64_t p = p_begin + (tid + kThreads * i) / GA;
+    const int pp = p < Mg ? (int)p : 0;
+    a_wo[i] = pp % g.Wo;
+    const int q = pp / g.Wo;
+    a_ho[i] = q % g.Ho;
+    a_n[i] = q / g.Ho;
+  }
+  const int adv_w = CH % g.Wo, adv_h = CH / g.Wo;
+  const bool a_lane_ok = (ci0 + a_cg * CPW) < g.Cin;
   auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       const int idx = tid + kThreads * i;
-      const int pl = idx / GA;
-      const int64_t p = pc + pl;
-      oka[i] = idx < CH * GA && p < p_end && (ci0 + a_cg * CPW) < g.Cin;
-      wa[i] = 0;
-      if (oka[i]) {
-        const int wo = (int)(p % g.Wo);
-        const int64_t q = p / g.Wo;
-        const int ho = (int)(q % g.Ho), n = (int)(q / g.Ho);
-        const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s - g.pad;
-        oka[i] = hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
-        if (oka[i])
-          wa[i] = packed[((((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci0) / CPW + a_cg];
-      }
+      const int64_t p = pc + idx / GA;
+      const int hi = a_ho[i] * g.stride + r - g.pad, wi = a_wo[i] * g.stride + s - g.pad;
+      oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end && hi >= 0 && hi < g.H &&
+               wi >= 0 && wi < g.W;
+      const int64_t e = oka[i] ? (((int64_t)a_n[i] * g.H + hi) * g.W + wi) * g.Cin + ci0 : 0;
+      wa[i] = packed[e / CPW + (oka[i] ? a_cg : 0)];
+      // advance to the same slot of the next chunk
+      a_wo[i] += adv_w;
+      a_ho[i] += adv_h;
+      if (a_wo[i] >= g.Wo) { a_wo[i] -= g.Wo; ++a_ho[i]; }
+      while (a_ho[i] >= g.Ho) { a_ho[i] -= g.Ho; ++a_n[i]; }
     }
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
       const int pl = idx / GB, c = co0 + 4 * (idx % GB);
       const int64_t p = pc + pl;
-      rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (idx < CH * GB && p < p_end && c < g.Cout)
-        rb[j] = *reinterpret_cast<const float4*>(dy + p * g.Cout + c);
+      const bool ok = (CH * GB % kThreads == 0 || idx < CH * GB) && p < p_end && c < g.Cout;
+      const float4 v = *reinterpret_cast<const float4*>(dy + (ok ? p * g.Cout + c : 0));
+      rb[j] = keep_if(ok, v);
     }
   };
   if (p_begin < p_end) fetch(p_begin);
@@ -397,19 +389,22 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
     }
     __syncthreads();
     if (pc + CH < p_end) fetch(pc + CH);  // in flight while this chunk is contracted
-    // wave w contracts pixels [16w, 16w+16) of the chunk: 4 MFMA k-steps of 4 pixels
+    // wave w contracts pixels [16w, 16w+16) of the chunk.  Component e of the operand vectors is
+    // pixel 4e + lk (fp32: k-step e, lane group = k) or 4lk + e (bf16: lane group owns 4 k).
+    {
+      float4 af[MT], bf[NT];
+      int row[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int row = 16 * wave + 4 * ks + lk;
-      float af[MT], bf[NT];
-#pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = As[row * LDA + 16 * i + li];
-#pragma unroll
-      for (int j = 0; j < NT; ++j) bf[j] = Bs[row * LDB + 16 * j + li];
+      for (int e = 0; e < 4; ++e) row[e] = 16 * wave + (BF16 ? 4 * lk + e : 4 * e + lk);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
+        af[i] = make_float4(As[row[0] * LDA + 16 * i + li], As[row[1] * LDA + 16 * i + li],
+                            As[row[2] * LDA + 16 * i + li], As[row[3] * LDA + 16 * i + li]);
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = mfma16(af[i], bf[j], acc[i][j]);
+      for (int j = 0; j < NT; ++j)
+        bf[j] = make_float4(Bs[row[0] * LDB + 16 * j + li], Bs[row[1] * LDB + 16 * j + li],
+                            Bs[row[2] * LDB + 16 * j + li], Bs[row[3] * LDB + 16 * j + li]);
+      mma_k4<BF16, MT, NT>(af, bf, acc);
     }
   }
 
@@ -557,8 +552,8 @@ inline bool mfma_ok(const ConvGeom& g) { return g.Cin % 16 == 0 && g.Cout % 16 =
 // Tile choice: the largest tile whose grid still gives every CU about two blocks; a tile
 // that is too large for a small GEMM leaves compute units idle.
 template <int MODE>
-int launch_igemm(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip,
-                 float* out) {
+int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w,
+                 const float* skip, float* out) {
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
   auto blocks = [&](int bm, int bn) __attribute__((always_inline)) { return ((Mg + bm - 1) / bm) * ((Ng + bn - 1) / bn); };
@@ -567,12 +562,12 @@ int launch_igemm(hipStream_t st, const ConvGeom& g, const float* in, const float
     const int64_t mb8 = ((Mg + BM_ - 1) / BM_ + 7) / 8 * 8;                                   \
     dim3 grid((unsigned)(mb8 * ((Ng + BN_ - 1) / BN_)));                                      \
     constexpr unsigned lds = 2u * (BM_ + BN_) * (BK_ + 4) * sizeof(float);                    \
-    auto kern = igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE>;                                   \
-    if (lds > 64 * 1024) {                                                                     \
-      static const hipError_t attr = hipFuncSetAttribute(                                     \
-          reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
-      if (attr != hipSuccess) return ABL_ERR_HIP;                                              \
-    }                                                                                          \
+    auto kern = bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true>                       \
+                     : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false>;                     \
+    if (lds > 64 * 1024 &&                                                                     \
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                               \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)    \
+      return ABL_ERR_HIP;                                                                                          \
     kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, g);                                    \
   } while (0)
   const int Cg = MODE == 0 ? g.Cin : g.Cout;
@@ -642,7 +637,7 @@ size_t wgrad_partial_bytes(const abl_shape& s) {
   return ((size_t)p.split * n + 255) / 256 * 256;
 }
 
-int launch_conv_fwd(hipStream_t st, const abl_shape& s, const float* a3, const float* w,
+int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,
                     const float* skip, float* y) {
   const ConvGeom g = geom_of(s);
   if (!mfma_ok(g)) {
@@ -650,11 +645,11 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, const float* a3, const f
     naive_fwd_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(a3, w, skip, y, g);
     return hip_status();
   }
-  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, a3, w, skip, y);
-  return launch_igemm<0>(st, g, a3, w, skip, y);
+  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y);
+  return launch_igemm<0>(st, g, bf16, a3, w, skip, y);
 }
 
-int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const float* w,
+int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float* dy, const float* w,
                       float* da3) {
   const ConvGeom g = geom_of(s);
   if (!mfma_ok(g)) {
@@ -662,22 +657,21 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, const float* dy, const
     naive_dgrad_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(dy, w, da3, g);
     return hip_status();
   }
-  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, dy, w, nullptr, da3);
-  return launch_igemm<1>(st, g, dy, w, nullptr, da3);
+  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
+  return launch_igemm<1>(st, g, bf16, dy, w, nullptr, da3);
 }
 
 template <int TM, int TN>
-static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K,
+static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K, bool bf16,
                               const void* packed, const float* stats, const float* dy, float* dst) {
   dim3 grid((unsigned)((p.split + 7) / 8 * 8 * p.tiles));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
-  if (K == 4)
-    wgrad_kernel<TM, TN, 4><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
-  else
-    wgrad_kernel<TM, TN, 8><<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
+  auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true> : wgrad_kernel<TM, TN, 4, false>)
+                     : (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>);
+  kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
 }
 
-int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const void* packed,
+int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
                              const void* stats, const float* dy, void* scratch, float* dw) {
   const ConvGeom g = geom_of(s);
   const float* sp = static_cast<const float*>(stats);
@@ -688,18 +682,18 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, const vo
     else naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
     return hip_status();
   }
-  if (use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, packed, sp, dy, scratch, dw);
+  if (use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
-  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 32) launch_wgrad_tile<32, 32>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 16) launch_wgrad_tile<32, 16>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, packed, sp, dy, dst);
-  else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, packed, sp, dy, dst);
-  else launch_wgrad_tile<16, 16>(st, g, p, K, packed, sp, dy, dst);
+  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 32) launch_wgrad_tile<32, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 32 && p.tn == 16) launch_wgrad_tile<32, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
+  else launch_wgrad_tile<16, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
   if (p.split > 1) {
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
     wgrad_reduce_kernel<<<(unsigned)((n + 63) / 64), kThreads, 0, st>>>(dst, p.split, n, dw);

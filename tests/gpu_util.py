@@ -99,29 +99,29 @@ def out_shape(s):
     return (s.N, s.Ho, s.Wo, s.Cout)
 
 
-def run_conv_fwd(s, a3, w, skip=None, alias_skip=False):
+def run_conv_fwd(s, a3, w, skip=None, alias_skip=False, flags=0):
     y = torch.empty(out_shape(s), dtype=torch.float32, device="cuda")
     sk = None
     if skip is not None:
         sk = dev(skip)
         if alias_skip:
             y = sk
-    B.abl_conv_fwd(s.as_tuple(), dev(a3), dev(w), sk, y)
+    B.abl_conv_fwd(s.as_tuple(), dev(a3), dev(w), sk, y, flags=flags)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def run_conv_dgrad(s, dy, w):
+def run_conv_dgrad(s, dy, w, flags=0):
     da3 = torch.empty((s.N, s.H, s.W, s.Cin), dtype=torch.float32, device="cuda")
-    B.abl_conv_dgrad(s.as_tuple(), dev(dy), dev(w), da3)
+    B.abl_conv_dgrad(s.as_tuple(), dev(dy), dev(w), da3, flags=flags)
     torch.cuda.synchronize()
     return da3.cpu().numpy()
 
 
-def run_conv_wgrad(s, K, packed, stats_t, dy):
+def run_conv_wgrad(s, K, packed, stats_t, dy, flags=0):
     scratch = zeros_bytes(B.abl_wgrad_scratch_bytes(s.as_tuple()))
     dw = torch.empty((s.R, s.S, s.Cin, s.Cout), dtype=torch.float32, device="cuda")
-    B.abl_conv_wgrad_packed(s.as_tuple(), K, dev(packed), stats_t, dev(dy), scratch, dw)
+    B.abl_conv_wgrad_packed(s.as_tuple(), K, dev(packed), stats_t, dev(dy), scratch, dw, flags=flags)
     torch.cuda.synchronize()
     return dw.cpu().numpy()
 
@@ -129,8 +129,8 @@ def run_conv_wgrad(s, K, packed, stats_t, dy):
 class LayerRun:
     """One abl_forward (+ abl_backward) on the device."""
 
-    def __init__(self, s, K):
-        self.s, self.K = s, K
+    def __init__(self, s, K, flags=0):
+        self.s, self.K, self.flags = s, K, flags
         t = s.as_tuple()
         self.scratch = zeros_bytes(B.abl_scratch_bytes(t, K))
         self.packed = torch.full((B.abl_packed_bytes(t, K),), 0xEE, dtype=torch.uint8, device="cuda")
@@ -145,7 +145,8 @@ class LayerRun:
         else:
             y = torch.empty(out_shape(s), dtype=torch.float32, device="cuda")
         B.abl_forward(s.as_tuple(), self.K, xd, dev(w), dev(gamma), dev(beta),
-                      None if skip is None else dev(skip), self.scratch, y, self.packed, self.stats)
+                      None if skip is None else dev(skip), self.scratch, y, self.packed, self.stats,
+                      flags=self.flags)
         torch.cuda.synchronize()
         return y.cpu().numpy()
 
@@ -156,7 +157,7 @@ class LayerRun:
         dg = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
         db = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
         B.abl_backward(s.as_tuple(), self.K, self.packed, self.stats, dev(dy), dev(w), self.scratch, dx, dw, dg, db,
-                       flags=B.ABL_ACCUM_DX if accum_into is not None else 0)
+                       flags=self.flags | (B.ABL_ACCUM_DX if accum_into is not None else 0))
         torch.cuda.synchronize()
         return dx.cpu().numpy(), dw.cpu().numpy(), dg.cpu().numpy(), db.cpu().numpy()
 
@@ -165,8 +166,8 @@ class StackRun:
     """A residual stack on the device: owns the two activation buffers, the workspace and the
     per-layer stores."""
 
-    def __init__(self, layers, K, skip_every):
-        self.K, self.skip_every = K, skip_every
+    def __init__(self, layers, K, skip_every, flags=0):
+        self.K, self.skip_every, self.flags = K, skip_every, flags
         self.descs = []
         for s, w, g, b in layers:
             t = s.as_tuple()
@@ -187,10 +188,12 @@ class StackRun:
         self.buf_s[: a.size].copy_(torch.from_numpy(np.ascontiguousarray(a)).view(-1))
 
     def forward(self):
-        B.abl_stack_forward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch)
+        B.abl_stack_forward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
+                            flags=self.flags)
 
     def backward(self):
-        B.abl_stack_backward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch)
+        B.abl_stack_backward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
+                             flags=self.flags)
 
     def output(self):
         n = int(np.prod(out_shape(self.last)))

@@ -13,6 +13,7 @@ from paper_1901_07988_amd.synth import LayerShape
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
+TOL_BF16 = 2e-2        # contractions with operands rounded to bf16 (8 mantissa bits), fp32 accumulation
 
 
 def close_but_for_flips(a, b, tol=TOL):
@@ -191,6 +192,38 @@ def test_conv_forward_and_dgrad(G, oracle, s):
 
 
 @pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
+def test_conv_bf16_variant(G, oracle, s):
+    """ABL_MATH_BF16: same contractions with operands rounded to bf16; the oracle stays fp32/fp64
+    and the bar is the looser 2e-2.  The result must differ from the fp32 path (the flag is live)
+    wherever the matrix-core kernels are used."""
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    print("case conv bf16", s.as_tuple(), flush=True)
+    rng = np.random.default_rng(sum(s.as_tuple()) + 99)
+    a3 = np.maximum(rng.standard_normal((s.N, s.H, s.W, s.Cin)), 0).astype(np.float32)
+    w = synth.he_normal(rng, s)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    skip = rng.standard_normal(dy.shape).astype(np.float32)
+    y_ref = o.conv_fwd(a3, w, oshape(o, s))
+    y = G.run_conv_fwd(s, a3, w, skip, flags=B.ABL_MATH_BF16)
+    assert rel(y, y_ref + skip) < TOL_BF16
+    da = G.run_conv_dgrad(s, dy, w, flags=B.ABL_MATH_BF16)
+    assert rel(da, o.conv_dgrad(dy, w, oshape(o, s))) < TOL_BF16
+    gamma, beta = rand_affine(rng, s.Cin)
+    a2 = (gamma * rng.standard_normal((s.N, s.H, s.W, s.Cin)) + beta).astype(np.float32)
+    K = 4
+    q = o.quantize(a2, gamma, beta, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    z = np.zeros(s.Cin, np.float32)
+    st = G.stats_from_arrays(z, z + 1, z + 1, gamma, beta, cq, step, fb)
+    dw_ref = o.conv_wgrad(np.maximum(o.dequantize(q, gamma, beta, K), 0), dy, oshape(o, s))
+    dw = G.run_conv_wgrad(s, K, o.pack_codes(q, K), st, dy, flags=B.ABL_MATH_BF16)
+    assert rel(dw, dw_ref) < TOL_BF16
+    if s.Cin % 16 == 0 and s.Cout % 16 == 0:
+        assert rel(y, y_ref + skip) > 1e-5 and rel(da, o.conv_dgrad(dy, w, oshape(o, s))) > 1e-5
+
+
+@pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
 @pytest.mark.parametrize("K", [4, 8])
 def test_conv_wgrad_from_packed(G, oracle, s, K):
     o = oracle
@@ -242,6 +275,26 @@ def test_layer_forward_backward(G, oracle, case, K):
     dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
     assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
     assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+
+
+@pytest.mark.parametrize("case", LAYER_CASES[:8], ids=lambda c: "x".join(map(str, c[0].as_tuple())))
+def test_layer_bf16_variant(G, oracle, case):
+    """Layer step with ABL_MATH_BF16: codes and statistics are untouched by the flag (bit-exact),
+    outputs and gradients within 2e-2."""
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    s, xd, aff = case
+    print("case layer bf16", s.as_tuple(), flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, synth.DEFAULT_SEED, xd, aff)
+    run = G.LayerRun(s, 4, flags=B.ABL_MATH_BF16)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, 4, oshape(o, s))
+    assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL_BF16
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL_BF16 and rel(dw, dw_ref) < TOL_BF16
+    assert rel(dg, dg_ref) < TOL_BF16 and rel(db, db_ref) < TOL_BF16
 
 
 def test_layer_forward_is_independent_of_K_and_repeatable(G):
