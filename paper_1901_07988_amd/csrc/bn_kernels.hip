@@ -24,6 +24,8 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
+// fp32 tensors at least this large are written with streaming (non-temporal) stores
+constexpr int64_t kStreamBytes = 64ll << 20;
 
 struct RowGeom {
   int CV;     // channel groups per row (C / VEC)
@@ -52,7 +54,7 @@ RowGeom make_geom(int64_t M, int C, int VEC, bool reduce) {
     const int64_t cap = (passes + kMaxPartialBlocks - 1) / kMaxPartialBlocks;
     if (rpt < cap) rpt = cap;
   } else {
-    if (rpt > 8) rpt = 8;
+    if (rpt > 16) rpt = 16;
   }
   if (rpt < 1) rpt = 1;
   g.rpt = (int)rpt;
@@ -89,12 +91,18 @@ __device__ inline void load_vec_i(const int32_t* __restrict__ p, int32_t (&v)[VE
   }
 }
 
-template <int VEC>
+// STREAM: the stores carry the non-temporal hint (large tensors that will not be re-read from
+// cache before they are evicted anyway).
+template <int VEC, bool STREAM = false>
 __device__ inline void store_vec(float* __restrict__ p, const float (&v)[VEC]) {
   if constexpr (VEC % 4 == 0) {
+    typedef float vec4f __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int i = 0; i < VEC / 4; ++i)
-      reinterpret_cast<float4*>(p)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+    for (int i = 0; i < VEC / 4; ++i) {
+      const vec4f t = {v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+      if constexpr (STREAM) __builtin_nontemporal_store(t, reinterpret_cast<vec4f*>(p) + i);
+      else reinterpret_cast<vec4f*>(p)[i] = t;
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) p[i] = v[i];
@@ -276,7 +284,7 @@ __global__ __launch_bounds__(kFinThreads) void stats_finalize_kernel(const doubl
 
 // ------------------------------------------------------------------------------------------
 // Forward elementwise pass.  MODE 0: x -> A3 and codes (Eq. 1-3, 9).  MODE 1: a2 -> codes (Eq. 9).
-template <int K, int VEC, int MODE>
+template <int K, int VEC, int MODE, bool STREAM>
 __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __restrict__ in, int64_t M, int C,
                                                               RowGeom g, const float* __restrict__ stats,
                                                               float* __restrict__ a3,
@@ -328,14 +336,14 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
           word |= quant_code<K>(a2, cq[v], fb[v]) << (K * v);
         }
         const int64_t e = r * C + p.c0;
-        if constexpr (MODE == 0) store_vec<VEC>(a3 + e, out);
+        if constexpr (MODE == 0) store_vec<VEC, STREAM>(a3 + e, out);
         pw[e / VEC] = (word_t)word;
       }
   }
 }
 
 // Eq. 10: codes -> fp32.
-template <int K, int VEC>
+template <int K, int VEC, bool STREAM>
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict__ packed, int64_t M, int C,
                                                           RowGeom g, const float* __restrict__ stats,
                                                           float* __restrict__ a2t) {
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict
 #pragma unroll
         for (int v = 0; v < VEC; ++v)
           out[v] = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
-        store_vec<VEC>(a2t + r * C + p.c0, out);
+        store_vec<VEC, STREAM>(a2t + r * C + p.c0, out);
       }
   }
 }
@@ -465,7 +473,7 @@ __global__ __launch_bounds__(kFinThreads) void bwd_finalize_kernel(const double*
 }
 
 // Backward, pass 2 (Eq. 8): dx = rstd * (dA1 - Mean(dA1) - A1~ * Mean(A1~ * dA1)).
-template <int K, int VEC, bool ACCUM>
+template <int K, int VEC, bool ACCUM, bool STREAM>
 __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restrict__ packed,
                                                              const float* da3, int64_t M, int C, RowGeom g,
                                                              const float* __restrict__ stats,
@@ -514,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
           out[v] = rstd[v] * t;                             // Eq. 8
           if constexpr (ACCUM) out[v] = acc[j][v] + out[v];
         }
-        store_vec<VEC>(dx + r * C + p.c0, out);
+        store_vec<VEC, STREAM>(dx + r * C + p.c0, out);
       }
   }
 }
@@ -696,12 +704,18 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
   }
   const RowGeom g = make_geom(M, C, vec, false);
   const int pad = (int)(pbytes - raw);
-  if (K == 4 && vec == 8)
-    quant_pack_kernel<4, 8, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
-  else if (K == 4)
-    quant_pack_kernel<4, 4, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
-  else
-    quant_pack_kernel<8, 4, MODE><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);
+  const bool stream = E * (int64_t)sizeof(float) >= kStreamBytes;
+#define ABL_QP(KK, VV)                                                                                   \
+  do {                                                                                                   \
+    if (stream)                                                                                          \
+      quant_pack_kernel<KK, VV, MODE, true><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);  \
+    else                                                                                                 \
+      quant_pack_kernel<KK, VV, MODE, false><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad); \
+  } while (0)
+  if (K == 4 && vec == 8) ABL_QP(4, 8);
+  else if (K == 4) ABL_QP(4, 4);
+  else ABL_QP(8, 4);
+#undef ABL_QP
   return hip_status();
 }
 
@@ -730,12 +744,15 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
-  if (K == 4 && vec == 8)
-    unpack_kernel<4, 8><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
-  else if (K == 4)
-    unpack_kernel<4, 4><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
-  else
-    unpack_kernel<8, 4><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);
+  // (streaming stores slow a pure-write kernel down on this part; measured 87 us vs 36 us)
+#define ABL_UP(KK, VV)                                                                              \
+  do {                                                                                              \
+    unpack_kernel<KK, VV, false><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);        \
+  } while (0)
+  if (K == 4 && vec == 8) ABL_UP(4, 8);
+  else if (K == 4) ABL_UP(4, 4);
+  else ABL_UP(8, 4);
+#undef ABL_UP
   return hip_status();
 }
 
@@ -771,16 +788,23 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
     return hip_status();
   }
   const RowGeom ga = make_geom(M, C, vec, false);
-#define ABL_APPLY(KK, VV)                                                                               \
-  do {                                                                                                  \
-    if (accum)                                                                                          \
-      bwd_apply_kernel<KK, VV, true><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
-    else                                                                                                \
-      bwd_apply_kernel<KK, VV, false><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
+  const bool stream = M * C * (int64_t)sizeof(float) >= kStreamBytes;
+#define ABL_APPLY1(KK, VV, AA)                                                                              \
+  do {                                                                                                      \
+    if (stream)                                                                                             \
+      bwd_apply_kernel<KK, VV, AA, true><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx);  \
+    else                                                                                                    \
+      bwd_apply_kernel<KK, VV, AA, false><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
+  } while (0)
+#define ABL_APPLY(KK, VV)             \
+  do {                                \
+    if (accum) ABL_APPLY1(KK, VV, true); \
+    else ABL_APPLY1(KK, VV, false);   \
   } while (0)
   if (K == 4 && vec == 8) ABL_APPLY(4, 8);
   else if (K == 4) ABL_APPLY(4, 4);
   else ABL_APPLY(8, 4);
+#undef ABL_APPLY1
 #undef ABL_APPLY
   return hip_status();
 }
