@@ -21,7 +21,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
 UNITS = {
     "bn_kernels.hip": ["-ffp-contract=off"],
     "conv_kernels.hip": [],
-    "conv_halo.hip": [],
+    "conv_halo.hip": ["-ffp-contract=off"],
     "abl_api.hip": [],
 }
 

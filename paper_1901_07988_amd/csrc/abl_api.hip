@@ -174,9 +174,16 @@ int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const f
   const size_t act = up256((size_t)M * s->Cin * sizeof(float));
   float* a3 = static_cast<float*>(scratch);
   void* red = static_cast<char*>(scratch) + act;
+  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
   if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
+  const ConvGeom g = geom_of(*s);
+  // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
+  // patch: x is read once and A3 never reaches memory.  y may still alias x only through the
+  // two-kernel path, so the fused kernel is used when they are distinct buffers.
+  if (halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y))
+    return launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
-  return launch_conv_fwd(st, *s, (flags & ABL_MATH_BF16) != 0, a3, W, skip, y);
+  return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
 }
 
 // Backward: dgrad (exact) and wgrad (from the packed copy) consume dy; then the BN/ReLU

@@ -50,6 +50,11 @@ inline ConvGeom geom_of(const abl_shape& s) {
 bool halo_conv_supported(const ConvGeom& g);
 int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
                      const float* skip, float* out);
+// Forward with Eq. 1-3 and Eq. 9 applied while the input patch is staged: reads x, writes y and
+// the packed codes; A3 never reaches memory.  Supported for 'same' stride-1 convolutions.
+bool halo_fused_supported(const ConvGeom& g);
+int launch_halo_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x,
+                          const void* stats, const float* w, const float* skip, float* y, void* packed);
 
 // Weight gradient of stride-1 3x3 convolutions from the packed activation, all taps per pass.
 // halo_wgrad_partial_bytes returns 0 when the shape is not supported.
@@ -65,6 +70,35 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
                       float* da3);
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
                              const void* stats, const float* dy, void* scratch, float* dw);
+
+// ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
+// off: the codes are compared bit for bit with an IEEE fp32 evaluation.
+// floor() limited to +-2^24 so that the integer conversion is defined for any input.
+__device__ inline float limit_floor(float u) {
+  const float lim = 16777216.0f;
+  u = floorf(u);
+  u = (u >= -lim) ? u : -lim;  // NaN -> -lim
+  u = (u > lim) ? lim : u;
+  return u;
+}
+
+// Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).
+template <int K>
+__device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
+  const float u = limit_floor(a2 * cq);
+  int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
+  v = v < 0 ? 0 : v;
+  v = v > (1 << K) - 1 ? (1 << K) - 1 : v;
+  return (uint32_t)v;
+}
+
+// Eq. 10 for one code.
+template <int K>
+__device__ inline float dequant(uint32_t q, float step, int32_t fb) {
+  const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
+  const float t = (float)j + 0.5f;
+  return step * t;
+}
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));

@@ -109,33 +109,6 @@ __device__ inline void store_vec(float* __restrict__ p, const float (&v)[VEC]) {
   }
 }
 
-// floor() limited to +-2^24 so that the integer conversion is defined for any input.
-__device__ inline float limit_floor(float u) {
-  const float lim = 16777216.0f;
-  u = floorf(u);
-  u = (u >= -lim) ? u : -lim;  // NaN -> -lim
-  u = (u > lim) ? lim : u;
-  return u;
-}
-
-// Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).
-template <int K>
-__device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
-  const float u = limit_floor(a2 * cq);
-  int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
-  v = v < 0 ? 0 : v;
-  v = v > (1 << K) - 1 ? (1 << K) - 1 : v;
-  return (uint32_t)v;
-}
-
-// Eq. 10 for one code.
-template <int K>
-__device__ inline float dequant(uint32_t q, float step, int32_t fb) {
-  const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
-  const float t = (float)j + 0.5f;
-  return step * t;
-}
-
 // Packed word of VEC codes: K*VEC bits (32 or 16).
 template <int K, int VEC>
 struct PackedWord {

@@ -16,6 +16,9 @@
 
 #include "abl_internal.h"
 
+// the fused forward evaluates Eq. 1-3 and Eq. 9 here: one rounded fp32 operation at a time
+#pragma clang fp contract(off)
+
 namespace abl {
 namespace {
 
@@ -35,6 +38,7 @@ struct HaloPlan {
   int a_dw, a_dh;                 // 64 patch pixels further = a_dh rows + a_dw cols
   int m_dw, m_dh;                 // 16 tile pixels further = m_dh rows + m_dw cols
   unsigned lds_bytes;
+  int pack_pad;                   // zero bytes after the last code (fused forward only)
 };
 
 // (ti, h, w) position inside a tile or patch, advanced without divisions.
@@ -61,10 +65,15 @@ struct Pos {
 // consecutive k of one output channel) for the next tap straight from L2 while the current
 // tap is contracted.  With more than 16 input channels the patch buffer is doubled and the
 // next chunk's global loads are in flight during the MFMAs.
-template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16>
+// FUSE = 0: `in` is the conv input.  FUSE = K (4 or 8, forward only): `in` is the layer input x;
+// BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied while the patch is staged, and the
+// block that owns a pixel also writes its K-bit codes (Eq. 9).
+template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16, int FUSE>
 __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
-                                                             float* out, ConvGeom g, HaloPlan p) {
+                                                             float* out, ConvGeom g, HaloPlan p,
+                                                             const float* __restrict__ stats,
+                                                             void* __restrict__ packed) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int WAVES_M = 4 / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
@@ -98,6 +107,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // global offsets (in floats, channel 0) of the patch elements this thread stages; -1 = zero fill
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AMAX];
+  bool own[AMAX];  // fused forward: this block writes the codes of the element
   {
     Pos q;
     q.init(tid >> 2, p.HW, p.HH);
@@ -108,9 +118,12 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       const int n = img0 + q.ti, hi = oh + q.h, wi = ow + q.w;
       if (idx < totalA && n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi)
         goff[j] = ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3);
+      own[j] = FUSE != 0 && goff[j] >= 0 && n0 == 0 && hi >= h0 && hi < h0 + p.TH && wi >= w0 && wi < w0 + p.TW;
       q.advance(p.a_dw, p.a_dh, p.HW, p.HH);
     }
   }
+  if (FUSE != 0 && blockIdx.x == 0 && tid < p.pack_pad)  // zero the tail of the last 128-byte row
+    static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + tid] = 0;
 
   // LDS base of this lane's pixel in each of the wave's M-tiles
   int base[MT];
@@ -133,6 +146,10 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   float4 ra[AMAX];
+  // per-channel constants of the 4 channels this thread stages (fused forward)
+  float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
+  int4 k_fb;
+  int k_c0 = 0;
   auto fetch_a = [&](int c0) __attribute__((always_inline)) {
     // unconditional loads (lanes outside the image read element 0 and are zeroed): no branch
     // separates the loads, so all of them are in flight together
@@ -142,12 +159,52 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       const float4 v = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
       ra[j] = keep_if(ok, v);
     }
+    if (FUSE != 0) {
+      const int c = c0 + 4 * (tid & 3);
+      k_mean = *reinterpret_cast<const float4*>(stats + P_MEAN * g.Cin + c);
+      k_rstd = *reinterpret_cast<const float4*>(stats + P_RSTD * g.Cin + c);
+      k_gamma = *reinterpret_cast<const float4*>(stats + P_GAMMA * g.Cin + c);
+      k_beta = *reinterpret_cast<const float4*>(stats + P_BETA * g.Cin + c);
+      k_cq = *reinterpret_cast<const float4*>(stats + P_CQ * g.Cin + c);
+      k_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * g.Cin + c);
+      k_c0 = c0;
+    }
   };
   auto stage_a = [&](float* tileA) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < AMAX; ++j) {
       const int idx = tid + kThreads * j;
-      if (idx < totalA) *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = ra[j];
+      if (idx < totalA) {
+        float4 v = ra[j];
+        if (FUSE != 0) {
+          const bool ok = goff[j] >= 0;
+          const float xs[4] = {v.x, v.y, v.z, v.w};
+          const float mean[4] = {k_mean.x, k_mean.y, k_mean.z, k_mean.w};
+          const float rstd[4] = {k_rstd.x, k_rstd.y, k_rstd.z, k_rstd.w};
+          const float gm[4] = {k_gamma.x, k_gamma.y, k_gamma.z, k_gamma.w};
+          const float bt[4] = {k_beta.x, k_beta.y, k_beta.z, k_beta.w};
+          const float cq[4] = {k_cq.x, k_cq.y, k_cq.z, k_cq.w};
+          const int32_t fb[4] = {k_fb.x, k_fb.y, k_fb.z, k_fb.w};
+          float a3[4];
+          uint32_t word = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float d = xs[e] - mean[e];
+            const float a1 = d * rstd[e];  // Eq. 1
+            const float t = gm[e] * a1;
+            const float a2 = t + bt[e];    // Eq. 2
+            a3[e] = (ok && a2 > 0.0f) ? a2 : 0.0f;  // Eq. 3; zero padding applies to A3
+            word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2, cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+          }
+          v = make_float4(a3[0], a3[1], a3[2], a3[3]);
+          if (own[j]) {
+            const int64_t e0 = (int64_t)goff[j] + k_c0;  // flat element index of the first of 4 codes
+            if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
+            else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+          }
+        }
+        *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = v;
+      }
     }
   };
   // B fragment of this lane for chunk c0, tap t: k = c0 + 4*lk .. +3, column = its channel
@@ -323,34 +380,33 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   return p.lds_bytes <= 64 * 1024 && p.TI * p.HH * p.HW * 4 <= AMAX * kThreads && p.TH > 0;
 }
 
-template <int MODE, int V>
+template <int MODE, int V, int FUSE>
 void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
-                    const float* skip, float* out) {
+                    const float* skip, float* out, const float* stats, void* packed) {
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * cdiv(Ng, p.bn));
   const bool unroll = g.R == 3 && g.S == 3 && var.mt * var.nt <= 4;
-  auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true>
-                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false>)
-                     : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true>
-                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false>);
-  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p);
+  auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true, FUSE>
+                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
+                     : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE>
+                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE>);
+  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed);
 }
 
-template <int MODE>
+template <int MODE, int FUSE>
 void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
-                 const float* skip, float* out) {
+                 const float* skip, float* out, const float* stats, void* packed) {
   switch (p.variant) {
-    case 0: launch_variant<MODE, 0>(st, g, p, bf16, in, w, skip, out); break;
-    case 1: launch_variant<MODE, 1>(st, g, p, bf16, in, w, skip, out); break;
-    case 2: launch_variant<MODE, 2>(st, g, p, bf16, in, w, skip, out); break;
-    case 3: launch_variant<MODE, 3>(st, g, p, bf16, in, w, skip, out); break;
-    case 4: launch_variant<MODE, 4>(st, g, p, bf16, in, w, skip, out); break;
-    case 5: launch_variant<MODE, 5>(st, g, p, bf16, in, w, skip, out); break;
-    default: launch_variant<MODE, 6>(st, g, p, bf16, in, w, skip, out); break;
+    case 0: launch_variant<MODE, 0, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 1: launch_variant<MODE, 1, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 2: launch_variant<MODE, 2, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 3: launch_variant<MODE, 3, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 4: launch_variant<MODE, 4, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 5: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    default: launch_variant<MODE, 6, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
   }
 }
-
 
 // ------------------------------------------------------------------------------------------
 // Weight gradient (Eq. 5) of a stride-1 RxS convolution from the packed activation, all taps
@@ -579,8 +635,25 @@ int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, con
                      const float* skip, float* out) {
   HaloPlan p;
   if (!make_plan(g, mode, p)) return ABL_ERR_SHAPE;
-  if (mode == 0) launch_mode<0>(st, g, p, bf16, in, w, skip, out);
-  else launch_mode<1>(st, g, p, bf16, in, w, nullptr, out);
+  p.pack_pad = 0;
+  if (mode == 0) launch_mode<0, 0>(st, g, p, bf16, in, w, skip, out, nullptr, nullptr);
+  else launch_mode<1, 0>(st, g, p, bf16, in, w, nullptr, out, nullptr, nullptr);
+  return hip_status();
+}
+
+bool halo_fused_supported(const ConvGeom& g) {
+  return halo_conv_supported(g) && g.Ho == g.H && g.Wo == g.W;
+}
+
+int launch_halo_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x,
+                          const void* stats, const float* w, const float* skip, float* y, void* packed) {
+  HaloPlan p;
+  if (!make_plan(g, 0, p)) return ABL_ERR_SHAPE;
+  const int64_t raw = ((int64_t)g.N * g.H * g.W * g.Cin * K + 7) / 8;
+  p.pack_pad = (int)((raw + 127) / 128 * 128 - raw);
+  const float* sp = static_cast<const float*>(stats);
+  if (K == 4) launch_mode<0, 4>(st, g, p, bf16, x, w, skip, y, sp, packed);
+  else launch_mode<0, 8>(st, g, p, bf16, x, w, skip, y, sp, packed);
   return hip_status();
 }
 

@@ -69,7 +69,10 @@ def test_full_size_layer(G, oracle, case, K):
     x, w, gamma, beta, dy = synth.draw_layer(s, synth.DEFAULT_SEED, xd, aff)
     run = G.LayerRun(s, K)
     y = run.forward(x, w, gamma, beta)
-    a3_gpu = run.scratch[: 4 * s.E].view(torch.float32).cpu().numpy().reshape(x.shape)
+    # A3 itself only exists inside the layer call (in LDS or in the workspace); the stage entry
+    # point exposes it, and must produce the same packed bytes as the layer call
+    a3_gpu, packed_stage = G.run_bn_relu_pack(x, run.stats, K)
+    assert packed_stage.tobytes() == run.packed.cpu().numpy().tobytes()
 
     # statistics, A3 and codes: everything, bit for bit
     mean, var = o.bn_stats(x)
