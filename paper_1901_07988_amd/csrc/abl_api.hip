@@ -156,9 +156,52 @@ int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, uint32_t flag
                                   scratch, dW);
 }
 
+}  // extern "C"
+
+namespace {
+
 // Forward: statistics -> (normalise, ReLU, quantize, pack) -> convolution.  A3 lives in the
 // workspace only until the convolution has read it (Sec. 3.2: full-precision intermediates
-// are overwritten as soon as they have been used).
+// are overwritten as soon as they have been used); 'same' stride-1 convolutions do not even
+// write it.
+//   in_partial / in_nb : first-pass sums of x's statistics left by the producer of x (nullable)
+//   out_partial        : where to leave the first-pass sums of y's statistics (nullable);
+//                        *out_nb = number of partial rows written, 0 if this layer could not
+int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, const float* x, const float* W,
+                 const float* gamma, const float* beta, const float* skip, void* scratch, float* y,
+                 void* packed, void* stats, const double* in_partial, int in_nb, double* out_partial,
+                 int* out_nb) {
+  const int64_t M = rows_of(*s);
+  const size_t act = up256((size_t)M * s->Cin * sizeof(float));
+  float* a3 = static_cast<float*>(scratch);
+  void* red = static_cast<char*>(scratch) + act;
+  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  if (out_nb != nullptr) *out_nb = 0;
+  if (in_partial != nullptr && in_nb > 0) {
+    if (int e = launch_bn_stats_finalize(st, in_partial, in_nb, nullptr, M, s->Cin, gamma, beta, K, stats)) return e;
+  } else {
+    if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
+  }
+  const ConvGeom g = geom_of(*s);
+  // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
+  // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
+  // overwrite input pixels that a neighbouring block has not staged yet.)
+  if (halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
+    const int tiles = halo_tile_count(g, 0);
+    const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
+    if (int e = launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed, want ? out_partial : nullptr))
+      return e;
+    if (want && out_nb != nullptr) *out_nb = tiles;
+    return ABL_OK;
+  }
+  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
+  return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
+}
+
+}  // namespace
+
+extern "C" {
+
 int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const float* W,
                 const float* gamma, const float* beta, const float* skip, void* scratch,
                 size_t scratch_bytes, float* y, void* packed, void* stats) {
@@ -169,21 +212,8 @@ int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const f
       bad_ptr(packed) || bad_ptr(stats) || (skip != nullptr && !aligned16(skip)))
     return ABL_ERR_ARG;
   if (scratch_bytes < abl_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
-  hipStream_t st = (hipStream_t)stream;
-  const int64_t M = rows_of(*s);
-  const size_t act = up256((size_t)M * s->Cin * sizeof(float));
-  float* a3 = static_cast<float*>(scratch);
-  void* red = static_cast<char*>(scratch) + act;
-  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
-  if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
-  const ConvGeom g = geom_of(*s);
-  // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
-  // patch: x is read once and A3 never reaches memory.  y may still alias x only through the
-  // two-kernel path, so the fused kernel is used when they are distinct buffers.
-  if (halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y))
-    return launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed);
-  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
-  return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
+  return forward_impl((hipStream_t)stream, s, K, flags, x, W, gamma, beta, skip, scratch, y, packed, stats,
+                      nullptr, 0, nullptr, nullptr);
 }
 
 // Backward: dgrad (exact) and wgrad (from the packed copy) consume dy; then the BN/ReLU
@@ -207,13 +237,33 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   void* red = static_cast<char*>(scratch) + act;
   void* wpart = static_cast<char*>(scratch) + act + redb;
   const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  const bool accum = (flags & ABL_ACCUM_DX) != 0;
+  const ConvGeom g = geom_of(*s);
+  // Stride-1 convolutions with a filter larger than 1x1 take the Eq. 6-7 sums in the epilogue of
+  // the dgrad kernel (dA3 is still in registers there), which saves the reduce pass over dA3.
+  const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
+  if (tiles > 0 && tiles <= kMaxPartialBlocks) {
+    if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))
+      return e;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta);
+  }
   if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
   if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
-  return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, (flags & ABL_ACCUM_DX) != 0, red, dx, dgamma,
-                       dbeta);
+  return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
 }
 
 // ---- residual stack ---------------------------------------------------------------------
+
+// Workspace of a stack: [cross-layer statistics partials | the largest per-layer workspace].
+static size_t stack_xpart_bytes(const abl_layer* layers, int32_t L) {
+  int cmax = 1;
+  for (int i = 0; i < L; ++i) {
+    if (layers[i].shape.Cin > cmax) cmax = layers[i].shape.Cin;
+    if (layers[i].shape.Cout > cmax) cmax = layers[i].shape.Cout;
+  }
+  return up256((size_t)kMaxPartialBlocks * 2 * (size_t)cmax * sizeof(double));
+}
 
 size_t abl_stack_scratch_bytes(const abl_layer* layers, int32_t L, int K) {
   if (layers == nullptr || L < 1) return 0;
@@ -223,7 +273,7 @@ size_t abl_stack_scratch_bytes(const abl_layer* layers, int32_t L, int K) {
     if (b == 0) return 0;
     if (b > m) m = b;
   }
-  return m;
+  return stack_xpart_bytes(layers, L) + m;
 }
 
 size_t abl_stack_buffer_bytes(const abl_layer* layers, int32_t L) {
@@ -299,6 +349,10 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
                       size_t scratch_bytes) {
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  const size_t xbytes = stack_xpart_bytes(layers, L);
+  double* xpart = static_cast<double*>(scratch);
+  void* lscratch = static_cast<char*>(scratch) + xbytes;
+  int in_nb = 0;
   for (int i = 0; i < L; ++i) {
     const abl_layer& l = layers[i];
     const GroupInfo gi = group_info(layers, L, skip_every, i);
@@ -310,9 +364,16 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
       y = gi.last ? buf_s : buf_t;
       if (gi.last && gi.shortcut) skip = buf_s;
     }
-    if (int e = abl_forward(stream, &l.shape, K, flags, x, l.W, l.gamma, l.beta, skip, scratch, scratch_bytes, y,
-                            l.packed, l.stats))
+    if (bad_ptr(l.W) || bad_ptr(l.gamma) || bad_ptr(l.beta) || bad_ptr(l.packed) || bad_ptr(l.stats))
+      return ABL_ERR_ARG;
+    // layer i's convolution leaves the first-pass statistics of its output (= layer i+1's input)
+    // in `xpart` when it can; layer i+1 then only runs the finalize kernel
+    int out_nb = 0;
+    if (int e = forward_impl((hipStream_t)stream, &l.shape, K, flags, x, l.W, l.gamma, l.beta, skip, lscratch, y,
+                             l.packed, l.stats, in_nb > 0 ? xpart : nullptr, in_nb,
+                             i + 1 < L ? xpart : nullptr, &out_nb))
       return e;
+    in_nb = out_nb;
   }
   return ABL_OK;
 }
@@ -326,6 +387,7 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
                        size_t scratch_bytes) {
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  const size_t xbytes = stack_xpart_bytes(layers, L);
   for (int i = L - 1; i >= 0; --i) {
     const abl_layer& l = layers[i];
     if (bad_ptr(l.dW) || bad_ptr(l.dgamma) || bad_ptr(l.dbeta)) return ABL_ERR_ARG;
@@ -338,8 +400,9 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
       dx = gi.first ? buf_s : buf_t;
       if (gi.first && gi.shortcut) f |= ABL_ACCUM_DX;
     }
-    if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W, scratch, scratch_bytes, dx,
-                             l.dW, l.dgamma, l.dbeta))
+    if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W,
+                             static_cast<char*>(scratch) + xbytes, scratch_bytes - xbytes, dx, l.dW, l.dgamma,
+                             l.dbeta))
       return e;
   }
   return ABL_OK;

@@ -12,7 +12,7 @@ namespace abl {
 // Planes of the per-channel `stats` block, each C 4-byte values.
 enum StatPlane { P_MEAN = 0, P_VAR, P_RSTD, P_GAMMA, P_BETA, P_CQ, P_STEP, P_FB };
 
-constexpr int kMaxPartialBlocks = 512;   // upper bound on per-block reduction partials
+constexpr int kMaxPartialBlocks = 512;  // upper bound on per-block reduction partials
 
 // Bytes of partial-sum workspace for the per-channel reductions over [M,C].
 size_t bn_partial_bytes(int64_t M, int C);
@@ -28,6 +28,13 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
                   float* a2t);
 int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                   int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta);
+// The second halves of the two reductions, for partial sums produced elsewhere (conv epilogues).
+size_t bn_means_offset(int C);
+int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, const float* shift_row, int64_t M,
+                             int C, const float* gamma, const float* beta, int K, void* stats);
+int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
+                         int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
+                         float* dbeta);
 
 // Convolution geometry passed to the kernels by value.
 struct ConvGeom {
@@ -53,8 +60,17 @@ int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, con
 // Forward with Eq. 1-3 and Eq. 9 applied while the input patch is staged: reads x, writes y and
 // the packed codes; A3 never reaches memory.  Supported for 'same' stride-1 convolutions.
 bool halo_fused_supported(const ConvGeom& g);
+// out_partial (nullable): [tiles][2][Cout] doubles = per-tile sum(y), sum(y^2) of the output,
+// the first pass of the next layer's statistics.  halo_tile_count gives `tiles` (0: unsupported).
+int halo_tile_count(const ConvGeom& g, int mode);
 int launch_halo_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x,
-                          const void* stats, const float* w, const float* skip, float* y, void* packed);
+                          const void* stats, const float* w, const float* skip, float* y, void* packed,
+                          double* out_partial);
+// Gradient to the conv input with the first pass of the BN backward (Eq. 6-7 sums from the
+// layer's packed codes) in the epilogue: partial = [tiles][2][Cin] doubles.
+int launch_halo_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy,
+                             const float* w, const void* packed, const void* stats, float* da3,
+                             double* partial);
 
 // Weight gradient of stride-1 3x3 convolutions from the packed activation, all taps per pass.
 // halo_wgrad_partial_bytes returns 0 when the shape is not supported.

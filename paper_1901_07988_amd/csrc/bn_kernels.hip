@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kFinThreads) void stats_finalize_kernel(const doubl
   double t[2];
   reduce_partials(partial, nb, C, t, sm);
   if (c >= C || threadIdx.x >= 16) return;
-  const double k = (double)x[c];
+  const double k = x != nullptr ? (double)x[c] : 0.0;  // the shift the partial sums were taken with
   const double mk = t[0] / (double)M;
   double var = t[1] / (double)M - mk * mk;
   var = var > 0.0 ? var : 0.0;
@@ -631,17 +631,17 @@ inline dim3 grid_of(const RowGeom& g) { return dim3(g.gridX, g.gridY, 1); }
 
 }  // namespace
 
+// Room for kMaxPartialBlocks partial rows (the reduce kernels of this file use at most that
+// many blocks, and so do the convolution epilogues that produce the same partial sums) plus the
+// two per-channel means of the BN backward.
 size_t bn_partial_bytes(int64_t M, int C) {
-  int gy = 1;
-  for (int vec : {1, 4, 8}) {
-    if (C % vec) continue;
-    const RowGeom g = make_geom(M, C, vec, true);
-    if (g.gridY > gy) gy = g.gridY;
-  }
-  const size_t partial = (size_t)gy * 2 * (size_t)C * sizeof(double);
+  (void)M;
+  const size_t partial = (size_t)kMaxPartialBlocks * 2 * (size_t)C * sizeof(double);
   const size_t means = ((size_t)2 * C * sizeof(float) + 255) / 256 * 256;
-  return (partial + 255) / 256 * 256 + means;
+  return partial + means;
 }
+
+size_t bn_means_offset(int C) { return (size_t)kMaxPartialBlocks * 2 * (size_t)C * sizeof(double); }
 
 int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const float* gamma,
                     const float* beta, int K, void* scratch, void* stats) {
@@ -652,7 +652,14 @@ int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const floa
     stats_partial_kernel<4><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
   else
     stats_partial_kernel<1><<<grid_of(g), kThreads, 0, st>>>(x, M, C, g, partial);
-  stats_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, g.gridY, x, M, C, gamma, beta, K,
+  return launch_bn_stats_finalize(st, partial, g.gridY, x, M, C, gamma, beta, K, stats);
+}
+
+// Second pass of the statistics from `nb` partial rows [nb][2][C]; `shift_row` is the row whose
+// values the sums were shifted by (nullptr: no shift).
+int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, const float* shift_row, int64_t M,
+                             int C, const float* gamma, const float* beta, int K, void* stats) {
+  stats_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, nb, shift_row, M, C, gamma, beta, K,
                                                             static_cast<float*>(stats));
   return hip_status();
 }
@@ -735,8 +742,6 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
   double* partial = static_cast<double*>(scratch);
   const int vec = fast_vec(K, C);
   const RowGeom gr = make_geom(M, C, vec ? vec : 1, true);
-  const size_t partial_bytes = ((size_t)gr.gridY * 2 * C * sizeof(double) + 255) / 256 * 256;
-  float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + partial_bytes);
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
   if (vec == 0) {
     if (K == 4)
@@ -750,7 +755,21 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
   } else {
     bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
   }
-  bwd_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, gr.gridY, M, C, sp, dgamma, dbeta, means);
+  if (hipGetLastError() != hipSuccess) return ABL_ERR_HIP;
+  return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta);
+}
+
+// Eq. 7 totals and Eq. 8 from `nb` partial rows [nb][2][C] of (sum dA2, sum A1~ dA2) at the
+// start of `scratch`: finalize kernel, then the apply pass.
+int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
+                         int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
+                         float* dbeta) {
+  const float* sp = static_cast<const float*>(stats);
+  const double* partial = static_cast<const double*>(scratch);
+  float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + bn_means_offset(C));
+  const uint8_t* pk = static_cast<const uint8_t*>(packed);
+  const int vec = fast_vec(K, C);
+  bwd_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means);
   if (vec == 0) {
     const int64_t E = M * C;
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);

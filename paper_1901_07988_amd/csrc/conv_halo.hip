@@ -41,6 +41,16 @@ struct HaloPlan {
   int pack_pad;                   // zero bytes after the last code (fused forward only)
 };
 
+// Optional per-channel reduction in the epilogue; one partial row [2][channels] per pixel tile.
+//   forward (MODE 0): sum(y), sum(y^2) of the output          -> the next layer's Eq. 1 statistics
+//   dgrad   (MODE 1): sum(dA2), sum(A1~ dA2) with the ReLU mask and A1~ rebuilt from the layer's
+//                     K-bit codes (Eq. 6, Eq. 7)               -> first pass of the BN backward
+struct EpiReduce {
+  double* partial;        // nullptr: no reduction
+  const uint8_t* codes;   // dgrad only: packed A2 of the layer
+  int K;
+};
+
 // (ti, h, w) position inside a tile or patch, advanced without divisions.
 struct Pos {
   int w, h, ti;
@@ -73,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
                                                              const float* __restrict__ wgt, const float* skip,
                                                              float* out, ConvGeom g, HaloPlan p,
                                                              const float* __restrict__ stats,
-                                                             void* __restrict__ packed) {
+                                                             void* __restrict__ packed, EpiReduce epi) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int WAVES_M = 4 / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
@@ -94,7 +104,8 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // different output-channel blocks run there back to back
   const int nblk_n = (Ng + BN - 1) / BN;
   const int slot = blockIdx.x >> 3;
-  int b = (slot / nblk_n) * 8 + (blockIdx.x & 7);
+  const int tile_id = (slot / nblk_n) * 8 + (blockIdx.x & 7);
+  int b = tile_id;
   if (b >= p.tiles_i * p.tiles_h * p.tiles_w) return;
   const int tw_i = b % p.tiles_w; b /= p.tiles_w;
   const int th_i = b % p.tiles_h; b /= p.tiles_h;
@@ -262,6 +273,23 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 
   // epilogue: the lane holds pixels 4*lk .. 4*lk+3 of each M-tile, channel li of each N-tile.
   // Output offsets first, then the shortcut values in one batch, then the stores.
+  const bool reduce = epi.partial != nullptr;
+  double s1[NT], s2[NT];
+  float r_step[NT], r_beta[NT], r_ig[NT];
+  int32_t r_fb[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    s1[j] = s2[j] = 0.0;
+    r_step[j] = r_beta[j] = r_ig[j] = 0.f;
+    r_fb[j] = 0;
+    const int c = n0 + wn0 + 16 * j + li;
+    if (MODE == 1 && reduce && c < Ng) {
+      r_step[j] = stats[P_STEP * Ng + c];
+      r_beta[j] = stats[P_BETA * Ng + c];
+      r_ig[j] = 1.0f / stats[P_GAMMA * Ng + c];
+      r_fb[j] = reinterpret_cast<const int32_t*>(stats)[P_FB * Ng + c];
+    }
+  }
   Pos e;
   int m = wave_m * MT * 16 + 4 * lk;
   e.init(m, p.TW, p.TH);
@@ -290,6 +318,41 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 #pragma unroll
         for (int j = 0; j < NT; ++j) acc[i][j][rr] += sv[rr][j];
     }
+    if (reduce) {
+      if (MODE == 0) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) {
+              const double v = (double)acc[i][j][rr];
+              s1[j] += v;
+              s2[j] += v * v;
+            }
+      } else {
+        uint32_t code[4][NT];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+          for (int j = 0; j < NT; ++j) {
+            const bool ok = off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng;
+            const int64_t el = ok ? off[rr] + 16 * j : 0;
+            code[rr][j] = epi.K == 4 ? (epi.codes[el >> 1] >> ((el & 1) * 4)) & 15u : epi.codes[el];
+          }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) {
+              const int32_t jj = (int32_t)code[rr][j] - (1 << (epi.K - 1)) + r_fb[j];
+              const float a2t = r_step[j] * ((float)jj + 0.5f);               // Eq. 10
+              const float da2 = a2t > 0.0f ? acc[i][j][rr] : 0.0f;           // Eq. 6
+              const float a1t = (a2t - r_beta[j]) * r_ig[j];                 // inverse of Eq. 2
+              s1[j] += (double)da2;
+              s2[j] += (double)a1t * (double)da2;
+            }
+      }
+    }
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
@@ -297,6 +360,26 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) out[off[rr] + 16 * j] = acc[i][j][rr];
     m += 16;
     e.advance(p.m_dw, p.m_dh, p.TW, p.TH);
+  }
+  if (reduce) {
+    // the lane groups and the waves that share a channel are summed in a fixed order through LDS
+    constexpr int R = WAVES_M * 4;
+    __syncthreads();  // every wave is done with the patch
+    double* red = reinterpret_cast<double*>(lds);  // [2][R][BN]
+    const int rs = wave_m * 4 + lk;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      red[(0 * R + rs) * BN + wn0 + 16 * j + li] = s1[j];
+      red[(1 * R + rs) * BN + wn0 + 16 * j + li] = s2[j];
+    }
+    __syncthreads();
+    for (int c = tid; c < 2 * BN; c += kThreads) {
+      const int qv = c / BN, ch = c % BN;
+      double t = 0.0;
+#pragma unroll
+      for (int k = 0; k < R; ++k) t += red[(qv * R + k) * BN + ch];
+      if (n0 + ch < Ng) epi.partial[((int64_t)tile_id * 2 + qv) * Ng + n0 + ch] = t;
+    }
   }
 }
 
@@ -382,7 +465,7 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
 
 template <int MODE, int V, int FUSE>
 void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
-                    const float* skip, float* out, const float* stats, void* packed) {
+                    const float* skip, float* out, const float* stats, void* packed, const EpiReduce& epi) {
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * cdiv(Ng, p.bn));
@@ -391,20 +474,20 @@ void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool b
                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
                      : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE>
                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE>);
-  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed);
+  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
 }
 
 template <int MODE, int FUSE>
 void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16, const float* in, const float* w,
-                 const float* skip, float* out, const float* stats, void* packed) {
+                 const float* skip, float* out, const float* stats, void* packed, const EpiReduce& epi) {
   switch (p.variant) {
-    case 0: launch_variant<MODE, 0, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    case 1: launch_variant<MODE, 1, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    case 2: launch_variant<MODE, 2, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    case 3: launch_variant<MODE, 3, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    case 4: launch_variant<MODE, 4, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    case 5: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
-    default: launch_variant<MODE, 6, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed); break;
+    case 0: launch_variant<MODE, 0, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 1: launch_variant<MODE, 1, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 2: launch_variant<MODE, 2, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 3: launch_variant<MODE, 3, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 4: launch_variant<MODE, 4, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 5: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    default: launch_variant<MODE, 6, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
   }
 }
 
@@ -636,8 +719,9 @@ int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, con
   HaloPlan p;
   if (!make_plan(g, mode, p)) return ABL_ERR_SHAPE;
   p.pack_pad = 0;
-  if (mode == 0) launch_mode<0, 0>(st, g, p, bf16, in, w, skip, out, nullptr, nullptr);
-  else launch_mode<1, 0>(st, g, p, bf16, in, w, nullptr, out, nullptr, nullptr);
+  const EpiReduce none{nullptr, nullptr, 0};
+  if (mode == 0) launch_mode<0, 0>(st, g, p, bf16, in, w, skip, out, nullptr, nullptr, none);
+  else launch_mode<1, 0>(st, g, p, bf16, in, w, nullptr, out, nullptr, nullptr, none);
   return hip_status();
 }
 
@@ -645,15 +729,34 @@ bool halo_fused_supported(const ConvGeom& g) {
   return halo_conv_supported(g) && g.Ho == g.H && g.Wo == g.W;
 }
 
+int halo_tile_count(const ConvGeom& g, int mode) {
+  HaloPlan p;
+  if (!make_plan(g, mode, p)) return 0;
+  return p.tiles_i * p.tiles_h * p.tiles_w;
+}
+
 int launch_halo_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x,
-                          const void* stats, const float* w, const float* skip, float* y, void* packed) {
+                          const void* stats, const float* w, const float* skip, float* y, void* packed,
+                          double* out_partial) {
   HaloPlan p;
   if (!make_plan(g, 0, p)) return ABL_ERR_SHAPE;
   const int64_t raw = ((int64_t)g.N * g.H * g.W * g.Cin * K + 7) / 8;
   p.pack_pad = (int)((raw + 127) / 128 * 128 - raw);
   const float* sp = static_cast<const float*>(stats);
-  if (K == 4) launch_mode<0, 4>(st, g, p, bf16, x, w, skip, y, sp, packed);
-  else launch_mode<0, 8>(st, g, p, bf16, x, w, skip, y, sp, packed);
+  const EpiReduce epi{out_partial, nullptr, 0};
+  if (K == 4) launch_mode<0, 4>(st, g, p, bf16, x, w, skip, y, sp, packed, epi);
+  else launch_mode<0, 8>(st, g, p, bf16, x, w, skip, y, sp, packed, epi);
+  return hip_status();
+}
+
+int launch_halo_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy,
+                             const float* w, const void* packed, const void* stats, float* da3,
+                             double* partial) {
+  HaloPlan p;
+  if (!make_plan(g, 1, p)) return ABL_ERR_SHAPE;
+  p.pack_pad = 0;
+  const EpiReduce epi{partial, static_cast<const uint8_t*>(packed), K};
+  launch_mode<1, 0>(st, g, p, bf16, dy, w, nullptr, da3, static_cast<const float*>(stats), nullptr, epi);
   return hip_status();
 }
 
