@@ -58,9 +58,12 @@ enum {
 
 enum {
   ABL_ACCUM_DX = 1u << 0, /* abl_backward / abl_bn_bwd: dx += result (residual-stream gradient, Sec. 3.4) */
-  ABL_MATH_BF16 = 1u << 1 /* contractions (Eq. 4, Eq. 5): operands rounded to bf16 on the way into the
+  ABL_MATH_BF16 = 1u << 1, /* contractions (Eq. 4, Eq. 5): operands rounded to bf16 on the way into the
                              matrix cores, fp32 accumulation; everything else (statistics, codes,
                              BN forward/backward) is unchanged.  Default: fp32 operands. */
+  ABL_XIN_F32 = 1u << 3,   /* abl_postact_backward: xin is the exact fp32 conv input            */
+  ABL_XIN_PACKED = 1u << 4 /* abl_postact_backward: xin / xin_stats are the previous layer's
+                              packed store and stats (its ReLU output is rebuilt on the fly)   */
 };
 
 #define ABL_BN_EPS 1e-5f
@@ -143,6 +146,32 @@ size_t abl_wgrad_scratch_bytes(const abl_shape* shape);
 int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, uint32_t flags, const void* packed,
                           const void* stats, const float* dy, void* scratch,
                           size_t scratch_bytes, float* dW);
+
+/* ---- the layer grouped as conv -> BN -> ReLU ----
+ * The paper groups a convolution with the non-linearities that PRECEDE it (Sec. 3.1) and that
+ * is what abl_forward / abl_backward implement.  These entry points run the same kernels with
+ * the convolution first:  y = ReLU(gamma * BN(conv(x, W)) + beta).  The BN tensor is then the
+ * conv OUTPUT: M' = N*Ho*Wo rows of Cout channels (gamma, beta, stats, packed are sized for it),
+ * and what is packed is still the pre-ReLU BN output A2 (Sec. 3.2).  For plain chains without
+ * shortcuts.
+ *   forward : x [N,H,W,Cin], W, gamma/beta [Cout] -> y [N,Ho,Wo,Cout], packed, stats
+ *   backward: dy [N,Ho,Wo,Cout] -> dx [N,H,W,Cin] (NULL: not wanted), dW, dgamma/dbeta [Cout].
+ *             Eq. 5's weight gradient needs the conv input, which this layer does not store:
+ *             ABL_XIN_F32    xin = the exact fp32 input (bottom of a network);
+ *             ABL_XIN_PACKED xin, xin_stats = packed store and stats of the previous layer of
+ *                            the chain (its channel count is Cin, its resolution H x W, same K);
+ *                            the input ReLU(dequantized A2) is rebuilt on the fly (Eq. 10, Eq. 3).
+ * flags: ABL_MATH_BF16, and for the backward exactly one of ABL_XIN_F32 / ABL_XIN_PACKED. */
+size_t abl_postact_packed_bytes(const abl_shape* shape, int K);
+size_t abl_postact_stats_bytes(const abl_shape* shape);
+size_t abl_postact_scratch_bytes(const abl_shape* shape, int K);
+int abl_postact_forward(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                        const float* x, const float* W, const float* gamma, const float* beta,
+                        void* scratch, size_t scratch_bytes, float* y, void* packed, void* stats);
+int abl_postact_backward(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                         const void* packed, const void* stats, const float* dy, const float* W,
+                         const void* xin, const void* xin_stats, void* scratch, size_t scratch_bytes,
+                         float* dx, float* dW, float* dgamma, float* dbeta);
 
 /* ---- residual stack (Sec. 3.4; Fig. 2; Sec. 4 first paragraph) ----
  * A chain of layers with an identity shortcut around every group of `skip_every`

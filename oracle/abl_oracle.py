@@ -413,3 +413,38 @@ def conv_wgrad_at(a3, dy, s: Shape, entries):
         g = np.asarray(dy[:, ho[hv]][:, :, wo[xv], :], np.float64)         # [N, ho', wo', Cout]
         out[i] = np.einsum("nhw,nhwc->c", a, g)
     return out
+
+
+# --------------------------------------------------------------------------- conv -> BN -> ReLU grouping
+# The paper groups a convolution with the non-linearities that precede it (Sec. 3.1).  The same
+# three operations grouped with the convolution FIRST give y = ReLU(gamma * BN(conv(x)) + beta);
+# what is stored is still the K-bit copy of the pre-ReLU BN output A2 (Sec. 3.2), which now has
+# the conv output's shape.  A chain of such layers is conv_0, then pre-activation layers, then a
+# trailing BN-ReLU - the CPU tests assert that identity bit for bit.
+def postact_forward(x, w, gamma, beta, K, s: Shape, dtype=np.float32, eps=EPS, keep=False):
+    """Returns (y, Saved); Saved.shape describes the BN tensor [N,Ho,Wo,Cout]."""
+    t = conv_fwd(x, w, s, dtype)                                 # Eq. 4
+    mean, var = bn_stats(t, dtype)
+    rstd = bn_rstd(var, eps, dtype)
+    a2, a3 = bn_relu(t, mean, rstd, gamma, beta, dtype)          # Eq. 1-3
+    bn_shape = Shape(s.N, s.Ho, s.Wo, s.Cout, s.Cout, 1, 1, 1, 0)
+    store = a2.copy() if K == 32 else pack_codes(quantize(a2, gamma, beta, K, dtype), K)   # Eq. 9
+    saved = Saved(K, bn_shape, store, mean, var, rstd, _c(gamma, dtype).copy(), _c(beta, dtype).copy())
+    if keep:
+        return a3, saved, dict(t=t, a2=a2)
+    return a3, saved
+
+
+def postact_backward(saved: Saved, dy, w, s: Shape, xin, dtype=np.float32):
+    """dy is the gradient of y = A3.  ``xin`` is the conv input: an fp32 array, or the Saved of the
+    previous layer of the chain, whose ReLU(dequantized A2) (Eq. 10, Eq. 3) was this layer's input.
+    Returns (dx, dW, dgamma, dbeta)."""
+    a2t = recover_a2(saved, dtype)
+    dt, dg, db = bn_relu_bwd(a2t, dy, saved.rstd, saved.gamma, saved.beta, dtype)   # Eq. 6-8
+    if isinstance(xin, Saved):
+        xa = np.maximum(recover_a2(xin, dtype), np.dtype(dtype).type(0))
+    else:
+        xa = _c(xin, dtype)
+    dw = conv_wgrad(xa, dt, s, dtype)      # Eq. 5
+    dx = conv_dgrad(dt, w, s, dtype)       # Eq. 5
+    return dx, dw, dg, db

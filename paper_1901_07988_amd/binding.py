@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libabl.so")
 ABL_OK, ABL_ERR_ARG, ABL_ERR_SHAPE, ABL_ERR_SCRATCH, ABL_ERR_HIP = range(5)
 ABL_ACCUM_DX = 1
 ABL_MATH_BF16 = 2
+ABL_XIN_F32 = 8
+ABL_XIN_PACKED = 16
 STATS_PLANES = 8
 
 
@@ -59,6 +61,12 @@ _SIGS = {
     "abl_conv_fwd": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp, _vp]),
     "abl_conv_dgrad": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp]),
     "abl_conv_wgrad_packed": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "abl_postact_packed_bytes": (_sz, [_shp, ctypes.c_int]),
+    "abl_postact_stats_bytes": (_sz, [_shp]),
+    "abl_postact_scratch_bytes": (_sz, [_shp, ctypes.c_int]),
+    "abl_postact_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "abl_postact_backward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                            _vp, _vp, _vp, _vp]),
     "abl_stack_scratch_bytes": (_sz, [_lay, _i32, ctypes.c_int]),
     "abl_stack_buffer_bytes": (_sz, [_lay, _i32]),
     "abl_stack_forward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
@@ -134,6 +142,34 @@ def abl_backward(shape, K, packed, stats, dy, W, scratch, dx, dW, dgamma, dbeta,
     _check(lib.abl_backward(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy), _ptr(W),
                             _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dx), _ptr(dW),
                             _ptr(dgamma), _ptr(dbeta)), "abl_backward")
+
+
+# ---- conv -> BN -> ReLU grouping -----------------------------------------------------------------
+def abl_postact_packed_bytes(shape, K):
+    return lib.abl_postact_packed_bytes(ctypes.byref(shape_struct(shape)), K)
+
+
+def abl_postact_stats_bytes(shape):
+    return lib.abl_postact_stats_bytes(ctypes.byref(shape_struct(shape)))
+
+
+def abl_postact_scratch_bytes(shape, K):
+    return lib.abl_postact_scratch_bytes(ctypes.byref(shape_struct(shape)), K)
+
+
+def abl_postact_forward(shape, K, x, W, gamma, beta, scratch, y, packed, stats, flags=0):
+    s = shape_struct(shape)
+    _check(lib.abl_postact_forward(_stream(), ctypes.byref(s), K, flags, _ptr(x), _ptr(W), _ptr(gamma), _ptr(beta),
+                                   _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(y), _ptr(packed),
+                                   _ptr(stats)), "abl_postact_forward")
+
+
+def abl_postact_backward(shape, K, packed, stats, dy, W, xin, xin_stats, scratch, dx, dW, dgamma, dbeta, flags):
+    s = shape_struct(shape)
+    _check(lib.abl_postact_backward(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy),
+                                    _ptr(W), _ptr(xin), _ptr(xin_stats), _ptr(scratch),
+                                    scratch.numel() * scratch.element_size(), _ptr(dx), _ptr(dW), _ptr(dgamma),
+                                    _ptr(dbeta)), "abl_postact_backward")
 
 
 # ---- stages --------------------------------------------------------------------------------

@@ -253,6 +253,80 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
 }
 
+// ---- the same layer grouped as conv -> BN -> ReLU ------------------------------------------
+// Same kernels in another order: F3 -> F1 -> F2 | B3 -> B4 -> B1, B2.  What is packed is still
+// the pre-ReLU BN output A2, now with Cout channels at the output resolution.
+
+static inline int64_t out_rows(const abl_shape& s) {
+  return (int64_t)s.N * out_dim(s.H, s.pad, s.R, s.stride) * out_dim(s.W, s.pad, s.S, s.stride);
+}
+
+size_t abl_postact_packed_bytes(const abl_shape* s, int K) {
+  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  return packed_bytes_of(out_rows(*s) * s->Cout, K);
+}
+
+size_t abl_postact_stats_bytes(const abl_shape* s) {
+  if (check_shape(s) != ABL_OK) return 0;
+  return (size_t)ABL_STATS_PLANES * 4 * (size_t)s->Cout;
+}
+
+size_t abl_postact_scratch_bytes(const abl_shape* s, int K) {
+  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  const size_t act = up256((size_t)out_rows(*s) * s->Cout * sizeof(float));
+  return act + up256(bn_partial_bytes(out_rows(*s), s->Cout)) + wgrad_partial_bytes(*s);
+}
+
+int abl_postact_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x,
+                        const float* W, const float* gamma, const float* beta, void* scratch,
+                        size_t scratch_bytes, float* y, void* packed, void* stats) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
+      bad_ptr(packed) || bad_ptr(stats))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_postact_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t Mo = out_rows(*s);
+  float* t = static_cast<float*>(scratch);  // conv output, consumed by the BN kernels
+  void* red = static_cast<char*>(scratch) + up256((size_t)Mo * s->Cout * sizeof(float));
+  if (int e = launch_conv_fwd(st, *s, (flags & ABL_MATH_BF16) != 0, x, W, nullptr, t)) return e;
+  if (int e = launch_bn_stats(st, t, Mo, s->Cout, gamma, beta, K, red, stats)) return e;
+  return launch_bn_relu_pack(st, t, Mo, s->Cout, K, stats, y, packed);
+}
+
+int abl_postact_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const void* packed,
+                         const void* stats, const float* dy, const float* W, const void* xin,
+                         const void* xin_stats, void* scratch, size_t scratch_bytes, float* dx, float* dW,
+                         float* dgamma, float* dbeta) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_XIN_F32 | ABL_XIN_PACKED)) return ABL_ERR_ARG;
+  const bool xin_f32 = (flags & ABL_XIN_F32) != 0, xin_packed = (flags & ABL_XIN_PACKED) != 0;
+  if (xin_f32 == xin_packed) return ABL_ERR_ARG;  // exactly one of the two
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(W) || bad_ptr(xin) || bad_ptr(scratch) ||
+      bad_ptr(dW) || bad_ptr(dgamma) || bad_ptr(dbeta) || (dx != nullptr && !aligned16(dx)) ||
+      (xin_packed && bad_ptr(xin_stats)))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_postact_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  const int64_t Mo = out_rows(*s);
+  const size_t act = up256((size_t)Mo * s->Cout * sizeof(float));
+  const size_t redb = up256(bn_partial_bytes(Mo, s->Cout));
+  float* dt = static_cast<float*>(scratch);  // gradient w.r.t. the conv output
+  void* red = static_cast<char*>(scratch) + act;
+  void* wpart = static_cast<char*>(scratch) + act + redb;
+  // Eq. 6-8 first: they turn dy into the gradient of the conv output
+  if (int e = launch_bn_bwd(st, packed, stats, dy, Mo, s->Cout, K, false, red, dt, dgamma, dbeta)) return e;
+  // Eq. 5: the weight gradient needs the conv input - the exact tensor at the bottom of a
+  // network, otherwise the previous layer's packed copy (its A3 is rebuilt on the fly)
+  if (int e = launch_conv_wgrad_packed(st, *s, xin_f32 ? 32 : K, bf16, xin, xin_stats, dt, wpart, dW)) return e;
+  if (dx != nullptr) return launch_conv_dgrad(st, *s, bf16, dt, W, dx);
+  return ABL_OK;
+}
+
 // ---- residual stack ---------------------------------------------------------------------
 
 // Workspace of a stack: [cross-layer statistics partials | the largest per-layer workspace].

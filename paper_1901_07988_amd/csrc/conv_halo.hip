@@ -12,8 +12,6 @@
 // MODE 0 forward : out[n,h,w,co] = sum in[n, h+r-pad, w+s-pad, ci] W[r,s,ci,co]
 // MODE 1 dgrad   : out[n,h,w,ci] = sum in[n, h+pad-r, w+pad-s, co] W[r,s,ci,co]   (in = dy)
 
-#include <cstdlib>
-
 #include "abl_internal.h"
 
 // the fused forward evaluates Eq. 1-3 and Eq. 9 here: one rounded fp32 operation at a time
@@ -395,7 +393,6 @@ constexpr Variant kVariants[] = {
     {4, 4, 1},   // 3: 64 px x 64 ch
     {4, 8, 1},   // 4: 128 px x 64 ch
     {4, 14, 1},  // 5: 224 px x 64 ch   (56x56 and 14x14 ImageNet layers)
-    {1, 2, 1},   // 6: 128 px x 16 ch
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -445,8 +442,7 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   const int Hq = mode == 0 ? g.Ho : g.H, Wq = mode == 0 ? g.Wo : g.W;
   const int Ng = mode == 0 ? g.Cout : g.Cin;
   int v;
-  static const int tune16 = getenv("ABL_TUNE16") ? atoi(getenv("ABL_TUNE16")) : 0;
-  if (Ng <= 16) v = tune16 ? 6 : 0;
+  if (Ng <= 16) v = 0;
   else if (Ng <= 32) v = (int64_t)g.N * Hq * Wq >= 256 * 512 ? 2 : 1;
   else {
     const int64_t px = (int64_t)g.N * Hq * Wq * cdiv(Ng, 64);
@@ -486,8 +482,7 @@ void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16
     case 2: launch_variant<MODE, 2, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
     case 3: launch_variant<MODE, 3, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
     case 4: launch_variant<MODE, 4, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
-    case 5: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
-    default: launch_variant<MODE, 6, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    default: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
   }
 }
 

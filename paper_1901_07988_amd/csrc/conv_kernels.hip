@@ -262,7 +262,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------------
 // Weight gradient from the packed activation.  One block = one filter tap x TM input
 // channels x TN output channels x one slice of the output pixels; a chunk of 64 pixels is
-// staged in LDS (activations dequantized + ReLU'd to fp32 on the way in), each wave
+// staged in LDS (activations dequantized + ReLU'd to fp32 on the way in; K == 32: `packed` is
+// an fp32 activation tensor that is used as it is), each wave
 // contracts 16 of them into its own accumulators, the four waves are summed in a fixed
 // order at the end.  partial layout: [split][R][S][Cin][Cout].
 template <int TM, int TN, int K, bool BF16>
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
 #pragma unroll
   for (int v = 0; v < CPW; ++v) {
     const int c = ci0 + a_cg * CPW + v;
-    const bool ok = c < g.Cin;
+    const bool ok = K != 32 && c < g.Cin;
     step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
     fb[v] = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
   }
@@ -376,9 +377,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
         float* dst = &As[(idx / GA) * LDA + a_cg * CPW];
 #pragma unroll
         for (int v = 0; v < CPW; ++v) {
-          const int32_t j = (int32_t)((wa[i] >> (K * v)) & ((1u << K) - 1)) - (1 << (K - 1)) + fb[v];
-          const float a2t = step[v] * ((float)j + 0.5f);          // Eq. 10
-          dst[v] = (oka[i] && a2t > 0.f) ? a2t : 0.f;             // Eq. 3
+          if constexpr (K == 32) {
+            dst[v] = oka[i] ? __uint_as_float(wa[i]) : 0.f;
+          } else {
+            const int32_t j = (int32_t)((wa[i] >> (K * v)) & ((1u << K) - 1)) - (1 << (K - 1)) + fb[v];
+            const float a2t = step[v] * ((float)j + 0.5f);          // Eq. 10
+            dst[v] = (oka[i] && a2t > 0.f) ? a2t : 0.f;             // Eq. 3
+          }
         }
       }
     }
@@ -520,8 +525,8 @@ __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __
   const int co = t % g.Cout; t /= g.Cout;
   const int ci = t % g.Cin; t /= g.Cin;
   const int s = t % g.S, r = t / g.S;
-  const float step = stats[P_STEP * g.Cin + ci];
-  const int32_t fb = reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci];
+  const float step = K == 32 ? 0.f : stats[P_STEP * g.Cin + ci];
+  const int32_t fb = K == 32 ? 0 : reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci];
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
   float acc = 0.f;
   for (int64_t p = threadIdx.x; p < Mg; p += kThreads) {
@@ -531,10 +536,14 @@ __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __
     const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s - g.pad;
     if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) continue;
     const int64_t e = (((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci;
+    if (K == 32) {
+      acc += reinterpret_cast<const float*>(packed)[e] * dy[p * g.Cout + co];
+      continue;
+    }
     uint32_t code;
     if (K == 4) code = (packed[e >> 1] >> ((e & 1) * 4)) & 15u;
     else code = packed[e];
-    const int32_t j = (int32_t)code - (1 << (K - 1)) + fb;
+    const int32_t j = (int32_t)code - (K == 32 ? 0 : (1 << (K - 1))) + fb;
     const float a2t = step * ((float)j + 0.5f);
     if (a2t > 0.f) acc += a2t * dy[p * g.Cout + co];
   }
@@ -631,7 +640,12 @@ inline bool use_halo_wgrad(const ConvGeom& g) { return g.Cin <= 64 && halo_wgrad
 size_t wgrad_partial_bytes(const abl_shape& s) {
   const ConvGeom g = geom_of(s);
   if (!mfma_ok(g)) return 256;
-  if (use_halo_wgrad(g)) return halo_wgrad_partial_bytes(g);
+  if (use_halo_wgrad(g)) {  // the per-tap kernel is still used when the activation is fp32
+    const WgradPlan p = wgrad_plan(g);
+    const size_t a = halo_wgrad_partial_bytes(g);
+    const size_t b = ((size_t)p.split * g.R * g.S * g.Cin * g.Cout * sizeof(float) + 255) / 256 * 256;
+    return a > b ? a : b;
+  }
   const WgradPlan p = wgrad_plan(g);
   const size_t n = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
   return ((size_t)p.split * n + 255) / 256 * 256;
@@ -667,7 +681,8 @@ static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan
   dim3 grid((unsigned)((p.split + 7) / 8 * 8 * p.tiles));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
   auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true> : wgrad_kernel<TM, TN, 4, false>)
-                     : (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>);
+            : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>)
+                     : (bf16 ? wgrad_kernel<TM, TN, 32, true> : wgrad_kernel<TM, TN, 32, false>);
   kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
 }
 
@@ -679,10 +694,11 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
     const unsigned blocks = (unsigned)(g.R * g.S * g.Cin * g.Cout);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
     if (K == 4) naive_wgrad_kernel<4><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
-    else naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
+    else if (K == 8) naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
+    else naive_wgrad_kernel<32><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
     return hip_status();
   }
-  if (use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
+  if (K != 32 && use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
   if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst);

@@ -206,3 +206,38 @@ class StackRun:
 
     def stored_bytes(self):
         return sum(d["packed"].numel() + d["stats"].numel() for d in self.descs)
+
+
+class PostactRun:
+    """One conv -> BN -> ReLU layer on the device (abl_postact_forward / abl_postact_backward)."""
+
+    def __init__(self, s, K, flags=0):
+        self.s, self.K, self.flags = s, K, flags
+        t = s.as_tuple()
+        self.scratch = zeros_bytes(B.abl_postact_scratch_bytes(t, K))
+        self.packed = torch.full((B.abl_postact_packed_bytes(t, K),), 0xEE, dtype=torch.uint8, device="cuda")
+        self.stats = zeros_bytes(B.abl_postact_stats_bytes(t))
+
+    def forward(self, x, w, gamma, beta):
+        s = self.s
+        self.y = torch.empty(out_shape(s), dtype=torch.float32, device="cuda")
+        B.abl_postact_forward(s.as_tuple(), self.K, dev(x), dev(w), dev(gamma), dev(beta), self.scratch, self.y,
+                              self.packed, self.stats, flags=self.flags)
+        torch.cuda.synchronize()
+        return self.y.cpu().numpy()
+
+    def backward(self, dy, w, xin=None, prev=None, want_dx=True):
+        """xin: fp32 conv input (numpy) or prev: the PostactRun of the previous layer."""
+        s = self.s
+        dx = torch.empty((s.N, s.H, s.W, s.Cin), dtype=torch.float32, device="cuda") if want_dx else None
+        dw = torch.empty((s.R, s.S, s.Cin, s.Cout), dtype=torch.float32, device="cuda")
+        dg = torch.empty(s.Cout, dtype=torch.float32, device="cuda")
+        db = torch.empty(s.Cout, dtype=torch.float32, device="cuda")
+        if prev is not None:
+            B.abl_postact_backward(s.as_tuple(), self.K, self.packed, self.stats, dev(dy), dev(w), prev.packed,
+                                   prev.stats, self.scratch, dx, dw, dg, db, self.flags | B.ABL_XIN_PACKED)
+        else:
+            B.abl_postact_backward(s.as_tuple(), self.K, self.packed, self.stats, dev(dy), dev(w), dev(xin), None,
+                                   self.scratch, dx, dw, dg, db, self.flags | B.ABL_XIN_F32)
+        torch.cuda.synchronize()
+        return (None if dx is None else dx.cpu().numpy()), dw.cpu().numpy(), dg.cpu().numpy(), db.cpu().numpy()

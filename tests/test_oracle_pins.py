@@ -452,3 +452,72 @@ def test_sampled_conv_evaluators_agree_with_full_loops(oracle, shape_t):
     np.testing.assert_allclose(o.conv_dgrad_at(dy, w, s, pts), da.reshape(-1, s.Cin), rtol=1e-12, atol=1e-12)
     ent = [(r, q, c) for r in range(s.R) for q in range(s.S) for c in range(s.Cin)]
     np.testing.assert_allclose(o.conv_wgrad_at(x, dy, s, ent), dw.reshape(-1, s.Cout), rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ conv -> BN -> ReLU grouping
+@pytest.mark.parametrize("shape_t", FD_SHAPES)
+def test_postact_layer_matches_torch_autograd(oracle, shape_t):
+    """The conv-first grouping with exact storage is relu(batch_norm(conv2d(x))) in PyTorch."""
+    o = oracle
+    rng = np.random.default_rng(17)
+    s = o.Shape(*shape_t)
+    x = rng.standard_normal((s.N, s.H, s.W, s.Cin))
+    w = rng.standard_normal((s.R, s.S, s.Cin, s.Cout)) * 0.5
+    gamma, beta = rng.uniform(0.5, 1.5, s.Cout), rng.standard_normal(s.Cout) * 0.3
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout))
+    y, saved = o.postact_forward(x, w, gamma, beta, 32, s, np.float64)
+    dx, dw, dg, db = o.postact_backward(saved, dy, w, s, x, np.float64)
+    xt = torch.tensor(x).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    wt = torch.tensor(w).permute(3, 2, 0, 1).contiguous().requires_grad_(True)
+    gt, bt = torch.tensor(gamma).requires_grad_(True), torch.tensor(beta).requires_grad_(True)
+    t = torch.nn.functional.conv2d(xt, wt, stride=s.stride, padding=s.pad)
+    yt = torch.relu(torch.nn.functional.batch_norm(t, None, None, gt, bt, training=True, eps=float(o.EPS)))
+    yt.backward(torch.tensor(dy).permute(0, 3, 1, 2))
+    tol = dict(rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dw, wt.grad.permute(2, 3, 1, 0).numpy(), **tol)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), **tol)
+    np.testing.assert_allclose(db, bt.grad.numpy(), **tol)
+
+
+@pytest.mark.parametrize("K", [4, 8])
+def test_postact_chain_is_conv_then_preact_layers_then_bn_relu(oracle, K):
+    """Both groupings are the same network: a conv-first chain equals conv_0, then pre-activation
+    layers, then a trailing BN-ReLU - outputs, codes and gradients bit for bit."""
+    o = oracle
+    rng = np.random.default_rng(23)
+    shapes = [o.Shape(2, 8, 8, 3, 6), o.Shape(2, 8, 8, 6, 4, 3, 3, 2, 1), o.Shape(2, 4, 4, 4, 5, 1, 1, 1, 0)]
+    ws = [(rng.standard_normal((s.R, s.S, s.Cin, s.Cout)) * 0.4).astype(np.float32) for s in shapes]
+    gs = [rng.uniform(0.5, 1.5, s.Cout).astype(np.float32) for s in shapes]
+    bs = [(rng.standard_normal(s.Cout) * 0.2).astype(np.float32) for s in shapes]
+    x = rng.standard_normal((2, 8, 8, 3)).astype(np.float32)
+    # conv-first chain
+    a, saved_post = x, []
+    for s, w, g, b in zip(shapes, ws, gs, bs):
+        a, sv = o.postact_forward(a, w, g, b, K, s)
+        saved_post.append(sv)
+    # conv_0, pre-activation layers, trailing BN-ReLU
+    t = o.conv_fwd(x, ws[0], shapes[0])
+    saved_pre = []
+    for i in (1, 2):
+        t, sv = o.layer_forward(t, ws[i], gs[i - 1], bs[i - 1], K, shapes[i])
+        saved_pre.append(sv)
+    mean, var = o.bn_stats(t)
+    a2, a3 = o.bn_relu(t, mean, o.bn_rstd(var), gs[2], bs[2])
+    assert a3.tobytes() == a.tobytes()
+    assert saved_post[0].store.tobytes() == saved_pre[0].store.tobytes()
+    assert saved_post[1].store.tobytes() == saved_pre[1].store.tobytes()
+    # backward: the weight gradient of conv_1 is the same in both groupings
+    dy = rng.standard_normal(a.shape).astype(np.float32)
+    g2 = o.postact_backward(saved_post[2], dy, ws[2], shapes[2], saved_post[1])
+    g1 = o.postact_backward(saved_post[1], g2[0], ws[1], shapes[1], saved_post[0])
+    g0 = o.postact_backward(saved_post[0], g1[0], ws[0], shapes[0], x)
+    dt2, dg2, db2 = o.bn_relu_bwd(o.dequantize(o.quantize(a2, gs[2], bs[2], K), gs[2], bs[2], K), dy,
+                                  o.bn_rstd(var), gs[2], bs[2])
+    p2 = o.layer_backward(saved_pre[1], dt2, ws[2])
+    p1 = o.layer_backward(saved_pre[0], p2[0], ws[1])
+    assert g2[1].tobytes() == p2[1].tobytes() and g1[1].tobytes() == p1[1].tobytes()     # dW_2, dW_1
+    assert g2[2].tobytes() == dg2.tobytes() and g2[3].tobytes() == db2.tobytes()
+    assert g1[2].tobytes() == p2[2].tobytes() and g0[2].tobytes() == p1[2].tobytes()     # dgamma_1, dgamma_0
+    np.testing.assert_array_equal(g0[1], o.conv_wgrad(x, p1[0], shapes[0]))               # dW_0 from exact x
