@@ -147,6 +147,24 @@ int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, uint32_t 
                           const void* stats, const float* dy, void* scratch,
                           size_t scratch_bytes, float* dW);
 
+/* ---- the two fused kernels that abl_forward / abl_backward use where they can ----
+ * Both exist for stride-1 convolutions with a filter larger than 1x1 and channel counts that
+ * are multiples of 16 (abl_bn_conv_fwd also needs Ho == H, Wo == W); other shapes give
+ * ABL_ERR_SHAPE and the layer calls fall back to the separate stages.
+ *
+ * abl_bn_conv_fwd: Eq. 1-3, Eq. 9 and Eq. 4 in one kernel - x is normalised, ReLU'd, quantized
+ * and packed while the convolution stages its input patch; A3 is never written to memory.
+ * stats must hold the statistics of x (abl_bn_stats).  y must not alias x; skip may alias y. */
+int abl_bn_conv_fwd(void* stream, const abl_shape* shape, int K, uint32_t flags, const float* x,
+                    const void* stats, const float* W, const float* skip, float* y, void* packed);
+/* abl_conv_dgrad_bn_reduce: Eq. 5 (gradient to the conv input) with the sums of Eq. 7 taken in
+ * the epilogue from the layer's packed codes (Eq. 10, Eq. 6): writes da3 and `*rows` partial rows
+ * [rows][2][Cin] of doubles (sum dA2, sum A1~ dA2) at the start of scratch
+ * (abl_bn_scratch_bytes(N*H*W, Cin)); `*rows` is a host value set by the call. */
+int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                             const float* dy, const float* W, const void* packed, const void* stats,
+                             void* scratch, size_t scratch_bytes, float* da3, int32_t* rows);
+
 /* ---- the layer grouped as conv -> BN -> ReLU ----
  * The paper groups a convolution with the non-linearities that PRECEDE it (Sec. 3.1) and that
  * is what abl_forward / abl_backward implement.  These entry points run the same kernels with

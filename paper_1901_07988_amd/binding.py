@@ -61,6 +61,9 @@ _SIGS = {
     "abl_conv_fwd": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp, _vp]),
     "abl_conv_dgrad": (ctypes.c_int, [_vp, _shp, _u32, _vp, _vp, _vp]),
     "abl_conv_wgrad_packed": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "abl_bn_conv_fwd": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "abl_conv_dgrad_bn_reduce": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp,
+                                                ctypes.POINTER(ctypes.c_int32)]),
     "abl_postact_packed_bytes": (_sz, [_shp, ctypes.c_int]),
     "abl_postact_stats_bytes": (_sz, [_shp]),
     "abl_postact_scratch_bytes": (_sz, [_shp, ctypes.c_int]),
@@ -142,6 +145,23 @@ def abl_backward(shape, K, packed, stats, dy, W, scratch, dx, dW, dgamma, dbeta,
     _check(lib.abl_backward(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy), _ptr(W),
                             _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dx), _ptr(dW),
                             _ptr(dgamma), _ptr(dbeta)), "abl_backward")
+
+
+# ---- fused kernels -------------------------------------------------------------------------------
+def abl_bn_conv_fwd(shape, K, x, stats, W, skip, y, packed, flags=0):
+    s = shape_struct(shape)
+    _check(lib.abl_bn_conv_fwd(_stream(), ctypes.byref(s), K, flags, _ptr(x), _ptr(stats), _ptr(W), _ptr(skip),
+                               _ptr(y), _ptr(packed)), "abl_bn_conv_fwd")
+
+
+def abl_conv_dgrad_bn_reduce(shape, K, dy, W, packed, stats, scratch, da3, flags=0):
+    """Returns the number of partial rows written to the start of scratch."""
+    s = shape_struct(shape)
+    rows = ctypes.c_int32(0)
+    _check(lib.abl_conv_dgrad_bn_reduce(_stream(), ctypes.byref(s), K, flags, _ptr(dy), _ptr(W), _ptr(packed),
+                                        _ptr(stats), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                        _ptr(da3), ctypes.byref(rows)), "abl_conv_dgrad_bn_reduce")
+    return rows.value
 
 
 # ---- conv -> BN -> ReLU grouping -----------------------------------------------------------------

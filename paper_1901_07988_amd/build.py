@@ -33,18 +33,22 @@ def hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, only=None) -> str:
+    """Compile every translation unit (or, with `only`, just the named ones, reusing the other
+    object files of an earlier build) and link libabl.so."""
     cc = hipcc()
     objs = []
     procs = []
     for unit, extra in UNITS.items():
         src = os.path.join(CSRC, unit)
         obj = os.path.join(CSRC, unit.replace(".hip", ".o"))
+        objs.append(obj)
+        if only and unit.replace(".hip", "") not in only and os.path.exists(obj):
+            continue
         cmd = [cc, *COMMON, *extra, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((unit, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        objs.append(obj)
     for unit, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and l.strip())
@@ -60,5 +64,5 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(only=[a for a in sys.argv[1:] if not a.startswith("-")] or None)
     sys.exit(0)

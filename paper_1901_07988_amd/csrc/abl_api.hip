@@ -253,6 +253,40 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
 }
 
+// ---- the two fused kernels of the layer step, callable on their own --------------------------
+
+int abl_bn_conv_fwd(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const void* stats,
+                    const float* W, const float* skip, float* y, void* packed) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (bad_ptr(x) || bad_ptr(stats) || bad_ptr(W) || bad_ptr(y) || bad_ptr(packed) ||
+      (skip != nullptr && !aligned16(skip)) || static_cast<const void*>(x) == static_cast<const void*>(y))
+    return ABL_ERR_ARG;
+  const ConvGeom g = geom_of(*s);
+  if (!halo_fused_supported(g)) return ABL_ERR_SHAPE;
+  return launch_halo_fwd_fused((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, x, stats, W, skip, y,
+                               packed, nullptr);
+}
+
+int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t flags, const float* dy,
+                             const float* W, const void* packed, const void* stats, void* scratch,
+                             size_t scratch_bytes, float* da3, int32_t* rows) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(packed) || bad_ptr(stats) || bad_ptr(scratch) || bad_ptr(da3) ||
+      rows == nullptr)
+    return ABL_ERR_ARG;
+  const ConvGeom g = geom_of(*s);
+  const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
+  if (tiles <= 0 || tiles > kMaxPartialBlocks) return ABL_ERR_SHAPE;
+  if (scratch_bytes < bn_partial_bytes(rows_of(*s), s->Cin)) return ABL_ERR_SCRATCH;
+  *rows = tiles;
+  return launch_halo_dgrad_reduce((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, dy, W, packed, stats,
+                                  da3, static_cast<double*>(scratch));
+}
+
 // ---- the same layer grouped as conv -> BN -> ReLU ------------------------------------------
 // Same kernels in another order: F3 -> F1 -> F2 | B3 -> B4 -> B1, B2.  What is packed is still
 // the pre-ReLU BN output A2, now with Cout channels at the output resolution.

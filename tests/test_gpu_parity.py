@@ -461,3 +461,48 @@ def test_postact_chain_with_packed_inputs(G, oracle, K):
     # K-bit storage of the conv-first layer: K/32 of the fp32 tensor it replaces
     from paper_1901_07988_amd import binding as B
     assert B.abl_postact_packed_bytes(s1.as_tuple(), K) == (-(-s1.N * s1.Ho * s1.Wo * s1.Cout * K // 8) + 127) // 128 * 128
+
+
+@pytest.mark.parametrize("s", [LayerShape(4, 32, 32, 16, 16), LayerShape(2, 16, 16, 32, 64),
+                               LayerShape(2, 14, 14, 64, 64), LayerShape(1, 14, 14, 256, 256)],
+                         ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_fused_kernels_on_their_own(G, oracle, s, K):
+    """abl_bn_conv_fwd (Eq. 1-3, 9, 4 in one kernel) and abl_conv_dgrad_bn_reduce (Eq. 5 with the
+    Eq. 7 sums in the epilogue) against the oracle's separate steps."""
+    import torch
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    print("case fused", s.as_tuple(), K, flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 5, "normal", "random")
+    st = G.run_bn_stats(x, gamma, beta, K)
+    t = s.as_tuple()
+    y = torch.empty(G.out_shape(s), dtype=torch.float32, device="cuda")
+    packed = torch.full((B.abl_packed_bytes(t, K),), 0x77, dtype=torch.uint8, device="cuda")
+    skip = np.random.default_rng(1).standard_normal(G.out_shape(s)).astype(np.float32)
+    B.abl_bn_conv_fwd(t, K, G.dev(x), st, G.dev(w), G.dev(skip), y, packed)
+    torch.cuda.synchronize()
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s), skip=skip)
+    assert packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y.cpu().numpy(), y_ref) < TOL
+    # dgrad + reduce: da3 against the oracle, the partial rows against the oracle's Eq. 7 totals
+    scratch = G.zeros_bytes(B.abl_bn_scratch_bytes(s.M, s.Cin))
+    da3 = torch.empty((s.N, s.H, s.W, s.Cin), dtype=torch.float32, device="cuda")
+    rows = B.abl_conv_dgrad_bn_reduce(t, K, G.dev(dy), G.dev(w), packed, st, scratch, da3)
+    torch.cuda.synchronize()
+    da3_ref = o.conv_dgrad(dy, w, oshape(o, s))
+    assert rel(da3.cpu().numpy(), da3_ref) < TOL
+    part = scratch[: rows * 2 * s.Cin * 8].cpu().numpy().view(np.float64).reshape(rows, 2, s.Cin).sum(0)
+    _, dg_ref, db_ref = o.bn_relu_bwd(o.recover_a2(saved), da3_ref, saved.rstd, gamma, beta)
+    scale = max(1.0, float(np.abs(da3_ref).sum((0, 1, 2)).max()))
+    assert np.max(np.abs(part[0] - db_ref)) < TOL * scale and np.max(np.abs(part[1] - dg_ref)) < TOL * scale
+
+
+def test_fused_kernels_reject_unsupported_shapes(G):
+    import torch
+    from paper_1901_07988_amd import binding as B
+    t = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    for shape in ((2, 8, 8, 16, 16, 1, 1, 1, 0), (2, 8, 8, 16, 16, 3, 3, 2, 1), (2, 8, 8, 12, 16, 3, 3, 1, 1)):
+        with pytest.raises(B.AblError) as e:
+            B.abl_bn_conv_fwd(shape, 4, t, t, t, None, t[4096:], t)
+        assert e.value.code == B.ABL_ERR_SHAPE
