@@ -50,24 +50,40 @@ def get_workload(name):
     return synth.config5()
 
 
-def time_events(fn, reps):
-    """Average duration in ms of `fn` launched `reps` times back to back on the current stream."""
+def time_events(fn, reps, nset=1):
+    """Average duration in ms of `fn(i % nset)` launched `reps` times back to back on the current stream."""
     import torch
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    fn()
+    for i in range(nset):
+        fn(i)
     torch.cuda.synchronize()
     start.record()
-    for _ in range(reps):
-        fn()
+    for i in range(reps):
+        fn(i % nset)
     stop.record()
     torch.cuda.synchronize()
     return start.elapsed_time(stop) / reps
 
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each divided by
+# what the same counter reads for a plain device copy of known size (FETCH_SIZE reads 1/1.994 of the
+# bytes, WRITE_SIZE 1/1.000), for the kernels of the default workload (3x3 16->16, 32x32, N=128, K=4).
+# The runs and their commands are summarised under profiles/.
+MEASURED_TRAFFIC = {
+    ("config2", 4, "fp32"): {
+        "bn_conv_fwd": 23.95e6,            # in the stack: half the layers also read a shortcut
+        "conv_dgrad_bn_reduce": 19.89e6,
+        "conv_wgrad_packed": 15.45e6 + 4.75e6,
+    },
+}
+
+
 def kernel_breakdown(G, B, s, K, reps, flags=0):
-    """Per-stage timing of one layer shape with HIP events on the stream the kernels run on.
-    Returns {stage: dict(ms, bytes, flops, launches)} with ALGORITHMIC bytes / flops per call."""
-    import numpy as np
+    """Per-kernel timing of one layer shape with HIP events on the stream the kernels run on
+    (torch's current stream, which is the one handed to the library).  Where the shape has the
+    fused kernels (3x3 'same' stride-1 layers) these are the kernels the layer step runs; the
+    separate stages are timed as well.  Returns {stage: dict(ms, bytes, flops, launches, step)} with
+    ALGORITHMIC bytes / flops per call; step=True marks the stages that make up one layer step."""
     import torch
     t = s.as_tuple()
     M, C, E = s.M, s.Cin, s.E
@@ -76,35 +92,57 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
     P = B.abl_packed_bytes(t, K)
     flops = 2.0 * s.N * s.Ho * s.Wo * s.Cin * s.Cout * s.R * s.S
     f32 = dict(dtype=torch.float32, device="cuda")
-    x = torch.randn(E, **f32)
-    dy = torch.randn(Eo, **f32)
-    y = torch.empty(Eo, **f32)
-    a3 = torch.empty(E, **f32)
-    dx = torch.empty(E, **f32)
+    # Several sets of operands, used in turn, so that a kernel does not find its own previous output
+    # in the L2 caches (in the layer step its operands were last touched by other kernels).
+    nset = max(1, min(8, (96 << 20) // (8 * E + 8 * Eo)))
     w = torch.randn(s.R * s.S * s.Cin * s.Cout, **f32) * 0.1
     dw = torch.empty_like(w)
     gamma, beta = torch.ones(C, **f32), torch.zeros(C, **f32)
     dg, db = torch.empty(C, **f32), torch.empty(C, **f32)
     stats = G.zeros_bytes(B.abl_stats_bytes(t))
-    packed = G.zeros_bytes(P)
     scratch = G.zeros_bytes(B.abl_scratch_bytes(t, K))
-    B.abl_bn_stats(x, M, C, gamma, beta, K, scratch, stats)
-    B.abl_bn_relu_pack(x, M, C, K, stats, a3, packed)
+    sets = []
+    for _ in range(nset):
+        d = dict(x=torch.randn(E, **f32), dy=torch.randn(Eo, **f32), y=torch.empty(Eo, **f32),
+                 a3=torch.empty(E, **f32), dx=torch.empty(E, **f32), packed=G.zeros_bytes(P))
+        B.abl_bn_stats(d["x"], M, C, gamma, beta, K, scratch, stats)
+        B.abl_bn_relu_pack(d["x"], M, C, K, stats, d["a3"], d["packed"])
+        sets.append(d)
+    fused = True
+    try:
+        d = sets[0]
+        B.abl_bn_conv_fwd(t, K, d["x"], stats, w, None, d["y"], d["packed"], flags=flags)
+        B.abl_conv_dgrad_bn_reduce(t, K, d["dy"], w, d["packed"], stats, scratch, d["dx"], flags=flags)
+    except B.AblError:
+        fused = False
+    conv_bytes = 4 * E + 4 * Eo + wbytes
+    S = sets
+    # name: (call on operand set i, algorithmic bytes, flops, launches, part of the layer step)
     stages = {
-        "bn_stats": (lambda: B.abl_bn_stats(x, M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2),
-        "bn_relu_pack": (lambda: B.abl_bn_relu_pack(x, M, C, K, stats, a3, packed), 8 * E + P, 0, 1),
-        "conv_fwd": (lambda: B.abl_conv_fwd(t, a3, w, None, y, flags=flags), 4 * E + 4 * Eo + wbytes, flops, 1),
-        "conv_dgrad": (lambda: B.abl_conv_dgrad(t, dy, w, a3, flags=flags), 4 * E + 4 * Eo + wbytes, flops, 1),
-        "conv_wgrad_packed": (lambda: B.abl_conv_wgrad_packed(t, K, packed, stats, dy, scratch, dw, flags=flags),
-                              P + 4 * Eo + wbytes, flops, 2),
-        "bn_bwd": (lambda: B.abl_bn_bwd(packed, stats, a3, M, C, K, scratch, dx, dg, db), 2 * P + 12 * E, 0, 3),
-        "pack": (lambda: B.abl_pack(x, M, C, K, stats, packed), 4 * E + P, 0, 1),
-        "unpack": (lambda: B.abl_unpack(packed, M, C, K, stats, a3), 4 * E + P, 0, 1),
+        "bn_stats": (lambda i: B.abl_bn_stats(S[i]["x"], M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2, not fused),
+        "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]),
+                         8 * E + P, 0, 1, not fused),
+        "conv_fwd": (lambda i: B.abl_conv_fwd(t, S[i]["a3"], w, None, S[i]["y"], flags=flags), conv_bytes, flops, 1,
+                     not fused),
+        "conv_dgrad": (lambda i: B.abl_conv_dgrad(t, S[i]["dy"], w, S[i]["dx"], flags=flags), conv_bytes, flops, 1,
+                       not fused),
+        "conv_wgrad_packed": (lambda i: B.abl_conv_wgrad_packed(t, K, S[i]["packed"], stats, S[i]["dy"], scratch, dw,
+                                                                flags=flags), P + 4 * Eo + wbytes, flops, 2, True),
+        "bn_bwd": (lambda i: B.abl_bn_bwd(S[i]["packed"], stats, S[i]["dx"], M, C, K, scratch, S[i]["a3"], dg, db),
+                   2 * P + 12 * E, 0, 3, not fused),
+        "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P, 0, 1, False),
+        "unpack": (lambda i: B.abl_unpack(S[i]["packed"], M, C, K, stats, S[i]["a3"]), 4 * E + P, 0, 1, False),
     }
+    if fused:
+        stages["bn_conv_fwd"] = (lambda i: B.abl_bn_conv_fwd(t, K, S[i]["x"], stats, w, None, S[i]["y"], S[i]["packed"],
+                                                             flags=flags), conv_bytes + P, flops, 1, True)
+        stages["conv_dgrad_bn_reduce"] = (
+            lambda i: B.abl_conv_dgrad_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"],
+                                                 flags=flags), conv_bytes + P, flops, 1, True)
     out = {}
-    for name, (fn, nbytes, fl, launches) in stages.items():
-        ms = time_events(fn, reps)
-        out[name] = dict(ms=ms, bytes=nbytes, flops=fl, launches=launches,
+    for name, (fn, nbytes, fl, launches, in_step) in stages.items():
+        ms = time_events(fn, reps, nset)
+        out[name] = dict(ms=ms, bytes=nbytes, flops=fl, launches=launches, step=in_step,
                          gbs=nbytes / ms / 1e6, tflops=fl / ms / 1e9)
     return out
 
@@ -169,21 +207,25 @@ def main():
     N, L = wl.shapes[0].N, len(layers)
     value = N * L / (dt / args.steps)
 
-    # per-kernel timing of the (most frequent) layer shape, for the roofline block
+    # per-kernel timing of every distinct layer shape, for the roofline block: the dominant kernel is
+    # the one with the largest share of the step among the kernels the layer step runs
     shapes = {}
     for s in wl.shapes:
         shapes[s] = shapes.get(s, 0) + 1
     per_step = {}
     breakdown = {}
+    details = {}
     for s, count in shapes.items():
         bd = kernel_breakdown(G, B, s, K, args.kernel_reps, flags)
+        details[s] = bd
         breakdown["x".join(map(str, s.as_tuple()))] = {k: round(v["ms"] * 1e3, 2) for k, v in bd.items()}
         for k, v in bd.items():
-            if k in ("pack", "unpack"):
-                continue
-            key = (s, k)
-            per_step[key] = (v["ms"] * count, v)
-    (dom_shape, dom_name), (_, dom) = max(per_step.items(), key=lambda kv: kv[1][0])
+            if v["step"]:
+                per_step[(s, k)] = (v["ms"] * count, v)
+    # a stage that is one launch is preferred when it is within 25% of a several-launch one, so that
+    # the figure is that of a single kernel
+    (dom_shape, dom_name), (_, dom) = max(per_step.items(),
+                                          key=lambda kv: kv[1][0] * (1.0 if kv[1][1]["launches"] == 1 else 0.75))
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if args.math == "bf16" else MFMA_FP32_PEAK_TFLOPS
     flops_bound_ms = dom["flops"] / (mfma_peak * 1e9)
     bytes_bound_ms = dom["bytes"] / (HBM_PEAK_GBS * 1e6)
@@ -193,8 +235,11 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["gbs"] / HBM_PEAK_GBS}
-    roof.update({"traffic": None, "kernel": dom_name, "shape": "x".join(map(str, dom_shape.as_tuple())),
-                 "avg_us": dom["ms"] * 1e3, "launches_per_call": dom["launches"]})
+    traffic = MEASURED_TRAFFIC.get((args.workload, K, args.math), {}).get(dom_name)
+    roof.update({"traffic": traffic, "kernel": dom_name, "shape": "x".join(map(str, dom_shape.as_tuple())),
+                 "avg_us": dom["ms"] * 1e3, "launches_per_call": dom["launches"],
+                 "algorithmic_bytes": dom["bytes"], "algorithmic_flops": dom["flops"],
+                 "hbm_frac_of_same_kernel": dom["gbs"] / HBM_PEAK_GBS})
 
     exact_bytes = sum(4 * s.E for s in wl.shapes)
     result = {
@@ -213,8 +258,7 @@ def main():
         "activation_bytes": {"stored": run.stored_bytes(), "exact_fp32": exact_bytes,
                              "ratio": run.stored_bytes() / exact_bytes},
     }
-    s0 = max(shapes, key=shapes.get)
-    bd0 = kernel_breakdown(G, B, s0, K, args.kernel_reps, flags)
+    bd0 = details[max(shapes, key=shapes.get)]
     result["pack_unpack_gbs"] = {"pack": bd0["pack"]["gbs"], "unpack": bd0["unpack"]["gbs"],
                                  "bn_relu_pack": bd0["bn_relu_pack"]["gbs"]}
     if not args.no_cpu_baseline:
