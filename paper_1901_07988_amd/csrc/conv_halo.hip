@@ -33,8 +33,7 @@ struct HaloPlan {
   int mtiles;                     // ceil(npix / 16)
   int variant;                    // index into the instantiation table
   int bn;                         // output channels per block
-  int a_dw, a_dh;                 // 64 patch pixels further = a_dh rows + a_dw cols
-  int m_dw, m_dh;                 // 16 tile pixels further = m_dh rows + m_dw cols
+  unsigned inv_HW, inv_HH, inv_TW, inv_TH;  // ceil(2^32 / d): exact quotients for operands < 2^16
   unsigned lds_bytes;
   int pack_pad;                   // zero bytes after the last code (fused forward only)
 };
@@ -49,30 +48,38 @@ struct EpiReduce {
   int K;
 };
 
-// (ti, h, w) position inside a tile or patch, advanced without divisions.
-struct Pos {
-  int w, h, ti;
-  __device__ inline void init(int idx, int width, int height) {
-    w = idx % width;
-    const int q = idx / width;
-    h = q % height;
-    ti = q / height;
-  }
-  __device__ inline void advance(int dw, int dh, int width, int height) {
-    w += dw;
-    h += dh;
-    if (w >= width) { w -= width; ++h; }
-    while (h >= height) { h -= height; ++ti; }
-  }
-};
+// idx -> (ti, h, w) of a [.. x height x width] box, divisions by multiplication
+__device__ inline void split3(int idx, int width, unsigned inv_w, int height, unsigned inv_h, int& ti, int& h,
+                              int& w) {
+  const int q = width == 1 ? idx : (int)__umulhi((unsigned)idx, inv_w);
+  w = idx - q * width;
+  ti = height == 1 ? q : (int)__umulhi((unsigned)q, inv_h);
+  h = q - ti * height;
+}
+
+// Sum over the 16 lanes of a row (lanes that differ in bits 0-3); every lane gets the total.
+__device__ inline double row16_sum(double v) {
+  v += __shfl_xor(v, 1);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 8);
+  return v;
+}
 
 
 // WAVES_N waves share the block's M-tiles and split its N-tiles; the other 4/WAVES_N groups
-// split the M-tiles.  MT = M-tiles per wave (upper bound, `mtiles` is the real count),
-// NT = N-tiles per wave.  The weights are not staged: each lane fetches its B fragment (four
-// consecutive k of one output channel) for the next tap straight from L2 while the current
-// tap is contracted.  With more than 16 input channels the patch buffer is doubled and the
-// next chunk's global loads are in flight during the MFMAs.
+// split the M-tiles.  MT = M-tiles (16 pixels) per wave (upper bound, `mtiles` is the real
+// count), NT = N-tiles (16 output channels) per wave.
+// The MFMA computes the TRANSPOSED output tile: its first operand is the weight fragment (row =
+// output channel), its second the pixel fragment (column = pixel), so a lane ends up with four
+// consecutive channels of one pixel - one 16-byte store, one 16-byte shortcut load and one
+// 16-/32-bit load of that pixel's codes in the epilogue.
+// The weights are not staged: each lane fetches its fragment (four consecutive k of one output
+// channel) straight from L2.  3x3 filters with few tiles per wave (UNROLL_TAPS) hold the
+// fragments of all nine taps in registers: they are requested together with the first patch,
+// and the registers of a tap are refilled for the next channel chunk right after its MFMAs.
+// Other shapes fetch one tap ahead.  With more than 16 input channels the patch buffer is
+// doubled and the next chunk's global loads are in flight during the MFMAs.
 // FUSE = 0: `in` is the conv input.  FUSE = K (4 or 8, forward only): `in` is the layer input x;
 // BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied while the patch is staged, and the
 // block that owns a pixel also writes its K-bit codes (Eq. 9).
@@ -117,42 +124,18 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AMAX];
   bool own[AMAX];  // fused forward: this block writes the codes of the element
-  {
-    Pos q;
-    q.init(tid >> 2, p.HW, p.HH);
 #pragma unroll
-    for (int j = 0; j < AMAX; ++j) {
-      const int idx = tid + kThreads * j;
-      goff[j] = -1;
-      const int n = img0 + q.ti, hi = oh + q.h, wi = ow + q.w;
-      if (idx < totalA && n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi)
-        goff[j] = ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3);
-      own[j] = FUSE != 0 && goff[j] >= 0 && n0 == 0 && hi >= h0 && hi < h0 + p.TH && wi >= w0 && wi < w0 + p.TW;
-      q.advance(p.a_dw, p.a_dh, p.HW, p.HH);
-    }
+  for (int j = 0; j < AMAX; ++j) {
+    const int idx = tid + kThreads * j;
+    int ti, h, w;
+    split3(idx >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
+    const int n = img0 + ti, hi = oh + h, wi = ow + w;
+    const bool ok = idx < totalA && n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi;
+    goff[j] = ok ? ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3) : -1;
+    own[j] = FUSE != 0 && ok && n0 == 0 && hi >= h0 && hi < h0 + p.TH && wi >= w0 && wi < w0 + p.TW;
   }
   if (FUSE != 0 && blockIdx.x == 0 && tid < p.pack_pad)  // zero the tail of the last 128-byte row
     static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + tid] = 0;
-
-  // LDS base of this lane's pixel in each of the wave's M-tiles
-  int base[MT];
-  {
-    Pos q;
-    int m = wave_m * MT * 16 + li;
-    q.init(m < p.npix ? m : p.npix - 1, p.TW, p.TH);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      base[i] = ((q.ti * p.HH + q.h) * p.HW + q.w) * PS + 4 * lk;
-      m += 16;
-      if (m < p.npix) q.advance(p.m_dw, p.m_dh, p.TW, p.TH);
-    }
-  }
-
-  floatx4 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   float4 ra[AMAX];
   // per-channel constants of the 4 channels this thread stages (fused forward)
@@ -165,8 +148,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 #pragma unroll
     for (int j = 0; j < AMAX; ++j) {
       const bool ok = goff[j] >= 0;
-      const float4 v = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
-      ra[j] = keep_if(ok, v);
+      ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
     }
     if (FUSE != 0) {
       const int c = c0 + 4 * (tid & 3);
@@ -184,9 +166,9 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     for (int j = 0; j < AMAX; ++j) {
       const int idx = tid + kThreads * j;
       if (idx < totalA) {
-        float4 v = ra[j];
+        const bool ok = goff[j] >= 0;
+        float4 v = keep_if(ok, ra[j]);
         if (FUSE != 0) {
-          const bool ok = goff[j] >= 0;
           const float xs[4] = {v.x, v.y, v.z, v.w};
           const float mean[4] = {k_mean.x, k_mean.y, k_mean.z, k_mean.w};
           const float rstd[4] = {k_rstd.x, k_rstd.y, k_rstd.z, k_rstd.w};
@@ -216,27 +198,47 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       }
     }
   };
-  // B fragment of this lane for chunk c0, tap t: k = c0 + 4*lk .. +3, column = its channel
-  auto fetch_b = [&](int c0, int t, float4 (&bf)[NT]) {
+  // Weight fragment of this lane for chunk c0, tap t: k = c0 + 4*lk .. +3 of output channel
+  // n0 + wn0 + 16j + li.  Channels past the last one re-read the last one (never stored), so the
+  // loaded registers go to the MFMAs untouched and no wait has to precede them.
+  auto fetch_b = [&](int c0, int t, float4 (&bf)[NT]) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      const int n = n0 + wn0 + 16 * j + li, c = c0 + 4 * lk;
-      const bool ok = n < Ng;
-      float4 v;
+      int n = n0 + wn0 + 16 * j + li;
+      n = n < Ng ? n : Ng - 1;
+      const int c = c0 + 4 * lk;
       if (MODE == 0) {
-        const float* src = ok ? wgt + ((int64_t)t * g.Cin + c) * g.Cout + n : wgt;
-        const int64_t ld = ok ? g.Cout : 0;
-        v = make_float4(src[0], src[ld], src[2 * ld], src[3 * ld]);
+        const float* src = wgt + ((int64_t)t * g.Cin + c) * g.Cout + n;
+        bf[j] = make_float4(src[0], src[g.Cout], src[2 * g.Cout], src[3 * g.Cout]);
       } else {
-        v = *reinterpret_cast<const float4*>(ok ? wgt + ((int64_t)t * g.Cin + n) * g.Cout + c : wgt);
+        bf[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)t * g.Cin + n) * g.Cout + c);
       }
-      bf[j] = keep_if(ok, v);
     }
   };
 
-  float4 bcur[NT], bnext[NT];
+  constexpr int HELD = UNROLL_TAPS ? 9 : 1;
+  float4 bw[HELD][NT], bnext[NT];
   fetch_a(0);
-  fetch_b(0, 0, bcur);
+#pragma unroll
+  for (int t = 0; t < HELD; ++t) fetch_b(0, t, bw[t]);
+
+  // LDS base of this lane's pixel in each of the wave's M-tiles
+  int base[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int m = wave_m * MT * 16 + 16 * i + li;
+    m = m < p.npix ? m : p.npix - 1;
+    int ti, h, w;
+    split3(m, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    base[i] = ((ti * p.HH + h) * p.HW + w) * PS + 4 * lk;
+  }
+
+  floatx4 acc[NT][MT];  // acc[j][i][r]: pixel 16i + li of the wave, channel 16j + 4lk + r
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[j][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
   stage_a(lds);
   __syncthreads();
   int buf = 0;
@@ -244,23 +246,33 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     const float* tileA = lds + buf * patch_floats;
     const bool more = c0 + 16 < Cg;
     if (more) fetch_a(c0 + 16);
-    auto tap_step = [&](int t, int r, int s) __attribute__((always_inline)) {
-      if (t + 1 < taps) fetch_b(c0, t + 1, bnext);
-      else if (more) fetch_b(c0 + 16, 0, bnext);
-      const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
-      const int aoff = (rr * p.HW + ss) * PS;
-      float4 af[MT];
-#pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
-      mma_k4<BF16, MT, NT>(af, bcur, acc);
-#pragma unroll
-      for (int j = 0; j < NT; ++j) bcur[j] = bnext[j];
-    };
     if (UNROLL_TAPS) {
 #pragma unroll
-      for (int t = 0; t < 9; ++t) tap_step(t, t / 3, t % 3);
+      for (int t = 0; t < 9; ++t) {
+        const int r = t / 3, s = t % 3;
+        const int rr = MODE == 0 ? r : 2 - r, ss = MODE == 0 ? s : 2 - s;
+        const int aoff = (rr * p.HW + ss) * PS;
+        float4 af[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+        mma_k4<BF16, NT, MT>(bw[t], af, acc);
+        if (more) fetch_b(c0 + 16, t, bw[t]);
+      }
     } else {
-      for (int t = 0; t < taps; ++t) tap_step(t, t / g.S, t % g.S);
+      int r = 0, s = 0;
+      for (int t = 0; t < taps; ++t) {
+        if (t + 1 < taps) fetch_b(c0, t + 1, bnext);
+        else if (more) fetch_b(c0 + 16, 0, bnext);
+        const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
+        const int aoff = (rr * p.HW + ss) * PS;
+        float4 af[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+        mma_k4<BF16, NT, MT>(bw[0], af, acc);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bw[0][j] = bnext[j];
+        if (++s == g.S) { s = 0; ++r; }
+      }
     }
     if (more) {
       stage_a(lds + (buf ^ 1) * patch_floats);
@@ -269,113 +281,112 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     }
   }
 
-  // epilogue: the lane holds pixels 4*lk .. 4*lk+3 of each M-tile, channel li of each N-tile.
-  // Output offsets first, then the shortcut values in one batch, then the stores.
+  // epilogue: the lane holds channels cb + 16j .. +3 (cb = n0 + wn0 + 4lk) of pixel 16i + li
   const bool reduce = epi.partial != nullptr;
-  double s1[NT], s2[NT];
-  float r_step[NT], r_beta[NT], r_ig[NT];
-  int32_t r_fb[NT];
+  const int cb = n0 + wn0 + 4 * lk;
+  double s1[NT][4], s2[NT][4];
+  float4 r_step[NT], r_beta[NT], r_ig[NT];
+  int4 r_fb[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    s1[j] = s2[j] = 0.0;
-    r_step[j] = r_beta[j] = r_ig[j] = 0.f;
-    r_fb[j] = 0;
-    const int c = n0 + wn0 + 16 * j + li;
-    if (MODE == 1 && reduce && c < Ng) {
-      r_step[j] = stats[P_STEP * Ng + c];
-      r_beta[j] = stats[P_BETA * Ng + c];
-      r_ig[j] = 1.0f / stats[P_GAMMA * Ng + c];
-      r_fb[j] = reinterpret_cast<const int32_t*>(stats)[P_FB * Ng + c];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = 0.0;
+    if (MODE == 1 && reduce) {
+      const int c = cb + 16 * j < Ng ? cb + 16 * j : 0;
+      r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * Ng + c);
+      r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * Ng + c);
+      const float4 gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * Ng + c);
+      r_ig[j] = make_float4(1.0f / gm.x, 1.0f / gm.y, 1.0f / gm.z, 1.0f / gm.w);
+      r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * Ng + c);
     }
   }
-  Pos e;
-  int m = wave_m * MT * 16 + 4 * lk;
-  e.init(m, p.TW, p.TH);
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    Pos q = e;
-    int64_t off[4];  // element offset of (pixel, channel 0 of this block), -1 = outside
+    const int m = wave_m * MT * 16 + 16 * i + li;
+    int ti, h, w;
+    split3(m, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
+    const bool pix_ok = m < p.npix && n < g.N && hq < Hq && wq < Wq;
+    const int64_t off = (((int64_t)n * Hq + hq) * Wq + wq) * Ng + cb;  // element (pixel, channel cb)
+    bool ok[NT];
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int n = img0 + q.ti, hq = h0 + q.h, wq = w0 + q.w;
-      const bool ok = m + rr < p.npix && n < g.N && hq < Hq && wq < Wq;
-      off[rr] = ok ? (((int64_t)n * Hq + hq) * Wq + wq) * Ng + n0 + wn0 + li : -1;
-      q.advance(1, 0, p.TW, p.TH);
-    }
+    for (int j = 0; j < NT; ++j) ok[j] = pix_ok && cb + 16 * j < Ng;
     if (skip != nullptr) {
-      float sv[4][NT];
+      float4 sv[NT];
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr)
+      for (int j = 0; j < NT; ++j) sv[j] = *reinterpret_cast<const float4*>(skip + (ok[j] ? off + 16 * j : 0));
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const bool ok = off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng;
-          sv[rr][j] = skip[ok ? off[rr] + 16 * j : 0];
-        }
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j][rr] += sv[rr][j];
+      for (int j = 0; j < NT; ++j) {
+        acc[j][i][0] += sv[j].x; acc[j][i][1] += sv[j].y; acc[j][i][2] += sv[j].z; acc[j][i][3] += sv[j].w;
+      }
     }
     if (reduce) {
       if (MODE == 0) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
+        for (int j = 0; j < NT; ++j)
+          if (ok[j]) {
 #pragma unroll
-          for (int j = 0; j < NT; ++j)
-            if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) {
-              const double v = (double)acc[i][j][rr];
-              s1[j] += v;
-              s2[j] += v * v;
+            for (int r = 0; r < 4; ++r) {
+              const double v = (double)acc[j][i][r];
+              s1[j][r] += v;
+              s2[j][r] += v * v;
             }
-      } else {
-        uint32_t code[4][NT];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
-#pragma unroll
-          for (int j = 0; j < NT; ++j) {
-            const bool ok = off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng;
-            const int64_t el = ok ? off[rr] + 16 * j : 0;
-            code[rr][j] = epi.K == 4 ? (epi.codes[el >> 1] >> ((el & 1) * 4)) & 15u : epi.codes[el];
           }
+      } else {
+        uint32_t cw[NT];  // the K-bit codes of the lane's 4 channels
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
+        for (int j = 0; j < NT; ++j) {
+          const int64_t el = ok[j] ? off + 16 * j : 0;
+          cw[j] = epi.K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(epi.codes + (el >> 1))
+                             : *reinterpret_cast<const uint32_t*>(epi.codes + el);
+        }
 #pragma unroll
-          for (int j = 0; j < NT; ++j)
-            if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) {
-              const int32_t jj = (int32_t)code[rr][j] - (1 << (epi.K - 1)) + r_fb[j];
-              const float a2t = r_step[j] * ((float)jj + 0.5f);               // Eq. 10
-              const float da2 = a2t > 0.0f ? acc[i][j][rr] : 0.0f;           // Eq. 6
-              const float a1t = (a2t - r_beta[j]) * r_ig[j];                 // inverse of Eq. 2
-              s1[j] += (double)da2;
-              s2[j] += (double)a1t * (double)da2;
+        for (int j = 0; j < NT; ++j)
+          if (ok[j]) {
+            const float st4[4] = {r_step[j].x, r_step[j].y, r_step[j].z, r_step[j].w};
+            const float bt4[4] = {r_beta[j].x, r_beta[j].y, r_beta[j].z, r_beta[j].w};
+            const float ig4[4] = {r_ig[j].x, r_ig[j].y, r_ig[j].z, r_ig[j].w};
+            const int32_t fb4[4] = {r_fb[j].x, r_fb[j].y, r_fb[j].z, r_fb[j].w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint32_t code = (cw[j] >> (epi.K * r)) & ((1u << epi.K) - 1u);
+              const int32_t jj = (int32_t)code - (1 << (epi.K - 1)) + fb4[r];
+              const float a2t = st4[r] * ((float)jj + 0.5f);                   // Eq. 10
+              const float da2 = a2t > 0.0f ? acc[j][i][r] : 0.0f;             // Eq. 6
+              const float a1t = (a2t - bt4[r]) * ig4[r];                      // inverse of Eq. 2
+              s1[j][r] += (double)da2;
+              s2[j][r] += (double)a1t * (double)da2;
             }
+          }
       }
     }
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-        if (off[rr] >= 0 && n0 + wn0 + 16 * j + li < Ng) out[off[rr] + 16 * j] = acc[i][j][rr];
-    m += 16;
-    e.advance(p.m_dw, p.m_dh, p.TW, p.TH);
+    for (int j = 0; j < NT; ++j)
+      if (ok[j])
+        *reinterpret_cast<float4*>(out + off + 16 * j) =
+            make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
   }
   if (reduce) {
-    // the lane groups and the waves that share a channel are summed in a fixed order through LDS
-    constexpr int R = WAVES_M * 4;
+    // fixed order: the 16 pixels of a row of lanes by a butterfly, then the waves that share a
+    // channel through LDS
     __syncthreads();  // every wave is done with the patch
-    double* red = reinterpret_cast<double*>(lds);  // [2][R][BN]
-    const int rs = wave_m * 4 + lk;
+    double* red = reinterpret_cast<double*>(lds);  // [2][WAVES_M][BN]
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      red[(0 * R + rs) * BN + wn0 + 16 * j + li] = s1[j];
-      red[(1 * R + rs) * BN + wn0 + 16 * j + li] = s2[j];
-    }
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const double t1 = row16_sum(s1[j][r]), t2 = row16_sum(s2[j][r]);
+        if (li == 0) {
+          red[(0 * WAVES_M + wave_m) * BN + wn0 + 16 * j + 4 * lk + r] = t1;
+          red[(1 * WAVES_M + wave_m) * BN + wn0 + 16 * j + 4 * lk + r] = t2;
+        }
+      }
     __syncthreads();
     for (int c = tid; c < 2 * BN; c += kThreads) {
       const int qv = c / BN, ch = c % BN;
       double t = 0.0;
 #pragma unroll
-      for (int k = 0; k < R; ++k) t += red[(qv * R + k) * BN + ch];
+      for (int k = 0; k < WAVES_M; ++k) t += red[(qv * WAVES_M + k) * BN + ch];
       if (n0 + ch < Ng) epi.partial[((int64_t)tile_id * 2 + qv) * Ng + n0 + ch] = t;
     }
   }
@@ -434,8 +445,9 @@ void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
   p.tiles_w = cdiv(Wq, p.TW);
   p.npix = p.TI * p.TH * p.TW;
   p.mtiles = cdiv(p.npix, 16);
-  p.a_dw = 64 % p.HW; p.a_dh = 64 / p.HW;
-  p.m_dw = 16 % p.TW; p.m_dh = 16 / p.TW;
+  auto inv = [](int d) { return (unsigned)(((1ull << 32) + d - 1) / d); };  // unused for d == 1
+  p.inv_HW = inv(p.HW); p.inv_HH = inv(p.HH);
+  p.inv_TW = inv(p.TW); p.inv_TH = inv(p.TH);
 }
 
 bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
