@@ -25,6 +25,12 @@ constexpr int kThreads = 256;
 constexpr int PS = 20;     // floats per staged pixel: 16 channels + 4 pad (conflict-free b128 reads)
 constexpr int AMAX = 6;    // float4 slots per thread for the input patch (<= 384 staged pixels)
 
+// A step of a fixed number of cells through a [.. x height x width] box, split into digits
+// (w < width, h < height), so that advancing a position carries at most once per digit.
+struct BoxStep {
+  int w, h, ti;
+};
+
 struct HaloPlan {
   int TI, TH, TW;                 // output tile: images, rows, cols
   int HH, HW;                     // staged patch rows, cols
@@ -33,7 +39,11 @@ struct HaloPlan {
   int mtiles;                     // ceil(npix / 16)
   int variant;                    // index into the instantiation table
   int bn;                         // output channels per block
-  unsigned inv_HW, inv_HH, inv_TW, inv_TH;  // ceil(2^32 / d): exact quotients for operands < 2^16
+  unsigned inv_HW, inv_HH, inv_TW, inv_TH;  // ceil(2^32 / d): exact quotient x/d while x*d < 2^32
+  unsigned inv_tiles_w, inv_tiles_h;
+  unsigned nblk_n, inv_nblk_n;    // blocks along the output channels
+  BoxStep a_step;                 // 64 patch pixels further, as (cols, rows, images) of the patch
+  BoxStep m_step;                 // 16 tile pixels further, as (cols, rows, images) of the tile
   unsigned lds_bytes;
   int pack_pad;                   // zero bytes after the last code (fused forward only)
 };
@@ -56,6 +66,30 @@ __device__ inline void split3(int idx, int width, unsigned inv_w, int height, un
   ti = height == 1 ? q : (int)__umulhi((unsigned)q, inv_h);
   h = q - ti * height;
 }
+
+__device__ inline unsigned udiv(unsigned x, unsigned d, unsigned inv) { return d == 1 ? x : __umulhi(x, inv); }
+
+__device__ inline void box_advance(int& w, int& h, int& ti, const BoxStep& s, int width, int height) {
+  w += s.w;
+  const int cw = w >= width ? 1 : 0;
+  w -= cw ? width : 0;
+  h += s.h + cw;
+  const int ch = h >= height ? 1 : 0;
+  h -= ch ? height : 0;
+  ti += s.ti + ch;
+}
+
+// A block-uniform value held in a vector register.  The kernels below have more uniform state
+// than scalar registers; what the unrolled per-lane index arithmetic uses again and again is
+// moved to vector registers once, or the compiler re-loads it from the argument block (a
+// scalar-cache round trip) at every use.
+__device__ inline int in_vgpr(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
+// a * b + c for operands below 2^23 in magnitude (full-rate 24-bit multiplier)
+__device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 
 // Sum over the 16 lanes of a row (lanes that differ in bits 0-3); every lane gets the total.
 __device__ inline double row16_sum(double v) {
@@ -92,6 +126,16 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int WAVES_M = 4 / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
+  // Everything the set-up below reads from the argument block is requested here, in one batch
+  // with one wait; left alone, the compiler fetches it field by field where it is first used and
+  // the wave pays a scalar-cache round trip each time.
+  asm volatile("" ::"s"(in), "s"(wgt), "s"(g.N), "s"(g.H), "s"(g.W), "s"(g.Cin), "s"(g.Cout), "s"(g.R), "s"(g.S),
+               "s"(g.pad), "s"(g.Ho), "s"(g.Wo), "s"(p.TI), "s"(p.TH), "s"(p.TW), "s"(p.HH), "s"(p.HW),
+               "s"(p.tiles_i), "s"(p.tiles_h), "s"(p.tiles_w), "s"(p.npix), "s"(p.inv_HW), "s"(p.inv_HH),
+               "s"(p.inv_TW), "s"(p.inv_TH), "s"(p.inv_tiles_w), "s"(p.inv_tiles_h), "s"(p.nblk_n),
+               "s"(p.inv_nblk_n));
+  asm volatile("" ::"s"(p.a_step.w), "s"(p.a_step.h), "s"(p.a_step.ti), "s"(p.m_step.w), "s"(p.m_step.h),
+               "s"(p.m_step.ti));
   const int taps = g.R * g.S;
   const int patch_floats = p.TI * p.HH * p.HW * PS;
 
@@ -107,32 +151,55 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 
   // ids 8 apart share an XCD (and its L2): the blocks that contract the same pixel tile against
   // different output-channel blocks run there back to back
-  const int nblk_n = (Ng + BN - 1) / BN;
-  const int slot = blockIdx.x >> 3;
-  const int tile_id = (slot / nblk_n) * 8 + (blockIdx.x & 7);
-  int b = tile_id;
-  if (b >= p.tiles_i * p.tiles_h * p.tiles_w) return;
-  const int tw_i = b % p.tiles_w; b /= p.tiles_w;
-  const int th_i = b % p.tiles_h; b /= p.tiles_h;
-  const int img0 = b * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
-  const int n0 = (slot % nblk_n) * BN;
+  const unsigned slot = blockIdx.x >> 3;
+  const unsigned sq = udiv(slot, p.nblk_n, p.inv_nblk_n);
+  const int tile_id = sq * 8 + (blockIdx.x & 7);
+  if (tile_id >= p.tiles_i * p.tiles_h * p.tiles_w) return;
+  const unsigned t1 = udiv(tile_id, p.tiles_w, p.inv_tiles_w);
+  const unsigned t2 = udiv(t1, p.tiles_h, p.inv_tiles_h);
+  const int tw_i = tile_id - t1 * p.tiles_w, th_i = t1 - t2 * p.tiles_h;
+  const int img0 = t2 * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
+  const int n0 = (slot - sq * p.nblk_n) * BN;
   // input coordinate of patch element (0,0)
   const int oh = h0 + (MODE == 0 ? -g.pad : g.pad - (g.R - 1));
   const int ow = w0 + (MODE == 0 ? -g.pad : g.pad - (g.S - 1));
 
-  // global offsets (in floats, channel 0) of the patch elements this thread stages; -1 = zero fill
+  // global offsets (in floats, channel 0) of the patch elements this thread stages; -1 = zero
+  // fill, -2 = past the end of the patch.  Kept as numbers in vector registers: per-slot
+  // predicates would each occupy a pair of scalar registers for the whole kernel.
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AMAX];
-  bool own[AMAX];  // fused forward: this block writes the codes of the element
-#pragma unroll
-  for (int j = 0; j < AMAX; ++j) {
-    const int idx = tid + kThreads * j;
+  unsigned ownbits = 0;  // fused forward: bit j = this block writes the codes of slot j
+  {
     int ti, h, w;
-    split3(idx >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
-    const int n = img0 + ti, hi = oh + h, wi = ow + w;
-    const bool ok = idx < totalA && n < g.N && hi >= 0 && hi < Hi && wi >= 0 && wi < Wi;
-    goff[j] = ok ? ((n * Hi + hi) * Wi + wi) * Cg + 4 * (idx & 3) : -1;
-    own[j] = FUSE != 0 && ok && n0 == 0 && hi >= h0 && hi < h0 + p.TH && wi >= w0 && wi < w0 + p.TW;
+    split3(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
+    // position in the input instead of in the patch
+    ti += img0; h += oh; w += ow;
+    const BoxStep step{in_vgpr(p.a_step.w), in_vgpr(p.a_step.h), in_vgpr(p.a_step.ti)};
+    const int width = in_vgpr(p.HW), height = in_vgpr(p.HH);
+    const int w_end = in_vgpr(ow + p.HW), h_end = in_vgpr(oh + p.HH);
+    const int vN = in_vgpr(g.N), vHi = in_vgpr(Hi), vWi = in_vgpr(Wi), vCg = in_vgpr(Cg);
+    const int vtotal = in_vgpr(totalA);
+    const int vh0 = in_vgpr(h0), vw0 = in_vgpr(w0), vTH = in_vgpr(p.TH), vTW = in_vgpr(p.TW);
+    const int c4 = 4 * (tid & 3);
+#pragma unroll
+    for (int j = 0; j < AMAX; ++j) {
+      const int idx = tid + kThreads * j;
+      const bool ok = idx < vtotal && ti < vN && (unsigned)h < (unsigned)vHi && (unsigned)w < (unsigned)vWi;
+      goff[j] = ok ? mad24(mad24(mad24(ti, vHi, h), vWi, w), vCg, c4) : (idx < vtotal ? -1 : -2);
+      if (FUSE != 0) {
+        const bool own = ok && n0 == 0 && (unsigned)(h - vh0) < (unsigned)vTH && (unsigned)(w - vw0) < (unsigned)vTW;
+        ownbits |= (own ? 1u : 0u) << j;
+      }
+      // 64 patch pixels further
+      w += step.w;
+      const bool cw = w >= w_end;
+      w -= cw ? width : 0;
+      h += step.h + (cw ? 1 : 0);
+      const bool ch = h >= h_end;
+      h -= ch ? height : 0;
+      ti += step.ti + (ch ? 1 : 0);
+    }
   }
   if (FUSE != 0 && blockIdx.x == 0 && tid < p.pack_pad)  // zero the tail of the last 128-byte row
     static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + tid] = 0;
@@ -165,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 #pragma unroll
     for (int j = 0; j < AMAX; ++j) {
       const int idx = tid + kThreads * j;
-      if (idx < totalA) {
+      if (goff[j] != -2) {
         const bool ok = goff[j] >= 0;
         float4 v = keep_if(ok, ra[j]);
         if (FUSE != 0) {
@@ -188,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
             word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2, cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
           }
           v = make_float4(a3[0], a3[1], a3[2], a3[3]);
-          if (own[j]) {
+          if ((ownbits >> j) & 1u) {
             const int64_t e0 = (int64_t)goff[j] + k_c0;  // flat element index of the first of 4 codes
             if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
             else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
@@ -201,17 +268,23 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // Weight fragment of this lane for chunk c0, tap t: k = c0 + 4*lk .. +3 of output channel
   // n0 + wn0 + 16j + li.  Channels past the last one re-read the last one (never stored), so the
   // loaded registers go to the MFMAs untouched and no wait has to precede them.
+  int boff[NT];  // lane part of the fragment address: (k = 4lk, its channel) of chunk 0, tap 0
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int n = n0 + wn0 + 16 * j + li;
+    n = n < Ng ? n : Ng - 1;
+    boff[j] = MODE == 0 ? mad24(4 * lk, g.Cout, n) : mad24(n, g.Cout, 4 * lk);
+  }
   auto fetch_b = [&](int c0, int t, float4 (&bf)[NT]) __attribute__((always_inline)) {
+    // uniform part: tap t, chunk c0
+    const float* src = wgt + (int64_t)t * g.Cin * g.Cout + (MODE == 0 ? (int64_t)c0 * g.Cout : c0);
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      int n = n0 + wn0 + 16 * j + li;
-      n = n < Ng ? n : Ng - 1;
-      const int c = c0 + 4 * lk;
       if (MODE == 0) {
-        const float* src = wgt + ((int64_t)t * g.Cin + c) * g.Cout + n;
-        bf[j] = make_float4(src[0], src[g.Cout], src[2 * g.Cout], src[3 * g.Cout]);
+        const float* q = src + boff[j];
+        bf[j] = make_float4(q[0], q[g.Cout], q[2 * g.Cout], q[3 * g.Cout]);
       } else {
-        bf[j] = *reinterpret_cast<const float4*>(wgt + ((int64_t)t * g.Cin + n) * g.Cout + c);
+        bf[j] = *reinterpret_cast<const float4*>(src + boff[j]);
       }
     }
   };
@@ -224,13 +297,19 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 
   // LDS base of this lane's pixel in each of the wave's M-tiles
   int base[MT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    int m = wave_m * MT * 16 + 16 * i + li;
-    m = m < p.npix ? m : p.npix - 1;
+  const BoxStep mstep{in_vgpr(p.m_step.w), in_vgpr(p.m_step.h), in_vgpr(p.m_step.ti)};
+  const int vTW = in_vgpr(p.TW), vTH = in_vgpr(p.TH), vnpix = in_vgpr(p.npix);
+  {
+    const int m0 = wave_m * MT * 16 + li;
     int ti, h, w;
-    split3(m, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
-    base[i] = ((ti * p.HH + h) * p.HW + w) * PS + 4 * lk;
+    split3(m0, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    const int vHH = in_vgpr(p.HH), vHW = in_vgpr(p.HW);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      // lanes past the last pixel read the first one (their results are not stored)
+      base[i] = m0 + 16 * i < vnpix ? mad24(mad24(mad24(ti, vHH, h), vHW, w), PS, 4 * lk) : 4 * lk;
+      box_advance(w, h, ti, mstep, vTW, vTH);
+    }
   }
 
   floatx4 acc[NT][MT];  // acc[j][i][r]: pixel 16i + li of the wave, channel 16j + 4lk + r
@@ -300,14 +379,17 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * Ng + c);
     }
   }
+  int e_ti, e_h, e_w;
+  split3(wave_m * MT * 16 + li, p.TW, p.inv_TW, p.TH, p.inv_TH, e_ti, e_h, e_w);
+  const int vN = in_vgpr(g.N), vHq = in_vgpr(Hq), vWq = in_vgpr(Wq), vNg = in_vgpr(Ng);
+  const int vimg0 = in_vgpr(img0), vh0 = in_vgpr(h0), vw0 = in_vgpr(w0);
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     const int m = wave_m * MT * 16 + 16 * i + li;
-    int ti, h, w;
-    split3(m, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
-    const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
-    const bool pix_ok = m < p.npix && n < g.N && hq < Hq && wq < Wq;
-    const int64_t off = (((int64_t)n * Hq + hq) * Wq + wq) * Ng + cb;  // element (pixel, channel cb)
+    const int n = vimg0 + e_ti, hq = vh0 + e_h, wq = vw0 + e_w;
+    const bool pix_ok = m < vnpix && n < vN && hq < vHq && wq < vWq;
+    const int off = mad24(mad24(mad24(n, vHq, hq), vWq, wq), vNg, cb);  // element (pixel, channel cb)
+    box_advance(e_w, e_h, e_ti, mstep, vTW, vTH);
     bool ok[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) ok[j] = pix_ok && cb + 16 * j < Ng;
@@ -336,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         uint32_t cw[NT];  // the K-bit codes of the lane's 4 channels
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-          const int64_t el = ok[j] ? off + 16 * j : 0;
+          const int el = ok[j] ? off + 16 * j : 0;
           cw[j] = epi.K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(epi.codes + (el >> 1))
                              : *reinterpret_cast<const uint32_t*>(epi.codes + el);
         }
@@ -448,6 +530,16 @@ void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
   auto inv = [](int d) { return (unsigned)(((1ull << 32) + d - 1) / d); };  // unused for d == 1
   p.inv_HW = inv(p.HW); p.inv_HH = inv(p.HH);
   p.inv_TW = inv(p.TW); p.inv_TH = inv(p.TH);
+  p.inv_tiles_w = inv(p.tiles_w); p.inv_tiles_h = inv(p.tiles_h);
+  auto digits = [](int cells, int width, int height) {
+    BoxStep b;
+    b.w = cells % width;
+    b.h = (cells / width) % height;
+    b.ti = cells / width / height;
+    return b;
+  };
+  p.a_step = digits(64, p.HW, p.HH);
+  p.m_step = digits(16, p.TW, p.TH);
 }
 
 bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
@@ -465,6 +557,11 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   choose_tile(Hq, Wq, g.N, g.R, g.S, waves_m * var.mt * 16, p);
   p.variant = v;
   p.bn = var.waves_n * var.nt * 16;
+  p.nblk_n = (unsigned)cdiv(Ng, p.bn);
+  p.inv_nblk_n = (unsigned)(((1ull << 32) + p.nblk_n - 1) / p.nblk_n);
+  // 24-bit index arithmetic and multiply-high divisions in the kernel
+  const int64_t pixels = (int64_t)g.N * (g.H > g.Ho ? g.H : g.Ho) * (g.W > g.Wo ? g.W : g.Wo);
+  if (pixels >= (1 << 23) || pixels * (g.Cin > g.Cout ? g.Cin : g.Cout) >= (1ll << 31)) return false;
   const int Cg = mode == 0 ? g.Cin : g.Cout;
   const size_t fl = (size_t)p.TI * p.HH * p.HW * PS * (Cg > 16 ? 2 : 1);
   p.lds_bytes = (unsigned)(fl * sizeof(float));
@@ -476,7 +573,7 @@ void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool b
                     const float* skip, float* out, const float* stats, void* packed, const EpiReduce& epi) {
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
-  dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * cdiv(Ng, p.bn));
+  dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * p.nblk_n);
   const bool unroll = g.R == 3 && g.S == 3 && var.mt * var.nt <= 4;
   auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true, FUSE>
                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
