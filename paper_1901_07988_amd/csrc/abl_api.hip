@@ -241,6 +241,12 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   const ConvGeom g = geom_of(*s);
   // Stride-1 convolutions with a filter larger than 1x1 take the Eq. 6-7 sums in the epilogue of
   // the dgrad kernel (dA3 is still in registers there), which saves the reduce pass over dA3.
+  // 16-channel 3x3 layers: both contractions and the Eq. 6-7 sums in one kernel
+  if (const int t16 = halo_bwd16_tiles(g)) {
+    if (int e = launch_halo_bwd16(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red), wpart, dW))
+      return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta);
+  }
   const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))

@@ -78,6 +78,14 @@ size_t halo_wgrad_partial_bytes(const ConvGeom& g);
 int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                       const float* dy, void* scratch, float* dw);
 
+// Whole conv backward of a 3x3 'same' stride-1 layer with 16 input and 16 output channels:
+// dA3, the Eq. 6-7 partial sums ([tiles][2][16] doubles) and dW in one pass over dy and the codes.
+// halo_bwd16_tiles returns 0 when the shape is not supported.  wscratch: as for launch_halo_wgrad.
+int halo_bwd16_tiles(const ConvGeom& g);
+int launch_halo_bwd16(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy, const float* w,
+                      const void* packed, const void* stats, float* da3, double* partial, void* wscratch,
+                      float* dw);
+
 // ---- convolution kernels (conv_kernels.hip) ----
 size_t wgrad_partial_bytes(const abl_shape& s);
 int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,

@@ -808,6 +808,240 @@ bool make_wgrad_plan(const ConvGeom& g, WgradHaloPlan& wp) {
   return true;
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Backward of a 3x3 'same' stride-1 layer with 16 input and 16 output channels in ONE kernel:
+// the gradient to the conv input (Eq. 5) with its Eq. 6-7 sums, and the weight gradient (Eq. 5)
+// from the packed activation.  Both contractions consume dy; a block stages the dy patch of its
+// pixel tile and the dequantized, ReLU'd activation patch (Eq. 10, Eq. 3) once, in the same
+// geometry, and runs the two sets of MFMAs from them:
+//   dA3[p, ci]      = sum_t sum_co dy[p + pad - t, co] W[t, ci, co]    (A = W, B = dy patch)
+//   dW[t, ci, co]  += sum_p A3~[p + t - pad, ci] dy[p, co]              (A = A3~ patch, B = dy)
+// The Eq. 6-7 sums take the mask and A1~ from the staged activation, so the codes are read from
+// memory once.  At 16 channels the per-block fixed costs (index set-up, the first loads, the
+// epilogues) outweigh the MFMAs; sharing them between the two contractions halves them.
+// Outputs per pixel tile: partial[tile][2][16] doubles, wpartial[tile][3][3][16][16] floats.
+template <int K, bool BF16>
+__global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __restrict__ dy,
+                                                              const float* __restrict__ wgt,
+                                                              const uint8_t* __restrict__ packed,
+                                                              const float* __restrict__ stats,
+                                                              float* __restrict__ da3, double* __restrict__ partial,
+                                                              float* __restrict__ wpartial, ConvGeom g, HaloPlan p) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  constexpr int C = 16;
+  asm volatile("" ::"s"(dy), "s"(wgt), "s"(packed), "s"(stats), "s"(g.N), "s"(g.H), "s"(g.W), "s"(p.TI), "s"(p.TH),
+               "s"(p.TW), "s"(p.HH), "s"(p.HW), "s"(p.tiles_h), "s"(p.tiles_w), "s"(p.npix), "s"(p.inv_HW),
+               "s"(p.inv_HH), "s"(p.inv_TW), "s"(p.inv_TH), "s"(p.inv_tiles_w), "s"(p.inv_tiles_h),
+               "s"(p.a_step.w), "s"(p.a_step.h), "s"(p.a_step.ti));
+  const int patch = p.TI * p.HH * p.HW;
+  float* tdy = lds;                                       // [patch][PS] dy
+  float* tact = lds + patch * PS;                         // [patch][PS] A3~
+  // the two patches are reused for the cross-wave sum of dW (4 x 9 x 256 floats) at the end
+  const int region = 2 * patch * PS > 4 * 9 * 256 ? 2 * patch * PS : 4 * 9 * 256;
+  int* pixbase = reinterpret_cast<int*>(lds + region);    // [256] LDS offset of tile pixel m, tap (0,0)
+  int* pixoff = pixbase + kThreads;                       // [256] global offset of (pixel m, channel 0), -1 outside
+  double* red = reinterpret_cast<double*>(pixoff + kThreads);  // [2][4][16]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lk = lane >> 4;
+  const int tile = blockIdx.x;
+  const unsigned t1 = udiv(tile, p.tiles_w, p.inv_tiles_w);
+  const unsigned t2 = udiv(t1, p.tiles_h, p.inv_tiles_h);
+  const int img0 = t2 * p.TI, h0 = (t1 - t2 * p.tiles_h) * p.TH, w0 = (tile - t1 * p.tiles_w) * p.TW;
+  const int oh = h0 - 1, ow = w0 - 1;  // image coordinate of patch element (0,0), both patches
+
+  // table entry of tile pixel m = tid
+  {
+    int ti, h, w;
+    split3(tid, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    const bool in_tile = tid < p.npix;
+    const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
+    pixbase[tid] = in_tile ? mad24(mad24(mad24(ti, p.HH, h), p.HW, w), PS, 0) : 0;
+    pixoff[tid] = in_tile && n < g.N && hq < g.H && wq < g.W ? mad24(mad24(mad24(n, g.H, hq), g.W, wq), C, 0) : -1;
+  }
+
+  // global element offsets of the patch elements this thread stages (4 channels each); -1 = zero
+  // fill, -2 = past the end of the patch
+  const int totalA = patch * 4;
+  int goff[AMAX];
+  {
+    int ti, h, w;
+    split3(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
+    ti += img0; h += oh; w += ow;
+    const BoxStep step{in_vgpr(p.a_step.w), in_vgpr(p.a_step.h), in_vgpr(p.a_step.ti)};
+    const int width = in_vgpr(p.HW), height = in_vgpr(p.HH);
+    const int w_end = in_vgpr(ow + p.HW), h_end = in_vgpr(oh + p.HH);
+    const int vN = in_vgpr(g.N), vH = in_vgpr(g.H), vW = in_vgpr(g.W), vtotal = in_vgpr(totalA);
+    const int c4 = 4 * (tid & 3);
+#pragma unroll
+    for (int j = 0; j < AMAX; ++j) {
+      const int idx = tid + kThreads * j;
+      const bool ok = idx < vtotal && ti < vN && (unsigned)h < (unsigned)vH && (unsigned)w < (unsigned)vW;
+      goff[j] = ok ? mad24(mad24(mad24(ti, vH, h), vW, w), C, c4) : (idx < vtotal ? -1 : -2);
+      w += step.w;
+      const bool cw = w >= w_end;
+      w -= cw ? width : 0;
+      h += step.h + (cw ? 1 : 0);
+      const bool ch = h >= h_end;
+      h -= ch ? height : 0;
+      ti += step.ti + (ch ? 1 : 0);
+    }
+  }
+
+  // all loads of the block in one batch: dy, the codes of the same elements, the weight fragments
+  float4 rd[AMAX];
+  uint32_t rc[AMAX];
+#pragma unroll
+  for (int j = 0; j < AMAX; ++j) {
+    const int e0 = goff[j] >= 0 ? goff[j] : 0;
+    rd[j] = *reinterpret_cast<const float4*>(dy + e0);
+    rc[j] = K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(packed + (e0 >> 1))
+                   : *reinterpret_cast<const uint32_t*>(packed + e0);
+  }
+  const int c4 = 4 * (tid & 3);
+  const float4 q_step = *reinterpret_cast<const float4*>(stats + P_STEP * C + c4);
+  const int4 q_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + c4);
+  // dgrad weight fragment: k = co = 4lk .. +3, row = ci = li
+  float4 bw[9][1];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+    bw[t][0] = *reinterpret_cast<const float4*>(wgt + (t * C + li) * C + 4 * lk);
+
+#pragma unroll
+  for (int j = 0; j < AMAX; ++j) {
+    const int idx = tid + kThreads * j;
+    if (goff[j] != -2) {
+      const bool ok = goff[j] >= 0;
+      const float st4[4] = {q_step.x, q_step.y, q_step.z, q_step.w};
+      const int32_t fb4[4] = {q_fb.x, q_fb.y, q_fb.z, q_fb.w};
+      float a[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a2t = dequant<K>((rc[j] >> (K * e)) & ((1u << K) - 1u), st4[e], fb4[e]);  // Eq. 10
+        a[e] = (ok && a2t > 0.0f) ? a2t : 0.0f;                                              // Eq. 3
+      }
+      const int o = (idx >> 2) * PS + 4 * (idx & 3);
+      *reinterpret_cast<float4*>(&tdy[o]) = keep_if(ok, rd[j]);
+      *reinterpret_cast<float4*>(&tact[o]) = make_float4(a[0], a[1], a[2], a[3]);
+    }
+  }
+  __syncthreads();
+
+  const int ctr = (p.HW + 1) * PS;  // from tap (0,0) to the pixel itself
+  // ---- dA3 tile: 4 M-tiles of 16 pixels per wave, transposed output (lane = pixel li, channels 4lk..) ----
+  floatx4 accd[1][4];
+  int mbase[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    accd[0][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    mbase[i] = pixbase[wave * 64 + 16 * i + li];
+  }
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int aoff = ((2 - t / 3) * p.HW + (2 - t % 3)) * PS + 4 * lk;
+    float4 af[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const float4*>(&tdy[mbase[i] + aoff]);
+    mma_k4<BF16, 1, 4>(bw[t], af, accd);
+  }
+
+  // ---- dW: the wave's 64 pixels, 16 per step; component e of the operand vectors is pixel
+  // 4e + lk of the step (fp32: k-step e, lane group = k) or 4lk + e (bf16) ----
+  floatx4 accw[9][1][1];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) accw[t][0][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int q = 0; q < 4; ++q) {
+    int pb[4];
+    float bv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int m = wave * 64 + 16 * q + (BF16 ? 4 * lk + e : 4 * e + lk);
+      pb[e] = pixbase[m] + li;
+      // pixels that are not part of the tile or the image contribute nothing
+      bv[e] = pixoff[m] >= 0 ? tdy[pb[e] + ctr] : 0.0f;
+    }
+    const float4 bf[1] = {make_float4(bv[0], bv[1], bv[2], bv[3])};
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      const int toff = ((t / 3) * p.HW + (t % 3)) * PS;
+      const float4 a[1] = {make_float4(tact[pb[0] + toff], tact[pb[1] + toff], tact[pb[2] + toff], tact[pb[3] + toff])};
+      mma_k4<BF16, 1, 1>(a, bf, accw[t]);
+    }
+  }
+
+  // ---- epilogue of dA3: store, and the Eq. 6-7 sums with mask and A1~ from the staged activation ----
+  {
+    const float4 e_beta = *reinterpret_cast<const float4*>(stats + P_BETA * C + 4 * lk);
+    const float4 e_gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * C + 4 * lk);
+    const float bt4[4] = {e_beta.x, e_beta.y, e_beta.z, e_beta.w};
+    const float ig4[4] = {1.0f / e_gm.x, 1.0f / e_gm.y, 1.0f / e_gm.z, 1.0f / e_gm.w};
+    double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int off = pixoff[wave * 64 + 16 * i + li];
+      const float4 a3 = *reinterpret_cast<const float4*>(&tact[mbase[i] + ctr + 4 * lk]);
+      const float a3t[4] = {a3.x, a3.y, a3.z, a3.w};
+      if (off >= 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float da2 = a3t[r] > 0.0f ? accd[0][i][r] : 0.0f;  // Eq. 6
+          const float a1t = (a3t[r] - bt4[r]) * ig4[r];             // inverse of Eq. 2
+          s1[r] += (double)da2;
+          s2[r] += (double)a1t * (double)da2;
+        }
+        *reinterpret_cast<float4*>(da3 + off + 4 * lk) =
+            make_float4(accd[0][i][0], accd[0][i][1], accd[0][i][2], accd[0][i][3]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const double u1 = row16_sum(s1[r]), u2 = row16_sum(s2[r]);
+      if (li == 0) {
+        red[(0 * 4 + wave) * C + 4 * lk + r] = u1;
+        red[(1 * 4 + wave) * C + 4 * lk + r] = u2;
+      }
+    }
+  }
+  __syncthreads();  // every wave is done with the patches
+  if (tid < 2 * C) {
+    const int qv = tid / C, ch = tid % C;
+    const double t = ((red[(qv * 4 + 0) * C + ch] + red[(qv * 4 + 1) * C + ch]) + red[(qv * 4 + 2) * C + ch]) +
+                     red[(qv * 4 + 3) * C + ch];
+    partial[((int64_t)tile * 2 + qv) * C + ch] = t;
+  }
+  // ---- dW: the four waves are summed in order through LDS; wred[wave][t][ci][co] ----
+  float* wred = lds;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) wred[(wave * 9 + t) * 256 + (4 * lk + r) * C + li] = accw[t][0][0][r];
+  __syncthreads();
+  float* dst = wpartial + (int64_t)tile * (9 * C * C);
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    const int idx = tid + kThreads * k;
+    dst[idx] = ((wred[idx] + wred[2304 + idx]) + wred[2 * 2304 + idx]) + wred[3 * 2304 + idx];
+  }
+}
+
+bool make_bwd16_plan(const ConvGeom& g, HaloPlan& p) {
+  if (g.stride != 1 || g.R != 3 || g.S != 3 || g.pad != 1 || g.Cin != 16 || g.Cout != 16) return false;
+  const int64_t pixels = (int64_t)g.N * g.H * g.W;
+  if (pixels >= (1 << 23)) return false;  // 24-bit index arithmetic
+  choose_tile(g.H, g.W, g.N, 3, 3, 256, p);
+  if (p.TH <= 0) return false;
+  const int tiles = p.tiles_i * p.tiles_h * p.tiles_w;
+  if (tiles > kMaxPartialBlocks) return false;
+  size_t bytes = (size_t)2 * p.TI * p.HH * p.HW * PS * sizeof(float);
+  const size_t wred = (size_t)4 * 9 * 256 * sizeof(float);
+  if (bytes < wred) bytes = wred;
+  bytes += 2 * kThreads * sizeof(int) + 2 * 4 * 16 * sizeof(double);
+  p.lds_bytes = (unsigned)bytes;
+  return bytes <= 64 * 1024;
+}
+
 }  // namespace
 
 bool halo_conv_supported(const ConvGeom& g) {
@@ -871,7 +1105,11 @@ namespace abl {
 size_t halo_wgrad_partial_bytes(const ConvGeom& g) {
   WgradHaloPlan wp;
   if (!make_wgrad_plan(g, wp)) return 0;
-  return ((size_t)wp.nblk * g.R * g.S * g.Cin * g.Cout * sizeof(float) + 255) / 256 * 256;
+  size_t copies = (size_t)wp.nblk;
+  HaloPlan p;  // the fused backward kernel keeps one copy per pixel tile
+  if (make_bwd16_plan(g, p) && (size_t)p.tiles_i * p.tiles_h * p.tiles_w > copies)
+    copies = (size_t)p.tiles_i * p.tiles_h * p.tiles_w;
+  return (copies * g.R * g.S * g.Cin * g.Cout * sizeof(float) + 255) / 256 * 256;
 }
 
 int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
@@ -897,6 +1135,29 @@ int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
     partial_sum_kernel<<<(unsigned)((n + 15) / 16), kThreads, 0, st>>>(part, wp.nblk, n, dw);
   }
+  return hip_status();
+}
+
+int halo_bwd16_tiles(const ConvGeom& g) {
+  HaloPlan p;
+  if (!make_bwd16_plan(g, p)) return 0;
+  return p.tiles_i * p.tiles_h * p.tiles_w;
+}
+
+int launch_halo_bwd16(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy, const float* w,
+                      const void* packed, const void* stats, float* da3, double* partial, void* wscratch,
+                      float* dw) {
+  HaloPlan p;
+  if (!make_bwd16_plan(g, p)) return ABL_ERR_SHAPE;
+  const int tiles = p.tiles_i * p.tiles_h * p.tiles_w;
+  const uint8_t* pk = static_cast<const uint8_t*>(packed);
+  const float* sp = static_cast<const float*>(stats);
+  float* wpart = static_cast<float*>(wscratch);
+  auto kern = K == 4 ? (bf16 ? halo_bwd16_kernel<4, true> : halo_bwd16_kernel<4, false>)
+                     : (bf16 ? halo_bwd16_kernel<8, true> : halo_bwd16_kernel<8, false>);
+  kern<<<tiles, kThreads, p.lds_bytes, st>>>(dy, w, pk, sp, da3, partial, wpart, g, p);
+  const int64_t n = 9 * 16 * 16;
+  partial_sum_kernel<<<(unsigned)((n + 15) / 16), kThreads, 0, st>>>(wpart, tiles, n, dw);
   return hip_status();
 }
 
