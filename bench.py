@@ -115,6 +115,12 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
         B.abl_conv_dgrad_bn_reduce(t, K, d["dy"], w, d["packed"], stats, scratch, d["dx"], flags=flags)
     except B.AblError:
         fused = False
+    bwd_fused = fused
+    if fused:
+        try:
+            B.abl_conv_bwd_bn_reduce(t, K, d["dy"], w, d["packed"], stats, scratch, d["dx"], dw, flags=flags)
+        except B.AblError:
+            bwd_fused = False
     conv_bytes = 4 * E + 4 * Eo + wbytes
     S = sets
     # name: (call on operand set i, algorithmic bytes, flops, launches, part of the layer step)
@@ -127,7 +133,8 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
         "conv_dgrad": (lambda i: B.abl_conv_dgrad(t, S[i]["dy"], w, S[i]["dx"], flags=flags), conv_bytes, flops, 1,
                        not fused),
         "conv_wgrad_packed": (lambda i: B.abl_conv_wgrad_packed(t, K, S[i]["packed"], stats, S[i]["dy"], scratch, dw,
-                                                                flags=flags), P + 4 * Eo + wbytes, flops, 2, True),
+                                                                flags=flags), P + 4 * Eo + wbytes, flops, 2,
+                              not bwd_fused),
         "bn_bwd": (lambda i: B.abl_bn_bwd(S[i]["packed"], stats, S[i]["dx"], M, C, K, scratch, S[i]["a3"], dg, db),
                    2 * P + 12 * E, 0, 3, not fused),
         "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P, 0, 1, False),
@@ -138,7 +145,12 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
                                                              flags=flags), conv_bytes + P, flops, 1, True)
         stages["conv_dgrad_bn_reduce"] = (
             lambda i: B.abl_conv_dgrad_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"],
-                                                 flags=flags), conv_bytes + P, flops, 1, True)
+                                                 flags=flags), conv_bytes + P, flops, 1, not bwd_fused)
+    if bwd_fused:
+        # both contractions of the backward in one kernel (+ the small sum of its dW partials)
+        stages["conv_bwd_bn_reduce"] = (
+            lambda i: B.abl_conv_bwd_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"], dw,
+                                               flags=flags), conv_bytes + P + wbytes, 2 * flops, 2, True)
     out = {}
     for name, (fn, nbytes, fl, launches, in_step) in stages.items():
         ms = time_events(fn, reps, nset)

@@ -165,6 +165,16 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* shape, int K, uint32
                              const float* dy, const float* W, const void* packed, const void* stats,
                              void* scratch, size_t scratch_bytes, float* da3, int32_t* rows);
 
+/* abl_conv_bwd_bn_reduce: both contractions of Eq. 5 and the sums of Eq. 7 in one pass over dy
+ * and the packed codes, for 3x3 'same' stride-1 layers with 16 input and 16 output channels
+ * (ABL_ERR_SHAPE otherwise): writes da3 (gradient to the conv input), dW (from the dequantized
+ * activation, Eq. 10 and Eq. 3) and `*rows` partial rows [rows][2][16] of doubles (sum dA2,
+ * sum A1~ dA2) at the start of scratch.  scratch: abl_bn_scratch_bytes(N*H*W, 16) rounded up to
+ * 256 + abl_wgrad_scratch_bytes(shape) bytes; `*rows` is a host value set by the call. */
+int abl_conv_bwd_bn_reduce(void* stream, const abl_shape* shape, int K, uint32_t flags, const float* dy,
+                           const float* W, const void* packed, const void* stats, void* scratch,
+                           size_t scratch_bytes, float* da3, float* dW, int32_t* rows);
+
 /* ---- the layer grouped as conv -> BN -> ReLU ----
  * The paper groups a convolution with the non-linearities that PRECEDE it (Sec. 3.1) and that
  * is what abl_forward / abl_backward implement.  These entry points run the same kernels with

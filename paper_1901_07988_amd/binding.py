@@ -64,6 +64,8 @@ _SIGS = {
     "abl_bn_conv_fwd": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "abl_conv_dgrad_bn_reduce": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp,
                                                 ctypes.POINTER(ctypes.c_int32)]),
+    "abl_conv_bwd_bn_reduce": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp,
+                                              ctypes.POINTER(ctypes.c_int32)]),
     "abl_postact_packed_bytes": (_sz, [_shp, ctypes.c_int]),
     "abl_postact_stats_bytes": (_sz, [_shp]),
     "abl_postact_scratch_bytes": (_sz, [_shp, ctypes.c_int]),
@@ -161,6 +163,16 @@ def abl_conv_dgrad_bn_reduce(shape, K, dy, W, packed, stats, scratch, da3, flags
     _check(lib.abl_conv_dgrad_bn_reduce(_stream(), ctypes.byref(s), K, flags, _ptr(dy), _ptr(W), _ptr(packed),
                                         _ptr(stats), _ptr(scratch), scratch.numel() * scratch.element_size(),
                                         _ptr(da3), ctypes.byref(rows)), "abl_conv_dgrad_bn_reduce")
+    return rows.value
+
+
+def abl_conv_bwd_bn_reduce(shape, K, dy, W, packed, stats, scratch, da3, dW, flags=0):
+    """Returns the number of partial rows written to the start of scratch."""
+    s = shape_struct(shape)
+    rows = ctypes.c_int32(0)
+    _check(lib.abl_conv_bwd_bn_reduce(_stream(), ctypes.byref(s), K, flags, _ptr(dy), _ptr(W), _ptr(packed),
+                                      _ptr(stats), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                      _ptr(da3), _ptr(dW), ctypes.byref(rows)), "abl_conv_bwd_bn_reduce")
     return rows.value
 
 

@@ -293,6 +293,25 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t f
                                   da3, static_cast<double*>(scratch));
 }
 
+int abl_conv_bwd_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t flags, const float* dy, const float* W,
+                           const void* packed, const void* stats, void* scratch, size_t scratch_bytes, float* da3,
+                           float* dW, int32_t* rows) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(packed) || bad_ptr(stats) || bad_ptr(scratch) || bad_ptr(da3) ||
+      bad_ptr(dW) || rows == nullptr)
+    return ABL_ERR_ARG;
+  const ConvGeom g = geom_of(*s);
+  const int tiles = halo_bwd16_tiles(g);
+  if (tiles <= 0) return ABL_ERR_SHAPE;
+  const size_t redb = up256(bn_partial_bytes(rows_of(*s), s->Cin));
+  if (scratch_bytes < redb + wgrad_partial_bytes(*s)) return ABL_ERR_SCRATCH;
+  *rows = tiles;
+  return launch_halo_bwd16((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, dy, W, packed, stats, da3,
+                           static_cast<double*>(scratch), static_cast<char*>(scratch) + redb, dW);
+}
+
 // ---- the same layer grouped as conv -> BN -> ReLU ------------------------------------------
 // Same kernels in another order: F3 -> F1 -> F2 | B3 -> B4 -> B1, B2.  What is packed is still
 // the pre-ReLU BN output A2, now with Cout channels at the output resolution.

@@ -506,3 +506,36 @@ def test_fused_kernels_reject_unsupported_shapes(G):
         with pytest.raises(B.AblError) as e:
             B.abl_bn_conv_fwd(shape, 4, t, t, t, None, t[4096:], t)
         assert e.value.code == B.ABL_ERR_SHAPE
+
+
+@pytest.mark.parametrize("s", [LayerShape(4, 32, 32, 16, 16), LayerShape(3, 20, 28, 16, 16), LayerShape(10, 8, 8, 16, 16),
+                               LayerShape(2, 5, 40, 16, 16)],
+                         ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_one_kernel_conv_backward(G, oracle, s, K):
+    """abl_conv_bwd_bn_reduce (both contractions of Eq. 5 and the Eq. 7 sums in one kernel) against the
+    oracle's separate steps; tiles that do not divide the image, several images per tile."""
+    import torch
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    print("case conv_bwd", s.as_tuple(), K, flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 9, "normal", "random")
+    t = s.as_tuple()
+    _, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+    st = G.run_bn_stats(x, gamma, beta, K)
+    packed = G.dev(saved.store)
+    nred = (B.abl_bn_scratch_bytes(s.M, s.Cin) + 255) // 256 * 256
+    scratch = G.zeros_bytes(nred + B.abl_wgrad_scratch_bytes(t))
+    da3 = torch.empty((s.N, s.H, s.W, s.Cin), dtype=torch.float32, device="cuda")
+    dw = torch.empty(w.shape, dtype=torch.float32, device="cuda")
+    rows = B.abl_conv_bwd_bn_reduce(t, K, G.dev(dy), G.dev(w), packed, st, scratch, da3, dw)
+    torch.cuda.synchronize()
+    da3_ref = o.conv_dgrad(dy, w, oshape(o, s))
+    a2t = o.recover_a2(saved)
+    dw_ref = o.conv_wgrad(np.maximum(a2t, 0).astype(np.float32), dy, oshape(o, s))
+    assert rel(da3.cpu().numpy(), da3_ref) < TOL
+    assert rel(dw.cpu().numpy(), dw_ref) < TOL
+    part = scratch[: rows * 2 * s.Cin * 8].cpu().numpy().view(np.float64).reshape(rows, 2, s.Cin).sum(0)
+    _, dg_ref, db_ref = o.bn_relu_bwd(a2t, da3_ref, saved.rstd, gamma, beta)
+    scale = max(1.0, float(np.abs(da3_ref).sum((0, 1, 2)).max()))
+    assert np.max(np.abs(part[0] - db_ref)) < TOL * scale and np.max(np.abs(part[1] - dg_ref)) < TOL * scale
