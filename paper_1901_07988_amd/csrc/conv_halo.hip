@@ -92,11 +92,20 @@ __device__ inline int in_vgpr(int x) {
 __device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 
 // Sum over the 16 lanes of a row (lanes that differ in bits 0-3); every lane gets the total.
+// (Data-parallel-primitive moves within the row: swap neighbours, swap pairs, mirror each half,
+// mirror the row.)
+template <int CTRL>
+__device__ inline double dpp_move(double v) {
+  const unsigned long long u = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
 __device__ inline double row16_sum(double v) {
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
   return v;
 }
 
@@ -948,26 +957,52 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
 
   // ---- dW: the wave's 64 pixels, 16 per step; component e of the operand vectors is pixel
   // 4e + lk of the step (fp32: k-step e, lane group = k) or 4lk + e (bf16) ----
-  floatx4 accw[9][1][1];
+  // The operands of a step (9 taps x 4 pixels of A3~, 4 pixels of dy per lane) are read into
+  // registers one step ahead of the MFMAs that use them.
+  floatx4 accw[9];
 #pragma unroll
-  for (int t = 0; t < 9; ++t) accw[t][0][0] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-  for (int q = 0; q < 4; ++q) {
+  for (int t = 0; t < 9; ++t) accw[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float av[2][9][4], bv[2][4];
+  auto read_step = [&](int q, float (&a)[9][4], float (&b)[4]) __attribute__((always_inline)) {
     int pb[4];
-    float bv[4];
+    bool in[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int m = wave * 64 + 16 * q + (BF16 ? 4 * lk + e : 4 * e + lk);
       pb[e] = pixbase[m] + li;
-      // pixels that are not part of the tile or the image contribute nothing
-      bv[e] = pixoff[m] >= 0 ? tdy[pb[e] + ctr] : 0.0f;
+      in[e] = pixoff[m] >= 0;
     }
-    const float4 bf[1] = {make_float4(bv[0], bv[1], bv[2], bv[3])};
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-      const int toff = ((t / 3) * p.HW + (t % 3)) * PS;
-      const float4 a[1] = {make_float4(tact[pb[0] + toff], tact[pb[1] + toff], tact[pb[2] + toff], tact[pb[3] + toff])};
-      mma_k4<BF16, 1, 1>(a, bf, accw[t]);
+    for (int e = 0; e < 4; ++e) {
+      // pixels that are not part of the tile or the image contribute nothing
+      const float v = tdy[pb[e] + ctr];
+      b[e] = in[e] ? v : 0.0f;
+    }
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[t][e] = tact[pb[e] + ((t / 3) * p.HW + (t % 3)) * PS];
+  };
+  read_step(0, av[0], bv[0]);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    // the scheduler would otherwise sink every read to just before its MFMA and wait for it there
+    if (q + 1 < 4) read_step(q + 1, av[(q + 1) & 1], bv[(q + 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);
+    const float(&a)[9][4] = av[q & 1];
+    const float(&b)[4] = bv[q & 1];
+    if constexpr (BF16) {
+      const shortx4 bb = to_bf16x4(make_float4(b[0], b[1], b[2], b[3]));
+#pragma unroll
+      for (int t = 0; t < 9; ++t)
+        accw[t] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(to_bf16x4(make_float4(a[t][0], a[t][1], a[t][2], a[t][3])),
+                                                            bb, accw[t], 0, 0, 0);
+    } else {
+      // k-step outermost: consecutive MFMAs write different accumulators
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) accw[t] = mfma16(a[t][e], b[e], accw[t]);
     }
   }
 
@@ -1016,7 +1051,7 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) wred[(wave * 9 + t) * 256 + (4 * lk + r) * C + li] = accw[t][0][0][r];
+    for (int r = 0; r < 4; ++r) wred[(wave * 9 + t) * 256 + (4 * lk + r) * C + li] = accw[t][r];
   __syncthreads();
   float* dst = wpartial + (int64_t)tile * (9 * C * C);
 #pragma unroll
