@@ -243,9 +243,12 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   // the dgrad kernel (dA3 is still in registers there), which saves the reduce pass over dA3.
   // 16-channel 3x3 layers: both contractions and the Eq. 6-7 sums in one kernel
   if (const int t16 = halo_bwd16_tiles(g)) {
-    if (int e = launch_halo_bwd16(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red), wpart, dW))
+    if (int e = launch_halo_bwd16(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red), wpart,
+                                  nullptr))
       return e;
-    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta);
+    // the second pass of the Eq. 7 sums and the sum of the per-tile copies of dW share a launch
+    const DwSum dwsum{static_cast<const float*>(wpart), t16, (int64_t)9 * 16 * 16, dW};
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta, &dwsum);
   }
   const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {

@@ -32,9 +32,17 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
 size_t bn_means_offset(int C);
 int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, const float* shift_row, int64_t M,
                              int C, const float* gamma, const float* beta, int K, void* stats);
+// dwsum (nullable): a weight gradient left as `copies` partial copies of n floats by the conv
+// backward kernel; the finalize launch also sums them into dw (fixed order).
+struct DwSum {
+  const float* partial;
+  int copies;
+  int64_t n;
+  float* dw;
+};
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
-                         float* dbeta);
+                         float* dbeta, const DwSum* dwsum = nullptr);
 
 // Convolution geometry passed to the kernels by value.
 struct ConvGeom {
@@ -82,6 +90,7 @@ int launch_halo_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const
 // dA3, the Eq. 6-7 partial sums ([tiles][2][16] doubles) and dW in one pass over dy and the codes.
 // halo_bwd16_tiles returns 0 when the shape is not supported.  wscratch: as for launch_halo_wgrad.
 int halo_bwd16_tiles(const ConvGeom& g);
+// dw == nullptr: the per-tile copies of dW ([tiles][3][3][16][16]) are left in wscratch unsummed.
 int launch_halo_bwd16(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy, const float* w,
                       const void* packed, const void* stats, float* da3, double* partial, void* wscratch,
                       float* dw);

@@ -445,6 +445,49 @@ __global__ __launch_bounds__(kFinThreads) void bwd_finalize_kernel(const double*
   means[C + c] = (float)(gm * t[1] / (double)M);
 }
 
+// The same second pass (blocks 0 .. nfin-1) and, in the other blocks of the same launch, the sum
+// of `ncopies` partial copies of a weight gradient of n floats (64 outputs x 16 interleaved parts
+// per block, a binary tree over the parts): two small dependent-free jobs that follow the conv
+// backward kernel share one launch.
+__global__ __launch_bounds__(kFinThreads) void bwd_finalize_dwsum_kernel(const double* __restrict__ partial, int nb,
+                                                                      int64_t M, int C,
+                                                                      const float* __restrict__ stats,
+                                                                      float* __restrict__ dgamma,
+                                                                      float* __restrict__ dbeta,
+                                                                      float* __restrict__ means, int nfin,
+                                                                      const float* __restrict__ wpartial,
+                                                                      int ncopies, int64_t n,
+                                                                      float* __restrict__ dw) {
+  __shared__ double sm[32][32];
+  if ((int)blockIdx.x < nfin) {
+    const int c = blockIdx.x * 16 + (threadIdx.x & 15);
+    double t[2];
+    reduce_partials(partial, nb, C, t, sm);
+    if (c >= C || threadIdx.x >= 16) return;
+    const double gm = (double)stats[P_GAMMA * C + c];
+    dbeta[c] = (float)t[0];
+    dgamma[c] = (float)t[1];
+    means[c] = (float)(gm * t[0] / (double)M);
+    means[C + c] = (float)(gm * t[1] / (double)M);
+    return;
+  }
+  float(*sw)[64] = reinterpret_cast<float(*)[64]>(&sm[0][0]);  // [16][64]
+  const int o = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int64_t i = (int64_t)(blockIdx.x - nfin) * 64 + o;
+  float a = 0.f;
+  if (i < n) {
+#pragma unroll 8
+    for (int k = part; k < ncopies; k += 16) a += wpartial[(int64_t)k * n + i];
+  }
+  sw[part][o] = a;
+  __syncthreads();
+  for (int h = 8; h >= 1; h >>= 1) {
+    if (part < h) sw[part][o] += sw[part + h][o];
+    __syncthreads();
+  }
+  if (part == 0 && i < n) dw[i] = sw[0][o];
+}
+
 // Backward, pass 2 (Eq. 8): dx = rstd * (dA1 - Mean(dA1) - A1~ * Mean(A1~ * dA1)).
 template <int K, int VEC, bool ACCUM, bool STREAM>
 __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restrict__ packed,
@@ -763,13 +806,18 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
 // start of `scratch`: finalize kernel, then the apply pass.
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
-                         float* dbeta) {
+                         float* dbeta, const DwSum* dwsum) {
   const float* sp = static_cast<const float*>(stats);
   const double* partial = static_cast<const double*>(scratch);
   float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + bn_means_offset(C));
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
   const int vec = fast_vec(K, C);
-  bwd_finalize_kernel<<<(C + 15) / 16, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means);
+  const int nfin = (C + 15) / 16;
+  if (dwsum != nullptr)
+    bwd_finalize_dwsum_kernel<<<nfin + (unsigned)((dwsum->n + 63) / 64), kFinThreads, 0, st>>>(
+        partial, nb, M, C, sp, dgamma, dbeta, means, nfin, dwsum->partial, dwsum->copies, dwsum->n, dwsum->dw);
+  else
+    bwd_finalize_kernel<<<nfin, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means);
   if (vec == 0) {
     const int64_t E = M * C;
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);

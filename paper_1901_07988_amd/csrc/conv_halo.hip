@@ -1191,8 +1191,10 @@ int launch_halo_bwd16(hipStream_t st, const ConvGeom& g, int K, bool bf16, const
   auto kern = K == 4 ? (bf16 ? halo_bwd16_kernel<4, true> : halo_bwd16_kernel<4, false>)
                      : (bf16 ? halo_bwd16_kernel<8, true> : halo_bwd16_kernel<8, false>);
   kern<<<tiles, kThreads, p.lds_bytes, st>>>(dy, w, pk, sp, da3, partial, wpart, g, p);
-  const int64_t n = 9 * 16 * 16;
-  partial_sum_kernel<<<(unsigned)((n + 15) / 16), kThreads, 0, st>>>(wpart, tiles, n, dw);
+  if (dw != nullptr) {
+    const int64_t n = 9 * 16 * 16;
+    partial_sum_kernel<<<(unsigned)((n + 15) / 16), kThreads, 0, st>>>(wpart, tiles, n, dw);
+  }
   return hip_status();
 }
 
