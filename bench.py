@@ -71,9 +71,8 @@ def time_events(fn, reps, nset=1):
 # The runs and their commands are summarised under profiles/.
 MEASURED_TRAFFIC = {
     ("config2", 4, "fp32"): {
-        "bn_conv_fwd": 23.95e6,            # in the stack: half the layers also read a shortcut
-        "conv_dgrad_bn_reduce": 19.89e6,
-        "conv_wgrad_packed": 15.45e6 + 4.75e6,
+        "bn_conv_fwd": 23.77e6,            # in the stack: half the layers also read a shortcut
+        "conv_bwd_bn_reduce": 25.74e6,     # includes 4.7 MB of per-tile dW copies
     },
 }
 
@@ -147,10 +146,11 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
             lambda i: B.abl_conv_dgrad_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"],
                                                  flags=flags), conv_bytes + P, flops, 1, not bwd_fused)
     if bwd_fused:
-        # both contractions of the backward in one kernel (+ the small sum of its dW partials)
+        # both contractions of the backward in one kernel; its per-tile copies of dW are summed by the
+        # launch that also finishes the BN-backward sums, so the kernel is timed without that sum
         stages["conv_bwd_bn_reduce"] = (
-            lambda i: B.abl_conv_bwd_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"], dw,
-                                               flags=flags), conv_bytes + P + wbytes, 2 * flops, 2, True)
+            lambda i: B.abl_conv_bwd_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"], None,
+                                               flags=flags), conv_bytes + P + wbytes, 2 * flops, 1, True)
     out = {}
     for name, (fn, nbytes, fl, launches, in_step) in stages.items():
         ms = time_events(fn, reps, nset)

@@ -170,7 +170,10 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* shape, int K, uint32
  * (ABL_ERR_SHAPE otherwise): writes da3 (gradient to the conv input), dW (from the dequantized
  * activation, Eq. 10 and Eq. 3) and `*rows` partial rows [rows][2][16] of doubles (sum dA2,
  * sum A1~ dA2) at the start of scratch.  scratch: abl_bn_scratch_bytes(N*H*W, 16) rounded up to
- * 256 + abl_wgrad_scratch_bytes(shape) bytes; `*rows` is a host value set by the call. */
+ * 256 + abl_wgrad_scratch_bytes(shape) bytes; `*rows` is a host value set by the call.
+ * dW may be NULL: the weight gradient is then left as `*rows` unsummed copies [rows][3][3][16][16]
+ * behind the partial rows (at scratch + the rounded abl_bn_scratch_bytes) and the call is a
+ * single kernel launch. */
 int abl_conv_bwd_bn_reduce(void* stream, const abl_shape* shape, int K, uint32_t flags, const float* dy,
                            const float* W, const void* packed, const void* stats, void* scratch,
                            size_t scratch_bytes, float* da3, float* dW, int32_t* rows);

@@ -303,7 +303,7 @@ int abl_conv_bwd_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t fla
   if (int e = check_k(K)) return e;
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(packed) || bad_ptr(stats) || bad_ptr(scratch) || bad_ptr(da3) ||
-      bad_ptr(dW) || rows == nullptr)
+      (dW != nullptr && !aligned16(dW)) || rows == nullptr)
     return ABL_ERR_ARG;
   const ConvGeom g = geom_of(*s);
   const int tiles = halo_bwd16_tiles(g);
