@@ -88,11 +88,13 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     }
   }
 
-  floatx4 acc[MT][NT];
+  // The MFMA computes the transposed tile (first operand = weights): a lane ends up with four
+  // consecutive output channels of one pixel, stored and read (shortcut) 16 bytes at a time.
+  floatx4 acc[NT][MT];  // acc[j][i][r]: pixel wm0 + 16i + li, channel wn0 + 16j + 4lk + r
 #pragma unroll
-  for (int i = 0; i < MT; ++i)
+  for (int j = 0; j < NT; ++j)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MT; ++i) acc[j][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int cchunks = (Cg + BK - 1) / BK;
   const int taps = g.R * g.S;
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 #pragma unroll
       for (int j = 0; j < NT; ++j)
         bf[j] = *reinterpret_cast<const float4*>(&Bs[(wn0 + 16 * j + li) * LDK + 16 * kg + 4 * lk]);
-      mma_k4<BF16, MT, NT>(af, bf, acc);
+      mma_k4<BF16, NT, MT>(bf, af, acc);
     }
   };
   // The loads of chunk i+1 are issued before chunk i is contracted and written to the other
@@ -224,39 +226,47 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     __syncthreads();
   }
 
-  // epilogue: lane holds rows 4*lk + r, column li of each 16x16 tile.  The shortcut values are
-  // loaded in one batch (clamped addresses), then added and stored.
+  // epilogue: the lane holds channels n0 + wn0 + 16j + 4lk .. +3 of pixel m0 + wm0 + 16i + li.
+  // Channel counts that are not a multiple of 4 take the element-wise path.
   const bool full = m0 + BM <= Mg && n0 + BN <= Ng;
-  if (skip != nullptr) {
+  const bool vec4 = (Ng & 3) == 0;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      float sv[4][NT];
+  for (int i = 0; i < MT; ++i) {
+    const int64_t p = m0 + wm0 + 16 * i + li;
+    const bool p_ok = full || p < Mg;
+    if (vec4) {
+      bool ok[NT];
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
+      for (int j = 0; j < NT; ++j) ok[j] = p_ok && (full || n0 + wn0 + 16 * j + 4 * lk < Ng);
+      if (skip != nullptr) {
+        float4 sv[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          sv[j] = *reinterpret_cast<const float4*>(skip + (ok[j] ? p * Ng + n0 + wn0 + 16 * j + 4 * lk : 0));
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-          const int64_t p = m0 + wm0 + 16 * i + 4 * lk + r;
-          const int n = n0 + wn0 + 16 * j + li;
-          const bool ok = full || (p < Mg && n < Ng);
-          sv[r][j] = skip[ok ? p * Ng + n : 0];
+          acc[j][i][0] += sv[j].x; acc[j][i][1] += sv[j].y; acc[j][i][2] += sv[j].z; acc[j][i][3] += sv[j].w;
         }
+      }
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
+      for (int j = 0; j < NT; ++j)
+        if (ok[j])
+          *reinterpret_cast<float4*>(out + p * Ng + n0 + wn0 + 16 * j + 4 * lk) =
+              make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
+    } else {
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j][r] += sv[r][j];
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int n = n0 + wn0 + 16 * j + 4 * lk + r;
+          if (p_ok && n < Ng) {
+            float v = acc[j][i][r];
+            if (skip != nullptr) v += skip[p * Ng + n];
+            out[p * Ng + n] = v;
+          }
+        }
     }
   }
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int64_t p = m0 + wm0 + 16 * i + 4 * lk + r;
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn0 + 16 * j + li;
-        if (full || (p < Mg && n < Ng)) out[p * Ng + n] = acc[i][j][r];
-      }
-    }
 }
 
 // ------------------------------------------------------------------------------------------
