@@ -107,10 +107,13 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
         B.abl_bn_stats(d["x"], M, C, gamma, beta, K, scratch, stats)
         B.abl_bn_relu_pack(d["x"], M, C, K, stats, d["a3"], d["packed"])
         sets.append(d)
-    fused = True
+    d = sets[0]
+    fwd_fused = fused = True
     try:
-        d = sets[0]
         B.abl_bn_conv_fwd(t, K, d["x"], stats, w, None, d["y"], d["packed"], flags=flags)
+    except B.AblError:
+        fwd_fused = False
+    try:
         B.abl_conv_dgrad_bn_reduce(t, K, d["dy"], w, d["packed"], stats, scratch, d["dx"], flags=flags)
     except B.AblError:
         fused = False
@@ -126,9 +129,9 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
     stages = {
         "bn_stats": (lambda i: B.abl_bn_stats(S[i]["x"], M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2, not fused),
         "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]),
-                         8 * E + P, 0, 1, not fused),
+                         8 * E + P, 0, 1, not fwd_fused),
         "conv_fwd": (lambda i: B.abl_conv_fwd(t, S[i]["a3"], w, None, S[i]["y"], flags=flags), conv_bytes, flops, 1,
-                     not fused),
+                     not fwd_fused),
         "conv_dgrad": (lambda i: B.abl_conv_dgrad(t, S[i]["dy"], w, S[i]["dx"], flags=flags), conv_bytes, flops, 1,
                        not fused),
         "conv_wgrad_packed": (lambda i: B.abl_conv_wgrad_packed(t, K, S[i]["packed"], stats, S[i]["dy"], scratch, dw,
@@ -139,9 +142,10 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
         "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P, 0, 1, False),
         "unpack": (lambda i: B.abl_unpack(S[i]["packed"], M, C, K, stats, S[i]["a3"]), 4 * E + P, 0, 1, False),
     }
-    if fused:
+    if fwd_fused:
         stages["bn_conv_fwd"] = (lambda i: B.abl_bn_conv_fwd(t, K, S[i]["x"], stats, w, None, S[i]["y"], S[i]["packed"],
                                                              flags=flags), conv_bytes + P, flops, 1, True)
+    if fused:
         stages["conv_dgrad_bn_reduce"] = (
             lambda i: B.abl_conv_dgrad_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"],
                                                  flags=flags), conv_bytes + P, flops, 1, not bwd_fused)

@@ -194,6 +194,9 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     if (want && out_nb != nullptr) *out_nb = tiles;
     return ABL_OK;
   }
+  // 1x1 convolutions do the same while they stage their A tile
+  if (igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
+    return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
   return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
 }
@@ -273,6 +276,9 @@ int abl_bn_conv_fwd(void* stream, const abl_shape* s, int K, uint32_t flags, con
       (skip != nullptr && !aligned16(skip)) || static_cast<const void*>(x) == static_cast<const void*>(y))
     return ABL_ERR_ARG;
   const ConvGeom g = geom_of(*s);
+  if (igemm_fused_supported(*s))
+    return launch_conv_fwd_fused((hipStream_t)stream, *s, K, (flags & ABL_MATH_BF16) != 0, x, stats, W, skip, y,
+                                 packed);
   if (!halo_fused_supported(g)) return ABL_ERR_SHAPE;
   return launch_halo_fwd_fused((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, x, stats, W, skip, y,
                                packed, nullptr);

@@ -101,6 +101,12 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
                     const float* skip, float* y);
 int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float* dy, const float* w,
                       float* da3);
+// Forward of a 1x1 stride-1 convolution without padding with Eq. 1-3 and Eq. 9 applied while the
+// A tile is staged: reads x, writes y and the packed codes; A3 never reaches memory.  y must not
+// alias x.
+bool igemm_fused_supported(const abl_shape& s);
+int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
+                          const float* w, const float* skip, float* y, void* packed);
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
                              const void* stats, const float* dy, void* scratch, float* dw);
 

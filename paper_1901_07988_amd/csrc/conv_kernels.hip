@@ -11,6 +11,9 @@
 
 #include "abl_internal.h"
 
+// the fused forward evaluates Eq. 1-3 and Eq. 9 here: one rounded fp32 operation at a time
+#pragma clang fp contract(off)
+
 namespace abl {
 namespace {
 
@@ -29,10 +32,16 @@ constexpr int kThreads = 256;
 // tiles are double buffered: the global loads of chunk i+1 are in flight while chunk i is
 // contracted, and one barrier per chunk separates "everyone has read buffer b" from
 // "buffer b is overwritten".
-template <int BM, int BN, int WM, int WN, int BK, int MODE, bool BF16>
+// FUSE = K (4 or 8; forward of 1x1 stride-1 convolutions without padding only): `in` is the layer
+// input x; BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied to the A tile on its way into
+// LDS and the blocks of the first output-channel block also write the K-bit codes (Eq. 9), so A3
+// never reaches memory.  pack_pad: zero bytes after the last code.
+template <int BM, int BN, int WM, int WN, int BK, int MODE, bool BF16, int FUSE>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict__ in,
                                                          const float* __restrict__ wgt,
-                                                         const float* skip, float* out, ConvGeom g) {
+                                                         const float* skip, float* out, ConvGeom g,
+                                                         const float* __restrict__ stats,
+                                                         void* __restrict__ packed, int pack_pad) {
   constexpr int LDK = BK + 4;
   constexpr int KQ = BK / 4;                               // float4 per tile row
   constexpr int WAVES_N = BN / WN, WAVES_M = BM / WM;
@@ -64,6 +73,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int64_t m0 = ((int64_t)(slot / nblk_n) * 8 + xcd) * BM;
   const int n0 = (slot % nblk_n) * BN;
+  if (FUSE != 0 && blockIdx.x == 0 && (int)threadIdx.x < pack_pad)  // tail of the last 128-byte row
+    static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + threadIdx.x] = 0;
   if (m0 >= Mg) return;
 
   // rows of the A tile this thread fetches (one float4 = 4 channels per row and pass)
@@ -143,6 +154,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   }
   set_tap(0);
 
+  // per-channel constants of the 4 channels this thread stages (fused forward)
+  float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
+  int4 k_fb;
+  int k_c = 0;
   auto fetch = [&]() __attribute__((always_inline)) {
     // every load is issued unconditionally (out-of-range lanes read element 0 and are zeroed
     // afterwards): no branches between the loads, so they are all in flight together
@@ -151,7 +166,16 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     for (int i = 0; i < A_PASSES; ++i) {
       const bool ok = a_off[i] >= 0 && c < Cg;
       const float4 v = *reinterpret_cast<const float4*>(in + (ok ? a_off[i] + c : 0));
-      ra[i] = keep_if(ok, v);
+      ra[i] = FUSE != 0 ? v : keep_if(ok, v);
+    }
+    if (FUSE != 0) {
+      k_mean = *reinterpret_cast<const float4*>(stats + P_MEAN * g.Cin + c);
+      k_rstd = *reinterpret_cast<const float4*>(stats + P_RSTD * g.Cin + c);
+      k_gamma = *reinterpret_cast<const float4*>(stats + P_GAMMA * g.Cin + c);
+      k_beta = *reinterpret_cast<const float4*>(stats + P_BETA * g.Cin + c);
+      k_cq = *reinterpret_cast<const float4*>(stats + P_CQ * g.Cin + c);
+      k_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * g.Cin + c);
+      k_c = c;
     }
     const float* wb = MODE == 0 ? wgt + ((int64_t)f_tap * g.Cin + f_c0) * g.Cout
                                 : wgt + (int64_t)f_tap * g.Cin * g.Cout + f_c0;
@@ -182,8 +206,38 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     float* As = As0 + buf * BM * LDK;
     float* Bs = Bs0 + buf * BN * LDK;
 #pragma unroll
-    for (int i = 0; i < A_PASSES; ++i)
-      *reinterpret_cast<float4*>(&As[(a_row + ROWS * i) * LDK + 4 * a_kq]) = ra[i];
+    for (int i = 0; i < A_PASSES; ++i) {
+      float4 v = ra[i];
+      if (FUSE != 0) {
+        // a 1x1 convolution has one tap, so a_off[] still belongs to the chunk in ra[]
+        const bool ok = a_off[i] >= 0;
+        const float xs[4] = {v.x, v.y, v.z, v.w};
+        const float mean[4] = {k_mean.x, k_mean.y, k_mean.z, k_mean.w};
+        const float rstd[4] = {k_rstd.x, k_rstd.y, k_rstd.z, k_rstd.w};
+        const float gm[4] = {k_gamma.x, k_gamma.y, k_gamma.z, k_gamma.w};
+        const float bt[4] = {k_beta.x, k_beta.y, k_beta.z, k_beta.w};
+        const float cq[4] = {k_cq.x, k_cq.y, k_cq.z, k_cq.w};
+        const int32_t fb[4] = {k_fb.x, k_fb.y, k_fb.z, k_fb.w};
+        float a3[4];
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float d = xs[e] - mean[e];
+          const float a1 = d * rstd[e];  // Eq. 1
+          const float t = gm[e] * a1;
+          const float a2 = t + bt[e];    // Eq. 2
+          a3[e] = (ok && a2 > 0.0f) ? a2 : 0.0f;  // Eq. 3
+          word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2, cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+        }
+        v = make_float4(a3[0], a3[1], a3[2], a3[3]);
+        if (ok && n0 == 0) {
+          const int64_t e0 = (int64_t)a_off[i] + k_c;  // flat element index of the first of 4 codes
+          if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
+          else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+        }
+      }
+      *reinterpret_cast<float4*>(&As[(a_row + ROWS * i) * LDK + 4 * a_kq]) = v;
+    }
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
@@ -570,9 +624,11 @@ inline bool mfma_ok(const ConvGeom& g) { return g.Cin % 16 == 0 && g.Cout % 16 =
 
 // Tile choice: the largest tile whose grid still gives every CU about two blocks; a tile
 // that is too large for a small GEMM leaves compute units idle.
-template <int MODE>
+template <int MODE, int FUSE>
 int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w,
-                 const float* skip, float* out) {
+                 const float* skip, float* out, const float* stats, void* packed) {
+  const int64_t raw = FUSE != 0 ? ((int64_t)g.N * g.H * g.W * g.Cin * FUSE + 7) / 8 : 0;
+  const int pack_pad = (int)((raw + 127) / 128 * 128 - raw);
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
   auto blocks = [&](int bm, int bn) __attribute__((always_inline)) { return ((Mg + bm - 1) / bm) * ((Ng + bn - 1) / bn); };
@@ -581,13 +637,13 @@ int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, 
     const int64_t mb8 = ((Mg + BM_ - 1) / BM_ + 7) / 8 * 8;                                   \
     dim3 grid((unsigned)(mb8 * ((Ng + BN_ - 1) / BN_)));                                      \
     constexpr unsigned lds = 2u * (BM_ + BN_) * (BK_ + 4) * sizeof(float);                    \
-    auto kern = bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true>                       \
-                     : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false>;                     \
+    auto kern = bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true, FUSE>                 \
+                     : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false, FUSE>;               \
     if (lds > 64 * 1024 &&                                                                     \
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                               \
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)    \
       return ABL_ERR_HIP;                                                                                          \
-    kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, g);                                    \
+    kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, g, stats, packed, pack_pad);           \
   } while (0)
   const int Cg = MODE == 0 ? g.Cin : g.Cout;
   const int64_t want = 512;
@@ -670,7 +726,22 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     return hip_status();
   }
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y);
-  return launch_igemm<0>(st, g, bf16, a3, w, skip, y);
+  return launch_igemm<0, 0>(st, g, bf16, a3, w, skip, y, nullptr, nullptr);
+}
+
+bool igemm_fused_supported(const abl_shape& s) {
+  const ConvGeom g = geom_of(s);
+  return mfma_ok(g) && g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0 &&
+         (int64_t)g.N * g.H * g.W * g.Cin < (1ll << 31);
+}
+
+int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
+                          const float* w, const float* skip, float* y, void* packed) {
+  if (!igemm_fused_supported(s)) return ABL_ERR_SHAPE;
+  const ConvGeom g = geom_of(s);
+  const float* sp = static_cast<const float*>(stats);
+  if (K == 4) return launch_igemm<0, 4>(st, g, bf16, x, w, skip, y, sp, packed);
+  return launch_igemm<0, 8>(st, g, bf16, x, w, skip, y, sp, packed);
 }
 
 int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float* dy, const float* w,
@@ -682,7 +753,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
     return hip_status();
   }
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
-  return launch_igemm<1>(st, g, bf16, dy, w, nullptr, da3);
+  return launch_igemm<1, 0>(st, g, bf16, dy, w, nullptr, da3, nullptr, nullptr);
 }
 
 template <int TM, int TN>

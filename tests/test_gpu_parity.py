@@ -468,6 +468,20 @@ def test_postact_chain_with_packed_inputs(G, oracle, K):
                          ids=lambda s: "x".join(map(str, s.as_tuple())))
 @pytest.mark.parametrize("K", [4, 8])
 def test_fused_kernels_on_their_own(G, oracle, s, K):
+    _fused_kernels_case(G, oracle, s, K, True)
+
+
+@pytest.mark.parametrize("s", [LayerShape(3, 14, 14, 64, 32, 1, 1, 1, 0), LayerShape(2, 9, 7, 256, 64, 1, 1, 1, 0),
+                               LayerShape(5, 8, 8, 48, 272, 1, 1, 1, 0), LayerShape(40, 14, 14, 32, 16, 1, 1, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_fused_forward_1x1(G, oracle, s, K):
+    """abl_bn_conv_fwd on 1x1 convolutions (Eq. 1-3, 9 while the A tile is staged): ragged row
+    tiles, several output-channel blocks, 16- and 32-channel chunks."""
+    _fused_kernels_case(G, oracle, s, K, False)
+
+
+def _fused_kernels_case(G, oracle, s, K, backward):
     """abl_bn_conv_fwd (Eq. 1-3, 9, 4 in one kernel) and abl_conv_dgrad_bn_reduce (Eq. 5 with the
     Eq. 7 sums in the epilogue) against the oracle's separate steps."""
     import torch
@@ -485,6 +499,8 @@ def test_fused_kernels_on_their_own(G, oracle, s, K):
     y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s), skip=skip)
     assert packed.cpu().numpy().tobytes() == saved.store.tobytes()
     assert rel(y.cpu().numpy(), y_ref) < TOL
+    if not backward:
+        return
     # dgrad + reduce: da3 against the oracle, the partial rows against the oracle's Eq. 7 totals
     scratch = G.zeros_bytes(B.abl_bn_scratch_bytes(s.M, s.Cin))
     da3 = torch.empty((s.N, s.H, s.W, s.Cin), dtype=torch.float32, device="cuda")
@@ -502,7 +518,7 @@ def test_fused_kernels_reject_unsupported_shapes(G):
     import torch
     from paper_1901_07988_amd import binding as B
     t = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
-    for shape in ((2, 8, 8, 16, 16, 1, 1, 1, 0), (2, 8, 8, 16, 16, 3, 3, 2, 1), (2, 8, 8, 12, 16, 3, 3, 1, 1)):
+    for shape in ((2, 8, 8, 16, 16, 1, 1, 2, 0), (2, 8, 8, 16, 16, 3, 3, 2, 1), (2, 8, 8, 12, 16, 3, 3, 1, 1)):
         with pytest.raises(B.AblError) as e:
             B.abl_bn_conv_fwd(shape, 4, t, t, t, None, t[4096:], t)
         assert e.value.code == B.ABL_ERR_SHAPE
