@@ -17,7 +17,11 @@
  *     Eq. 4 is a zero-padded cross-correlation without bias.
  *   - the BN tensor of a layer is its input: M = N*H*W rows of Cin channels,
  *     E = M*Cin elements.  Batch statistics use the biased variance, eps = 1e-5.
- *   - K is 4 or 8.
+ *   - K is 4 or 8, or 32 for exact storage (the paper's baseline, Sec. 4: one full-precision
+ *     copy of A2 per layer, alpha = 1): the "codes" are then the fp32 values themselves, the
+ *     quantizer planes of `stats` are zero, and the backward pass is exact back-propagation.
+ *     The fused-kernel entry points (abl_bn_conv_fwd, abl_conv_dgrad_bn_reduce,
+ *     abl_conv_bwd_bn_reduce) and the abl_postact_* grouping take K = 4 or 8 only.
  *   - `flags` is a bit set of the ABL_* flags an entry point documents; unknown bits are an
  *     ABL_ERR_ARG.
  *   - return value: ABL_OK or an ABL_ERR_* code; on error nothing was enqueued
@@ -50,7 +54,7 @@ typedef struct abl_shape {
 
 enum {
   ABL_OK = 0,
-  ABL_ERR_ARG = 1,      /* null / misaligned pointer, K not in {4,8}, bad flag      */
+  ABL_ERR_ARG = 1,      /* null / misaligned pointer, unsupported K, bad flag       */
   ABL_ERR_SHAPE = 2,    /* non-positive dim, empty output, more than 2^31-1 elements */
   ABL_ERR_SCRATCH = 3,  /* scratch buffer smaller than abl_scratch_bytes            */
   ABL_ERR_HIP = 4       /* kernel launch failed                                     */

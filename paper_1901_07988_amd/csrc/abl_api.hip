@@ -13,7 +13,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline bool bad_ptr(const void* p) { return p == nullptr || !aligned16(p); }
 
-int check_k(int K) { return (K == 4 || K == 8) ? ABL_OK : ABL_ERR_ARG; }
+// K = 32 is exact storage (the fp32 A2 itself is kept, Sec. 3.2's alpha = 1); the fused kernels
+// and the conv -> BN -> ReLU grouping take the two quantized widths only.
+int check_k(int K) { return (K == 4 || K == 8 || K == 32) ? ABL_OK : ABL_ERR_ARG; }
+int check_k48(int K) { return (K == 4 || K == 8) ? ABL_OK : ABL_ERR_ARG; }
 
 int check_shape(const abl_shape* s) {
   if (s == nullptr) return ABL_ERR_ARG;
@@ -153,7 +156,7 @@ int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, uint32_t flag
   if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(scratch) || bad_ptr(dW)) return ABL_ERR_ARG;
   if (scratch_bytes < wgrad_partial_bytes(*s)) return ABL_ERR_SCRATCH;
   return launch_conv_wgrad_packed((hipStream_t)stream, *s, K, (flags & ABL_MATH_BF16) != 0, packed, stats, dy,
-                                  scratch, dW);
+                                  scratch, dW, K == 32);
 }
 
 }  // extern "C"
@@ -186,7 +189,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
   // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
   // overwrite input pixels that a neighbouring block has not staged yet.)
-  if (halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
+  if (K != 32 && halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
     const int tiles = halo_tile_count(g, 0);
     const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
     if (int e = launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed, want ? out_partial : nullptr))
@@ -195,7 +198,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     return ABL_OK;
   }
   // 1x1 convolutions do the same while they stage their A tile
-  if (igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
+  if (K != 32 && igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
     return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
   return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
@@ -245,7 +248,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   // Stride-1 convolutions with a filter larger than 1x1 take the Eq. 6-7 sums in the epilogue of
   // the dgrad kernel (dA3 is still in registers there), which saves the reduce pass over dA3.
   // 16-channel 3x3 layers: both contractions and the Eq. 6-7 sums in one kernel
-  if (const int t16 = halo_bwd16_tiles(g)) {
+  if (const int t16 = K != 32 ? halo_bwd16_tiles(g) : 0) {
     if (int e = launch_halo_bwd16(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red), wpart,
                                   nullptr))
       return e;
@@ -253,7 +256,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     const DwSum dwsum{static_cast<const float*>(wpart), t16, (int64_t)9 * 16 * 16, dW};
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta, &dwsum);
   }
-  const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
+  const int tiles = K != 32 && halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))
       return e;
@@ -261,7 +264,8 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta);
   }
   if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
-  if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
+  // exact storage keeps the pre-ReLU A2: the weight gradient applies Eq. 3 on the way in
+  if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, K == 32)) return e;
   return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
 }
 
@@ -270,7 +274,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
 int abl_bn_conv_fwd(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const void* stats,
                     const float* W, const float* skip, float* y, void* packed) {
   if (int e = check_shape(s)) return e;
-  if (int e = check_k(K)) return e;
+  if (int e = check_k48(K)) return e;
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(x) || bad_ptr(stats) || bad_ptr(W) || bad_ptr(y) || bad_ptr(packed) ||
       (skip != nullptr && !aligned16(skip)) || static_cast<const void*>(x) == static_cast<const void*>(y))
@@ -288,7 +292,7 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t f
                              const float* W, const void* packed, const void* stats, void* scratch,
                              size_t scratch_bytes, float* da3, int32_t* rows) {
   if (int e = check_shape(s)) return e;
-  if (int e = check_k(K)) return e;
+  if (int e = check_k48(K)) return e;
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(packed) || bad_ptr(stats) || bad_ptr(scratch) || bad_ptr(da3) ||
       rows == nullptr)
@@ -306,7 +310,7 @@ int abl_conv_bwd_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t fla
                            const void* packed, const void* stats, void* scratch, size_t scratch_bytes, float* da3,
                            float* dW, int32_t* rows) {
   if (int e = check_shape(s)) return e;
-  if (int e = check_k(K)) return e;
+  if (int e = check_k48(K)) return e;
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(dy) || bad_ptr(W) || bad_ptr(packed) || bad_ptr(stats) || bad_ptr(scratch) || bad_ptr(da3) ||
       (dW != nullptr && !aligned16(dW)) || rows == nullptr)
@@ -330,7 +334,7 @@ static inline int64_t out_rows(const abl_shape& s) {
 }
 
 size_t abl_postact_packed_bytes(const abl_shape* s, int K) {
-  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  if (check_shape(s) != ABL_OK || check_k48(K) != ABL_OK) return 0;
   return packed_bytes_of(out_rows(*s) * s->Cout, K);
 }
 
@@ -340,7 +344,7 @@ size_t abl_postact_stats_bytes(const abl_shape* s) {
 }
 
 size_t abl_postact_scratch_bytes(const abl_shape* s, int K) {
-  if (check_shape(s) != ABL_OK || check_k(K) != ABL_OK) return 0;
+  if (check_shape(s) != ABL_OK || check_k48(K) != ABL_OK) return 0;
   const size_t act = up256((size_t)out_rows(*s) * s->Cout * sizeof(float));
   return act + up256(bn_partial_bytes(out_rows(*s), s->Cout)) + wgrad_partial_bytes(*s);
 }
@@ -349,7 +353,7 @@ int abl_postact_forward(void* stream, const abl_shape* s, int K, uint32_t flags,
                         const float* W, const float* gamma, const float* beta, void* scratch,
                         size_t scratch_bytes, float* y, void* packed, void* stats) {
   if (int e = check_shape(s)) return e;
-  if (int e = check_k(K)) return e;
+  if (int e = check_k48(K)) return e;
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
   if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
       bad_ptr(packed) || bad_ptr(stats))
@@ -369,7 +373,7 @@ int abl_postact_backward(void* stream, const abl_shape* s, int K, uint32_t flags
                          const void* xin_stats, void* scratch, size_t scratch_bytes, float* dx, float* dW,
                          float* dgamma, float* dbeta) {
   if (int e = check_shape(s)) return e;
-  if (int e = check_k(K)) return e;
+  if (int e = check_k48(K)) return e;
   if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_XIN_F32 | ABL_XIN_PACKED)) return ABL_ERR_ARG;
   const bool xin_f32 = (flags & ABL_XIN_F32) != 0, xin_packed = (flags & ABL_XIN_PACKED) != 0;
   if (xin_f32 == xin_packed) return ABL_ERR_ARG;  // exactly one of the two

@@ -107,8 +107,9 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
 bool igemm_fused_supported(const abl_shape& s);
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
                           const float* w, const float* skip, float* y, void* packed);
+// K = 32: `packed` is an fp32 tensor, used as it is or (relu32) as the pre-ReLU activation A2.
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
-                             const void* stats, const float* dy, void* scratch, float* dw);
+                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32 = false);
 
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.
@@ -121,9 +122,11 @@ __device__ inline float limit_floor(float u) {
   return u;
 }
 
-// Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).
+// Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).  K = 32 is exact storage: the
+// "code" is the value's bit pattern.
 template <int K>
 __device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
+  if constexpr (K == 32) return __float_as_uint(a2);
   const float u = limit_floor(a2 * cq);
   int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
   v = v < 0 ? 0 : v;
@@ -134,6 +137,7 @@ __device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
 // Eq. 10 for one code.
 template <int K>
 __device__ inline float dequant(uint32_t q, float step, int32_t fb) {
+  if constexpr (K == 32) return __uint_as_float(q);
   const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
   const float t = (float)j + 0.5f;
   return step * t;

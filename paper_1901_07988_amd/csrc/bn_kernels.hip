@@ -239,12 +239,13 @@ __global__ __launch_bounds__(kFinThreads) void stats_finalize_kernel(const doubl
   const float var_f = (float)var;
   const float rstd = (float)(1.0 / sqrt((double)var_f + (double)ABL_BN_EPS));
   const float gm = gamma[c], bt = beta[c];
-  const float two_k = (float)(1 << K);
+  // K = 32 (exact storage) has no quantizer: the constants are written as zeros
+  const float two_k = K < 32 ? (float)(1 << K) : 0.0f;
   const float six_g = 6.0f * gm;
   // double division then one rounding == correctly rounded fp32 division
-  const float cq = (float)((double)two_k / (double)six_g);
-  const float step = (float)((double)six_g / (double)two_k);
-  const int32_t fb = (int32_t)limit_floor(bt * cq);
+  const float cq = K < 32 ? (float)((double)two_k / (double)six_g) : 0.0f;
+  const float step = K < 32 ? (float)((double)six_g / (double)two_k) : 0.0f;
+  const int32_t fb = K < 32 ? (int32_t)limit_floor(bt * cq) : 0;
   stats[P_MEAN * C + c] = mean_f;
   stats[P_VAR * C + c] = var_f;
   stats[P_RSTD * C + c] = rstd;
@@ -574,7 +575,10 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
       codes[i] = quant_code<K>(a2, stats[P_CQ * C + c], fbp[c]);
     }
   }
-  if constexpr (K == 4) {
+  if constexpr (K == 32) {
+#pragma unroll
+    for (int b = 0; b < 8; ++b) reinterpret_cast<uint32_t*>(packed)[e0 + b] = codes[b];
+  } else if constexpr (K == 4) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) packed[e0 / 2 + b] = (uint8_t)(codes[2 * b] | (codes[2 * b + 1] << 4));
   } else {
@@ -585,6 +589,7 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
 
 template <int K>
 __device__ inline uint32_t flat_code(const uint8_t* __restrict__ packed, int64_t e) {
+  if constexpr (K == 32) return reinterpret_cast<const uint32_t*>(packed)[e];
   if constexpr (K == 4) return (packed[e >> 1] >> ((e & 1) * 4)) & 15u;
   return packed[e];
 }
@@ -666,6 +671,7 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_apply_kernel(const uint8_t*
 
 // VEC used by the fast path for (K, C); 0 = use the flat fallback.
 int fast_vec(int K, int C) {
+  if (K == 32) return 0;  // exact storage runs on the element-wise kernels
   if (K == 4) return C % 8 == 0 ? 8 : (C % 4 == 0 ? 4 : 0);
   return C % 4 == 0 ? 4 : 0;
 }
@@ -721,8 +727,10 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
     uint8_t* pk = static_cast<uint8_t*>(packed);
     if (K == 4)
       flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
-    else
+    else if (K == 8)
       flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+    else
+      flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
@@ -762,8 +770,10 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
     if (K == 4)
       flat_unpack_kernel<4><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
-    else
+    else if (K == 8)
       flat_unpack_kernel<8><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+    else
+      flat_unpack_kernel<32><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
@@ -789,8 +799,10 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
   if (vec == 0) {
     if (K == 4)
       flat_bwd_reduce_kernel<4><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
-    else
+    else if (K == 8)
       flat_bwd_reduce_kernel<8><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+    else
+      flat_bwd_reduce_kernel<32><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
   } else if (K == 4 && vec == 8) {
     bwd_reduce_kernel<4, 8><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
   } else if (K == 4) {
@@ -823,8 +835,10 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
     if (K == 4 && accum) flat_bwd_apply_kernel<4, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
     else if (K == 4) flat_bwd_apply_kernel<4, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else if (accum) flat_bwd_apply_kernel<8, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else flat_bwd_apply_kernel<8, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else if (K == 8 && accum) flat_bwd_apply_kernel<8, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else if (K == 8) flat_bwd_apply_kernel<8, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else if (accum) flat_bwd_apply_kernel<32, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    else flat_bwd_apply_kernel<32, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
     return hip_status();
   }
   const RowGeom ga = make_geom(M, C, vec, false);

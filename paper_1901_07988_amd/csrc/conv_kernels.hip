@@ -327,7 +327,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 // Weight gradient from the packed activation.  One block = one filter tap x TM input
 // channels x TN output channels x one slice of the output pixels; a chunk of 64 pixels is
 // staged in LDS (activations dequantized + ReLU'd to fp32 on the way in; K == 32: `packed` is
-// an fp32 activation tensor that is used as it is), each wave
+// an fp32 tensor: the conv input itself, or with relu32 the pre-ReLU activation A2 of exact
+// storage), each wave
 // contracts 16 of them into its own accumulators, the four waves are summed in a fixed
 // order at the end.  partial layout: [split][R][S][Cin][Cout].
 template <int TM, int TN, int K, bool BF16>
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
                                                          float* __restrict__ partial, ConvGeom g,
-                                                         int chunks_per_split, int nsplit) {
+                                                         int chunks_per_split, int nsplit, int relu32) {
   constexpr int CH = 64;                                  // pixels per chunk
   constexpr int LDA = (TM % 32 == 0) ? TM + 16 : TM;
   constexpr int LDB = (TN % 32 == 0) ? TN + 16 : TN;
@@ -442,7 +443,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
 #pragma unroll
         for (int v = 0; v < CPW; ++v) {
           if constexpr (K == 32) {
-            dst[v] = oka[i] ? __uint_as_float(wa[i]) : 0.f;
+            const float f = __uint_as_float(wa[i]);
+            dst[v] = (oka[i] && !(relu32 != 0 && f < 0.f)) ? f : 0.f;
           } else {
             const int32_t j = (int32_t)((wa[i] >> (K * v)) & ((1u << K) - 1)) - (1 << (K - 1)) + fb[v];
             const float a2t = step[v] * ((float)j + 0.5f);          // Eq. 10
@@ -583,7 +585,7 @@ template <int K>
 __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __restrict__ packed,
                                                                const float* __restrict__ stats,
                                                                const float* __restrict__ dy,
-                                                               float* __restrict__ dw, ConvGeom g) {
+                                                               float* __restrict__ dw, ConvGeom g, int relu32) {
   __shared__ float red[kThreads];
   int t = blockIdx.x;
   const int co = t % g.Cout; t /= g.Cout;
@@ -601,7 +603,8 @@ __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __
     if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) continue;
     const int64_t e = (((int64_t)n * g.H + hi) * g.W + wi) * g.Cin + ci;
     if (K == 32) {
-      acc += reinterpret_cast<const float*>(packed)[e] * dy[p * g.Cout + co];
+      const float f = reinterpret_cast<const float*>(packed)[e];
+      if (!(relu32 != 0 && f < 0.f)) acc += f * dy[p * g.Cout + co];
       continue;
     }
     uint32_t code;
@@ -758,39 +761,40 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
 
 template <int TM, int TN>
 static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K, bool bf16,
-                              const void* packed, const float* stats, const float* dy, float* dst) {
+                              const void* packed, const float* stats, const float* dy, float* dst, int relu32) {
   dim3 grid((unsigned)((p.split + 7) / 8 * 8 * p.tiles));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
   auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true> : wgrad_kernel<TM, TN, 4, false>)
             : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>)
                      : (bf16 ? wgrad_kernel<TM, TN, 32, true> : wgrad_kernel<TM, TN, 32, false>);
-  kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split);
+  kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split, relu32);
 }
 
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
-                             const void* stats, const float* dy, void* scratch, float* dw) {
+                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32) {
+  const int r32 = relu32 ? 1 : 0;
   const ConvGeom g = geom_of(s);
   const float* sp = static_cast<const float*>(stats);
   if (!mfma_ok(g)) {
     const unsigned blocks = (unsigned)(g.R * g.S * g.Cin * g.Cout);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
-    if (K == 4) naive_wgrad_kernel<4><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
-    else if (K == 8) naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
-    else naive_wgrad_kernel<32><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g);
+    if (K == 4) naive_wgrad_kernel<4><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g, 0);
+    else if (K == 8) naive_wgrad_kernel<8><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g, 0);
+    else naive_wgrad_kernel<32><<<blocks, kThreads, 0, st>>>(pk, sp, dy, dw, g, r32);
     return hip_status();
   }
   if (K != 32 && use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
-  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 32) launch_wgrad_tile<32, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 32 && p.tn == 16) launch_wgrad_tile<32, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, bf16, packed, sp, dy, dst);
-  else launch_wgrad_tile<16, 16>(st, g, p, K, bf16, packed, sp, dy, dst);
+  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 32 && p.tn == 32) launch_wgrad_tile<32, 32>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 32 && p.tn == 16) launch_wgrad_tile<32, 16>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else launch_wgrad_tile<16, 16>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   if (p.split > 1) {
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
     wgrad_reduce_kernel<<<(unsigned)((n + 63) / 64), kThreads, 0, st>>>(dst, p.split, n, dw);

@@ -74,3 +74,16 @@ def test_stack_plan_validation(B):
     assert B.abl_stack_scratch_bytes(ok, 4) >= 2 * 8 * 8 * 16 * 4
     broken = B.make_layers([mk((2, 8, 8, 16, 32, 3, 3, 2, 1)), mk((2, 8, 8, 32, 32, 3, 3, 1, 1))])
     assert B.lib.abl_stack_forward(None, broken, 2, 4, 0, 0, 16, 32, 48, 1 << 30) == B.ABL_ERR_SHAPE
+
+
+def test_exact_storage_sizes_and_k_validation(B):
+    """K = 32 keeps the fp32 tensor (alpha = 1, Sec. 3.4); the fused entry points refuse it."""
+    t = (4, 32, 32, 16, 16, 3, 3, 1, 1)
+    E = 4 * 32 * 32 * 16
+    assert B.abl_packed_bytes(t, 32) == 4 * E
+    assert B.abl_packed_bytes(t, 8) * 4 == B.abl_packed_bytes(t, 32)
+    assert B.abl_scratch_bytes(t, 32) > 0
+    ref = ctypes.byref(B.shape_struct(t))
+    assert B.lib.abl_packed_bytes(ref, 16) == 0
+    assert B.lib.abl_bn_conv_fwd(None, ref, 32, 0, 16, 16, 16, None, 32, 16) == B.ABL_ERR_ARG
+    assert B.lib.abl_postact_packed_bytes(ref, 32) == 0

@@ -555,3 +555,53 @@ def test_one_kernel_conv_backward(G, oracle, s, K):
     _, dg_ref, db_ref = o.bn_relu_bwd(a2t, da3_ref, saved.rstd, gamma, beta)
     scale = max(1.0, float(np.abs(da3_ref).sum((0, 1, 2)).max()))
     assert np.max(np.abs(part[0] - db_ref)) < TOL * scale and np.max(np.abs(part[1] - dg_ref)) < TOL * scale
+
+
+@pytest.mark.parametrize("case", LAYER_CASES[:10], ids=lambda c: "x".join(map(str, c[0].as_tuple())))
+def test_layer_exact_storage(G, oracle, case):
+    """K = 32 (Sec. 3.2 with alpha = 1: the fp32 A2 itself is stored): the store is bit-exact, the
+    gradients are those of exact back-propagation."""
+    o = oracle
+    s, xd, aff = case
+    print("case layer K=32", s.as_tuple(), flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, synth.DEFAULT_SEED, xd, aff)
+    run = G.LayerRun(s, 32)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, 32, oshape(o, s))
+    n = saved.store.size * saved.store.itemsize
+    assert run.packed.cpu().numpy().tobytes()[:n] == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+    assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+
+
+def test_exact_storage_stack_and_round_trip(G, oracle):
+    """A residual stack with K = 32 against the oracle's exact mode, and pack -> unpack at K = 32
+    returning the input bits."""
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    wl = synth.config2(N=8, layers=6)
+    x, layers, dy = synth.draw_stack(wl)
+    run = G.StackRun(layers, 32, wl.skip_every)
+    run.load(x)
+    run.forward()
+    ol = [(oshape(o, s), w, g, b) for s, w, g, b in layers]
+    y_ref, saved = o.stack_forward(x, ol, 32, np.float32, wl.skip_every)
+    assert rel(run.output(), y_ref) < TOL
+    run.load(dy)
+    run.backward()
+    dx_ref, grads = o.stack_backward(saved, ol, dy, np.float32, wl.skip_every)
+    # (an activation within rounding of zero may take the other side of the ReLU on the two sides:
+    # the same allowance as for the quantized stacks)
+    assert close_but_for_flips(run.input_grad(), dx_ref)
+    for d, (dw_ref, dg_ref, db_ref) in zip(run.descs, grads):
+        assert close_but_for_flips(d["dW"].cpu().numpy(), dw_ref, 20 * TOL)
+        assert close_but_for_flips(d["dbeta"].cpu().numpy(), db_ref, 50 * TOL)
+    assert run.stored_bytes() >= sum(4 * s.E for s in wl.shapes)
+    a2 = np.random.default_rng(3).standard_normal((50, 20)).astype(np.float32)
+    st = G.run_bn_stats(a2, np.ones(20, np.float32), np.zeros(20, np.float32), 32)
+    packed = G.run_pack(a2, st, 32)
+    assert packed.tobytes()[: a2.size * 4] == a2.tobytes()
+    assert G.run_unpack(packed, a2.shape, st, 32).tobytes() == a2.tobytes()
