@@ -66,6 +66,10 @@ enum {
                              matrix cores, fp32 accumulation; everything else (statistics, codes,
                              BN forward/backward) is unchanged.  Default: fp32 operands. */
   ABL_XIN_F32 = 1u << 3,   /* abl_postact_backward: xin is the exact fp32 conv input            */
+  ABL_NAIVE_FWD = 1u << 5, /* abl_forward / abl_stack_forward: the comparison baseline of Sec. 4 - the
+                              convolution consumes the ReLU of the DEQUANTIZED copy (Eq. 10) instead
+                              of the exact A3, so the approximation error enters the forward pass and
+                              compounds from layer to layer; for error studies, not for speed */
   ABL_XIN_PACKED = 1u << 4 /* abl_postact_backward: xin / xin_stats are the previous layer's
                               packed store and stats (its ReLU output is rebuilt on the fly)   */
 };

@@ -267,13 +267,16 @@ class Saved:
 
 
 def layer_forward(x, w, gamma, beta, K, s: Shape, skip=None, dtype=np.float32, eps=EPS,
-                  stats=None, keep=False):
+                  stats=None, keep=False, naive=False):
     """Forward of one pre-activation layer.  The output never sees the codes: it is computed
     from the full-precision A3 (Sec. 3.2), so it is the same for every K.
 
     ``stats`` = (mean, var) overrides the batch statistics (used to feed the GPU's own
     statistics to the quantizer in the two-tier code-parity test).
     Returns (y, Saved) and, with ``keep``, also a dict of the intermediates.
+
+    ``naive``: the comparison baseline of Sec. 4 - the convolution consumes the ReLU of the
+    dequantized copy instead of the exact A3, so the approximation also enters the forward pass.
     """
     x = _c(x, dtype)
     mean, var = bn_stats(x, dtype) if stats is None else (_c(stats[0], dtype), _c(stats[1], dtype))
@@ -284,6 +287,8 @@ def layer_forward(x, w, gamma, beta, K, s: Shape, skip=None, dtype=np.float32, e
     else:
         q = quantize(a2, gamma, beta, K, dtype)
         store = pack_codes(q, K)
+        if naive:
+            a3 = np.maximum(dequantize(q, gamma, beta, K, dtype), np.dtype(dtype).type(0))
     y = conv_fwd(a3, w, s, dtype)
     if skip is not None:
         y = y + _c(skip, dtype)
@@ -317,7 +322,7 @@ def layer_backward(saved: Saved, dy, w, dtype=np.float32, keep=False):
 
 
 # --------------------------------------------------------------------------- residual stack
-def stack_forward(x, layers, K, dtype=np.float32, skip_every=2):
+def stack_forward(x, layers, K, dtype=np.float32, skip_every=2, naive=False):
     """Chain of pre-activation layers with identity skips (Sec. 3.4, Fig. 2).
 
     ``layers`` is a list of (Shape, W, gamma, beta).  The residual stream enters a group of
@@ -328,7 +333,7 @@ def stack_forward(x, layers, K, dtype=np.float32, skip_every=2):
     saved = []
     for i, (sh, w, g, b) in enumerate(layers):
         last_of_group = skip_every > 0 and (i + 1) % skip_every == 0
-        y, sv = layer_forward(t, w, g, b, K, sh, dtype=dtype)
+        y, sv = layer_forward(t, w, g, b, K, sh, dtype=dtype, naive=naive)
         if last_of_group and y.shape == s_stream.shape:
             y = y + s_stream
         saved.append(sv)

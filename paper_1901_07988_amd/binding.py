@@ -16,6 +16,7 @@ ABL_OK, ABL_ERR_ARG, ABL_ERR_SHAPE, ABL_ERR_SCRATCH, ABL_ERR_HIP = range(5)
 ABL_ACCUM_DX = 1
 ABL_MATH_BF16 = 2
 ABL_XIN_F32 = 8
+ABL_NAIVE_FWD = 32
 ABL_XIN_PACKED = 16
 STATS_PLANES = 8
 

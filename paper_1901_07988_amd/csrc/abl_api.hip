@@ -179,6 +179,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   float* a3 = static_cast<float*>(scratch);
   void* red = static_cast<char*>(scratch) + act;
   const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  const bool naive = (flags & ABL_NAIVE_FWD) != 0 && K != 32;
   if (out_nb != nullptr) *out_nb = 0;
   if (in_partial != nullptr && in_nb > 0) {
     if (int e = launch_bn_stats_finalize(st, in_partial, in_nb, nullptr, M, s->Cin, gamma, beta, K, stats)) return e;
@@ -189,7 +190,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
   // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
   // overwrite input pixels that a neighbouring block has not staged yet.)
-  if (K != 32 && halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
+  if (K != 32 && !naive && halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
     const int tiles = halo_tile_count(g, 0);
     const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
     if (int e = launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed, want ? out_partial : nullptr))
@@ -198,9 +199,9 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     return ABL_OK;
   }
   // 1x1 convolutions do the same while they stage their A tile
-  if (K != 32 && igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
+  if (K != 32 && !naive && igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
     return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed);
-  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed)) return e;
+  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, naive)) return e;
   return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
 }
 
@@ -213,7 +214,7 @@ int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const f
                 size_t scratch_bytes, float* y, void* packed, void* stats) {
   if (int e = check_shape(s)) return e;
   if (int e = check_k(K)) return e;
-  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_NAIVE_FWD)) return ABL_ERR_ARG;
   if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
       bad_ptr(packed) || bad_ptr(stats) || (skip != nullptr && !aligned16(skip)))
     return ABL_ERR_ARG;
@@ -493,7 +494,7 @@ extern "C" {
 int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
                       size_t scratch_bytes) {
-  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_NAIVE_FWD)) return ABL_ERR_ARG;
   if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
   const size_t xbytes = stack_xpart_bytes(layers, L);
   double* xpart = static_cast<double*>(scratch);

@@ -20,8 +20,9 @@ size_t bn_partial_bytes(int64_t M, int C);
 // ---- batch-norm / quantizer kernels (bn_kernels.hip) ----
 int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const float* gamma,
                     const float* beta, int K, void* scratch, void* stats);
+// naive: a3 = ReLU of the dequantized code instead of the exact A3 (the baseline of Sec. 4).
 int launch_bn_relu_pack(hipStream_t st, const float* x, int64_t M, int C, int K, const void* stats,
-                        float* a3, void* packed);
+                        float* a3, void* packed, bool naive = false);
 int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const void* stats,
                 void* packed);
 int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, const void* stats,

@@ -552,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
                                                                    int C, int64_t packed_bytes,
                                                                    const float* __restrict__ stats,
                                                                    float* __restrict__ a3,
-                                                                   uint8_t* __restrict__ packed) {
+                                                                   uint8_t* __restrict__ packed, int naive) {
   const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t e0 = t * 8;
   if (e0 * K / 8 >= packed_bytes) return;
@@ -573,6 +573,12 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
         a3[e] = a2 > 0.0f ? a2 : 0.0f;
       }
       codes[i] = quant_code<K>(a2, stats[P_CQ * C + c], fbp[c]);
+      if constexpr (MODE == 0) {
+        if (naive) {  // the convolution gets the approximation (Eq. 10), not A3
+          const float a2t = dequant<K>(codes[i], stats[P_STEP * C + c], fbp[c]);
+          a3[e] = a2t > 0.0f ? a2t : 0.0f;
+        }
+      }
     }
   }
   if constexpr (K == 32) {
@@ -715,22 +721,23 @@ int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, cons
 
 template <int MODE>
 static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, int K, const void* stats,
-                             float* a3, void* packed) {
+                             float* a3, void* packed, bool naive = false) {
   const float* sp = static_cast<const float*>(stats);
   const int64_t E = M * C;
   const int64_t raw = (E * K + 7) / 8;
   const int64_t pbytes = (raw + 127) / 128 * 128;
-  const int vec = fast_vec(K, C);
+  const int vec = naive ? 0 : fast_vec(K, C);  // the baseline variant exists in the element-wise kernel only
   if (vec == 0) {
+    const int nv = naive ? 1 : 0;
     const int64_t threads = pbytes * 8 / K / 8;
     const unsigned blocks = (unsigned)((threads + kThreads - 1) / kThreads);
     uint8_t* pk = static_cast<uint8_t*>(packed);
     if (K == 4)
-      flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+      flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
     else if (K == 8)
-      flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+      flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
     else
-      flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk);
+      flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
@@ -751,8 +758,8 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
 }
 
 int launch_bn_relu_pack(hipStream_t st, const float* x, int64_t M, int C, int K, const void* stats,
-                        float* a3, void* packed) {
-  return launch_quant_pack<0>(st, x, M, C, K, stats, a3, packed);
+                        float* a3, void* packed, bool naive) {
+  return launch_quant_pack<0>(st, x, M, C, K, stats, a3, packed, naive);
 }
 
 int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const void* stats,

@@ -157,7 +157,7 @@ class LayerRun:
         dg = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
         db = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
         B.abl_backward(s.as_tuple(), self.K, self.packed, self.stats, dev(dy), dev(w), self.scratch, dx, dw, dg, db,
-                       flags=self.flags | (B.ABL_ACCUM_DX if accum_into is not None else 0))
+                       flags=(self.flags & ~B.ABL_NAIVE_FWD) | (B.ABL_ACCUM_DX if accum_into is not None else 0))
         torch.cuda.synchronize()
         return dx.cpu().numpy(), dw.cpu().numpy(), dg.cpu().numpy(), db.cpu().numpy()
 
@@ -193,7 +193,7 @@ class StackRun:
 
     def backward(self):
         B.abl_stack_backward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
-                             flags=self.flags)
+                             flags=self.flags & ~B.ABL_NAIVE_FWD)
 
     def output(self):
         n = int(np.prod(out_shape(self.last)))

@@ -605,3 +605,42 @@ def test_exact_storage_stack_and_round_trip(G, oracle):
     packed = G.run_pack(a2, st, 32)
     assert packed.tobytes()[: a2.size * 4] == a2.tobytes()
     assert G.run_unpack(packed, a2.shape, st, 32).tobytes() == a2.tobytes()
+
+
+@pytest.mark.parametrize("s", [LayerShape(4, 16, 16, 16, 16), LayerShape(2, 14, 14, 64, 32, 1, 1, 1, 0),
+                               LayerShape(3, 7, 5, 6, 10)], ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_naive_forward_baseline(G, oracle, s, K):
+    """ABL_NAIVE_FWD (the comparison baseline of Sec. 4): the convolution consumes the ReLU of the
+    dequantized codes.  Codes bit-exact, outputs and gradients against the oracle's naive mode."""
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    print("case naive", s.as_tuple(), K, flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 21, "normal", "random")
+    run = G.LayerRun(s, K, flags=B.ABL_NAIVE_FWD)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s), naive=True)
+    y_exact, _ = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+    assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL
+    assert rel(y, y_exact) > 10 * TOL          # it really is another forward pass
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+    assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+
+
+def test_errors_do_not_compound_with_depth(G):
+    """Sec. 3.2-3.3 on a 12-layer residual stack: with the proposed method the forward output is
+    that of exact training and the weight-gradient error is of the same size at the top and at
+    the bottom of the stack; with the naive baseline the output is wrong and the error of the
+    bottom layers is several times that of the proposed method."""
+    from paper_1901_07988_amd import error_study
+    res = error_study.study(layers_n=12, batch=8, ks=(4,))
+    p, n = res["proposed K=4"], res["naive K=4"]
+    assert p["out"] < 1e-6                      # exact forward pass
+    assert n["out"] > 1e-2                      # the baseline's forward pass has drifted
+    assert max(p["dW"]) < 0.25 and max(p["dW"]) < 2 * min(p["dW"])   # proposed: no trend with depth
+    assert all(a > 1.5 * b for a, b in zip(n["dW"], p["dW"]))        # the baseline is worse everywhere,
+    assert n["dW"][0] > 1.2 * n["dW"][-1]                            # and worse the further the error travelled
+    assert p["dx"] < 0.02 and n["dx"] > 10 * p["dx"]

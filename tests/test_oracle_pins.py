@@ -521,3 +521,50 @@ def test_postact_chain_is_conv_then_preact_layers_then_bn_relu(oracle, K):
     assert g2[2].tobytes() == dg2.tobytes() and g2[3].tobytes() == db2.tobytes()
     assert g1[2].tobytes() == p2[2].tobytes() and g0[2].tobytes() == p1[2].tobytes()     # dgamma_1, dgamma_0
     np.testing.assert_array_equal(g0[1], o.conv_wgrad(x, p1[0], shapes[0]))               # dW_0 from exact x
+
+
+# ---- the naive-approximation baseline (Sec. 4): the approximation also enters the forward pass
+def test_naive_forward_baseline_pins(oracle):
+    o = oracle
+    s = o.Shape(2, 8, 8, 4, 5, 3, 3, 1, 1)
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((s.N, s.H, s.W, s.Cin)).astype(np.float32)
+    w = (rng.standard_normal((3, 3, s.Cin, s.Cout)) * 0.3).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, s.Cin).astype(np.float32)
+    beta = (rng.standard_normal(s.Cin) * 0.1).astype(np.float32)
+    y_exact, sv_exact = o.layer_forward(x, w, gamma, beta, 4, s)
+    # exact storage has nothing to approximate: the flag changes nothing
+    y32, _ = o.layer_forward(x, w, gamma, beta, 32, s, naive=True)
+    assert y32.tobytes() == o.layer_forward(x, w, gamma, beta, 32, s)[0].tobytes()
+    for K in (4, 8):
+        y_naive, sv, inter = o.layer_forward(x, w, gamma, beta, K, s, naive=True, keep=True)
+        # what is stored does not depend on the flag, what the convolution sees does
+        assert sv.store.tobytes() == o.layer_forward(x, w, gamma, beta, K, s)[1].store.tobytes()
+        assert not np.array_equal(y_naive, y_exact)
+        # the input of the convolution moved by at most half a step per element (Sec. 3.2) where
+        # nothing was clipped, so each output moved by at most sum |W| step/2 over its window
+        step = 6.0 * gamma / 2.0 ** K
+        a2 = inter["a2"]
+        a3t = np.maximum(o.recover_a2(sv), 0).astype(np.float32)
+        # by linearity of Eq. 4 the output moved by the convolution of what the input moved by
+        shift = o.conv_fwd((a3t - np.maximum(a2, 0)).astype(np.float32), w, s)
+        assert np.max(np.abs(y_naive - (y_exact + shift))) < 1e-5 * max(1.0, float(np.abs(y_exact).max()))
+        clipped = np.abs(o.recover_a2(sv) - a2) > np.abs(step) / 2 * (1 + 1e-5) + 1e-7
+        if not clipped.any():
+            bound = np.abs(w).transpose(0, 1, 3, 2).reshape(-1, s.Cin) @ (np.abs(step) / 2)
+            assert np.all(np.abs(y_naive - y_exact) <= bound.reshape(3, 3, s.Cout).sum((0, 1)) * (1 + 1e-4) + 1e-5)
+    # in a stack the naive forward drifts away from the exact one with depth, the proposed one
+    # (forward untouched) does not move at all
+    L = 8
+    sh = o.Shape(2, 8, 8, 8, 8, 3, 3, 1, 1)
+    xs = rng.standard_normal((2, 8, 8, 8)).astype(np.float32)
+    layers = [(sh, (rng.standard_normal((3, 3, 8, 8)) * np.sqrt(2 / 72)).astype(np.float32),
+               np.ones(8, np.float32), np.zeros(8, np.float32)) for _ in range(L)]
+    errs = []
+    for depth in (2, 4, 8):
+        y_e, _ = o.stack_forward(xs, layers[:depth], 32, np.float32, 2)
+        y_p, _ = o.stack_forward(xs, layers[:depth], 4, np.float32, 2)
+        y_n, _ = o.stack_forward(xs, layers[:depth], 4, np.float32, 2, naive=True)
+        assert y_p.tobytes() == y_e.tobytes()
+        errs.append(float(np.linalg.norm(y_n - y_e) / np.linalg.norm(y_e)))
+    assert errs[0] > 0 and errs[2] > errs[0]
