@@ -847,7 +847,8 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   float* tdy = lds;                                       // [patch][PS] dy
   float* tact = lds + patch * PS;                         // [patch][PS] A3~
   // the two patches are reused for the cross-wave sum of dW (4 x 9 x 256 floats) at the end
-  const int region = 2 * patch * PS > 4 * 9 * 256 ? 2 * patch * PS : 4 * 9 * 256;
+  // (+ one spare pixel row behind the activation patch: the target of staging slots past its end)
+  const int region = (2 * patch + 1) * PS > 4 * 9 * 256 ? (2 * patch + 1) * PS : 4 * 9 * 256;
   int* pixbase = reinterpret_cast<int*>(lds + region);    // [256] LDS offset of tile pixel m, tap (0,0)
   int* pixoff = pixbase + kThreads;                       // [256] global offset of (pixel m, channel 0), -1 outside
   double* red = reinterpret_cast<double*>(pixoff + kThreads);  // [2][4][16]
@@ -917,24 +918,30 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   for (int t = 0; t < 9; ++t)
     bw[t][0] = *reinterpret_cast<const float4*>(wgt + (t * C + li) * C + 4 * lk);
 
+  // dy goes to LDS first: the dA3 contraction needs nothing else, so the first MFMAs start one
+  // global-load round trip after the kernel does.  The activation patch is dequantized between
+  // the taps of that contraction (branch-free: slots past the end of the patch write the spare
+  // row).  (fp32 MFMAs and vector ALU instructions share the SIMD's issue slots on this chip -
+  // measured: their times add up, across waves too - so this hides latency, not arithmetic.)
 #pragma unroll
   for (int j = 0; j < AMAX; ++j) {
     const int idx = tid + kThreads * j;
-    if (goff[j] != -2) {
-      const bool ok = goff[j] >= 0;
-      const float st4[4] = {q_step.x, q_step.y, q_step.z, q_step.w};
-      const int32_t fb4[4] = {q_fb.x, q_fb.y, q_fb.z, q_fb.w};
-      float a[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float a2t = dequant<K>((rc[j] >> (K * e)) & ((1u << K) - 1u), st4[e], fb4[e]);  // Eq. 10
-        a[e] = (ok && a2t > 0.0f) ? a2t : 0.0f;                                              // Eq. 3
-      }
-      const int o = (idx >> 2) * PS + 4 * (idx & 3);
-      *reinterpret_cast<float4*>(&tdy[o]) = keep_if(ok, rd[j]);
-      *reinterpret_cast<float4*>(&tact[o]) = make_float4(a[0], a[1], a[2], a[3]);
-    }
+    if (goff[j] != -2) *reinterpret_cast<float4*>(&tdy[(idx >> 2) * PS + 4 * (idx & 3)]) = keep_if(goff[j] >= 0, rd[j]);
   }
+  auto stage_act = [&](int j) __attribute__((always_inline)) {
+    const int idx = tid + kThreads * j;
+    const bool ok = goff[j] >= 0;
+    const float st4[4] = {q_step.x, q_step.y, q_step.z, q_step.w};
+    const int32_t fb4[4] = {q_fb.x, q_fb.y, q_fb.z, q_fb.w};
+    float a[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a2t = dequant<K>((rc[j] >> (K * e)) & ((1u << K) - 1u), st4[e], fb4[e]);  // Eq. 10
+      a[e] = (ok && a2t > 0.0f) ? a2t : 0.0f;                                              // Eq. 3
+    }
+    const int o = goff[j] != -2 ? (idx >> 2) * PS + 4 * (idx & 3) : patch * PS + 4 * (idx & 3);
+    *reinterpret_cast<float4*>(&tact[o]) = make_float4(a[0], a[1], a[2], a[3]);
+  };
   __syncthreads();
 
   const int ctr = (p.HW + 1) * PS;  // from tap (0,0) to the pixel itself
@@ -953,7 +960,9 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
 #pragma unroll
     for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const float4*>(&tdy[mbase[i] + aoff]);
     mma_k4<BF16, 1, 4>(bw[t], af, accd);
+    if (t < AMAX) stage_act(t);
   }
+  __syncthreads();  // the activation patch is complete
 
   // ---- dW: the wave's 64 pixels, 16 per step; component e of the operand vectors is pixel
   // 4e + lk of the step (fp32: k-step e, lane group = k) or 4lk + e (bf16) ----
@@ -1072,6 +1081,7 @@ bool make_bwd16_plan(const ConvGeom& g, HaloPlan& p) {
   size_t bytes = (size_t)2 * p.TI * p.HH * p.HW * PS * sizeof(float);
   const size_t wred = (size_t)4 * 9 * 256 * sizeof(float);
   if (bytes < wred) bytes = wred;
+  bytes += PS * sizeof(float);  // spare pixel row
   bytes += 2 * kThreads * sizeof(int) + 2 * 4 * 16 * sizeof(double);
   p.lds_bytes = (unsigned)bytes;
   return bytes <= 64 * 1024;
