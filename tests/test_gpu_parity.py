@@ -644,3 +644,27 @@ def test_errors_do_not_compound_with_depth(G):
     assert all(a > 1.5 * b for a, b in zip(n["dW"], p["dW"]))        # the baseline is worse everywhere,
     assert n["dW"][0] > 1.2 * n["dW"][-1]                            # and worse the further the error travelled
     assert p["dx"] < 0.02 and n["dx"] > 10 * p["dx"]
+
+
+@pytest.mark.parametrize("s", [LayerShape(128, 1, 1, 64, 10, 1, 1, 1, 0), LayerShape(37, 1, 1, 256, 48, 1, 1, 1, 0),
+                               LayerShape(16, 1, 1, 100, 10, 1, 1, 1, 0)], ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_fully_connected_layer(G, oracle, s, K):
+    """A fully-connected layer is the same layer with 2-D activations (Sec. 3.1: [B, C] tensors,
+    statistics over the batch): here a 1x1 convolution on 1x1 images.  Channel counts that are not
+    multiples of 16 (a 10-way classifier) run on the element-wise kernels."""
+    o = oracle
+    print("case fc", s.as_tuple(), K, flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 33, "normal", "random")
+    run = G.LayerRun(s, K)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+    assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL
+    # the library routine this reduces to: batch norm over the batch, ReLU, matrix product
+    a2 = (x.reshape(s.N, s.Cin).astype(np.float64) - saved.mean) * saved.rstd * gamma + beta
+    assert rel(y.reshape(s.N, s.Cout), np.maximum(a2, 0) @ w.reshape(s.Cin, s.Cout).astype(np.float64)) < TOL
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+    assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
