@@ -465,6 +465,34 @@ GroupInfo group_info(const abl_layer* layers, int L, int skip_every, int i) {
   return gi;
 }
 
+// Which of the two buffers a layer reads (x / dx) and writes (y / dy): true = S.
+//  * In a group the first layer reads S and writes T, middle layers run in place on T, the last
+//    layer writes S (+ the shortcut).
+//  * Layers outside the groups (a plain chain, or what is left after the last complete group)
+//    alternate S -> T -> S ... so that input and output are different buffers and the fused
+//    forward kernels apply; when their number is odd the first of them runs in place on S, so
+//    that the chain ends in S.
+void layer_buffers(const abl_layer* layers, int L, int skip_every, int i, bool* x_is_s, bool* y_is_s) {
+  const GroupInfo gi = group_info(layers, L, skip_every, i);
+  if (gi.in_group) {
+    *x_is_s = gi.first;
+    *y_is_s = gi.last;
+    return;
+  }
+  const int a = skip_every > 0 ? (L / skip_every) * skip_every : 0;  // first layer outside the groups
+  const int len = L - a;
+  int pos = i - a;
+  if (len % 2 == 1) {
+    if (pos == 0) {
+      *x_is_s = *y_is_s = true;
+      return;
+    }
+    --pos;
+  }
+  *x_is_s = pos % 2 == 0;
+  *y_is_s = !*x_is_s;
+}
+
 int check_stack(const abl_layer* layers, int L, int K, int skip_every, const float* s, const float* t,
                 void* scratch, size_t scratch_bytes) {
   if (layers == nullptr || L < 1 || skip_every < 0) return ABL_ERR_ARG;
@@ -490,7 +518,8 @@ extern "C" {
 
 // Buffer plan (Fig. 2): S holds the residual stream, T the straight path.  The first layer
 // of a group reads S and writes T, middle layers run in place on T (a layer's input is dead
-// once A3 is in the workspace), the last layer writes S = conv + S.
+// once A3 is in the workspace), the last layer writes S = conv + S; layers outside the groups
+// alternate between the two buffers (layer_buffers).
 int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
                       size_t scratch_bytes) {
@@ -503,14 +532,11 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
   for (int i = 0; i < L; ++i) {
     const abl_layer& l = layers[i];
     const GroupInfo gi = group_info(layers, L, skip_every, i);
-    const float* x = buf_s;
-    float* y = buf_s;
-    const float* skip = nullptr;
-    if (gi.in_group) {
-      x = gi.first ? buf_s : buf_t;
-      y = gi.last ? buf_s : buf_t;
-      if (gi.last && gi.shortcut) skip = buf_s;
-    }
+    bool x_is_s, y_is_s;
+    layer_buffers(layers, L, skip_every, i, &x_is_s, &y_is_s);
+    const float* x = x_is_s ? buf_s : buf_t;
+    float* y = y_is_s ? buf_s : buf_t;
+    const float* skip = gi.in_group && gi.last && gi.shortcut ? buf_s : nullptr;
     if (bad_ptr(l.W) || bad_ptr(l.gamma) || bad_ptr(l.beta) || bad_ptr(l.packed) || bad_ptr(l.stats))
       return ABL_ERR_ARG;
     // layer i's convolution leaves the first-pass statistics of its output (= layer i+1's input)
@@ -539,14 +565,12 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
     const abl_layer& l = layers[i];
     if (bad_ptr(l.dW) || bad_ptr(l.dgamma) || bad_ptr(l.dbeta)) return ABL_ERR_ARG;
     const GroupInfo gi = group_info(layers, L, skip_every, i);
-    const float* dy = buf_s;
-    float* dx = buf_s;
+    bool x_is_s, y_is_s;
+    layer_buffers(layers, L, skip_every, i, &x_is_s, &y_is_s);
+    const float* dy = y_is_s ? buf_s : buf_t;
+    float* dx = x_is_s ? buf_s : buf_t;
     uint32_t f = flags;
-    if (gi.in_group) {
-      dy = gi.last ? buf_s : buf_t;
-      dx = gi.first ? buf_s : buf_t;
-      if (gi.first && gi.shortcut) f |= ABL_ACCUM_DX;
-    }
+    if (gi.in_group && gi.first && gi.shortcut) f |= ABL_ACCUM_DX;
     if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W,
                              static_cast<char*>(scratch) + xbytes, scratch_bytes - xbytes, dx, l.dW, l.dgamma,
                              l.dbeta))

@@ -116,11 +116,12 @@ def config2(N=128, layers=18):
 def config3(N=128, per_stage=18):
     """CIFAR-ResNet wider stages: a stride-2 transition then 3x3 layers at (32ch,16x16), then
     a stride-2 transition and 3x3 layers at (64ch, 8x8).  No skip crosses a transition, so the
-    two stages are returned as separate workloads."""
+    two stages are returned as separate workloads; identity skips every 2 layers where the
+    shapes agree (the pair that holds the transition has none)."""
     a = [LayerShape(N, 32, 32, 16, 32, stride=2)] + [LayerShape(N, 16, 16, 32, 32)] * (per_stage - 1)
     b = [LayerShape(N, 16, 16, 32, 64, stride=2)] + [LayerShape(N, 8, 8, 64, 64)] * (per_stage - 1)
-    return [Workload("config3a: 16->32 /2 then %dx(3x3 32->32 @16x16) N=%d" % (per_stage - 1, N), a, 0),
-            Workload("config3b: 32->64 /2 then %dx(3x3 64->64 @8x8) N=%d" % (per_stage - 1, N), b, 0)]
+    return [Workload("config3a: 16->32 /2 then %dx(3x3 32->32 @16x16) N=%d" % (per_stage - 1, N), a, 2),
+            Workload("config3b: 32->64 /2 then %dx(3x3 64->64 @8x8) N=%d" % (per_stage - 1, N), b, 2)]
 
 
 def config4(N=64, HW=56):

@@ -668,3 +668,24 @@ def test_fully_connected_layer(G, oracle, s, K):
     dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
     assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
     assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 4])
+def test_plain_chain_alternates_buffers(G, oracle, L):
+    """Stacks without shortcuts: the layers alternate between the two buffers (an odd chain runs
+    its first layer in place) and the result still lands in the first buffer."""
+    o = oracle
+    wl = synth.Workload("plain chain of %d" % L, [LayerShape(4, 16, 16, 16, 16)] * L, 0, "normal", "random")
+    x, layers, dy = synth.draw_stack(wl, 77)
+    run = G.StackRun(layers, 4, 0)
+    run.load(x)
+    run.forward()
+    ol = [(oshape(o, s), w, g, b) for s, w, g, b in layers]
+    y_ref, saved = o.stack_forward(x, ol, 4, np.float32, 0)
+    assert rel(run.output(), y_ref) < TOL
+    run.load(dy)
+    run.backward()
+    dx_ref, grads = o.stack_backward(saved, ol, dy, np.float32, 0)
+    assert close_but_for_flips(run.input_grad(), dx_ref, 5 * TOL, 0.01, 2e-3)
+    for d, (dw_ref, dg_ref, db_ref) in zip(run.descs, grads):
+        assert close_but_for_flips(d["dW"].cpu().numpy(), dw_ref, 20 * TOL, 0.01, 2e-3)
