@@ -117,10 +117,9 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
 // floor() limited to +-2^24 so that the integer conversion is defined for any input.
 __device__ inline float limit_floor(float u) {
   const float lim = 16777216.0f;
-  u = floorf(u);
-  u = (u >= -lim) ? u : -lim;  // NaN -> -lim
-  u = (u > lim) ? lim : u;
-  return u;
+  // one instruction: the median of (u, -lim, lim); a NaN input gives the smallest of the other
+  // two, -lim, as the comparison form (u >= -lim ? u : -lim) does
+  return __builtin_amdgcn_fmed3f(floorf(u), -lim, lim);
 }
 
 // Eq. 9 for one value (cq = 2^K/(6 gamma), fb = floor(beta*cq)).  K = 32 is exact storage: the

@@ -689,3 +689,29 @@ def test_plain_chain_alternates_buffers(G, oracle, L):
     assert close_but_for_flips(run.input_grad(), dx_ref, 5 * TOL, 0.01, 2e-3)
     for d, (dw_ref, dg_ref, db_ref) in zip(run.descs, grads):
         assert close_but_for_flips(d["dW"].cpu().numpy(), dw_ref, 20 * TOL, 0.01, 2e-3)
+
+
+@pytest.mark.parametrize("K", [4, 8])
+def test_quantizer_on_non_finite_and_huge_values(G, oracle, K):
+    """Eq. 9 must be defined for any input: floor() is limited to +-2^24 before the integer
+    conversion, a NaN takes the lowest code.  Same bytes on both sides."""
+    o = oracle
+    C = 16
+    rng = np.random.default_rng(5)
+    a2 = rng.standard_normal((64, C)).astype(np.float32)
+    a2[0, :] = np.nan
+    a2[1, :] = np.inf
+    a2[2, :] = -np.inf
+    a2[3, :] = 3e38
+    a2[4, :] = -3e38
+    a2[5, ::2] = 2.0 ** 25
+    a2[5, 1::2] = -(2.0 ** 25)
+    gamma = rng.uniform(0.5, 1.5, C).astype(np.float32)
+    beta = (rng.standard_normal(C) * 0.1).astype(np.float32)
+    st = G.run_bn_stats(rng.standard_normal((64, C)).astype(np.float32), gamma, beta, K)
+    got = G.run_pack(a2, st, K)
+    with np.errstate(all="ignore"):
+        ref = o.pack_codes(o.quantize(a2, gamma, beta, K), K)
+    assert got.tobytes()[: ref.size] == ref.tobytes()
+    codes = o.unpack_codes(ref, a2.shape, K)
+    assert np.all(codes[0] == 0) and np.all(codes[2] == 0) and np.all(codes[1] == 2 ** K - 1)
