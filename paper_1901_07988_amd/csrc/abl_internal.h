@@ -126,21 +126,27 @@ __device__ inline float limit_floor(float u) {
 // "code" is the value's bit pattern.
 template <int K>
 __device__ inline uint32_t quant_code(float a2, float cq, int32_t fb) {
-  if constexpr (K == 32) return __float_as_uint(a2);
-  const float u = limit_floor(a2 * cq);
-  int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
-  v = v < 0 ? 0 : v;
-  v = v > (1 << K) - 1 ? (1 << K) - 1 : v;
-  return (uint32_t)v;
+  if constexpr (K == 32) {
+    return __float_as_uint(a2);
+  } else {
+    const float u = limit_floor(a2 * cq);
+    int32_t v = (int32_t)u + (1 << (K - 1)) - fb;
+    v = v < 0 ? 0 : v;
+    v = v > (1 << K) - 1 ? (1 << K) - 1 : v;
+    return (uint32_t)v;
+  }
 }
 
 // Eq. 10 for one code.
 template <int K>
 __device__ inline float dequant(uint32_t q, float step, int32_t fb) {
-  if constexpr (K == 32) return __uint_as_float(q);
-  const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
-  const float t = (float)j + 0.5f;
-  return step * t;
+  if constexpr (K == 32) {
+    return __uint_as_float(q);
+  } else {
+    const int32_t j = (int32_t)q - (1 << (K - 1)) + fb;
+    const float t = (float)j + 0.5f;
+    return step * t;
+  }
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));

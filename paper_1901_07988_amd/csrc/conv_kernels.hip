@@ -625,8 +625,14 @@ __global__ __launch_bounds__(kThreads) void naive_wgrad_kernel(const uint8_t* __
 
 inline bool mfma_ok(const ConvGeom& g) { return g.Cin % 16 == 0 && g.Cout % 16 == 0; }
 
-// Tile choice: the largest tile whose grid still gives every CU about two blocks; a tile
-// that is too large for a small GEMM leaves compute units idle.
+// Tile choice, from timing the candidates on 1x1 and 3x3 layers at 56x56 and 14x14.  Blocks
+// of one wave per SIMD spend much of their time at the two barriers of a chunk, so the tile
+// that lets most blocks share a compute unit usually wins over the one with the fewest
+// operand re-reads: 64x64 with 32-channel chunks (four blocks per unit) when the grid has
+// at least two thousand of them, 128x64 (two per unit) below that; a contraction of at most
+// 64 channels has too few chunks to fill the double buffer and takes 16-channel chunks.  With
+// the normalize/quantize prologue the per-element work of staging is repeated by every block
+// along the output channels, so that variant prefers 128 output channels per block.
 template <int MODE, int FUSE>
 int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w,
                  const float* skip, float* out, const float* stats, void* packed) {
@@ -649,33 +655,26 @@ int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, 
     kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, g, stats, packed, pack_pad);           \
   } while (0)
   const int Cg = MODE == 0 ? g.Cin : g.Cout;
-  const int64_t want = 512;
-  if (Cg % 32 == 0) {  // 32-channel chunks: whole 128-byte lines per pixel row
-    if (Ng > 64) {
-      if (blocks(128, 128) >= want) ABL_IGEMM(128, 128, 64, 64, 32);
-      else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 32);
-      else ABL_IGEMM(64, 64, 32, 32, 32);
-    } else if (Ng > 32) {
-      if (blocks(256, 64) >= want) ABL_IGEMM(256, 64, 64, 64, 32);
-      else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 32);
-      else ABL_IGEMM(64, 64, 32, 32, 32);
-    } else if (Ng > 16) {
-      ABL_IGEMM(256, 32, 64, 32, 32);
+  const bool deep = (int64_t)Cg * g.R * g.S > 64;
+  if (Ng > 32) {
+    if (FUSE != 0 && Ng > 64) {
+      if (Cg % 32 != 0) ABL_IGEMM(128, 128, 64, 64, 16);
+      else if (blocks(128, 128) >= 512) ABL_IGEMM(128, 128, 64, 64, 32);
+      else ABL_IGEMM(64, 128, 32, 64, 32);
+    } else if (Cg % 32 != 0 || !deep) {
+      if (Ng > 64 && blocks(128, 64) >= 1024) ABL_IGEMM(128, 64, 64, 32, 16);
+      else ABL_IGEMM(64, 64, 32, 32, 16);
+    } else if (blocks(64, 64) >= 2048 || blocks(128, 64) < 256) {
+      ABL_IGEMM(64, 64, 32, 32, 32);
     } else {
-      ABL_IGEMM(256, 16, 64, 16, 32);
+      ABL_IGEMM(128, 64, 64, 32, 32);
     }
-  } else if (Ng > 64) {
-    if (blocks(128, 128) >= want) ABL_IGEMM(128, 128, 64, 64, 16);
-    else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 16);
-    else ABL_IGEMM(64, 64, 32, 32, 16);
-  } else if (Ng > 32) {
-    if (blocks(256, 64) >= want) ABL_IGEMM(256, 64, 64, 64, 16);
-    else if (blocks(128, 64) >= want) ABL_IGEMM(128, 64, 64, 32, 16);
-    else ABL_IGEMM(64, 64, 32, 32, 16);
-  } else if (Ng > 16) {
-    ABL_IGEMM(256, 32, 64, 32, 16);
+  } else if (Cg % 32 == 0) {  // 32-channel chunks: whole 128-byte lines per pixel row
+    if (Ng > 16) ABL_IGEMM(256, 32, 64, 32, 32);
+    else ABL_IGEMM(256, 16, 64, 16, 32);
   } else {
-    ABL_IGEMM(256, 16, 64, 16, 16);
+    if (Ng > 16) ABL_IGEMM(256, 32, 64, 32, 16);
+    else ABL_IGEMM(256, 16, 64, 16, 16);
   }
 #undef ABL_IGEMM
   return hip_status();
