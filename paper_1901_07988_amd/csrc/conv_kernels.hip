@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 // contracts 16 of them into its own accumulators, the four waves are summed in a fixed
 // order at the end.  partial layout: [split][R][S][Cin][Cout].
 template <int TM, int TN, int K, bool BF16>
-__global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restrict__ packed,
+__global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
                                                          float* __restrict__ partial, ConvGeom g,
@@ -353,12 +353,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_m = (g.Cin + TM - 1) / TM, tiles_n = (g.Cout + TN - 1) / TN;
-  // ids 8 apart share an XCD (and its L2): all tiles of one pixel slice run there back to back
+  // ids 8 apart share an XCD (and its L2): each XCD takes an equal, contiguous run of the
+  // (pixel slice, tile) pairs, so the tiles of one slice run there back to back
   const int ntiles = g.R * g.S * tiles_m * tiles_n;
-  const int slot = blockIdx.x >> 3;
-  const int split_idx = (slot / ntiles) * 8 + (blockIdx.x & 7);
-  if (split_idx >= nsplit) return;
-  int t = slot % ntiles;
+  const int per_xcd = (nsplit * ntiles + 7) >> 3;
+  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per_xcd || item >= nsplit * ntiles) return;
+  const int split_idx = item / ntiles;
+  int t = item - split_idx * ntiles;
   const int tn = t % tiles_n; t /= tiles_n;
   const int tm = t % tiles_m; t /= tiles_m;
   const int tap = t;
@@ -371,14 +373,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
 
   // per-thread dequantization constants: the thread's channel group is the same in every pass
   const int a_cg = tid % GA;
-  float step[CPW];
-  int32_t fb[CPW];
+  // Eq. 10 as one fused multiply-add per element: step * ((code - 2^(K-1) + fb) + 0.5) equals
+  // fma(step, code + off, step / 2) bit for bit, since code + off is an exact small integer,
+  // step / 2 is exact, and both forms round the same exact product once.
+  float step[CPW], off[CPW], half_step[CPW];
 #pragma unroll
   for (int v = 0; v < CPW; ++v) {
     const int c = ci0 + a_cg * CPW + v;
     const bool ok = K != 32 && c < g.Cin;
     step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
-    fb[v] = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
+    const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
+    off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
+    half_step[v] = 0.5f * step[v];
   }
 
   floatx4 acc[MT][NT];
@@ -404,13 +410,22 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
     a_ho[i] = q % g.Ho;
     a_n[i] = q / g.Ho;
   }
-  const int adv_w = CH % g.Wo, adv_h = CH / g.Wo;
+  // one chunk ahead = (adv_n images, adv_h rows, adv_w columns), carried without a loop
+  const int adv_n = CH / (g.Ho * g.Wo), adv_r = CH - adv_n * (g.Ho * g.Wo);
+  const int adv_h = adv_r / g.Wo, adv_w = adv_r - adv_h * g.Wo;
+  const bool flat = g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0;  // input pixel = output pixel
   const bool a_lane_ok = (ci0 + a_cg * CPW) < g.Cin;
   auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       const int idx = tid + kThreads * i;
       const int64_t p = pc + idx / GA;
+      if (flat) {
+        oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end;
+        const int64_t e = oka[i] ? p * g.Cin + ci0 : 0;
+        wa[i] = packed[e / CPW + (oka[i] ? a_cg : 0)];
+        continue;
+      }
       const int hi = a_ho[i] * g.stride + r - g.pad, wi = a_wo[i] * g.stride + s - g.pad;
       oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end && hi >= 0 && hi < g.H &&
                wi >= 0 && wi < g.W;
@@ -419,8 +434,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
       // advance to the same slot of the next chunk
       a_wo[i] += adv_w;
       a_ho[i] += adv_h;
+      a_n[i] += adv_n;
       if (a_wo[i] >= g.Wo) { a_wo[i] -= g.Wo; ++a_ho[i]; }
-      while (a_ho[i] >= g.Ho) { a_ho[i] -= g.Ho; ++a_n[i]; }
+      if (a_ho[i] >= g.Ho) { a_ho[i] -= g.Ho; ++a_n[i]; }
     }
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
@@ -446,9 +462,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const uint32_t* __restr
             const float f = __uint_as_float(wa[i]);
             dst[v] = (oka[i] && !(relu32 != 0 && f < 0.f)) ? f : 0.f;
           } else {
-            const int32_t j = (int32_t)((wa[i] >> (K * v)) & ((1u << K) - 1)) - (1 << (K - 1)) + fb[v];
-            const float a2t = step[v] * ((float)j + 0.5f);          // Eq. 10
-            dst[v] = (oka[i] && a2t > 0.f) ? a2t : 0.f;             // Eq. 3
+            const float code = (float)((wa[i] >> (K * v)) & ((1u << K) - 1));
+            const float a2t = __builtin_fmaf(step[v], code + off[v], half_step[v]);  // Eq. 10
+            dst[v] = oka[i] ? fmaxf(a2t, 0.f) : 0.f;                                 // Eq. 3
           }
         }
       }
@@ -691,10 +707,12 @@ WgradPlan wgrad_plan(const ConvGeom& g) {
   p.tiles = g.R * g.S * ((g.Cin + p.tm - 1) / p.tm) * ((g.Cout + p.tn - 1) / p.tn);
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
   const int64_t chunks = (Mg + 63) / 64;
-  int64_t split = 1024 / p.tiles;
-  if (split > 64) split = 64;
+  // three blocks share a compute unit: about 768 blocks in all (fewer only when the layer has
+  // fewer than two chunks per block to give)
+  int64_t split = 768 / p.tiles;
+  if (split > 256) split = 256;
+  if (split > chunks / 2) split = chunks / 2;
   if (split < 1) split = 1;
-  if (split > chunks) split = chunks;
   p.chunks_per_split = (int)((chunks + split - 1) / split);
   p.split = (int)((chunks + p.chunks_per_split - 1) / p.chunks_per_split);
   return p;
@@ -761,7 +779,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
 template <int TM, int TN>
 static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan& p, int K, bool bf16,
                               const void* packed, const float* stats, const float* dy, float* dst, int relu32) {
-  dim3 grid((unsigned)((p.split + 7) / 8 * 8 * p.tiles));
+  dim3 grid((unsigned)(((int64_t)p.split * p.tiles + 7) / 8 * 8));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
   auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true> : wgrad_kernel<TM, TN, 4, false>)
             : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>)
