@@ -199,7 +199,10 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     return ABL_OK;
   }
   // 1x1 convolutions do the same while they stage their A tile
-  if (K != 32 && !naive && igemm_fused_supported(*s) && static_cast<const void*>(x) != static_cast<const void*>(y))
+  // With the prologue every block along the output channels repeats the normalization of its
+  // input rows; measured against the separate pack kernel this pays up to 256 output channels.
+  if (K != 32 && !naive && igemm_fused_supported(*s) && s->Cout <= 256 &&
+      static_cast<const void*>(x) != static_cast<const void*>(y))
     return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, naive)) return e;
   return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);

@@ -218,22 +218,26 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
         const float bt[4] = {k_beta.x, k_beta.y, k_beta.z, k_beta.w};
         const float cq[4] = {k_cq.x, k_cq.y, k_cq.z, k_cq.w};
         const int32_t fb[4] = {k_fb.x, k_fb.y, k_fb.z, k_fb.w};
-        float a3[4];
-        uint32_t word = 0;
+        float a2[4], a3[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float d = xs[e] - mean[e];
           const float a1 = d * rstd[e];  // Eq. 1
           const float t = gm[e] * a1;
-          const float a2 = t + bt[e];    // Eq. 2
-          a3[e] = (ok && a2 > 0.0f) ? a2 : 0.0f;  // Eq. 3
-          word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2, cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+          a2[e] = t + bt[e];             // Eq. 2
+          a3[e] = (ok && a2[e] > 0.0f) ? a2[e] : 0.0f;  // Eq. 3
         }
         v = make_float4(a3[0], a3[1], a3[2], a3[3]);
-        if (ok && n0 == 0) {
-          const int64_t e0 = (int64_t)a_off[i] + k_c;  // flat element index of the first of 4 codes
-          if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
-          else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+        if (n0 == 0) {  // block-uniform: only the first output-channel block quantizes
+          uint32_t word = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2[e], cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+          if (ok) {
+            const int64_t e0 = (int64_t)a_off[i] + k_c;  // flat element index of the first of 4 codes
+            if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
+            else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+          }
         }
       }
       *reinterpret_cast<float4*>(&As[(a_row + ROWS * i) * LDK + 4 * a_kq]) = v;
@@ -374,8 +378,9 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   // per-thread dequantization constants: the thread's channel group is the same in every pass
   const int a_cg = tid % GA;
   // Eq. 10 as one fused multiply-add per element: step * ((code - 2^(K-1) + fb) + 0.5) equals
-  // fma(step, code + off, step / 2) bit for bit, since code + off is an exact small integer,
-  // step / 2 is exact, and both forms round the same exact product once.
+  // fma(step, code + off, step / 2) bit for bit while |fb| < 2^22 (any layer whose codes are
+  // not all saturated): code + off is then an exact integer, step / 2 is exact, and both forms
+  // round the same exact product once.
   float step[CPW], off[CPW], half_step[CPW];
 #pragma unroll
   for (int v = 0; v < CPW; ++v) {
