@@ -332,25 +332,30 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 // channels x TN output channels x one slice of the output pixels; a chunk of 64 pixels is
 // staged in LDS (activations dequantized + ReLU'd to fp32 on the way in; K == 32: `packed` is
 // an fp32 tensor: the conv input itself, or with relu32 the pre-ReLU activation A2 of exact
-// storage), each wave
-// contracts 16 of them into its own accumulators, the four waves are summed in a fixed
-// order at the end.  partial layout: [split][R][S][Cin][Cout].
-template <int TM, int TN, int K, bool BF16>
+// storage).  Small tiles: each wave contracts 16 of the pixels into its own accumulators and
+// the four waves are summed in a fixed order at the end.  QUAD (64-channel-wide tiles): each
+// wave owns a quadrant of the tile and contracts all 64 pixels, so nothing is summed and the
+// accumulators are a quarter of the size.  The summation order over pixels is fixed either
+// way.  partial layout: [split][R][S][Cin][Cout].
+template <int TM, int TN, int K, bool BF16, bool QUAD = false>
 __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
                                                          float* __restrict__ partial, ConvGeom g,
                                                          int chunks_per_split, int nsplit, int relu32) {
   constexpr int CH = 64;                                  // pixels per chunk
-  constexpr int LDA = (TM % 32 == 0) ? TM + 16 : TM;
-  constexpr int LDB = (TN % 32 == 0) ? TN + 16 : TN;
+  constexpr int LDA = (TM % 32 == 0) ? TM + (TN == 128 ? 8 : 16) : TM;
+  constexpr int LDB = (TN % 32 == 0) ? TN + (TN == 128 ? 8 : 16) : TN;
   constexpr int CPW = 32 / K;                             // codes per 32-bit word
   constexpr int GA = TM / CPW;                            // words per pixel of the A tile
   constexpr int A_PASSES = (CH * GA + kThreads - 1) / kThreads;
   constexpr int GB = TN / 4;                              // float4 per pixel of the B tile
   constexpr int B_PASSES = (CH * GB + kThreads - 1) / kThreads;
-  constexpr int MT = TM / 16, NT = TN / 16;
-  constexpr int SM_AB = CH * (LDA + LDB), SM_RED = TM * TN;
+  // QUAD: the four waves own the quadrants of the tile and each contracts all 64 pixels;
+  // otherwise every wave owns the whole tile and a quarter of the pixels.
+  static_assert(!QUAD || (TM % 32 == 0 && TN % 32 == 0), "quadrants are whole 16x16 tiles");
+  constexpr int MT = (QUAD ? TM / 2 : TM) / 16, NT = (QUAD ? TN / 2 : TN) / 16;
+  constexpr int SM_AB = CH * (LDA + LDB), SM_RED = QUAD ? 0 : TM * TN;
   __shared__ __attribute__((aligned(16))) float sm[SM_AB > SM_RED ? SM_AB : SM_RED];
   float* As = sm;
   float* Bs = sm + CH * LDA;
@@ -483,21 +488,38 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     if (pc + CH < p_end) fetch(pc + CH);  // in flight while this chunk is contracted
     // wave w contracts pixels [16w, 16w+16) of the chunk.  Component e of the operand vectors is
     // pixel 4e + lk (fp32: k-step e, lane group = k) or 4lk + e (bf16: lane group owns 4 k).
-    {
+    const int am0 = QUAD ? (wave >> 1) * (TM / 2) : 0, bn0 = QUAD ? (wave & 1) * (TN / 2) : 0;
+#pragma unroll
+    for (int kq = 0; kq < (QUAD ? 4 : 1); ++kq) {
       float4 af[MT], bf[NT];
       int row[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) row[e] = 16 * wave + (BF16 ? 4 * lk + e : 4 * e + lk);
+      for (int e = 0; e < 4; ++e) row[e] = 16 * (QUAD ? kq : wave) + (BF16 ? 4 * lk + e : 4 * e + lk);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
-        af[i] = make_float4(As[row[0] * LDA + 16 * i + li], As[row[1] * LDA + 16 * i + li],
-                            As[row[2] * LDA + 16 * i + li], As[row[3] * LDA + 16 * i + li]);
+        af[i] = make_float4(As[row[0] * LDA + am0 + 16 * i + li], As[row[1] * LDA + am0 + 16 * i + li],
+                            As[row[2] * LDA + am0 + 16 * i + li], As[row[3] * LDA + am0 + 16 * i + li]);
 #pragma unroll
       for (int j = 0; j < NT; ++j)
-        bf[j] = make_float4(Bs[row[0] * LDB + 16 * j + li], Bs[row[1] * LDB + 16 * j + li],
-                            Bs[row[2] * LDB + 16 * j + li], Bs[row[3] * LDB + 16 * j + li]);
+        bf[j] = make_float4(Bs[row[0] * LDB + bn0 + 16 * j + li], Bs[row[1] * LDB + bn0 + 16 * j + li],
+                            Bs[row[2] * LDB + bn0 + 16 * j + li], Bs[row[3] * LDB + bn0 + 16 * j + li]);
       mma_k4<BF16, MT, NT>(af, bf, acc);
     }
+  }
+
+  float* dst = partial + (int64_t)split_idx * g.R * g.S * g.Cin * g.Cout;
+  if constexpr (QUAD) {  // each wave writes its own quadrant: nothing to sum
+    const int am0 = (wave >> 1) * (TM / 2), bn0 = (wave & 1) * (TN / 2);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int ci = ci0 + am0 + 16 * i + 4 * lk + rr, co = co0 + bn0 + 16 * j + li;
+          if (ci < g.Cin && co < g.Cout) dst[((int64_t)tap * g.Cin + ci) * g.Cout + co] = acc[i][j][rr];
+        }
+    return;
   }
 
   // sum the four waves in order 0,1,2,3 through LDS, then write the tile
@@ -516,7 +538,6 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     }
   }
   __syncthreads();
-  float* dst = partial + (int64_t)split_idx * g.R * g.S * g.Cin * g.Cout;
   for (int idx = tid; idx < TM * TN / 4; idx += kThreads) {
     const int i = idx / (TN / 4), j = 4 * (idx % (TN / 4));
     const int ci = ci0 + i, co = co0 + j;
@@ -709,6 +730,9 @@ WgradPlan wgrad_plan(const ConvGeom& g) {
   WgradPlan p;
   p.tm = g.Cin >= 64 ? 64 : (g.Cin >= 32 ? 32 : 16);
   p.tn = g.Cout >= 64 ? 64 : (g.Cout >= 32 ? 32 : 16);
+  // 128 output channels per block where they divide evenly: the dequantization of the
+  // activation chunk is shared by twice as many MFMAs
+  if (p.tm == 64 && g.Cout % 128 == 0) p.tn = 128;
   p.tiles = g.R * g.S * ((g.Cin + p.tm - 1) / p.tm) * ((g.Cout + p.tn - 1) / p.tn);
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
   const int64_t chunks = (Mg + 63) / 64;
@@ -786,9 +810,10 @@ static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan
                               const void* packed, const float* stats, const float* dy, float* dst, int relu32) {
   dim3 grid((unsigned)(((int64_t)p.split * p.tiles + 7) / 8 * 8));
   const uint32_t* pk = static_cast<const uint32_t*>(packed);
-  auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true> : wgrad_kernel<TM, TN, 4, false>)
-            : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true> : wgrad_kernel<TM, TN, 8, false>)
-                     : (bf16 ? wgrad_kernel<TM, TN, 32, true> : wgrad_kernel<TM, TN, 32, false>);
+  constexpr bool Q = TM == 64 && TN >= 64;
+  auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true, Q> : wgrad_kernel<TM, TN, 4, false, Q>)
+            : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true, Q> : wgrad_kernel<TM, TN, 8, false, Q>)
+                     : (bf16 ? wgrad_kernel<TM, TN, 32, true, Q> : wgrad_kernel<TM, TN, 32, false, Q>);
   kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split, relu32);
 }
 
@@ -808,7 +833,8 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
   if (K != 32 && use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
-  if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  if (p.tm == 64 && p.tn == 128) launch_wgrad_tile<64, 128>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
+  else if (p.tm == 64 && p.tn == 64) launch_wgrad_tile<64, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   else if (p.tm == 64 && p.tn == 32) launch_wgrad_tile<64, 32>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   else if (p.tm == 64 && p.tn == 16) launch_wgrad_tile<64, 16>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   else if (p.tm == 32 && p.tn == 64) launch_wgrad_tile<32, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
