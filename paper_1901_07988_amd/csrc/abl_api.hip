@@ -264,8 +264,11 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))
       return e;
-    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
-    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta);
+    // split partial copies of dW are summed by the launch that finishes the Eq. 7 sums
+    DwSum dwsum;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta,
+                                dwsum.copies > 0 ? &dwsum : nullptr);
   }
   if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
   // exact storage keeps the pre-ReLU A2: the weight gradient applies Eq. 3 on the way in

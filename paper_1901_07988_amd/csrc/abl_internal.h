@@ -109,8 +109,11 @@ bool igemm_fused_supported(const abl_shape& s);
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
                           const float* w, const float* skip, float* y, void* packed);
 // K = 32: `packed` is an fp32 tensor, used as it is or (relu32) as the pre-ReLU activation A2.
+// defer (nullable): where the kernel leaves split partial copies, describe them there instead of
+// summing them (copies = 0 when dw is already complete) - for launch_bn_bwd_finish.
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
-                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32 = false);
+                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32 = false,
+                             DwSum* defer = nullptr);
 
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.

@@ -818,8 +818,10 @@ static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan
 }
 
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
-                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32) {
+                             const void* stats, const float* dy, void* scratch, float* dw, bool relu32,
+                             DwSum* defer) {
   const int r32 = relu32 ? 1 : 0;
+  if (defer != nullptr) defer->copies = 0;
   const ConvGeom g = geom_of(s);
   const float* sp = static_cast<const float*>(stats);
   if (!mfma_ok(g)) {
@@ -843,7 +845,9 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
   else if (p.tm == 16 && p.tn == 64) launch_wgrad_tile<16, 64>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   else if (p.tm == 16 && p.tn == 32) launch_wgrad_tile<16, 32>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
   else launch_wgrad_tile<16, 16>(st, g, p, K, bf16, packed, sp, dy, dst, r32);
-  if (p.split > 1) {
+  if (p.split > 1 && defer != nullptr) {  // the caller sums the copies in a launch of its own
+    *defer = DwSum{dst, p.split, (int64_t)g.R * g.S * g.Cin * g.Cout, dw};
+  } else if (p.split > 1) {
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
     wgrad_reduce_kernel<<<(unsigned)((n + 63) / 64), kThreads, 0, st>>>(dst, p.split, n, dw);
   }
