@@ -246,6 +246,18 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
                        int32_t skip_every, float* buf_s, float* buf_t,
                        void* scratch, size_t scratch_bytes);
 
+/* ---- parameter update -----------------------------------------------------------
+ * SGD with momentum and weight decay, the update rule of the paper's experiments
+ * (Sec. 4: momentum 0.9, weight decay 2e-4 on CIFAR and 1e-4 on ImageNet), applied to
+ * one parameter tensor of n floats in place:
+ *     v <- momentum * v + (grad + weight_decay * w);   w <- w - lr * v
+ * every operation rounded to fp32 on its own, in this order.  w, grad, v: device
+ * pointers, 16-byte aligned, caller-owned; grad is read only; n >= 0 (n = 0 is a
+ * no-op that does not look at the pointers).  Errors: ABL_ERR_ARG (null / misaligned
+ * pointer, n < 0), ABL_ERR_SHAPE (n >= 2^40), ABL_ERR_HIP. */
+int abl_sgd_momentum(void* stream, int64_t n, float lr, float momentum, float weight_decay,
+                     float* w, const float* grad, float* v);
+
 #ifdef __cplusplus
 }
 #endif

@@ -453,3 +453,14 @@ def postact_backward(saved: Saved, dy, w, s: Shape, xin, dtype=np.float32):
     dw = conv_wgrad(xa, dt, s, dtype)      # Eq. 5
     dx = conv_dgrad(dt, w, s, dtype)       # Eq. 5
     return dx, dw, dg, db
+
+
+def sgd_momentum(w, grad, v, lr, momentum, weight_decay, dtype=np.float32):
+    """SGD with momentum and weight decay, the update rule of the paper's experiments (Sec. 4):
+    v <- momentum * v + (grad + weight_decay * w);  w <- w - lr * v, each operation rounded to
+    ``dtype``.  Returns (w_new, v_new)."""
+    t = np.dtype(dtype).type
+    w, grad, v = _c(w, dtype), _c(grad, dtype), _c(v, dtype)
+    d = grad + t(weight_decay) * w
+    v_new = t(momentum) * v + d
+    return w - t(lr) * v_new, v_new

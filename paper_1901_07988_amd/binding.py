@@ -77,6 +77,7 @@ _SIGS = {
     "abl_stack_buffer_bytes": (_sz, [_lay, _i32]),
     "abl_stack_forward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
     "abl_stack_backward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
+    "abl_sgd_momentum": (ctypes.c_int, [_vp, _i64, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -275,3 +276,8 @@ def abl_stack_forward(layers, K, skip_every, buf_s, buf_t, scratch, flags=0):
 def abl_stack_backward(layers, K, skip_every, buf_s, buf_t, scratch, flags=0):
     _check(lib.abl_stack_backward(_stream(), layers, len(layers), K, flags, skip_every, _ptr(buf_s), _ptr(buf_t),
                                   _ptr(scratch), scratch.numel() * scratch.element_size()), "abl_stack_backward")
+
+
+def abl_sgd_momentum(w, grad, v, lr, momentum, weight_decay):
+    _check(lib.abl_sgd_momentum(_stream(), w.numel(), lr, momentum, weight_decay, _ptr(w), _ptr(grad), _ptr(v)),
+           "abl_sgd_momentum")

@@ -585,4 +585,13 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
   return ABL_OK;
 }
 
+int abl_sgd_momentum(void* stream, int64_t n, float lr, float momentum, float weight_decay, float* w,
+                     const float* grad, float* v) {
+  if (n < 0) return ABL_ERR_ARG;
+  if (n == 0) return ABL_OK;
+  if (bad_ptr(w) || bad_ptr(grad) || bad_ptr(v)) return ABL_ERR_ARG;
+  if (n >= (int64_t)1 << 40) return ABL_ERR_SHAPE;
+  return launch_sgd_momentum((hipStream_t)stream, n, lr, momentum, weight_decay, w, grad, v);
+}
+
 }  // extern "C"

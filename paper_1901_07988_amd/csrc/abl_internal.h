@@ -41,6 +41,8 @@ struct DwSum {
   int64_t n;
   float* dw;
 };
+int launch_sgd_momentum(hipStream_t st, int64_t n, float lr, float mu, float wd, float* w, const float* grad,
+                        float* v);
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
                          float* dbeta, const DwSum* dwsum = nullptr);

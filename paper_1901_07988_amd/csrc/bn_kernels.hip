@@ -870,4 +870,48 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
   return hip_status();
 }
 
+
+// ------------------------------------------------------------------------------------------
+// SGD with momentum and weight decay (Sec. 4), in place; four elements per lane, scalar tail.
+namespace {
+__device__ inline void sgd_one(float& w, float g, float& v, float lr, float mu, float wd) {
+  const float d = g + wd * w;
+  v = mu * v + d;
+  w = w - lr * v;
+}
+
+__global__ __launch_bounds__(kThreads) void sgd_momentum_kernel(int64_t n, float lr, float mu, float wd,
+                                                                float* __restrict__ w,
+                                                                const float* __restrict__ grad,
+                                                                float* __restrict__ v) {
+  const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (i + 4 <= n) {
+    float4 wv = *reinterpret_cast<const float4*>(w + i);
+    float4 vv = *reinterpret_cast<const float4*>(v + i);
+    const float4 gv = *reinterpret_cast<const float4*>(grad + i);
+    sgd_one(wv.x, gv.x, vv.x, lr, mu, wd);
+    sgd_one(wv.y, gv.y, vv.y, lr, mu, wd);
+    sgd_one(wv.z, gv.z, vv.z, lr, mu, wd);
+    sgd_one(wv.w, gv.w, vv.w, lr, mu, wd);
+    *reinterpret_cast<float4*>(w + i) = wv;
+    *reinterpret_cast<float4*>(v + i) = vv;
+  } else {
+    for (int64_t k = i; k < n; ++k) {
+      float wk = w[k], vk = v[k];
+      sgd_one(wk, grad[k], vk, lr, mu, wd);
+      w[k] = wk;
+      v[k] = vk;
+    }
+  }
+}
+}  // namespace
+
+int launch_sgd_momentum(hipStream_t st, int64_t n, float lr, float mu, float wd, float* w, const float* grad,
+                        float* v) {
+  if (n == 0) return ABL_OK;
+  const int64_t lanes = (n + 3) / 4;
+  sgd_momentum_kernel<<<(unsigned)((lanes + kThreads - 1) / kThreads), kThreads, 0, st>>>(n, lr, mu, wd, w, grad, v);
+  return hip_status();
+}
+
 }  // namespace abl

@@ -715,3 +715,25 @@ def test_quantizer_on_non_finite_and_huge_values(G, oracle, K):
     assert got.tobytes()[: ref.size] == ref.tobytes()
     codes = o.unpack_codes(ref, a2.shape, K)
     assert np.all(codes[0] == 0) and np.all(codes[2] == 0) and np.all(codes[1] == 2 ** K - 1)
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4099, 1 << 16])
+def test_sgd_momentum_update(G, oracle, n):
+    """The parameter update of Sec. 4's training setup: bit-exact against the fp32 oracle over
+    several steps (every operation is rounded on its own on both sides), ragged tails included."""
+    import torch
+    from paper_1901_07988_amd import binding as B
+    print("case sgd", n, flush=True)
+    rng = np.random.default_rng(n)
+    w = rng.standard_normal(n).astype(np.float32)
+    v = np.zeros(n, np.float32)
+    wt, vt = G.dev(w), G.dev(v)
+    for step in range(4):
+        g = rng.standard_normal(n).astype(np.float32)
+        B.abl_sgd_momentum(wt, G.dev(g), vt, 0.1, 0.9, 2e-4)
+        w, v = oracle.sgd_momentum(w, g, v, 0.1, 0.9, 2e-4, np.float32)
+        assert wt.cpu().numpy().tobytes() == w.tobytes()
+        assert vt.cpu().numpy().tobytes() == v.tobytes()
+    with pytest.raises(B.AblError):
+        B.abl_sgd_momentum(wt, None, vt, 0.1, 0.9, 0.0)
+    B.abl_sgd_momentum(wt[:0], wt[:0], vt[:0], 0.1, 0.9, 0.0)   # n = 0: nothing to do

@@ -568,3 +568,43 @@ def test_naive_forward_baseline_pins(oracle):
         assert y_p.tobytes() == y_e.tobytes()
         errs.append(float(np.linalg.norm(y_n - y_e) / np.linalg.norm(y_e)))
     assert errs[0] > 0 and errs[2] > errs[0]
+
+
+# ---- SGD with momentum (Sec. 4's training setup) against closed forms ------------------------
+def test_sgd_momentum_closed_forms(oracle):
+    o = oracle
+    rng = np.random.default_rng(11)
+    w0 = rng.standard_normal(37)
+    g = rng.standard_normal(37)
+    z = np.zeros(37)
+    # no momentum, no decay: plain gradient descent, and the velocity is the gradient
+    w1, v1 = o.sgd_momentum(w0, g, z, 0.1, 0.0, 0.0, np.float64)
+    assert np.allclose(w1, w0 - 0.1 * g, rtol=0, atol=1e-15) and np.array_equal(v1, g)
+    # constant gradient: v_T = g (1 - mu^T) / (1 - mu), w_T = w0 - lr * sum_t v_t
+    mu, lr, T = 0.9, 0.05, 25
+    w, v, acc = w0.copy(), z.copy(), z.copy()
+    for t in range(1, T + 1):
+        w, v = o.sgd_momentum(w, g, v, lr, mu, 0.0, np.float64)
+        acc += g * (1 - mu ** t) / (1 - mu)
+    assert np.allclose(v, g * (1 - mu ** T) / (1 - mu), rtol=1e-12)
+    assert np.allclose(w, w0 - lr * acc, rtol=1e-12, atol=1e-12)
+    # decay only: w_T = w0 (1 - lr wd)^T (the decay acts on the weights, through the velocity)
+    w = w0.copy()
+    for _ in range(10):
+        w, v = o.sgd_momentum(w, z, z, 0.1, 0.0, 0.02, np.float64)
+    assert np.allclose(w, w0 * (1 - 0.1 * 0.02) ** 10, rtol=1e-12)
+    # decay and momentum together on a scalar: the linear recurrence [w, v] <- A [w, v]
+    lr, mu, wd = 0.1, 0.9, 2e-4
+    A = np.array([[1 - lr * wd, -lr * mu], [wd, mu]])
+    s = np.array([1.5, -0.25])
+    w, v = np.array([1.5]), np.array([-0.25])
+    for _ in range(7):
+        w, v = o.sgd_momentum(w, np.zeros(1), v, lr, mu, wd, np.float64)
+        s = A @ s
+    assert np.allclose([w[0], v[0]], s, rtol=1e-12)
+    # fp32 mode rounds to fp32 and stays within an ulp or two of the fp64 result
+    w32, v32 = o.sgd_momentum(w0, g, g, 0.1, 0.9, 2e-4, np.float32)
+    w64, v64 = o.sgd_momentum(w0.astype(np.float32), g.astype(np.float32), g.astype(np.float32), 0.1, 0.9, 2e-4,
+                              np.float64)
+    assert w32.dtype == np.float32 and v32.dtype == np.float32
+    assert np.allclose(w32, w64, rtol=1e-6, atol=1e-7) and np.allclose(v32, v64, rtol=1e-6, atol=1e-7)
