@@ -737,3 +737,42 @@ def test_sgd_momentum_update(G, oracle, n):
     with pytest.raises(B.AblError):
         B.abl_sgd_momentum(wt, None, vt, 0.1, 0.9, 0.0)
     B.abl_sgd_momentum(wt[:0], wt[:0], vt[:0], 0.1, 0.9, 0.0)   # n = 0: nothing to do
+
+
+@pytest.mark.parametrize("s,pool", [(LayerShape(16, 8, 8, 64, 10, 8, 8, 1, 0), 8),      # global pool + classifier
+                                    (LayerShape(8, 8, 8, 64, 32, 8, 8, 1, 0), 8),
+                                    (LayerShape(4, 12, 12, 32, 32, 2, 2, 2, 0), 2)],    # 2x2 pool + 1x1 conv
+                         ids=["global-pool+fc10", "global-pool+fc32", "pool2+conv1x1"])
+def test_average_pool_folded_into_linear(G, oracle, s, pool):
+    """Average pooling is folded into the linear transform that follows it (Sec. 3.4): BN -> ReLU
+    -> pool x pool average -> 1x1 convolution V is the layer with the pool x pool, stride-pool
+    kernel W[r, s] = V / pool^2.  Checked against the pooling written out on the oracle's A3, and
+    the gradient of V, sum_rs dW[r, s] / pool^2, against pooling of the dequantized activation."""
+    o = oracle
+    K = 4
+    print("case folded average pool", s.as_tuple(), flush=True)
+    assert s.R == s.S == pool and s.stride in (1, pool) and s.pad == 0
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((s.N, s.H, s.W, s.Cin)).astype(np.float32)
+    gamma, beta = rand_affine(rng, s.Cin)
+    V = (rng.standard_normal((s.Cin, s.Cout)) * np.sqrt(2.0 / s.Cin)).astype(np.float32)
+    w = np.ascontiguousarray(np.broadcast_to(V / np.float32(pool * pool), (pool, pool, s.Cin, s.Cout)))
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    run = G.LayerRun(s, K)
+    y = run.forward(x, w, gamma, beta)
+    y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+    assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+    assert rel(y, y_ref) < TOL
+
+    def pooled(a):   # non-overlapping pool x pool average of an NHWC tensor, in fp64
+        a = np.asarray(a, np.float64)
+        return a.reshape(s.N, s.Ho, pool, s.Wo, pool, s.Cin).mean(axis=(2, 4))
+
+    a2 = (x.astype(np.float64) - saved.mean) * saved.rstd * gamma + beta
+    assert rel(y, pooled(np.maximum(a2, 0)) @ V.astype(np.float64)) < TOL
+    dx, dw, dg, db = run.backward(dy, w)
+    dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+    assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL and rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
+    a3t = np.maximum(o.recover_a2(saved), 0)
+    dV = np.einsum("nhwc,nhwk->ck", pooled(a3t), dy.astype(np.float64))
+    assert rel(dw.astype(np.float64).sum(axis=(0, 1)) / (pool * pool), dV) < TOL
