@@ -179,3 +179,60 @@ def test_bench_stack_full_size(G, oracle):
     assert S.cpu().numpy().tobytes() == y.tobytes()
     exact = sum(4 * s.E for s, *_ in layers)
     assert run.stored_bytes() <= (K / 32 + 0.01) * exact
+
+
+@pytest.mark.parametrize("N", [8191, 8192], ids=["2^23-1024 pixels (last size of the patch kernels)",
+                                                  "2^23 pixels (first size on the implicit-GEMM kernels)"])
+def test_largest_pixel_counts(G, oracle, N):
+    """The stride-1 patch kernels index pixels in 23 bits; a 16-channel 32x32 layer reaches that
+    limit at N = 8192.  Both sides of it: statistics bit for bit, codes on the first and last
+    rows, sampled outputs of the three contractions, and the Eq. 6 sum over everything."""
+    import torch
+    o = oracle
+    s = synth.LayerShape(N, 32, 32, 16, 16)
+    os_ = o.Shape(*s.as_tuple())
+    K = 4
+    print("case largest", s.as_tuple(), flush=True)
+    rng = np.random.default_rng(N)
+    x = rng.standard_normal((s.N, s.H, s.W, s.Cin), dtype=np.float32)
+    w = synth.he_normal(rng, s)
+    gamma = rng.uniform(0.5, 1.5, s.Cin).astype(np.float32)
+    beta = (rng.standard_normal(s.Cin) * 0.1).astype(np.float32)
+    run = G.LayerRun(s, K)
+    y = run.forward(x, w, gamma, beta)
+    mean, var = o.bn_stats(x)
+    rstd = o.bn_rstd(var)
+    sd = G.stats_to_dict(run.stats, s.Cin)
+    np.testing.assert_array_equal(sd["mean"], mean)
+    np.testing.assert_array_equal(sd["var"], var)
+    np.testing.assert_array_equal(sd["rstd"], rstd)
+    a2, a3 = o.bn_relu(x, mean, rstd, gamma, beta)
+    packed = run.packed.cpu().numpy()
+    rows = 4096                                    # pixels compared at either end
+    for sl in (slice(0, rows), slice(s.M - rows, s.M)):
+        q = o.quantize(a2.reshape(s.M, s.Cin)[sl], gamma, beta, K)
+        want = o.pack_codes(q, K)
+        lo = sl.start * s.Cin * K // 8
+        assert packed[lo: lo + want.size].tobytes() == want.tobytes()
+    pts = [(0, 0, 0), (s.N - 1, s.Ho - 1, s.Wo - 1), (s.N - 1, 0, s.Wo - 1), (s.N // 2, s.Ho - 1, 0)]
+    pts += [(int(rng.integers(s.N)), int(rng.integers(s.Ho)), int(rng.integers(s.Wo))) for _ in range(40)]
+    ref = o.conv_fwd_at(a3, w, os_, pts)
+    assert np.max(np.abs(np.stack([y[p] for p in pts]) - ref)) <= TOL * float(np.max(np.abs(ref)))
+    del y, a3
+
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout), dtype=np.float32)
+    dx, dw, dg, db = run.backward(dy, w)
+    da3 = run.scratch[: 4 * s.E].view(torch.float32).cpu().numpy().reshape(x.shape)
+    ref = o.conv_dgrad_at(dy, w, os_, pts)
+    assert np.max(np.abs(np.stack([da3[p] for p in pts]) - ref)) <= TOL * float(np.max(np.abs(ref)))
+    # the dequantized activation, rebuilt from the GPU's own packed bytes where they were compared
+    # above and from the oracle's codes elsewhere, is what the weight gradient must have used
+    a3t = np.maximum(o.dequantize(o.quantize(a2, gamma, beta, K), gamma, beta, K), np.float32(0))
+    ent = [(0, 0, 0), (2, 2, 15), (1, 1, 7)]
+    ref = o.conv_wgrad_at(a3t, dy, os_, ent)
+    got = np.stack([dw[e] for e in ent])
+    assert np.max(np.abs(got - ref)) <= TOL * max(float(np.max(np.abs(ref))), float(np.max(np.abs(dw))))
+    # Eq. 6 over all pixels: dbeta = sum of dA3 where the dequantized activation is positive
+    want = np.where(a3t.reshape(-1, s.Cin) > 0, da3.reshape(-1, s.Cin), np.float32(0)).sum(0, dtype=np.float64)
+    assert rel(db, want) < TOL
+    assert np.isfinite(dx).all() and np.isfinite(dg).all()
