@@ -22,6 +22,7 @@ UNITS = {
     "bn_kernels.hip": ["-ffp-contract=off"],
     "conv_kernels.hip": [],
     "conv_halo.hip": ["-ffp-contract=off"],
+    "conv_pointwise.hip": ["-ffp-contract=off"],
     "abl_api.hip": [],
 }
 

@@ -107,6 +107,14 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
 // Forward of a 1x1 stride-1 convolution without padding with Eq. 1-3 and Eq. 9 applied while the
 // A tile is staged: reads x, writes y and the packed codes; A3 never reaches memory.  y must not
 // alias x.
+// 1x1 stride-1 convolutions without padding whose channel counts allow it (contraction a
+// multiple of 64, outputs a multiple of 16) run as plain GEMMs with the activation operand
+// loaded straight into MFMA layout.  mode 0 forward (skip nullable), 1 dgrad.
+bool pointwise_supported(const ConvGeom& g, int mode);
+int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
+                          const float* skip, float* out);
+int launch_pointwise_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x, const float* stats,
+                               const float* w, const float* skip, float* y, void* packed);
 bool igemm_fused_supported(const abl_shape& s);
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
                           const float* w, const float* skip, float* y, void* packed);

@@ -775,6 +775,7 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     return hip_status();
   }
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y);
+  if (pointwise_supported(g, 0)) return launch_pointwise_conv(st, g, 0, bf16, a3, w, skip, y);
   return launch_igemm<0, 0>(st, g, bf16, a3, w, skip, y, nullptr, nullptr);
 }
 
@@ -789,6 +790,7 @@ int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, 
   if (!igemm_fused_supported(s)) return ABL_ERR_SHAPE;
   const ConvGeom g = geom_of(s);
   const float* sp = static_cast<const float*>(stats);
+  if (pointwise_supported(g, 0)) return launch_pointwise_fwd_fused(st, g, K, bf16, x, sp, w, skip, y, packed);
   if (K == 4) return launch_igemm<0, 4>(st, g, bf16, x, w, skip, y, sp, packed);
   return launch_igemm<0, 8>(st, g, bf16, x, w, skip, y, sp, packed);
 }
@@ -802,6 +804,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
     return hip_status();
   }
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
+  if (pointwise_supported(g, 1)) return launch_pointwise_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   return launch_igemm<1, 0>(st, g, bf16, dy, w, nullptr, da3, nullptr, nullptr);
 }
 

@@ -1,0 +1,337 @@
+// Pointwise (1x1, stride 1, no padding) convolutions of the approximate-activation layer as
+// plain GEMMs for gfx950 (CDNA4):
+//   forward  Eq. 4           y[p][co]   = sum_ci A3[p][ci] W[ci][co]     (+ identity shortcut)
+//   dgrad    Eq. 5, 2nd half dA3[p][ci] = sum_co dy[p][co] W[ci][co]
+// and the forward with Eq. 1-3 and Eq. 9 applied to the input on its way to the matrix cores
+// (A3 never reaches memory; the first output-channel block writes the K-bit codes).
+//
+// A pixel's channels are contiguous in NHWC, which is exactly what a lane of
+// v_mfma_f32_16x16x4_f32 needs of the activation operand: four consecutive k of one row.  So
+// the activations go from global memory straight into registers in MFMA layout - no LDS
+// staging and no barrier for them - with a ring of four 16-channel groups in flight per wave
+// that runs on from one pixel tile into the next.  A wave owns 16 pixels x 16*NT output
+// channels: few accumulators, so many waves share a compute unit, and tiles small enough to
+// spread evenly (measured: occupancy and an even spread decide here, larger tiles lose).
+// Only the weights (shared by all waves, and needed with k contiguous, i.e. transposed in
+// the forward) sit in LDS:
+//   contraction of at most 256 channels: the whole slice, written once per block;
+//   longer: 128-channel chunks in two buffers, the next chunk's global loads in flight while
+//           the current one is contracted, one barrier per chunk.
+// Every block walks over a run of consecutive pixel tiles; the runs differ by at most one tile.
+#include "abl_internal.h"
+
+// Eq. 1-3 and Eq. 9 are evaluated here: one rounded fp32 operation at a time
+#pragma clang fp contract(off)
+
+namespace abl {
+namespace {
+
+constexpr int KC = 256;    // longest contraction whose weights stay in LDS for the whole block
+constexpr int CHC = 128;   // chunk length beyond that
+constexpr int PF = 4;      // 16-channel groups in flight per wave
+constexpr int NCONST = 6;  // per-channel constants of the fused prologue: mean rstd gamma beta cq fb
+
+inline int pointwise_chunk(int Kd) { return Kd <= KC ? Kd : CHC; }
+inline unsigned pointwise_lds_bytes(int Kd, int nt, bool fuse) {
+  const int ch = pointwise_chunk(Kd), nbuf = Kd <= KC ? 1 : 2;
+  return (unsigned)(nbuf * (16 * nt * (ch + 4) + (fuse ? NCONST * ch : 0)) * sizeof(float));
+}
+
+// MODE 0: in = A3 (or x with FUSE) [M][Kd = Cin], out = y [M][N = Cout], weight(k, n) = wgt[k * ldw + n]
+// MODE 1: in = dy [M][Kd = Cout], out = dA3 [M][N = Cin],                weight(k, n) = wgt[n * ldw + k]
+// ldw = Cout.  Kd is a multiple of 64 (of 128 when CHUNKED), N a multiple of 16 * NT.
+// Pixel tiles of 16 * WAVES rows; block `r` of an output-channel block takes run_base tiles, one
+// more if r < run_rem, in order.
+template <int MODE, int NT, bool CHUNKED, bool BF16, int FUSE>
+__global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
+    const float* __restrict__ in, const float* __restrict__ wgt, const float* skip, float* out, int64_t M, int Kd,
+    int N, int ldw, int run_base, int run_rem, const float* __restrict__ stats, void* __restrict__ packed,
+    int pack_pad) {
+  static_assert(FUSE == 0 || MODE == 0, "the prologue belongs to the forward");
+  constexpr int WAVES = CHUNKED ? 8 : 4;
+  constexpr int kThreads = 64 * WAVES;
+  constexpr int BN = 16 * NT, BM = 16 * WAVES;
+  constexpr int KB = FUSE != 0 ? FUSE : 4;
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int CH = CHUNKED ? CHC : Kd;  // contraction channels per weight chunk
+  const int LDW = CH + 4;             // row stride: 16-byte aligned rows, each shifted by 4 banks
+  constexpr int NBUF = CHUNKED ? 2 : 1;
+  float* const Ws = lds;                    // [NBUF][BN][LDW]  weight(k, n) at [n * LDW + k - chunk start]
+  float* const Cs = lds + NBUF * BN * LDW;  // [NBUF][NCONST][CH]  (fused prologue only)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD (and its L2): the blocks that read the same pixel rows for
+  // different output-channel blocks run there back to back
+  const int nblk_n = N / BN;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int run = (slot / nblk_n) * 8 + xcd;
+  const int n0 = (slot % nblk_n) * BN;
+  if (FUSE != 0 && blockIdx.x == 0 && tid < pack_pad)  // tail of the last 128-byte row of codes
+    static_cast<uint8_t*>(packed)[(M * Kd * FUSE) / 8 + tid] = 0;
+  const int64_t t_begin = (int64_t)run * run_base + (run < run_rem ? run : run_rem);
+  const int64_t t_end = t_begin + run_base + (run < run_rem ? 1 : 0);
+  if (t_end == t_begin) return;
+
+  constexpr int planes[NCONST] = {P_MEAN, P_RSTD, P_GAMMA, P_BETA, P_CQ, P_FB};
+  if (!CHUNKED) {  // the whole slice of the weights (and the prologue constants), once
+    const int q4 = Kd >> 2;
+    if (MODE == 0) {  // transposed on the way: four k rows of column n -> one 16-byte write
+      for (int idx = tid; idx < BN * q4; idx += kThreads) {
+        const int n = idx % BN, q = idx / BN;
+        const float* src = wgt + (int64_t)(4 * q) * ldw + n0 + n;
+        *reinterpret_cast<float4*>(&Ws[n * LDW + 4 * q]) = make_float4(src[0], src[ldw], src[2 * ldw], src[3 * ldw]);
+      }
+    } else {
+      for (int idx = tid; idx < BN * q4; idx += kThreads) {
+        const int n = idx / q4, q = idx - n * q4;
+        *reinterpret_cast<float4*>(&Ws[n * LDW + 4 * q]) =
+            *reinterpret_cast<const float4*>(wgt + (int64_t)(n0 + n) * ldw + 4 * q);
+      }
+    }
+    if (FUSE != 0) {
+      for (int idx = tid; idx < NCONST * q4; idx += kThreads) {
+        const int pl = idx / q4, q = idx - pl * q4;
+        *reinterpret_cast<float4*>(&Cs[pl * CH + 4 * q]) =
+            *reinterpret_cast<const float4*>(stats + (int64_t)planes[pl] * Kd + 4 * q);
+      }
+    }
+  }
+  // chunked: this thread's share of a 128-channel chunk, held in registers between its global
+  // loads and its LDS writes
+  constexpr int WITEMS = CHUNKED ? BN * (CHC / 4) / kThreads : 1;
+  static_assert(!CHUNKED || BN * (CHC / 4) % kThreads == 0, "whole staging items per thread");
+  float4 wreg[WITEMS];
+  float4 creg = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto load_chunk = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < WITEMS; ++it) {
+      const int idx = tid + it * kThreads;
+      if (MODE == 0) {
+        const int n = idx % BN, q = idx / BN;
+        const float* src = wgt + (int64_t)(c0 + 4 * q) * ldw + n0 + n;
+        wreg[it] = make_float4(src[0], src[ldw], src[2 * ldw], src[3 * ldw]);
+      } else {
+        const int n = idx / (CHC / 4), q = idx % (CHC / 4);
+        wreg[it] = *reinterpret_cast<const float4*>(wgt + (int64_t)(n0 + n) * ldw + c0 + 4 * q);
+      }
+    }
+    if (FUSE != 0 && tid < NCONST * (CHC / 4)) {
+      const int pl = tid / (CHC / 4), q = tid % (CHC / 4);
+      creg = *reinterpret_cast<const float4*>(stats + (int64_t)planes[pl] * Kd + c0 + 4 * q);
+    }
+  };
+  auto store_chunk = [&](int buf) __attribute__((always_inline)) {
+    float* W = Ws + buf * BN * LDW;
+#pragma unroll
+    for (int it = 0; it < WITEMS; ++it) {
+      const int idx = tid + it * kThreads;
+      const int n = MODE == 0 ? idx % BN : idx / (CHC / 4), q = MODE == 0 ? idx / BN : idx % (CHC / 4);
+      *reinterpret_cast<float4*>(&W[n * LDW + 4 * q]) = wreg[it];
+    }
+    if (FUSE != 0 && tid < NCONST * (CHC / 4)) {
+      const int pl = tid / (CHC / 4), q = tid % (CHC / 4);
+      *reinterpret_cast<float4*>(&Cs[buf * NCONST * CH + pl * CH + 4 * q]) = creg;
+    }
+  };
+  if (CHUNKED) {
+    load_chunk(0);
+    store_chunk(0);
+  }
+  __syncthreads();
+
+  const int KG = Kd >> 4;        // 16-channel groups of the contraction
+  const int GPC = CH >> 4;       // ... per weight chunk
+  const int NC = CHUNKED ? Kd / CHC : 1;
+
+  // The ring of loads runs on across pixel tiles: while a tile's last groups are contracted
+  // and its results stored, the first groups of the block's next tile are already in flight.
+  auto row_ptr = [&](int64_t tile) __attribute__((always_inline)) {
+    const int64_t p = tile * BM + wave * 16 + li;
+    return in + (p < M ? p : 0) * Kd + 4 * lk;  // rows past the end read row 0 and are never stored
+  };
+  const float* xp = row_ptr(t_begin);
+  float4 ring[PF];
+#pragma unroll
+  for (int s = 0; s < PF; ++s) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * s);
+
+  int step = 0;  // (tile, chunk) pairs done so far: chunk buffers alternate with it
+  for (int64_t tile = t_begin; tile < t_end; ++tile) {
+    const bool has_next = tile + 1 < t_end;
+    const float* xpn = row_ptr(has_next ? tile + 1 : tile);
+    const int64_t prow = tile * BM + wave * 16 + li;
+    const bool pok = prow < M;
+    floatx4 acc[NT][1];  // acc[j][0][r]: pixel prow, channel n0 + 16j + 4lk + r
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    for (int c = 0; c < NC; ++c, ++step) {
+      const int buf = CHUNKED ? (step & 1) : 0;
+      const bool more = CHUNKED && (has_next || c + 1 < NC);  // another chunk follows: fetch it now
+      if (more) load_chunk(c + 1 < NC ? (c + 1) * CHC : 0);
+      const float* W = Ws + buf * BN * LDW;
+      const float* Cc = Cs + buf * NCONST * CH;
+      for (int g0 = 0; g0 < GPC; g0 += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+          const int kl = (g0 + s) * 16;     // offset inside the chunk
+          const int kg = c * GPC + g0 + s;  // group of the whole contraction
+          float4 a[1] = {ring[s]};
+          if (kg + PF < KG) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * (kg + PF));
+          else if (has_next) ring[s] = *reinterpret_cast<const float4*>(xpn + 16 * (kg + PF - KG));
+          if (FUSE != 0) {
+            const float4 c_mean = *reinterpret_cast<const float4*>(&Cc[0 * CH + kl + 4 * lk]);
+            const float4 c_rstd = *reinterpret_cast<const float4*>(&Cc[1 * CH + kl + 4 * lk]);
+            const float4 c_gm = *reinterpret_cast<const float4*>(&Cc[2 * CH + kl + 4 * lk]);
+            const float4 c_bt = *reinterpret_cast<const float4*>(&Cc[3 * CH + kl + 4 * lk]);
+            const float xs[4] = {a[0].x, a[0].y, a[0].z, a[0].w};
+            const float mean[4] = {c_mean.x, c_mean.y, c_mean.z, c_mean.w};
+            const float rstd[4] = {c_rstd.x, c_rstd.y, c_rstd.z, c_rstd.w};
+            const float gm[4] = {c_gm.x, c_gm.y, c_gm.z, c_gm.w};
+            const float bt[4] = {c_bt.x, c_bt.y, c_bt.z, c_bt.w};
+            float a2[4], a3[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float d = xs[e] - mean[e];
+              const float a1 = d * rstd[e];  // Eq. 1
+              const float t = gm[e] * a1;
+              a2[e] = t + bt[e];             // Eq. 2
+              a3[e] = a2[e] > 0.0f ? a2[e] : 0.0f;  // Eq. 3
+            }
+            a[0] = make_float4(a3[0], a3[1], a3[2], a3[3]);
+            if (n0 == 0) {  // block-uniform: the first output-channel block quantizes and packs
+              const float4 c_cq = *reinterpret_cast<const float4*>(&Cc[4 * CH + kl + 4 * lk]);
+              const int4 c_fb = *reinterpret_cast<const int4*>(&Cc[5 * CH + kl + 4 * lk]);
+              const float cq[4] = {c_cq.x, c_cq.y, c_cq.z, c_cq.w};
+              const int32_t fb[4] = {c_fb.x, c_fb.y, c_fb.z, c_fb.w};
+              uint32_t word = 0;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) word |= quant_code<KB>(a2[e], cq[e], fb[e]) << (KB * e);  // Eq. 9
+              if (pok) {
+                const int64_t e0 = prow * Kd + kg * 16 + 4 * lk;  // flat index of the first of 4 codes
+                if (KB == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
+                else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+              }
+            }
+          }
+          float4 wf[NT];
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            wf[j] = *reinterpret_cast<const float4*>(&W[(16 * j + li) * LDW + kl + 4 * lk]);
+          mma_k4<BF16, NT, 1>(wf, a, acc);
+        }
+      }
+      if (CHUNKED) {
+        // the other buffer was last read in the previous step, which every wave left at that
+        // step's barrier
+        if (more) store_chunk(buf ^ 1);
+        __syncthreads();
+      }
+    }
+
+    // 16-byte stores (and shortcut loads) of four consecutive channels of the pixel
+    if (pok) {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int64_t o = prow * N + n0 + 16 * j + 4 * lk;
+        float4 v = make_float4(acc[j][0][0], acc[j][0][1], acc[j][0][2], acc[j][0][3]);
+        if (skip != nullptr) {
+          const float4 sv = *reinterpret_cast<const float4*>(skip + o);
+          v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
+        }
+        *reinterpret_cast<float4*>(out + o) = v;
+      }
+    }
+    xp = xpn;
+  }
+}
+
+struct PointwisePlan {
+  int nt;
+  bool chunked;
+  int run_base, run_rem;
+  unsigned grid;
+};
+
+bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, PointwisePlan& p) {
+  if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
+  const int Kd = mode == 0 ? g.Cin : g.Cout, N = mode == 0 ? g.Cout : g.Cin;
+  if (Kd % 64 != 0 || N % 16 != 0) return false;
+  p.chunked = Kd > KC;
+  if (p.chunked && Kd % CHC != 0) return false;
+  const int64_t M = (int64_t)g.N * g.H * g.W;
+  if (M * Kd >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 31)) return false;
+  p.nt = N % 64 == 0 ? 4 : (N % 32 == 0 ? 2 : 1);
+  const int nblk_n = N / (16 * p.nt);
+  // as many blocks as fit the compute units at once (the weights' LDS; four waves per SIMD)
+  const unsigned lds = pointwise_lds_bytes(Kd, p.nt, fuse);
+  int occ = (int)((160u * 1024u) / lds);
+  const int occ_max = p.chunked ? 2 : 4;
+  if (occ > occ_max) occ = occ_max;
+  if (occ < 1) occ = 1;
+  const int bm = p.chunked ? 128 : 64;
+  const int64_t mtiles = (M + bm - 1) / bm;
+  int64_t runs = (int64_t)256 * occ / nblk_n / 8 * 8;  // blocks per output-channel block, whole XCD rounds
+  if (runs < 8) runs = 8;
+  if (runs > (mtiles + 7) / 8 * 8) runs = (mtiles + 7) / 8 * 8;
+  p.run_base = (int)(mtiles / runs);
+  p.run_rem = (int)(mtiles % runs);
+  p.grid = (unsigned)(runs * nblk_n);
+  return true;
+}
+
+template <int MODE, int FUSE>
+int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w, const float* skip,
+                     float* out, const float* stats, void* packed) {
+  PointwisePlan p;
+  if (!make_pointwise_plan(g, MODE, FUSE != 0, p)) return ABL_ERR_SHAPE;
+  const int64_t M = (int64_t)g.N * g.H * g.W;
+  const int Kd = MODE == 0 ? g.Cin : g.Cout, N = MODE == 0 ? g.Cout : g.Cin;
+  const int64_t raw = FUSE != 0 ? (M * Kd * FUSE + 7) / 8 : 0;
+  const int pack_pad = (int)((raw + 127) / 128 * 128 - raw);
+  const unsigned lds = pointwise_lds_bytes(Kd, p.nt, FUSE != 0);
+#define ABL_PW(NT_, CHUNKED_)                                                                                \
+  do {                                                                                                       \
+    auto kern = bf16 ? pointwise_kernel<MODE, NT_, CHUNKED_, true, FUSE>                                     \
+                     : pointwise_kernel<MODE, NT_, CHUNKED_, false, FUSE>;                                   \
+    if (lds > 64 * 1024 &&                                                                                   \
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                            lds) != hipSuccess)                                                              \
+      return ABL_ERR_HIP;                                                                                    \
+    kern<<<p.grid, CHUNKED_ ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,          \
+                                                    p.run_rem, stats, packed, pack_pad);                     \
+  } while (0)
+#define ABL_PW_C(NT_)                      \
+  do {                                     \
+    if (p.chunked) ABL_PW(NT_, true);      \
+    else ABL_PW(NT_, false);               \
+  } while (0)
+  if (p.nt == 4) ABL_PW_C(4);
+  else if (p.nt == 2) ABL_PW_C(2);
+  else ABL_PW_C(1);
+#undef ABL_PW_C
+#undef ABL_PW
+  return hip_status();
+}
+
+}  // namespace
+
+bool pointwise_supported(const ConvGeom& g, int mode) {
+  PointwisePlan p;
+  return make_pointwise_plan(g, mode, false, p);
+}
+
+int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
+                          const float* skip, float* out) {
+  if (mode == 0) return launch_pointwise<0, 0>(st, g, bf16, in, w, skip, out, nullptr, nullptr);
+  return launch_pointwise<1, 0>(st, g, bf16, in, w, nullptr, out, nullptr, nullptr);
+}
+
+int launch_pointwise_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x, const float* stats,
+                               const float* w, const float* skip, float* y, void* packed) {
+  if (K == 4) return launch_pointwise<0, 4>(st, g, bf16, x, w, skip, y, stats, packed);
+  if (K == 8) return launch_pointwise<0, 8>(st, g, bf16, x, w, skip, y, stats, packed);
+  return ABL_ERR_ARG;
+}
+
+}  // namespace abl
