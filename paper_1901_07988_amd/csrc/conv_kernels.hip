@@ -380,23 +380,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   int64_t p_end = p_begin + (int64_t)chunks_per_split * CH;
   if (p_end > Mg) p_end = Mg;
 
-  // per-thread dequantization constants: the thread's channel group is the same in every pass
-  const int a_cg = tid % GA;
-  // Eq. 10 as one fused multiply-add per element: step * ((code - 2^(K-1) + fb) + 0.5) equals
-  // fma(step, code + off, step / 2) bit for bit while |fb| < 2^22 (any layer whose codes are
-  // not all saturated): code + off is then an exact integer, step / 2 is exact, and both forms
-  // round the same exact product once.
-  float step[CPW], off[CPW], half_step[CPW];
-#pragma unroll
-  for (int v = 0; v < CPW; ++v) {
-    const int c = ci0 + a_cg * CPW + v;
-    const bool ok = K != 32 && c < g.Cin;
-    step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
-    const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
-    off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
-    half_step[v] = 0.5f * step[v];
-  }
-
+  const int a_cg = tid % GA;  // the thread's channel group is the same in every pass
   floatx4 acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -407,6 +391,8 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   uint32_t wa[A_PASSES];
   bool oka[A_PASSES];
   float4 rb[B_PASSES];
+  uint32_t okb = 0;  // bit j: pass j of the dy tile is inside the slice (applied when it is staged, so
+                     // that nothing waits for the loads before the MFMAs of the current chunk)
   // global loads of one 64-pixel chunk into registers
   // Output-pixel position (n, ho, wo) of each A pass, advanced by one chunk per fetch without
   // divisions; all loads are unconditional (clamped address, zeroed afterwards).
@@ -430,16 +416,13 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     for (int i = 0; i < A_PASSES; ++i) {
       const int idx = tid + kThreads * i;
       const int64_t p = pc + idx / GA;
-      if (flat) {
-        oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end;
-        const int64_t e = oka[i] ? p * g.Cin + ci0 : 0;
-        wa[i] = packed[e / CPW + (oka[i] ? a_cg : 0)];
-        continue;
-      }
+      // branch-free (a 1x1 stride-1 layer reads pixel p itself): a branch here would make the
+      // compiler wait for the loads already in flight
       const int hi = a_ho[i] * g.stride + r - g.pad, wi = a_wo[i] * g.stride + s - g.pad;
-      oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end && hi >= 0 && hi < g.H &&
-               wi >= 0 && wi < g.W;
-      const int64_t e = oka[i] ? (((int64_t)a_n[i] * g.H + hi) * g.W + wi) * g.Cin + ci0 : 0;
+      const bool inside = flat || (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W);
+      oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end && inside;
+      const int64_t pix = flat ? p : ((int64_t)a_n[i] * g.H + hi) * g.W + wi;
+      const int64_t e = oka[i] ? pix * g.Cin + ci0 : 0;
       wa[i] = packed[e / CPW + (oka[i] ? a_cg : 0)];
       // advance to the same slot of the next chunk
       a_wo[i] += adv_w;
@@ -454,35 +437,63 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       const int pl = idx / GB, c = co0 + 4 * (idx % GB);
       const int64_t p = pc + pl;
       const bool ok = (CH * GB % kThreads == 0 || idx < CH * GB) && p < p_end && c < g.Cout;
-      const float4 v = *reinterpret_cast<const float4*>(dy + (ok ? p * g.Cout + c : 0));
-      rb[j] = keep_if(ok, v);
+      rb[j] = *reinterpret_cast<const float4*>(dy + (ok ? p * g.Cout + c : 0));
+      okb = ok ? (okb | (1u << j)) : (okb & ~(1u << j));
     }
   };
   if (p_begin < p_end) fetch(p_begin);
+  // (the first chunk's loads are in flight while these constants arrive)
+  // per-thread dequantization constants: the thread's channel group is the same in every pass
+  // Eq. 10 as one fused multiply-add per element: step * ((code - 2^(K-1) + fb) + 0.5) equals
+  // fma(step, code + off, step / 2) bit for bit while |fb| < 2^22 (any layer whose codes are
+  // not all saturated): code + off is then an exact integer, step / 2 is exact, and both forms
+  // round the same exact product once.
+  float step[CPW], off[CPW], half_step[CPW];
+#pragma unroll
+  for (int v = 0; v < CPW; ++v) {
+    const int c = ci0 + a_cg * CPW + v;
+    const bool ok = K != 32 && c < g.Cin;
+    step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
+    const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
+    off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
+    half_step[v] = 0.5f * step[v];
+  }
+
   for (int64_t pc = p_begin; pc < p_end; pc += CH) {
     __syncthreads();  // previous chunk fully consumed
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       const int idx = tid + kThreads * i;
-      if (idx < CH * GA) {
+      if (CH * GA % kThreads == 0 || idx < CH * GA) {
         float* dst = &As[(idx / GA) * LDA + a_cg * CPW];
+        float vals[CPW];
 #pragma unroll
         for (int v = 0; v < CPW; ++v) {
           if constexpr (K == 32) {
             const float f = __uint_as_float(wa[i]);
-            dst[v] = (oka[i] && !(relu32 != 0 && f < 0.f)) ? f : 0.f;
+            vals[v] = (oka[i] && !(relu32 != 0 && f < 0.f)) ? f : 0.f;
           } else {
             const float code = (float)((wa[i] >> (K * v)) & ((1u << K) - 1));
             const float a2t = __builtin_fmaf(step[v], code + off[v], half_step[v]);  // Eq. 10
-            dst[v] = oka[i] ? fmaxf(a2t, 0.f) : 0.f;                                 // Eq. 3
+            vals[v] = oka[i] ? fmaxf(a2t, 0.f) : 0.f;                                // Eq. 3
           }
+        }
+        // 16-byte writes: element-wise ones would land 64 lanes on four LDS banks
+        if constexpr (CPW % 4 == 0) {
+#pragma unroll
+          for (int v = 0; v < CPW; v += 4)
+            *reinterpret_cast<float4*>(dst + v) = make_float4(vals[v], vals[v + 1], vals[v + 2], vals[v + 3]);
+        } else {
+#pragma unroll
+          for (int v = 0; v < CPW; ++v) dst[v] = vals[v];
         }
       }
     }
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
-      if (idx < CH * GB) *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = rb[j];
+      if (idx < CH * GB)
+        *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = keep_if((okb >> j) & 1u, rb[j]);
     }
     __syncthreads();
     if (pc + CH < p_end) fetch(pc + CH);  // in flight while this chunk is contracted
