@@ -158,6 +158,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
   int4 k_fb;
   int k_c = 0;
+  // bit i / j: pass i of the A tile / pass j of the B tile holds real data.  The zeroing of the
+  // rest happens when the tile is staged, so that nothing waits for the loads before the MFMAs
+  // of the current chunk.
+  uint32_t a_live = 0, b_live = 0;
   auto fetch = [&]() __attribute__((always_inline)) {
     // every load is issued unconditionally (out-of-range lanes read element 0 and are zeroed
     // afterwards): no branches between the loads, so they are all in flight together
@@ -165,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       const bool ok = a_off[i] >= 0 && c < Cg;
-      const float4 v = *reinterpret_cast<const float4*>(in + (ok ? a_off[i] + c : 0));
-      ra[i] = FUSE != 0 ? v : keep_if(ok, v);
+      ra[i] = *reinterpret_cast<const float4*>(in + (ok ? a_off[i] + c : 0));
+      a_live = ok ? (a_live | (1u << i)) : (a_live & ~(1u << i));
     }
     if (FUSE != 0) {
       k_mean = *reinterpret_cast<const float4*>(stats + P_MEAN * g.Cin + c);
@@ -186,12 +190,12 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
         const bool ok = b_ok[j] && f_c0 + 4 * (idx / BN) < Cg;
         const float* src = ok ? wb + b_thr[j] : wgt;
         const int64_t ld = ok ? g.Cout : 0;
-        const float4 v = make_float4(src[0], src[ld], src[2 * ld], src[3 * ld]);
-        rb[j] = keep_if(ok, v);
+        rb[j] = make_float4(src[0], src[ld], src[2 * ld], src[3 * ld]);
+        b_live = ok ? (b_live | (1u << j)) : (b_live & ~(1u << j));
       } else {
         const bool ok = b_ok[j] && f_c0 + 4 * (idx % KQ) < Cg;
-        const float4 v = *reinterpret_cast<const float4*>(ok ? wb + b_thr[j] : wgt);
-        rb[j] = keep_if(ok, v);
+        rb[j] = *reinterpret_cast<const float4*>(ok ? wb + b_thr[j] : wgt);
+        b_live = ok ? (b_live | (1u << j)) : (b_live & ~(1u << j));
       }
     }
     f_c0 += BK;
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     float* Bs = Bs0 + buf * BN * LDK;
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
-      float4 v = ra[i];
+      float4 v = FUSE != 0 ? ra[i] : keep_if((a_live >> i) & 1u, ra[i]);
       if (FUSE != 0) {
         // a 1x1 convolution has one tap, so a_off[] still belongs to the chunk in ra[]
         const bool ok = a_off[i] >= 0;
@@ -246,10 +250,11 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     for (int j = 0; j < B_PASSES; ++j) {
       const int idx = tid + kThreads * j;
       if (B_F4 % kThreads == 0 || idx < B_F4) {
+        const float4 v = keep_if((b_live >> j) & 1u, rb[j]);
         if (MODE == 0) {
-          *reinterpret_cast<float4*>(&Bs[(idx % BN) * LDK + 4 * (idx / BN)]) = rb[j];
+          *reinterpret_cast<float4*>(&Bs[(idx % BN) * LDK + 4 * (idx / BN)]) = v;
         } else {
-          *reinterpret_cast<float4*>(&Bs[(idx / KQ) * LDK + 4 * (idx % KQ)]) = rb[j];
+          *reinterpret_cast<float4*>(&Bs[(idx / KQ) * LDK + 4 * (idx % KQ)]) = v;
         }
       }
     }
