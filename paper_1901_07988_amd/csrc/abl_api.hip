@@ -203,9 +203,9 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   // input rows; measured against the separate pack kernel this pays up to 256 output channels.
   if (K != 32 && !naive && igemm_fused_supported(*s) && s->Cout <= 256 &&
       static_cast<const void*>(x) != static_cast<const void*>(y))
-    return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed);
+    return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed, out_partial, out_nb);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, naive)) return e;
-  return launch_conv_fwd(st, *s, bf16, a3, W, skip, y);
+  return launch_conv_fwd(st, *s, bf16, a3, W, skip, y, out_partial, out_nb);
 }
 
 }  // namespace

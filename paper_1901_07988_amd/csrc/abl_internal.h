@@ -67,7 +67,7 @@ inline ConvGeom geom_of(const abl_shape& s) {
 // mode 0: forward, mode 1: gradient to the input.
 bool halo_conv_supported(const ConvGeom& g);
 int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
-                     const float* skip, float* out);
+                     const float* skip, float* out, double* out_partial = nullptr);
 // Forward with Eq. 1-3 and Eq. 9 applied while the input patch is staged: reads x, writes y and
 // the packed codes; A3 never reaches memory.  Supported for 'same' stride-1 convolutions.
 bool halo_fused_supported(const ConvGeom& g);
@@ -100,8 +100,10 @@ int launch_halo_bwd16(hipStream_t st, const ConvGeom& g, int K, bool bf16, const
 
 // ---- convolution kernels (conv_kernels.hip) ----
 size_t wgrad_partial_bytes(const abl_shape& s);
+// sums / rows (nullable): where the kernel can, it leaves per-block fp64 sums of y and y^2
+// ([rows][2][Cout], *rows <= kMaxPartialBlocks) for the next layer's statistics; *rows = 0 if not.
 int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,
-                    const float* skip, float* y);
+                    const float* skip, float* y, double* sums = nullptr, int* rows = nullptr);
 int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float* dy, const float* w,
                       float* da3);
 // Forward of a 1x1 stride-1 convolution without padding with Eq. 1-3 and Eq. 9 applied while the
@@ -112,12 +114,14 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
 // loaded straight into MFMA layout.  mode 0 forward (skip nullable), 1 dgrad.
 bool pointwise_supported(const ConvGeom& g, int mode);
 int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
-                          const float* skip, float* out);
+                          const float* skip, float* out, double* sums = nullptr, int* rows = nullptr);
 int launch_pointwise_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x, const float* stats,
-                               const float* w, const float* skip, float* y, void* packed);
+                               const float* w, const float* skip, float* y, void* packed, double* sums = nullptr,
+                               int* rows = nullptr);
 bool igemm_fused_supported(const abl_shape& s);
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
-                          const float* w, const float* skip, float* y, void* packed);
+                          const float* w, const float* skip, float* y, void* packed, double* sums = nullptr,
+                          int* rows = nullptr);
 // K = 32: `packed` is an fp32 tensor, used as it is or (relu32) as the pre-ReLU activation A2.
 // defer (nullable): where the kernel leaves split partial copies, describe them there instead of
 // summing them (copies = 0 when dw is already complete) - for launch_bn_bwd_finish.
@@ -160,6 +164,24 @@ __device__ inline float dequant(uint32_t q, float step, int32_t fb) {
     const float t = (float)j + 0.5f;
     return step * t;
   }
+}
+
+// Sum over the 16 lanes of a row (lanes that differ in bits 0-3); every lane gets the total.
+// (Data-parallel-primitive moves within the row: swap neighbours, swap pairs, mirror each half,
+// mirror the row.)
+template <int CTRL>
+__device__ inline double dpp_move(double v) {
+  const unsigned long long u = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+__device__ inline double row16_sum(double v) {
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
+  return v;
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));

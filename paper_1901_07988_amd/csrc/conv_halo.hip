@@ -91,25 +91,6 @@ __device__ inline int in_vgpr(int x) {
 // a * b + c for operands below 2^23 in magnitude (full-rate 24-bit multiplier)
 __device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 
-// Sum over the 16 lanes of a row (lanes that differ in bits 0-3); every lane gets the total.
-// (Data-parallel-primitive moves within the row: swap neighbours, swap pairs, mirror each half,
-// mirror the row.)
-template <int CTRL>
-__device__ inline double dpp_move(double v) {
-  const unsigned long long u = __double_as_longlong(v);
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, false);
-  return __longlong_as_double(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
-}
-__device__ inline double row16_sum(double v) {
-  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
-  v += dpp_move<0x141>(v);  // row_half_mirror
-  v += dpp_move<0x140>(v);  // row_mirror
-  return v;
-}
-
-
 // WAVES_N waves share the block's M-tiles and split its N-tiles; the other 4/WAVES_N groups
 // split the M-tiles.  MT = M-tiles (16 pixels) per wave (upper bound, `mtiles` is the real
 // count), NT = N-tiles (16 output channels) per wave.
@@ -1116,12 +1097,13 @@ bool halo_conv_supported(const ConvGeom& g) {
 }
 
 int launch_halo_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
-                     const float* skip, float* out) {
+                     const float* skip, float* out, double* out_partial) {
   HaloPlan p;
   if (!make_plan(g, mode, p)) return ABL_ERR_SHAPE;
   p.pack_pad = 0;
   const EpiReduce none{nullptr, nullptr, 0};
-  if (mode == 0) launch_mode<0, 0>(st, g, p, bf16, in, w, skip, out, nullptr, nullptr, none);
+  const EpiReduce sums{out_partial, nullptr, 0};  // forward only: sums of y for the next layer's Eq. 1
+  if (mode == 0) launch_mode<0, 0>(st, g, p, bf16, in, w, skip, out, nullptr, nullptr, sums);
   else launch_mode<1, 0>(st, g, p, bf16, in, w, nullptr, out, nullptr, nullptr, none);
   return hip_status();
 }

@@ -783,15 +783,22 @@ size_t wgrad_partial_bytes(const abl_shape& s) {
 }
 
 int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,
-                    const float* skip, float* y) {
+                    const float* skip, float* y, double* sums, int* rows) {
   const ConvGeom g = geom_of(s);
+  if (rows != nullptr) *rows = 0;
   if (!mfma_ok(g)) {
     const int64_t total = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
     naive_fwd_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(a3, w, skip, y, g);
     return hip_status();
   }
-  if (halo_conv_supported(g)) return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y);
-  if (pointwise_supported(g, 0)) return launch_pointwise_conv(st, g, 0, bf16, a3, w, skip, y);
+  if (halo_conv_supported(g)) {
+    const int tiles = sums != nullptr && rows != nullptr ? halo_tile_count(g, 0) : 0;
+    const bool want = tiles > 0 && tiles <= kMaxPartialBlocks;
+    if (want) *rows = tiles;
+    return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y, want ? sums : nullptr);
+  }
+  if (pointwise_supported(g, 0))
+    return launch_pointwise_conv(st, g, 0, bf16, a3, w, skip, y, rows != nullptr ? sums : nullptr, rows);
   return launch_igemm<0, 0>(st, g, bf16, a3, w, skip, y, nullptr, nullptr);
 }
 
@@ -802,11 +809,14 @@ bool igemm_fused_supported(const abl_shape& s) {
 }
 
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
-                          const float* w, const float* skip, float* y, void* packed) {
+                          const float* w, const float* skip, float* y, void* packed, double* sums, int* rows) {
   if (!igemm_fused_supported(s)) return ABL_ERR_SHAPE;
   const ConvGeom g = geom_of(s);
   const float* sp = static_cast<const float*>(stats);
-  if (pointwise_supported(g, 0)) return launch_pointwise_fwd_fused(st, g, K, bf16, x, sp, w, skip, y, packed);
+  if (rows != nullptr) *rows = 0;
+  if (pointwise_supported(g, 0))
+    return launch_pointwise_fwd_fused(st, g, K, bf16, x, sp, w, skip, y, packed, rows != nullptr ? sums : nullptr,
+                                      rows);
   if (K == 4) return launch_igemm<0, 4>(st, g, bf16, x, w, skip, y, sp, packed);
   return launch_igemm<0, 8>(st, g, bf16, x, w, skip, y, sp, packed);
 }

@@ -42,11 +42,13 @@ inline unsigned pointwise_lds_bytes(int Kd, int nt, bool fuse) {
 // ldw = Cout.  Kd is a multiple of 64 (of 128 when CHUNKED), N a multiple of 16 * NT.
 // Pixel tiles of 16 * WAVES rows; block `r` of an output-channel block takes run_base tiles, one
 // more if r < run_rem, in order.
-template <int MODE, int NT, bool CHUNKED, bool BF16, int FUSE>
+// SUMS (forward): the block also leaves the per-channel sums of its outputs and of their squares
+// (fp64; row `run`, layout [rows][2][N]) for the statistics of the next layer's Eq. 1.
+template <int MODE, int NT, bool CHUNKED, bool BF16, int FUSE, bool SUMS>
 __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
     const float* __restrict__ in, const float* __restrict__ wgt, const float* skip, float* out, int64_t M, int Kd,
     int N, int ldw, int run_base, int run_rem, const float* __restrict__ stats, void* __restrict__ packed,
-    int pack_pad) {
+    int pack_pad, double* __restrict__ sums) {
   static_assert(FUSE == 0 || MODE == 0, "the prologue belongs to the forward");
   constexpr int WAVES = CHUNKED ? 8 : 4;
   constexpr int kThreads = 64 * WAVES;
@@ -155,6 +157,12 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
 #pragma unroll
   for (int s = 0; s < PF; ++s) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * s);
 
+  double s1[NT][4], s2[NT][4];  // SUMS: this lane's pixels, its four channels of every tile column
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = 0.0;
+
   int step = 0;  // (tile, chunk) pairs done so far: chunk buffers alternate with it
   for (int64_t tile = t_begin; tile < t_end; ++tile) {
     const bool has_next = tile + 1 < t_end;
@@ -240,9 +248,41 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
           v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
         }
         *reinterpret_cast<float4*>(out + o) = v;
+        if (SUMS) {
+          const float vs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const double d = (double)vs[r];
+            s1[j][r] += d;
+            s2[j][r] += d * d;
+          }
+        }
       }
     }
     xp = xpn;
+  }
+  if (SUMS) {
+    // fixed order: the 16 pixels of a row of lanes by a butterfly, then the waves through LDS
+    __syncthreads();  // every wave is done with the weights
+    double* red = reinterpret_cast<double*>(lds);  // [2][WAVES][BN]
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const double t1 = row16_sum(s1[j][r]), t2 = row16_sum(s2[j][r]);
+        if (li == 0) {
+          red[(0 * WAVES + wave) * BN + 16 * j + 4 * lk + r] = t1;
+          red[(1 * WAVES + wave) * BN + 16 * j + 4 * lk + r] = t2;
+        }
+      }
+    __syncthreads();
+    for (int c = tid; c < 2 * BN; c += kThreads) {
+      const int qv = c / BN, ch = c % BN;
+      double t = 0.0;
+#pragma unroll
+      for (int k = 0; k < WAVES; ++k) t += red[(qv * WAVES + k) * BN + ch];
+      sums[((int64_t)run * 2 + qv) * N + n0 + ch] = t;
+    }
   }
 }
 
@@ -250,6 +290,7 @@ struct PointwisePlan {
   int nt;
   bool chunked;
   int run_base, run_rem;
+  int rows;  // blocks per output-channel block that have tiles (= rows of sums)
   unsigned grid;
 };
 
@@ -272,17 +313,19 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, PointwisePlan& 
   const int bm = p.chunked ? 128 : 64;
   const int64_t mtiles = (M + bm - 1) / bm;
   int64_t runs = (int64_t)256 * occ / nblk_n / 8 * 8;  // blocks per output-channel block, whole XCD rounds
+  if (runs > kMaxPartialBlocks) runs = kMaxPartialBlocks;  // one row of sums per block
   if (runs < 8) runs = 8;
   if (runs > (mtiles + 7) / 8 * 8) runs = (mtiles + 7) / 8 * 8;
   p.run_base = (int)(mtiles / runs);
   p.run_rem = (int)(mtiles % runs);
+  p.rows = p.run_base > 0 ? (int)runs : p.run_rem;
   p.grid = (unsigned)(runs * nblk_n);
   return true;
 }
 
 template <int MODE, int FUSE>
 int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w, const float* skip,
-                     float* out, const float* stats, void* packed) {
+                     float* out, const float* stats, void* packed, double* sums, int* rows) {
   PointwisePlan p;
   if (!make_pointwise_plan(g, MODE, FUSE != 0, p)) return ABL_ERR_SHAPE;
   const int64_t M = (int64_t)g.N * g.H * g.W;
@@ -290,16 +333,22 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
   const int64_t raw = FUSE != 0 ? (M * Kd * FUSE + 7) / 8 : 0;
   const int pack_pad = (int)((raw + 127) / 128 * 128 - raw);
   const unsigned lds = pointwise_lds_bytes(Kd, p.nt, FUSE != 0);
+  if (rows != nullptr) *rows = sums != nullptr ? p.rows : 0;
 #define ABL_PW(NT_, CHUNKED_)                                                                                \
   do {                                                                                                       \
-    auto kern = bf16 ? pointwise_kernel<MODE, NT_, CHUNKED_, true, FUSE>                                     \
-                     : pointwise_kernel<MODE, NT_, CHUNKED_, false, FUSE>;                                   \
+    if (MODE == 0 && sums != nullptr) ABL_PW_S(NT_, CHUNKED_, (MODE == 0));                                  \
+    else ABL_PW_S(NT_, CHUNKED_, false);                                                                     \
+  } while (0)
+#define ABL_PW_S(NT_, CHUNKED_, SUMS_)                                                                       \
+  do {                                                                                                       \
+    auto kern = bf16 ? pointwise_kernel<MODE, NT_, CHUNKED_, true, FUSE, SUMS_>                              \
+                     : pointwise_kernel<MODE, NT_, CHUNKED_, false, FUSE, SUMS_>;                            \
     if (lds > 64 * 1024 &&                                                                                   \
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             lds) != hipSuccess)                                                              \
       return ABL_ERR_HIP;                                                                                    \
     kern<<<p.grid, CHUNKED_ ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,          \
-                                                    p.run_rem, stats, packed, pack_pad);                     \
+                                                    p.run_rem, stats, packed, pack_pad, sums);               \
   } while (0)
 #define ABL_PW_C(NT_)                      \
   do {                                     \
@@ -311,6 +360,7 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
   else ABL_PW_C(1);
 #undef ABL_PW_C
 #undef ABL_PW
+#undef ABL_PW_S
   return hip_status();
 }
 
@@ -322,15 +372,16 @@ bool pointwise_supported(const ConvGeom& g, int mode) {
 }
 
 int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
-                          const float* skip, float* out) {
-  if (mode == 0) return launch_pointwise<0, 0>(st, g, bf16, in, w, skip, out, nullptr, nullptr);
-  return launch_pointwise<1, 0>(st, g, bf16, in, w, nullptr, out, nullptr, nullptr);
+                          const float* skip, float* out, double* sums, int* rows) {
+  if (mode == 0) return launch_pointwise<0, 0>(st, g, bf16, in, w, skip, out, nullptr, nullptr, sums, rows);
+  if (rows != nullptr) *rows = 0;
+  return launch_pointwise<1, 0>(st, g, bf16, in, w, nullptr, out, nullptr, nullptr, nullptr, nullptr);
 }
 
 int launch_pointwise_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x, const float* stats,
-                               const float* w, const float* skip, float* y, void* packed) {
-  if (K == 4) return launch_pointwise<0, 4>(st, g, bf16, x, w, skip, y, stats, packed);
-  if (K == 8) return launch_pointwise<0, 8>(st, g, bf16, x, w, skip, y, stats, packed);
+                               const float* w, const float* skip, float* y, void* packed, double* sums, int* rows) {
+  if (K == 4) return launch_pointwise<0, 4>(st, g, bf16, x, w, skip, y, stats, packed, sums, rows);
+  if (K == 8) return launch_pointwise<0, 8>(st, g, bf16, x, w, skip, y, stats, packed, sums, rows);
   return ABL_ERR_ARG;
 }
 
