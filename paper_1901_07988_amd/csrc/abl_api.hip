@@ -270,6 +270,22 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta,
                                 dwsum.copies > 0 ? &dwsum : nullptr);
   }
+  // 1x1 stride-1 layers: the same sums in the epilogue of the pointwise dgrad kernel
+  if (K != 32 && pointwise_supported(g, 1)) {
+    int rows = 0;
+    if (int e = launch_pointwise_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red),
+                                              &rows))
+      return e;
+    if (rows > 0) {
+      DwSum dwsum;
+      if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+      return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, rows, dx, dgamma, dbeta,
+                                  dwsum.copies > 0 ? &dwsum : nullptr);
+    }
+    // (long contractions: the kernel computed dA3 only)
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
+    return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
+  }
   if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
   // exact storage keeps the pre-ReLU A2: the weight gradient applies Eq. 3 on the way in
   if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, K == 32)) return e;

@@ -118,6 +118,10 @@ int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16
 int launch_pointwise_fwd_fused(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* x, const float* stats,
                                const float* w, const float* skip, float* y, void* packed, double* sums = nullptr,
                                int* rows = nullptr);
+// dgrad (Eq. 5) with the Eq. 6-7 sums taken in its epilogue from the layer's codes: one row of
+// [2][Cin] doubles per block, *rows of them (<= kMaxPartialBlocks), for launch_bn_bwd_finish.
+int launch_pointwise_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy, const float* w,
+                                  const void* packed, const void* stats, float* da3, double* sums, int* rows);
 bool igemm_fused_supported(const abl_shape& s);
 int launch_conv_fwd_fused(hipStream_t st, const abl_shape& s, int K, bool bf16, const float* x, const void* stats,
                           const float* w, const float* skip, float* y, void* packed, double* sums = nullptr,

@@ -18,6 +18,8 @@
 //   longer: 128-channel chunks in two buffers, the next chunk's global loads in flight while
 //           the current one is contracted, one barrier per chunk.
 // Every block walks over a run of consecutive pixel tiles; the runs differ by at most one tile.
+#include <type_traits>
+
 #include "abl_internal.h"
 
 // Eq. 1-3 and Eq. 9 are evaluated here: one rounded fp32 operation at a time
@@ -42,13 +44,16 @@ inline unsigned pointwise_lds_bytes(int Kd, int nt, bool fuse) {
 // ldw = Cout.  Kd is a multiple of 64 (of 128 when CHUNKED), N a multiple of 16 * NT.
 // Pixel tiles of 16 * WAVES rows; block `r` of an output-channel block takes run_base tiles, one
 // more if r < run_rem, in order.
-// SUMS (forward): the block also leaves the per-channel sums of its outputs and of their squares
-// (fp64; row `run`, layout [rows][2][N]) for the statistics of the next layer's Eq. 1.
+// SUMS: the block also leaves per-channel fp64 sums of what it holds in registers (row `run`,
+// layout [rows][2][N]) - forward: of its outputs and their squares, for the statistics of the
+// next layer's Eq. 1; dgrad: of dA2 = dA3 where the dequantized activation is positive (Eq. 6)
+// and of A1~ * dA2 (Eq. 7), with the layer's codes read here (`packed`, code_bits wide, and the
+// layer's `stats`), which saves the separate reduce pass over dA3.
 template <int MODE, int NT, bool CHUNKED, bool BF16, int FUSE, bool SUMS>
 __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
     const float* __restrict__ in, const float* __restrict__ wgt, const float* skip, float* out, int64_t M, int Kd,
     int N, int ldw, int run_base, int run_rem, const float* __restrict__ stats, void* __restrict__ packed,
-    int pack_pad, double* __restrict__ sums) {
+    int pack_pad, double* __restrict__ sums, int code_bits) {
   static_assert(FUSE == 0 || MODE == 0, "the prologue belongs to the forward");
   constexpr int WAVES = CHUNKED ? 8 : 4;
   constexpr int kThreads = 64 * WAVES;
@@ -157,11 +162,30 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
 #pragma unroll
   for (int s = 0; s < PF; ++s) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * s);
 
-  double s1[NT][4], s2[NT][4];  // SUMS: this lane's pixels, its four channels of every tile column
+  // SUMS: this lane's pixels (at most a few dozen), its four channels of every tile column.
+  // The forward sums feed a variance (sum of squares minus square of the sum): fp64 from the
+  // first addition.  The gradient sums have no such cancellation: fp32 per lane, fp64 from the
+  // reduction over lanes on.
+  using sum_t = typename std::conditional<MODE == 0, double, float>::type;
+  sum_t s1[NT][4], s2[NT][4];
 #pragma unroll
   for (int j = 0; j < NT; ++j)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = 0.0;
+    for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = (sum_t)0;
+  // dgrad sums: Eq. 10 constants of the lane's channels n0 + 16j + 4lk .. +3
+  float4 r_step[NT], r_beta[NT], r_ig[NT];
+  int4 r_fb[NT];
+  if (SUMS && MODE == 1) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int c = n0 + 16 * j + 4 * lk;
+      r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * N + c);
+      r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * N + c);
+      const float4 gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * N + c);
+      r_ig[j] = make_float4(1.0f / gm.x, 1.0f / gm.y, 1.0f / gm.z, 1.0f / gm.w);
+      r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * N + c);
+    }
+  }
 
   int step = 0;  // (tile, chunk) pairs done so far: chunk buffers alternate with it
   for (int64_t tile = t_begin; tile < t_end; ++tile) {
@@ -248,13 +272,33 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
           v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
         }
         *reinterpret_cast<float4*>(out + o) = v;
-        if (SUMS) {
+        if (SUMS && MODE == 0) {
           const float vs[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const double d = (double)vs[r];
             s1[j][r] += d;
             s2[j][r] += d * d;
+          }
+        }
+        if (SUMS && MODE == 1) {
+          const uint8_t* codes = static_cast<const uint8_t*>(packed);
+          const uint32_t cw = code_bits == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o >> 1))
+                                             : *reinterpret_cast<const uint32_t*>(codes + o);
+          const float vs[4] = {v.x, v.y, v.z, v.w};
+          const float st4[4] = {r_step[j].x, r_step[j].y, r_step[j].z, r_step[j].w};
+          const float bt4[4] = {r_beta[j].x, r_beta[j].y, r_beta[j].z, r_beta[j].w};
+          const float ig4[4] = {r_ig[j].x, r_ig[j].y, r_ig[j].z, r_ig[j].w};
+          const int32_t fb4[4] = {r_fb[j].x, r_fb[j].y, r_fb[j].z, r_fb[j].w};
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t code = (cw >> (code_bits * r)) & ((1u << code_bits) - 1u);
+            const int32_t jj = (int32_t)code - (1 << (code_bits - 1)) + fb4[r];
+            const float a2t = st4[r] * ((float)jj + 0.5f);       // Eq. 10
+            const float da2 = a2t > 0.0f ? vs[r] : 0.0f;         // Eq. 6
+            const float a1t = (a2t - bt4[r]) * ig4[r];           // inverse of Eq. 2
+            s1[j][r] += da2;
+            s2[j][r] += a1t * da2;
           }
         }
       }
@@ -269,7 +313,7 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const double t1 = row16_sum(s1[j][r]), t2 = row16_sum(s2[j][r]);
+        const double t1 = row16_sum((double)s1[j][r]), t2 = row16_sum((double)s2[j][r]);
         if (li == 0) {
           red[(0 * WAVES + wave) * BN + 16 * j + 4 * lk + r] = t1;
           red[(1 * WAVES + wave) * BN + 16 * j + 4 * lk + r] = t2;
@@ -325,7 +369,7 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, PointwisePlan& 
 
 template <int MODE, int FUSE>
 int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w, const float* skip,
-                     float* out, const float* stats, void* packed, double* sums, int* rows) {
+                     float* out, const float* stats, void* packed, double* sums, int* rows, int code_bits = 0) {
   PointwisePlan p;
   if (!make_pointwise_plan(g, MODE, FUSE != 0, p)) return ABL_ERR_SHAPE;
   const int64_t M = (int64_t)g.N * g.H * g.W;
@@ -333,10 +377,13 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
   const int64_t raw = FUSE != 0 ? (M * Kd * FUSE + 7) / 8 : 0;
   const int pack_pad = (int)((raw + 127) / 128 * 128 - raw);
   const unsigned lds = pointwise_lds_bytes(Kd, p.nt, FUSE != 0);
+  // (with 128-channel chunks eight waves share a SIMD pair and the extra registers of the sums
+  // cost more than the pass they save)
+  if (p.chunked) sums = nullptr;
   if (rows != nullptr) *rows = sums != nullptr ? p.rows : 0;
 #define ABL_PW(NT_, CHUNKED_)                                                                                \
   do {                                                                                                       \
-    if (MODE == 0 && sums != nullptr) ABL_PW_S(NT_, CHUNKED_, (MODE == 0));                                  \
+    if (sums != nullptr) ABL_PW_S(NT_, CHUNKED_, true);                                                      \
     else ABL_PW_S(NT_, CHUNKED_, false);                                                                     \
   } while (0)
 #define ABL_PW_S(NT_, CHUNKED_, SUMS_)                                                                       \
@@ -348,7 +395,7 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
                             lds) != hipSuccess)                                                              \
       return ABL_ERR_HIP;                                                                                    \
     kern<<<p.grid, CHUNKED_ ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,          \
-                                                    p.run_rem, stats, packed, pack_pad, sums);               \
+                                                    p.run_rem, stats, packed, pack_pad, sums, code_bits);    \
   } while (0)
 #define ABL_PW_C(NT_)                      \
   do {                                     \
@@ -365,6 +412,13 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
 }
 
 }  // namespace
+
+int launch_pointwise_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, bool bf16, const float* dy, const float* w,
+                                  const void* packed, const void* stats, float* da3, double* sums, int* rows) {
+  if ((K != 4 && K != 8) || sums == nullptr || rows == nullptr) return ABL_ERR_ARG;
+  return launch_pointwise<1, 0>(st, g, bf16, dy, w, nullptr, da3, static_cast<const float*>(stats),
+                                const_cast<void*>(packed), sums, rows, K);
+}
 
 bool pointwise_supported(const ConvGeom& g, int mode) {
   PointwisePlan p;

@@ -122,9 +122,11 @@ def test_full_size_layer(G, oracle, case, K):
     dx_ref, dg_ref, db_ref = o.bn_relu_bwd(a2t, g_in, rstd, gamma, beta)
     dx_s, dg_s, db_s = G.run_bn_bwd(run.packed.cpu().numpy(), run.stats, g_in, K)
     assert rel(dx_s, dx_ref) < TOL and rel(dg_s, dg_ref) < TOL and rel(db_s, db_ref) < TOL
-    # ... and the layer call must be exactly that stage applied to its own dA3
+    # ... and the layer call must be that stage applied to its own dA3.  (Not bit for bit: where
+    # the layer takes the Eq. 6-7 sums in the epilogue of its dgrad kernel they are added in
+    # another order, per lane in fp32 for 1x1 layers, than in the stage's fp64 passes.)
     dx_c, dg_c, db_c = G.run_bn_bwd(run.packed.cpu().numpy(), run.stats, da3_gpu, K)
-    assert dx_c.tobytes() == dx.tobytes() and dg_c.tobytes() == dg.tobytes() and db_c.tobytes() == db.tobytes()
+    assert rel(dx, dx_c) < 1e-5 and rel(dg, dg_c) < 1e-5 and rel(db, db_c) < 1e-5
     # Eq. 8 summed over a channel: the first two terms cancel, the third leaves
     # sum(dx) = -rstd * Mean(A1~ * dA1) * sum(A1~), with Mean(A1~ * dA1) = gamma * dgamma / M
     a1t_sum = ((a2t.reshape(-1, s.Cin).sum(0, dtype=np.float64) - s.M * beta.astype(np.float64))
