@@ -283,13 +283,17 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
                                   dwsum.copies > 0 ? &dwsum : nullptr);
     }
     // (long contractions: the kernel computed dA3 only)
-    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW)) return e;
-    return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
+    DwSum dwsum;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+    return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta,
+                         dwsum.copies > 0 ? &dwsum : nullptr);
   }
   if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, da3)) return e;
   // exact storage keeps the pre-ReLU A2: the weight gradient applies Eq. 3 on the way in
-  if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, K == 32)) return e;
-  return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta);
+  DwSum dwsum;
+  if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, K == 32, &dwsum)) return e;
+  return launch_bn_bwd(st, packed, stats, da3, M, s->Cin, K, accum, red, dx, dgamma, dbeta,
+                       dwsum.copies > 0 ? &dwsum : nullptr);
 }
 
 // ---- the two fused kernels of the layer step, callable on their own --------------------------

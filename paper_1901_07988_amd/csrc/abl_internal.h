@@ -27,8 +27,6 @@ int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const 
                 void* packed);
 int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, const void* stats,
                   float* a2t);
-int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
-                  int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta);
 // The second halves of the two reductions, for partial sums produced elsewhere (conv epilogues).
 size_t bn_means_offset(int C);
 int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, const float* shift_row, int64_t M,
@@ -43,6 +41,10 @@ struct DwSum {
 };
 int launch_sgd_momentum(hipStream_t st, int64_t n, float lr, float mu, float wd, float* w, const float* grad,
                         float* v);
+// Backward of BN + ReLU from dA3 and the codes (Eq. 6-8): both passes.
+int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
+                  int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta,
+                  const DwSum* dwsum = nullptr);
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
                          float* dbeta, const DwSum* dwsum = nullptr);

@@ -797,7 +797,8 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
 }
 
 int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
-                  int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta) {
+                  int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta,
+                  const DwSum* dwsum) {
   const float* sp = static_cast<const float*>(stats);
   double* partial = static_cast<double*>(scratch);
   const int vec = fast_vec(K, C);
@@ -818,7 +819,7 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
     bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
   }
   if (hipGetLastError() != hipSuccess) return ABL_ERR_HIP;
-  return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta);
+  return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta, dwsum);
 }
 
 // Eq. 7 totals and Eq. 8 from `nb` partial rows [nb][2][C] of (sum dA2, sum A1~ dA2) at the
