@@ -156,8 +156,9 @@ int abl_conv_wgrad_packed(void* stream, const abl_shape* shape, int K, uint32_t 
                           size_t scratch_bytes, float* dW);
 
 /* ---- the two fused kernels that abl_forward / abl_backward use where they can ----
- * Both exist for stride-1 convolutions with a filter larger than 1x1 and channel counts that
- * are multiples of 16 (abl_bn_conv_fwd also needs Ho == H, Wo == W); other shapes give
+ * Both exist for stride-1 convolutions with channel counts that are multiples of 16: filters
+ * larger than 1x1 (abl_bn_conv_fwd also needs Ho == H, Wo == W), and 1x1 filters without padding
+ * (abl_conv_dgrad_bn_reduce: Cout a multiple of 64 and at most 256).  Other shapes give
  * ABL_ERR_SHAPE and the layer calls fall back to the separate stages.
  *
  * abl_bn_conv_fwd: Eq. 1-3, Eq. 9 and Eq. 4 in one kernel - x is normalised, ReLU'd, quantized

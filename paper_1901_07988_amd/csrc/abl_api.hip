@@ -325,9 +325,18 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t f
       rows == nullptr)
     return ABL_ERR_ARG;
   const ConvGeom g = geom_of(*s);
+  if (scratch_bytes < bn_partial_bytes(rows_of(*s), s->Cin)) return ABL_ERR_SCRATCH;
+  if (!halo_conv_supported(g) && pointwise_supported(g, 1)) {  // 1x1 stride 1: the pointwise kernel's epilogue
+    int r = 0;
+    if (int e = launch_pointwise_dgrad_reduce((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, dy, W, packed,
+                                              stats, da3, static_cast<double*>(scratch), &r))
+      return e;
+    *rows = r;
+    // contractions of more than 256 channels run without the sums: dA3 is written, no rows
+    return r > 0 ? ABL_OK : ABL_ERR_SHAPE;
+  }
   const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles <= 0 || tiles > kMaxPartialBlocks) return ABL_ERR_SHAPE;
-  if (scratch_bytes < bn_partial_bytes(rows_of(*s), s->Cin)) return ABL_ERR_SCRATCH;
   *rows = tiles;
   return launch_halo_dgrad_reduce((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, dy, W, packed, stats,
                                   da3, static_cast<double*>(scratch));

@@ -481,6 +481,27 @@ def test_fused_forward_1x1(G, oracle, s, K):
     _fused_kernels_case(G, oracle, s, K, False)
 
 
+@pytest.mark.parametrize("s", [LayerShape(2, 14, 14, 256, 64, 1, 1, 1, 0), LayerShape(3, 9, 7, 64, 256, 1, 1, 1, 0),
+                               LayerShape(40, 14, 14, 32, 128, 1, 1, 1, 0), LayerShape(1, 5, 5, 1024, 256, 1, 1, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_fused_kernels_1x1_with_backward(G, oracle, s, K):
+    """1x1 layers whose dgrad takes the Eq. 6-7 sums in its epilogue (the contraction runs over
+    Cout: a multiple of 64, at most 256): ragged pixel tiles, one to four blocks of input channels."""
+    _fused_kernels_case(G, oracle, s, K, True)
+
+
+def test_dgrad_with_sums_rejects_long_contractions(G):
+    import torch
+    from paper_1901_07988_amd import binding as B
+    t = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    sc = G.zeros_bytes(B.abl_bn_scratch_bytes(50, 256))
+    for shape in ((2, 5, 5, 256, 1024, 1, 1, 1, 0), (2, 5, 5, 256, 48, 1, 1, 1, 0)):
+        with pytest.raises(B.AblError) as e:
+            B.abl_conv_dgrad_bn_reduce(shape, 4, t, t, t, t, sc, t[1 << 19:])
+        assert e.value.code == B.ABL_ERR_SHAPE
+
+
 def _fused_kernels_case(G, oracle, s, K, backward):
     """abl_bn_conv_fwd (Eq. 1-3, 9, 4 in one kernel) and abl_conv_dgrad_bn_reduce (Eq. 5 with the
     Eq. 7 sums in the epilogue) against the oracle's separate steps."""
