@@ -797,3 +797,35 @@ def test_average_pool_folded_into_linear(G, oracle, s, pool):
     a3t = np.maximum(o.recover_a2(saved), 0)
     dV = np.einsum("nhwc,nhwk->ck", pooled(a3t), dy.astype(np.float64))
     assert rel(dw.astype(np.float64).sum(axis=(0, 1)) / (pool * pool), dV) < TOL
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout", [
+    (1, 1, 1, 64, 16), (3, 5, 7, 128, 48), (2, 9, 9, 192, 96), (5, 6, 6, 256, 320), (1, 13, 11, 384, 64),
+    (2, 8, 8, 512, 272), (7, 3, 3, 1024, 128), (1, 40, 40, 64, 64), (4, 17, 5, 640, 192), (2, 5, 5, 320, 64)],
+    ids=lambda v: str(v))
+def test_pointwise_convolutions(G, oracle, N, H, W, Cin, Cout):
+    """1x1 stride-1 layers through the kernel that loads activations straight into MFMA layout:
+    contractions held whole in LDS (up to 256 channels) and in 128-channel chunks, one to four
+    16-channel tiles per wave, pixel counts that leave ragged tiles and idle blocks; 320 input
+    channels (a multiple of 64 but not of 128 beyond 256) fall back to the tiled kernel."""
+    o = oracle
+    s = LayerShape(N, H, W, Cin, Cout, 1, 1, 1, 0)
+    print("case pointwise", s.as_tuple(), flush=True)
+    x, w, gamma, beta, dy = synth.draw_layer(s, 17, "normal", "random")
+    a3 = np.maximum(x, np.float32(0))
+    skip = np.random.default_rng(3).standard_normal(G.out_shape(s)).astype(np.float32)
+    y_ref = o.conv_fwd(a3, w, oshape(o, s))
+    assert rel(G.run_conv_fwd(s, a3, w), y_ref) < TOL
+    assert rel(G.run_conv_fwd(s, a3, w, skip=skip), y_ref + skip) < TOL
+    assert rel(G.run_conv_dgrad(s, dy, w), o.conv_dgrad(dy, w, oshape(o, s))) < TOL
+    # the whole layer (fused prologue where the output has at most 256 channels; sums epilogues)
+    for K in (4, 8):
+        run = G.LayerRun(s, K)
+        y = run.forward(x, w, gamma, beta)
+        yl_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s))
+        assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+        assert rel(y, yl_ref) < TOL
+        dx, dw, dg, db = run.backward(dy, w)
+        dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+        assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+        assert rel(dg, dg_ref) < 5 * TOL and rel(db, db_ref) < 5 * TOL
