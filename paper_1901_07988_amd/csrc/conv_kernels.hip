@@ -416,19 +416,41 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   const int adv_h = adv_r / g.Wo, adv_w = adv_r - adv_h * g.Wo;
   const bool flat = g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0;  // input pixel = output pixel
   const bool a_lane_ok = (ci0 + a_cg * CPW) < g.Cin;
+  // Addresses advance by a constant per chunk: every tensor has fewer than 2^31 elements, so
+  // element offsets are 32-bit, computed once per pass and stepped (64-bit multiplies per load
+  // and chunk took as long to issue as half the chunk's MFMAs).
+  int b_off[B_PASSES];    // element offset in dy of this pass at the current chunk
+  int b_row[B_PASSES];    // its pixel row within the chunk, CH if the pass never loads
+#pragma unroll
+  for (int j = 0; j < B_PASSES; ++j) {
+    const int idx = tid + kThreads * j;
+    const int pl = idx / GB, c = co0 + 4 * (idx % GB);
+    const bool lane_ok = (CH * GB % kThreads == 0 || idx < CH * GB) && c < g.Cout;
+    b_row[j] = lane_ok ? pl : CH;
+    b_off[j] = (int)((p_begin + pl) * g.Cout + c);
+  }
+  int a_off[A_PASSES];    // word offset in `packed` for 1x1 stride-1 layers (pixel p itself)
+  int a_row[A_PASSES];
+#pragma unroll
+  for (int i = 0; i < A_PASSES; ++i) {
+    const int idx = tid + kThreads * i;
+    const bool lane_ok = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA);
+    a_row[i] = lane_ok ? idx / GA : CH;
+    a_off[i] = (int)(((p_begin + idx / GA) * g.Cin + ci0) / CPW) + a_cg;
+  }
+  const int b_step = CH * g.Cout, a_step = CH * g.Cin / CPW;
   auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
+    const int rem = (int)(p_end - pc < CH ? p_end - pc : CH);  // rows of this chunk inside the slice
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
-      const int idx = tid + kThreads * i;
-      const int64_t p = pc + idx / GA;
       // branch-free (a 1x1 stride-1 layer reads pixel p itself): a branch here would make the
       // compiler wait for the loads already in flight
       const int hi = a_ho[i] * g.stride + r - g.pad, wi = a_wo[i] * g.stride + s - g.pad;
       const bool inside = flat || (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W);
-      oka[i] = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA) && p < p_end && inside;
-      const int64_t pix = flat ? p : ((int64_t)a_n[i] * g.H + hi) * g.W + wi;
-      const int64_t e = oka[i] ? pix * g.Cin + ci0 : 0;
-      wa[i] = packed[e / CPW + (oka[i] ? a_cg : 0)];
+      oka[i] = a_row[i] < rem && inside;
+      const int word = flat ? a_off[i] : (((a_n[i] * g.H + hi) * g.W + wi) * g.Cin + ci0) / CPW + a_cg;
+      wa[i] = packed[oka[i] ? word : 0];
+      a_off[i] += a_step;
       // advance to the same slot of the next chunk
       a_wo[i] += adv_w;
       a_ho[i] += adv_h;
@@ -438,11 +460,9 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     }
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) {
-      const int idx = tid + kThreads * j;
-      const int pl = idx / GB, c = co0 + 4 * (idx % GB);
-      const int64_t p = pc + pl;
-      const bool ok = (CH * GB % kThreads == 0 || idx < CH * GB) && p < p_end && c < g.Cout;
-      rb[j] = *reinterpret_cast<const float4*>(dy + (ok ? p * g.Cout + c : 0));
+      const bool ok = b_row[j] < rem;
+      rb[j] = *reinterpret_cast<const float4*>(dy + (ok ? b_off[j] : 0));
+      b_off[j] += b_step;
       okb = ok ? (okb | (1u << j)) : (okb & ~(1u << j));
     }
   };
