@@ -474,14 +474,37 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   // not all saturated): code + off is then an exact integer, step / 2 is exact, and both forms
   // round the same exact product once.
   float step[CPW], off[CPW], half_step[CPW];
+  if constexpr (CPW % 4 == 0) {  // the thread's channels are CPW consecutive ones: 16-byte loads, all in flight at once
+    const bool ok = a_lane_ok;   // channel counts are multiples of 16 here, so a group is inside or outside as a whole
+    const int c = ok ? ci0 + a_cg * CPW : 0;
+    float4 st4[CPW / 4];
+    int4 fb4[CPW / 4];
 #pragma unroll
-  for (int v = 0; v < CPW; ++v) {
-    const int c = ci0 + a_cg * CPW + v;
-    const bool ok = K != 32 && c < g.Cin;
-    step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
-    const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
-    off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
-    half_step[v] = 0.5f * step[v];
+    for (int v = 0; v < CPW / 4; ++v) {
+      st4[v] = *reinterpret_cast<const float4*>(stats + P_STEP * g.Cin + c + 4 * v);
+      fb4[v] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * g.Cin + c + 4 * v);
+    }
+#pragma unroll
+    for (int v = 0; v < CPW / 4; ++v) {
+      const float sv[4] = {st4[v].x, st4[v].y, st4[v].z, st4[v].w};
+      const int32_t fv[4] = {fb4[v].x, fb4[v].y, fb4[v].z, fb4[v].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        step[4 * v + e] = ok ? sv[e] : 0.f;
+        off[4 * v + e] = (float)((ok ? fv[e] : 0) - (1 << (K % 32 - 1)));
+        half_step[4 * v + e] = 0.5f * step[4 * v + e];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int v = 0; v < CPW; ++v) {
+      const int c = ci0 + a_cg * CPW + v;
+      const bool ok = K != 32 && c < g.Cin;
+      step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
+      const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
+      off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
+      half_step[v] = 0.5f * step[v];
+    }
   }
 
   for (int64_t pc = p_begin; pc < p_end; pc += CH) {
