@@ -54,9 +54,11 @@ void bn_rstd(const T* var, int C, T eps, T* rstd) {
 }
 
 // ---- Eq. 1-3: normalise, scale & bias, ReLU ---------------------------------------
+// slope: 0 for the ReLU of Eq. 3; in (0, 1] the "leaky" ReLU that Sec. 3.4 admits (negative
+// inputs are scaled by `slope` instead of being zeroed; the gradient still depends on the sign only).
 template <typename T>
 void bn_relu(const T* x, int64_t M, int C, const T* mean, const T* rstd, const T* gamma,
-             const T* beta, T* a2, T* a3) {
+             const T* beta, T slope, T* a2, T* a3) {
 #pragma omp parallel for schedule(static)
   for (int64_t m = 0; m < M; ++m)
     for (int c = 0; c < C; ++c) {
@@ -65,7 +67,7 @@ void bn_relu(const T* x, int64_t M, int C, const T* mean, const T* rstd, const T
       const T g = gamma[c] * a1;
       const T v = g + beta[c];           // Eq. 2
       a2[m * C + c] = v;
-      a3[m * C + c] = v > (T)0 ? v : (T)0;  // Eq. 3
+      a3[m * C + c] = v > (T)0 ? v : (slope != (T)0 ? slope * v : (T)0);  // Eq. 3
     }
 }
 
@@ -206,13 +208,13 @@ void conv_wgrad(const T* a3, const T* dy, int N, int H, int W, int Cin, int Cout
 // copy a2t of the pre-ReLU activation.  A1 is rebuilt by inverting Eq. 2.
 template <typename T>
 void bn_relu_bwd(const T* a2t, const T* da3, int64_t M, int C, const T* rstd, const T* gamma,
-                 const T* beta, T* dx, T* dgamma, T* dbeta) {
+                 const T* beta, T slope, T* dx, T* dgamma, T* dbeta) {
 #pragma omp parallel for schedule(static)
   for (int c = 0; c < C; ++c) {
     double sum_da2 = 0.0, sum_a1_da2 = 0.0, sum_da1 = 0.0, sum_a1_da1 = 0.0;
     for (int64_t m = 0; m < M; ++m) {
       const T v = a2t[m * C + c];
-      const T da2 = v > (T)0 ? da3[m * C + c] : (T)0;  // Eq. 6
+      const T da2 = v > (T)0 ? da3[m * C + c] : (slope != (T)0 ? slope * da3[m * C + c] : (T)0);  // Eq. 6
       const T a1 = (v - beta[c]) / gamma[c];          // inverse of Eq. 2
       const T da1 = gamma[c] * da2;                   // Eq. 7
       sum_da2 += (double)da2;
@@ -226,7 +228,7 @@ void bn_relu_bwd(const T* a2t, const T* da3, int64_t M, int C, const T* rstd, co
     const T mean_a1_da1 = (T)(sum_a1_da1 / (double)M);
     for (int64_t m = 0; m < M; ++m) {
       const T v = a2t[m * C + c];
-      const T da2 = v > (T)0 ? da3[m * C + c] : (T)0;
+      const T da2 = v > (T)0 ? da3[m * C + c] : (slope != (T)0 ? slope * da3[m * C + c] : (T)0);
       const T a1 = (v - beta[c]) / gamma[c];
       const T da1 = gamma[c] * da2;
       const T t1 = da1 - mean_da1;
@@ -270,8 +272,8 @@ void unpack_codes(const uint8_t* in, int64_t E, int K, int32_t* q) {
     bn_rstd<T>(var, C, eps, rstd);                                                                 \
   }                                                                                                \
   extern "C" void orc_bn_relu_##SUF(const T* x, int64_t M, int C, const T* mean, const T* rstd,    \
-                                    const T* gamma, const T* beta, T* a2, T* a3) {                 \
-    bn_relu<T>(x, M, C, mean, rstd, gamma, beta, a2, a3);                                          \
+                                    const T* gamma, const T* beta, T slope, T* a2, T* a3) {        \
+    bn_relu<T>(x, M, C, mean, rstd, gamma, beta, slope, a2, a3);                                   \
   }                                                                                                \
   extern "C" void orc_quant_consts_##SUF(const T* gamma, const T* beta, int C, int K, T* cq,       \
                                          T* step, int32_t* fb) {                                   \
@@ -298,9 +300,9 @@ void unpack_codes(const uint8_t* in, int64_t E, int K, int32_t* q) {
     conv_wgrad<T>(a3, dy, N, H, W, Cin, Cout, R, S, st, pad, dw);                                  \
   }                                                                                                \
   extern "C" void orc_bn_relu_bwd_##SUF(const T* a2t, const T* da3, int64_t M, int C,              \
-                                        const T* rstd, const T* gamma, const T* beta, T* dx,       \
-                                        T* dgamma, T* dbeta) {                                     \
-    bn_relu_bwd<T>(a2t, da3, M, C, rstd, gamma, beta, dx, dgamma, dbeta);                          \
+                                        const T* rstd, const T* gamma, const T* beta, T slope,     \
+                                        T* dx, T* dgamma, T* dbeta) {                              \
+    bn_relu_bwd<T>(a2t, da3, M, C, rstd, gamma, beta, slope, dx, dgamma, dbeta);                   \
   }
 
 ORC_INSTANTIATE(float, f32)

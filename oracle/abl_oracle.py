@@ -119,9 +119,9 @@ def bn_rstd(var, eps=EPS, dtype=np.float32):
     return rstd
 
 
-def bn_relu(x, mean, rstd, gamma, beta, dtype=np.float32):
-    """Eq. 1-3: returns (A2, A3)."""
-    suf, _ = _suf(dtype)
+def bn_relu(x, mean, rstd, gamma, beta, dtype=np.float32, slope=0.0):
+    """Eq. 1-3: returns (A2, A3).  ``slope`` > 0: leaky ReLU (Sec. 3.4), A3 = slope * A2 where A2 <= 0."""
+    suf, ct = _suf(dtype)
     x = _c(x, dtype)
     C = x.shape[-1]
     M = x.size // C
@@ -129,7 +129,7 @@ def bn_relu(x, mean, rstd, gamma, beta, dtype=np.float32):
     a3 = np.empty_like(x)
     getattr(_L(), f"orc_bn_relu_{suf}")(_p(x), ctypes.c_int64(M), C, _p(_c(mean, dtype)),
                                         _p(_c(rstd, dtype)), _p(_c(gamma, dtype)),
-                                        _p(_c(beta, dtype)), _p(a2), _p(a3))
+                                        _p(_c(beta, dtype)), ct(np.dtype(dtype).type(slope)), _p(a2), _p(a3))
     return a2, a3
 
 
@@ -230,9 +230,10 @@ def conv_wgrad(a3, dy, s: Shape, dtype=np.float32):
     return dw
 
 
-def bn_relu_bwd(a2t, da3, rstd, gamma, beta, dtype=np.float32):
-    """Eq. 6-8 from a (possibly approximate) copy of A2: returns (dx, dgamma, dbeta)."""
-    suf, _ = _suf(dtype)
+def bn_relu_bwd(a2t, da3, rstd, gamma, beta, dtype=np.float32, slope=0.0):
+    """Eq. 6-8 from a (possibly approximate) copy of A2: returns (dx, dgamma, dbeta).
+    ``slope`` > 0: leaky ReLU, dA2 = slope * dA3 where the copy of A2 is <= 0."""
+    suf, ct = _suf(dtype)
     a2t = _c(a2t, dtype)
     da3 = _c(da3, dtype)
     C = a2t.shape[-1]
@@ -242,7 +243,8 @@ def bn_relu_bwd(a2t, da3, rstd, gamma, beta, dtype=np.float32):
     db = np.empty(C, dtype)
     getattr(_L(), f"orc_bn_relu_bwd_{suf}")(_p(a2t), _p(da3), ctypes.c_int64(M), C,
                                             _p(_c(rstd, dtype)), _p(_c(gamma, dtype)),
-                                            _p(_c(beta, dtype)), _p(dx), _p(dg), _p(db))
+                                            _p(_c(beta, dtype)), ct(np.dtype(dtype).type(slope)),
+                                            _p(dx), _p(dg), _p(db))
     return dx, dg, db
 
 
@@ -260,6 +262,7 @@ class Saved:
     rstd: np.ndarray
     gamma: np.ndarray
     beta: np.ndarray
+    slope: float = 0.0  # 0: ReLU; > 0: leaky ReLU (Sec. 3.4)
 
     @property
     def nbytes(self):
@@ -267,7 +270,7 @@ class Saved:
 
 
 def layer_forward(x, w, gamma, beta, K, s: Shape, skip=None, dtype=np.float32, eps=EPS,
-                  stats=None, keep=False, naive=False):
+                  stats=None, keep=False, naive=False, slope=0.0):
     """Forward of one pre-activation layer.  The output never sees the codes: it is computed
     from the full-precision A3 (Sec. 3.2), so it is the same for every K.
 
@@ -277,11 +280,16 @@ def layer_forward(x, w, gamma, beta, K, s: Shape, skip=None, dtype=np.float32, e
 
     ``naive``: the comparison baseline of Sec. 4 - the convolution consumes the ReLU of the
     dequantized copy instead of the exact A3, so the approximation also enters the forward pass.
+
+    ``slope`` > 0: the non-linearity is a leaky ReLU (Sec. 3.4 admits any whose gradient depends
+    on the sign of the activation only); what is stored is unchanged - the K-bit copy of A2.
     """
     x = _c(x, dtype)
     mean, var = bn_stats(x, dtype) if stats is None else (_c(stats[0], dtype), _c(stats[1], dtype))
     rstd = bn_rstd(var, eps, dtype)
-    a2, a3 = bn_relu(x, mean, rstd, gamma, beta, dtype)
+    if naive and slope != 0.0:
+        raise ValueError("the naive baseline is defined for the plain ReLU only")
+    a2, a3 = bn_relu(x, mean, rstd, gamma, beta, dtype, slope)
     if K == 32:
         store, q = a2.copy(), None
     else:
@@ -292,7 +300,7 @@ def layer_forward(x, w, gamma, beta, K, s: Shape, skip=None, dtype=np.float32, e
     y = conv_fwd(a3, w, s, dtype)
     if skip is not None:
         y = y + _c(skip, dtype)
-    saved = Saved(K, s, store, mean, var, rstd, _c(gamma, dtype).copy(), _c(beta, dtype).copy())
+    saved = Saved(K, s, store, mean, var, rstd, _c(gamma, dtype).copy(), _c(beta, dtype).copy(), float(slope))
     if keep:
         return y, saved, dict(a2=a2, a3=a3, q=q)
     return y, saved
@@ -312,10 +320,13 @@ def layer_backward(saved: Saved, dy, w, dtype=np.float32, keep=False):
     Returns (dx, dW, dgamma, dbeta)."""
     s = saved.shape
     a2t = recover_a2(saved, dtype)
-    a3t = np.maximum(a2t, np.dtype(dtype).type(0))      # Eq. 3 on the approximate copy
+    if saved.slope == 0.0:
+        a3t = np.maximum(a2t, np.dtype(dtype).type(0))  # Eq. 3 on the approximate copy
+    else:                                               # ... or its leaky version (Sec. 3.4)
+        a3t = np.where(a2t > 0, a2t, np.dtype(dtype).type(saved.slope) * a2t).astype(dtype)
     dw = conv_wgrad(a3t, dy, s, dtype)                  # Eq. 5, approximate
     da3 = conv_dgrad(dy, w, s, dtype)                   # Eq. 5, exact
-    dx, dg, db = bn_relu_bwd(a2t, da3, saved.rstd, saved.gamma, saved.beta, dtype)
+    dx, dg, db = bn_relu_bwd(a2t, da3, saved.rstd, saved.gamma, saved.beta, dtype, saved.slope)
     if keep:
         return dx, dw, dg, db, dict(a2t=a2t, a3t=a3t, da3=da3)
     return dx, dw, dg, db

@@ -608,3 +608,96 @@ def test_sgd_momentum_closed_forms(oracle):
                               np.float64)
     assert w32.dtype == np.float32 and v32.dtype == np.float32
     assert np.allclose(w32, w64, rtol=1e-6, atol=1e-7) and np.allclose(v32, v64, rtol=1e-6, atol=1e-7)
+
+
+# ------------------------------------------------------------------ leaky ReLU (Sec. 3.4)
+@pytest.mark.parametrize("shape_t", FD_SHAPES[:3])
+@pytest.mark.parametrize("slope", [0.1, 0.3])
+def test_leaky_layer_matches_torch_autograd_and_finite_differences(oracle, shape_t, slope):
+    """With a leaky ReLU the exact layer is batch_norm -> leaky_relu -> conv2d: outputs and the
+    four gradients against PyTorch's CPU autograd in double, and dgamma / dbeta / a sample of dx
+    and dW against central differences of L = sum(y * dy)."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _rand_layer(o, shape_t, 23)
+    f64 = np.float64
+    y, saved = o.layer_forward(x, w, gamma, beta, 32, s, dtype=f64, slope=slope)
+    dx, dw, dg, db = o.layer_backward(saved, dy, w, dtype=f64)
+
+    xt = torch.tensor(x).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    wt = torch.tensor(w).permute(3, 2, 0, 1).contiguous().requires_grad_(True)
+    gt = torch.tensor(gamma).requires_grad_(True)
+    bt = torch.tensor(beta).requires_grad_(True)
+    a2 = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=float(np.float64(o.EPS)))
+    yt = torch.nn.functional.conv2d(torch.nn.functional.leaky_relu(a2, slope), wt, stride=s.stride, padding=s.pad)
+    yt.backward(torch.tensor(dy).permute(0, 3, 1, 2))
+    tol = dict(rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy(), **tol)
+    np.testing.assert_allclose(dw, wt.grad.permute(2, 3, 1, 0).numpy(), **tol)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), **tol)
+    np.testing.assert_allclose(db, bt.grad.numpy(), **tol)
+
+    def loss(x_, w_, g_, b_):
+        return float(np.sum(o.layer_forward(x_, w_, g_, b_, 32, s, dtype=f64, slope=slope)[0] * dy))
+
+    h = 1e-6
+    args = [x, w, gamma, beta]
+    rng = np.random.default_rng(5)
+    for idx, (name, grad) in enumerate([("dx", dx), ("dW", dw), ("dgamma", dg), ("dbeta", db)]):
+        flat = args[idx].reshape(-1)
+        picks = rng.choice(flat.size, size=min(flat.size, 12), replace=False)
+        for i in picks:
+            keep = flat[i]
+            flat[i] = keep + h
+            lp = loss(*args)
+            flat[i] = keep - h
+            lm = loss(*args)
+            flat[i] = keep
+            num = (lp - lm) / (2 * h)
+            assert abs(num - grad.reshape(-1)[i]) < 2e-6 * max(np.max(np.abs(grad)), 1.0), (name, i)
+
+
+@pytest.mark.parametrize("K", [4, 8])
+def test_leaky_layer_is_a_blend_of_the_relu_and_the_linear_layer(oracle, K):
+    """leaky(v) = s * v + (1 - s) * relu(v), and Eq. 4-8 are linear in A3 and in dA2: the output
+    and every gradient of the leaky layer are that blend of the ReLU layer (slope 0, pinned above)
+    and of the layer without a non-linearity (slope 1).  Holds for the approximate path too,
+    because what is stored - the K-bit codes of A2 - does not depend on the slope."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _rand_layer(o, (3, 6, 5, 4, 3, 3, 3, 1, 1), 31)
+    f64 = np.float64
+    sl = 0.2
+    outs = {}
+    for slope in (0.0, 1.0, sl):
+        y, saved = o.layer_forward(x, w, gamma, beta, K, s, dtype=f64, slope=slope)
+        outs[slope] = (y, saved.store.copy()) + tuple(o.layer_backward(saved, dy, w, dtype=f64))
+    assert outs[0.0][1].tobytes() == outs[sl][1].tobytes() == outs[1.0][1].tobytes()
+    for i in (0, 2, 3, 4, 5):
+        blend = sl * outs[1.0][i] + (1 - sl) * outs[0.0][i]
+        np.testing.assert_allclose(outs[sl][i], blend, rtol=1e-10, atol=1e-11)
+    # slope 1: no non-linearity at all - A3 = A2, and the sign of the stored copy plays no part
+    a2, a3 = o.bn_relu(x, *(lambda m, v: (m, o.bn_rstd(v, dtype=f64)))(*o.bn_stats(x, f64)), gamma, beta, f64, slope=1.0)
+    assert np.array_equal(a2, a3)
+
+
+def test_leaky_sign_is_preserved_so_dgrad_path_stays_exact(oracle):
+    """Sec. 3.3 with a leaky ReLU: dbeta is still exact, because Eq. 6 needs the sign of A2 only and
+    the codes keep it (up to the one exception: A2 in (-step, 0] is reconstructed positive)."""
+    o = oracle
+    s, x, w, gamma, beta, dy = _rand_layer(o, (4, 6, 6, 3, 4, 3, 3, 1, 1), 41)
+    f64 = np.float64
+    slope = 0.25
+    _, exact = o.layer_forward(x, w, gamma, beta, 32, s, dtype=f64, slope=slope)
+    _, approx = o.layer_forward(x, w, gamma, beta, 8, s, dtype=f64, slope=slope)
+    a2 = exact.store
+    a2t = o.recover_a2(approx, f64)
+    flips = (a2 > 0) != (a2t > 0)
+    step = 6 * gamma / 256
+    assert np.all((a2[flips] <= 0) & (a2[flips] > -np.broadcast_to(step, a2.shape)[flips]))
+    ge = o.layer_backward(exact, dy, w, dtype=f64)
+    *ga, inter = o.layer_backward(approx, dy, w, dtype=f64, keep=True)
+    # dbeta differs by exactly the flipped elements' (1 - slope) * dA3, and by nothing else
+    extra = np.where(flips, (1 - slope) * inter["da3"], 0.0).reshape(-1, s.Cin).sum(axis=0)
+    np.testing.assert_allclose(ga[3] - ge[3], extra, rtol=1e-9, atol=1e-11)
+    assert np.max(np.abs(ga[1] - ge[1])) > 0                                # dW is approximate
+    assert np.max(np.abs(ga[1] - ge[1])) < 0.15 * np.max(np.abs(ge[1]))
