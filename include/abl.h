@@ -119,6 +119,24 @@ int abl_backward(void* stream, const abl_shape* shape, int K, uint32_t flags,
                  void* scratch, size_t scratch_bytes,
                  float* dx, float* dW, float* dgamma, float* dbeta);
 
+/* The same layer with a leaky ReLU in place of Eq. 3 (Sec. 3.4: the method carries over to
+ * non-linearities whose gradient depends on the sign of the activation only):
+ * A3 = A2 where A2 > 0, slope * A2 elsewhere; Eq. 6 becomes dA2 = dA3 resp. slope * dA3, taken
+ * from the sign of the dequantized copy (Eq. 10), and the weight gradient contracts the leaky
+ * ReLU of that copy.  What is stored is unchanged (the K-bit codes of A2, Eq. 9), so packed,
+ * stats and scratch have the sizes of abl_forward / abl_backward and all arguments the same
+ * meaning, layout and aliasing rules.  slope in [0, 1] (0 = the ReLU; else ABL_ERR_ARG); the
+ * backward must be given the slope of the forward.  These calls run the unfused stages.
+ * flags: ABL_MATH_BF16; backward also ABL_ACCUM_DX. */
+int abl_leaky_forward(void* stream, const abl_shape* shape, int K, uint32_t flags, float slope,
+                      const float* x, const float* W, const float* gamma, const float* beta,
+                      const float* skip, void* scratch, size_t scratch_bytes,
+                      float* y, void* packed, void* stats);
+int abl_leaky_backward(void* stream, const abl_shape* shape, int K, uint32_t flags, float slope,
+                       const void* packed, const void* stats, const float* dy, const float* W,
+                       void* scratch, size_t scratch_bytes,
+                       float* dx, float* dW, float* dgamma, float* dbeta);
+
 /* ---- stage-level entry points (the steps the two calls above are made of) ---- */
 
 /* Eq. 1 statistics of x [M,C] and the per-channel constants of Eq. 9/10 -> stats.

@@ -54,6 +54,10 @@ _SIGS = {
     "abl_wgrad_scratch_bytes": (_sz, [_shp]),
     "abl_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "abl_backward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp, _vp]),
+    "abl_leaky_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
+                                         _sz, _vp, _vp, _vp]),
+    "abl_leaky_backward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _sz,
+                                          _vp, _vp, _vp, _vp]),
     "abl_bn_stats": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp, ctypes.c_int, _vp, _sz, _vp]),
     "abl_bn_relu_pack": (ctypes.c_int, [_vp, _vp, _i64, _i32, ctypes.c_int, _vp, _vp, _vp]),
     "abl_pack": (ctypes.c_int, [_vp, _vp, _i64, _i32, ctypes.c_int, _vp, _vp]),
@@ -149,6 +153,20 @@ def abl_backward(shape, K, packed, stats, dy, W, scratch, dx, dW, dgamma, dbeta,
     _check(lib.abl_backward(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy), _ptr(W),
                             _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dx), _ptr(dW),
                             _ptr(dgamma), _ptr(dbeta)), "abl_backward")
+
+
+def abl_leaky_forward(shape, K, slope, x, W, gamma, beta, skip, scratch, y, packed, stats, flags=0):
+    s = shape_struct(shape)
+    _check(lib.abl_leaky_forward(_stream(), ctypes.byref(s), K, flags, slope, _ptr(x), _ptr(W), _ptr(gamma),
+                                 _ptr(beta), _ptr(skip), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                 _ptr(y), _ptr(packed), _ptr(stats)), "abl_leaky_forward")
+
+
+def abl_leaky_backward(shape, K, slope, packed, stats, dy, W, scratch, dx, dW, dgamma, dbeta, flags=0):
+    s = shape_struct(shape)
+    _check(lib.abl_leaky_backward(_stream(), ctypes.byref(s), K, flags, slope, _ptr(packed), _ptr(stats), _ptr(dy),
+                                  _ptr(W), _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dx),
+                                  _ptr(dW), _ptr(dgamma), _ptr(dbeta)), "abl_leaky_backward")
 
 
 # ---- fused kernels -------------------------------------------------------------------------------

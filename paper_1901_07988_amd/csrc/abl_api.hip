@@ -296,6 +296,60 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
                        dwsum.copies > 0 ? &dwsum : nullptr);
 }
 
+// ---- the layer with a leaky ReLU (Sec. 3.4) ---------------------------------------------------
+// Same stages as above with the slope passed to the element-wise kernels.  The contraction
+// kernels know the plain ReLU only, so the backward first rebuilds A3~ = leaky(Eq. 10) in the
+// workspace and hands it to the weight gradient as a full-precision operand; dA3 then takes
+// its place.
+
+static int check_slope(float slope) { return (slope >= 0.0f && slope <= 1.0f) ? ABL_OK : ABL_ERR_ARG; }
+
+int abl_leaky_forward(void* stream, const abl_shape* s, int K, uint32_t flags, float slope, const float* x,
+                      const float* W, const float* gamma, const float* beta, const float* skip, void* scratch,
+                      size_t scratch_bytes, float* y, void* packed, void* stats) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (int e = check_slope(slope)) return e;
+  if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
+  if (bad_ptr(x) || bad_ptr(W) || bad_ptr(gamma) || bad_ptr(beta) || bad_ptr(scratch) || bad_ptr(y) ||
+      bad_ptr(packed) || bad_ptr(stats) || (skip != nullptr && !aligned16(skip)))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t M = rows_of(*s);
+  float* a3 = static_cast<float*>(scratch);
+  void* red = static_cast<char*>(scratch) + up256((size_t)M * s->Cin * sizeof(float));
+  if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
+  if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, false, slope)) return e;
+  return launch_conv_fwd(st, *s, (flags & ABL_MATH_BF16) != 0, a3, W, skip, y);
+}
+
+int abl_leaky_backward(void* stream, const abl_shape* s, int K, uint32_t flags, float slope, const void* packed,
+                       const void* stats, const float* dy, const float* W, void* scratch, size_t scratch_bytes,
+                       float* dx, float* dW, float* dgamma, float* dbeta) {
+  if (int e = check_shape(s)) return e;
+  if (int e = check_k(K)) return e;
+  if (int e = check_slope(slope)) return e;
+  if (flags & ~(uint32_t)(ABL_ACCUM_DX | ABL_MATH_BF16)) return ABL_ERR_ARG;
+  if (bad_ptr(packed) || bad_ptr(stats) || bad_ptr(dy) || bad_ptr(W) || bad_ptr(scratch) || bad_ptr(dx) ||
+      bad_ptr(dW) || bad_ptr(dgamma) || bad_ptr(dbeta))
+    return ABL_ERR_ARG;
+  if (scratch_bytes < abl_scratch_bytes(s, K)) return ABL_ERR_SCRATCH;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t M = rows_of(*s);
+  const size_t act = up256((size_t)M * s->Cin * sizeof(float));
+  float* buf = static_cast<float*>(scratch);  // A3~, then dA3
+  void* red = static_cast<char*>(scratch) + act;
+  void* wpart = static_cast<char*>(scratch) + act + up256(bn_partial_bytes(M, s->Cin));
+  const bool bf16 = (flags & ABL_MATH_BF16) != 0;
+  if (int e = launch_unpack(st, packed, M, s->Cin, K, stats, buf, true, slope)) return e;
+  DwSum dwsum;
+  if (int e = launch_conv_wgrad_packed(st, *s, 32, bf16, buf, stats, dy, wpart, dW, false, &dwsum)) return e;
+  if (int e = launch_conv_dgrad(st, *s, bf16, dy, W, buf)) return e;
+  return launch_bn_bwd(st, packed, stats, buf, M, s->Cin, K, (flags & ABL_ACCUM_DX) != 0, red, dx, dgamma, dbeta,
+                       dwsum.copies > 0 ? &dwsum : nullptr, slope);
+}
+
 // ---- the two fused kernels of the layer step, callable on their own --------------------------
 
 int abl_bn_conv_fwd(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const void* stats,

@@ -21,12 +21,14 @@ size_t bn_partial_bytes(int64_t M, int C);
 int launch_bn_stats(hipStream_t st, const float* x, int64_t M, int C, const float* gamma,
                     const float* beta, int K, void* scratch, void* stats);
 // naive: a3 = ReLU of the dequantized code instead of the exact A3 (the baseline of Sec. 4).
+// slope: 0 = ReLU (Eq. 3); > 0 = leaky ReLU (Sec. 3.4), in every launcher below that takes one.
 int launch_bn_relu_pack(hipStream_t st, const float* x, int64_t M, int C, int K, const void* stats,
-                        float* a3, void* packed, bool naive = false);
+                        float* a3, void* packed, bool naive = false, float slope = 0.0f);
 int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const void* stats,
                 void* packed);
+// act: apply the non-linearity to the dequantized values (the A3~ the weight gradient contracts).
 int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, const void* stats,
-                  float* a2t);
+                  float* a2t, bool act = false, float slope = 0.0f);
 // The second halves of the two reductions, for partial sums produced elsewhere (conv epilogues).
 size_t bn_means_offset(int C);
 int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, const float* shift_row, int64_t M,
@@ -44,10 +46,10 @@ int launch_sgd_momentum(hipStream_t st, int64_t n, float lr, float mu, float wd,
 // Backward of BN + ReLU from dA3 and the codes (Eq. 6-8): both passes.
 int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                   int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta,
-                  const DwSum* dwsum = nullptr);
+                  const DwSum* dwsum = nullptr, float slope = 0.0f);
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
-                         float* dbeta, const DwSum* dwsum = nullptr);
+                         float* dbeta, const DwSum* dwsum = nullptr, float slope = 0.0f);
 
 // Convolution geometry passed to the kernels by value.
 struct ConvGeom {

@@ -262,9 +262,11 @@ template <int K, int VEC, int MODE, bool STREAM>
 __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __restrict__ in, int64_t M, int C,
                                                               RowGeom g, const float* __restrict__ stats,
                                                               float* __restrict__ a3,
-                                                              void* __restrict__ packed, int pad_bytes) {
+                                                              void* __restrict__ packed, int pad_bytes,
+                                                              float slope) {
   using word_t = typename PackedWord<K, VEC>::type;
   const ThreadPos p = thread_pos<VEC>(g);
+  const bool leaky = slope != 0.0f;
   if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < pad_bytes)  // zero the 128-byte row tail
     reinterpret_cast<uint8_t*>(packed)[(M * C * K) / 8 + threadIdx.x] = 0;
   if (!p.active) return;
@@ -303,7 +305,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
             const float a1 = d * rstd[v];   // Eq. 1
             const float t = gm[v] * a1;
             a2 = t + bt[v];                 // Eq. 2
-            out[v] = a2 > 0.0f ? a2 : 0.0f; // Eq. 3
+            out[v] = a2 > 0.0f ? a2 : (leaky ? slope * a2 : 0.0f);  // Eq. 3 (leaky: Sec. 3.4)
           } else {
             a2 = xv[j][v];
           }
@@ -316,11 +318,11 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
   }
 }
 
-// Eq. 10: codes -> fp32.
+// Eq. 10: codes -> fp32; with `act` the non-linearity on top (negative values times `slope`).
 template <int K, int VEC, bool STREAM>
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict__ packed, int64_t M, int C,
                                                           RowGeom g, const float* __restrict__ stats,
-                                                          float* __restrict__ a2t) {
+                                                          float* __restrict__ a2t, int act, float slope) {
   using word_t = typename PackedWord<K, VEC>::type;
   const ThreadPos p = thread_pos<VEC>(g);
   if (!p.active) return;
@@ -345,8 +347,10 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict
         const int64_t r = row0 + (int64_t)(i + j) * g.TY;
         float out[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v)
-          out[v] = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+        for (int v = 0; v < VEC; ++v) {
+          const float a = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          out[v] = (act == 0 || a > 0.0f) ? a : slope * a;  // act: Eq. 3 (slope 0) or its leaky version
+        }
         store_vec<VEC, STREAM>(a2t + r * C + p.c0, out);
       }
   }
@@ -358,10 +362,11 @@ template <int K, int VEC>
 __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __restrict__ packed,
                                                               const float* __restrict__ da3, int64_t M, int C,
                                                               RowGeom g, const float* __restrict__ stats,
-                                                              double* __restrict__ partial) {
+                                                              double* __restrict__ partial, float slope) {
   using word_t = typename PackedWord<K, VEC>::type;
   __shared__ double red[2 * VEC][kThreads];  // [value][thread]: conflict-free
   const ThreadPos p = thread_pos<VEC>(g);
+  const bool leaky = slope != 0.0f;
   float step[VEC], bt[VEC], ig[VEC];
   int32_t fb[VEC];
   load_vec<VEC>(stats + P_STEP * C + p.c0, step);
@@ -394,7 +399,7 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
           const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
-          const float da2 = a2t > 0.0f ? gv[j][v] : 0.0f;  // Eq. 6
+          const float da2 = a2t > 0.0f ? gv[j][v] : (leaky ? slope * gv[j][v] : 0.0f);  // Eq. 6
           const float a1t = (a2t - bt[v]) * ig[v];          // inverse of Eq. 2
           s1[v] += (double)da2;
           s2[v] += (double)a1t * (double)da2;
@@ -494,10 +499,12 @@ template <int K, int VEC, bool ACCUM, bool STREAM>
 __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restrict__ packed,
                                                              const float* da3, int64_t M, int C, RowGeom g,
                                                              const float* __restrict__ stats,
-                                                             const float* __restrict__ means, float* dx) {
+                                                             const float* __restrict__ means, float* dx,
+                                                             float slope) {
   using word_t = typename PackedWord<K, VEC>::type;
   const ThreadPos p = thread_pos<VEC>(g);
   if (!p.active) return;
+  const bool leaky = slope != 0.0f;
   float step[VEC], bt[VEC], gm[VEC], ig[VEC], rstd[VEC], m1[VEC], m2[VEC];
   int32_t fb[VEC];
   load_vec<VEC>(stats + P_STEP * C + p.c0, step);
@@ -532,7 +539,7 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
           const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
-          const float da2 = a2t > 0.0f ? gv[j][v] : 0.0f;  // Eq. 6
+          const float da2 = a2t > 0.0f ? gv[j][v] : (leaky ? slope * gv[j][v] : 0.0f);  // Eq. 6
           const float a1t = (a2t - bt[v]) * ig[v];
           const float da1 = gm[v] * da2;                    // Eq. 7
           const float t = (da1 - m1[v]) - a1t * m2[v];
@@ -552,7 +559,8 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
                                                                    int C, int64_t packed_bytes,
                                                                    const float* __restrict__ stats,
                                                                    float* __restrict__ a3,
-                                                                   uint8_t* __restrict__ packed, int naive) {
+                                                                   uint8_t* __restrict__ packed, int naive,
+                                                                   float slope) {
   const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t e0 = t * 8;
   if (e0 * K / 8 >= packed_bytes) return;
@@ -570,7 +578,7 @@ __global__ __launch_bounds__(kThreads) void flat_quant_pack_kernel(const float* 
         const float a1 = d * stats[P_RSTD * C + c];
         const float g = stats[P_GAMMA * C + c] * a1;
         a2 = g + stats[P_BETA * C + c];
-        a3[e] = a2 > 0.0f ? a2 : 0.0f;
+        a3[e] = a2 > 0.0f ? a2 : (slope != 0.0f ? slope * a2 : 0.0f);
       }
       codes[i] = quant_code<K>(a2, stats[P_CQ * C + c], fbp[c]);
       if constexpr (MODE == 0) {
@@ -603,12 +611,13 @@ __device__ inline uint32_t flat_code(const uint8_t* __restrict__ packed, int64_t
 template <int K>
 __global__ __launch_bounds__(kThreads) void flat_unpack_kernel(const uint8_t* __restrict__ packed, int64_t E,
                                                                int C, const float* __restrict__ stats,
-                                                               float* __restrict__ a2t) {
+                                                               float* __restrict__ a2t, int act, float slope) {
   const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (e >= E) return;
   const int c = (int)(e % C);
-  a2t[e] = dequant<K>(flat_code<K>(packed, e), stats[P_STEP * C + c],
-                      reinterpret_cast<const int32_t*>(stats)[P_FB * C + c]);
+  const float a = dequant<K>(flat_code<K>(packed, e), stats[P_STEP * C + c],
+                             reinterpret_cast<const int32_t*>(stats)[P_FB * C + c]);
+  a2t[e] = (act == 0 || a > 0.0f) ? a : slope * a;
 }
 
 // Reduce pass for any C: one thread per channel per block pass (VEC = 1 geometry).
@@ -617,7 +626,7 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_reduce_kernel(const uint8_t
                                                                    const float* __restrict__ da3, int64_t M,
                                                                    int C, RowGeom g,
                                                                    const float* __restrict__ stats,
-                                                                   double* __restrict__ partial) {
+                                                                   double* __restrict__ partial, float slope) {
   __shared__ double red[2][kThreads];
   const ThreadPos p = thread_pos<1>(g);
   const int c = p.c0;
@@ -631,7 +640,7 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_reduce_kernel(const uint8_t
     if (p.active && r < M) {
       const int64_t e = r * C + c;
       const float a2t = dequant<K>(flat_code<K>(packed, e), step, fb);
-      const float da2 = a2t > 0.0f ? da3[e] : 0.0f;
+      const float da2 = a2t > 0.0f ? da3[e] : (slope != 0.0f ? slope * da3[e] : 0.0f);
       const float a1t = (a2t - bt) * ig;
       s1 += (double)da2;
       s2 += (double)a1t * (double)da2;
@@ -659,14 +668,15 @@ template <int K, bool ACCUM>
 __global__ __launch_bounds__(kThreads) void flat_bwd_apply_kernel(const uint8_t* __restrict__ packed,
                                                                   const float* da3, int64_t E, int C,
                                                                   const float* __restrict__ stats,
-                                                                  const float* __restrict__ means, float* dx) {
+                                                                  const float* __restrict__ means, float* dx,
+                                                                  float slope) {
   const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (e >= E) return;
   const int c = (int)(e % C);
   const float gm = stats[P_GAMMA * C + c];
   const float a2t = dequant<K>(flat_code<K>(packed, e), stats[P_STEP * C + c],
                                reinterpret_cast<const int32_t*>(stats)[P_FB * C + c]);
-  const float da2 = a2t > 0.0f ? da3[e] : 0.0f;
+  const float da2 = a2t > 0.0f ? da3[e] : (slope != 0.0f ? slope * da3[e] : 0.0f);
   const float a1t = (a2t - stats[P_BETA * C + c]) * (1.0f / gm);
   const float da1 = gm * da2;
   const float t = (da1 - means[c]) - a1t * means[C + c];
@@ -721,7 +731,7 @@ int launch_bn_stats_finalize(hipStream_t st, const double* partial, int nb, cons
 
 template <int MODE>
 static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, int K, const void* stats,
-                             float* a3, void* packed, bool naive = false) {
+                             float* a3, void* packed, bool naive = false, float slope = 0.0f) {
   const float* sp = static_cast<const float*>(stats);
   const int64_t E = M * C;
   const int64_t raw = (E * K + 7) / 8;
@@ -733,11 +743,11 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
     const unsigned blocks = (unsigned)((threads + kThreads - 1) / kThreads);
     uint8_t* pk = static_cast<uint8_t*>(packed);
     if (K == 4)
-      flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
+      flat_quant_pack_kernel<4, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv, slope);
     else if (K == 8)
-      flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
+      flat_quant_pack_kernel<8, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv, slope);
     else
-      flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv);
+      flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv, slope);
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
@@ -746,9 +756,9 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
 #define ABL_QP(KK, VV)                                                                                   \
   do {                                                                                                   \
     if (stream)                                                                                          \
-      quant_pack_kernel<KK, VV, MODE, true><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad);  \
+      quant_pack_kernel<KK, VV, MODE, true><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope);  \
     else                                                                                                 \
-      quant_pack_kernel<KK, VV, MODE, false><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad); \
+      quant_pack_kernel<KK, VV, MODE, false><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope); \
   } while (0)
   if (K == 4 && vec == 8) ABL_QP(4, 8);
   else if (K == 4) ABL_QP(4, 4);
@@ -758,8 +768,8 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
 }
 
 int launch_bn_relu_pack(hipStream_t st, const float* x, int64_t M, int C, int K, const void* stats,
-                        float* a3, void* packed, bool naive) {
-  return launch_quant_pack<0>(st, x, M, C, K, stats, a3, packed, naive);
+                        float* a3, void* packed, bool naive, float slope) {
+  return launch_quant_pack<0>(st, x, M, C, K, stats, a3, packed, naive, slope);
 }
 
 int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const void* stats,
@@ -768,7 +778,8 @@ int launch_pack(hipStream_t st, const float* a2, int64_t M, int C, int K, const 
 }
 
 int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, const void* stats,
-                  float* a2t) {
+                  float* a2t, bool act, float slope) {
+  const int ac = act ? 1 : 0;
   const float* sp = static_cast<const float*>(stats);
   const int vec = fast_vec(K, C);
   if (vec == 0) {
@@ -776,18 +787,18 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
     const uint8_t* pk = static_cast<const uint8_t*>(packed);
     if (K == 4)
-      flat_unpack_kernel<4><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+      flat_unpack_kernel<4><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t, ac, slope);
     else if (K == 8)
-      flat_unpack_kernel<8><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+      flat_unpack_kernel<8><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t, ac, slope);
     else
-      flat_unpack_kernel<32><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t);
+      flat_unpack_kernel<32><<<blocks, kThreads, 0, st>>>(pk, E, C, sp, a2t, ac, slope);
     return hip_status();
   }
   const RowGeom g = make_geom(M, C, vec, false);
   // (streaming stores slow a pure-write kernel down on this part; measured 87 us vs 36 us)
 #define ABL_UP(KK, VV)                                                                              \
   do {                                                                                              \
-    unpack_kernel<KK, VV, false><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t);        \
+    unpack_kernel<KK, VV, false><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t, ac, slope); \
   } while (0)
   if (K == 4 && vec == 8) ABL_UP(4, 8);
   else if (K == 4) ABL_UP(4, 4);
@@ -798,7 +809,7 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
 
 int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                   int C, int K, bool accum, void* scratch, float* dx, float* dgamma, float* dbeta,
-                  const DwSum* dwsum) {
+                  const DwSum* dwsum, float slope) {
   const float* sp = static_cast<const float*>(stats);
   double* partial = static_cast<double*>(scratch);
   const int vec = fast_vec(K, C);
@@ -806,27 +817,28 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
   if (vec == 0) {
     if (K == 4)
-      flat_bwd_reduce_kernel<4><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+      flat_bwd_reduce_kernel<4><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
     else if (K == 8)
-      flat_bwd_reduce_kernel<8><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+      flat_bwd_reduce_kernel<8><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
     else
-      flat_bwd_reduce_kernel<32><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial);
+      flat_bwd_reduce_kernel<32><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
   } else if (K == 4 && vec == 8) {
-    bwd_reduce_kernel<4, 8><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+    bwd_reduce_kernel<4, 8><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   } else if (K == 4) {
-    bwd_reduce_kernel<4, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+    bwd_reduce_kernel<4, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   } else {
-    bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial);
+    bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   }
   if (hipGetLastError() != hipSuccess) return ABL_ERR_HIP;
-  return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta, dwsum);
+  return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta, dwsum,
+                              slope);
 }
 
 // Eq. 7 totals and Eq. 8 from `nb` partial rows [nb][2][C] of (sum dA2, sum A1~ dA2) at the
 // start of `scratch`: finalize kernel, then the apply pass.
 int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, const float* da3, int64_t M,
                          int C, int K, bool accum, void* scratch, int nb, float* dx, float* dgamma,
-                         float* dbeta, const DwSum* dwsum) {
+                         float* dbeta, const DwSum* dwsum, float slope) {
   const float* sp = static_cast<const float*>(stats);
   const double* partial = static_cast<const double*>(scratch);
   float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + bn_means_offset(C));
@@ -841,12 +853,12 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
   if (vec == 0) {
     const int64_t E = M * C;
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
-    if (K == 4 && accum) flat_bwd_apply_kernel<4, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else if (K == 4) flat_bwd_apply_kernel<4, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else if (K == 8 && accum) flat_bwd_apply_kernel<8, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else if (K == 8) flat_bwd_apply_kernel<8, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else if (accum) flat_bwd_apply_kernel<32, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
-    else flat_bwd_apply_kernel<32, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx);
+    if (K == 4 && accum) flat_bwd_apply_kernel<4, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
+    else if (K == 4) flat_bwd_apply_kernel<4, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
+    else if (K == 8 && accum) flat_bwd_apply_kernel<8, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
+    else if (K == 8) flat_bwd_apply_kernel<8, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
+    else if (accum) flat_bwd_apply_kernel<32, true><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
+    else flat_bwd_apply_kernel<32, false><<<blocks, kThreads, 0, st>>>(pk, da3, E, C, sp, means, dx, slope);
     return hip_status();
   }
   const RowGeom ga = make_geom(M, C, vec, false);
@@ -854,9 +866,9 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
 #define ABL_APPLY1(KK, VV, AA)                                                                              \
   do {                                                                                                      \
     if (stream)                                                                                             \
-      bwd_apply_kernel<KK, VV, AA, true><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx);  \
+      bwd_apply_kernel<KK, VV, AA, true><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx, slope); \
     else                                                                                                    \
-      bwd_apply_kernel<KK, VV, AA, false><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx); \
+      bwd_apply_kernel<KK, VV, AA, false><<<grid_of(ga), kThreads, 0, st>>>(packed, da3, M, C, ga, sp, means, dx, slope); \
   } while (0)
 #define ABL_APPLY(KK, VV)             \
   do {                                \

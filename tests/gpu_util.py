@@ -127,10 +127,10 @@ def run_conv_wgrad(s, K, packed, stats_t, dy, flags=0):
 
 
 class LayerRun:
-    """One abl_forward (+ abl_backward) on the device."""
+    """One abl_forward (+ abl_backward) on the device; with `slope` the leaky-ReLU calls."""
 
-    def __init__(self, s, K, flags=0):
-        self.s, self.K, self.flags = s, K, flags
+    def __init__(self, s, K, flags=0, slope=None):
+        self.s, self.K, self.flags, self.slope = s, K, flags, slope
         t = s.as_tuple()
         self.scratch = zeros_bytes(B.abl_scratch_bytes(t, K))
         self.packed = torch.full((B.abl_packed_bytes(t, K),), 0xEE, dtype=torch.uint8, device="cuda")
@@ -144,9 +144,12 @@ class LayerRun:
             y = xd.view(-1)[: int(np.prod(out_shape(s)))].view(out_shape(s))
         else:
             y = torch.empty(out_shape(s), dtype=torch.float32, device="cuda")
-        B.abl_forward(s.as_tuple(), self.K, xd, dev(w), dev(gamma), dev(beta),
-                      None if skip is None else dev(skip), self.scratch, y, self.packed, self.stats,
-                      flags=self.flags)
+        args = (xd, dev(w), dev(gamma), dev(beta), None if skip is None else dev(skip), self.scratch, y,
+                self.packed, self.stats)
+        if self.slope is None:
+            B.abl_forward(s.as_tuple(), self.K, *args, flags=self.flags)
+        else:
+            B.abl_leaky_forward(s.as_tuple(), self.K, self.slope, *args, flags=self.flags)
         torch.cuda.synchronize()
         return y.cpu().numpy()
 
@@ -156,8 +159,12 @@ class LayerRun:
         dw = torch.empty((s.R, s.S, s.Cin, s.Cout), dtype=torch.float32, device="cuda")
         dg = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
         db = torch.empty(s.Cin, dtype=torch.float32, device="cuda")
-        B.abl_backward(s.as_tuple(), self.K, self.packed, self.stats, dev(dy), dev(w), self.scratch, dx, dw, dg, db,
-                       flags=(self.flags & ~B.ABL_NAIVE_FWD) | (B.ABL_ACCUM_DX if accum_into is not None else 0))
+        flags = (self.flags & ~B.ABL_NAIVE_FWD) | (B.ABL_ACCUM_DX if accum_into is not None else 0)
+        args = (self.packed, self.stats, dev(dy), dev(w), self.scratch, dx, dw, dg, db)
+        if self.slope is None:
+            B.abl_backward(s.as_tuple(), self.K, *args, flags=flags)
+        else:
+            B.abl_leaky_backward(s.as_tuple(), self.K, self.slope, *args, flags=flags)
         torch.cuda.synchronize()
         return dx.cpu().numpy(), dw.cpu().numpy(), dg.cpu().numpy(), db.cpu().numpy()
 
