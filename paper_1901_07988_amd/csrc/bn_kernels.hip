@@ -209,9 +209,23 @@ __device__ inline void reduce_partials(const double* __restrict__ partial, int n
   const int c = blockIdx.x * 16 + (v & 15), q = v >> 4;
   double a = 0.0;
   if (c < C) {
+    // at most kMaxPartialBlocks / 32 rows per thread: all of them are requested before the first
+    // is added (one memory round trip instead of one per batch); the order of the adds is fixed
+    static_assert(kMaxPartialBlocks % 32 == 0, "rows per part");
+    constexpr int kRows = kMaxPartialBlocks / 32;
     const double* src = partial + (int64_t)q * C + c;
-#pragma unroll 8
-    for (int i = part; i < nb; i += 32) a += src[(int64_t)i * 2 * C];
+    double r[kRows];
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+      const int i = part + 32 * k;
+      r[k] = src[(int64_t)(i < nb ? i : 0) * 2 * C];
+    }
+    if (nb <= kMaxPartialBlocks) {
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) a += (part + 32 * k < nb) ? r[k] : 0.0;
+    } else {
+      for (int i = part; i < nb; i += 32) a += src[(int64_t)i * 2 * C];
+    }
   }
   sm[part][v] = a;
   __syncthreads();
