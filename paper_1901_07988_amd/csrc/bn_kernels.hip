@@ -203,29 +203,36 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(const float* __
 // adds up its interleaved share of the rows, then the 32 parts are combined by a tree in LDS.
 // Returns the two totals of channel blockIdx.x*16 + (threadIdx.x & 15) to threads < 16.
 constexpr int kFinThreads = 1024;
+// One part's share of the rows (part, part + 32, ...; at most ROWS of them): every row is
+// requested before the first is added - one memory round trip - and the adds keep their order.
+template <int ROWS>
+__device__ inline double sum_part_rows(const double* __restrict__ src, int part, int nb, int C) {
+  double r[ROWS];
+#pragma unroll
+  for (int k = 0; k < ROWS; ++k) {
+    const int i = part + 32 * k;
+    r[k] = src[(int64_t)(i < nb ? i : 0) * 2 * C];
+  }
+  double a = 0.0;
+#pragma unroll
+  for (int k = 0; k < ROWS; ++k) a += (part + 32 * k < nb) ? r[k] : 0.0;
+  return a;
+}
+
 __device__ inline void reduce_partials(const double* __restrict__ partial, int nb, int C,
                                        double (&out)[2], double (*sm)[32]) {
   const int v = threadIdx.x & 31, part = threadIdx.x >> 5;
   const int c = blockIdx.x * 16 + (v & 15), q = v >> 4;
   double a = 0.0;
   if (c < C) {
-    // at most kMaxPartialBlocks / 32 rows per thread: all of them are requested before the first
-    // is added (one memory round trip instead of one per batch); the order of the adds is fixed
-    static_assert(kMaxPartialBlocks % 32 == 0, "rows per part");
-    constexpr int kRows = kMaxPartialBlocks / 32;
+    static_assert(kMaxPartialBlocks == 512, "at most 16 rows per part");
     const double* src = partial + (int64_t)q * C + c;
-    double r[kRows];
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-      const int i = part + 32 * k;
-      r[k] = src[(int64_t)(i < nb ? i : 0) * 2 * C];
-    }
-    if (nb <= kMaxPartialBlocks) {
-#pragma unroll
-      for (int k = 0; k < kRows; ++k) a += (part + 32 * k < nb) ? r[k] : 0.0;
-    } else {
+    if (nb <= 64) a = sum_part_rows<2>(src, part, nb, C);
+    else if (nb <= 128) a = sum_part_rows<4>(src, part, nb, C);
+    else if (nb <= 256) a = sum_part_rows<8>(src, part, nb, C);
+    else if (nb <= 512) a = sum_part_rows<16>(src, part, nb, C);
+    else
       for (int i = part; i < nb; i += 32) a += src[(int64_t)i * 2 * C];
-    }
   }
   sm[part][v] = a;
   __syncthreads();
@@ -480,8 +487,18 @@ __global__ __launch_bounds__(kFinThreads) void bwd_finalize_dwsum_kernel(const d
                                                                       float* __restrict__ means, int nfin,
                                                                       const float* __restrict__ wpartial,
                                                                       int ncopies, int64_t n,
-                                                                      float* __restrict__ dw) {
+                                                                      float* __restrict__ dw, int straight) {
   __shared__ double sm[32][32];
+  if ((int)blockIdx.x >= nfin && straight != 0) {
+    // large weight tensors in few copies: one output per thread, the copies added in order
+    const int64_t i = (int64_t)(blockIdx.x - nfin) * kFinThreads + threadIdx.x;
+    if (i >= n) return;
+    float a = wpartial[i];
+#pragma unroll 8
+    for (int k = 1; k < ncopies; ++k) a += wpartial[(int64_t)k * n + i];
+    dw[i] = a;
+    return;
+  }
   if ((int)blockIdx.x < nfin) {
     const int c = blockIdx.x * 16 + (threadIdx.x & 15);
     double t[2];
@@ -862,10 +879,16 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
   const int vec = fast_vec(K, C);
   const int nfin = (C + 15) / 16;
-  if (dwsum != nullptr)
-    bwd_finalize_dwsum_kernel<<<nfin + (unsigned)((dwsum->n + 63) / 64), kFinThreads, 0, st>>>(
-        partial, nb, M, C, sp, dgamma, dbeta, means, nfin, dwsum->partial, dwsum->copies, dwsum->n, dwsum->dw);
-  else
+  if (dwsum != nullptr) {
+    // many small copies (one per pixel tile): 16 interleaved parts per output and a tree;
+    // few large ones (split contraction): one thread per output
+    const bool straight = dwsum->copies <= 32 && dwsum->n >= 131072;
+    const unsigned wblocks = straight ? (unsigned)((dwsum->n + kFinThreads - 1) / kFinThreads)
+                                      : (unsigned)((dwsum->n + 63) / 64);
+    bwd_finalize_dwsum_kernel<<<nfin + wblocks, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means, nfin,
+                                                                      dwsum->partial, dwsum->copies, dwsum->n,
+                                                                      dwsum->dw, straight ? 1 : 0);
+  } else
     bwd_finalize_kernel<<<nfin, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means);
   if (vec == 0) {
     const int64_t E = M * C;
