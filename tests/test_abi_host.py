@@ -87,3 +87,15 @@ def test_exact_storage_sizes_and_k_validation(B):
     assert B.lib.abl_packed_bytes(ref, 16) == 0
     assert B.lib.abl_bn_conv_fwd(None, ref, 32, 0, 16, 16, 16, None, 32, 16) == B.ABL_ERR_ARG
     assert B.lib.abl_postact_packed_bytes(ref, 32) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share; a larger --gpus exits with a message and a non-zero code
+    before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
