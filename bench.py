@@ -163,6 +163,33 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
     return out
 
 
+def pack_unpack_large(G, B, K, reps):
+    """Pack / unpack / fused normalise-ReLU-pack rates on a tensor large enough to be bound by HBM and
+    not by the launch: the input of the first ImageNet bottleneck layer, [64*56*56, 256] fp32 (205 MB)."""
+    import torch
+    M, C = 64 * 56 * 56, 256
+    E = M * C
+    t = (64, 56, 56, C, 64, 1, 1, 1, 0)
+    P = B.abl_packed_bytes(t, K)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    gamma, beta = torch.ones(C, **f32), torch.zeros(C, **f32)
+    stats = G.zeros_bytes(B.abl_stats_bytes(t))
+    scratch = G.zeros_bytes(B.abl_bn_scratch_bytes(M, C))
+    S = [dict(x=torch.randn(E, **f32), a3=torch.empty(E, **f32), packed=G.zeros_bytes(P)) for _ in range(2)]
+    B.abl_bn_stats(S[0]["x"], M, C, gamma, beta, K, scratch, stats)
+    for d in S:
+        B.abl_bn_relu_pack(d["x"], M, C, K, stats, d["a3"], d["packed"])
+    stages = {
+        "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P),
+        "unpack": (lambda i: B.abl_unpack(S[i]["packed"], M, C, K, stats, S[i]["a3"]), 4 * E + P),
+        "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]), 8 * E + P),
+    }
+    out = {"shape": "[%d, %d] fp32" % (M, C)}
+    for name, (fn, nbytes) in stages.items():
+        out[name] = nbytes / time_events(fn, reps, 2) / 1e6
+    return out
+
+
 def cpu_baseline(wl, K):
     """The CPU oracle, as it stands, on one full step of the same workload."""
     import numpy as np
@@ -277,6 +304,8 @@ def main():
     bd0 = details[max(shapes, key=shapes.get)]
     result["pack_unpack_gbs"] = {"pack": bd0["pack"]["gbs"], "unpack": bd0["unpack"]["gbs"],
                                  "bn_relu_pack": bd0["bn_relu_pack"]["gbs"]}
+    if args.kernel_reps > 0:
+        result["pack_unpack_gbs_large"] = pack_unpack_large(G, B, K, max(2, min(args.kernel_reps, 20)))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, K)
     print(json.dumps(result))

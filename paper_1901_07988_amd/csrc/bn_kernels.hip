@@ -57,7 +57,9 @@ RowGeom make_geom(int64_t M, int C, int VEC, bool reduce) {
     const int64_t cap = (passes + kMaxPartialBlocks - 1) / kMaxPartialBlocks;
     if (rpt < cap) rpt = cap;
   } else {
-    if (rpt > 16) rpt = 16;
+    // one batch of kUnroll rows per thread and no loop: measured best from 50 MB tensors up
+    // (pack on 205 MB: 4.5 -> 5.3 TB/s against 16 rows per thread)
+    if (rpt > kUnroll) rpt = kUnroll;
   }
   if (rpt < 1) rpt = 1;
   g.rpt = (int)rpt;
