@@ -159,6 +159,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // predicates would each occupy a pair of scalar registers for the whole kernel.
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AMAX];
+  float4 ra[AMAX];
   unsigned ownbits = 0;  // fused forward: bit j = this block writes the codes of slot j
   {
     int ti, h, w;
@@ -177,6 +178,9 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
       const int idx = tid + kThreads * j;
       const bool ok = idx < vtotal && ti < vN && (unsigned)h < (unsigned)vHi && (unsigned)w < (unsigned)vWi;
       goff[j] = ok ? mad24(mad24(mad24(ti, vHi, h), vWi, w), vCg, c4) : (idx < vtotal ? -1 : -2);
+      // the first chunk's load of a slot leaves as soon as its address is known, ahead of the
+      // position arithmetic of the slots after it
+      ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] : 0));
       if (FUSE != 0) {
         const bool own = ok && n0 == 0 && (unsigned)(h - vh0) < (unsigned)vTH && (unsigned)(w - vw0) < (unsigned)vTW;
         ownbits |= (own ? 1u : 0u) << j;
@@ -194,7 +198,6 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   if (FUSE != 0 && blockIdx.x == 0 && tid < p.pack_pad)  // zero the tail of the last 128-byte row
     static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + tid] = 0;
 
-  float4 ra[AMAX];
   // per-channel constants of the 4 channels this thread stages (fused forward)
   float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
   int4 k_fb;
@@ -202,10 +205,12 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   auto fetch_a = [&](int c0) __attribute__((always_inline)) {
     // unconditional loads (lanes outside the image read element 0 and are zeroed): no branch
     // separates the loads, so all of them are in flight together
+    if (c0 != 0) {
 #pragma unroll
-    for (int j = 0; j < AMAX; ++j) {
-      const bool ok = goff[j] >= 0;
-      ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
+      for (int j = 0; j < AMAX; ++j) {
+        const bool ok = goff[j] >= 0;
+        ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
+      }
     }
     if (FUSE != 0) {
       const int c = c0 + 4 * (tid & 3);
@@ -874,6 +879,9 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   // fill, -2 = past the end of the patch
   const int totalA = patch * 4;
   int goff[AMAX];
+  // dy and the codes of the same elements: each slot's loads leave as soon as its address is known
+  float4 rd[AMAX];
+  uint32_t rc[AMAX];
   {
     int ti, h, w;
     split3(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
@@ -888,6 +896,12 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
       const int idx = tid + kThreads * j;
       const bool ok = idx < vtotal && ti < vN && (unsigned)h < (unsigned)vH && (unsigned)w < (unsigned)vW;
       goff[j] = ok ? mad24(mad24(mad24(ti, vH, h), vW, w), C, c4) : (idx < vtotal ? -1 : -2);
+      {
+        const int e0 = ok ? goff[j] : 0;
+        rd[j] = *reinterpret_cast<const float4*>(dy + e0);
+        rc[j] = K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(packed + (e0 >> 1))
+                       : *reinterpret_cast<const uint32_t*>(packed + e0);
+      }
       w += step.w;
       const bool cw = w >= w_end;
       w -= cw ? width : 0;
@@ -898,16 +912,7 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
     }
   }
 
-  // all loads of the block in one batch: dy, the codes of the same elements, the weight fragments
-  float4 rd[AMAX];
-  uint32_t rc[AMAX];
-#pragma unroll
-  for (int j = 0; j < AMAX; ++j) {
-    const int e0 = goff[j] >= 0 ? goff[j] : 0;
-    rd[j] = *reinterpret_cast<const float4*>(dy + e0);
-    rc[j] = K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(packed + (e0 >> 1))
-                   : *reinterpret_cast<const uint32_t*>(packed + e0);
-  }
+  // the rest of the block's loads in one batch: quantizer constants and the weight fragments
   const int c4 = 4 * (tid & 3);
   const float4 q_step = *reinterpret_cast<const float4*>(stats + P_STEP * C + c4);
   const int4 q_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + c4);
