@@ -58,16 +58,38 @@ struct EpiReduce {
   int K;
 };
 
-// idx -> (ti, h, w) of a [.. x height x width] box, divisions by multiplication
+// idx -> (ti, h, w) of a [.. x height x width] box, divisions by multiplication with
+// inv = ceil(2^32 / d) (d = 1 has none).  EAGER: the products are formed unconditionally - as
+// one arm of a conditional each drags the load of its `inv` from the argument block into a branch
+// of its own, which the small 16-channel kernels pay for in set-up time; the larger variants
+// measured faster with the conditional form.
+template <bool EAGER = false>
 __device__ inline void split3(int idx, int width, unsigned inv_w, int height, unsigned inv_h, int& ti, int& h,
                               int& w) {
-  const int q = width == 1 ? idx : (int)__umulhi((unsigned)idx, inv_w);
-  w = idx - q * width;
-  ti = height == 1 ? q : (int)__umulhi((unsigned)q, inv_h);
-  h = q - ti * height;
+  if constexpr (EAGER) {
+    const int q0 = (int)__umulhi((unsigned)idx, inv_w);
+    const int q = width == 1 ? idx : q0;
+    w = idx - q * width;
+    const int t0 = (int)__umulhi((unsigned)q, inv_h);
+    ti = height == 1 ? q : t0;
+    h = q - ti * height;
+  } else {
+    const int q = width == 1 ? idx : (int)__umulhi((unsigned)idx, inv_w);
+    w = idx - q * width;
+    ti = height == 1 ? q : (int)__umulhi((unsigned)q, inv_h);
+    h = q - ti * height;
+  }
 }
 
-__device__ inline unsigned udiv(unsigned x, unsigned d, unsigned inv) { return d == 1 ? x : __umulhi(x, inv); }
+template <bool EAGER = false>
+__device__ inline unsigned udiv(unsigned x, unsigned d, unsigned inv) {
+  if constexpr (EAGER) {
+    const unsigned q = __umulhi(x, inv);
+    return d == 1 ? x : q;
+  } else {
+    return d == 1 ? x : __umulhi(x, inv);
+  }
+}
 
 __device__ inline void box_advance(int& w, int& h, int& ti, const BoxStep& s, int width, int height) {
   w += s.w;
@@ -142,11 +164,11 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // ids 8 apart share an XCD (and its L2): the blocks that contract the same pixel tile against
   // different output-channel blocks run there back to back
   const unsigned slot = blockIdx.x >> 3;
-  const unsigned sq = udiv(slot, p.nblk_n, p.inv_nblk_n);
+  const unsigned sq = udiv<UNROLL_TAPS>(slot, p.nblk_n, p.inv_nblk_n);
   const int tile_id = sq * 8 + (blockIdx.x & 7);
   if (tile_id >= p.tiles_i * p.tiles_h * p.tiles_w) return;
-  const unsigned t1 = udiv(tile_id, p.tiles_w, p.inv_tiles_w);
-  const unsigned t2 = udiv(t1, p.tiles_h, p.inv_tiles_h);
+  const unsigned t1 = udiv<UNROLL_TAPS>(tile_id, p.tiles_w, p.inv_tiles_w);
+  const unsigned t2 = udiv<UNROLL_TAPS>(t1, p.tiles_h, p.inv_tiles_h);
   const int tw_i = tile_id - t1 * p.tiles_w, th_i = t1 - t2 * p.tiles_h;
   const int img0 = t2 * p.TI, h0 = th_i * p.TH, w0 = tw_i * p.TW;
   const int n0 = (slot - sq * p.nblk_n) * BN;
@@ -163,7 +185,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   unsigned ownbits = 0;  // fused forward: bit j = this block writes the codes of slot j
   {
     int ti, h, w;
-    split3(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
+    split3<UNROLL_TAPS>(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
     // position in the input instead of in the patch
     ti += img0; h += oh; w += ow;
     const BoxStep step{in_vgpr(p.a_step.w), in_vgpr(p.a_step.h), in_vgpr(p.a_step.ti)};
@@ -297,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   {
     const int m0 = wave_m * MT * 16 + li;
     int ti, h, w;
-    split3(m0, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    split3<UNROLL_TAPS>(m0, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
     const int vHH = in_vgpr(p.HH), vHW = in_vgpr(p.HW);
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -375,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     }
   }
   int e_ti, e_h, e_w;
-  split3(wave_m * MT * 16 + li, p.TW, p.inv_TW, p.TH, p.inv_TH, e_ti, e_h, e_w);
+  split3<UNROLL_TAPS>(wave_m * MT * 16 + li, p.TW, p.inv_TW, p.TH, p.inv_TH, e_ti, e_h, e_w);
   const int vN = in_vgpr(g.N), vHq = in_vgpr(Hq), vWq = in_vgpr(Wq), vNg = in_vgpr(Ng);
   const int vimg0 = in_vgpr(img0), vh0 = in_vgpr(h0), vw0 = in_vgpr(w0);
 #pragma unroll
@@ -860,15 +882,15 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lk = lane >> 4;
   const int tile = blockIdx.x;
-  const unsigned t1 = udiv(tile, p.tiles_w, p.inv_tiles_w);
-  const unsigned t2 = udiv(t1, p.tiles_h, p.inv_tiles_h);
+  const unsigned t1 = udiv<true>(tile, p.tiles_w, p.inv_tiles_w);
+  const unsigned t2 = udiv<true>(t1, p.tiles_h, p.inv_tiles_h);
   const int img0 = t2 * p.TI, h0 = (t1 - t2 * p.tiles_h) * p.TH, w0 = (tile - t1 * p.tiles_w) * p.TW;
   const int oh = h0 - 1, ow = w0 - 1;  // image coordinate of patch element (0,0), both patches
 
   // table entry of tile pixel m = tid
   {
     int ti, h, w;
-    split3(tid, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
+    split3<true>(tid, p.TW, p.inv_TW, p.TH, p.inv_TH, ti, h, w);
     const bool in_tile = tid < p.npix;
     const int n = img0 + ti, hq = h0 + h, wq = w0 + w;
     pixbase[tid] = in_tile ? mad24(mad24(mad24(ti, p.HH, h), p.HW, w), PS, 0) : 0;
@@ -884,7 +906,7 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   uint32_t rc[AMAX];
   {
     int ti, h, w;
-    split3(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
+    split3<true>(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
     ti += img0; h += oh; w += ow;
     const BoxStep step{in_vgpr(p.a_step.w), in_vgpr(p.a_step.h), in_vgpr(p.a_step.ti)};
     const int width = in_vgpr(p.HW), height = in_vgpr(p.HH);
