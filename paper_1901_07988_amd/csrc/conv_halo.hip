@@ -335,6 +335,55 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[j][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  // The small (all-taps-in-registers) variants spend the wait for their first loads on the
+  // epilogue's index arithmetic and request the shortcut values now: in the epilogue itself a
+  // memory round trip would be exposed in every block.
+  int eoff[UNROLL_TAPS ? MT : 1];
+  unsigned epix = 0;
+  float4 esv[UNROLL_TAPS ? MT : 1][NT];
+  uint32_t ecw[UNROLL_TAPS ? MT : 1][NT];
+  float4 r_step[NT], r_beta[NT], r_gm[NT];  // per-channel constants of the Eq. 6-7 epilogue
+  int4 r_fb[NT];
+  if constexpr (UNROLL_TAPS) {
+    int e_ti, e_h, e_w;
+    split3<true>(wave_m * MT * 16 + li, p.TW, p.inv_TW, p.TH, p.inv_TH, e_ti, e_h, e_w);
+    const int vN = in_vgpr(g.N), vHq = in_vgpr(Hq), vWq = in_vgpr(Wq), vNg = in_vgpr(Ng);
+    const int vimg0 = in_vgpr(img0), vh0 = in_vgpr(h0), vw0 = in_vgpr(w0);
+    const int cb = n0 + wn0 + 4 * lk;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int m = wave_m * MT * 16 + 16 * i + li;
+      const int n = vimg0 + e_ti, hq = vh0 + e_h, wq = vw0 + e_w;
+      const bool pix_ok = m < vnpix && n < vN && hq < vHq && wq < vWq;
+      eoff[i] = mad24(mad24(mad24(n, vHq, hq), vWq, wq), vNg, cb);  // element (pixel, channel cb)
+      epix |= (pix_ok ? 1u : 0u) << i;
+      box_advance(e_w, e_h, e_ti, mstep, vTW, vTH);
+      if (skip != nullptr) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          esv[i][j] = *reinterpret_cast<const float4*>(skip + (pix_ok && cb + 16 * j < Ng ? eoff[i] + 16 * j : 0));
+      }
+      if (MODE == 1 && epi.partial != nullptr) {  // the codes behind the Eq. 6-7 sums
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int el = pix_ok && cb + 16 * j < Ng ? eoff[i] + 16 * j : 0;
+          ecw[i][j] = epi.K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(epi.codes + (el >> 1))
+                                 : *reinterpret_cast<const uint32_t*>(epi.codes + el);
+        }
+      }
+    }
+    if (MODE == 1 && epi.partial != nullptr) {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int c = cb + 16 * j < Ng ? cb + 16 * j : 0;
+        r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * Ng + c);
+        r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * Ng + c);
+        r_gm[j] = *reinterpret_cast<const float4*>(stats + P_GAMMA * Ng + c);
+        r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * Ng + c);
+      }
+    }
+  }
+
   stage_a(lds);
   __syncthreads();
   int buf = 0;
@@ -381,19 +430,20 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   const bool reduce = epi.partial != nullptr;
   const int cb = n0 + wn0 + 4 * lk;
   double s1[NT][4], s2[NT][4];
-  float4 r_step[NT], r_beta[NT], r_ig[NT];
-  int4 r_fb[NT];
+  float4 r_ig[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = 0.0;
     if (MODE == 1 && reduce) {
-      const int c = cb + 16 * j < Ng ? cb + 16 * j : 0;
-      r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * Ng + c);
-      r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * Ng + c);
-      const float4 gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * Ng + c);
-      r_ig[j] = make_float4(1.0f / gm.x, 1.0f / gm.y, 1.0f / gm.z, 1.0f / gm.w);
-      r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * Ng + c);
+      if constexpr (!UNROLL_TAPS) {
+        const int c = cb + 16 * j < Ng ? cb + 16 * j : 0;
+        r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * Ng + c);
+        r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * Ng + c);
+        r_gm[j] = *reinterpret_cast<const float4*>(stats + P_GAMMA * Ng + c);
+        r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * Ng + c);
+      }
+      r_ig[j] = make_float4(1.0f / r_gm[j].x, 1.0f / r_gm[j].y, 1.0f / r_gm[j].z, 1.0f / r_gm[j].w);
     }
   }
   int e_ti, e_h, e_w;
@@ -402,18 +452,28 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   const int vimg0 = in_vgpr(img0), vh0 = in_vgpr(h0), vw0 = in_vgpr(w0);
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    const int m = wave_m * MT * 16 + 16 * i + li;
-    const int n = vimg0 + e_ti, hq = vh0 + e_h, wq = vw0 + e_w;
-    const bool pix_ok = m < vnpix && n < vN && hq < vHq && wq < vWq;
-    const int off = mad24(mad24(mad24(n, vHq, hq), vWq, wq), vNg, cb);  // element (pixel, channel cb)
-    box_advance(e_w, e_h, e_ti, mstep, vTW, vTH);
+    bool pix_ok;
+    int off;
+    if constexpr (UNROLL_TAPS) {
+      pix_ok = ((epix >> i) & 1u) != 0;
+      off = eoff[i];
+    } else {
+      const int m = wave_m * MT * 16 + 16 * i + li;
+      const int n = vimg0 + e_ti, hq = vh0 + e_h, wq = vw0 + e_w;
+      pix_ok = m < vnpix && n < vN && hq < vHq && wq < vWq;
+      off = mad24(mad24(mad24(n, vHq, hq), vWq, wq), vNg, cb);  // element (pixel, channel cb)
+      box_advance(e_w, e_h, e_ti, mstep, vTW, vTH);
+    }
     bool ok[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) ok[j] = pix_ok && cb + 16 * j < Ng;
     if (skip != nullptr) {
       float4 sv[NT];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) sv[j] = *reinterpret_cast<const float4*>(skip + (ok[j] ? off + 16 * j : 0));
+      for (int j = 0; j < NT; ++j) {
+        if constexpr (UNROLL_TAPS) sv[j] = esv[i][j];
+        else sv[j] = *reinterpret_cast<const float4*>(skip + (ok[j] ? off + 16 * j : 0));
+      }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         acc[j][i][0] += sv[j].x; acc[j][i][1] += sv[j].y; acc[j][i][2] += sv[j].z; acc[j][i][3] += sv[j].w;
@@ -435,9 +495,13 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         uint32_t cw[NT];  // the K-bit codes of the lane's 4 channels
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-          const int el = ok[j] ? off + 16 * j : 0;
-          cw[j] = epi.K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(epi.codes + (el >> 1))
-                             : *reinterpret_cast<const uint32_t*>(epi.codes + el);
+          if constexpr (UNROLL_TAPS) {
+            cw[j] = ecw[i][j];
+          } else {
+            const int el = ok[j] ? off + 16 * j : 0;
+            cw[j] = epi.K == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(epi.codes + (el >> 1))
+                               : *reinterpret_cast<const uint32_t*>(epi.codes + el);
+          }
         }
 #pragma unroll
         for (int j = 0; j < NT; ++j)
@@ -938,6 +1002,9 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   const int c4 = 4 * (tid & 3);
   const float4 q_step = *reinterpret_cast<const float4*>(stats + P_STEP * C + c4);
   const int4 q_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + c4);
+  // (the epilogue's constants too: requested there, their round trip would be exposed)
+  const float4 e_beta = *reinterpret_cast<const float4*>(stats + P_BETA * C + 4 * lk);
+  const float4 e_gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * C + 4 * lk);
   // dgrad weight fragment: k = co = 4lk .. +3, row = ci = li
   float4 bw[9][1];
 #pragma unroll
@@ -1043,8 +1110,6 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
 
   // ---- epilogue of dA3: store, and the Eq. 6-7 sums with mask and A1~ from the staged activation ----
   {
-    const float4 e_beta = *reinterpret_cast<const float4*>(stats + P_BETA * C + 4 * lk);
-    const float4 e_gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * C + 4 * lk);
     const float bt4[4] = {e_beta.x, e_beta.y, e_beta.z, e_beta.w};
     const float ig4[4] = {1.0f / e_gm.x, 1.0f / e_gm.y, 1.0f / e_gm.z, 1.0f / e_gm.w};
     double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
