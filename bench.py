@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--math", default="fp32", choices=["fp32", "bf16"],
                     help="operand type of the conv contractions (bf16 = ABL_MATH_BF16 variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into a HIP graph once and time replays (pays for launch-bound workloads)")
     ap.add_argument("--kernel-reps", type=int, default=50)
     return ap.parse_args()
 
@@ -241,9 +243,26 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    timed_step = step
+    if args.graph:
+        # the library enqueues kernels only (no allocation, no synchronisation, no memset nodes), so
+        # the whole step can be recorded once; tests/test_gpu_graph.py checks replays against eager
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        timed_step = graph.replay
+        for _ in range(2):
+            timed_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -294,6 +313,7 @@ def main():
         "dtype": "f32" if args.math == "fp32" else "bf16 operands, f32 accumulate (contractions); f32 elsewhere",
         "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "layers": L, "batch": N, "skip_every": wl.skip_every,
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "stack_images_per_sec": N / (dt / args.steps)},
         "roofline": roof,
         "stage_us": breakdown,
