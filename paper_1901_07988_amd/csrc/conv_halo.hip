@@ -1011,11 +1011,12 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
   for (int t = 0; t < 9; ++t)
     bw[t][0] = *reinterpret_cast<const float4*>(wgt + (t * C + li) * C + 4 * lk);
 
-  // dy goes to LDS first: the dA3 contraction needs nothing else, so the first MFMAs start one
-  // global-load round trip after the kernel does.  The activation patch is dequantized between
-  // the taps of that contraction (branch-free: slots past the end of the patch write the spare
-  // row).  (fp32 MFMAs and vector ALU instructions share the SIMD's issue slots on this chip -
-  // measured: their times add up, across waves too - so this hides latency, not arithmetic.)
+  // Both patches are staged before the first MFMA (the activation one branch-free: slots past the
+  // end of the patch write the spare row).  dy and the codes of a slot are requested together,
+  // so neither patch has to wait for the other, and dequantizing between the taps of the dA3
+  // contraction instead gained nothing: fp32 MFMAs and vector ALU instructions share the SIMD's
+  // issue slots on this chip (measured: their times add up, across waves too), and the staging
+  // stores between the taps kept every fragment read right in front of its MFMAs.
 #pragma unroll
   for (int j = 0; j < AMAX; ++j) {
     const int idx = tid + kThreads * j;
@@ -1035,6 +1036,8 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
     const int o = goff[j] != -2 ? (idx >> 2) * PS + 4 * (idx & 3) : patch * PS + 4 * (idx & 3);
     *reinterpret_cast<float4*>(&tact[o]) = make_float4(a[0], a[1], a[2], a[3]);
   };
+#pragma unroll
+  for (int j = 0; j < AMAX; ++j) stage_act(j);
   __syncthreads();
 
   const int ctr = (p.HW + 1) * PS;  // from tap (0,0) to the pixel itself
@@ -1053,9 +1056,7 @@ __global__ __launch_bounds__(kThreads) void halo_bwd16_kernel(const float* __res
 #pragma unroll
     for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const float4*>(&tdy[mbase[i] + aoff]);
     mma_k4<BF16, 1, 4>(bw[t], af, accd);
-    if (t < AMAX) stage_act(t);
   }
-  __syncthreads();  // the activation patch is complete
 
   // ---- dW: the wave's 64 pixels, 16 per step; component e of the operand vectors is pixel
   // 4e + lk of the step (fp32: k-step e, lane group = k) or 4lk + e (bf16) ----
