@@ -221,7 +221,7 @@ def main():
     import torch
     from paper_1901_07988_amd import binding as B
     from paper_1901_07988_amd import synth
-    from tests import gpu_util as G
+    from paper_1901_07988_amd import runtime as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
