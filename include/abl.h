@@ -9,7 +9,8 @@
  *
  * General rules, valid for every entry point unless it says otherwise:
  *   - every tensor pointer is a DEVICE pointer owned by the caller, 16-byte
- *     aligned; the library allocates nothing, keeps no state, enqueues its
+ *     aligned; the library allocates nothing, keeps no state (abl_backward_noalloc apart:
+ *     it remembers where its fixed workspace lives), enqueues its
  *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and never synchronises.  Shapes and sizes are host values.
  *   - activations are fp32, NHWC ("first dim = sample, last dim = channel",
@@ -118,6 +119,25 @@ int abl_backward(void* stream, const abl_shape* shape, int K, uint32_t flags,
                  const void* packed, const void* stats, const float* dy, const float* W,
                  void* scratch, size_t scratch_bytes,
                  float* dx, float* dW, float* dgamma, float* dbeta);
+
+/* abl_backward for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs, aliasing rules and flags as abl_backward, without `scratch`: the workspace is
+ * a fixed array of ABL_NOALLOC_SCRATCH_BYTES in device memory that the library itself holds (one
+ * copy on every GPU that loads the library, kept until the process ends).  The call allocates and
+ * frees nothing; its first use on a device looks up that device's address of the array.
+ *   - shapes whose abl_scratch_bytes(shape, K) exceeds the array give ABL_ERR_SCRATCH and enqueue
+ *     nothing (abl_noalloc_scratch_limit() returns the limit); a failed address lookup gives
+ *     ABL_ERR_HIP; other errors as abl_backward.
+ *   - all calls on one GPU share the one array and it keeps the previous call's contents (nothing
+ *     in it needs clearing: whatever a kernel reads there an earlier kernel of the same call has
+ *     written).  Two calls that overlap in time on one GPU - different streams, or graphs replayed
+ *     concurrently - race on it; calls on one stream are ordered and safe. */
+#define ABL_NOALLOC_SCRATCH_BYTES (32u << 20)
+size_t abl_noalloc_scratch_limit(void);
+int abl_backward_noalloc(void* stream, const abl_shape* shape, int K, uint32_t flags,
+                         const void* packed, const void* stats, const float* dy, const float* W,
+                         float* dx, float* dW, float* dgamma, float* dbeta);
 
 /* The same layer with a leaky ReLU in place of Eq. 3 (Sec. 3.4: the method carries over to
  * non-linearities whose gradient depends on the sign of the activation only):

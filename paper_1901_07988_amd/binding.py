@@ -54,6 +54,8 @@ _SIGS = {
     "abl_wgrad_scratch_bytes": (_sz, [_shp]),
     "abl_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "abl_backward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp, _vp]),
+    "abl_noalloc_scratch_limit": (_sz, []),
+    "abl_backward_noalloc": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "abl_leaky_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
                                          _sz, _vp, _vp, _vp]),
     "abl_leaky_backward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _sz,
@@ -153,6 +155,16 @@ def abl_backward(shape, K, packed, stats, dy, W, scratch, dx, dW, dgamma, dbeta,
     _check(lib.abl_backward(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy), _ptr(W),
                             _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(dx), _ptr(dW),
                             _ptr(dgamma), _ptr(dbeta)), "abl_backward")
+
+
+def abl_noalloc_scratch_limit():
+    return lib.abl_noalloc_scratch_limit()
+
+
+def abl_backward_noalloc(shape, K, packed, stats, dy, W, dx, dW, dgamma, dbeta, flags=0):
+    s = shape_struct(shape)
+    _check(lib.abl_backward_noalloc(_stream(), ctypes.byref(s), K, flags, _ptr(packed), _ptr(stats), _ptr(dy),
+                                    _ptr(W), _ptr(dx), _ptr(dW), _ptr(dgamma), _ptr(dbeta)), "abl_backward_noalloc")
 
 
 def abl_leaky_forward(shape, K, slope, x, W, gamma, beta, skip, scratch, y, packed, stats, flags=0):
