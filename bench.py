@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the approximate-activation layer step on one MI355X.
 
-A step is one forward + one backward pass of the whole hot path over the CIFAR-ResNet-shaped
-residual stage (18 stacked 3x3 BN-ReLU-conv layers, N=128, 16 channels, 32x32, identity skip
-every 2 layers, K=4) on seeded synthetic tensors that are already resident in HBM.  Prints one
-JSON line: layer train-step images/sec (images x layers / second), the roofline figures of the
-dominant kernel and the CPU oracle's throughput on the same workload.
+A step is one forward + one backward pass of the whole hot path over the ImageNet deep-stage
+bottleneck stack (12 x [1x1 1024->256, 3x3 256->256, 1x1 256->1024] BN-ReLU-conv layers at 14x14,
+N=64, identity skip around every block, K=4, fp32) on seeded synthetic tensors that are already
+resident in HBM.  Prints one JSON line: layer train-step images/sec (images x layers / second), the
+roofline figures of the dominant kernel, the same step on the 56x56 bottleneck and on the CIFAR
+stage as sub-results, the rates of the HBM-bound passes on a 205 MB tensor next to measured
+read / write / copy ceilings, and the CPU oracle's throughput on a bounded sample of the workload.
 """
 import argparse
 import json
@@ -25,17 +27,18 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--K", type=int, default=4)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3a", "config3b",
+    ap.add_argument("--workload", default="config5", choices=["config1", "config2", "config3a", "config3b",
                                                               "config4", "config5"])
     ap.add_argument("--math", default="fp32", choices=["fp32", "bf16"],
                     help="operand type of the conv contractions (bf16 = ABL_MATH_BF16 variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="record the step into a HIP graph once and time replays (pays for launch-bound workloads)")
-    ap.add_argument("--kernel-reps", type=int, default=50)
+    ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--no-sub", action="store_true", help="skip the sub-results on the other workloads")
     return ap.parse_args()
 
 
@@ -67,14 +70,27 @@ def time_events(fn, reps, nset=1):
     return start.elapsed_time(stop) / reps
 
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each divided by
-# what the same counter reads for a plain device copy of known size (FETCH_SIZE reads 1/1.994 of the
-# bytes, WRITE_SIZE 1/1.000), for the kernels of the default workload (3x3 16->16, 32x32, N=128, K=4).
-# The runs and their commands are summarised under profiles/.
+# HBM bytes per launch (fetch + write) from two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE in KiB per
+# dispatch, each scaled by what the same counter reads for the plain streaming kernels of the same run
+# (abl_hbm_probe on 205 MB: FETCH_SIZE reads 1/2.000 of the bytes, WRITE_SIZE 1/1.000).  The runs, their
+# commands and the per-kernel tables are under profiles/*_hbm_traffic.txt; counters cannot be read inside
+# a timed run, so the figures of the single-launch stages are kept here, by workload and layer shape.
+S3 = "64x14x14x256x256x3x3x1x1"
 MEASURED_TRAFFIC = {
+    ("config5", 4, "fp32"): {
+        (S3, "bn_conv_fwd"): 46.54e6,            # x 12.8 MB + the weights once per XCD (8 x 2.4 MB) + y + codes
+        (S3, "conv_dgrad_bn_reduce"): 46.67e6,
+        ("64x14x14x1024x256x1x1x1x0", "bn_conv_fwd"): 81.12e6,
+        ("64x14x14x1024x256x1x1x1x0", "conv_dgrad_bn_reduce"): 79.89e6,
+    },
+    ("config4", 4, "fp32"): {
+        ("64x56x56x64x64x3x3x1x1", "bn_conv_fwd"): 139.35e6,
+        ("64x56x56x64x64x3x3x1x1", "conv_dgrad_bn_reduce"): 119.01e6,
+        ("64x56x56x256x64x1x1x1x0", "bn_conv_fwd"): 284.48e6,
+    },
     ("config2", 4, "fp32"): {
-        "bn_conv_fwd": 23.77e6,            # in the stack: half the layers also read a shortcut
-        "conv_bwd_bn_reduce": 25.74e6,     # includes 4.7 MB of per-tile dW copies
+        ("128x32x32x16x16x3x3x1x1", "bn_conv_fwd"): 23.77e6,         # in the stack: half the layers also read a shortcut
+        ("128x32x32x16x16x3x3x1x1", "conv_bwd_bn_reduce"): 25.74e6,  # includes 4.7 MB of per-tile dW copies
     },
 }
 
@@ -165,9 +181,11 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
     return out
 
 
-def pack_unpack_large(G, B, K, reps):
-    """Pack / unpack / fused normalise-ReLU-pack rates on a tensor large enough to be bound by HBM and
-    not by the launch: the input of the first ImageNet bottleneck layer, [64*56*56, 256] fp32 (205 MB)."""
+def hbm_bound_passes(G, B, K, reps):
+    """The HBM-bound passes of the method on a tensor large enough to be bound by memory and not by
+    the launch - the input of the first ImageNet bottleneck layer, [64*56*56, 256] fp32 (205 MB) - next
+    to what plain read-only / write-only / copy kernels reach on the same tensor (abl_hbm_probe).
+    Three operand sets are used in turn (1.3 GB in all), so nothing is found in a cache."""
     import torch
     M, C = 64 * 56 * 56, 256
     E = M * C
@@ -175,60 +193,101 @@ def pack_unpack_large(G, B, K, reps):
     P = B.abl_packed_bytes(t, K)
     f32 = dict(dtype=torch.float32, device="cuda")
     gamma, beta = torch.ones(C, **f32), torch.zeros(C, **f32)
+    dg, db = torch.empty(C, **f32), torch.empty(C, **f32)
     stats = G.zeros_bytes(B.abl_stats_bytes(t))
     scratch = G.zeros_bytes(B.abl_bn_scratch_bytes(M, C))
-    S = [dict(x=torch.randn(E, **f32), a3=torch.empty(E, **f32), packed=G.zeros_bytes(P)) for _ in range(2)]
+    nset = 3
+    S = [dict(x=torch.randn(E, **f32), a3=torch.empty(E, **f32), packed=G.zeros_bytes(P)) for _ in range(nset)]
     B.abl_bn_stats(S[0]["x"], M, C, gamma, beta, K, scratch, stats)
     for d in S:
         B.abl_bn_relu_pack(d["x"], M, C, K, stats, d["a3"], d["packed"])
-    stages = {
-        "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P),
-        "unpack": (lambda i: B.abl_unpack(S[i]["packed"], M, C, K, stats, S[i]["a3"]), 4 * E + P),
-        "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]), 8 * E + P),
+    nb = 4 * E
+    probes = {
+        "read": (lambda i: B.abl_hbm_probe(0, S[i]["x"], scratch, nb), nb),
+        "write": (lambda i: B.abl_hbm_probe(1, None, S[i]["a3"], nb), nb),
+        "copy": (lambda i: B.abl_hbm_probe(2, S[i]["x"], S[i]["a3"], nb), 2 * nb),
     }
-    out = {"shape": "[%d, %d] fp32" % (M, C)}
-    for name, (fn, nbytes) in stages.items():
-        out[name] = nbytes / time_events(fn, reps, 2) / 1e6
+    ceil = {k: nbytes / time_events(fn, reps, nset) / 1e6 for k, (fn, nbytes) in probes.items()}
+    # name: (call, algorithmic bytes, launches, which ceiling its traffic mix is compared with)
+    stages = {
+        "bn_stats": (lambda i: B.abl_bn_stats(S[i]["x"], M, C, gamma, beta, K, scratch, stats), 4 * E, 2, "read"),
+        "pack": (lambda i: B.abl_pack(S[i]["x"], M, C, K, stats, S[i]["packed"]), 4 * E + P, 1, "read"),
+        "unpack": (lambda i: B.abl_unpack(S[i]["packed"], M, C, K, stats, S[i]["a3"]), 4 * E + P, 1, "write"),
+        "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]),
+                         8 * E + P, 1, "copy"),
+        # Eq. 6-7 sums (read dA3 + codes), second pass, Eq. 8 (read dA3 + codes, write dx): three launches
+        "bn_bwd": (lambda i: B.abl_bn_bwd(S[i]["packed"], stats, S[i]["x"], M, C, K, scratch, S[i]["a3"], dg, db),
+                   12 * E + 2 * P, 3, "copy"),
+    }
+    out = {"shape": "[%d, %d] fp32" % (M, C), "hbm_peak_gbs": HBM_PEAK_GBS,
+           "ceiling_gbs": {k: round(v, 1) for k, v in ceil.items()}}
+    for name, (fn, nbytes, launches, kind) in stages.items():
+        gbs = nbytes / time_events(fn, reps, nset) / 1e6
+        out[name] = {"gbs": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 3),
+                     "frac_of_%s_ceiling" % kind: round(gbs / ceil[kind], 3), "launches": launches}
     return out
 
 
+def omp_threads(set_to=None):
+    """Size of the OpenMP team the oracle's loops run with (optionally change it first)."""
+    import ctypes
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+    except OSError:
+        return None
+    if set_to is not None:
+        gomp.omp_set_num_threads(int(set_to))
+    return int(gomp.omp_get_max_threads())
+
+
+def oracle_step_seconds(o, np, x, layers, dy, K, skip_every):
+    ol = [(o.Shape(*s.as_tuple()), w, g, b) for s, w, g, b in layers]
+    t0 = time.time()
+    _, saved = o.stack_forward(x, ol, K, np.float32, skip_every)
+    o.stack_backward(saved, ol, dy, np.float32, skip_every)
+    return time.time() - t0
+
+
 def cpu_baseline(wl, K):
-    """The CPU oracle, as it stands, on one full step of the same workload."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the whole step where
+    that takes seconds, else the first group of layers (one bottleneck block), scaled by the number
+    of identical groups."""
     import numpy as np
     from oracle import abl_oracle as o
     from paper_1901_07988_amd import synth
     o.build()
     x, layers, dy = synth.draw_stack(wl)
-    ol = [(o.Shape(*s.as_tuple()), w, g, b) for s, w, g, b in layers]
-    t0 = time.time()
-    _, saved = o.stack_forward(x, ol, K, np.float32, wl.skip_every)
-    o.stack_backward(saved, ol, dy, np.float32, wl.skip_every)
-    dt = time.time() - t0
-    n = wl.shapes[0].N
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": n * len(layers) / dt, "unit": "images/sec per layer step", "cores": cores, "kind": "oracle",
-            "sample": "1 full step (forward+backward, all %d layers, N=%d) of the same workload, %.1f s"
-                      % (len(layers), n, dt)}
+    n, L = wl.shapes[0].N, len(layers)
+    g = wl.skip_every
+    periodic = g > 0 and L > g and L % g == 0 and all(wl.shapes[i] == wl.shapes[i % g] for i in range(L))
+    flops = sum(6.0 * s.N * s.Ho * s.Wo * s.Cin * s.Cout * s.R * s.S for s in wl.shapes)
+    threads = omp_threads()
+    if periodic and flops > 200e9:
+        # dy of the sample: the seeded gradient at the top of the stack has the block's output shape
+        dt_block = oracle_step_seconds(o, np, x, layers[:g], dy, K, g)
+        dt = dt_block * (L // g)
+        sample = ("forward+backward of the first block (%d layers, N=%d) of the same workload: %.1f s, times the %d "
+                  "identical blocks" % (g, n, dt_block, L // g))
+    else:
+        dt = oracle_step_seconds(o, np, x, layers, dy, K, g)
+        sample = "1 full step (forward+backward, all %d layers, N=%d) of the same workload, %.1f s" % (L, n, dt)
+    out = {"value": n * L / dt, "unit": "images/sec per layer step", "cores": threads, "kind": "oracle",
+           "sample": sample}
+    # one core on the smallest configuration (a single 3x3 16->16 layer at 32x32, N=8)
+    w1 = synth.config1()
+    x1, l1, dy1 = synth.draw_stack(w1)
+    omp_threads(set_to=1)
+    dt1 = min(oracle_step_seconds(o, np, x1, l1, dy1, K, 0) for _ in range(3))
+    omp_threads(set_to=threads)
+    out["config1_single_thread"] = {"value": w1.shapes[0].N / dt1, "unit": "images/sec per layer step", "cores": 1,
+                                    "sample": "forward+backward of %s, best of 3, %.1f ms" % (w1.name, dt1 * 1e3)}
+    return out
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
+def time_stack(G, B, synth, wl, K, flags, steps, warmup, graph=False):
+    """ms per step (forward + backward of the whole stack, inputs resident in HBM) and the StackRun."""
     import torch
-    from paper_1901_07988_amd import binding as B
-    from paper_1901_07988_amd import synth
-    from paper_1901_07988_amd import runtime as G
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    wl = get_workload(args.workload)
-    K = args.K
     x, layers, dy = synth.draw_stack(wl)
-    flags = B.ABL_MATH_BF16 if args.math == "bf16" else 0
     run = G.StackRun(layers, K, wl.skip_every, flags=flags)
     xd = G.dev(x).view(-1)
     dyd = G.dev(dy).view(-1)
@@ -240,11 +299,11 @@ def main():
         run.buf_s[:n_out].copy_(dyd)      # the loss gradient arrives in the same buffer
         run.backward()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     timed_step = step
-    if args.graph:
+    if graph:
         # the library enqueues kernels only (no allocation, no synchronisation, no memset nodes), so
         # the whole step can be recorded once; tests/test_gpu_graph.py checks replays against eager
         side = torch.cuda.Stream()
@@ -253,21 +312,43 @@ def main():
             step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
             step()
-        timed_step = graph.replay
+        timed_step = g.replay
         for _ in range(2):
             timed_step()
         torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         timed_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    N, L = wl.shapes[0].N, len(layers)
-    value = N * L / (dt / args.steps)
+    return dt / steps * 1e3, run
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1901_07988_amd import binding as B
+    from paper_1901_07988_amd import synth
+    from paper_1901_07988_amd import runtime as G
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = get_workload(args.workload)
+    K = args.K
+    flags = B.ABL_MATH_BF16 if args.math == "bf16" else 0
+    ms_per_step, run = time_stack(G, B, synth, wl, K, flags, args.steps, args.warmup, args.graph)
+    N, L = wl.shapes[0].N, len(wl.shapes)
+    value = N * L / (ms_per_step * 1e-3)
+    stored = run.stored_bytes()
+    del run
+    torch.cuda.empty_cache()
 
     # per-kernel timing of every distinct layer shape, for the roofline block: the dominant kernel is
     # the one with the largest share of the step among the kernels the layer step runs
@@ -297,11 +378,18 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["gbs"] / HBM_PEAK_GBS}
-    traffic = MEASURED_TRAFFIC.get((args.workload, K, args.math), {}).get(dom_name)
-    roof.update({"traffic": traffic, "kernel": dom_name, "shape": "x".join(map(str, dom_shape.as_tuple())),
+    wl_key = args.workload
+    dom_shape_str = "x".join(map(str, dom_shape.as_tuple()))
+    traffic = MEASURED_TRAFFIC.get((wl_key, K, args.math), {}).get((dom_shape_str, dom_name))
+    roof.update({"traffic": traffic, "kernel": dom_name, "shape": dom_shape_str,
                  "avg_us": dom["ms"] * 1e3, "launches_per_call": dom["launches"],
                  "algorithmic_bytes": dom["bytes"], "algorithmic_flops": dom["flops"],
                  "hbm_frac_of_same_kernel": dom["gbs"] / HBM_PEAK_GBS})
+    # every contraction of the step against the fp32 (or bf16) matrix peak
+    roof["contractions_frac_of_mfma_peak"] = {
+        "x".join(map(str, s.as_tuple())): {k: round(v["tflops"] / mfma_peak, 3) for k, v in bd.items()
+                                             if v["step"] and v["flops"] > 0}
+        for s, bd in details.items()}
 
     exact_bytes = sum(4 * s.E for s in wl.shapes)
     result = {
@@ -314,18 +402,33 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "layers": L, "batch": N, "skip_every": wl.skip_every,
                    "launch": "hip graph replay" if args.graph else "eager",
-                   "stack_images_per_sec": N / (dt / args.steps)},
+                   "stack_images_per_sec": N / (ms_per_step * 1e-3)},
         "roofline": roof,
         "stage_us": breakdown,
-        "pack_unpack_gbs": {},
-        "activation_bytes": {"stored": run.stored_bytes(), "exact_fp32": exact_bytes,
-                             "ratio": run.stored_bytes() / exact_bytes},
+        "activation_bytes": {"stored": stored, "exact_fp32": exact_bytes, "ratio": stored / exact_bytes},
     }
     bd0 = details[max(shapes, key=shapes.get)]
     result["pack_unpack_gbs"] = {"pack": bd0["pack"]["gbs"], "unpack": bd0["unpack"]["gbs"],
                                  "bn_relu_pack": bd0["bn_relu_pack"]["gbs"]}
+    del details
+    torch.cuda.empty_cache()
     if args.kernel_reps > 0:
-        result["pack_unpack_gbs_large"] = pack_unpack_large(G, B, K, max(2, min(args.kernel_reps, 20)))
+        result["hbm_bound_passes_large"] = hbm_bound_passes(G, B, K, max(3, min(args.kernel_reps, 24)))
+        torch.cuda.empty_cache()
+    if not args.no_sub:
+        # the same step on the other ImageNet-shaped workload and on the CIFAR stage
+        subs = []
+        for name, steps in (("config4", 30), ("config2", 100)):
+            if name == args.workload:
+                continue
+            w2 = get_workload(name)
+            ms2, run2 = time_stack(G, B, synth, w2, K, flags, steps, 5)
+            n2, l2 = w2.shapes[0].N, len(w2.shapes)
+            subs.append({"workload": w2.name, "K": K, "steps": steps, "ms_per_step": ms2,
+                         "value": n2 * l2 / (ms2 * 1e-3), "unit": result["unit"]})
+            del run2
+            torch.cuda.empty_cache()
+        result["sub_results"] = subs
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, K)
     print(json.dumps(result))

@@ -297,6 +297,16 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
 int abl_sgd_momentum(void* stream, int64_t n, float lr, float momentum, float weight_decay,
                      float* w, const float* grad, float* v);
 
+/* ---- measurement aid ---------------------------------------------------------------
+ * Not a step of the method: plain streaming kernels that show what this device's memory system
+ * delivers, the ceiling that the HBM-bound passes (Eq. 1-3, Eq. 8-10) are reported against.
+ *   mode 0: read `bytes` from src (dst: at least 16 writable bytes, normally left untouched)
+ *   mode 1: write `bytes` to dst (src ignored)
+ *   mode 2: copy `bytes` from src to dst (no overlap)
+ * src, dst: device pointers, 16-byte aligned, caller-owned; bytes a positive multiple of 16.
+ * Errors: ABL_ERR_ARG (mode, null / misaligned pointer), ABL_ERR_SHAPE (bytes), ABL_ERR_HIP. */
+int abl_hbm_probe(void* stream, int mode, const void* src, void* dst, size_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,7 @@ _SIGS = {
     "abl_stack_forward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
     "abl_stack_backward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
     "abl_sgd_momentum": (ctypes.c_int, [_vp, _i64, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]),
+    "abl_hbm_probe": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _sz]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -311,3 +312,9 @@ def abl_stack_backward(layers, K, skip_every, buf_s, buf_t, scratch, flags=0):
 def abl_sgd_momentum(w, grad, v, lr, momentum, weight_decay):
     _check(lib.abl_sgd_momentum(_stream(), w.numel(), lr, momentum, weight_decay, _ptr(w), _ptr(grad), _ptr(v)),
            "abl_sgd_momentum")
+
+
+# ---- measurement aid -------------------------------------------------------------------------
+def abl_hbm_probe(mode, src, dst, nbytes):
+    """mode 0 read src, 1 write dst, 2 copy src -> dst; nbytes a multiple of 16."""
+    _check(lib.abl_hbm_probe(_stream(), mode, _ptr(src), _ptr(dst), nbytes), "abl_hbm_probe")

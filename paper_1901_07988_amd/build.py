@@ -25,6 +25,7 @@ UNITS = {
     "conv_pointwise.hip": ["-ffp-contract=off"],
     "abl_api.hip": [],
     "abl_noalloc.hip": [],
+    "probe_kernels.hip": [],
 }
 
 

@@ -37,8 +37,9 @@ struct RowGeom {
 };
 
 // reduce == true bounds gridY (partials) and keeps >= 64 rows per block so that the
-// partial sums stay below 1/16 of the tensor's bytes.
-RowGeom make_geom(int64_t M, int C, int VEC, bool reduce) {
+// partial sums stay below 1/16 of the tensor's bytes.  rows: rows in flight per thread of the
+// element-wise kernel this geometry is for (its ROWS template parameter).
+RowGeom make_geom(int64_t M, int C, int VEC, bool reduce, int rows = kUnroll) {
   RowGeom g;
   g.CV = C / VEC;
   g.TX = g.CV < 64 ? g.CV : 64;
@@ -57,9 +58,9 @@ RowGeom make_geom(int64_t M, int C, int VEC, bool reduce) {
     const int64_t cap = (passes + kMaxPartialBlocks - 1) / kMaxPartialBlocks;
     if (rpt < cap) rpt = cap;
   } else {
-    // one batch of kUnroll rows per thread and no loop: measured best from 50 MB tensors up
+    // one batch of rows per thread and no loop: measured best from 50 MB tensors up
     // (pack on 205 MB: 4.5 -> 5.3 TB/s against 16 rows per thread)
-    if (rpt > kUnroll) rpt = kUnroll;
+    if (rpt > rows) rpt = rows;
   }
   if (rpt < 1) rpt = 1;
   g.rpt = (int)rpt;
@@ -284,7 +285,8 @@ __global__ __launch_bounds__(kFinThreads) void stats_finalize_kernel(const doubl
 
 // ------------------------------------------------------------------------------------------
 // Forward elementwise pass.  MODE 0: x -> A3 and codes (Eq. 1-3, 9).  MODE 1: a2 -> codes (Eq. 9).
-template <int K, int VEC, int MODE, bool STREAM>
+// ROWS: rows in flight per thread.
+template <int K, int VEC, int MODE, bool STREAM, int ROWS>
 __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __restrict__ in, int64_t M, int C,
                                                               RowGeom g, const float* __restrict__ stats,
                                                               float* __restrict__ a3,
@@ -308,17 +310,17 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
   load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
   word_t* __restrict__ pw = reinterpret_cast<word_t*>(packed);
   const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
-  for (int i = 0; i < g.rpt; i += kUnroll) {
-    float xv[kUnroll][VEC];
-    bool ok[kUnroll];
+  for (int i = 0; i < g.rpt; i += ROWS) {
+    float xv[ROWS][VEC];
+    bool ok[ROWS];
 #pragma unroll
-    for (int j = 0; j < kUnroll; ++j) {
+    for (int j = 0; j < ROWS; ++j) {
       const int64_t r = row0 + (int64_t)(i + j) * g.TY;
       ok[j] = (i + j) < g.rpt && r < M;
       load_vec<VEC>(in + (ok[j] ? r : 0) * C + p.c0, xv[j]);
     }
 #pragma unroll
-    for (int j = 0; j < kUnroll; ++j)
+    for (int j = 0; j < ROWS; ++j)
       if (ok[j]) {
         const int64_t r = row0 + (int64_t)(i + j) * g.TY;
         uint32_t word = 0;
@@ -721,10 +723,16 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_apply_kernel(const uint8_t*
   dx[e] = out;
 }
 
-// VEC used by the fast path for (K, C); 0 = use the flat fallback.
-int fast_vec(int K, int C) {
+// Channels per thread of the row kernels for (K, C); 0 = use the flat fallback.
+// wide: eight channels per thread where K = 4 allows (one 32-bit word of codes per thread and
+// row) - measured best for the pass that only reads fp32 (pack: 5.3 -> 5.9 TB/s on a 205 MB
+// tensor with one row per thread).  Kernels that WRITE fp32 rows take four channels: a lane then
+// stores 16 bytes next to its neighbours' instead of 32 bytes in two instructions that each
+// leave every other 16 bytes out (unpack 3.8 -> 5.4 TB/s, normalise-ReLU-pack 5.2 -> 5.9,
+// Eq. 6-8 5.5 -> 5.9).
+int fast_vec(int K, int C, bool wide) {
   if (K == 32) return 0;  // exact storage runs on the element-wise kernels
-  if (K == 4) return C % 8 == 0 ? 8 : (C % 4 == 0 ? 4 : 0);
+  if (K == 4 && wide && C % 8 == 0) return 8;
   return C % 4 == 0 ? 4 : 0;
 }
 
@@ -772,7 +780,8 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
   const int64_t E = M * C;
   const int64_t raw = (E * K + 7) / 8;
   const int64_t pbytes = (raw + 127) / 128 * 128;
-  const int vec = naive ? 0 : fast_vec(K, C);  // the baseline variant exists in the element-wise kernel only
+  // the baseline variant exists in the element-wise kernel only
+  const int vec = naive ? 0 : fast_vec(K, C, MODE == 1);
   if (vec == 0) {
     const int nv = naive ? 1 : 0;
     const int64_t threads = pbytes * 8 / K / 8;
@@ -786,19 +795,22 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
       flat_quant_pack_kernel<32, MODE><<<blocks, kThreads, 0, st>>>(in, E, C, pbytes, sp, a3, pk, nv, slope);
     return hip_status();
   }
-  const RowGeom g = make_geom(M, C, vec, false);
+  // rows in flight per thread (measured on 205 MB, 51 MB and 13 MB tensors): the pass that writes
+  // fp32 runs best with two, the read-only pack with one (K = 4) or two
+  constexpr int ROWS_WIDE = 1, ROWS = 2;
+  const RowGeom g = make_geom(M, C, vec, false, vec == 8 ? ROWS_WIDE : ROWS);
   const int pad = (int)(pbytes - raw);
   const bool stream = E * (int64_t)sizeof(float) >= kStreamBytes;
-#define ABL_QP(KK, VV)                                                                                   \
-  do {                                                                                                   \
-    if (stream)                                                                                          \
-      quant_pack_kernel<KK, VV, MODE, true><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope);  \
-    else                                                                                                 \
-      quant_pack_kernel<KK, VV, MODE, false><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope); \
+#define ABL_QP(KK, VV, RR)                                                                                   \
+  do {                                                                                                       \
+    if (stream)                                                                                              \
+      quant_pack_kernel<KK, VV, MODE, true, RR><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope);  \
+    else                                                                                                     \
+      quant_pack_kernel<KK, VV, MODE, false, RR><<<grid_of(g), kThreads, 0, st>>>(in, M, C, g, sp, a3, packed, pad, slope); \
   } while (0)
-  if (K == 4 && vec == 8) ABL_QP(4, 8);
-  else if (K == 4) ABL_QP(4, 4);
-  else ABL_QP(8, 4);
+  if (K == 4 && vec == 8) ABL_QP(4, 8, ROWS_WIDE);
+  else if (K == 4) ABL_QP(4, 4, ROWS);
+  else ABL_QP(8, 4, ROWS);
 #undef ABL_QP
   return hip_status();
 }
@@ -817,7 +829,7 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
                   float* a2t, bool act, float slope) {
   const int ac = act ? 1 : 0;
   const float* sp = static_cast<const float*>(stats);
-  const int vec = fast_vec(K, C);
+  const int vec = fast_vec(K, C, false);
   if (vec == 0) {
     const int64_t E = M * C;
     const unsigned blocks = (unsigned)((E + kThreads - 1) / kThreads);
@@ -836,8 +848,7 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
   do {                                                                                              \
     unpack_kernel<KK, VV, false><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t, ac, slope); \
   } while (0)
-  if (K == 4 && vec == 8) ABL_UP(4, 8);
-  else if (K == 4) ABL_UP(4, 4);
+  if (K == 4) ABL_UP(4, 4);
   else ABL_UP(8, 4);
 #undef ABL_UP
   return hip_status();
@@ -848,7 +859,7 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
                   const DwSum* dwsum, float slope) {
   const float* sp = static_cast<const float*>(stats);
   double* partial = static_cast<double*>(scratch);
-  const int vec = fast_vec(K, C);
+  const int vec = fast_vec(K, C, false);
   const RowGeom gr = make_geom(M, C, vec ? vec : 1, true);
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
   if (vec == 0) {
@@ -858,8 +869,6 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
       flat_bwd_reduce_kernel<8><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
     else
       flat_bwd_reduce_kernel<32><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
-  } else if (K == 4 && vec == 8) {
-    bwd_reduce_kernel<4, 8><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   } else if (K == 4) {
     bwd_reduce_kernel<4, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   } else {
@@ -879,7 +888,7 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
   const double* partial = static_cast<const double*>(scratch);
   float* means = reinterpret_cast<float*>(static_cast<char*>(scratch) + bn_means_offset(C));
   const uint8_t* pk = static_cast<const uint8_t*>(packed);
-  const int vec = fast_vec(K, C);
+  const int vec = fast_vec(K, C, false);
   const int nfin = (C + 15) / 16;
   if (dwsum != nullptr) {
     // many small copies (one per pixel tile): 16 interleaved parts per output and a tree;
@@ -917,8 +926,7 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
     if (accum) ABL_APPLY1(KK, VV, true); \
     else ABL_APPLY1(KK, VV, false);   \
   } while (0)
-  if (K == 4 && vec == 8) ABL_APPLY(4, 8);
-  else if (K == 4) ABL_APPLY(4, 4);
+  if (K == 4) ABL_APPLY(4, 4);
   else ABL_APPLY(8, 4);
 #undef ABL_APPLY1
 #undef ABL_APPLY

@@ -108,8 +108,10 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
   // loads and its LDS writes
   constexpr int WITEMS = CHUNKED ? BN * (CHC / 4) / kThreads : 1;
   static_assert(!CHUNKED || BN * (CHC / 4) % kThreads == 0, "whole staging items per thread");
-  float4 wreg[WITEMS];
-  float4 creg = make_float4(0.f, 0.f, 0.f, 0.f);
+  // (first-class vector values: as HIP's float4 structs this array was left in scratch memory by
+  // the dgrad instantiation, with a full wait before every spill)
+  floatx4 wreg[WITEMS];
+  floatx4 creg = floatx4{0.f, 0.f, 0.f, 0.f};
   auto load_chunk = [&](int c0) __attribute__((always_inline)) {
 #pragma unroll
     for (int it = 0; it < WITEMS; ++it) {
@@ -117,15 +119,15 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
       if (MODE == 0) {
         const int n = idx % BN, q = idx / BN;
         const float* src = wgt + (int64_t)(c0 + 4 * q) * ldw + n0 + n;
-        wreg[it] = make_float4(src[0], src[ldw], src[2 * ldw], src[3 * ldw]);
+        wreg[it] = floatx4{src[0], src[ldw], src[2 * ldw], src[3 * ldw]};
       } else {
         const int n = idx / (CHC / 4), q = idx % (CHC / 4);
-        wreg[it] = *reinterpret_cast<const float4*>(wgt + (int64_t)(n0 + n) * ldw + c0 + 4 * q);
+        wreg[it] = *reinterpret_cast<const floatx4*>(wgt + (int64_t)(n0 + n) * ldw + c0 + 4 * q);
       }
     }
     if (FUSE != 0 && tid < NCONST * (CHC / 4)) {
       const int pl = tid / (CHC / 4), q = tid % (CHC / 4);
-      creg = *reinterpret_cast<const float4*>(stats + (int64_t)planes[pl] * Kd + c0 + 4 * q);
+      creg = *reinterpret_cast<const floatx4*>(stats + (int64_t)planes[pl] * Kd + c0 + 4 * q);
     }
   };
   auto store_chunk = [&](int buf) __attribute__((always_inline)) {
@@ -134,11 +136,11 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
     for (int it = 0; it < WITEMS; ++it) {
       const int idx = tid + it * kThreads;
       const int n = MODE == 0 ? idx % BN : idx / (CHC / 4), q = MODE == 0 ? idx / BN : idx % (CHC / 4);
-      *reinterpret_cast<float4*>(&W[n * LDW + 4 * q]) = wreg[it];
+      *reinterpret_cast<floatx4*>(&W[n * LDW + 4 * q]) = wreg[it];
     }
     if (FUSE != 0 && tid < NCONST * (CHC / 4)) {
       const int pl = tid / (CHC / 4), q = tid % (CHC / 4);
-      *reinterpret_cast<float4*>(&Cs[buf * NCONST * CH + pl * CH + 4 * q]) = creg;
+      *reinterpret_cast<floatx4*>(&Cs[buf * NCONST * CH + pl * CH + 4 * q]) = creg;
     }
   };
   if (CHUNKED) {

@@ -25,7 +25,9 @@ def test_bench_line_has_the_agreed_fields():
     assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2
     assert d["vs_baseline"] is None and d["higher_is_better"] is True and d["data"] == "synthetic"
     assert d["dtype"] == "f32" and "workload" in d["config"] and "model" not in d["config"]
-    assert d["value"] > 0 and abs(d["value"] - 128 * 18 / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
+    # the headline is the ImageNet deep-stage bottleneck stack: 36 layers, N = 64
+    assert d["config"]["workload"].startswith("config5") and d["config"]["layers"] == 36
+    assert d["value"] > 0 and abs(d["value"] - 64 * 36 / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
     roof = d["roofline"]
     for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
         assert key in roof, key
@@ -35,6 +37,14 @@ def test_bench_line_has_the_agreed_fields():
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1
+    assert cpu["config1_single_thread"]["cores"] == 1 and cpu["config1_single_thread"]["value"] > 0
     assert abs(d["activation_bytes"]["ratio"] - 4 / 32) < 0.01       # K/32 of fp32 (+ row padding)
+    big = d["hbm_bound_passes_large"]
+    for name in ("read", "write", "copy"):
+        assert 0 < big["ceiling_gbs"][name] < 8000.0
     for name in ("pack", "unpack", "bn_relu_pack"):
-        assert d["pack_unpack_gbs"][name] > 0 and d["pack_unpack_gbs_large"][name] > 0
+        assert d["pack_unpack_gbs"][name] > 0
+    for name in ("bn_stats", "pack", "unpack", "bn_relu_pack", "bn_bwd"):
+        assert 0 < big[name]["frac_of_peak"] < 1 and big[name]["gbs"] > 0
+    subs = d["sub_results"]
+    assert [x["workload"][:7] for x in subs] == ["config4", "config2"] and all(x["value"] > 0 for x in subs)
