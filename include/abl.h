@@ -26,7 +26,8 @@
  *   - `flags` is a bit set of the ABL_* flags an entry point documents; unknown bits are an
  *     ABL_ERR_ARG.
  *   - return value: ABL_OK or an ABL_ERR_* code; on error nothing was enqueued
- *     (ABL_ERR_HIP: a launch failed, earlier launches of the call may have run).
+ *     (ABL_ERR_HIP: a launch failed, earlier launches of the call may have run).  The stack
+ *     calls validate every layer's shape and pointers before their first launch.
  *   - preconditions that are NOT checked: finite inputs, gamma != 0.
  *
  * Packed store (opaque to callers, specified because parity is on bytes):
@@ -284,6 +285,21 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
 int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
                        int32_t skip_every, float* buf_s, float* buf_t,
                        void* scratch, size_t scratch_bytes);
+
+/* The same two calls with an inspection hook, for parity tests that check every layer against a
+ * reference on the layer's own inputs: before layer i runs, its input x_i [N,H,W,Cin] (forward)
+ * resp. its incoming gradient dy_i [N,Ho,Wo,Cout] (backward) is copied to trace[i].  `trace` is a
+ * host array of L device pointers (caller-owned, 16-byte aligned, each large enough for that
+ * tensor); NULL entries, or trace == NULL, copy nothing.  Results are those of the plain calls bit
+ * for bit (the copies only read).  With an identity shortcut around a group, the value added to
+ * the group's output is the input of its first layer, and the gradient its first layer
+ * accumulates into is the incoming gradient of its last layer. */
+int abl_stack_forward_traced(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                             int32_t skip_every, float* buf_s, float* buf_t,
+                             void* scratch, size_t scratch_bytes, float* const* trace);
+int abl_stack_backward_traced(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                              int32_t skip_every, float* buf_s, float* buf_t,
+                              void* scratch, size_t scratch_bytes, float* const* trace);
 
 /* ---- parameter update -----------------------------------------------------------
  * SGD with momentum and weight decay, the update rule of the paper's experiments

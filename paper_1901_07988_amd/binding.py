@@ -83,6 +83,10 @@ _SIGS = {
     "abl_stack_buffer_bytes": (_sz, [_lay, _i32]),
     "abl_stack_forward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
     "abl_stack_backward": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz]),
+    "abl_stack_forward_traced": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz,
+                                                ctypes.POINTER(_vp)]),
+    "abl_stack_backward_traced": (ctypes.c_int, [_vp, _lay, _i32, ctypes.c_int, _u32, _i32, _vp, _vp, _vp, _sz,
+                                                 ctypes.POINTER(_vp)]),
     "abl_sgd_momentum": (ctypes.c_int, [_vp, _i64, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]),
     "abl_hbm_probe": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _sz]),
 }
@@ -307,6 +311,27 @@ def abl_stack_forward(layers, K, skip_every, buf_s, buf_t, scratch, flags=0):
 def abl_stack_backward(layers, K, skip_every, buf_s, buf_t, scratch, flags=0):
     _check(lib.abl_stack_backward(_stream(), layers, len(layers), K, flags, skip_every, _ptr(buf_s), _ptr(buf_t),
                                   _ptr(scratch), scratch.numel() * scratch.element_size()), "abl_stack_backward")
+
+
+def _trace_array(trace, n):
+    arr = (_vp * n)()
+    for i in range(n):
+        arr[i] = _ptr(trace[i]) if trace is not None and trace[i] is not None else None
+    return arr
+
+
+def abl_stack_forward_traced(layers, K, skip_every, buf_s, buf_t, scratch, trace, flags=0):
+    """trace: list of len(layers) device tensors (or None entries) that receive each layer's input."""
+    _check(lib.abl_stack_forward_traced(_stream(), layers, len(layers), K, flags, skip_every, _ptr(buf_s),
+                                        _ptr(buf_t), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                        _trace_array(trace, len(layers))), "abl_stack_forward_traced")
+
+
+def abl_stack_backward_traced(layers, K, skip_every, buf_s, buf_t, scratch, trace, flags=0):
+    """trace: list of len(layers) device tensors (or None entries) that receive each layer's incoming gradient."""
+    _check(lib.abl_stack_backward_traced(_stream(), layers, len(layers), K, flags, skip_every, _ptr(buf_s),
+                                         _ptr(buf_t), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                         _trace_array(trace, len(layers))), "abl_stack_backward_traced")
 
 
 def abl_sgd_momentum(w, grad, v, lr, momentum, weight_decay):

@@ -582,8 +582,10 @@ void layer_buffers(const abl_layer* layers, int L, int skip_every, int i, bool* 
   *y_is_s = !*x_is_s;
 }
 
+// backward: which per-layer pointers the direction needs (parameters, store and statistics always;
+// the gradient outputs in the backward pass).  Everything is validated before the first launch.
 int check_stack(const abl_layer* layers, int L, int K, int skip_every, const float* s, const float* t,
-                void* scratch, size_t scratch_bytes) {
+                void* scratch, size_t scratch_bytes, bool backward) {
   if (layers == nullptr || L < 1 || skip_every < 0) return ABL_ERR_ARG;
   if (int e = check_k(K)) return e;
   if (bad_ptr(s) || bad_ptr(t) || bad_ptr(scratch)) return ABL_ERR_ARG;
@@ -597,8 +599,22 @@ int check_stack(const abl_layer* layers, int L, int K, int skip_every, const flo
         return ABL_ERR_SHAPE;
     }
   }
+  for (int i = 0; i < L; ++i) {
+    const abl_layer& l = layers[i];
+    if (bad_ptr(l.W) || bad_ptr(l.packed) || bad_ptr(l.stats)) return ABL_ERR_ARG;
+    if (!backward && (bad_ptr(l.gamma) || bad_ptr(l.beta))) return ABL_ERR_ARG;
+    if (backward && (bad_ptr(l.dW) || bad_ptr(l.dgamma) || bad_ptr(l.dbeta))) return ABL_ERR_ARG;
+  }
   if (scratch_bytes < abl_stack_scratch_bytes(layers, L, K)) return ABL_ERR_SCRATCH;
   return ABL_OK;
+}
+
+// Inspection copy of a layer's input (or incoming gradient) before the layer runs.
+int trace_copy(hipStream_t st, float* const* trace, int i, const float* src, size_t floats) {
+  if (trace == nullptr || trace[i] == nullptr) return ABL_OK;
+  return hipMemcpyAsync(trace[i], src, floats * sizeof(float), hipMemcpyDeviceToDevice, st) == hipSuccess
+             ? ABL_OK
+             : ABL_ERR_HIP;
 }
 
 }  // namespace
@@ -609,11 +625,14 @@ extern "C" {
 // of a group reads S and writes T, middle layers run in place on T (a layer's input is dead
 // once A3 is in the workspace), the last layer writes S = conv + S; layers outside the groups
 // alternate between the two buffers (layer_buffers).
-int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
-                      int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
-                      size_t scratch_bytes) {
+int abl_stack_forward_traced(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                             int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                             size_t scratch_bytes, float* const* trace) {
   if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_NAIVE_FWD)) return ABL_ERR_ARG;
-  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes, false)) return e;
+  if (trace != nullptr)
+    for (int i = 0; i < L; ++i)
+      if (trace[i] != nullptr && !aligned16(trace[i])) return ABL_ERR_ARG;
   const size_t xbytes = stack_xpart_bytes(layers, L);
   double* xpart = static_cast<double*>(scratch);
   void* lscratch = static_cast<char*>(scratch) + xbytes;
@@ -626,8 +645,7 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
     const float* x = x_is_s ? buf_s : buf_t;
     float* y = y_is_s ? buf_s : buf_t;
     const float* skip = gi.in_group && gi.last && gi.shortcut ? buf_s : nullptr;
-    if (bad_ptr(l.W) || bad_ptr(l.gamma) || bad_ptr(l.beta) || bad_ptr(l.packed) || bad_ptr(l.stats))
-      return ABL_ERR_ARG;
+    if (int e = trace_copy((hipStream_t)stream, trace, i, x, (size_t)rows_of(l.shape) * l.shape.Cin)) return e;
     // layer i's convolution leaves the first-pass statistics of its output (= layer i+1's input)
     // in `xpart` when it can; layer i+1 then only runs the finalize kernel
     int out_nb = 0;
@@ -640,19 +658,28 @@ int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, u
   return ABL_OK;
 }
 
+int abl_stack_forward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                      int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                      size_t scratch_bytes) {
+  return abl_stack_forward_traced(stream, layers, L, K, flags, skip_every, buf_s, buf_t, scratch, scratch_bytes,
+                                  nullptr);
+}
+
 // Mirror image: S holds the gradient of the residual stream.  The last layer of a group reads
 // S and writes T, middle layers run in place on T, the first layer adds its dx into S
 // (gradients through a shortcut are copied and added, Sec. 3.4).  Without a shortcut the
 // first layer overwrites S.
-int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
-                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
-                       size_t scratch_bytes) {
+int abl_stack_backward_traced(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                              int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                              size_t scratch_bytes, float* const* trace) {
   if (flags & ~(uint32_t)ABL_MATH_BF16) return ABL_ERR_ARG;
-  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes)) return e;
+  if (int e = check_stack(layers, L, K, skip_every, buf_s, buf_t, scratch, scratch_bytes, true)) return e;
+  if (trace != nullptr)
+    for (int i = 0; i < L; ++i)
+      if (trace[i] != nullptr && !aligned16(trace[i])) return ABL_ERR_ARG;
   const size_t xbytes = stack_xpart_bytes(layers, L);
   for (int i = L - 1; i >= 0; --i) {
     const abl_layer& l = layers[i];
-    if (bad_ptr(l.dW) || bad_ptr(l.dgamma) || bad_ptr(l.dbeta)) return ABL_ERR_ARG;
     const GroupInfo gi = group_info(layers, L, skip_every, i);
     bool x_is_s, y_is_s;
     layer_buffers(layers, L, skip_every, i, &x_is_s, &y_is_s);
@@ -660,12 +687,23 @@ int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, 
     float* dx = x_is_s ? buf_s : buf_t;
     uint32_t f = flags;
     if (gi.in_group && gi.first && gi.shortcut) f |= ABL_ACCUM_DX;
+    const abl_shape& sh = l.shape;
+    const size_t out_floats = (size_t)sh.N * out_dim(sh.H, sh.pad, sh.R, sh.stride) *
+                              out_dim(sh.W, sh.pad, sh.S, sh.stride) * sh.Cout;
+    if (int e = trace_copy((hipStream_t)stream, trace, i, dy, out_floats)) return e;
     if (int e = abl_backward(stream, &l.shape, K, f, l.packed, l.stats, dy, l.W,
                              static_cast<char*>(scratch) + xbytes, scratch_bytes - xbytes, dx, l.dW, l.dgamma,
                              l.dbeta))
       return e;
   }
   return ABL_OK;
+}
+
+int abl_stack_backward(void* stream, const abl_layer* layers, int32_t L, int K, uint32_t flags,
+                       int32_t skip_every, float* buf_s, float* buf_t, void* scratch,
+                       size_t scratch_bytes) {
+  return abl_stack_backward_traced(stream, layers, L, K, flags, skip_every, buf_s, buf_t, scratch, scratch_bytes,
+                                   nullptr);
 }
 
 int abl_sgd_momentum(void* stream, int64_t n, float lr, float momentum, float weight_decay, float* w,

@@ -88,17 +88,35 @@ class StackRun:
         self.buf_s = torch.zeros(nb // 4, dtype=torch.float32, device="cuda")
         self.buf_t = torch.zeros(nb // 4, dtype=torch.float32, device="cuda")
         self.first, self.last = layers[0][0], layers[-1][0]
+        self.shapes = [l[0] for l in layers]
 
     def load(self, a):
         self.buf_s[: a.size].copy_(torch.from_numpy(np.ascontiguousarray(a)).view(-1))
 
-    def forward(self):
-        B.abl_stack_forward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
-                            flags=self.flags)
+    def forward(self, trace=False):
+        """trace=True: returns one device tensor per layer holding that layer's input (inspection
+        hook of the library; results are unchanged)."""
+        if not trace:
+            B.abl_stack_forward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
+                                flags=self.flags)
+            return None
+        tr = [torch.empty(d["shape"][0] * d["shape"][1] * d["shape"][2] * d["shape"][3], dtype=torch.float32,
+                          device="cuda") for d in self.descs]
+        B.abl_stack_forward_traced(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch, tr,
+                                   flags=self.flags)
+        return tr
 
-    def backward(self):
-        B.abl_stack_backward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
-                             flags=self.flags & ~B.ABL_NAIVE_FWD)
+    def backward(self, trace=False):
+        """trace=True: returns one device tensor per layer holding that layer's incoming gradient."""
+        flags = self.flags & ~B.ABL_NAIVE_FWD
+        if not trace:
+            B.abl_stack_backward(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch,
+                                 flags=flags)
+            return None
+        tr = [torch.empty(int(np.prod(out_shape(s))), dtype=torch.float32, device="cuda") for s in self.shapes]
+        B.abl_stack_backward_traced(self.layers, self.K, self.skip_every, self.buf_s, self.buf_t, self.scratch, tr,
+                                    flags=flags)
+        return tr
 
     def output(self):
         n = int(np.prod(out_shape(self.last)))

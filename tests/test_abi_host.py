@@ -76,6 +76,29 @@ def test_stack_plan_validation(B):
     assert B.lib.abl_stack_forward(None, broken, 2, 4, 0, 0, 16, 32, 48, 1 << 30) == B.ABL_ERR_SHAPE
 
 
+def test_stack_calls_validate_every_layer_before_the_first_launch(B):
+    """A null or misaligned pointer in the LAST layer is reported as an argument error: had the
+    layers before it been enqueued first, the call would have launched kernels on the made-up
+    addresses of this test (and, on a machine without a GPU, returned a launch failure instead)."""
+    shapes = [(2, 8, 8, 16, 16, 3, 3, 1, 1)] * 3
+    full = dict(W=16, gamma=32, beta=48, packed=64, stats=80, dW=96, dgamma=112, dbeta=128)
+    for direction, fields in (("forward", ("W", "gamma", "beta", "packed", "stats")),
+                              ("backward", ("W", "packed", "stats", "dW", "dgamma", "dbeta"))):
+        fn = getattr(B.lib, "abl_stack_" + direction)
+        for name in fields:
+            for bad in (None, 24):                       # null, not 16-byte aligned
+                descs = [dict(shape=t, **full) for t in shapes]
+                descs[-1][name] = bad
+                layers = B.make_layers(descs)
+                assert fn(None, layers, 3, 4, 0, 0, 16, 32, 48, 1 << 30) == B.ABL_ERR_ARG, (direction, name, bad)
+    # a workspace that is too small is reported before any launch as well
+    layers = B.make_layers([dict(shape=t, **full) for t in shapes])
+    assert B.lib.abl_stack_forward(None, layers, 3, 4, 0, 0, 16, 32, 48, 1024) == B.ABL_ERR_SCRATCH
+    trace = (ctypes.c_void_p * 3)(16, 32, 40)            # misaligned inspection pointer
+    assert B.lib.abl_stack_forward_traced(None, layers, 3, 4, 0, 0, 16, 32, 48, 1 << 30, trace) == B.ABL_ERR_ARG
+    assert B.lib.abl_stack_backward_traced(None, layers, 3, 4, 0, 0, 16, 32, 48, 1 << 30, trace) == B.ABL_ERR_ARG
+
+
 def test_exact_storage_sizes_and_k_validation(B):
     """K = 32 keeps the fp32 tensor (alpha = 1, Sec. 3.4); the fused entry points refuse it."""
     t = (4, 32, 32, 16, 16, 3, 3, 1, 1)
