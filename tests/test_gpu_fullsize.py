@@ -1,9 +1,10 @@
 """Parity at the full sizes of the workloads, in the launch configuration bench.py times.
 
 Every distinct layer shape of the five workloads runs abl_forward / abl_backward once at its
-real batch size.  What the oracle can afford in full is compared in full (statistics, packed
-bytes, the BN backward stage); the convolutions are compared on sampled outputs that the
-oracle evaluates one by one; what remains is checked through identities that hold at any size."""
+real batch size and every output tensor is compared with the oracle in full.  The benchmark
+stack is also compared end to end with the oracle's own chain; there the two sides quantize
+activations that differ by conv rounding, so what differs is checked to be explained by the
+codes that differ (tests/test_gpu_teacher_forced.py holds the layer-by-layer statement)."""
 import numpy as np
 import pytest
 
@@ -12,22 +13,6 @@ from paper_1901_07988_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
-
-
-def close_but_for_flips(a, b, tol=TOL, bad_frac=1e-4, max_l2=1e-3):
-    """Stack-level comparison.  Below the first layer the two sides quantize activations that
-    differ by fp32 rounding of the convolutions, so a handful of elements that sit within 1e-6
-    of a bin edge (or of the ReLU threshold) take the other code on one side; each such element
-    moves single entries of dx by O(1) and of dW by O(step * dy).  Everything else must agree to
-    the usual bar: at most `bad_frac` of the elements may exceed it, and the L2 error stays below
-    `max_l2`.  (A flipped ReLU mask in layer l perturbs the whole receptive-field cone of that
-    element in the dx of the layers below, so for a deep stack the allowance is larger.)"""
-    a = np.asarray(a, np.float64)
-    b = np.asarray(b, np.float64)
-    scale = max(float(np.max(np.abs(b))), 1e-30)
-    bad = np.count_nonzero(np.abs(a - b) > tol * scale)
-    l2 = float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
-    return bad <= max(1, int(a.size * bad_frac)) and l2 < max_l2
 
 
 @pytest.fixture(scope="module")
@@ -59,11 +44,8 @@ def rel(a, b):
 @pytest.mark.parametrize("K", [4, 8])
 def test_full_size_layer(G, oracle, case, K):
     import torch
-    from paper_1901_07988_amd import binding as B
     o = oracle
     s, xd, aff = case
-    if K == 8 and s.E > 20_000_000:
-        pytest.skip("K=8 at the largest tensor adds nothing over K=4 but minutes of CPU time")
     print("case full", s.as_tuple(), K, flush=True)
     os_ = o.Shape(*s.as_tuple())
     x, w, gamma, beta, dy = synth.draw_layer(s, synth.DEFAULT_SEED, xd, aff)
@@ -73,6 +55,7 @@ def test_full_size_layer(G, oracle, case, K):
     # point exposes it, and must produce the same packed bytes as the layer call
     a3_gpu, packed_stage = G.run_bn_relu_pack(x, run.stats, K)
     assert packed_stage.tobytes() == run.packed.cpu().numpy().tobytes()
+    del packed_stage
 
     # statistics, A3 and codes: everything, bit for bit
     mean, var = o.bn_stats(x)
@@ -83,50 +66,26 @@ def test_full_size_layer(G, oracle, case, K):
     np.testing.assert_array_equal(sd["rstd"], rstd)
     a2, a3 = o.bn_relu(x, mean, rstd, gamma, beta)
     assert a3_gpu.tobytes() == a3.tobytes()
+    del a3_gpu
     q = o.quantize(a2, gamma, beta, K)
     assert run.packed.cpu().numpy().tobytes() == o.pack_codes(q, K).tobytes()
     assert run.packed.numel() + run.stats.numel() <= (K / 32 + 0.01) * 4 * s.E
     del a2
 
-    # forward output on sampled pixels (corners, edges, interior)
-    rng = np.random.default_rng(5)
-    pts = [(0, 0, 0), (s.N - 1, s.Ho - 1, s.Wo - 1), (s.N // 2, 0, s.Wo - 1), (1, s.Ho - 1, 0)]
-    pts += [(int(rng.integers(s.N)), int(rng.integers(s.Ho)), int(rng.integers(s.Wo))) for _ in range(60)]
-    ref = o.conv_fwd_at(a3, w, os_, pts)
-    got = np.stack([y[p] for p in pts])
-    scale = float(np.max(np.abs(ref)))
-    assert np.max(np.abs(got - ref)) <= TOL * scale
-    del a3
+    # forward output: the whole tensor
+    assert rel(y, o.conv_fwd(a3, w, os_)) < TOL
+    del a3, y
 
-    # backward
+    # backward: every output in full.  dA3 sits in the workspace after the call.
     dx, dw, dg, db = run.backward(dy, w)
     da3_gpu = run.scratch[: 4 * s.E].view(torch.float32).cpu().numpy().reshape(x.shape)
-    pts = [(0, 0, 0), (s.N - 1, s.H - 1, s.W - 1), (s.N // 2, 0, s.W - 1), (1, s.H - 1, 0)]
-    pts += [(int(rng.integers(s.N)), int(rng.integers(s.H)), int(rng.integers(s.W))) for _ in range(60)]
-    ref = o.conv_dgrad_at(dy, w, os_, pts)
-    got = np.stack([da3_gpu[p] for p in pts])
-    assert np.max(np.abs(got - ref)) <= TOL * float(np.max(np.abs(ref)))
-
+    da3 = o.conv_dgrad(dy, w, os_)
+    assert rel(da3_gpu, da3) < TOL
+    del da3_gpu
     a2t = o.dequantize(q, gamma, beta, K)
-    a3t = np.maximum(a2t, np.float32(0))
-    ent = [(0, 0, 0), (s.R - 1, s.S - 1, s.Cin - 1), (s.R // 2, s.S // 2, s.Cin // 2)]
-    ent += [(int(rng.integers(s.R)), int(rng.integers(s.S)), int(rng.integers(s.Cin))) for _ in range(5)]
-    ref = o.conv_wgrad_at(a3t, dy, os_, ent)
-    got = np.stack([dw[e] for e in ent])
-    assert np.max(np.abs(got - ref)) <= TOL * max(float(np.max(np.abs(ref))), float(np.max(np.abs(dw))))
-    del a3t
-
-    # BN backward: the oracle on the GPU path's own dA3 is not a parity statement, so the stage is
-    # checked on an independent random gradient, in full ...
-    g_in = rng.standard_normal(x.shape).astype(np.float32)
-    dx_ref, dg_ref, db_ref = o.bn_relu_bwd(a2t, g_in, rstd, gamma, beta)
-    dx_s, dg_s, db_s = G.run_bn_bwd(run.packed.cpu().numpy(), run.stats, g_in, K)
-    assert rel(dx_s, dx_ref) < TOL and rel(dg_s, dg_ref) < TOL and rel(db_s, db_ref) < TOL
-    # ... and the layer call must be that stage applied to its own dA3.  (Not bit for bit: where
-    # the layer takes the Eq. 6-7 sums in the epilogue of its dgrad kernel they are added in
-    # another order, per lane in fp32 for 1x1 layers, than in the stage's fp64 passes.)
-    dx_c, dg_c, db_c = G.run_bn_bwd(run.packed.cpu().numpy(), run.stats, da3_gpu, K)
-    assert rel(dx, dx_c) < 1e-5 and rel(dg, dg_c) < 1e-5 and rel(db, db_c) < 1e-5
+    assert rel(dw, o.conv_wgrad(np.maximum(a2t, np.float32(0)), dy, os_)) < TOL
+    dx_ref, dg_ref, db_ref = o.bn_relu_bwd(a2t, da3, rstd, gamma, beta)
+    assert rel(dx, dx_ref) < TOL and rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
     # Eq. 8 summed over a channel: the first two terms cancel, the third leaves
     # sum(dx) = -rstd * Mean(A1~ * dA1) * sum(A1~), with Mean(A1~ * dA1) = gamma * dgamma / M
     a1t_sum = ((a2t.reshape(-1, s.Cin).sum(0, dtype=np.float64) - s.M * beta.astype(np.float64))
@@ -136,9 +95,32 @@ def test_full_size_layer(G, oracle, case, K):
     assert np.max(np.abs(got - expect)) < 1e-5 * np.abs(dx).reshape(-1, s.Cin).sum(0, dtype=np.float64).max() + 1e-3
 
 
-def test_bench_stack_full_size(G, oracle):
-    """The benchmark workload itself (18 layers, N=128): forward output and all gradients against
-    the oracle run on the same stack."""
+def flipped_pixels(got_bytes, ref_bytes, s, K):
+    """Boolean [N,H,W] map of the pixels that hold at least one code that differs."""
+    diff = np.flatnonzero(got_bytes != ref_bytes)
+    m = np.zeros(s.N * s.H * s.W, bool)
+    m[(diff * (8 // K)) // s.Cin] = True          # a byte holds 8/K codes of one pixel (Cin is even)
+    return m.reshape(s.N, s.H, s.W)
+
+
+def dilate(mask, r):
+    """Every pixel within Chebyshev distance r (same image) of a set pixel."""
+    if r == 0:
+        return mask
+    from scipy.ndimage import maximum_filter
+    return maximum_filter(mask, size=(1, 2 * r + 1, 2 * r + 1), mode="constant", cval=False)
+
+
+def test_bench_stack_end_to_end_differences_are_explained_by_flipped_codes(G, oracle):
+    """The CIFAR stage (18 layers, N=128) against the oracle's own chain.  The forward is exact on
+    both sides up to conv rounding, so y agrees to 1e-4; a few codes per layer sit within that
+    rounding of a bin edge or of the ReLU threshold and come out differently.  A different code at
+    pixel p of layer l changes dx of layer l at p, and from there the stack's input gradient only
+    inside the receptive-field cone below p (radius l for l 3x3 layers).  So: every element of the
+    input gradient that is out of tolerance must lie in such a cone, the number of differing bytes
+    is bounded, and everything outside the cones meets the bar (widened by the one indirect path -
+    the per-channel means of Eq. 8, through which a flipped mask of layer l moves every dx of its
+    channel by about |dA3| / M)."""
     o = oracle
     wl = synth.config2()
     x, layers, dy = synth.draw_stack(wl, synth.DEFAULT_SEED)
@@ -152,25 +134,51 @@ def test_bench_stack_full_size(G, oracle):
         run.backward()
         outs[K] = (y, run.input_grad(), run)
     assert outs[4][0].tobytes() == outs[8][0].tobytes()          # the forward never sees the codes
-    K = 4
-    y, dx, run = outs[K]
     ol = [(o.Shape(*s.as_tuple()), w, g, b) for s, w, g, b in layers]
-    y_ref, saved = o.stack_forward(x, ol, K, np.float32, wl.skip_every)
-    dx_ref, grads = o.stack_backward(saved, ol, dy, np.float32, wl.skip_every)
-    assert rel(y, y_ref) < TOL
-    assert run.descs[0]["packed"].cpu().numpy().tobytes() == saved[0].store.tobytes()
-    for d, sv in zip(run.descs, saved):
-        got = d["packed"].cpu().numpy()
-        assert np.count_nonzero(got != sv.store) <= sv.store.size // 2000
-    assert close_but_for_flips(dx, dx_ref, TOL, 0.02, 5e-3)
-    for d, (dw, dg, db) in zip(run.descs, grads):
-        assert close_but_for_flips(d["dW"].cpu().numpy(), dw, 20 * TOL, 0.01, 5e-3)
-        assert close_but_for_flips(d["dgamma"].cpu().numpy(), dg, 50 * TOL, 0.1, 1e-2)
-        assert close_but_for_flips(d["dbeta"].cpu().numpy(), db, 50 * TOL, 0.1, 1e-2)
+    for K in (4, 8):
+        y, dx, run = outs[K]
+        y_ref, saved = o.stack_forward(x, ol, K, np.float32, wl.skip_every)
+        dx_ref, grads = o.stack_backward(saved, ol, dy, np.float32, wl.skip_every)
+        assert rel(y, y_ref) < TOL
+        assert run.descs[0]["packed"].cpu().numpy().tobytes() == saved[0].store.tobytes()
+        cone = np.zeros(dx.shape[:3], bool)
+        nflip = 0
+        for l, (d, sv) in enumerate(zip(run.descs, saved)):
+            got = d["packed"].cpu().numpy()
+            f = flipped_pixels(got, sv.store, layers[l][0], K)
+            n = int(np.count_nonzero(got != sv.store))
+            assert n <= sv.store.size // 2000, (l, n)
+            nflip += n
+            cone |= dilate(f, l)
+        scale = float(np.max(np.abs(dx_ref)))
+        err = np.max(np.abs(dx.astype(np.float64) - dx_ref), axis=3)      # per pixel, over channels
+        outside = err[~cone]
+        print("K=%d: %d differing bytes in %d layers, cones cover %.1f %% of the pixels; max error outside %.2g, "
+              "inside %.2g (relative to max|dx|)" % (K, nflip, len(layers), 100.0 * cone.mean(),
+                                                     outside.max() / scale if outside.size else 0.0,
+                                                     err.max() / scale), flush=True)
+        bad = err > 10 * TOL * scale
+        assert not np.any(bad & ~cone), "an out-of-tolerance input-gradient element lies outside every cone"
+        assert nflip > 0 or not np.any(err > TOL * scale)
+        # the top layer's parameter gradients see the exact dy: they differ only through that
+        # layer's own differing codes (one quantization step times |dy| per code for dW)
+        top = len(layers) - 1
+        dw_top, dg_top, db_top = grads[top]
+        ntop = int(np.count_nonzero(run.descs[top]["packed"].cpu().numpy() != saved[top].store))
+        allow = TOL + ntop * 6.0 / (1 << K) * float(np.max(np.abs(dy))) / max(float(np.max(np.abs(dw_top))), 1e-30)
+        assert rel(run.descs[top]["dW"].cpu().numpy(), dw_top) < allow
+        # layers below inherit differences through dy: their parameter gradients are held to an L2
+        # bar here (the layer-by-layer statement on identical inputs is the teacher-forced test)
+        for d, (dw, dg, db) in zip(run.descs, grads):
+            for name, ref in (("dW", dw), ("dgamma", dg), ("dbeta", db)):
+                gotv = d[name].cpu().numpy().astype(np.float64)
+                assert np.linalg.norm(gotv - ref) <= 1e-2 * np.linalg.norm(ref), name
     # the stack driver is exactly the per-layer calls chained through the two buffers: redo the
     # forward by hand (first layer of a pair reads S writes T, second reads T writes S + S)
     import torch
     from paper_1901_07988_amd import binding as B
+    K = 4
+    y, dx, run = outs[K]
     S = G.dev(x)
     T = torch.empty_like(S)
     for i, d in enumerate(run.descs):

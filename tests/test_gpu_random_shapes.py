@@ -8,7 +8,8 @@ import pytest
 from paper_1901_07988_amd import synth
 from paper_1901_07988_amd.synth import LayerShape
 
-from tests.test_gpu_parity import TOL, close_but_for_flips, oshape, rel, G  # noqa: F401  (G is a fixture)
+from tests.stack_check import teacher_forced
+from tests.test_gpu_parity import TOL, oshape, rel, G  # noqa: F401  (G is a fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +46,7 @@ def test_random_layers(G, oracle, seed):
         dx, dw, dg, db = run.backward(dy, w)
         dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
         assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
-        assert rel(dg, dg_ref) < 5 * TOL and rel(db, db_ref) < 5 * TOL
+        assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -67,16 +68,13 @@ def test_random_stacks(G, oracle, seed):
         K = int(rng.choice([4, 8]))
         print("case random stack", [s.as_tuple() for s in shapes], "skip", skip_every, "K", K, flush=True)
         wl = synth.Workload("random stack", shapes, skip_every, "normal", "random")
-        x, layers, dy = synth.draw_stack(wl, int(rng.integers(1 << 30)))
+        seed = int(rng.integers(1 << 30))
+        x, layers, dy = synth.draw_stack(wl, seed)
         run = G.StackRun(layers, K, skip_every)
         run.load(x)
         run.forward()
         ol = [(oshape(o, s), w, g, b) for s, w, g, b in layers]
         y_ref, saved = o.stack_forward(x, ol, K, np.float32, skip_every)
         assert rel(run.output(), y_ref) < TOL
-        run.load(dy)
-        run.backward()
-        dx_ref, grads = o.stack_backward(saved, ol, dy, np.float32, skip_every)
-        assert close_but_for_flips(run.input_grad(), dx_ref, 5 * TOL, 0.02, 1e-2)
-        for d, (dw, dg, db) in zip(run.descs, grads):
-            assert close_but_for_flips(d["dW"].cpu().numpy(), dw, 20 * TOL, 0.02, 1e-2)
+        # codes and gradients: every layer on the GPU's own tensors
+        teacher_forced(G, o, wl, K, seed=seed, verbose=False)
