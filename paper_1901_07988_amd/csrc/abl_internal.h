@@ -250,6 +250,42 @@ __device__ inline void mma_k4(const float4 (&af)[MT], const float4 (&bf)[NT], fl
   }
 }
 
+// The same contraction for the first NB (compile-time, <= NT) tiles of the second operand only;
+// the others are left untouched and cost no matrix-core time.
+template <bool BF16, int MT, int NT, int NB>
+__device__ inline void mma_k4_first(const float4 (&af)[MT], const float4 (&bf)[NT], floatx4 (&acc)[MT][NT]) {
+  static_assert(NB <= NT, "at most all tiles");
+  if constexpr (BF16) {
+    shortx4 a[MT], b[NB > 0 ? NB : 1];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) a[i] = to_bf16x4(af[i]);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) b[j] = to_bf16x4(bf[j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(af[i].x, bf[j].x, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(af[i].y, bf[j].y, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(af[i].z, bf[j].z, acc[i][j]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(af[i].w, bf[j].w, acc[i][j]);
+  }
+}
+
 // v where ok, zeros elsewhere - written per component so that it stays in registers
 __device__ inline float4 keep_if(bool ok, const float4& v) {
   return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);

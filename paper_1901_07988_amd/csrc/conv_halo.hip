@@ -38,11 +38,12 @@ struct HaloPlan {
   int npix;                       // TI*TH*TW
   int mtiles;                     // ceil(npix / 16)
   int variant;                    // index into the instantiation table
+  int threads;                    // threads per block of that variant (256 or 512)
   int bn;                         // output channels per block
   unsigned inv_HW, inv_HH, inv_TW, inv_TH;  // ceil(2^32 / d): exact quotient x/d while x*d < 2^32
   unsigned inv_tiles_w, inv_tiles_h;
   unsigned nblk_n, inv_nblk_n;    // blocks along the output channels
-  BoxStep a_step;                 // 64 patch pixels further, as (cols, rows, images) of the patch
+  BoxStep a_step;                 // threads/4 patch pixels further, as (cols, rows, images) of the patch
   BoxStep m_step;                 // 16 tile pixels further, as (cols, rows, images) of the tile
   unsigned lds_bytes;
   int pack_pad;                   // zero bytes after the last code (fused forward only)
@@ -129,15 +130,20 @@ __device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 // FUSE = 0: `in` is the conv input.  FUSE = K (4 or 8, forward only): `in` is the layer input x;
 // BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied while the patch is staged, and the
 // block that owns a pixel also writes its K-bit codes (Eq. 9).
-template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16, int FUSE>
-__global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __restrict__ in,
+// NW: waves per block (4 or 8).  Eight waves put two on every SIMD, so that one wave's waits (the
+// LDS reads of a tap, the staging of the next chunk) are covered by the other's MFMAs where a
+// shape yields only one block per compute unit (14x14 images: 64 tiles x 4 channel blocks).
+template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16, int FUSE, int NW = 4>
+__global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
                                                              float* out, ConvGeom g, HaloPlan p,
                                                              const float* __restrict__ stats,
                                                              void* __restrict__ packed, EpiReduce epi) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  constexpr int WAVES_M = 4 / WAVES_N;
+  constexpr int WAVES_M = NW / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
+  constexpr int TPB = 64 * NW;          // threads per block
+  constexpr int AM = AMAX * 256 / TPB;  // patch slots per thread
   // Everything the set-up below reads from the argument block is requested here, in one batch
   // with one wait; left alone, the compiler fetches it field by field where it is first used and
   // the wave pays a scalar-cache round trip each time.
@@ -160,6 +166,10 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   const int li = lane & 15, lk = lane >> 4;
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int wn0 = wave_n * NT * 16;
+  // M-tiles of this wave that hold pixels of the tile (wave-uniform): the others are skipped
+  // where the variant has waves that would otherwise spend matrix-core time on padding (NW == 8)
+  const int mt_left = p.mtiles - __builtin_amdgcn_readfirstlane(wave_m) * MT;
+  const int mt_act = mt_left < 0 ? 0 : (mt_left < MT ? mt_left : MT);
 
   // ids 8 apart share an XCD (and its L2): the blocks that contract the same pixel tile against
   // different output-channel blocks run there back to back
@@ -180,8 +190,8 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   // fill, -2 = past the end of the patch.  Kept as numbers in vector registers: per-slot
   // predicates would each occupy a pair of scalar registers for the whole kernel.
   const int totalA = p.TI * p.HH * p.HW * 4;
-  int goff[AMAX];
-  float4 ra[AMAX];
+  int goff[AM];
+  float4 ra[AM];
   unsigned ownbits = 0;  // fused forward: bit j = this block writes the codes of slot j
   {
     int ti, h, w;
@@ -196,8 +206,8 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     const int vh0 = in_vgpr(h0), vw0 = in_vgpr(w0), vTH = in_vgpr(p.TH), vTW = in_vgpr(p.TW);
     const int c4 = 4 * (tid & 3);
 #pragma unroll
-    for (int j = 0; j < AMAX; ++j) {
-      const int idx = tid + kThreads * j;
+    for (int j = 0; j < AM; ++j) {
+      const int idx = tid + TPB * j;
       const bool ok = idx < vtotal && ti < vN && (unsigned)h < (unsigned)vHi && (unsigned)w < (unsigned)vWi;
       goff[j] = ok ? mad24(mad24(mad24(ti, vHi, h), vWi, w), vCg, c4) : (idx < vtotal ? -1 : -2);
       // the first chunk's load of a slot leaves as soon as its address is known, ahead of the
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         const bool own = ok && n0 == 0 && (unsigned)(h - vh0) < (unsigned)vTH && (unsigned)(w - vw0) < (unsigned)vTW;
         ownbits |= (own ? 1u : 0u) << j;
       }
-      // 64 patch pixels further
+      // TPB/4 patch pixels further
       w += step.w;
       const bool cw = w >= w_end;
       w -= cw ? width : 0;
@@ -229,7 +239,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
     // separates the loads, so all of them are in flight together
     if (c0 != 0) {
 #pragma unroll
-      for (int j = 0; j < AMAX; ++j) {
+      for (int j = 0; j < AM; ++j) {
         const bool ok = goff[j] >= 0;
         ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] + c0 : 0));
       }
@@ -247,8 +257,8 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
   };
   auto stage_a = [&](float* tileA) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < AMAX; ++j) {
-      const int idx = tid + kThreads * j;
+    for (int j = 0; j < AM; ++j) {
+      const int idx = tid + TPB * j;
       if (goff[j] != -2) {
         const bool ok = goff[j] >= 0;
         float4 v = keep_if(ok, ra[j]);
@@ -411,9 +421,17 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
         const int aoff = (rr * p.HW + ss) * PS;
         float4 af[MT];
+        if (NW == 8 && mt_act == MT - 1) {
+          // the wave's last M-tile lies past the tile's pixels: neither read nor contracted
 #pragma unroll
-        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
-        mma_k4<BF16, NT, MT>(bw[0], af, acc);
+          for (int i = 0; i < MT - 1; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+          af[MT - 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+          mma_k4_first<BF16, NT, MT, MT - 1>(bw[0], af, acc);
+        } else {
+#pragma unroll
+          for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+          mma_k4<BF16, NT, MT>(bw[0], af, acc);
+        }
 #pragma unroll
         for (int j = 0; j < NT; ++j) bw[0][j] = bnext[j];
         if (++s == g.S) { s = 0; ++r; }
@@ -545,7 +563,7 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
         }
       }
     __syncthreads();
-    for (int c = tid; c < 2 * BN; c += kThreads) {
+    for (int c = tid; c < 2 * BN; c += TPB) {
       const int qv = c / BN, ch = c % BN;
       double t = 0.0;
 #pragma unroll
@@ -557,29 +575,31 @@ __global__ __launch_bounds__(kThreads) void halo_conv_kernel(const float* __rest
 
 // ---- host side ----------------------------------------------------------------------------
 struct Variant {
-  int waves_n, mt, nt;
+  int waves_n, mt, nt, nw;
 };
 // instantiation table; `variant` in the plan indexes it
 constexpr Variant kVariants[] = {
-    {1, 4, 1},   // 0: 256 px x 16 ch   (16-channel CIFAR layers)
-    {1, 2, 2},   // 1: 128 px x 32 ch
-    {1, 4, 2},   // 2: 256 px x 32 ch
-    {4, 4, 1},   // 3: 64 px x 64 ch
-    {4, 8, 1},   // 4: 128 px x 64 ch
-    {4, 14, 1},  // 5: 224 px x 64 ch   (56x56 and 14x14 ImageNet layers)
+    {1, 4, 1, 4},   // 0: 256 px x 16 ch   (16-channel CIFAR layers)
+    {1, 2, 2, 4},   // 1: 128 px x 32 ch
+    {1, 4, 2, 4},   // 2: 256 px x 32 ch
+    {4, 4, 1, 4},   // 3: 64 px x 64 ch
+    {4, 8, 1, 4},   // 4: 128 px x 64 ch
+    {4, 14, 1, 4},  // 5: 224 px x 64 ch   (56x56 ImageNet layers)
+    {4, 7, 1, 8},   // 6: 224 px x 64 ch in eight waves, two halves of the pixels (14x14 ImageNet layers)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kPatchSlots = AMAX * kThreads;  // float4 patch elements a block can stage, whatever its size
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // Choose the tile shape with at most `maxpix` output pixels that minimises staged patch
 // elements plus padded M-tile work over the whole image.
-void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
+void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p, int threads = kThreads) {
   if (Hq * Wq <= maxpix) {
     p.TH = Hq; p.TW = Wq;
     p.TI = maxpix / (Hq * Wq);
     if (p.TI > N) p.TI = N;
-    while (p.TI > 1 && p.TI * (Hq + R - 1) * (Wq + S - 1) * 4 > AMAX * kThreads) --p.TI;
+    while (p.TI > 1 && p.TI * (Hq + R - 1) * (Wq + S - 1) * 4 > kPatchSlots) --p.TI;
   } else {
     p.TI = 1;
     p.TH = p.TW = 0;
@@ -590,7 +610,7 @@ void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
       for (int kh = 1; kh <= Hq; ++kh) {
         const int th = cdiv(Hq, kh);
         if (th * tw > maxpix) continue;
-        if ((th + R - 1) * (tw + S - 1) * 4 > AMAX * kThreads) continue;
+        if ((th + R - 1) * (tw + S - 1) * 4 > kPatchSlots) continue;
         const long tiles = (long)cdiv(Hq, th) * cdiv(Wq, tw);
         const long cost = tiles * ((long)(th + R - 1) * (tw + S - 1) + 2L * 16 * cdiv(th * tw, 16));
         if (best < 0 || cost < best) {
@@ -619,7 +639,8 @@ void choose_tile(int Hq, int Wq, int N, int R, int S, int maxpix, HaloPlan& p) {
     b.ti = cells / width / height;
     return b;
   };
-  p.a_step = digits(64, p.HW, p.HH);
+  p.threads = threads;
+  p.a_step = digits(threads / 4, p.HW, p.HH);
   p.m_step = digits(16, p.TW, p.TH);
 }
 
@@ -651,9 +672,17 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
       }
     }
   }
+#ifndef ABL_HALO_NO_8WAVES
+  if (v == 5) {
+    // the 224-pixel tile with fewer than two blocks per compute unit: eight waves per block
+    HaloPlan t;
+    choose_tile(Hq, Wq, g.N, g.R, g.S, kVariants[5].mt * 16, t);
+    if ((int64_t)t.tiles_i * t.tiles_h * t.tiles_w * cdiv(Ng, 64) < 2 * 256) v = 6;
+  }
+#endif
   const Variant& var = kVariants[v];
-  const int waves_m = 4 / var.waves_n;
-  choose_tile(Hq, Wq, g.N, g.R, g.S, waves_m * var.mt * 16, p);
+  const int waves_m = var.nw / var.waves_n;
+  choose_tile(Hq, Wq, g.N, g.R, g.S, waves_m * var.mt * 16, p, 64 * var.nw);
   p.variant = v;
   p.bn = var.waves_n * var.nt * 16;
   p.nblk_n = (unsigned)cdiv(Ng, p.bn);
@@ -664,7 +693,7 @@ bool make_plan(const ConvGeom& g, int mode, HaloPlan& p) {
   const int Cg = mode == 0 ? g.Cin : g.Cout;
   const size_t fl = (size_t)p.TI * p.HH * p.HW * PS * (Cg > 16 ? 2 : 1);
   p.lds_bytes = (unsigned)(fl * sizeof(float));
-  return p.lds_bytes <= 64 * 1024 && p.TI * p.HH * p.HW * 4 <= AMAX * kThreads && p.TH > 0;
+  return p.lds_bytes <= 64 * 1024 && p.TI * p.HH * p.HW * 4 <= kPatchSlots && p.TH > 0;
 }
 
 template <int MODE, int V, int FUSE>
@@ -674,11 +703,17 @@ void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool b
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * p.nblk_n);
   const bool unroll = g.R == 3 && g.S == 3 && var.mt * var.nt <= 4;
-  auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true, FUSE>
-                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
-                     : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE>
-                             : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE>);
-  kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
+  if constexpr (var.nw == 8) {
+    auto kern = bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE, 8>
+                     : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE, 8>;
+    kern<<<grid, 512, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
+  } else {
+    auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true, FUSE>
+                               : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
+                       : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE>
+                               : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE>);
+    kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
+  }
 }
 
 template <int MODE, int FUSE>
@@ -690,7 +725,8 @@ void launch_mode(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool bf16
     case 2: launch_variant<MODE, 2, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
     case 3: launch_variant<MODE, 3, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
     case 4: launch_variant<MODE, 4, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
-    default: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    case 5: launch_variant<MODE, 5, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
+    default: launch_variant<MODE, 6, FUSE>(st, g, p, bf16, in, w, skip, out, stats, packed, epi); break;
   }
 }
 
