@@ -228,6 +228,17 @@ def hbm_bound_passes(G, B, K, reps):
     return out
 
 
+def mfma_ceilings(G, B, reps=5):
+    """TFLOP/s that a loop of independent matrix instructions on register operands reaches
+    (abl_mfma_probe): the practical ceiling of the contractions next to the published peak."""
+    out = G.zeros_bytes(B.abl_mfma_probe_out_bytes())
+    res = {}
+    for name, mode, iters in (("fp32_16x16x4", 0, 4000), ("bf16_16x16x32", 1, 8000)):
+        ms = time_events(lambda i: B.abl_mfma_probe(mode, iters, out), reps)
+        res[name] = round(B.abl_mfma_probe_flops(mode, iters) / ms / 1e9, 1)
+    return res
+
+
 def omp_threads(set_to=None):
     """Size of the OpenMP team the oracle's loops run with (optionally change it first)."""
     import ctypes
@@ -385,6 +396,7 @@ def main():
                  "avg_us": dom["ms"] * 1e3, "launches_per_call": dom["launches"],
                  "algorithmic_bytes": dom["bytes"], "algorithmic_flops": dom["flops"],
                  "hbm_frac_of_same_kernel": dom["gbs"] / HBM_PEAK_GBS})
+    roof["measured_mfma_ceiling_tflops"] = mfma_ceilings(G, B)
     # every contraction of the step against the fp32 (or bf16) matrix peak
     roof["contractions_frac_of_mfma_peak"] = {
         "x".join(map(str, s.as_tuple())): {k: round(v["tflops"] / mfma_peak, 3) for k, v in bd.items()

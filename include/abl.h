@@ -322,6 +322,17 @@ int abl_sgd_momentum(void* stream, int64_t n, float lr, float momentum, float we
  * src, dst: device pointers, 16-byte aligned, caller-owned; bytes a positive multiple of 16.
  * Errors: ABL_ERR_ARG (mode, null / misaligned pointer), ABL_ERR_SHAPE (bytes), ABL_ERR_HIP. */
 int abl_hbm_probe(void* stream, int mode, const void* src, void* dst, size_t bytes);
+/* The matrix-core counterpart, the ceiling that the contractions (Eq. 4, Eq. 5) are reported
+ * against: every wave of a fixed grid issues `iters` rounds of eight independent matrix
+ * instructions on register operands - mode 0: fp32 16x16x4 (the instruction of the default
+ * path), mode 1: bf16 16x16x32 with fp32 accumulation (ABL_MATH_BF16).  abl_mfma_probe_flops
+ * returns the floating-point operations one such launch performs (0 on invalid arguments);
+ * `out` receives abl_mfma_probe_out_bytes() bytes of sums that only keep the work alive.
+ * Errors: ABL_ERR_ARG (mode, iters outside [1, 2^24], null / misaligned out), ABL_ERR_SCRATCH
+ * (out_bytes too small), ABL_ERR_HIP. */
+size_t abl_mfma_probe_out_bytes(void);
+double abl_mfma_probe_flops(int mode, int iters);
+int abl_mfma_probe(void* stream, int mode, int iters, void* out, size_t out_bytes);
 
 #ifdef __cplusplus
 }

@@ -89,6 +89,9 @@ _SIGS = {
                                                  ctypes.POINTER(_vp)]),
     "abl_sgd_momentum": (ctypes.c_int, [_vp, _i64, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]),
     "abl_hbm_probe": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _sz]),
+    "abl_mfma_probe_out_bytes": (_sz, []),
+    "abl_mfma_probe_flops": (ctypes.c_double, [ctypes.c_int, ctypes.c_int]),
+    "abl_mfma_probe": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, _sz]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -343,3 +346,16 @@ def abl_sgd_momentum(w, grad, v, lr, momentum, weight_decay):
 def abl_hbm_probe(mode, src, dst, nbytes):
     """mode 0 read src, 1 write dst, 2 copy src -> dst; nbytes a multiple of 16."""
     _check(lib.abl_hbm_probe(_stream(), mode, _ptr(src), _ptr(dst), nbytes), "abl_hbm_probe")
+
+
+def abl_mfma_probe_out_bytes():
+    return lib.abl_mfma_probe_out_bytes()
+
+
+def abl_mfma_probe_flops(mode, iters):
+    return lib.abl_mfma_probe_flops(mode, iters)
+
+
+def abl_mfma_probe(mode, iters, out):
+    """mode 0 fp32 16x16x4, mode 1 bf16 16x16x32; out: abl_mfma_probe_out_bytes() bytes."""
+    _check(lib.abl_mfma_probe(_stream(), mode, iters, _ptr(out), out.numel() * out.element_size()), "abl_mfma_probe")

@@ -122,10 +122,10 @@ __device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 // consecutive channels of one pixel - one 16-byte store, one 16-byte shortcut load and one
 // 16-/32-bit load of that pixel's codes in the epilogue.
 // The weights are not staged: each lane fetches its fragment (four consecutive k of one output
-// channel) straight from L2.  3x3 filters with few tiles per wave (UNROLL_TAPS) hold the
-// fragments of all nine taps in registers: they are requested together with the first patch,
-// and the registers of a tap are refilled for the next channel chunk right after its MFMAs.
-// Other shapes fetch one tap ahead.  With more than 16 input channels the patch buffer is
+// channel) straight from L2.  3x3 filters hold the fragments of all nine taps in registers: they
+// are requested together with the first patch, and the registers of a tap are refilled for the
+// next channel chunk right after its MFMAs (one tap of lookahead is about an L2 round trip: too
+// little).  Other filter sizes fetch one tap ahead.  With more than 16 input channels the patch buffer is
 // doubled and the next chunk's global loads are in flight during the MFMAs.
 // FUSE = 0: `in` is the conv input.  FUSE = K (4 or 8, forward only): `in` is the layer input x;
 // BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied while the patch is staged, and the
@@ -133,13 +133,17 @@ __device__ inline int mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 // NW: waves per block (4 or 8).  Eight waves put two on every SIMD, so that one wave's waits (the
 // LDS reads of a tap, the staging of the next chunk) are covered by the other's MFMAs where a
 // shape yields only one block per compute unit (14x14 images: 64 tiles x 4 channel blocks).
-template <int MODE, int WAVES_N, int MT, int NT, bool UNROLL_TAPS, bool BF16, int FUSE, int NW = 4>
+template <int MODE, int WAVES_N, int MT, int NT, int TAPS9, bool BF16, int FUSE, int NW = 4>
 __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
                                                              float* out, ConvGeom g, HaloPlan p,
                                                              const float* __restrict__ stats,
                                                              void* __restrict__ packed, EpiReduce epi) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
+  // TAPS9 (3x3 filters only): 0 - weight fragments fetched one tap ahead; 1 - the fragments of all
+  // nine taps held in registers and the epilogue's addresses and loads prepared during the first
+  // wait (tiles of few M-tiles, where set-up and epilogue weigh most); 2 - fragments held only.
+  constexpr bool HOLD9 = TAPS9 != 0, UNROLL_TAPS = TAPS9 == 1;
   constexpr int WAVES_M = NW / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
   constexpr int TPB = 64 * NW;          // threads per block
@@ -316,7 +320,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
     }
   };
 
-  constexpr int HELD = UNROLL_TAPS ? 9 : 1;
+  constexpr int HELD = HOLD9 ? 9 : 1;
   float4 bw[HELD][NT], bnext[NT];
   fetch_a(0);
 #pragma unroll
@@ -401,16 +405,25 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
     const float* tileA = lds + buf * patch_floats;
     const bool more = c0 + 16 < Cg;
     if (more) fetch_a(c0 + 16);
-    if (UNROLL_TAPS) {
+    if (HOLD9) {
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
         const int r = t / 3, s = t % 3;
         const int rr = MODE == 0 ? r : 2 - r, ss = MODE == 0 ? s : 2 - s;
         const int aoff = (rr * p.HW + ss) * PS;
         float4 af[MT];
+        if (NW == 8 && mt_act == MT - 1) {
+          // the wave's last M-tile lies past the tile's pixels: neither read nor contracted
 #pragma unroll
-        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
-        mma_k4<BF16, NT, MT>(bw[t], af, acc);
+          for (int i = 0; i < MT - 1; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+          af[MT - 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+          mma_k4_first<BF16, NT, MT, MT - 1>(bw[t], af, acc);
+        } else {
+#pragma unroll
+          for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const float4*>(&tileA[base[i] + aoff]);
+          mma_k4<BF16, NT, MT>(bw[t], af, acc);
+        }
+        // the same tap of the next chunk: a whole chunk of matrix work ahead of its use
         if (more) fetch_b(c0 + 16, t, bw[t]);
       }
     } else {
@@ -702,16 +715,23 @@ void launch_variant(hipStream_t st, const ConvGeom& g, const HaloPlan& p, bool b
   constexpr Variant var = kVariants[V];
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   dim3 grid(cdiv(p.tiles_i * p.tiles_h * p.tiles_w, 8) * 8 * p.nblk_n);
-  const bool unroll = g.R == 3 && g.S == 3 && var.mt * var.nt <= 4;
+  const bool taps9 = g.R == 3 && g.S == 3;
   if constexpr (var.nw == 8) {
-    auto kern = bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE, 8>
-                     : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE, 8>;
+    auto kern = taps9 ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 2, true, FUSE, 8>
+                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 2, false, FUSE, 8>)
+                      : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 0, true, FUSE, 8>
+                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 0, false, FUSE, 8>);
     kern<<<grid, 512, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
   } else {
-    auto kern = unroll ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, true, FUSE>
-                               : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, true, false, FUSE>)
-                       : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, true, FUSE>
-                               : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, false, false, FUSE>);
+    // 3x3 filters: the weight fragments of all nine taps stay in registers; tiles of few M-tiles
+    // also prepare their epilogue early
+    // (the fused forward of the 14-M-tile variant would pass 256 registers with the held
+    // fragments and lose its second wave per SIMD: it keeps the one-tap lookahead)
+    constexpr int T9 = var.mt * var.nt <= 4 ? 1 : (FUSE != 0 && var.mt >= 14 ? 0 : 2);
+    auto kern = taps9 ? (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, T9, true, FUSE>
+                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, T9, false, FUSE>)
+                      : (bf16 ? halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 0, true, FUSE>
+                              : halo_conv_kernel<MODE, var.waves_n, var.mt, var.nt, 0, false, FUSE>);
     kern<<<grid, kThreads, p.lds_bytes, st>>>(in, w, skip, out, g, p, stats, packed, epi);
   }
 }
