@@ -440,6 +440,15 @@ def main():
                          "value": n2 * l2 / (ms2 * 1e-3), "unit": result["unit"]})
             del run2
             torch.cuda.empty_cache()
+        if args.math == "fp32" and args.workload != "config4":
+            # the bf16-operand variant (32-deep bf16 matrix instruction, fp32 accumulation) on config 4
+            w2 = get_workload("config4")
+            ms2, run2 = time_stack(G, B, synth, w2, K, B.ABL_MATH_BF16, 30, 5)
+            subs.append({"workload": w2.name + " --math bf16", "K": K, "steps": 30, "ms_per_step": ms2,
+                         "value": w2.shapes[0].N * len(w2.shapes) / (ms2 * 1e-3), "unit": result["unit"],
+                         "dtype": "bf16 operands, f32 accumulate (contractions); f32 elsewhere"})
+            del run2
+            torch.cuda.empty_cache()
         result["sub_results"] = subs
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, K)

@@ -23,6 +23,7 @@ UNITS = {
     "conv_kernels.hip": [],
     "conv_halo.hip": ["-ffp-contract=off"],
     "conv_pointwise.hip": ["-ffp-contract=off"],
+    "conv_bf16.hip": [],
     "abl_api.hip": [],
     "abl_noalloc.hip": [],
     "probe_kernels.hip": [],

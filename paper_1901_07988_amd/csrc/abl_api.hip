@@ -187,10 +187,17 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
   }
   const ConvGeom g = geom_of(*s);
+  // bf16 operands: the contraction runs on the 32-deep bf16 matrix instruction with bf16 tiles in
+  // LDS (its kernel has no BN prologue), so the layer takes the separate stages
+  // - where the contraction is heavy enough to pay for the separate normalise-ReLU-pack pass
+  // (measured: from 512 flops per input element on; below, e.g. 1x1 256->64 at 56x56, reading x
+  // once in the fused kernel wins)
+  const bool bf16_gemm = bf16 && bf16_gemm_supported(g, 0) && 2 * g.Cout * g.R * g.S >= 512;
   // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
   // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
   // overwrite input pixels that a neighbouring block has not staged yet.)
-  if (K != 32 && !naive && halo_fused_supported(g) && static_cast<const void*>(x) != static_cast<const void*>(y)) {
+  if (K != 32 && !naive && !bf16_gemm && halo_fused_supported(g) &&
+      static_cast<const void*>(x) != static_cast<const void*>(y)) {
     const int tiles = halo_tile_count(g, 0);
     const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
     if (int e = launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed, want ? out_partial : nullptr))
@@ -201,7 +208,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   // 1x1 convolutions do the same while they stage their A tile
   // With the prologue every block along the output channels repeats the normalization of its
   // input rows; measured against the separate pack kernel this pays up to 256 output channels.
-  if (K != 32 && !naive && igemm_fused_supported(*s) && s->Cout <= 256 &&
+  if (K != 32 && !naive && !bf16_gemm && igemm_fused_supported(*s) && s->Cout <= 256 &&
       static_cast<const void*>(x) != static_cast<const void*>(y))
     return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed, out_partial, out_nb);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, naive)) return e;
@@ -251,6 +258,8 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
   const ConvGeom g = geom_of(*s);
   // Stride-1 convolutions with a filter larger than 1x1 take the Eq. 6-7 sums in the epilogue of
   // the dgrad kernel (dA3 is still in registers there), which saves the reduce pass over dA3.
+  // bf16 operands with a dgrad on the 32-deep bf16 matrix instruction: the separate stages
+  const bool bf16_gemm = bf16 && bf16_gemm_supported(g, 1);
   // 16-channel 3x3 layers: both contractions and the Eq. 6-7 sums in one kernel
   if (const int t16 = K != 32 ? halo_bwd16_tiles(g) : 0) {
     if (int e = launch_halo_bwd16(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red), wpart,
@@ -260,7 +269,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     const DwSum dwsum{static_cast<const float*>(wpart), t16, (int64_t)9 * 16 * 16, dW};
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta, &dwsum);
   }
-  const int tiles = K != 32 && halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
+  const int tiles = K != 32 && !bf16_gemm && halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))
       return e;
@@ -271,7 +280,7 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
                                 dwsum.copies > 0 ? &dwsum : nullptr);
   }
   // 1x1 stride-1 layers: the same sums in the epilogue of the pointwise dgrad kernel
-  if (K != 32 && pointwise_supported(g, 1)) {
+  if (K != 32 && !bf16_gemm && pointwise_supported(g, 1)) {
     int rows = 0;
     if (int e = launch_pointwise_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red),
                                               &rows))

@@ -137,6 +137,13 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
                              const void* stats, const float* dy, void* scratch, float* dw, bool relu32 = false,
                              DwSum* defer = nullptr);
 
+// ---- ABL_MATH_BF16 contractions on the 32-deep bf16 matrix instruction (conv_bf16.hip) ----
+// Forward (mode 0) / gradient to the input (mode 1) of any stride, filter and padding whose
+// contraction channels are a multiple of 32 and output channels a multiple of 64.
+bool bf16_gemm_supported(const ConvGeom& g, int mode);
+int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
+                     float* out);
+
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.
 // floor() limited to +-2^24 so that the integer conversion is defined for any input.
@@ -201,15 +208,17 @@ __device__ inline floatx4 mfma16(float a, float b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
-__device__ inline short bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (short)(u >> 16);
+// fp32 -> bf16, round to nearest even, by the hardware's packed convert (v_cvt_pk_bf16_f32).
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+// eight floats -> the 8-deep bf16 operand of one lane of v_mfma_f32_16x16x32_bf16
+__device__ inline bf16x8_t to_bf16x8(const float (&v)[8]) {
+  return bf16x8_t{(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3],
+                  (__bf16)v[4], (__bf16)v[5], (__bf16)v[6], (__bf16)v[7]};
 }
-
 __device__ inline shortx4 to_bf16x4(const float4& v) {
-  return shortx4{bf16_bits(v.x), bf16_bits(v.y), bf16_bits(v.z), bf16_bits(v.w)};
+  const bf16x4_t b = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+  return __builtin_bit_cast(shortx4, b);
 }
 
 // Contract four consecutive k (one float4 per lane and operand row) into every accumulator

@@ -548,6 +548,34 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     // wave w contracts pixels [16w, 16w+16) of the chunk.  Component e of the operand vectors is
     // pixel 4e + lk (fp32: k-step e, lane group = k) or 4lk + e (bf16: lane group owns 4 k).
     const int am0 = QUAD ? (wave >> 1) * (TM / 2) : 0, bn0 = QUAD ? (wave & 1) * (TN / 2) : 0;
+    if constexpr (BF16 && QUAD) {
+      // bf16 operands on the 32-deep matrix instruction: a lane supplies eight consecutive pixels
+      // (k = 8 lk .. 8 lk + 7 of each half of the chunk), rounded by the hardware's packed convert
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh) {
+        const int r0 = 32 * kh + 8 * lk;
+        bf16x8_t a8[MT], b8[NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = As[(r0 + e) * LDA + am0 + 16 * i + li];
+          a8[i] = to_bf16x8(v);
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = Bs[(r0 + e) * LDB + bn0 + 16 * j + li];
+          b8[j] = to_bf16x8(v);
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8[i], b8[j], acc[i][j], 0, 0, 0);
+      }
+    } else
 #pragma unroll
     for (int kq = 0; kq < (QUAD ? 4 : 1); ++kq) {
       float4 af[MT], bf[NT];
@@ -834,6 +862,8 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     naive_fwd_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(a3, w, skip, y, g);
     return hip_status();
   }
+  // bf16 operands: the 32-deep bf16 matrix instruction with bf16 tiles in LDS
+  if (bf16 && bf16_gemm_supported(g, 0)) return launch_bf16_gemm(st, g, 0, a3, w, skip, y);
   if (halo_conv_supported(g)) {
     const int tiles = sums != nullptr && rows != nullptr ? halo_tile_count(g, 0) : 0;
     const bool want = tiles > 0 && tiles <= kMaxPartialBlocks;
@@ -872,6 +902,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
     naive_dgrad_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(dy, w, da3, g);
     return hip_status();
   }
+  if (bf16 && bf16_gemm_supported(g, 1)) return launch_bf16_gemm(st, g, 1, dy, w, nullptr, da3);
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   if (pointwise_supported(g, 1)) return launch_pointwise_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   return launch_igemm<1, 0>(st, g, bf16, dy, w, nullptr, da3, nullptr, nullptr);

@@ -159,6 +159,8 @@ CONV_CASES = [
     LayerShape(2, 16, 16, 32, 32, 3, 3, 1, 0),         # no padding
     LayerShape(1, 12, 12, 16, 32, 3, 3, 1, 2),         # padding larger than 'same'
     LayerShape(2, 9, 11, 32, 16, 1, 3, 1, 1),          # 1x3 filter
+    LayerShape(3, 13, 11, 64, 128, stride=2),          # strided, channel counts of the bf16 GEMM kernels
+    LayerShape(2, 10, 10, 128, 64, 5, 5, 1, 2),
 ]
 
 
@@ -176,6 +178,13 @@ def test_conv_forward_and_dgrad(G, oracle, s):
     assert rel(G.run_conv_fwd(s, a3, w, skip), y_ref + skip) < TOL
     assert rel(G.run_conv_fwd(s, a3, w, skip, alias_skip=True), y_ref + skip) < TOL
     assert rel(G.run_conv_dgrad(s, dy, w), o.conv_dgrad(dy, w, oshape(o, s))) < TOL
+
+
+def to_bf16(a):
+    """fp32 array rounded to the nearest bf16 (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a))
 
 
 @pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
@@ -208,6 +217,12 @@ def test_conv_bf16_variant(G, oracle, s):
     assert rel(dw, dw_ref) < TOL_BF16
     if s.Cin % 16 == 0 and s.Cout % 16 == 0:
         assert rel(y, y_ref + skip) > 1e-5 and rel(da, o.conv_dgrad(dy, w, oshape(o, s))) > 1e-5
+        # the same precision on both sides: the oracle on operands rounded to bf16 (round to nearest
+        # even) differs from the kernels by the order of the fp32 accumulation only
+        assert rel(y, o.conv_fwd(to_bf16(a3), to_bf16(w), oshape(o, s)) + skip) < TOL
+        assert rel(da, o.conv_dgrad(to_bf16(dy), to_bf16(w), oshape(o, s))) < TOL
+        a3t = np.maximum(o.dequantize(q, gamma, beta, K), np.float32(0))
+        assert rel(dw, o.conv_wgrad(to_bf16(a3t), to_bf16(dy), oshape(o, s))) < TOL
 
 
 @pytest.mark.parametrize("s", CONV_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
