@@ -163,6 +163,9 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
   float4 ring[PF];
 #pragma unroll
   for (int s = 0; s < PF; ++s) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * s);
+  // (the same explicit wait as after a tile's stores, see below: the contraction loop is then
+  // entered with nothing pending on every path, and the compiler can count the ring's loads)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
   // SUMS: this lane's pixels (at most a few dozen), its four channels of every tile column.
   // The forward sums feed a variance (sum of squares minus square of the sum): fp64 from the
@@ -211,8 +214,6 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
           const int kl = (g0 + s) * 16;     // offset inside the chunk
           const int kg = c * GPC + g0 + s;  // group of the whole contraction
           float4 a[1] = {ring[s]};
-          if (kg + PF < KG) ring[s] = *reinterpret_cast<const float4*>(xp + 16 * (kg + PF));
-          else if (has_next) ring[s] = *reinterpret_cast<const float4*>(xpn + 16 * (kg + PF - KG));
           if (FUSE != 0) {
             const float4 c_mean = *reinterpret_cast<const float4*>(&Cc[0 * CH + kl + 4 * lk]);
             const float4 c_rstd = *reinterpret_cast<const float4*>(&Cc[1 * CH + kl + 4 * lk]);
@@ -253,6 +254,17 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
           for (int j = 0; j < NT; ++j)
             wf[j] = *reinterpret_cast<const float4*>(&W[(16 * j + li) * LDW + kl + 4 * lk]);
           mma_k4<BF16, NT, 1>(wf, a, acc);
+          // Refill the slot AFTER the MFMAs that read it (no copy of the old value is needed, so
+          // nothing has to wait for a younger load), without a branch (past the block's last tile
+          // the loads re-read that tile and are never used: behind a branch the compiler cannot
+          // count the loads in flight and waits for all of them), and pinned here (left alone, the
+          // scheduler sinks all PF refills to the end of the loop body, right in front of their use).
+          {
+            const bool same = kg + PF < KG;
+            const float* src = (same ? xp : xpn) + 16 * (same ? kg + PF : kg + PF - KG);
+            ring[s] = *reinterpret_cast<const float4*>(src);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       }
       if (CHUNKED) {
@@ -305,6 +317,12 @@ __global__ __launch_bounds__(CHUNKED ? 512 : 256) void pointwise_kernel(
         }
       }
     }
+    // The tile's stores share the counter of the loads and may complete out of order with them:
+    // while one is pending the compiler must wait for everything before it may read a loaded
+    // register, and it would do so at the head of the contraction loop in every iteration.  One
+    // explicit wait here (the next tile's first groups have been in flight for a while) lets it
+    // count the ring's loads instead.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     xp = xpn;
   }
   if (SUMS) {
