@@ -238,10 +238,10 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
   float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
   int4 k_fb;
   int k_c0 = 0;
-  auto fetch_a = [&](int c0) __attribute__((always_inline)) {
+  auto fetch_a = [&](int c0, bool load_x) __attribute__((always_inline)) {
     // unconditional loads (lanes outside the image read element 0 and are zeroed): no branch
     // separates the loads, so all of them are in flight together
-    if (c0 != 0) {
+    if (load_x) {
 #pragma unroll
       for (int j = 0; j < AM; ++j) {
         const bool ok = goff[j] >= 0;
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
 
   constexpr int HELD = HOLD9 ? 9 : 1;
   float4 bw[HELD][NT], bnext[NT];
-  fetch_a(0);
+  fetch_a(0, false);  // chunk 0 of the patch was requested while the offsets were computed
 #pragma unroll
   for (int t = 0; t < HELD; ++t) fetch_b(0, t, bw[t]);
 
@@ -404,7 +404,11 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
   for (int c0 = 0; c0 < Cg; c0 += 16) {
     const float* tileA = lds + buf * patch_floats;
     const bool more = c0 + 16 < Cg;
-    if (more) fetch_a(c0 + 16);
+    // Loads for the next chunk are issued without a branch (the last chunk re-reads itself and
+    // drops the result): the compiler can then count the loads in flight and wait only for the
+    // ones a tap needs, instead of draining all of them at every branch target.
+    const int cn = more ? c0 + 16 : c0;
+    fetch_a(cn, true);
     if (HOLD9) {
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
@@ -424,13 +428,15 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
           mma_k4<BF16, NT, MT>(bw[t], af, acc);
         }
         // the same tap of the next chunk: a whole chunk of matrix work ahead of its use
-        if (more) fetch_b(c0 + 16, t, bw[t]);
+        fetch_b(cn, t, bw[t]);
       }
     } else {
       int r = 0, s = 0;
       for (int t = 0; t < taps; ++t) {
-        if (t + 1 < taps) fetch_b(c0, t + 1, bnext);
-        else if (more) fetch_b(c0 + 16, 0, bnext);
+        {
+          const bool last = t + 1 == taps;
+          fetch_b(last ? cn : c0, last ? 0 : t + 1, bnext);
+        }
         const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
         const int aoff = (rr * p.HW + ss) * PS;
         float4 af[MT];
