@@ -17,6 +17,14 @@
 // the fused forward evaluates Eq. 1-3 and Eq. 9 here: one rounded fp32 operation at a time
 #pragma clang fp contract(off)
 
+// Scheduling fence that neither global memory nor matrix instructions may cross (vector, scalar and LDS ones may): keeps
+// a prefetch where the source puts it, a whole tap or chunk of matrix work ahead of its use,
+// instead of letting the scheduler sink it to the end of the loop body.
+#define PIN_VMEM()                                      \
+  do {                                                  \
+    if (PIN) __builtin_amdgcn_sched_barrier(0x786);     \
+  } while (0)
+
 namespace abl {
 namespace {
 
@@ -144,6 +152,9 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
   // nine taps held in registers and the epilogue's addresses and loads prepared during the first
   // wait (tiles of few M-tiles, where set-up and epilogue weigh most); 2 - fragments held only.
   constexpr bool HOLD9 = TAPS9 != 0, UNROLL_TAPS = TAPS9 == 1;
+  // The pinned schedule of the widest unfused forward tile with held weights needs more than
+  // 256 registers (one wave per SIMD instead of two): that variant keeps the free schedule.
+  constexpr bool PIN = !(MODE == 0 && FUSE == 0 && MT >= 14 && TAPS9 == 2);
   constexpr int WAVES_M = NW / WAVES_N;
   constexpr int BN = WAVES_N * NT * 16;
   constexpr int TPB = 64 * NW;          // threads per block
@@ -196,7 +207,9 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
   const int totalA = p.TI * p.HH * p.HW * 4;
   int goff[AM];
   float4 ra[AM];
-  unsigned ownbits = 0;  // fused forward: bit j = this block writes the codes of slot j
+  // fused forward: bit j = slot j lies inside the block's pixel tile (not in its halo), where the
+  // block writes codes
+  unsigned ownbits = 0;
   {
     int ti, h, w;
     split3<UNROLL_TAPS>(tid >> 2, p.HW, p.inv_HW, p.HH, p.inv_HH, ti, h, w);
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
       // position arithmetic of the slots after it
       ra[j] = *reinterpret_cast<const float4*>(in + (ok ? goff[j] : 0));
       if (FUSE != 0) {
-        const bool own = ok && n0 == 0 && (unsigned)(h - vh0) < (unsigned)vTH && (unsigned)(w - vw0) < (unsigned)vTW;
+        const bool own = ok && (unsigned)(h - vh0) < (unsigned)vTH && (unsigned)(w - vw0) < (unsigned)vTW;
         ownbits |= (own ? 1u : 0u) << j;
       }
       // TPB/4 patch pixels further
@@ -259,7 +272,13 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
       k_c0 = c0;
     }
   };
+  // Fused forward: all output-channel blocks of a pixel tile normalize the same patch; they take
+  // turns over the 16-channel chunks in quantizing it and writing the codes, so that every block
+  // has the same amount of vector work (were it all the first block's, the compute units holding
+  // first blocks would finish last).
+  const unsigned nblk_i = slot - sq * p.nblk_n;
   auto stage_a = [&](float* tileA) __attribute__((always_inline)) {
+    const bool packs = FUSE != 0 && ((unsigned)k_c0 >> 4) % p.nblk_n == nblk_i;  // block-uniform
 #pragma unroll
     for (int j = 0; j < AM; ++j) {
       const int idx = tid + TPB * j;
@@ -274,22 +293,26 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
           const float bt[4] = {k_beta.x, k_beta.y, k_beta.z, k_beta.w};
           const float cq[4] = {k_cq.x, k_cq.y, k_cq.z, k_cq.w};
           const int32_t fb[4] = {k_fb.x, k_fb.y, k_fb.z, k_fb.w};
-          float a3[4];
-          uint32_t word = 0;
+          float a2[4], a3[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float d = xs[e] - mean[e];
             const float a1 = d * rstd[e];  // Eq. 1
             const float t = gm[e] * a1;
-            const float a2 = t + bt[e];    // Eq. 2
-            a3[e] = (ok && a2 > 0.0f) ? a2 : 0.0f;  // Eq. 3; zero padding applies to A3
-            word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2, cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+            a2[e] = t + bt[e];             // Eq. 2
+            a3[e] = (ok && a2[e] > 0.0f) ? a2[e] : 0.0f;  // Eq. 3; zero padding applies to A3
           }
           v = make_float4(a3[0], a3[1], a3[2], a3[3]);
-          if ((ownbits >> j) & 1u) {
-            const int64_t e0 = (int64_t)goff[j] + k_c0;  // flat element index of the first of 4 codes
-            if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
-            else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+          if (packs) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              word |= quant_code<(FUSE != 0 ? FUSE : 4)>(a2[e], cq[e], fb[e]) << ((FUSE != 0 ? FUSE : 4) * e);  // Eq. 9
+            if ((ownbits >> j) & 1u) {
+              const int64_t e0 = (int64_t)goff[j] + k_c0;  // flat element index of the first of 4 codes
+              if (FUSE == 4) reinterpret_cast<uint16_t*>(packed)[e0 >> 2] = (uint16_t)word;
+              else reinterpret_cast<uint32_t*>(packed)[e0 >> 2] = word;
+            }
           }
         }
         *reinterpret_cast<float4*>(&tileA[(idx >> 2) * PS + 4 * (idx & 3)]) = v;
@@ -409,6 +432,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
     // ones a tap needs, instead of draining all of them at every branch target.
     const int cn = more ? c0 + 16 : c0;
     fetch_a(cn, true);
+    PIN_VMEM();
     if (HOLD9) {
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
@@ -429,6 +453,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
         }
         // the same tap of the next chunk: a whole chunk of matrix work ahead of its use
         fetch_b(cn, t, bw[t]);
+        PIN_VMEM();
       }
     } else {
       int r = 0, s = 0;
@@ -436,6 +461,7 @@ __global__ __launch_bounds__(64 * NW) void halo_conv_kernel(const float* __restr
         {
           const bool last = t + 1 == taps;
           fetch_b(last ? cn : c0, last ? 0 : t + 1, bnext);
+          PIN_VMEM();
         }
         const int rr = MODE == 0 ? r : g.R - 1 - r, ss = MODE == 0 ? s : g.S - 1 - s;
         const int aoff = (rr * p.HW + ss) * PS;

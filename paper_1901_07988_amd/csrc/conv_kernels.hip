@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   // per-channel constants of the 4 channels this thread stages (fused forward)
   float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
   int4 k_fb;
-  int k_c = 0;
+  int k_c = 0, k_chunk = 0;
   // bit i / j: pass i of the A tile / pass j of the B tile holds real data.  The zeroing of the
   // rest happens when the tile is staged, so that nothing waits for the loads before the MFMAs
   // of the current chunk.
@@ -180,6 +180,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
       k_cq = *reinterpret_cast<const float4*>(stats + P_CQ * g.Cin + c);
       k_fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * g.Cin + c);
       k_c = c;
+      k_chunk = f_c0 / BK;
     }
     const float* wb = MODE == 0 ? wgt + ((int64_t)f_tap * g.Cin + f_c0) * g.Cout
                                 : wgt + (int64_t)f_tap * g.Cin * g.Cout + f_c0;
@@ -232,7 +233,9 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
           a3[e] = (ok && a2[e] > 0.0f) ? a2[e] : 0.0f;  // Eq. 3
         }
         v = make_float4(a3[0], a3[1], a3[2], a3[3]);
-        if (n0 == 0) {  // block-uniform: only the first output-channel block quantizes
+        // block-uniform: the output-channel blocks of a pixel tile take turns over the chunks in
+        // quantizing, so that each has the same amount of vector work
+        if (k_chunk % nblk_n == n0 / BN) {
           uint32_t word = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e)
