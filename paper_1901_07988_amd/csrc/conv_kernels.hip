@@ -399,8 +399,8 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   uint32_t wa[A_PASSES];
   bool oka[A_PASSES];
   float4 rb[B_PASSES];
-  uint32_t okb = 0;  // bit j: pass j of the dy tile is inside the slice (applied when it is staged, so
-                     // that nothing waits for the loads before the MFMAs of the current chunk)
+  int rem_st = 0;  // pixel rows of the chunk in rb[] that lie inside the slice (the rest is zeroed when
+                   // the chunk is staged, so that nothing waits for the loads before the MFMAs)
   // global loads of one 64-pixel chunk into registers
   // Output-pixel position (n, ho, wo) of each A pass, advanced by one chunk per fetch without
   // divisions; all loads are unconditional (clamped address, zeroed afterwards).
@@ -422,15 +422,17 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   // Addresses advance by a constant per chunk: every tensor has fewer than 2^31 elements, so
   // element offsets are 32-bit, computed once per pass and stepped (64-bit multiplies per load
   // and chunk took as long to issue as half the chunk's MFMAs).
-  int b_off[B_PASSES];    // element offset in dy of this pass at the current chunk
-  int b_row[B_PASSES];    // its pixel row within the chunk, CH if the pass never loads
+  // dy: one base per chunk (uniform, kept in scalar registers) plus a constant offset per pass -
+  // no vector arithmetic per load
+  unsigned b_off[B_PASSES];  // element offset of this pass from the chunk's first pixel, channel 0
+  int b_row[B_PASSES];       // its pixel row within the chunk, CH if the pass never loads
 #pragma unroll
   for (int j = 0; j < B_PASSES; ++j) {
     const int idx = tid + kThreads * j;
     const int pl = idx / GB, c = co0 + 4 * (idx % GB);
     const bool lane_ok = (CH * GB % kThreads == 0 || idx < CH * GB) && c < g.Cout;
     b_row[j] = lane_ok ? pl : CH;
-    b_off[j] = (int)((p_begin + pl) * g.Cout + c);
+    b_off[j] = (unsigned)(pl * g.Cout + c);
   }
   int a_off[A_PASSES];    // word offset in `packed` for 1x1 stride-1 layers (pixel p itself)
   int a_row[A_PASSES];
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     a_row[i] = lane_ok ? idx / GA : CH;
     a_off[i] = (int)(((p_begin + idx / GA) * g.Cin + ci0) / CPW) + a_cg;
   }
-  const int b_step = CH * g.Cout, a_step = CH * g.Cin / CPW;
+  const int a_step = CH * g.Cin / CPW;
   auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
     const int rem = (int)(p_end - pc < CH ? p_end - pc : CH);  // rows of this chunk inside the slice
 #pragma unroll
@@ -461,22 +463,19 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       if (a_wo[i] >= g.Wo) { a_wo[i] -= g.Wo; ++a_ho[i]; }
       if (a_ho[i] >= g.Ho) { a_ho[i] -= g.Ho; ++a_n[i]; }
     }
+    const float* dyc = dy + pc * g.Cout;  // rows outside the slice read the chunk's first element
 #pragma unroll
-    for (int j = 0; j < B_PASSES; ++j) {
-      const bool ok = b_row[j] < rem;
-      rb[j] = *reinterpret_cast<const float4*>(dy + (ok ? b_off[j] : 0));
-      b_off[j] += b_step;
-      okb = ok ? (okb | (1u << j)) : (okb & ~(1u << j));
-    }
+    for (int j = 0; j < B_PASSES; ++j) rb[j] = *reinterpret_cast<const float4*>(dyc + (b_row[j] < rem ? b_off[j] : 0u));
+    rem_st = rem;
   };
   if (p_begin < p_end) fetch(p_begin);
   // (the first chunk's loads are in flight while these constants arrive)
   // per-thread dequantization constants: the thread's channel group is the same in every pass
-  // Eq. 10 as one fused multiply-add per element: step * ((code - 2^(K-1) + fb) + 0.5) equals
-  // fma(step, code + off, step / 2) bit for bit while |fb| < 2^22 (any layer whose codes are
-  // not all saturated): code + off is then an exact integer, step / 2 is exact, and both forms
-  // round the same exact product once.
-  float step[CPW], off[CPW], half_step[CPW];
+  // Eq. 10 as one multiply per element: step * ((code - 2^(K-1) + fb) + 0.5) = step * (code + offh)
+  // with offh = fb - 2^(K-1) + 0.5, which fp32 holds exactly while |fb| < 2^22 (any layer whose
+  // codes are not all saturated), as it does code + offh: the product is rounded once, as in the
+  // formula.
+  float step[CPW], offh[CPW];
   if constexpr (CPW % 4 == 0) {  // the thread's channels are CPW consecutive ones: 16-byte loads, all in flight at once
     const bool ok = a_lane_ok;   // channel counts are multiples of 16 here, so a group is inside or outside as a whole
     const int c = ok ? ci0 + a_cg * CPW : 0;
@@ -494,8 +493,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         step[4 * v + e] = ok ? sv[e] : 0.f;
-        off[4 * v + e] = (float)((ok ? fv[e] : 0) - (1 << (K % 32 - 1)));
-        half_step[4 * v + e] = 0.5f * step[4 * v + e];
+        offh[4 * v + e] = (float)((ok ? fv[e] : 0) - (1 << (K % 32 - 1))) + 0.5f;
       }
     }
   } else {
@@ -505,8 +503,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       const bool ok = K != 32 && c < g.Cin;
       step[v] = ok ? stats[P_STEP * g.Cin + c] : 0.f;
       const int32_t fb = ok ? reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] : 0;
-      off[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1))));
-      half_step[v] = 0.5f * step[v];
+      offh[v] = (float)(fb - (K == 32 ? 0 : (1 << (K % 32 - 1)))) + 0.5f;
     }
   }
 
@@ -518,15 +515,29 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       if (CH * GA % kThreads == 0 || idx < CH * GA) {
         float* dst = &As[(idx / GA) * LDA + a_cg * CPW];
         float vals[CPW];
+        // Vector instructions and matrix instructions do not overlap on a SIMD, so every one here
+        // is matrix time lost: the codes are spread to one per byte (a byte converts to float in
+        // one instruction), and the ReLU and the zeroing of pixels outside the slice or the image
+        // are one median: med3(x, 0, inf) = max(x, 0), med3(x, 0, 0) = 0.
+        const float lim = oka[i] ? __builtin_inff() : 0.f;
+        uint32_t by[K == 4 ? 2 : 1];  // K == 4: codes 0,2,4,6 / 1,3,5,7 of the word, one per byte
+        if constexpr (K == 4) {
+          by[0] = wa[i] & 0x0F0F0F0Fu;
+          by[1] = (wa[i] >> 4) & 0x0F0F0F0Fu;
+        } else {
+          by[0] = wa[i];
+        }
 #pragma unroll
         for (int v = 0; v < CPW; ++v) {
           if constexpr (K == 32) {
             const float f = __uint_as_float(wa[i]);
             vals[v] = (oka[i] && !(relu32 != 0 && f < 0.f)) ? f : 0.f;
           } else {
-            const float code = (float)((wa[i] >> (K * v)) & ((1u << K) - 1));
-            const float a2t = __builtin_fmaf(step[v], code + off[v], half_step[v]);  // Eq. 10
-            vals[v] = oka[i] ? fmaxf(a2t, 0.f) : 0.f;                                // Eq. 3
+            const uint32_t src = K == 4 ? by[v & 1] : by[0];
+            const int b = K == 4 ? v >> 1 : v;
+            const float code = (float)((src >> (8 * b)) & 0xFFu);
+            const float a2t = step[v] * (code + offh[v]);         // Eq. 10
+            vals[v] = __builtin_amdgcn_fmed3f(a2t, 0.f, lim);     // Eq. 3
           }
         }
         // 16-byte writes: element-wise ones would land 64 lanes on four LDS banks
@@ -540,11 +551,19 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
         }
       }
     }
+    if (rem_st == CH && co0 + TN <= g.Cout) {  // block-uniform: every pass holds real data
 #pragma unroll
-    for (int j = 0; j < B_PASSES; ++j) {
-      const int idx = tid + kThreads * j;
-      if (idx < CH * GB)
-        *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = keep_if((okb >> j) & 1u, rb[j]);
+      for (int j = 0; j < B_PASSES; ++j) {
+        const int idx = tid + kThreads * j;
+        if (idx < CH * GB) *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = rb[j];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < B_PASSES; ++j) {
+        const int idx = tid + kThreads * j;
+        if (idx < CH * GB)
+          *reinterpret_cast<float4*>(&Bs[(idx / GB) * LDB + 4 * (idx % GB)]) = keep_if(b_row[j] < rem_st, rb[j]);
+      }
     }
     __syncthreads();
     if (pc + CH < p_end) fetch(pc + CH);  // in flight while this chunk is contracted
