@@ -350,7 +350,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
                                                          const float* __restrict__ stats,
                                                          const float* __restrict__ dy,
                                                          float* __restrict__ partial, ConvGeom g,
-                                                         int chunks_per_split, int nsplit, int relu32) {
+                                                         int chunks, int nsplit, int relu32) {
   constexpr int CH = 64;                                  // pixels per chunk
   constexpr int LDA = (TM % 32 == 0) ? TM + (TN == 128 ? 8 : 16) : TM;
   constexpr int LDB = (TN % 32 == 0) ? TN + (TN == 128 ? 8 : 16) : TN;
@@ -384,8 +384,10 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   const int r = tap / g.S, s = tap - r * g.S;
   const int ci0 = tm * TM, co0 = tn * TN;
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
-  const int64_t p_begin = (int64_t)split_idx * chunks_per_split * CH;
-  int64_t p_end = p_begin + (int64_t)chunks_per_split * CH;
+  // the slices differ by at most one 64-pixel chunk
+  const int ch_base = chunks / nsplit, ch_rem = chunks - ch_base * nsplit;
+  const int64_t p_begin = (int64_t)(split_idx * ch_base + (split_idx < ch_rem ? split_idx : ch_rem)) * CH;
+  int64_t p_end = p_begin + (int64_t)(ch_base + (split_idx < ch_rem ? 1 : 0)) * CH;
   if (p_end > Mg) p_end = Mg;
 
   const int a_cg = tid % GA;  // the thread's channel group is the same in every pass
@@ -424,7 +426,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   // and chunk took as long to issue as half the chunk's MFMAs).
   // dy: one base per chunk (uniform, kept in scalar registers) plus a constant offset per pass -
   // no vector arithmetic per load
-  unsigned b_off[B_PASSES];  // element offset of this pass from the chunk's first pixel, channel 0
+  unsigned b_off[B_PASSES];  // byte offset of this pass from the chunk's first pixel, channel 0
   int b_row[B_PASSES];       // its pixel row within the chunk, CH if the pass never loads
 #pragma unroll
   for (int j = 0; j < B_PASSES; ++j) {
@@ -432,20 +434,21 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
     const int pl = idx / GB, c = co0 + 4 * (idx % GB);
     const bool lane_ok = (CH * GB % kThreads == 0 || idx < CH * GB) && c < g.Cout;
     b_row[j] = lane_ok ? pl : CH;
-    b_off[j] = (unsigned)(pl * g.Cout + c);
+    b_off[j] = (unsigned)(pl * g.Cout + c) * 4u;
   }
-  int a_off[A_PASSES];    // word offset in `packed` for 1x1 stride-1 layers (pixel p itself)
+  unsigned a_off[A_PASSES];  // 1x1 stride-1 layers (pixel p itself): byte offset of the pass's word from
+                             // the word of the chunk's first pixel, channel 0
   int a_row[A_PASSES];
 #pragma unroll
   for (int i = 0; i < A_PASSES; ++i) {
     const int idx = tid + kThreads * i;
     const bool lane_ok = a_lane_ok && (CH * GA % kThreads == 0 || idx < CH * GA);
     a_row[i] = lane_ok ? idx / GA : CH;
-    a_off[i] = (int)(((p_begin + idx / GA) * g.Cin + ci0) / CPW) + a_cg;
+    a_off[i] = (unsigned)(((idx / GA) * g.Cin + ci0) / CPW + a_cg) * 4u;
   }
-  const int a_step = CH * g.Cin / CPW;
   auto fetch = [&](int64_t pc) __attribute__((always_inline)) {
     const int rem = (int)(p_end - pc < CH ? p_end - pc : CH);  // rows of this chunk inside the slice
+    const char* pkc = reinterpret_cast<const char*>(flat ? packed + pc * g.Cin / CPW : packed);
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
       // branch-free (a 1x1 stride-1 layer reads pixel p itself): a branch here would make the
@@ -453,9 +456,9 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       const int hi = a_ho[i] * g.stride + r - g.pad, wi = a_wo[i] * g.stride + s - g.pad;
       const bool inside = flat || (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W);
       oka[i] = a_row[i] < rem && inside;
-      const int word = flat ? a_off[i] : (((a_n[i] * g.H + hi) * g.W + wi) * g.Cin + ci0) / CPW + a_cg;
-      wa[i] = packed[oka[i] ? word : 0];
-      a_off[i] += a_step;
+      const unsigned word =
+          flat ? a_off[i] : (unsigned)((((a_n[i] * g.H + hi) * g.W + wi) * g.Cin + ci0) / CPW + a_cg) * 4u;
+      wa[i] = *reinterpret_cast<const uint32_t*>(pkc + (oka[i] ? word : 0u));
       // advance to the same slot of the next chunk
       a_wo[i] += adv_w;
       a_ho[i] += adv_h;
@@ -463,7 +466,7 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
       if (a_wo[i] >= g.Wo) { a_wo[i] -= g.Wo; ++a_ho[i]; }
       if (a_ho[i] >= g.Ho) { a_ho[i] -= g.Ho; ++a_n[i]; }
     }
-    const float* dyc = dy + pc * g.Cout;  // rows outside the slice read the chunk's first element
+    const char* dyc = reinterpret_cast<const char*>(dy + pc * g.Cout);  // rows outside the slice read its first element
 #pragma unroll
     for (int j = 0; j < B_PASSES; ++j) rb[j] = *reinterpret_cast<const float4*>(dyc + (b_row[j] < rem ? b_off[j] : 0u));
     rem_st = rem;
@@ -832,7 +835,7 @@ int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, 
 }
 
 struct WgradPlan {
-  int tm, tn, tiles, split, chunks_per_split;
+  int tm, tn, tiles, split, chunks;
 };
 
 WgradPlan wgrad_plan(const ConvGeom& g) {
@@ -851,8 +854,8 @@ WgradPlan wgrad_plan(const ConvGeom& g) {
   if (split > 256) split = 256;
   if (split > chunks / 2) split = chunks / 2;
   if (split < 1) split = 1;
-  p.chunks_per_split = (int)((chunks + split - 1) / split);
-  p.split = (int)((chunks + p.chunks_per_split - 1) / p.chunks_per_split);
+  p.chunks = (int)chunks;
+  p.split = (int)split;
   return p;
 }
 
@@ -939,7 +942,7 @@ static void launch_wgrad_tile(hipStream_t st, const ConvGeom& g, const WgradPlan
   auto kern = K == 4 ? (bf16 ? wgrad_kernel<TM, TN, 4, true, Q> : wgrad_kernel<TM, TN, 4, false, Q>)
             : K == 8 ? (bf16 ? wgrad_kernel<TM, TN, 8, true, Q> : wgrad_kernel<TM, TN, 8, false, Q>)
                      : (bf16 ? wgrad_kernel<TM, TN, 32, true, Q> : wgrad_kernel<TM, TN, 32, false, Q>);
-  kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks_per_split, p.split, relu32);
+  kern<<<grid, kThreads, 0, st>>>(pk, stats, dy, dst, g, p.chunks, p.split, relu32);
 }
 
 int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf16, const void* packed,
