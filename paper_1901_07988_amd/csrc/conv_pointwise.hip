@@ -37,6 +37,7 @@ namespace {
 constexpr int KC = 256;    // longest contraction whose weights stay in LDS for the whole block
 constexpr int CHC_N = 64;   // chunk length beyond that: four-wave blocks (the balanced grid, see below)
 constexpr int CHC_W = 128;  // ... eight-wave blocks
+constexpr int CHC_U8 = -1;  // template code: whole contraction in LDS, eight-wave blocks
 constexpr int PF = 4;      // 16-channel groups in flight per wave
 constexpr int NCONST = 6;  // per-channel constants of the fused prologue: mean rstd gamma beta cq fb
 
@@ -59,13 +60,13 @@ inline unsigned pointwise_lds_bytes(int Kd, int nt, bool fuse, bool wide) {
 // and of A1~ * dA2 (Eq. 7), with the layer's codes read here (`packed`, code_bits wide, and the
 // layer's `stats`), which saves the separate reduce pass over dA3.
 template <int MODE, int NT, int CHC, bool BF16, int FUSE, bool SUMS>
-__global__ __launch_bounds__(CHC == CHC_W ? 512 : 256, CHC == CHC_N ? 4 : 1) void pointwise_kernel(
+__global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC == CHC_N || CHC == CHC_U8) ? 4 : 1) void pointwise_kernel(
     const float* __restrict__ in, const float* __restrict__ wgt, const float* skip, float* out, int64_t M, int Kd,
     int N, int ldw, int run_base, int run_rem, const float* __restrict__ stats, void* __restrict__ packed,
     int pack_pad, double* __restrict__ sums, int code_bits, int main_grid, int rem_sub0) {
   static_assert(FUSE == 0 || MODE == 0, "the prologue belongs to the forward");
-  constexpr bool CHUNKED = CHC != 0;  // CHC: 0 (the whole contraction in LDS), CHC_N or CHC_W
-  constexpr int WAVES = CHC == CHC_W ? 8 : 4;
+  constexpr bool CHUNKED = CHC > 0;  // CHC: 0 or CHC_U8 (the whole contraction in LDS), CHC_N or CHC_W
+  constexpr int WAVES = (CHC == CHC_W || CHC == CHC_U8) ? 8 : 4;
   constexpr int CQ4 = CHUNKED ? CHC / 4 : 1;  // 16-byte items of a chunk row
   static_assert(!(CHUNKED && SUMS), "the sums are kept by the unchunked kernels only");
   constexpr int kThreads = 64 * WAVES;
@@ -99,11 +100,19 @@ __global__ __launch_bounds__(CHC == CHC_W ? 512 : 256, CHC == CHC_N ? 4 : 1) voi
   constexpr int planes[NCONST] = {P_MEAN, P_RSTD, P_GAMMA, P_BETA, P_CQ, P_FB};
   if (!CHUNKED) {  // the whole slice of the weights (and the prologue constants), once
     const int q4 = Kd >> 2;
-    if (MODE == 0) {  // transposed on the way: four k rows of column n -> one 16-byte write
+    if (MODE == 0) {
+      // transposed on the way: 16-byte loads along the output channels (the tensor's contiguous
+      // direction), element-wise LDS writes.  A wave takes 16 k x 16 channels per step: its
+      // writes of one element each land 4 banks apart per channel and one apart per k, on all 32
+      // banks.
       for (int idx = tid; idx < BN * q4; idx += kThreads) {
-        const int n = idx % BN, q = idx / BN;
-        const float* src = wgt + (int64_t)(4 * q) * ldw + n0 + n;
-        *reinterpret_cast<float4*>(&Ws[n * LDW + 4 * q]) = make_float4(src[0], src[ldw], src[2 * ldw], src[3 * ldw]);
+        const int l = idx & 63, up = idx >> 6;
+        const int k = 16 * (up / NT) + (l & 15), n = 16 * (up % NT) + 4 * (l >> 4);
+        const float4 v = *reinterpret_cast<const float4*>(wgt + (int64_t)k * ldw + n0 + n);
+        Ws[(n + 0) * LDW + k] = v.x;
+        Ws[(n + 1) * LDW + k] = v.y;
+        Ws[(n + 2) * LDW + k] = v.z;
+        Ws[(n + 3) * LDW + k] = v.w;
       }
     } else {
       for (int idx = tid; idx < BN * q4; idx += kThreads) {
@@ -455,6 +464,7 @@ struct PointwisePlan {
   int nt;
   bool chunked;
   bool wide;  // chunked with eight-wave blocks and CHC_W-channel chunks
+  bool u8;    // unchunked with eight-wave blocks
   int run_base, run_rem;
   int rows;  // blocks per output-channel block that have tiles (= rows of sums)
   unsigned grid;
@@ -462,7 +472,7 @@ struct PointwisePlan {
   int rem_sub0;   // first 16-pixel row group of the split part
 };
 
-bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, PointwisePlan& p) {
+bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, PointwisePlan& p) {
   if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
   const int Kd = mode == 0 ? g.Cin : g.Cout, N = mode == 0 ? g.Cout : g.Cin;
   if (Kd % 64 != 0 || N % 16 != 0) return false;
@@ -485,10 +495,15 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, PointwisePlan& 
   // as many blocks as fit the compute units at once (the weights' LDS; four waves per SIMD)
   const unsigned lds = pointwise_lds_bytes(Kd, p.nt, fuse, p.wide);
   int occ = (int)((160u * 1024u) / lds);
-  const int occ_max = p.wide ? 2 : 4;
+  // a long unchunked contraction leaves LDS for two blocks: eight waves each, or a SIMD would
+  // have only two waves to hide its loads and stores with
+  // (measured: not where the kernel also keeps the Eq. 6-7 sums - their registers do not fit four
+  // waves per SIMD - nor where a single output-channel block does all of the quantizing)
+  p.u8 = !p.chunked && occ <= 2 && !(sums && mode == 1) && !(fuse && nblk_n < 4);
+  const int occ_max = p.wide || p.u8 ? 2 : 4;
   if (occ > occ_max) occ = occ_max;
   if (occ < 1) occ = 1;
-  const int bm = p.wide ? 128 : 64;
+  const int bm = p.wide || p.u8 ? 128 : 64;
   int64_t mtiles = (M + bm - 1) / bm;
   int64_t rem_sub = 0;
   if (balanced) {
@@ -512,7 +527,7 @@ template <int MODE, int FUSE>
 int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, const float* w, const float* skip,
                      float* out, const float* stats, void* packed, double* sums, int* rows, int code_bits = 0) {
   PointwisePlan p;
-  if (!make_pointwise_plan(g, MODE, FUSE != 0, p)) return ABL_ERR_SHAPE;
+  if (!make_pointwise_plan(g, MODE, FUSE != 0, sums != nullptr, p)) return ABL_ERR_SHAPE;
   const int64_t M = (int64_t)g.N * g.H * g.W;
   const int Kd = MODE == 0 ? g.Cin : g.Cout, N = MODE == 0 ? g.Cout : g.Cin;
   const int64_t raw = FUSE != 0 ? (M * Kd * FUSE + 7) / 8 : 0;
@@ -528,13 +543,13 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
   } while (0)
 #define ABL_PW_S(NT_, CHC_, SUMS_)                                                                           \
   do {                                                                                                       \
-    auto kern = bf16 ? pointwise_kernel<MODE, NT_, CHC_, true, FUSE, (SUMS_) && (CHC_) == 0>                 \
-                     : pointwise_kernel<MODE, NT_, CHC_, false, FUSE, (SUMS_) && (CHC_) == 0>;               \
+    auto kern = bf16 ? pointwise_kernel<MODE, NT_, CHC_, true, FUSE, (SUMS_) && (CHC_) <= 0>                 \
+                     : pointwise_kernel<MODE, NT_, CHC_, false, FUSE, (SUMS_) && (CHC_) <= 0>;               \
     if (lds > 64 * 1024 &&                                                                                   \
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             lds) != hipSuccess)                                                              \
       return ABL_ERR_HIP;                                                                                    \
-    kern<<<p.grid, (CHC_) == CHC_W ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,   \
+    kern<<<p.grid, (CHC_) == CHC_W || (CHC_) == CHC_U8 ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,   \
                                                            p.run_rem, stats, packed, pack_pad, sums,         \
                                                            code_bits, p.main_grid, p.rem_sub0);              \
   } while (0)
@@ -542,6 +557,7 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
   do {                                     \
     if (p.wide) ABL_PW(NT_, CHC_W);        \
     else if (p.chunked) ABL_PW(NT_, CHC_N); \
+    else if (p.u8) ABL_PW(NT_, CHC_U8);    \
     else ABL_PW(NT_, 0);                   \
   } while (0)
   if (p.nt == 4) ABL_PW_C(4);
@@ -564,7 +580,7 @@ int launch_pointwise_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, bool
 
 bool pointwise_supported(const ConvGeom& g, int mode) {
   PointwisePlan p;
-  return make_pointwise_plan(g, mode, false, p);
+  return make_pointwise_plan(g, mode, false, false, p);
 }
 
 int launch_pointwise_conv(hipStream_t st, const ConvGeom& g, int mode, bool bf16, const float* in, const float* w,
