@@ -781,13 +781,16 @@ def test_average_pool_folded_into_linear(G, oracle, s, pool):
 
 @pytest.mark.parametrize("N,H,W,Cin,Cout", [
     (1, 1, 1, 64, 16), (3, 5, 7, 128, 48), (2, 9, 9, 192, 96), (5, 6, 6, 256, 320), (1, 13, 11, 384, 64),
-    (2, 8, 8, 512, 272), (7, 3, 3, 1024, 128), (1, 40, 40, 64, 64), (4, 17, 5, 640, 192), (2, 5, 5, 320, 64)],
+    (2, 8, 8, 512, 272), (7, 3, 3, 1024, 128), (1, 40, 40, 64, 64), (4, 17, 5, 640, 192), (2, 5, 5, 320, 64),
+    (1, 67, 126, 512, 256), (1, 67, 126, 256, 512)],
     ids=lambda v: str(v))
 def test_pointwise_convolutions(G, oracle, N, H, W, Cin, Cout):
     """1x1 stride-1 layers through the kernel that loads activations straight into MFMA layout:
-    contractions held whole in LDS (up to 256 channels) and in 128-channel chunks, one to four
-    16-channel tiles per wave, pixel counts that leave ragged tiles and idle blocks; 320 input
-    channels (a multiple of 64 but not of 128 beyond 256) fall back to the tiled kernel."""
+    contractions held whole in LDS (up to 256 channels, four- and eight-wave blocks) and in 64- or
+    128-channel chunks, one to four 16-channel tiles per wave, pixel counts that leave ragged
+    tiles and idle blocks; the two largest cases have enough pixels (8442, not a multiple of 16)
+    for the grid of whole rounds plus row groups split over the contraction, forward (512 -> 256)
+    and data gradient (256 -> 512)."""
     o = oracle
     s = LayerShape(N, H, W, Cin, Cout, 1, 1, 1, 0)
     print("case pointwise", s.as_tuple(), flush=True)
