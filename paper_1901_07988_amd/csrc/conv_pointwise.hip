@@ -24,7 +24,9 @@
 // There the grid is cut in two: whole rounds of one tile per SIMD, and the pixel rows left over
 // in blocks whose four waves share one 16-pixel row group and take a quarter of the contraction
 // each - a quarter of a tile's time.
+#include <mutex>
 #include <type_traits>
+#include <unordered_map>
 
 #include "abl_internal.h"
 
@@ -256,18 +258,18 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) s1[j][r] = s2[j][r] = (sum_t)0;
-    // dgrad sums: Eq. 10 constants of the lane's channels n0 + 16j + 4lk .. +3
-    float4 r_step[NT], r_beta[NT], r_ig[NT];
-    int4 r_fb[NT];
+    // dgrad sums: Eq. 10 constants of the lane's channels n0 + 16j + 4lk .. +3.  Eq. 10 is one add
+    // and one multiply: step * ((code - 2^(K-1) + fb) + 0.5) = step * (code + offh), offh exact in
+    // fp32 while |fb| < 2^22.
+    float4 r_step[NT], r_offh[NT];
     if (SUMS && MODE == 1) {
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int c = n0 + 16 * j + 4 * lk;
         r_step[j] = *reinterpret_cast<const float4*>(stats + P_STEP * N + c);
-        r_beta[j] = *reinterpret_cast<const float4*>(stats + P_BETA * N + c);
-        const float4 gm = *reinterpret_cast<const float4*>(stats + P_GAMMA * N + c);
-        r_ig[j] = make_float4(1.0f / gm.x, 1.0f / gm.y, 1.0f / gm.z, 1.0f / gm.w);
-        r_fb[j] = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * N + c);
+        const int4 fb = *reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(stats) + P_FB * N + c);
+        const float half = 0.5f - (float)(1 << (code_bits - 1));
+        r_offh[j] = make_float4((float)fb.x + half, (float)fb.y + half, (float)fb.z + half, (float)fb.w + half);
       }
     }
 
@@ -280,6 +282,25 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
       floatx4 acc[NT][1];  // acc[j][0][r]: pixel prow, channel n0 + 16j + 4lk + r
 #pragma unroll
       for (int j = 0; j < NT; ++j) acc[j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+      // What the epilogue reads from memory is requested now, without branches on the lane: asked
+      // for between the tile's stores, each value would cost a wait for the store before it as
+      // well (a load's wait covers everything older), four memory round trips in a row per tile.
+      float4 skv[NT];
+      uint32_t cwv[NT];
+      {
+        const int64_t o0 = (pok ? prow : 0) * N + n0 + 4 * lk;
+        if (skip != nullptr) {
+#pragma unroll
+          for (int j = 0; j < NT; ++j) skv[j] = *reinterpret_cast<const float4*>(skip + o0 + 16 * j);
+        }
+        if (SUMS && MODE == 1) {
+          const uint8_t* codes = static_cast<const uint8_t*>(packed);
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            cwv[j] = code_bits == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + ((o0 + 16 * j) >> 1))
+                                    : *reinterpret_cast<const uint32_t*>(codes + o0 + 16 * j);
+        }
+      }
 
       for (int c = 0; c < NC; ++c, ++step) {
         const int buf = CHUNKED ? (step & 1) : 0;
@@ -327,7 +348,7 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
           const int64_t o = prow * N + n0 + 16 * j + 4 * lk;
           float4 v = make_float4(acc[j][0][0], acc[j][0][1], acc[j][0][2], acc[j][0][3]);
           if (skip != nullptr) {
-            const float4 sv = *reinterpret_cast<const float4*>(skip + o);
+            const float4 sv = skv[j];
             v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
           }
           *reinterpret_cast<float4*>(out + o) = v;
@@ -341,23 +362,33 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
             }
           }
           if (SUMS && MODE == 1) {
-            const uint8_t* codes = static_cast<const uint8_t*>(packed);
-            const uint32_t cw = code_bits == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o >> 1))
-                                               : *reinterpret_cast<const uint32_t*>(codes + o);
+            // Eq. 6 and the sum of Eq. 7 by linearity: sum A1~ dA2 = (sum A2~ dA2 - beta sum dA2) / gamma,
+            // so a lane adds up dA2 and A2~ dA2 (a handful of pixels in fp32, fp64 from the reduction
+            // over lanes on) and beta, gamma enter once per block - vector instructions cost matrix
+            // time here, and this epilogue runs once per 16 x 64 outputs.
+            const uint32_t cw = cwv[j];
+            // one code per byte (a byte at a fixed position converts to float in one instruction); K = 4:
+            // codes 0, 2 in the bytes of one word, codes 1, 3 in those of the other
+            float code[4];
+            if (code_bits == 4) {  // uniform
+              const uint32_t ce = cw & 0x0F0Fu, co = (cw >> 4) & 0x0F0Fu;
+              code[0] = (float)(ce & 0xFFu);
+              code[1] = (float)(co & 0xFFu);
+              code[2] = (float)((ce >> 8) & 0xFFu);
+              code[3] = (float)((co >> 8) & 0xFFu);
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) code[r] = (float)((cw >> (8 * r)) & 0xFFu);
+            }
             const float vs[4] = {v.x, v.y, v.z, v.w};
             const float st4[4] = {r_step[j].x, r_step[j].y, r_step[j].z, r_step[j].w};
-            const float bt4[4] = {r_beta[j].x, r_beta[j].y, r_beta[j].z, r_beta[j].w};
-            const float ig4[4] = {r_ig[j].x, r_ig[j].y, r_ig[j].z, r_ig[j].w};
-            const int32_t fb4[4] = {r_fb[j].x, r_fb[j].y, r_fb[j].z, r_fb[j].w};
+            const float oh4[4] = {r_offh[j].x, r_offh[j].y, r_offh[j].z, r_offh[j].w};
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const uint32_t code = (cw >> (code_bits * r)) & ((1u << code_bits) - 1u);
-              const int32_t jj = (int32_t)code - (1 << (code_bits - 1)) + fb4[r];
-              const float a2t = st4[r] * ((float)jj + 0.5f);       // Eq. 10
+              const float a2t = st4[r] * (code[r] + oh4[r]);       // Eq. 10
               const float da2 = a2t > 0.0f ? vs[r] : 0.0f;         // Eq. 6
-              const float a1t = (a2t - bt4[r]) * ig4[r];           // inverse of Eq. 2
               s1[j][r] += da2;
-              s2[j][r] += a1t * da2;
+              s2[j][r] = __builtin_fmaf(a2t, da2, s2[j][r]);
             }
           }
         }
@@ -385,12 +416,17 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
           }
         }
       __syncthreads();
-      for (int c = tid; c < 2 * BN; c += kThreads) {
-        const int qv = c / BN, ch = c % BN;
-        double t = 0.0;
+      for (int ch = tid; ch < BN; ch += kThreads) {
+        double t1 = 0.0, t2 = 0.0;
 #pragma unroll
-        for (int k = 0; k < WAVES; ++k) t += red[(qv * WAVES + k) * BN + ch];
-        sums[((int64_t)run * 2 + qv) * N + n0 + ch] = t;
+        for (int k = 0; k < WAVES; ++k) {
+          t1 += red[(0 * WAVES + k) * BN + ch];
+          t2 += red[(1 * WAVES + k) * BN + ch];
+        }
+        if (MODE == 1)  // the lanes added up A2~ dA2: A1~ = (A2~ - beta) / gamma (inverse of Eq. 2)
+          t2 = (t2 - (double)stats[P_BETA * N + n0 + ch] * t1) / (double)stats[P_GAMMA * N + n0 + ch];
+        sums[((int64_t)run * 2 + 0) * N + n0 + ch] = t1;
+        sums[((int64_t)run * 2 + 1) * N + n0 + ch] = t2;
       }
     }
   };
@@ -472,7 +508,26 @@ struct PointwisePlan {
   int rem_sub0;   // first 16-pixel row group of the split part
 };
 
-bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, PointwisePlan& p) {
+// Blocks of a kernel that its registers allow on one compute unit (asked of the runtime once per
+// kernel).  The grid is sized to what is resident at once: a plan that counts on four blocks per
+// unit where the registers admit three leaves a quarter of the blocks for a second, mostly empty
+// round.
+int resident_blocks(const void* kern, int threads) {
+  static std::mutex mu;
+  static std::unordered_map<const void*, int> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(kern);
+  if (it != cache.end()) return it->second;
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, 0) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    n = 1;
+  }
+  cache.emplace(kern, n);
+  return n;
+}
+
+bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, PointwisePlan& p, int occ_regs = 4) {
   if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
   const int Kd = mode == 0 ? g.Cin : g.Cout, N = mode == 0 ? g.Cout : g.Cin;
   if (Kd % 64 != 0 || N % 16 != 0) return false;
@@ -502,6 +557,7 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, Poin
   p.u8 = !p.chunked && occ <= 2 && !(sums && mode == 1) && !(fuse && nblk_n < 4);
   const int occ_max = p.wide || p.u8 ? 2 : 4;
   if (occ > occ_max) occ = occ_max;
+  if (occ > occ_regs) occ = occ_regs;
   if (occ < 1) occ = 1;
   const int bm = p.wide || p.u8 ? 128 : 64;
   int64_t mtiles = (M + bm - 1) / bm;
@@ -549,6 +605,11 @@ int launch_pointwise(hipStream_t st, const ConvGeom& g, bool bf16, const float* 
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                             lds) != hipSuccess)                                                              \
       return ABL_ERR_HIP;                                                                                    \
+    /* same variant, grid sized to the blocks the kernel's registers allow per compute unit */              \
+    make_pointwise_plan(g, MODE, FUSE != 0, sums != nullptr, p,                                              \
+                        resident_blocks(reinterpret_cast<const void*>(kern),                                 \
+                                        (CHC_) == CHC_W || (CHC_) == CHC_U8 ? 512 : 256));                   \
+    if (rows != nullptr) *rows = sums != nullptr ? p.rows : 0;                                               \
     kern<<<p.grid, (CHC_) == CHC_W || (CHC_) == CHC_U8 ? 512 : 256, lds, st>>>(in, w, skip, out, M, Kd, N, g.Cout, p.run_base,   \
                                                            p.run_rem, stats, packed, pack_pad, sums,         \
                                                            code_bits, p.main_grid, p.rem_sub0);              \
