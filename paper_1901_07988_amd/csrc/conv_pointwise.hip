@@ -95,9 +95,23 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
   if (FUSE != 0 && blockIdx.x == 0 && tid < pack_pad)  // tail of the last 128-byte row of codes
     static_cast<uint8_t*>(packed)[(M * Kd * FUSE) / 8 + tid] = 0;
   // tiles of BM pixels, or (split blocks) of one 16-pixel row group
-  const int64_t t_begin = split ? rem_sub0 + rem_i / nblk_n : (int64_t)run * run_base + (run < run_rem ? run : run_rem);
-  const int64_t t_end = split ? t_begin + 1 : t_begin + run_base + (run < run_rem ? 1 : 0);
-  if (t_end == t_begin) return;
+  // Eight-wave unchunked blocks (DEAL): nothing ties the waves of a block to each other inside
+  // the tile loop, so the 16-pixel row groups are dealt to the waves directly - wave w of all
+  // (run_base blocks x 8) takes groups [w * groups / waves, (w + 1) * groups / waves) - and no
+  // wave has more than one group above the average (128-pixel tiles per block: 3.06 tiles per
+  // block meant 4 for some).
+  constexpr bool DEAL = CHC == CHC_U8;
+  int64_t t_begin, t_end;
+  if (!DEAL) {
+    t_begin = split ? rem_sub0 + rem_i / nblk_n : (int64_t)run * run_base + (run < run_rem ? run : run_rem);
+    t_end = split ? t_begin + 1 : t_begin + run_base + (run < run_rem ? 1 : 0);
+    if (t_end == t_begin) return;
+  } else {  // (a wave without groups still takes part in the barriers)
+    const int64_t groups = (M + 15) >> 4, waves = (int64_t)run_base * WAVES;
+    const int64_t gw = (int64_t)run * WAVES + __builtin_amdgcn_readfirstlane(tid >> 6);
+    t_begin = gw * groups / waves;
+    t_end = (gw + 1) * groups / waves;
+  }
 
   constexpr int planes[NCONST] = {P_MEAN, P_RSTD, P_GAMMA, P_BETA, P_CQ, P_FB};
   if (!CHUNKED) {  // the whole slice of the weights (and the prologue constants), once
@@ -237,7 +251,7 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
     // The ring of loads runs on across pixel tiles: while a tile's last groups are contracted
     // and its results stored, the first groups of the block's next tile are already in flight.
     auto row_ptr = [&](int64_t tile) __attribute__((always_inline)) {
-      const int64_t p = tile * BM + wave * 16 + li;
+      const int64_t p = DEAL ? tile * 16 + li : tile * BM + wave * 16 + li;
       return in + (p < M ? p : 0) * Kd + 4 * lk;  // rows past the end read row 0 and are never stored
     };
     const float* xp = row_ptr(t_begin);
@@ -277,7 +291,7 @@ __global__ __launch_bounds__((CHC == CHC_W || CHC == CHC_U8) ? 512 : 256, (CHC =
     for (int64_t tile = t_begin; tile < t_end; ++tile) {
       const bool has_next = tile + 1 < t_end;
       const float* xpn = row_ptr(has_next ? tile + 1 : tile);
-      const int64_t prow = tile * BM + wave * 16 + li;
+      const int64_t prow = DEAL ? tile * 16 + li : tile * BM + wave * 16 + li;
       const bool pok = prow < M;
       floatx4 acc[NT][1];  // acc[j][0][r]: pixel prow, channel n0 + 16j + 4lk + r
 #pragma unroll
@@ -553,7 +567,7 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, Poin
   // a long unchunked contraction leaves LDS for two blocks: eight waves each, or a SIMD would
   // have only two waves to hide its loads and stores with
   // (measured: not where the kernel also keeps the Eq. 6-7 sums - their registers do not fit four
-  // waves per SIMD - nor where a single output-channel block does all of the quantizing)
+  // waves per SIMD - and no gain where a single output-channel block does all of the quantizing)
   p.u8 = !p.chunked && occ <= 2 && !(sums && mode == 1) && !(fuse && nblk_n < 4);
   const int occ_max = p.wide || p.u8 ? 2 : 4;
   if (occ > occ_max) occ = occ_max;
@@ -570,9 +584,15 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, Poin
   if (runs > kMaxPartialBlocks) runs = kMaxPartialBlocks;  // one row of sums per block
   if (runs < 8) runs = 8;
   if (runs > (mtiles + 7) / 8 * 8) runs = (mtiles + 7) / 8 * 8;
-  p.run_base = runs > 0 ? (int)(mtiles / runs) : 0;
-  p.run_rem = runs > 0 ? (int)(mtiles % runs) : 0;
-  p.rows = p.run_base > 0 ? (int)runs : p.run_rem;
+  if (p.u8) {  // the kernel deals the row groups to the waves of `runs` blocks itself
+    p.run_base = (int)runs;
+    p.run_rem = 0;
+    p.rows = (int)runs;
+  } else {
+    p.run_base = runs > 0 ? (int)(mtiles / runs) : 0;
+    p.run_rem = runs > 0 ? (int)(mtiles % runs) : 0;
+    p.rows = p.run_base > 0 ? (int)runs : p.run_rem;
+  }
   p.main_grid = (int)(runs * nblk_n);
   p.rem_sub0 = (int)(4 * mtiles);
   p.grid = (unsigned)(p.main_grid + rem_sub * nblk_n);
