@@ -566,9 +566,9 @@ bool make_pointwise_plan(const ConvGeom& g, int mode, bool fuse, bool sums, Poin
   int occ = (int)((160u * 1024u) / lds);
   // a long unchunked contraction leaves LDS for two blocks: eight waves each, or a SIMD would
   // have only two waves to hide its loads and stores with
-  // (measured: not where the kernel also keeps the Eq. 6-7 sums - their registers do not fit four
-  // waves per SIMD - and no gain where a single output-channel block does all of the quantizing)
-  p.u8 = !p.chunked && occ <= 2 && !(sums && mode == 1) && !(fuse && nblk_n < 4);
+  // (not where the kernel also keeps per-channel sums - their registers do not fit four waves per
+  // SIMD - and, measured, no gain where a single output-channel block does all of the quantizing)
+  p.u8 = !p.chunked && occ <= 2 && !sums && !(fuse && nblk_n < 4);
   const int occ_max = p.wide || p.u8 ? 2 : 4;
   if (occ > occ_max) occ = occ_max;
   if (occ > occ_regs) occ = occ_regs;
