@@ -78,15 +78,15 @@ def time_events(fn, reps, nset=1):
 S3 = "64x14x14x256x256x3x3x1x1"
 MEASURED_TRAFFIC = {
     ("config5", 4, "fp32"): {
-        (S3, "bn_conv_fwd"): 46.51e6,            # x 12.8 MB + the weights once per XCD (8 x 2.4 MB) + y + codes
+        (S3, "bn_conv_fwd"): 46.50e6,            # x 12.8 MB + the weights once per XCD (8 x 2.4 MB) + y + codes
         (S3, "conv_dgrad_bn_reduce"): 46.62e6,
-        ("64x14x14x1024x256x1x1x1x0", "bn_conv_fwd"): 87.15e6,
-        ("64x14x14x1024x256x1x1x1x0", "conv_dgrad_bn_reduce"): 79.89e6,
+        ("64x14x14x1024x256x1x1x1x0", "bn_conv_fwd"): 86.82e6,
+        ("64x14x14x1024x256x1x1x1x0", "conv_dgrad_bn_reduce"): 79.86e6,
     },
     ("config4", 4, "fp32"): {
-        ("64x56x56x64x64x3x3x1x1", "bn_conv_fwd"): 143.18e6,
-        ("64x56x56x64x64x3x3x1x1", "conv_dgrad_bn_reduce"): 119.49e6,
-        ("64x56x56x256x64x1x1x1x0", "bn_conv_fwd"): 288.79e6,
+        ("64x56x56x64x64x3x3x1x1", "bn_conv_fwd"): 143.07e6,
+        ("64x56x56x64x64x3x3x1x1", "conv_dgrad_bn_reduce"): 119.33e6,
+        ("64x56x56x256x64x1x1x1x0", "bn_conv_fwd"): 288.55e6,
     },
     ("config2", 4, "fp32"): {
         ("128x32x32x16x16x3x3x1x1", "bn_conv_fwd"): 23.77e6,         # in the stack: half the layers also read a shortcut
