@@ -79,12 +79,14 @@ S3 = "64x14x14x256x256x3x3x1x1"
 MEASURED_TRAFFIC = {
     ("config5", 4, "fp32"): {
         (S3, "bn_conv_fwd"): 46.50e6,            # x 12.8 MB + the weights once per XCD (8 x 2.4 MB) + y + codes
+        (S3, "conv_fwd"): 45.04e6,
         (S3, "conv_dgrad_bn_reduce"): 46.62e6,
         ("64x14x14x1024x256x1x1x1x0", "bn_conv_fwd"): 86.82e6,
         ("64x14x14x1024x256x1x1x1x0", "conv_dgrad_bn_reduce"): 79.86e6,
     },
     ("config4", 4, "fp32"): {
         ("64x56x56x64x64x3x3x1x1", "bn_conv_fwd"): 143.07e6,
+        ("64x56x56x64x64x3x3x1x1", "conv_fwd"): 120.12e6,
         ("64x56x56x64x64x3x3x1x1", "conv_dgrad_bn_reduce"): 119.33e6,
         ("64x56x56x256x64x1x1x1x0", "bn_conv_fwd"): 288.55e6,
     },
@@ -95,12 +97,15 @@ MEASURED_TRAFFIC = {
 }
 
 
-def kernel_breakdown(G, B, s, K, reps, flags=0):
+def kernel_breakdown(G, B, s, K, reps, flags=0, in_place=False):
     """Per-kernel timing of one layer shape with HIP events on the stream the kernels run on
     (torch's current stream, which is the one handed to the library).  Where the shape has the
     fused kernels (3x3 'same' stride-1 layers) these are the kernels the layer step runs; the
     separate stages are timed as well.  Returns {stage: dict(ms, bytes, flops, launches, step)} with
-    ALGORITHMIC bytes / flops per call; step=True marks the stages that make up one layer step."""
+    ALGORITHMIC bytes / flops per call; step=True marks the stages that make up one layer step.
+    in_place: every layer of this shape in the stack runs in place on the shared buffer (the middle
+    layers of a residual group), where the forward with the fused prologue cannot be used: the step
+    then consists of the normalise-ReLU-pack pass and the plain forward."""
     import torch
     t = s.as_tuple()
     M, C, E = s.M, s.Cin, s.E
@@ -143,13 +148,14 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
             bwd_fused = False
     conv_bytes = 4 * E + 4 * Eo + wbytes
     S = sets
+    fwd_fused_step = fwd_fused and not in_place
     # name: (call on operand set i, algorithmic bytes, flops, launches, part of the layer step)
     stages = {
         "bn_stats": (lambda i: B.abl_bn_stats(S[i]["x"], M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2, not fused),
         "bn_relu_pack": (lambda i: B.abl_bn_relu_pack(S[i]["x"], M, C, K, stats, S[i]["a3"], S[i]["packed"]),
-                         8 * E + P, 0, 1, not fwd_fused),
+                         8 * E + P, 0, 1, not fwd_fused_step),
         "conv_fwd": (lambda i: B.abl_conv_fwd(t, S[i]["a3"], w, None, S[i]["y"], flags=flags), conv_bytes, flops, 1,
-                     not fwd_fused),
+                     not fwd_fused_step),
         "conv_dgrad": (lambda i: B.abl_conv_dgrad(t, S[i]["dy"], w, S[i]["dx"], flags=flags), conv_bytes, flops, 1,
                        not fused),
         "conv_wgrad_packed": (lambda i: B.abl_conv_wgrad_packed(t, K, S[i]["packed"], stats, S[i]["dy"], scratch, dw,
@@ -162,7 +168,7 @@ def kernel_breakdown(G, B, s, K, reps, flags=0):
     }
     if fwd_fused:
         stages["bn_conv_fwd"] = (lambda i: B.abl_bn_conv_fwd(t, K, S[i]["x"], stats, w, None, S[i]["y"], S[i]["packed"],
-                                                             flags=flags), conv_bytes + P, flops, 1, True)
+                                                             flags=flags), conv_bytes + P, flops, 1, fwd_fused_step)
     if fused:
         stages["conv_dgrad_bn_reduce"] = (
             lambda i: B.abl_conv_dgrad_bn_reduce(t, K, S[i]["dy"], w, S[i]["packed"], stats, scratch, S[i]["dx"],
@@ -366,11 +372,18 @@ def main():
     shapes = {}
     for s in wl.shapes:
         shapes[s] = shapes.get(s, 0) + 1
+    # layers that the stack runs in place (include/abl.h, abl_stack_forward: the middle layers of a
+    # complete residual group; of an odd chain outside the groups, the first)
+    g = wl.skip_every
+    n_grouped = (L // g) * g if g > 0 else 0
+    in_place_layer = [(g > 0 and i < n_grouped and 0 < i % g < g - 1) or
+                      (i == n_grouped and (L - n_grouped) % 2 == 1) for i in range(L)]
+    in_place_shape = {s: all(in_place_layer[i] for i, t in enumerate(wl.shapes) if t == s) for s in shapes}
     per_step = {}
     breakdown = {}
     details = {}
     for s, count in shapes.items():
-        bd = kernel_breakdown(G, B, s, K, args.kernel_reps, flags)
+        bd = kernel_breakdown(G, B, s, K, args.kernel_reps, flags, in_place_shape[s])
         details[s] = bd
         breakdown["x".join(map(str, s.as_tuple()))] = {k: round(v["ms"] * 1e3, 2) for k, v in bd.items()}
         for k, v in bd.items():
