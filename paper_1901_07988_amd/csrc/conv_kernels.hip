@@ -36,7 +36,13 @@ constexpr int kThreads = 256;
 // input x; BatchNorm, scale & bias and ReLU (Eq. 1-3) are applied to the A tile on its way into
 // LDS and the blocks of the first output-channel block also write the K-bit codes (Eq. 9), so A3
 // never reaches memory.  pack_pad: zero bytes after the last code.
-template <int BM, int BN, int WM, int WN, int BK, int MODE, bool BF16, int FUSE>
+// CLS (dgrad of a strided convolution): an input pixel (h, w) receives the taps with
+// (h + pad - r) and (w + pad - s) divisible by the stride only - with stride 2, one, two, two or
+// four of nine, and for a 1x1 filter three pixels in four receive nothing.  The pixels are
+// therefore enumerated class by class ((h mod stride, w mod stride), each class's tiles after the
+// previous one's), so that a block's pixels share their taps and the block contracts just those
+// (all taps for every pixel, with the misses zeroed, is four times the matrix work).
+template <int BM, int BN, int WM, int WN, int BK, int MODE, bool BF16, int FUSE, bool CLS = false>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict__ in,
                                                          const float* __restrict__ wgt,
                                                          const float* skip, float* out, ConvGeom g,
@@ -71,11 +77,49 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   // they run on one XCD back to back and the tile comes from HBM once.
   const int nblk_n = (Ng + BN - 1) / BN;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int64_t m0 = ((int64_t)(slot / nblk_n) * 8 + xcd) * BM;
+  int64_t m0 = ((int64_t)(slot / nblk_n) * 8 + xcd) * BM;
   const int n0 = (slot % nblk_n) * BN;
   if (FUSE != 0 && blockIdx.x == 0 && (int)threadIdx.x < pack_pad)  // tail of the last 128-byte row
     static_cast<uint8_t*>(packed)[((int64_t)g.N * g.H * g.W * g.Cin * FUSE) / 8 + threadIdx.x] = 0;
-  if (m0 >= Mg) return;
+  // CLS: the block's class (ph, pw), its grid Hc x Wc of pixels (ph + stride h', pw + stride w'),
+  // their number Mc; m0 becomes the first of the block's pixels in the class's own numbering
+  int ph = 0, pw = 0, Hc = 0, Wc = 0;
+  int64_t Mc = 0;
+  if constexpr (CLS) {
+    const int st = g.stride;
+    int64_t mt = m0 / BM;
+    bool found = false;
+    for (int c = 0; c < st * st && !found; ++c) {
+      ph = c / st;
+      pw = c - ph * st;
+      Hc = g.H > ph ? (g.H - ph + st - 1) / st : 0;
+      Wc = g.W > pw ? (g.W - pw + st - 1) / st : 0;
+      Mc = (int64_t)g.N * Hc * Wc;
+      const int64_t tiles = (Mc + BM - 1) / BM;
+      if (mt < tiles) found = true;
+      else mt -= tiles;
+    }
+    if (!found) return;
+    m0 = mt * BM;
+  } else {
+    if (m0 >= Mg) return;
+  }
+  // pixel row `q` of the block's numbering -> (image, h, w) of the output pixel
+  auto pixel_of = [&](int64_t q, int& n, int& hq, int& wq) __attribute__((always_inline)) {
+    const int pp = (int)q;
+    if constexpr (CLS) {
+      const int wc = pp % Wc, t = pp / Wc;
+      wq = wc * g.stride + pw;
+      hq = (t % Hc) * g.stride + ph;
+      n = t / Hc;
+    } else {
+      wq = pp % Wq;
+      const int t = pp / Wq;
+      hq = t % Hq;
+      n = t / Hq;
+    }
+  };
+  const int64_t Mrows = CLS ? Mc : Mg;
 
   // rows of the A tile this thread fetches (one float4 = 4 channels per row and pass)
   const int a_kq = tid % KQ, a_row = tid / KQ;
@@ -84,12 +128,9 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 #pragma unroll
   for (int i = 0; i < A_PASSES; ++i) {
     const int64_t p = m0 + a_row + ROWS * i;
-    a_ok[i] = p < Mg;
-    const int pp = a_ok[i] ? (int)p : 0;
-    const int wq = pp % Wq;
-    const int t = pp / Wq;
-    const int hq = t % Hq;
-    a_n[i] = t / Hq;
+    a_ok[i] = p < Mrows;
+    int hq, wq;
+    pixel_of(a_ok[i] ? p : 0, a_n[i], hq, wq);
     if (MODE == 0) {
       a_h[i] = hq * g.stride - g.pad;
       a_w[i] = wq * g.stride - g.pad;
@@ -109,14 +150,34 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 
   const int cchunks = (Cg + BK - 1) / BK;
   const int taps = g.R * g.S;
-  const int iters = taps * cchunks;
+  // CLS: the taps that reach this class (bit t of the mask), walked in ascending order
+  uint64_t tap_mask = ~0ull;
+  int ntaps = taps;
+  if constexpr (CLS) {
+    tap_mask = 0;
+    ntaps = 0;
+    for (int t = 0; t < taps; ++t) {
+      const int r = t / g.S, sx = t - r * g.S;
+      if ((ph + g.pad - r) % g.stride == 0 && (pw + g.pad - sx) % g.stride == 0) {
+        tap_mask |= 1ull << t;
+        ++ntaps;
+      }
+    }
+  }
+  auto next_tap = [&](int t) __attribute__((always_inline)) {  // first tap of the block at or after t
+    if constexpr (CLS) {
+      while (t < taps && !((tap_mask >> t) & 1ull)) ++t;
+    }
+    return t;
+  };
+  const int iters = ntaps * cchunks;
   float4 ra[A_PASSES], rb[B_PASSES];
 
   // Fetch state.  Chunks are fetched in order, so everything that depends on the filter tap
   // (bounds, the division for strided dgrad, the pixel offset) is recomputed only when the tap
   // changes; within a tap a chunk is `offset + channel`.
   int a_off[A_PASSES];  // element offset of channel 0 of this thread's pixel for the tap, -1 = zero
-  int f_tap = 0, f_c0 = 0;
+  int f_tap = next_tap(0), f_c0 = 0;
   auto set_tap = [&](int tap) __attribute__((always_inline)) {
     const int r = tap / g.S, s = tap - r * g.S;
 #pragma unroll
@@ -152,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
       b_thr[j] = nn * g.Cout + 4 * (idx % KQ);
     }
   }
-  set_tap(0);
+  if (f_tap < taps) set_tap(f_tap);
 
   // per-channel constants of the 4 channels this thread stages (fused forward)
   float4 k_mean, k_rstd, k_gamma, k_beta, k_cq;
@@ -202,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
     f_c0 += BK;
     if (f_c0 >= Cg) {
       f_c0 = 0;
-      ++f_tap;
+      f_tap = next_tap(f_tap + 1);
       if (f_tap < taps) set_tap(f_tap);
     }
   };
@@ -281,8 +342,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
   };
   // The loads of chunk i+1 are issued before chunk i is contracted and written to the other
   // LDS buffer afterwards; one barrier per chunk.
-  fetch();
-  stage(0);
+  if (iters > 0) {  // (a class that no tap reaches: its pixels are zeros)
+    fetch();
+    stage(0);
+  }
   __syncthreads();
   for (int it = 0; it < iters; ++it) {
     const int cur = it & 1;
@@ -294,12 +357,17 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const float* __restrict
 
   // epilogue: the lane holds channels n0 + wn0 + 16j + 4lk .. +3 of pixel m0 + wm0 + 16i + li.
   // Channel counts that are not a multiple of 4 take the element-wise path.
-  const bool full = m0 + BM <= Mg && n0 + BN <= Ng;
+  const bool full = !CLS && m0 + BM <= Mg && n0 + BN <= Ng;
   const bool vec4 = (Ng & 3) == 0;
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    const int64_t p = m0 + wm0 + 16 * i + li;
-    const bool p_ok = full || p < Mg;
+    int64_t p = m0 + wm0 + 16 * i + li;
+    const bool p_ok = full || p < Mrows;
+    if constexpr (CLS) {  // the class's numbering -> the pixel's row in the tensor
+      int n, hq, wq;
+      pixel_of(p_ok ? p : 0, n, hq, wq);
+      p = ((int64_t)n * g.H + hq) * g.W + wq;
+    }
     if (vec4) {
       bool ok[NT];
 #pragma unroll
@@ -794,14 +862,30 @@ int launch_igemm(hipStream_t st, const ConvGeom& g, bool bf16, const float* in, 
   const int pack_pad = (int)((raw + 127) / 128 * 128 - raw);
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
-  auto blocks = [&](int bm, int bn) __attribute__((always_inline)) { return ((Mg + bm - 1) / bm) * ((Ng + bn - 1) / bn); };
+  // dgrad of a strided convolution: pixel tiles per class of (h mod stride, w mod stride)
+  constexpr bool CAN_CLS = MODE == 1 && FUSE == 0;
+  const bool cls = CAN_CLS && g.stride > 1;
+  auto mtiles = [&](int bm) __attribute__((always_inline)) {
+    if (!cls) return (Mg + bm - 1) / bm;
+    int64_t t = 0;
+    for (int c = 0; c < g.stride * g.stride; ++c) {
+      const int ph = c / g.stride, pw = c % g.stride;
+      const int64_t hc = g.H > ph ? (g.H - ph + g.stride - 1) / g.stride : 0;
+      const int64_t wc = g.W > pw ? (g.W - pw + g.stride - 1) / g.stride : 0;
+      t += (g.N * hc * wc + bm - 1) / bm;
+    }
+    return t;
+  };
+  auto blocks = [&](int bm, int bn) __attribute__((always_inline)) { return mtiles(bm) * ((Ng + bn - 1) / bn); };
 #define ABL_IGEMM(BM_, BN_, WM_, WN_, BK_)                                                     \
   do {                                                                                         \
-    const int64_t mb8 = ((Mg + BM_ - 1) / BM_ + 7) / 8 * 8;                                   \
+    const int64_t mb8 = (mtiles(BM_) + 7) / 8 * 8;                                            \
     dim3 grid((unsigned)(mb8 * ((Ng + BN_ - 1) / BN_)));                                      \
     constexpr unsigned lds = 2u * (BM_ + BN_) * (BK_ + 4) * sizeof(float);                    \
-    auto kern = bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true, FUSE>                 \
-                     : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false, FUSE>;               \
+    auto kern = cls ? (bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true, FUSE, CAN_CLS> \
+                            : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false, FUSE, CAN_CLS>) \
+                    : (bf16 ? igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, true, FUSE>          \
+                            : igemm_kernel<BM_, BN_, WM_, WN_, BK_, MODE, false, FUSE>);       \
     if (lds > 64 * 1024 &&                                                                     \
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                               \
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)    \

@@ -161,6 +161,10 @@ CONV_CASES = [
     LayerShape(2, 9, 11, 32, 16, 1, 3, 1, 1),          # 1x3 filter
     LayerShape(3, 13, 11, 64, 128, stride=2),          # strided, channel counts of the bf16 GEMM kernels
     LayerShape(2, 10, 10, 128, 64, 5, 5, 1, 2),
+    LayerShape(2, 14, 14, 64, 128, 1, 1, 2, 0),        # strided 1x1 (projection shortcut): three input pixels in four get no tap
+    LayerShape(1, 7, 9, 32, 48, 1, 1, 2, 0),           # ... odd image sizes
+    LayerShape(1, 10, 11, 16, 32, 3, 3, 3, 1),         # stride 3: nine classes of input pixels in the data gradient
+    LayerShape(2, 15, 13, 32, 32, 5, 5, 2, 2),         # 5x5 stride 2
 ]
 
 
