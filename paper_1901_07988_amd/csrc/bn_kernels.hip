@@ -122,6 +122,31 @@ struct PackedWord {
   using type = typename std::conditional<K * VEC == 32, uint32_t, uint16_t>::type;
 };
 
+// What a thread holds of one row's stored activation: VEC K-bit codes in one word, or (K = 32,
+// exact storage) the VEC fp32 values themselves.
+template <int K, int VEC>
+struct Stored {
+  using raw_t = uint32_t;
+  static __device__ inline raw_t load(const void* __restrict__ packed, int64_t e) {
+    return reinterpret_cast<const typename PackedWord<K, VEC>::type*>(packed)[e / VEC];
+  }
+  static __device__ inline float value(const raw_t& w, int v, float step, int32_t fb) {
+    return dequant<K>((w >> (K * v)) & ((1u << K) - 1), step, fb);  // Eq. 10
+  }
+};
+template <int VEC>
+struct Stored<32, VEC> {
+  struct raw_t {
+    float f[VEC];
+  };
+  static __device__ inline raw_t load(const void* __restrict__ packed, int64_t e) {
+    raw_t r;
+    load_vec<VEC>(reinterpret_cast<const float*>(packed) + e, r.f);
+    return r;
+  }
+  static __device__ inline float value(const raw_t& w, int v, float, int32_t) { return w.f[v]; }
+};
+
 struct ThreadPos {
   int tx, ty;
   int c0;       // first channel of this thread
@@ -292,7 +317,6 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
                                                               float* __restrict__ a3,
                                                               void* __restrict__ packed, int pad_bytes,
                                                               float slope) {
-  using word_t = typename PackedWord<K, VEC>::type;
   const ThreadPos p = thread_pos<VEC>(g);
   const bool leaky = slope != 0.0f;
   if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < pad_bytes)  // zero the 128-byte row tail
@@ -308,7 +332,6 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
   }
   load_vec<VEC>(stats + P_CQ * C + p.c0, cq);
   load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
-  word_t* __restrict__ pw = reinterpret_cast<word_t*>(packed);
   const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
   for (int i = 0; i < g.rpt; i += ROWS) {
     float xv[ROWS][VEC];
@@ -324,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
       if (ok[j]) {
         const int64_t r = row0 + (int64_t)(i + j) * g.TY;
         uint32_t word = 0;
-        float out[VEC];
+        float out[VEC], kept[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
           float a2;
@@ -337,11 +360,17 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const float* __res
           } else {
             a2 = xv[j][v];
           }
-          word |= quant_code<K>(a2, cq[v], fb[v]) << (K * v);
+          if constexpr (K == 32) kept[v] = a2;  // exact storage keeps the value itself
+          else word |= quant_code<K>(a2, cq[v], fb[v]) << (K * v);
         }
         const int64_t e = r * C + p.c0;
         if constexpr (MODE == 0) store_vec<VEC, STREAM>(a3 + e, out);
-        pw[e / VEC] = (word_t)word;
+        if constexpr (K == 32) {
+          store_vec<VEC, false>(reinterpret_cast<float*>(packed) + e, kept);
+        } else {
+          using word_t = typename PackedWord<K, VEC>::type;
+          reinterpret_cast<word_t*>(packed)[e / VEC] = (word_t)word;
+        }
       }
   }
 }
@@ -351,23 +380,22 @@ template <int K, int VEC, bool STREAM>
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict__ packed, int64_t M, int C,
                                                           RowGeom g, const float* __restrict__ stats,
                                                           float* __restrict__ a2t, int act, float slope) {
-  using word_t = typename PackedWord<K, VEC>::type;
+  using S = Stored<K, VEC>;
   const ThreadPos p = thread_pos<VEC>(g);
   if (!p.active) return;
   float step[VEC];
   int32_t fb[VEC];
   load_vec<VEC>(stats + P_STEP * C + p.c0, step);
   load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
-  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
   const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
   for (int i = 0; i < g.rpt; i += kUnroll) {
-    uint32_t w[kUnroll];
+    typename S::raw_t w[kUnroll];
     bool ok[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
       const int64_t r = row0 + (int64_t)(i + j) * g.TY;
       ok[j] = (i + j) < g.rpt && r < M;
-      w[j] = pw[((ok[j] ? r : 0) * C + p.c0) / VEC];
+      w[j] = S::load(packed, (ok[j] ? r : 0) * C + p.c0);
     }
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j)
@@ -376,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const void* __restrict
         float out[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-          const float a = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          const float a = S::value(w[j], v, step[v], fb[v]);
           out[v] = (act == 0 || a > 0.0f) ? a : slope * a;  // act: Eq. 3 (slope 0) or its leaky version
         }
         store_vec<VEC, STREAM>(a2t + r * C + p.c0, out);
@@ -391,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
                                                               const float* __restrict__ da3, int64_t M, int C,
                                                               RowGeom g, const float* __restrict__ stats,
                                                               double* __restrict__ partial, float slope) {
-  using word_t = typename PackedWord<K, VEC>::type;
+  using S = Stored<K, VEC>;
   __shared__ double red[2 * VEC][kThreads];  // [value][thread]: conflict-free
   const ThreadPos p = thread_pos<VEC>(g);
   const bool leaky = slope != 0.0f;
@@ -407,11 +435,10 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
     ig[v] = 1.0f / ig[v];
     s1[v] = s2[v] = 0.0;
   }
-  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
   const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
   for (int i = 0; i < g.rpt; i += kUnroll) {
     float gv[kUnroll][VEC];
-    uint32_t w[kUnroll];
+    typename S::raw_t w[kUnroll];
     bool ok[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
@@ -419,14 +446,14 @@ __global__ __launch_bounds__(kThreads) void bwd_reduce_kernel(const void* __rest
       ok[j] = p.active && (i + j) < g.rpt && r < M;
       const int64_t e = (ok[j] ? r : 0) * C + p.c0;
       load_vec<VEC>(da3 + e, gv[j]);
-      w[j] = pw[e / VEC];
+      w[j] = S::load(packed, e);
     }
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j)
       if (ok[j]) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-          const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          const float a2t = S::value(w[j], v, step[v], fb[v]);
           const float da2 = a2t > 0.0f ? gv[j][v] : (leaky ? slope * gv[j][v] : 0.0f);  // Eq. 6
           const float a1t = (a2t - bt[v]) * ig[v];          // inverse of Eq. 2
           s1[v] += (double)da2;
@@ -539,7 +566,7 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
                                                              const float* __restrict__ stats,
                                                              const float* __restrict__ means, float* dx,
                                                              float slope) {
-  using word_t = typename PackedWord<K, VEC>::type;
+  using S = Stored<K, VEC>;
   const ThreadPos p = thread_pos<VEC>(g);
   if (!p.active) return;
   const bool leaky = slope != 0.0f;
@@ -554,11 +581,10 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
   load_vec_i<VEC>(reinterpret_cast<const int32_t*>(stats) + P_FB * C + p.c0, fb);
 #pragma unroll
   for (int v = 0; v < VEC; ++v) ig[v] = 1.0f / gm[v];
-  const word_t* __restrict__ pw = reinterpret_cast<const word_t*>(packed);
   const int64_t row0 = (int64_t)blockIdx.y * g.TY * g.rpt + p.ty;
   for (int i = 0; i < g.rpt; i += kUnroll) {
     float gv[kUnroll][VEC], acc[kUnroll][VEC];
-    uint32_t w[kUnroll];
+    typename S::raw_t w[kUnroll];
     bool ok[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
@@ -567,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
       const int64_t e = (ok[j] ? r : 0) * C + p.c0;
       load_vec<VEC>(da3 + e, gv[j]);
       if constexpr (ACCUM) load_vec<VEC>(dx + e, acc[j]);
-      w[j] = pw[e / VEC];
+      w[j] = S::load(packed, e);
     }
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j)
@@ -576,7 +602,7 @@ __global__ __launch_bounds__(kThreads) void bwd_apply_kernel(const void* __restr
         float out[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-          const float a2t = dequant<K>((w[j] >> (K * v)) & ((1u << K) - 1), step[v], fb[v]);
+          const float a2t = S::value(w[j], v, step[v], fb[v]);
           const float da2 = a2t > 0.0f ? gv[j][v] : (leaky ? slope * gv[j][v] : 0.0f);  // Eq. 6
           const float a1t = (a2t - bt[v]) * ig[v];
           const float da1 = gm[v] * da2;                    // Eq. 7
@@ -731,7 +757,6 @@ __global__ __launch_bounds__(kThreads) void flat_bwd_apply_kernel(const uint8_t*
 // leave every other 16 bytes out (unpack 3.8 -> 5.4 TB/s, normalise-ReLU-pack 5.2 -> 5.9,
 // Eq. 6-8 5.5 -> 5.9).
 int fast_vec(int K, int C, bool wide) {
-  if (K == 32) return 0;  // exact storage runs on the element-wise kernels
   if (K == 4 && wide && C % 8 == 0) return 8;
   return C % 4 == 0 ? 4 : 0;
 }
@@ -810,7 +835,8 @@ static int launch_quant_pack(hipStream_t st, const float* in, int64_t M, int C, 
   } while (0)
   if (K == 4 && vec == 8) ABL_QP(4, 8, ROWS_WIDE);
   else if (K == 4) ABL_QP(4, 4, ROWS);
-  else ABL_QP(8, 4, ROWS);
+  else if (K == 8) ABL_QP(8, 4, ROWS);
+  else ABL_QP(32, 4, ROWS);
 #undef ABL_QP
   return hip_status();
 }
@@ -849,7 +875,8 @@ int launch_unpack(hipStream_t st, const void* packed, int64_t M, int C, int K, c
     unpack_kernel<KK, VV, false><<<grid_of(g), kThreads, 0, st>>>(packed, M, C, g, sp, a2t, ac, slope); \
   } while (0)
   if (K == 4) ABL_UP(4, 4);
-  else ABL_UP(8, 4);
+  else if (K == 8) ABL_UP(8, 4);
+  else ABL_UP(32, 4);
 #undef ABL_UP
   return hip_status();
 }
@@ -871,8 +898,10 @@ int launch_bn_bwd(hipStream_t st, const void* packed, const void* stats, const f
       flat_bwd_reduce_kernel<32><<<grid_of(gr), kThreads, 0, st>>>(pk, da3, M, C, gr, sp, partial, slope);
   } else if (K == 4) {
     bwd_reduce_kernel<4, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
-  } else {
+  } else if (K == 8) {
     bwd_reduce_kernel<8, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
+  } else {
+    bwd_reduce_kernel<32, 4><<<grid_of(gr), kThreads, 0, st>>>(packed, da3, M, C, gr, sp, partial, slope);
   }
   if (hipGetLastError() != hipSuccess) return ABL_ERR_HIP;
   return launch_bn_bwd_finish(st, packed, stats, da3, M, C, K, accum, scratch, gr.gridY, dx, dgamma, dbeta, dwsum,
@@ -927,7 +956,8 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
     else ABL_APPLY1(KK, VV, false);   \
   } while (0)
   if (K == 4) ABL_APPLY(4, 4);
-  else ABL_APPLY(8, 4);
+  else if (K == 8) ABL_APPLY(8, 4);
+  else ABL_APPLY(32, 4);
 #undef ABL_APPLY1
 #undef ABL_APPLY
   return hip_status();
