@@ -452,10 +452,11 @@ __global__ __launch_bounds__(kThreads, 3) void wgrad_kernel(const uint32_t* __re
   const int r = tap / g.S, s = tap - r * g.S;
   const int ci0 = tm * TM, co0 = tn * TN;
   const int64_t Mg = (int64_t)g.N * g.Ho * g.Wo;
-  // the slices differ by at most one 64-pixel chunk
-  const int ch_base = chunks / nsplit, ch_rem = chunks - ch_base * nsplit;
-  const int64_t p_begin = (int64_t)(split_idx * ch_base + (split_idx < ch_rem ? split_idx : ch_rem)) * CH;
-  int64_t p_end = p_begin + (int64_t)(ch_base + (split_idx < ch_rem ? 1 : 0)) * CH;
+  // The slices differ by at most one 64-pixel chunk, and the longer ones are spread evenly over the
+  // slice indices: consecutive slices run on the same XCD (and a compute unit there gets one block
+  // of each of them), so with the longer slices first the first XCD would finish last.
+  const int64_t p_begin = ((int64_t)split_idx * chunks / nsplit) * CH;
+  int64_t p_end = ((int64_t)(split_idx + 1) * chunks / nsplit) * CH;
   if (p_end > Mg) p_end = Mg;
 
   const int a_cg = tid % GA;  // the thread's channel group is the same in every pass
