@@ -143,6 +143,12 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
 bool bf16_gemm_supported(const ConvGeom& g, int mode);
 int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
                      float* out);
+// 3x3 'same' stride-1 convolutions whose whole image fits in LDS as bf16 (up to 208 pixels, e.g.
+// 14x14 with 256 channels): one block per image and 64 output channels.
+// sums (nullable, mode 0): [N][2][Cout] doubles = per-image sum(y), sum(y^2) of the output.
+bool image_bf16_supported(const ConvGeom& g, int mode);
+int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                      const float* skip, float* out, double* sums);
 
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.

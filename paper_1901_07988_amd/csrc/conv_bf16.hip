@@ -18,6 +18,10 @@
 // The MFMA computes the transposed tile (first operand = weights), so a lane ends up with four
 // consecutive channels of one pixel: 16-byte stores and shortcut loads.
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "abl_internal.h"
 
 namespace abl {
@@ -229,6 +233,261 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const float* __rest
   }
 }
 
+
+// ---- 3x3 'same' stride-1 convolutions on small images: the whole image stays in LDS -------------
+// One block = one image x 64 output channels.  The image, rounded to bf16 once, sits in LDS with
+// its zero border for the whole contraction ((H+2)(W+2) positions of Cg channels, 135 KB for
+// 14x14x256: what the 160 KB of LDS per compute unit are for), so every input element is fetched
+// and converted once per block instead of once per filter tap.  The four waves split the
+// CONTRACTION (tap, 32-channel chunk) between them and each keeps the block's whole output tile
+// (up to 13 x 4 MFMA tiles) in registers: an activation fragment is then read from LDS once per
+// block and k-step, the waves share no weights (each streams its own k-steps' fragments straight
+// from the L2 into registers, converted on arrival) and the main loop has no barrier.  The four
+// partial tiles are added through LDS at the end in a fixed wave order; the wave that owns an
+// output-channel tile adds the shortcut, stores, and takes the per-channel sums of the output for
+// the next layer's Eq. 1 statistics.
+constexpr int IMG_NB = 64;       // output channels per block
+
+template <int MODE, int MT>
+__global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __restrict__ in,
+                                                                 const float* __restrict__ wgt,
+                                                                 const float* skip, float* out,
+                                                                 double* __restrict__ sums, ConvGeom g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int H = g.H, W = g.W, HW = H * W, PW = W + 2;
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels: a power of two, 32 .. 1024
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;   // output channels: a multiple of 64
+  const int pitch = 2 * Cg + 16;               // bytes per patch position: 16-byte fragments of 16
+                                               // consecutive positions fall into different banks
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD and its L2: the blocks of one image (same input) run there
+  const int nblk = Ng / IMG_NB;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int img = (slot / nblk) * 8 + xcd;
+  const int n0 = (slot % nblk) * IMG_NB;
+  if (img >= g.N) return;
+
+  // ---- the image -> LDS (bf16), border positions zeroed
+  {
+    const int c4sh = __builtin_ctz((unsigned)Cg) - 2;   // log2 of float4 per pixel
+    const int total = HW << c4sh;
+    const uint32_t wmagic = 65536u / (unsigned)W + 1u;  // pix / W for pix * W < 65536
+    const floatx4* src = reinterpret_cast<const floatx4*>(in + (size_t)img * HW * Cg);
+    // No branch anywhere below (a guarded load or store makes the compiler wait for everything in
+    // flight): a lane past the end repeats the last item, which rewrites the same value.
+    constexpr int U = 13;   // loads in flight per lane: four round trips for 14x14x256
+    for (int f0 = 0; f0 < total; f0 += kThreads * U) {
+      floatx4 v[U];
+      int fi[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int f = f0 + tid + kThreads * u;
+        fi[u] = f < total ? f : total - 1;
+        v[u] = src[fi[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int pix = fi[u] >> c4sh, c4 = fi[u] - (pix << c4sh);
+        const int h = (int)(((unsigned)pix * wmagic) >> 16), w = pix - h * W;
+        uint2 o;
+        o.x = pack_bf16(v[u][0], v[u][1]);
+        o.y = pack_bf16(v[u][2], v[u][3]);
+        *reinterpret_cast<uint2*>(smem + ((h + 1) * PW + w + 1) * pitch + c4 * 8) = o;
+      }
+    }
+    const int per = pitch >> 4;                         // 16-byte pieces per position
+    const int border = 2 * PW + 2 * H;
+    const int nz = border * per;
+    for (int i0 = 0; i0 < nz; i0 += kThreads) {
+      const int it = i0 + tid < nz ? i0 + tid : nz - 1;
+      const int bp = it / per, piece = it - bp * per;
+      int pos;
+      if (bp < PW) pos = bp;
+      else if (bp < 2 * PW) pos = (H + 1) * PW + (bp - PW);
+      else pos = (((bp - 2 * PW) >> 1) + 1) * PW + (((bp - 2 * PW) & 1) ? PW - 1 : 0);
+      *reinterpret_cast<uint4*>(smem + pos * pitch + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+
+  // ---- fragment addresses.  acc[jj] is the output-channel tile (wave + jj) % 4, so that a wave's
+  // own tile (the one it finishes) is acc[0] whatever the wave.
+  int a_base[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int m = 16 * i + li;
+    m = m < HW ? m : HW - 1;   // rows past the image: any valid address, never stored
+    const int h = m / W, w = m - h * W;
+    a_base[i] = (h * PW + w) * pitch + lk * 16;
+    asm volatile("" : "+v"(a_base[i]));   // kept in its register, not recomputed in the loop
+  }
+  const int cch_sh = __builtin_ctz((unsigned)Cg) - 5;   // log2 of 32-channel chunks
+  const int T = 9 << cch_sh;
+  const int ks_begin = wave * T / 4, ks_end = (wave + 1) * T / 4;
+
+  // raw weights of one k-step: the lane's 8 contraction channels of its column in 4 tiles.
+  // Uniform part of the address in scalar registers, the lane's part a 32-bit offset.
+  floatx4 raw[4][2];
+  uint32_t w_lane[8];   // forward: byte offsets of the 8 rows; gradient: [0] only
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    w_lane[e] = 4u * (MODE == 0 ? (uint32_t)((8 * lk + e) * g.Cout + li) : (uint32_t)(li * g.Cout + 8 * lk));
+  auto load_w_tile = [&](int ks, int jj) __attribute__((always_inline)) {
+    const int tap = ks >> cch_sh, c0 = (ks - (tap << cch_sh)) * BK;
+    const int nt = n0 + 16 * ((wave + jj) & 3);
+    if (MODE == 0) {
+      // W[tap][c][n]: rows c0 + 8 lk + e of column n
+      const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)(tap * g.Cin + c0) * g.Cout + nt));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // (opaque to the optimizer: the 32-bit offset stays a 32-bit register operand of the load
+        // beside the scalar base instead of being widened to a 64-bit address outside the loop)
+        asm volatile("" : "+v"(w_lane[e]));
+        raw[jj][e >> 2][e & 3] = *reinterpret_cast<const float*>(wb + w_lane[e]);
+      }
+    } else {
+      // gradient to the input: tap (r', s') of the patch pairs with W[2 - r'][2 - s'][n][c]
+      const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)((8 - tap) * g.Cin + nt) * g.Cout + c0));
+      asm volatile("" : "+v"(w_lane[0]));
+      raw[jj][0] = *reinterpret_cast<const floatx4*>(wb + w_lane[0]);
+      raw[jj][1] = *reinterpret_cast<const floatx4*>(wb + w_lane[0] + 16);
+    }
+  };
+  auto a_offset = [&](int ks) __attribute__((always_inline)) {
+    const int tap = ks >> cch_sh, cc = ks - (tap << cch_sh);
+    const int r = tap / 3, s = tap - 3 * r;
+    return (r * PW + s) * pitch + cc * (BK * 2);
+  };
+
+  floatx4 acc[4][MT];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[jj][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // Per k-step: convert the weights that arrived during the previous one, read the activation
+  // fragments and issue the 4 x MT MFMAs, with the requests for the next k-step's weights behind
+  // the first four tiles.  PF fragments of the next k-step are requested behind the last
+  // MFMAs of this one, the rest at the top of their k-step behind them in the LDS queue: the
+  // first MFMAs of a k-step do not wait for LDS.
+  constexpr int PF = 2;
+  bf16x8 apf[PF];
+  if (ks_begin < ks_end) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) load_w_tile(ks_begin, jj);
+  }
+  __syncthreads();
+  if (ks_begin < ks_end) {
+    const int off = a_offset(ks_begin);
+#pragma unroll
+    for (int i = 0; i < PF; ++i) apf[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + off);
+  }
+  for (int ks = ks_begin; ks < ks_end; ++ks) {
+    bf16x8 wf[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const uint4 q = make_uint4(pack_bf16(raw[jj][0][0], raw[jj][0][1]), pack_bf16(raw[jj][0][2], raw[jj][0][3]),
+                                 pack_bf16(raw[jj][1][0], raw[jj][1][1]), pack_bf16(raw[jj][1][2], raw[jj][1][3]));
+      wf[jj] = __builtin_bit_cast(bf16x8, q);
+    }
+    const int kn = ks + 1 < ks_end ? ks + 1 : ks;   // the last k-step asks for its own operands again: no branch
+    const int off = a_offset(ks), offn = a_offset(kn);
+    bf16x8 a[MT];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) a[i] = apf[i];
+#pragma unroll
+    for (int i = PF; i < MT; ++i) a[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + off);
+    __builtin_amdgcn_sched_barrier(0);
+    // the order below is the schedule
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+        // written out so that the accumulator stays in one place (result register = addend
+        // register): left to the register allocator, some tiles get a result register of their
+        // own and are copied back every k-step.  The matrix core's results are not read before
+        // the wait states after the loop.
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wf[jj]), "v"(a[i]));
+      if (i < 4) load_w_tile(kn, i);
+      if (i >= MT - PF) apf[i - (MT - PF)] = *reinterpret_cast<const bf16x8*>(smem + a_base[i - (MT - PF)] + offn);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // the last MFMAs' results are read below by instructions the compiler does not know to depend
+  // on a matrix-core result: more wait states than the longest such hazard (18)
+  asm volatile("s_nop 15\n\ts_nop 15");
+  // ---- the four partial tiles -> one: wave w sends acc[jj], jj = 1..3, to the owner (w + jj) % 4,
+  // which adds what it receives in the order jj = 1, 2, 3 of the senders
+  __syncthreads();   // every wave has finished reading the image
+#pragma unroll
+  for (int jj = 1; jj < 4; ++jj) {
+    const int owner = (wave + jj) & 3;
+    unsigned char* dst = smem + (size_t)((owner * 3 + (jj - 1)) * MT) * 1024 + lane * 16;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) *reinterpret_cast<floatx4*>(dst + i * 1024) = acc[jj][i];
+  }
+  __syncthreads();
+  const int nch = n0 + 16 * wave + 4 * lk;
+  floatx4 v[MT];
+  size_t o[MT];   // element offset of the lane's four channels; rows past the image: the last pixel's
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    v[i] = acc[0][i];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const floatx4 t = *reinterpret_cast<const floatx4*>(smem + (size_t)((wave * 3 + q) * MT + i) * 1024 + lane * 16);
+      v[i][0] += t[0]; v[i][1] += t[1]; v[i][2] += t[2]; v[i][3] += t[3];
+    }
+    const int m = 16 * i + li;
+    o[i] = ((size_t)img * HW + (m < HW ? m : HW - 1)) * Ng + nch;
+  }
+  if (MODE == 0 && skip != nullptr) {
+    // all the shortcut loads together, none of them guarded
+    floatx4 sv[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) sv[i] = *reinterpret_cast<const floatx4*>(skip + o[i]);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      v[i][0] += sv[i][0]; v[i][1] += sv[i][1]; v[i][2] += sv[i][2]; v[i][3] += sv[i][3];
+    }
+  }
+  double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    if (16 * i + li < HW) {
+      *reinterpret_cast<floatx4*>(out + o[i]) = v[i];
+      if (MODE == 0 && sums != nullptr) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          s1[r] += (double)v[i][r];
+          s2[r] += (double)v[i][r] * (double)v[i][r];
+        }
+      }
+    }
+  }
+  if (MODE == 0 && sums != nullptr) {
+    // row `img` of [N][2][Ng]: sum(y), sum(y^2) over the image, added over the 16 pixel lanes
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) {
+        s1[r] += __shfl_xor(s1[r], d, 64);
+        s2[r] += __shfl_xor(s2[r], d, 64);
+      }
+    }
+    if (li == 0) {
+      double* row = sums + (size_t)img * 2 * Ng;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        row[nch + r] = s1[r];
+        row[Ng + nch + r] = s2[r];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 bool bf16_gemm_supported(const ConvGeom& g, int mode) {
@@ -255,6 +514,62 @@ int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* i
     if (wide) gemm_bf16_kernel<1, 128><<<grid, kThreads, 0, st>>>(in, w, nullptr, out, g);
     else gemm_bf16_kernel<1, 64><<<grid, kThreads, 0, st>>>(in, w, nullptr, out, g);
   }
+  return hip_status();
+}
+
+namespace {
+int image_mt(const ConvGeom& g) {
+  const int tiles = (g.H * g.W + 15) / 16;
+  return tiles <= 4 ? 4 : tiles <= 8 ? 8 : tiles <= 13 ? 13 : 0;
+}
+size_t image_lds_bytes(const ConvGeom& g, int mode) {
+  const int Cg = mode == 0 ? g.Cin : g.Cout;
+  const size_t patch = (size_t)(g.H + 2) * (g.W + 2) * (2 * Cg + 16);
+  const size_t red = (size_t)12 * image_mt(g) * 1024;
+  return patch > red ? patch : red;
+}
+}  // namespace
+
+bool image_bf16_supported(const ConvGeom& g, int mode) {
+  const int Cg = mode == 0 ? g.Cin : g.Cout, Ng = mode == 0 ? g.Cout : g.Cin;
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (Cg < 32 || Cg > 1024 || (Cg & (Cg - 1)) != 0 || Ng % IMG_NB != 0) return false;
+  if (image_mt(g) == 0 || g.H * g.W * g.W >= 65536) return false;
+  if (image_lds_bytes(g, mode) > (size_t)160 * 1024) return false;
+  const int64_t e_in = (int64_t)g.N * g.H * g.W * g.Cin, e_out = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
+  return e_in < ((int64_t)1 << 31) && e_out < ((int64_t)1 << 31);
+}
+
+int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                      const float* skip, float* out, double* sums) {
+  if (!image_bf16_supported(g, mode)) return ABL_ERR_SHAPE;
+  const int Ng = mode == 0 ? g.Cout : g.Cin;
+  const int mt = image_mt(g);
+  const size_t lds = image_lds_bytes(g, mode);
+  const unsigned grid = (unsigned)((g.N + 7) / 8 * 8 * (Ng / IMG_NB));
+  auto kern = mode == 0 ? (mt == 4 ? image_bf16_kernel<0, 4> : mt == 8 ? image_bf16_kernel<0, 8> : image_bf16_kernel<0, 13>)
+                        : (mt == 4 ? image_bf16_kernel<1, 4> : mt == 8 ? image_bf16_kernel<1, 8> : image_bf16_kernel<1, 13>);
+  // more than the default 64 KB of LDS per block has to be asked for, once per kernel and device
+  // (the full 160 KB, so that the answer does not depend on the first shape seen)
+  {
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+      (void)hipGetLastError();
+      return ABL_ERR_HIP;
+    }
+    const std::pair<int, const void*> key(dev, reinterpret_cast<const void*>(kern));
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.find(key) == done.end()) {
+      if (hipFuncSetAttribute(key.second, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+        (void)hipGetLastError();
+        return ABL_ERR_HIP;
+      }
+      done.insert(key);
+    }
+  }
+  kern<<<grid, kThreads, lds, st>>>(in, w, mode == 0 ? skip : nullptr, out, mode == 0 ? sums : nullptr, g);
   return hip_status();
 }
 

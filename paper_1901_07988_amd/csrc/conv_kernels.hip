@@ -973,6 +973,11 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     return hip_status();
   }
   // bf16 operands: the 32-deep bf16 matrix instruction with bf16 tiles in LDS
+  if (bf16 && image_bf16_supported(g, 0)) {
+    const bool want = sums != nullptr && rows != nullptr && g.N <= kMaxPartialBlocks;
+    if (want) *rows = g.N;
+    return launch_image_bf16(st, g, 0, a3, w, skip, y, want ? sums : nullptr);
+  }
   if (bf16 && bf16_gemm_supported(g, 0)) return launch_bf16_gemm(st, g, 0, a3, w, skip, y);
   if (halo_conv_supported(g)) {
     const int tiles = sums != nullptr && rows != nullptr ? halo_tile_count(g, 0) : 0;
@@ -1012,6 +1017,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
     naive_dgrad_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, st>>>(dy, w, da3, g);
     return hip_status();
   }
+  if (bf16 && image_bf16_supported(g, 1)) return launch_image_bf16(st, g, 1, dy, w, nullptr, da3, nullptr);
   if (bf16 && bf16_gemm_supported(g, 1)) return launch_bf16_gemm(st, g, 1, dy, w, nullptr, da3);
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   if (pointwise_supported(g, 1)) return launch_pointwise_conv(st, g, 1, bf16, dy, w, nullptr, da3);

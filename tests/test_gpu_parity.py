@@ -165,6 +165,10 @@ CONV_CASES = [
     LayerShape(1, 7, 9, 32, 48, 1, 1, 2, 0),           # ... odd image sizes
     LayerShape(1, 10, 11, 16, 32, 3, 3, 3, 1),         # stride 3: nine classes of input pixels in the data gradient
     LayerShape(2, 15, 13, 32, 32, 5, 5, 2, 2),         # 5x5 stride 2
+    LayerShape(9, 14, 14, 64, 128),                    # bf16: whole image in LDS, more images than XCDs
+    LayerShape(2, 14, 14, 256, 256),                   # ... the 135 KB patch of the 14x14 bottlenecks
+    LayerShape(2, 10, 11, 32, 64),                     # ... 7 pixel tiles
+    LayerShape(1, 13, 16, 128, 64),                    # ... 208 pixels: the largest image
 ]
 
 

@@ -47,3 +47,13 @@ def test_config4_block_layer_by_layer(G, oracle, K):
 def test_config3_stages_layer_by_layer(G, oracle, which):
     """Stride-2 transition + 17 stride-1 layers, N=128."""
     teacher_forced(G, oracle, synth.config3()[which], 4)
+
+
+def test_bf16_stack_layer_by_layer(G, oracle):
+    """ABL_MATH_BF16 on three bottlenecks 1024-256-256-1024 @14x14, N=9: the contractions round their
+    operands to bf16 (bar 2e-2), while every layer's statistics - taken from the sums that the
+    convolution above left in its epilogue - and its packed bytes stay exact on the GPU's own
+    tensors."""
+    from paper_1901_07988_amd import binding as B
+    wl = synth.config5(N=9, blocks=3)
+    teacher_forced(G, oracle, wl, 4, flags=B.ABL_MATH_BF16, tol=2e-2)
