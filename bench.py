@@ -462,6 +462,14 @@ def main():
                          "dtype": "bf16 operands, f32 accumulate (contractions); f32 elsewhere"})
             del run2
             torch.cuda.empty_cache()
+        if args.math == "fp32" and args.workload != "config4":
+            # ... and on the timed workload itself
+            ms2, run2 = time_stack(G, B, synth, wl, K, B.ABL_MATH_BF16, args.steps, args.warmup)
+            subs.append({"workload": wl.name + " --math bf16", "K": K, "steps": args.steps, "ms_per_step": ms2,
+                         "value": N * L / (ms2 * 1e-3), "unit": result["unit"],
+                         "dtype": "bf16 operands, f32 accumulate (contractions); f32 elsewhere"})
+            del run2
+            torch.cuda.empty_cache()
         if K == 4 and args.math == "fp32":
             # the same workload with 8-bit codes (twice the stored bytes, same kernels)
             ms2, run2 = time_stack(G, B, synth, wl, 8, flags, args.steps, args.warmup)

@@ -47,6 +47,8 @@ def test_bench_line_has_the_agreed_fields():
     for name in ("bn_stats", "pack", "unpack", "bn_relu_pack", "bn_bwd"):
         assert 0 < big[name]["frac_of_peak"] < 1 and big[name]["gbs"] > 0
     subs = d["sub_results"]
-    assert [x["workload"][:7] for x in subs] == ["config4", "config2", "config4", "config5"] and all(x["value"] > 0 for x in subs)
-    assert subs[3]["K"] == 8 and abs(subs[3]["stored_over_exact"] - 8 / 32) < 0.01
+    assert [x["workload"][:7] for x in subs] == ["config4", "config2", "config4", "config5", "config5"]
+    assert all(x["value"] > 0 for x in subs)
+    assert subs[4]["K"] == 8 and abs(subs[4]["stored_over_exact"] - 8 / 32) < 0.01
     assert subs[2]["workload"].endswith("--math bf16") and subs[2]["ms_per_step"] < subs[0]["ms_per_step"]
+    assert subs[3]["workload"].endswith("--math bf16") and subs[3]["ms_per_step"] < d["ms_per_step"]
