@@ -24,6 +24,7 @@ UNITS = {
     "conv_halo.hip": ["-ffp-contract=off"],
     "conv_pointwise.hip": ["-ffp-contract=off"],
     "conv_bf16.hip": [],
+    "conv_image.hip": ["-ffp-contract=off"],
     "abl_api.hip": [],
     "abl_noalloc.hip": [],
     "probe_kernels.hip": [],

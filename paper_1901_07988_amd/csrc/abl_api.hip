@@ -269,6 +269,14 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     const DwSum dwsum{static_cast<const float*>(wpart), t16, (int64_t)9 * 16 * 16, dW};
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, t16, dx, dgamma, dbeta, &dwsum);
   }
+  // small images (3x3 'same' stride 1): the image-resident kernel, one row of sums per image
+  if (K != 32 && !bf16 && image_f32_supported(g, 1)) {
+    if (int e = launch_image_dgrad_reduce(st, g, K, dy, W, packed, stats, da3, static_cast<double*>(red))) return e;
+    DwSum dwsum;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, g.N, dx, dgamma, dbeta,
+                                dwsum.copies > 0 ? &dwsum : nullptr);
+  }
   const int tiles = K != 32 && !bf16_gemm && halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))
@@ -397,6 +405,11 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t f
     *rows = r;
     // contractions of more than 256 channels run without the sums: dA3 is written, no rows
     return r > 0 ? ABL_OK : ABL_ERR_SHAPE;
+  }
+  if (!(flags & ABL_MATH_BF16) && image_f32_supported(g, 1)) {  // small images: one row of sums per image
+    *rows = g.N;
+    return launch_image_dgrad_reduce((hipStream_t)stream, g, K, dy, W, packed, stats, da3,
+                                     static_cast<double*>(scratch));
   }
   const int tiles = halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles <= 0 || tiles > kMaxPartialBlocks) return ABL_ERR_SHAPE;

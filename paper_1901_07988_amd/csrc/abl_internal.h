@@ -150,6 +150,19 @@ bool image_bf16_supported(const ConvGeom& g, int mode);
 int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
                       const float* skip, float* out, double* sums);
 
+// ---- fp32 3x3 'same' stride-1 convolutions with the whole image resident in LDS (conv_image.hip) ----
+// Images of up to 208 pixels (14x14, 7x7 ...), contraction channels a power of two from 16 or a
+// multiple of 128, output channels a multiple of 64, at most kMaxPartialBlocks images: one block per
+// image and 64 output channels.
+// sums (nullable, mode 0): [N][2][Cout] doubles = per-image sum(y), sum(y^2) of the output.
+bool image_f32_supported(const ConvGeom& g, int mode);
+int launch_image_f32(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                     const float* skip, float* out, double* sums);
+// Gradient to the conv input with the Eq. 6-7 sums from the layer's packed codes (K = 4 / 8) in the
+// epilogue: partial = [N][2][Cin] doubles, one row per image.
+int launch_image_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                              const void* packed, const void* stats, float* da3, double* partial);
+
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.
 // floor() limited to +-2^24 so that the integer conversion is defined for any input.

@@ -1,0 +1,384 @@
+// 3x3 'same' stride-1 convolutions on small images (up to 208 pixels: the 14x14 and 7x7 stages of
+// an ImageNet network) in fp32: Eq. 4 (forward, mode 0) and the second half of Eq. 5 (gradient to
+// the conv input, mode 1), the latter optionally with the Eq. 6-7 sums of the BN backward in its
+// epilogue.
+//
+// One block = one image x 64 output channels, and the image stays in LDS: 128 contraction
+// channels at a time ((H+2)(W+2) positions of 128 floats with their zero border, 135 KB for 14x14:
+// what the 160 KB of LDS per compute unit are for), staged once per block instead of once per
+// tile of a pixel grid.  The four waves split the CONTRACTION: of the 9 taps x 8 sixteen-channel
+// chunks of a 128-channel phase each wave takes 18, and each keeps the block's whole output tile
+// (up to 13 x 4 MFMA tiles = 208 accumulator registers) to itself.  So an activation fragment is
+// read from LDS once per block and k-step (one 16-byte read feeds four MFMAs of each of the four
+// channel tiles), no weights are shared (each wave streams its own k-steps' weights from the L2
+// straight into registers) and the main loop has no barrier and next to no vector-ALU work: per
+// k-step 208 MFMAs against 13 LDS reads, 16 loads and some thirty other instructions.  The four
+// partial tiles are added through the same LDS at the end in a fixed wave order; the wave that
+// owns an output-channel tile adds the shortcut, stores, and takes the per-channel sums (of y for
+// the next layer's Eq. 1, or Eq. 6-7 from the layer's codes).
+//
+// The MFMAs are written as inline assembly with the accumulator tied to the result: left to the
+// register allocator, some tiles get a result register of their own and are copied back every
+// k-step.  The compiler does not know these are matrix-core results, so the wait states they need
+// before another kind of instruction reads them are inserted by hand after the loop.
+
+#include <mutex>
+#include <set>
+#include <utility>
+
+#include "abl_internal.h"
+
+namespace abl {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int IMG_NB = 64;    // output channels per block
+constexpr int IMG_PC = 128;   // contraction channels resident at a time
+
+template <int MODE, int MT, int EPI>
+__global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __restrict__ in,
+                                                                const float* __restrict__ wgt, const float* skip,
+                                                                float* out, double* __restrict__ sums,
+                                                                const uint8_t* __restrict__ codes,
+                                                                const float* __restrict__ stats, ConvGeom g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int H = g.H, W = g.W, HW = H * W, PW = W + 2;
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels: 16 .. 128, or a multiple of 128
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;   // output channels: a multiple of 64
+  const int PC = Cg < IMG_PC ? Cg : IMG_PC;    // channels per phase (a power of two)
+  const int pitch = 4 * PC + 16;               // bytes per patch position: the 16-byte fragments of 16
+                                               // consecutive positions fall into different banks
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD and its L2: the blocks of one image (same input) run there
+  const int nblk = Ng / IMG_NB;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int img = (slot / nblk) * 8 + xcd;
+  const int n0 = (slot % nblk) * IMG_NB;
+  if (img >= g.N) return;
+
+  // ---- the zero border, once (the phases rewrite the interior only)
+  {
+    const int per = pitch >> 4;   // 16-byte pieces per position
+    const int nz = (2 * PW + 2 * H) * per;
+    for (int i0 = 0; i0 < nz; i0 += kThreads) {
+      const int it = i0 + tid < nz ? i0 + tid : nz - 1;   // (a lane past the end repeats the last piece)
+      const int bp = it / per, piece = it - bp * per;
+      int pos;
+      if (bp < PW) pos = bp;
+      else if (bp < 2 * PW) pos = (H + 1) * PW + (bp - PW);
+      else pos = (((bp - 2 * PW) >> 1) + 1) * PW + (((bp - 2 * PW) & 1) ? PW - 1 : 0);
+      *reinterpret_cast<uint4*>(smem + pos * pitch + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+
+  // ---- fragment addresses.  acc[jj] is the output-channel tile (wave + jj) % 4, so that a wave's
+  // own tile (the one it finishes) is acc[0] whatever the wave.
+  int a_base[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int m = 16 * i + li;
+    m = m < HW ? m : HW - 1;   // rows past the image: any valid address, never stored
+    const int h = m / W, w = m - h * W;
+    a_base[i] = (h * PW + w) * pitch + lk * 16;
+    asm volatile("" : "+v"(a_base[i]));   // kept in its register, not recomputed in the loop
+  }
+  const int cch_sh = __builtin_ctz((unsigned)PC) - 4;   // log2 of 16-channel chunks per phase
+  const int T = 9 << cch_sh;
+  const int ks_begin = wave * T / 4, ks_end = (wave + 1) * T / 4;
+  auto a_offset = [&](int ks) __attribute__((always_inline)) {
+    const int tap = ks >> cch_sh, cc = ks - (tap << cch_sh);
+    const int r = tap / 3, s = tap - 3 * r;
+    return (r * PW + s) * pitch + cc * 64;
+  };
+  // weights of one k-step: MFMA t of a chunk contracts channels 4 lk + t, so the lane's four
+  // registers are four consecutive channels of its column (forward: four rows of W; gradient: 16
+  // contiguous bytes).  Uniform part of the address in scalar registers, the lane's part a 32-bit
+  // byte offset.
+  uint32_t w_lane[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    w_lane[t] = 4u * (MODE == 0 ? (uint32_t)((4 * lk + t) * g.Cout + li) : (uint32_t)(li * g.Cout + 4 * lk));
+  int ph = 0;
+  auto load_w = [&](floatx4 (&dst)[4], int ks) __attribute__((always_inline)) {
+    const int tap = ks >> cch_sh, c0 = ph * PC + (ks - (tap << cch_sh)) * 16;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int nt = n0 + 16 * ((wave + jj) & 3);
+      if (MODE == 0) {
+        const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)(tap * g.Cin + c0) * g.Cout + nt));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          // (opaque to the optimizer: the 32-bit offset stays a register operand of the load beside
+          // the scalar base instead of being widened to a 64-bit address outside the loop)
+          asm volatile("" : "+v"(w_lane[t]));
+          dst[jj][t] = *reinterpret_cast<const float*>(wb + w_lane[t]);
+        }
+      } else {
+        // gradient to the input: tap (r', s') of the patch pairs with W[2 - r'][2 - s'][n][c]
+        const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)((8 - tap) * g.Cin + nt) * g.Cout + c0));
+        asm volatile("" : "+v"(w_lane[0]));
+        dst[jj] = *reinterpret_cast<const floatx4*>(wb + w_lane[0]);
+      }
+    }
+  };
+
+  floatx4 acc[4][MT];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[jj][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int c4sh = __builtin_ctz((unsigned)PC) - 2;    // log2 of float4 per pixel and phase
+  const int total = HW << c4sh;
+  const uint32_t wmagic = 65536u / (unsigned)W + 1u;   // pix / W for pix * W < 65536
+  const int nph = Cg / PC;
+  for (ph = 0; ph < nph; ++ph) {
+    // ---- this phase's channels of the image -> LDS.  No branch (a guarded load or store makes the
+    // compiler wait for everything in flight): a lane past the end repeats the last item.
+    if (ph > 0) __syncthreads();   // every wave is done with the previous phase's patch
+    {
+      const float* src = in + (size_t)img * HW * Cg + ph * PC;
+      constexpr int U = 13;
+      for (int f0 = 0; f0 < total; f0 += kThreads * U) {
+        floatx4 v[U];
+        int fi[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int f = f0 + tid + kThreads * u;
+          fi[u] = f < total ? f : total - 1;
+          const int pix = fi[u] >> c4sh, c4 = fi[u] - (pix << c4sh);
+          v[u] = *reinterpret_cast<const floatx4*>(src + (size_t)pix * Cg + 4 * c4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int pix = fi[u] >> c4sh, c4 = fi[u] - (pix << c4sh);
+          const int h = (int)(((unsigned)pix * wmagic) >> 16), w = pix - h * W;
+          *reinterpret_cast<floatx4*>(smem + ((h + 1) * PW + w + 1) * pitch + c4 * 16) = v[u];
+        }
+      }
+    }
+    floatx4 wnext[4];
+    if (ks_begin < ks_end) load_w(wnext, ks_begin);
+    __syncthreads();
+    // One set of activation fragments, refreshed in place: a tile's fragment of the next k-step
+    // is requested as soon as its MFMAs of this k-step have been issued, a whole k-step ahead.
+    floatx4 a[MT];
+    if (ks_begin < ks_end) {
+      const int off = a_offset(ks_begin);
+#pragma unroll
+      for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const floatx4*>(smem + a_base[i] + off);
+    }
+    for (int ks = ks_begin; ks < ks_end; ++ks) {
+      floatx4 wc[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) wc[jj] = wnext[jj];
+      const int kn = ks + 1 < ks_end ? ks + 1 : ks;   // the last k-step asks for its own operands again: no branch
+      const int offn = a_offset(kn);
+      __builtin_amdgcn_sched_barrier(0);
+      load_w(wnext, kn);
+      __builtin_amdgcn_sched_barrier(0);
+      // the order below is the schedule
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj)
+            asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wc[jj][t]), "v"(a[i][t]));
+        a[i] = *reinterpret_cast<const floatx4*>(smem + a_base[i] + offn);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+  // the last MFMAs' results are read below by instructions the compiler does not know to depend
+  // on a matrix-core result: more wait states than the longest such hazard (18)
+  asm volatile("s_nop 15\n\ts_nop 15");
+  // ---- the four partial tiles -> one: wave w sends acc[jj], jj = 1..3, to the owner (w + jj) % 4,
+  // which adds what it receives in the order jj = 1, 2, 3 of the senders
+  __syncthreads();   // every wave has finished reading the image
+#pragma unroll
+  for (int jj = 1; jj < 4; ++jj) {
+    const int owner = (wave + jj) & 3;
+    unsigned char* dst = smem + (size_t)((owner * 3 + (jj - 1)) * MT) * 1024 + lane * 16;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) *reinterpret_cast<floatx4*>(dst + i * 1024) = acc[jj][i];
+  }
+  __syncthreads();
+  const int nch = n0 + 16 * wave + 4 * lk;
+  floatx4 v[MT];
+  size_t o[MT];   // element offset of the lane's four channels; rows past the image: the last pixel's
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    v[i] = acc[0][i];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const floatx4 t = *reinterpret_cast<const floatx4*>(smem + (size_t)((wave * 3 + q) * MT + i) * 1024 + lane * 16);
+      v[i][0] += t[0]; v[i][1] += t[1]; v[i][2] += t[2]; v[i][3] += t[3];
+    }
+    const int m = 16 * i + li;
+    o[i] = ((size_t)img * HW + (m < HW ? m : HW - 1)) * Ng + nch;
+  }
+  double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+  if (MODE == 0) {
+    if (skip != nullptr) {
+      // all the shortcut loads together, none of them guarded
+      floatx4 sv[MT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) sv[i] = *reinterpret_cast<const floatx4*>(skip + o[i]);
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        v[i][0] += sv[i][0]; v[i][1] += sv[i][1]; v[i][2] += sv[i][2]; v[i][3] += sv[i][3];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if (16 * i + li < HW) {
+        *reinterpret_cast<floatx4*>(out + o[i]) = v[i];
+        if (sums != nullptr) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            s1[r] += (double)v[i][r];
+            s2[r] += (double)v[i][r] * (double)v[i][r];
+          }
+        }
+      }
+    }
+  } else {
+    if constexpr (EPI != 0) {
+      // Eq. 6-7 from the layer's K-bit codes: the codes of the lane's four channels per pixel
+      uint32_t cw[MT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        cw[i] = EPI == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o[i] >> 1))
+                         : *reinterpret_cast<const uint32_t*>(codes + o[i]);
+      const floatx4 st4 = *reinterpret_cast<const floatx4*>(stats + P_STEP * Ng + nch);
+      const floatx4 bt4 = *reinterpret_cast<const floatx4*>(stats + P_BETA * Ng + nch);
+      const floatx4 gm4 = *reinterpret_cast<const floatx4*>(stats + P_GAMMA * Ng + nch);
+      const int4 fb4 = *reinterpret_cast<const int4*>(stats + P_FB * Ng + nch);
+      const int32_t fbv[4] = {fb4.x, fb4.y, fb4.z, fb4.w};
+      float ig[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ig[r] = 1.0f / gm4[r];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        if (16 * i + li < HW) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t code = (cw[i] >> (EPI * r)) & ((1u << EPI) - 1u);
+            const int32_t j = (int32_t)code - (1 << (EPI - 1)) + fbv[r];
+            const float a2t = st4[r] * ((float)j + 0.5f);        // Eq. 10
+            const float da2 = a2t > 0.0f ? v[i][r] : 0.0f;       // Eq. 6
+            const float a1t = (a2t - bt4[r]) * ig[r];            // inverse of Eq. 2
+            s1[r] += (double)da2;
+            s2[r] += (double)a1t * (double)da2;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+      if (16 * i + li < HW) *reinterpret_cast<floatx4*>(out + o[i]) = v[i];
+  }
+  if (sums != nullptr && (MODE == 0 || EPI != 0)) {
+    // row `img` of [N][2][Ng]: the two sums over the image, added over the 16 pixel lanes
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) {
+        s1[r] += __shfl_xor(s1[r], d, 64);
+        s2[r] += __shfl_xor(s2[r], d, 64);
+      }
+    }
+    if (li == 0) {
+      double* row = sums + (size_t)img * 2 * Ng;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        row[nch + r] = s1[r];
+        row[Ng + nch + r] = s2[r];
+      }
+    }
+  }
+}
+
+int image_mt(const ConvGeom& g) {
+  const int tiles = (g.H * g.W + 15) / 16;
+  return tiles <= 4 ? 4 : tiles <= 8 ? 8 : tiles <= 13 ? 13 : 0;
+}
+
+size_t image_lds_bytes(const ConvGeom& g, int mode) {
+  const int Cg = mode == 0 ? g.Cin : g.Cout;
+  const int PC = Cg < IMG_PC ? Cg : IMG_PC;
+  const size_t patch = (size_t)(g.H + 2) * (g.W + 2) * (4 * PC + 16);
+  const size_t red = (size_t)12 * image_mt(g) * 1024;
+  return patch > red ? patch : red;
+}
+
+template <int MODE, int EPI>
+int launch_mt(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip, float* out,
+              double* sums, const uint8_t* codes, const float* stats) {
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const int mt = image_mt(g);
+  const size_t lds = image_lds_bytes(g, MODE);
+  const unsigned grid = (unsigned)((g.N + 7) / 8 * 8 * (Ng / IMG_NB));
+  auto kern = mt == 4 ? image_f32_kernel<MODE, 4, EPI> : mt == 8 ? image_f32_kernel<MODE, 8, EPI>
+                                                                  : image_f32_kernel<MODE, 13, EPI>;
+  // more than the default 64 KB of LDS per block has to be asked for, once per kernel and device
+  // (the full 160 KB, so that the answer does not depend on the first shape seen)
+  {
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+      (void)hipGetLastError();
+      return ABL_ERR_HIP;
+    }
+    const std::pair<int, const void*> key(dev, reinterpret_cast<const void*>(kern));
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.find(key) == done.end()) {
+      if (hipFuncSetAttribute(key.second, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+        (void)hipGetLastError();
+        return ABL_ERR_HIP;
+      }
+      done.insert(key);
+    }
+  }
+  kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, sums, codes, stats, g);
+  return hip_status();
+}
+
+}  // namespace
+
+bool image_f32_supported(const ConvGeom& g, int mode) {
+  const int Cg = mode == 0 ? g.Cin : g.Cout, Ng = mode == 0 ? g.Cout : g.Cin;
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (Cg < 16 || (Cg < IMG_PC ? (Cg & (Cg - 1)) != 0 : Cg % IMG_PC != 0) || Ng % IMG_NB != 0) return false;
+  if (image_mt(g) == 0 || g.N > kMaxPartialBlocks) return false;
+  // one block per compute unit and round is what the kernel is built for: with fewer blocks than
+  // most of a 256-unit round the tiled kernels are faster (measured: 64 images x 128 channels, 128
+  // blocks, 64 us against 44)
+  if ((int64_t)g.N * (Ng / IMG_NB) < 224) return false;
+  if (image_lds_bytes(g, mode) > (size_t)160 * 1024) return false;
+  const int64_t e_in = (int64_t)g.N * g.H * g.W * g.Cin, e_out = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
+  return e_in < ((int64_t)1 << 31) && e_out < ((int64_t)1 << 31);
+}
+
+int launch_image_f32(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                     const float* skip, float* out, double* sums) {
+  if (!image_f32_supported(g, mode)) return ABL_ERR_SHAPE;
+  if (mode == 0) return launch_mt<0, 0>(st, g, in, w, skip, out, sums, nullptr, nullptr);
+  return launch_mt<1, 0>(st, g, in, w, nullptr, out, nullptr, nullptr, nullptr);
+}
+
+int launch_image_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                              const void* packed, const void* stats, float* da3, double* partial) {
+  if (!image_f32_supported(g, 1) || (K != 4 && K != 8)) return ABL_ERR_SHAPE;
+  const uint8_t* codes = static_cast<const uint8_t*>(packed);
+  const float* sp = static_cast<const float*>(stats);
+  if (K == 4) return launch_mt<1, 4>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+  return launch_mt<1, 8>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+}
+
+}  // namespace abl

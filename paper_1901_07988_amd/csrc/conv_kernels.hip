@@ -979,6 +979,12 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     return launch_image_bf16(st, g, 0, a3, w, skip, y, want ? sums : nullptr);
   }
   if (bf16 && bf16_gemm_supported(g, 0)) return launch_bf16_gemm(st, g, 0, a3, w, skip, y);
+  // small images: the whole image resident in LDS, one row of sums per image
+  if (!bf16 && image_f32_supported(g, 0)) {
+    const bool want = sums != nullptr && rows != nullptr;
+    if (want) *rows = g.N;
+    return launch_image_f32(st, g, 0, a3, w, skip, y, want ? sums : nullptr);
+  }
   if (halo_conv_supported(g)) {
     const int tiles = sums != nullptr && rows != nullptr ? halo_tile_count(g, 0) : 0;
     const bool want = tiles > 0 && tiles <= kMaxPartialBlocks;
@@ -1019,6 +1025,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
   }
   if (bf16 && image_bf16_supported(g, 1)) return launch_image_bf16(st, g, 1, dy, w, nullptr, da3, nullptr);
   if (bf16 && bf16_gemm_supported(g, 1)) return launch_bf16_gemm(st, g, 1, dy, w, nullptr, da3);
+  if (!bf16 && image_f32_supported(g, 1)) return launch_image_f32(st, g, 1, dy, w, nullptr, da3, nullptr);
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   if (pointwise_supported(g, 1)) return launch_pointwise_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   return launch_igemm<1, 0>(st, g, bf16, dy, w, nullptr, da3, nullptr, nullptr);

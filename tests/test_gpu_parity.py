@@ -169,6 +169,9 @@ CONV_CASES = [
     LayerShape(2, 14, 14, 256, 256),                   # ... the 135 KB patch of the 14x14 bottlenecks
     LayerShape(2, 10, 11, 32, 64),                     # ... 7 pixel tiles
     LayerShape(1, 13, 16, 128, 64),                    # ... 208 pixels: the largest image
+    LayerShape(56, 3, 3, 256, 256),                    # fp32: whole image in LDS (grids of 224 blocks and more), two channel phases
+    LayerShape(28, 9, 9, 128, 512),                    # ... one phase, 6 pixel tiles
+    LayerShape(57, 14, 13, 64, 256),                   # ... 12 pixel tiles, ragged last tile, batch not a multiple of 8
 ]
 
 
@@ -262,6 +265,7 @@ LAYER_CASES = [
     (LayerShape(2, 14, 14, 64, 256, 1, 1, 1, 0), "relu_normal", "unit"),
     (LayerShape(2, 7, 7, 256, 256), "normal", "random"),
     (LayerShape(3, 7, 5, 6, 10), "normal", "random"),          # fallback path end to end
+    (LayerShape(56, 5, 5, 256, 256), "normal", "random"),      # image-resident kernels: dgrad with the Eq. 6-7 sums
 ]
 
 
