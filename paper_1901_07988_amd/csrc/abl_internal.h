@@ -151,9 +151,9 @@ int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* 
                       const float* skip, float* out, double* sums);
 
 // ---- fp32 3x3 'same' stride-1 convolutions with the whole image resident in LDS (conv_image.hip) ----
-// Images of up to 208 pixels (14x14, 7x7 ...), contraction channels a power of two from 16 or a
-// multiple of 128, output channels a multiple of 64, at most kMaxPartialBlocks images: one block per
-// image and 64 output channels.
+// Images of up to 208 pixels (14x14, 7x7 ...), 16, 32 or a multiple of 64 contraction channels,
+// output channels a multiple of 64, at most kMaxPartialBlocks images and at least 224 blocks: one
+// block per image and 64 output channels.
 // sums (nullable, mode 0): [N][2][Cout] doubles = per-image sum(y), sum(y^2) of the output.
 bool image_f32_supported(const ConvGeom& g, int mode);
 int launch_image_f32(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,

@@ -3,19 +3,22 @@
 // the conv input, mode 1), the latter optionally with the Eq. 6-7 sums of the BN backward in its
 // epilogue.
 //
-// One block = one image x 64 output channels, and the image stays in LDS: 128 contraction
-// channels at a time ((H+2)(W+2) positions of 128 floats with their zero border, 135 KB for 14x14:
-// what the 160 KB of LDS per compute unit are for), staged once per block instead of once per
-// tile of a pixel grid.  The four waves split the CONTRACTION: of the 9 taps x 8 sixteen-channel
-// chunks of a 128-channel phase each wave takes 18, and each keeps the block's whole output tile
-// (up to 13 x 4 MFMA tiles = 208 accumulator registers) to itself.  So an activation fragment is
-// read from LDS once per block and k-step (one 16-byte read feeds four MFMAs of each of the four
-// channel tiles), no weights are shared (each wave streams its own k-steps' weights from the L2
-// straight into registers) and the main loop has no barrier and next to no vector-ALU work: per
-// k-step 208 MFMAs against 13 LDS reads, 16 loads and some thirty other instructions.  The four
-// partial tiles are added through the same LDS at the end in a fixed wave order; the wave that
-// owns an output-channel tile adds the shortcut, stores, and takes the per-channel sums (of y for
-// the next layer's Eq. 1, or Eq. 6-7 from the layer's codes).
+// One block = one image x 64 output channels, and the image stays in LDS, 64 contraction channels
+// (one phase) at a time: (H+2)(W+2) positions of 64 floats with their zero border, 68 KB for 14x14,
+// in two buffers that take turns - the next phase's channels are requested during this phase's
+// MFMAs and written to the other buffer after them, so that only the first phase's loads are
+// waited for.  That is what the 160 KB of LDS per compute unit are for: every input element is
+// fetched once per block instead of once per tile of a pixel grid.  The four waves split the
+// CONTRACTION: of the 9 taps x 4 sixteen-channel chunks of a phase each wave takes 9, and each
+// keeps the block's whole output tile (up to 13 x 4 MFMA tiles = 208 accumulator registers) to
+// itself.  So an activation fragment is read from LDS once per block and k-step (one 16-byte
+// read feeds four MFMAs of each of the four channel tiles), no weights are shared (each wave
+// streams its own k-steps' weights from the L2 straight into registers) and the main loop has no
+// barrier and next to no vector-ALU work: per k-step 208 MFMAs against 13 LDS reads, 16 loads and
+// some thirty other instructions.  The four partial tiles are added through the same LDS at the
+// end in a fixed wave order; the wave that owns an output-channel tile adds the shortcut, stores,
+// and takes the per-channel sums (of y for the next layer's Eq. 1, or Eq. 6-7 from the layer's
+// codes).
 //
 // The MFMAs are written as inline assembly with the accumulator tied to the result: left to the
 // register allocator, some tiles get a result register of their own and are copied back every
@@ -33,7 +36,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int IMG_NB = 64;    // output channels per block
-constexpr int IMG_PC = 128;   // contraction channels resident at a time
+constexpr int IMG_PC = 64;    // contraction channels per phase; two phases' patches are resident
 
 template <int MODE, int MT, int EPI>
 __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __restrict__ in,
@@ -43,11 +46,12 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
                                                                 const float* __restrict__ stats, ConvGeom g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int H = g.H, W = g.W, HW = H * W, PW = W + 2;
-  const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels: 16 .. 128, or a multiple of 128
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels: 16, 32, or a multiple of 64
   const int Ng = MODE == 0 ? g.Cout : g.Cin;   // output channels: a multiple of 64
   const int PC = Cg < IMG_PC ? Cg : IMG_PC;    // channels per phase (a power of two)
   const int pitch = 4 * PC + 16;               // bytes per patch position: the 16-byte fragments of 16
                                                // consecutive positions fall into different banks
+  const int bufsz = (H + 2) * PW * pitch;      // one phase's patch; two of them take turns
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, lk = lane >> 4;
@@ -58,7 +62,7 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
   const int n0 = (slot % nblk) * IMG_NB;
   if (img >= g.N) return;
 
-  // ---- the zero border, once (the phases rewrite the interior only)
+  // ---- the zero border of both patch buffers, once (the phases rewrite the interior only)
   {
     const int per = pitch >> 4;   // 16-byte pieces per position
     const int nz = (2 * PW + 2 * H) * per;
@@ -70,6 +74,7 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
       else if (bp < 2 * PW) pos = (H + 1) * PW + (bp - PW);
       else pos = (((bp - 2 * PW) >> 1) + 1) * PW + (((bp - 2 * PW) & 1) ? PW - 1 : 0);
       *reinterpret_cast<uint4*>(smem + pos * pitch + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+      *reinterpret_cast<uint4*>(smem + bufsz + pos * pitch + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
     }
   }
 
@@ -134,42 +139,53 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
   const int total = HW << c4sh;
   const uint32_t wmagic = 65536u / (unsigned)W + 1u;   // pix / W for pix * W < 65536
   const int nph = Cg / PC;
-  for (ph = 0; ph < nph; ++ph) {
-    // ---- this phase's channels of the image -> LDS.  No branch (a guarded load or store makes the
-    // compiler wait for everything in flight): a lane past the end repeats the last item.
-    if (ph > 0) __syncthreads();   // every wave is done with the previous phase's patch
-    {
-      const float* src = in + (size_t)img * HW * Cg + ph * PC;
-      constexpr int U = 13;
-      for (int f0 = 0; f0 < total; f0 += kThreads * U) {
-        floatx4 v[U];
-        int fi[U];
+  // Staging of one phase, in two halves so that the next phase's loads can be in flight during
+  // this phase's MFMAs: SU float4 per lane (13 for 14x14x64).  No branch anywhere (a guarded load
+  // or store makes the compiler wait for everything in flight): a lane past the end repeats the
+  // last item, which rewrites the same value.
+  constexpr int SU = (16 * MT * (IMG_PC / 4) + kThreads - 1) / kThreads;
+  floatx4 sv[SU];
+  auto stage_load = [&](int p) __attribute__((always_inline)) {
+    const float* src = in + (size_t)img * HW * Cg + p * PC;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int f = f0 + tid + kThreads * u;
-          fi[u] = f < total ? f : total - 1;
-          const int pix = fi[u] >> c4sh, c4 = fi[u] - (pix << c4sh);
-          v[u] = *reinterpret_cast<const floatx4*>(src + (size_t)pix * Cg + 4 * c4);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int pix = fi[u] >> c4sh, c4 = fi[u] - (pix << c4sh);
-          const int h = (int)(((unsigned)pix * wmagic) >> 16), w = pix - h * W;
-          *reinterpret_cast<floatx4*>(smem + ((h + 1) * PW + w + 1) * pitch + c4 * 16) = v[u];
-        }
-      }
+    for (int u = 0; u < SU; ++u) {
+      const int f = tid + kThreads * u;
+      const int fi = f < total ? f : total - 1;
+      const int pix = fi >> c4sh, c4 = fi - (pix << c4sh);
+      sv[u] = *reinterpret_cast<const floatx4*>(src + (size_t)pix * Cg + 4 * c4);
     }
+  };
+  auto stage_store = [&](unsigned char* buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < SU; ++u) {
+      const int f = tid + kThreads * u;
+      const int fi = f < total ? f : total - 1;
+      const int pix = fi >> c4sh, c4 = fi - (pix << c4sh);
+      const int h = (int)(((unsigned)pix * wmagic) >> 16), w = pix - h * W;
+      *reinterpret_cast<floatx4*>(buf + ((h + 1) * PW + w + 1) * pitch + c4 * 16) = sv[u];
+    }
+  };
+  stage_load(0);
+  stage_store(smem);
+  for (ph = 0; ph < nph; ++ph) {
+    const unsigned char* cur = smem + (ph & 1) * bufsz;
+    unsigned char* nxt = smem + ((ph + 1) & 1) * bufsz;
+    const bool more_ph = ph + 1 < nph;
     floatx4 wnext[4];
-    if (ks_begin < ks_end) load_w(wnext, ks_begin);
-    __syncthreads();
+    load_w(wnext, ks_begin);
+    __syncthreads();   // this phase's patch is complete; every wave is done with the other buffer
     // One set of activation fragments, refreshed in place: a tile's fragment of the next k-step
     // is requested as soon as its MFMAs of this k-step have been issued, a whole k-step ahead.
     floatx4 a[MT];
-    if (ks_begin < ks_end) {
+    {
       const int off = a_offset(ks_begin);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const floatx4*>(smem + a_base[i] + off);
+      for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const floatx4*>(cur + a_base[i] + off);
     }
+    // The next phase's channels are requested behind the first k-step's MFMAs and have the rest
+    // of the phase to arrive (the load counter retires in order: requested any earlier, the first
+    // k-step's wait for its weights would wait for them too); they go to the other buffer after
+    // the last k-step.
     for (int ks = ks_begin; ks < ks_end; ++ks) {
       floatx4 wc[4];
 #pragma unroll
@@ -187,10 +203,13 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj)
             asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wc[jj][t]), "v"(a[i][t]));
-        a[i] = *reinterpret_cast<const floatx4*>(smem + a_base[i] + offn);
+        a[i] = *reinterpret_cast<const floatx4*>(cur + a_base[i] + offn);
         __builtin_amdgcn_sched_barrier(0);
       }
+      if (ks == ks_begin && more_ph) stage_load(ph + 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    if (more_ph) stage_store(nxt);
   }
 
   // the last MFMAs' results are read below by instructions the compiler does not know to depend
@@ -311,7 +330,7 @@ int image_mt(const ConvGeom& g) {
 size_t image_lds_bytes(const ConvGeom& g, int mode) {
   const int Cg = mode == 0 ? g.Cin : g.Cout;
   const int PC = Cg < IMG_PC ? Cg : IMG_PC;
-  const size_t patch = (size_t)(g.H + 2) * (g.W + 2) * (4 * PC + 16);
+  const size_t patch = (size_t)2 * (g.H + 2) * (g.W + 2) * (4 * PC + 16);
   const size_t red = (size_t)12 * image_mt(g) * 1024;
   return patch > red ? patch : red;
 }
