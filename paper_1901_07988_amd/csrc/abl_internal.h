@@ -163,6 +163,14 @@ int launch_image_f32(hipStream_t st, const ConvGeom& g, int mode, const float* i
 int launch_image_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
                               const void* packed, const void* stats, float* da3, double* partial);
 
+// Weight gradient of the same layers (14-pixel-wide images) from the K-bit codes (K = 4 / 8): one
+// block per 32 x 64 tile of (input, output) channels and share of the images, each share leaving
+// its own copy of dW in `copies` ([image_wgrad_copies][R][S][Cin][Cout] floats) for the caller to
+// sum.  image_wgrad_copies returns 0 when the shape is not supported.
+int image_wgrad_copies(const ConvGeom& g, int K);
+int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+                       const float* dy, float* copies);
+
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.
 // floor() limited to +-2^24 so that the integer conversion is defined for any input.

@@ -38,6 +38,28 @@ constexpr int kThreads = 256;
 constexpr int IMG_NB = 64;    // output channels per block
 constexpr int IMG_PC = 64;    // contraction channels per phase; two phases' patches are resident
 
+// More than the default 64 KB of LDS per block has to be asked for, once per kernel and device (the
+// full 160 KB, so that the answer does not depend on the first shape seen).
+int allow_full_lds(const void* kern) {
+  static std::mutex mu;
+  static std::set<std::pair<int, const void*>> done;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return ABL_ERR_HIP;
+  }
+  const std::pair<int, const void*> key(dev, kern);
+  std::lock_guard<std::mutex> lock(mu);
+  if (done.find(key) == done.end()) {
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+      (void)hipGetLastError();
+      return ABL_ERR_HIP;
+    }
+    done.insert(key);
+  }
+  return ABL_OK;
+}
+
 template <int MODE, int MT, int EPI>
 __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __restrict__ in,
                                                                 const float* __restrict__ wgt, const float* skip,
@@ -322,6 +344,231 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
   }
 }
 
+
+// ---- weight gradient (first half of Eq. 5) of the same layers from the packed codes ----------------
+// dW[tap][ci][co] = sum over images and pixels of A3~[pixel + tap][ci] * dy[pixel][co], A3~ = ReLU of Eq. 10.
+// One block owns a 32 (ci) x 64 (co) tile of all nine taps and a share of the images; per image it
+// dequantizes the tile's 32 channels of the image once into an LDS patch with its zero border (the nine
+// taps are nine offsets into it) and stages the tile's 64 channels of dy beside it.  The contraction
+// index of the MFMAs is the pixel (four per MFMA), the wave owns one 16-channel tile of ci and two of co for all 9
+// taps (18 accumulator tiles), and per 4-pixel step it reads 2 fragments of dy and 9 of the patch
+// - all at one address plus a constant (the image width is a template parameter) - for 18 MFMAs; the
+// fragments of the next step are read while this step's MFMAs run.  The next image's dy and codes are
+// requested at the start of an image's 49 steps and go to LDS after them.  Each share of the images
+// leaves its own copy of dW, summed in a fixed order by the caller's launch.
+constexpr int WG_CI = 32, WG_CO = 64;
+constexpr int WG_AP = 4 * WG_CI + 64;   // bytes per patch position: the four pixel groups of a read hit
+constexpr int WG_DP = 4 * WG_CO + 64;   // ... different quarters of the banks (48 resp. 80 words apart)
+
+template <int K, int IW>
+__global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t* __restrict__ codes,
+                                                                  const float* __restrict__ stats,
+                                                                  const float* __restrict__ dy,
+                                                                  float* __restrict__ dst, ConvGeom g, int splits) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int PW = IW + 2;
+  const int H = g.H, HW = H * IW;             // HW a multiple of 4
+  unsigned char* const AL = smem;                                 // [(H+2) * PW][WG_AP]
+  unsigned char* const DL = smem + (H + 2) * PW * WG_AP;          // [HW][WG_DP]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD and its L2: the blocks that stage the same dy (same co tile and share
+  // of the images, different ci tiles) run there
+  const int n_ci = g.Cin / WG_CI, n_co = g.Cout / WG_CO;
+  int ci_blk, pair;
+  if ((n_co * splits) % 8 == 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    pair = (slot / n_ci) * 8 + xcd;
+    ci_blk = slot % n_ci;
+  } else {
+    pair = blockIdx.x / n_ci;
+    ci_blk = blockIdx.x % n_ci;
+  }
+  const int co_blk = pair % n_co, split = pair / n_co;
+  const int ci0 = ci_blk * WG_CI, co0 = co_blk * WG_CO;
+  const int img_begin = split * g.N / splits, img_end = (split + 1) * g.N / splits;
+
+  // ---- zero border of the patch, once
+  {
+    constexpr int per = WG_AP / 16;
+    const int nz = (2 * PW + 2 * H) * per;
+    for (int i0 = 0; i0 < nz; i0 += kThreads) {
+      const int it = i0 + tid < nz ? i0 + tid : nz - 1;
+      const int bp = it / per, piece = it - bp * per;
+      int pos;
+      if (bp < PW) pos = bp;
+      else if (bp < 2 * PW) pos = (H + 1) * PW + (bp - PW);
+      else pos = (((bp - 2 * PW) >> 1) + 1) * PW + (((bp - 2 * PW) & 1) ? PW - 1 : 0);
+      *reinterpret_cast<uint4*>(AL + pos * WG_AP + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+
+  // ---- staging roles.  Codes: the thread dequantizes 8 channels (one 32- or 64-bit word) of pixels
+  // tid/4 + 64 q.  Eq. 10 as one multiply per element: step * ((code - 2^(K-1) + fb) + 0.5) =
+  // step * (code + offh), offh = fb - 2^(K-1) + 0.5 (exact in fp32 while |fb| < 2^22).
+  const int cg = tid & 3, cpix = tid >> 2;
+  constexpr int CQ = 4;                          // pixel rounds: 4 x 64 >= 196
+  float stp[8], offh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int c = ci0 + 8 * cg + e;
+    stp[e] = stats[P_STEP * g.Cin + c];
+    offh[e] = (float)(reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] - (1 << (K - 1))) + 0.5f;
+  }
+  constexpr int DU = 13;                         // float4 of dy per thread: 13 x 256 >= 196 x 16
+  floatx4 dyv[DU];
+  uint32_t cw[CQ][K / 4];
+  const int ndy = HW * (WG_CO / 4);
+  auto stage_load = [&](int img) __attribute__((always_inline)) {
+    const float* src = dy + ((size_t)img * HW) * g.Cout + co0;
+#pragma unroll
+    for (int u = 0; u < DU; ++u) {
+      const int f = tid + kThreads * u;
+      const int fi = f < ndy ? f : ndy - 1;   // (a lane past the end repeats the last item)
+      dyv[u] = *reinterpret_cast<const floatx4*>(src + (size_t)(fi >> 4) * g.Cout + 4 * (fi & 15));
+    }
+    const uint8_t* cs = codes + (((size_t)img * HW) * g.Cin + ci0 + 8 * cg) * K / 8;
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      const int px = cpix + 64 * q;
+      const int pc = px < HW ? px : HW - 1;
+      const uint8_t* a = cs + (size_t)pc * g.Cin * K / 8;
+      if (K == 4) cw[q][0] = *reinterpret_cast<const uint32_t*>(a);
+      else {
+        const uint2 t = *reinterpret_cast<const uint2*>(a);
+        cw[q][0] = t.x;
+        cw[q][K / 4 - 1] = t.y;
+      }
+    }
+  };
+  auto stage_store = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < DU; ++u) {
+      const int f = tid + kThreads * u;
+      const int fi = f < ndy ? f : ndy - 1;
+      *reinterpret_cast<floatx4*>(DL + (fi >> 4) * WG_DP + (fi & 15) * 16) = dyv[u];
+    }
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      const int px = cpix + 64 * q;
+      const int pc = px < HW ? px : HW - 1;
+      const int h = pc / IW, w = pc - h * IW;
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t word = cw[q][(e * K) / 32];
+        const uint32_t code = (word >> ((e * K) % 32)) & ((1u << K) - 1u);
+        v[e] = fmaxf(stp[e] * ((float)code + offh[e]), 0.0f);   // Eq. 10, then the ReLU
+      }
+      unsigned char* d = AL + ((h + 1) * PW + w + 1) * WG_AP + cg * 32;
+      *reinterpret_cast<floatx4*>(d) = floatx4{v[0], v[1], v[2], v[3]};
+      *reinterpret_cast<floatx4*>(d + 16) = floatx4{v[4], v[5], v[6], v[7]};
+    }
+  };
+
+  // the wave's tiles: ci tile wc, co tiles 2 wo and 2 wo + 1, all nine taps - 18 MFMAs per step
+  // from 9 + 2 fragments
+  const int wc = wave & 1, wo = wave >> 1;
+  floatx4 acc[9][2];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int o = 0; o < 2; ++o) acc[t][o] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // fragments of one 4-pixel step: the lane's pixel is 4 j + lk
+  struct Frag {
+    float d[2];   // dy[pixel][co0 + 16 (2 wo + o) + li]
+    float a[9];   // patch[pixel + tap][ci0 + 16 wc + li]
+  };
+  auto read_a = [&](Frag& f, int t, int abase) __attribute__((always_inline)) {
+    f.a[t] = *reinterpret_cast<const float*>(AL + abase + ((t / 3) * PW + (t % 3)) * WG_AP);
+  };
+  auto read_d = [&](Frag& f, int o, int dbase) __attribute__((always_inline)) {
+    f.d[o] = *reinterpret_cast<const float*>(DL + dbase + o * 64);
+  };
+  // One step: the 18 MFMAs on `cur` with the 11 reads of the next step's fragments spread between
+  // them, one behind every pair of MFMAs.  Measured on 64 x 14 x 14 x 256 -> 256: all reads in a burst
+  // between two steps 143 us, spread like this 136 us, the same reads as six two-address
+  // instructions behind the first six pairs 141 us, no reads at all 120 us - every vector-memory or
+  // vector-ALU instruction between two MFMAs costs the matrix pipe some 9 cycles, so what counts is
+  // their number and an even spread.  The order below is the schedule.
+  auto step = [&](const Frag& cur, Frag& nxt, int abase, int dbase) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+#pragma unroll
+      for (int o = 0; o < 2; ++o)
+        asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[t][o]) : "v"(cur.d[o]), "v"(cur.a[t]));
+      read_a(nxt, t, abase);
+      if (t < 2) read_d(nxt, t, dbase);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto mma = [&](const Frag& f) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int o = 0; o < 2; ++o)
+        asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[t][o]) : "v"(f.d[o]), "v"(f.a[t]));
+  };
+
+  if (img_begin < img_end) stage_load(img_begin);
+  for (int img = img_begin; img < img_end; ++img) {
+    __syncthreads();   // every wave is done with the previous image's patch and dy
+    stage_store();
+    __syncthreads();
+    if (img + 1 < img_end) stage_load(img + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // lane's pixel of step 0: lk (row 0, column lk); steps advance it by four
+    int w = lk;
+    int abase = lk * WG_AP + (16 * wc + li) * 4;
+    int dbase = lk * WG_DP + (32 * wo + li) * 4;
+    auto advance = [&]() __attribute__((always_inline)) {
+      w += 4;
+      const bool wrap = w >= IW;
+      w = wrap ? w - IW : w;
+      abase += (wrap ? 4 + (PW - IW) : 4) * WG_AP;
+      dbase += 4 * WG_DP;
+    };
+    Frag f0, f1;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) read_a(f0, t, abase);
+#pragma unroll
+    for (int o = 0; o < 2; ++o) read_d(f0, o, dbase);
+    const int steps = HW / 4;
+    for (int j = 0; j + 1 < steps; j += 2) {
+      advance();
+      __builtin_amdgcn_sched_barrier(0);
+      step(f0, f1, abase, dbase);
+      advance();
+      // (the last pair of an even count asks for one step past the image's pixels: address 0 - never used)
+      const bool more = j + 2 < steps;
+      const int ab = more ? abase : 0, db = more ? dbase : 0;
+      __builtin_amdgcn_sched_barrier(0);
+      step(f1, f0, ab, db);
+    }
+    if (steps & 1) mma(f0);
+  }
+  // the MFMAs' results are read below by instructions the compiler does not know to depend on a
+  // matrix-core result: more wait states than the longest such hazard
+  asm volatile("s_nop 15\n\ts_nop 15");
+  float* out = dst + (size_t)split * 9 * g.Cin * g.Cout;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int o = 0; o < 2; ++o)
+      *reinterpret_cast<floatx4*>(out + ((size_t)(t * g.Cin + ci0 + 16 * wc + li)) * g.Cout + co0 + 16 * (2 * wo + o) +
+                                  4 * lk) = acc[t][o];
+}
+
+int image_wgrad_splits(const ConvGeom& g) {
+  const int tiles = (g.Cin / WG_CI) * (g.Cout / WG_CO);
+  int s = 256 / tiles;
+  if (s > g.N) s = g.N;
+  if (s > 16) s = 16;
+  return s < 1 ? 1 : s;
+}
+
 int image_mt(const ConvGeom& g) {
   const int tiles = (g.H * g.W + 15) / 16;
   return tiles <= 4 ? 4 : tiles <= 8 ? 8 : tiles <= 13 ? 13 : 0;
@@ -344,26 +591,7 @@ int launch_mt(hipStream_t st, const ConvGeom& g, const float* in, const float* w
   const unsigned grid = (unsigned)((g.N + 7) / 8 * 8 * (Ng / IMG_NB));
   auto kern = mt == 4 ? image_f32_kernel<MODE, 4, EPI> : mt == 8 ? image_f32_kernel<MODE, 8, EPI>
                                                                   : image_f32_kernel<MODE, 13, EPI>;
-  // more than the default 64 KB of LDS per block has to be asked for, once per kernel and device
-  // (the full 160 KB, so that the answer does not depend on the first shape seen)
-  {
-    static std::mutex mu;
-    static std::set<std::pair<int, const void*>> done;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) {
-      (void)hipGetLastError();
-      return ABL_ERR_HIP;
-    }
-    const std::pair<int, const void*> key(dev, reinterpret_cast<const void*>(kern));
-    std::lock_guard<std::mutex> lock(mu);
-    if (done.find(key) == done.end()) {
-      if (hipFuncSetAttribute(key.second, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-        (void)hipGetLastError();
-        return ABL_ERR_HIP;
-      }
-      done.insert(key);
-    }
-  }
+  if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
   kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, sums, codes, stats, g);
   return hip_status();
 }
@@ -398,6 +626,29 @@ int launch_image_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const fl
   const float* sp = static_cast<const float*>(stats);
   if (K == 4) return launch_mt<1, 4>(st, g, dy, w, nullptr, da3, partial, codes, sp);
   return launch_mt<1, 8>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+}
+
+int image_wgrad_copies(const ConvGeom& g, int K) {
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1 || (K != 4 && K != 8)) return 0;
+  if (g.W != 14 || g.H < 2 || g.H > 14 || (g.H * g.W) % 4 != 0) return 0;
+  if (g.Cin % WG_CI != 0 || g.Cout % WG_CO != 0) return 0;
+  const int s = image_wgrad_splits(g);
+  if ((int64_t)s * (g.Cin / WG_CI) * (g.Cout / WG_CO) < 224) return 0;   // built for one block per compute unit
+  const int64_t e_in = (int64_t)g.N * g.H * g.W * g.Cin, e_out = (int64_t)g.N * g.Ho * g.Wo * g.Cout;
+  if (e_in >= ((int64_t)1 << 31) || e_out >= ((int64_t)1 << 31)) return 0;
+  return s;
+}
+
+int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+                       const float* dy, float* copies) {
+  const int s = image_wgrad_copies(g, K);
+  if (s == 0) return ABL_ERR_SHAPE;
+  const size_t lds = (size_t)(g.H + 2) * (g.W + 2) * WG_AP + (size_t)g.H * g.W * WG_DP;
+  const unsigned grid = (unsigned)(s * (g.Cin / WG_CI) * (g.Cout / WG_CO));
+  auto kern = K == 4 ? image_wgrad_kernel<4, 14> : image_wgrad_kernel<8, 14>;
+  if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
+  kern<<<grid, kThreads, lds, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
+  return hip_status();
 }
 
 }  // namespace abl

@@ -960,7 +960,8 @@ size_t wgrad_partial_bytes(const abl_shape& s) {
   }
   const WgradPlan p = wgrad_plan(g);
   const size_t n = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
-  return ((size_t)p.split * n + 255) / 256 * 256;
+  const int img = image_wgrad_copies(g, 4);   // the image-resident kernel's copies (same count for K = 8)
+  return ((size_t)(p.split > img ? p.split : img) * n + 255) / 256 * 256;
 }
 
 int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* a3, const float* w,
@@ -1059,6 +1060,18 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
     return hip_status();
   }
   if (K != 32 && use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
+  // 3x3 layers on 14-pixel-wide images: the image-resident kernel, one copy of dW per share of the images
+  if (const int copies = (!bf16 && !relu32) ? image_wgrad_copies(g, K) : 0) {
+    float* dst = copies == 1 ? dw : static_cast<float*>(scratch);
+    if (int e = launch_image_wgrad(st, g, K, packed, sp, dy, dst)) return e;
+    const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
+    if (copies > 1 && defer != nullptr) {
+      *defer = DwSum{dst, copies, n, dw};
+    } else if (copies > 1) {
+      wgrad_reduce_kernel<<<(unsigned)((n + 63) / 64), kThreads, 0, st>>>(dst, copies, n, dw);
+    }
+    return hip_status();
+  }
   const WgradPlan p = wgrad_plan(g);
   float* dst = p.split == 1 ? dw : static_cast<float*>(scratch);
   if (p.tm == 64 && p.tn == 128) launch_wgrad_tile<64, 128>(st, g, p, K, bf16, packed, sp, dy, dst, r32);

@@ -172,6 +172,9 @@ CONV_CASES = [
     LayerShape(56, 3, 3, 256, 256),                    # fp32: whole image in LDS (grids of 224 blocks and more), two channel phases
     LayerShape(28, 9, 9, 128, 512),                    # ... one phase, 6 pixel tiles
     LayerShape(57, 14, 13, 64, 256),                   # ... 12 pixel tiles, ragged last tile, batch not a multiple of 8
+    LayerShape(8, 14, 14, 256, 256),                   # ... weight gradient with the image in LDS: 49 pixel steps, 8 shares of the images
+    LayerShape(7, 6, 14, 64, 1024),                    # ... 21 steps, one image per share
+    LayerShape(9, 12, 14, 128, 512),                   # ... 42 steps, shares of one and two images
 ]
 
 
