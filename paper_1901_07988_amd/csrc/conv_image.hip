@@ -128,15 +128,19 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
   for (int t = 0; t < 4; ++t)
     w_lane[t] = 4u * (MODE == 0 ? (uint32_t)((4 * lk + t) * g.Cout + li) : (uint32_t)(li * g.Cout + 4 * lk));
   int ph = 0;
-  auto load_w = [&](floatx4 (&dst)[4], int ks) __attribute__((always_inline)) {
+  // part p of 8 (forward: two rows of one channel tile; gradient: parts 0, 2, 4, 6 a whole tile) or,
+  // p < 0, everything
+  auto load_w = [&](floatx4 (&dst)[4], int ks, int p) __attribute__((always_inline)) {
     const int tap = ks >> cch_sh, c0 = ph * PC + (ks - (tap << cch_sh)) * 16;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
+      if (p >= 0 && (p >> 1) != jj) continue;
       const int nt = n0 + 16 * ((wave + jj) & 3);
       if (MODE == 0) {
         const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)(tap * g.Cin + c0) * g.Cout + nt));
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
+          if (p >= 0 && (t >> 1) != (p & 1)) continue;
           // (opaque to the optimizer: the 32-bit offset stays a register operand of the load beside
           // the scalar base instead of being widened to a 64-bit address outside the loop)
           asm volatile("" : "+v"(w_lane[t]));
@@ -144,6 +148,7 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
         }
       } else {
         // gradient to the input: tap (r', s') of the patch pairs with W[2 - r'][2 - s'][n][c]
+        if (p >= 0 && (p & 1) != 0) continue;
         const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)((8 - tap) * g.Cin + nt) * g.Cout + c0));
         asm volatile("" : "+v"(w_lane[0]));
         dst[jj] = *reinterpret_cast<const floatx4*>(wb + w_lane[0]);
@@ -193,8 +198,11 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
     const unsigned char* cur = smem + (ph & 1) * bufsz;
     unsigned char* nxt = smem + ((ph + 1) & 1) * bufsz;
     const bool more_ph = ph + 1 < nph;
-    floatx4 wnext[4];
-    load_w(wnext, ks_begin);
+    // two sets of weight registers take turns by k-step; the next k-step's weights are requested in
+    // eight parts behind the first eight tiles' MFMAs (every vector instruction between two MFMAs
+    // costs the matrix pipe some cycles; a burst of them empties it)
+    floatx4 w0[4], w1[4];
+    load_w(w0, ks_begin, -1);
     __syncthreads();   // this phase's patch is complete; every wave is done with the other buffer
     // One set of activation fragments, refreshed in place: a tile's fragment of the next k-step
     // is requested as soon as its MFMAs of this k-step have been issued, a whole k-step ahead.
@@ -204,18 +212,9 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
 #pragma unroll
       for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const floatx4*>(cur + a_base[i] + off);
     }
-    // The next phase's channels are requested behind the first k-step's MFMAs and have the rest
-    // of the phase to arrive (the load counter retires in order: requested any earlier, the first
-    // k-step's wait for its weights would wait for them too); they go to the other buffer after
-    // the last k-step.
-    for (int ks = ks_begin; ks < ks_end; ++ks) {
-      floatx4 wc[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) wc[jj] = wnext[jj];
+    auto kstep = [&](const floatx4 (&wc)[4], floatx4 (&wn)[4], int ks) __attribute__((always_inline)) {
       const int kn = ks + 1 < ks_end ? ks + 1 : ks;   // the last k-step asks for its own operands again: no branch
       const int offn = a_offset(kn);
-      __builtin_amdgcn_sched_barrier(0);
-      load_w(wnext, kn);
       __builtin_amdgcn_sched_barrier(0);
       // the order below is the schedule
 #pragma unroll
@@ -226,10 +225,22 @@ __global__ __launch_bounds__(kThreads, 1) void image_f32_kernel(const float* __r
           for (int jj = 0; jj < 4; ++jj)
             asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wc[jj][t]), "v"(a[i][t]));
         a[i] = *reinterpret_cast<const floatx4*>(cur + a_base[i] + offn);
+        constexpr int PP = (8 + MT - 1) / MT;   // parts per tile: all eight within the MT tiles
+#pragma unroll
+        for (int q = 0; q < PP; ++q)
+          if (i * PP + q < 8) load_w(wn, kn, i * PP + q);
         __builtin_amdgcn_sched_barrier(0);
       }
+    };
+    // The next phase's channels are requested behind the first k-step's MFMAs and have the rest
+    // of the phase to arrive (the load counter retires in order: requested any earlier, the first
+    // k-step's wait for its weights would wait for them too); they go to the other buffer after
+    // the last k-step.
+    for (int ks = ks_begin; ks < ks_end; ks += 2) {
+      kstep(w0, w1, ks);
       if (ks == ks_begin && more_ph) stage_load(ph + 1);
       __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < ks_end) kstep(w1, w0, ks + 1);
     }
     if (more_ph) stage_store(nxt);
   }
