@@ -366,22 +366,20 @@ __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[jj][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // Per k-step: convert the weights that arrived during the previous one, read the activation
-  // fragments and issue the 4 x MT MFMAs, with the requests for the next k-step's weights behind
-  // the first four tiles.  PF fragments of the next k-step are requested behind the last
-  // MFMAs of this one, the rest at the top of their k-step behind them in the LDS queue: the
-  // first MFMAs of a k-step do not wait for LDS.
-  constexpr int PF = 2;
-  bf16x8 apf[PF];
+  // Per k-step: convert the weights that arrived during the previous one and issue the 4 x MT
+  // MFMAs, with the requests for the next k-step's weights behind the first four tiles.
   if (ks_begin < ks_end) {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) load_w_tile(ks_begin, jj);
   }
   __syncthreads();
+  // One set of activation fragments, refreshed in place: a tile's fragment of the next k-step is
+  // requested as soon as its four MFMAs of this k-step have been issued, a whole k-step ahead.
+  bf16x8 a[MT];
   if (ks_begin < ks_end) {
     const int off = a_offset(ks_begin);
 #pragma unroll
-    for (int i = 0; i < PF; ++i) apf[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + off);
+    for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + off);
   }
   for (int ks = ks_begin; ks < ks_end; ++ks) {
     bf16x8 wf[4];
@@ -392,12 +390,7 @@ __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __
       wf[jj] = __builtin_bit_cast(bf16x8, q);
     }
     const int kn = ks + 1 < ks_end ? ks + 1 : ks;   // the last k-step asks for its own operands again: no branch
-    const int off = a_offset(ks), offn = a_offset(kn);
-    bf16x8 a[MT];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) a[i] = apf[i];
-#pragma unroll
-    for (int i = PF; i < MT; ++i) a[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + off);
+    const int offn = a_offset(kn);
     __builtin_amdgcn_sched_barrier(0);
     // the order below is the schedule
 #pragma unroll
@@ -409,8 +402,9 @@ __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __
         // own and are copied back every k-step.  The matrix core's results are not read before
         // the wait states after the loop.
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wf[jj]), "v"(a[i]));
-      if (i < 4) load_w_tile(kn, i);
-      if (i >= MT - PF) apf[i - (MT - PF)] = *reinterpret_cast<const bf16x8*>(smem + a_base[i - (MT - PF)] + offn);
+      a[i] = *reinterpret_cast<const bf16x8*>(smem + a_base[i] + offn);
+      constexpr int WT = MT < 4 ? MT : 4;   // the next k-step's weights behind the first four tiles
+      if (i < WT) load_w_tile(kn, i);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
