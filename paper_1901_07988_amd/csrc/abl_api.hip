@@ -196,7 +196,9 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
   // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
   // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
   // overwrite input pixels that a neighbouring block has not staged yet.)
-  if (K != 32 && !naive && !bf16_gemm && halo_fused_supported(g) &&
+  // (Not for the small images of the image-resident kernel either: the pack pass plus that kernel is
+  // faster than the fused one - 14x14 256->256: 7 + 120 us against 146.)
+  if (K != 32 && !naive && !bf16_gemm && halo_fused_supported(g) && !(!bf16 && image_f32_supported(g, 0)) &&
       static_cast<const void*>(x) != static_cast<const void*>(y)) {
     const int tiles = halo_tile_count(g, 0);
     const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
