@@ -160,7 +160,7 @@ def kernel_breakdown(G, B, s, K, reps, flags=0, in_place=False):
             bwd_fused = False
     conv_bytes = 4 * E + 4 * Eo + wbytes
     S = sets
-    fwd_fused_step = fwd_fused and not in_place
+    fwd_fused_step = fwd_fused and not in_place and B.abl_forward_is_fused(t, K, flags)
     # name: (call on operand set i, algorithmic bytes, flops, launches, part of the layer step)
     stages = {
         "bn_stats": (lambda i: B.abl_bn_stats(S[i]["x"], M, C, gamma, beta, K, scratch, stats), 4 * E, 0, 2, not fused),

@@ -90,6 +90,12 @@ size_t abl_stats_bytes(const abl_shape* shape);
  * shape: one fp32 tensor for A3 (forward) or its gradient (backward) - the
  * "+1" buffer of Sec. 3.4 - plus reduction partials. */
 size_t abl_scratch_bytes(const abl_shape* shape, int K);
+/* Which kernels abl_forward uses for this shape when y does not alias x (for tools that report the
+ * launches of a layer step): 1 = one kernel applies Eq. 1-3 and Eq. 9 while it stages the input of
+ * the contraction (abl_bn_conv_fwd), 0 = the normalise-ReLU-pack pass followed by the plain
+ * contraction (abl_bn_relu_pack, abl_conv_fwd).  Negative (an ABL_ERR_ code, negated) on invalid
+ * arguments.  flags as for abl_forward. */
+int abl_forward_is_fused(const abl_shape* shape, int K, uint32_t flags);
 
 /* Forward of one layer (Sec. 3.2; Eq. 1-4 and Eq. 9).
  *   x      [N,H,W,Cin]      in

@@ -50,6 +50,7 @@ _SIGS = {
     "abl_packed_bytes": (_sz, [_shp, ctypes.c_int]),
     "abl_stats_bytes": (_sz, [_shp]),
     "abl_scratch_bytes": (_sz, [_shp, ctypes.c_int]),
+    "abl_forward_is_fused": (ctypes.c_int, [_shp, ctypes.c_int, ctypes.c_uint32]),
     "abl_bn_scratch_bytes": (_sz, [_i64, _i32]),
     "abl_wgrad_scratch_bytes": (_sz, [_shp]),
     "abl_forward": (ctypes.c_int, [_vp, _shp, ctypes.c_int, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
@@ -140,6 +141,13 @@ def abl_stats_bytes(shape):
 
 def abl_scratch_bytes(shape, K):
     return lib.abl_scratch_bytes(ctypes.byref(shape_struct(shape)), K)
+
+
+def abl_forward_is_fused(shape, K, flags=0):
+    r = lib.abl_forward_is_fused(ctypes.byref(shape_struct(shape)), K, flags)
+    if r < 0:
+        raise AblError(-r, "abl_forward_is_fused")
+    return r == 1
 
 
 def abl_bn_scratch_bytes(M, C):

@@ -163,6 +163,28 @@ int abl_conv_wgrad_packed(void* stream, const abl_shape* s, int K, uint32_t flag
 
 namespace {
 
+// Which forward kernel a layer with separate input and output takes: 1 = the 'same' stride-1 kernel
+// with the Eq. 1-3 / Eq. 9 prologue, 2 = the 1x1 kernel with it, 0 = pack pass + plain contraction.
+inline bool aliased(const void* a, const void* b) { return a == b; }
+int forward_fused_path(const abl_shape& s, const ConvGeom& g, int K, bool bf16, bool naive) {
+  // bf16 operands: the contraction runs on the 32-deep bf16 matrix instruction with bf16 tiles in
+  // LDS (its kernel has no BN prologue), so the layer takes the separate stages
+  // - where the contraction is heavy enough to pay for the separate normalise-ReLU-pack pass
+  // (measured: from 512 flops per input element on; below, e.g. 1x1 256->64 at 56x56, reading x
+  // once in the fused kernel wins)
+  const bool bf16_gemm = bf16 && bf16_gemm_supported(g, 0) && 2 * g.Cout * g.R * g.S >= 512;
+  if (K == 32 || naive || bf16_gemm) return 0;
+  // (Not for the small images of the image-resident kernel: the pack pass plus that kernel is
+  // faster than the fused one - 14x14 256->256: 7 + 120 us against 146.)
+  if (halo_fused_supported(g) && !(!bf16 && image_f32_supported(g, 0))) return 1;
+  // With the prologue every block along the output channels repeats the normalization of its
+  // input rows; measured against the separate pack kernel this pays up to 256 output channels.
+  // (Not for the long contractions that the register-resident 1x1 kernel takes: the pack pass plus
+  // that kernel is faster - 1024 -> 256 at 14x14: 17.6 + 55 us against 81.)
+  if (igemm_fused_supported(s) && s.Cout <= 256 && !(!bf16 && rows_f32_blocks(g, 0) > 0)) return 2;
+  return 0;
+}
+
 // Forward: statistics -> (normalise, ReLU, quantize, pack) -> convolution.  A3 lives in the
 // workspace only until the convolution has read it (Sec. 3.2: full-precision intermediates
 // are overwritten as soon as they have been used); 'same' stride-1 convolutions do not even
@@ -187,19 +209,11 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     if (int e = launch_bn_stats(st, x, M, s->Cin, gamma, beta, K, red, stats)) return e;
   }
   const ConvGeom g = geom_of(*s);
-  // bf16 operands: the contraction runs on the 32-deep bf16 matrix instruction with bf16 tiles in
-  // LDS (its kernel has no BN prologue), so the layer takes the separate stages
-  // - where the contraction is heavy enough to pay for the separate normalise-ReLU-pack pass
-  // (measured: from 512 flops per input element on; below, e.g. 1x1 256->64 at 56x56, reading x
-  // once in the fused kernel wins)
-  const bool bf16_gemm = bf16 && bf16_gemm_supported(g, 0) && 2 * g.Cout * g.R * g.S >= 512;
+  const int path = aliased(x, y) ? 0 : forward_fused_path(*s, g, K, bf16, naive);
   // 'same' stride-1 convolutions normalise, quantize and pack while they stage their input
   // patch: x is read once and A3 never reaches memory.  (Not when y aliases x: a block would
   // overwrite input pixels that a neighbouring block has not staged yet.)
-  // (Not for the small images of the image-resident kernel either: the pack pass plus that kernel is
-  // faster than the fused one - 14x14 256->256: 7 + 120 us against 146.)
-  if (K != 32 && !naive && !bf16_gemm && halo_fused_supported(g) && !(!bf16 && image_f32_supported(g, 0)) &&
-      static_cast<const void*>(x) != static_cast<const void*>(y)) {
+  if (path == 1) {
     const int tiles = halo_tile_count(g, 0);
     const bool want = out_partial != nullptr && tiles > 0 && tiles <= kMaxPartialBlocks;
     if (int e = launch_halo_fwd_fused(st, g, K, bf16, x, stats, W, skip, y, packed, want ? out_partial : nullptr))
@@ -208,11 +222,7 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
     return ABL_OK;
   }
   // 1x1 convolutions do the same while they stage their A tile
-  // With the prologue every block along the output channels repeats the normalization of its
-  // input rows; measured against the separate pack kernel this pays up to 256 output channels.
-  if (K != 32 && !naive && !bf16_gemm && igemm_fused_supported(*s) && s->Cout <= 256 &&
-      static_cast<const void*>(x) != static_cast<const void*>(y))
-    return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed, out_partial, out_nb);
+  if (path == 2) return launch_conv_fwd_fused(st, *s, K, bf16, x, stats, W, skip, y, packed, out_partial, out_nb);
   if (int e = launch_bn_relu_pack(st, x, M, s->Cin, K, stats, a3, packed, naive)) return e;
   return launch_conv_fwd(st, *s, bf16, a3, W, skip, y, out_partial, out_nb);
 }
@@ -220,6 +230,15 @@ int forward_impl(hipStream_t st, const abl_shape* s, int K, uint32_t flags, cons
 }  // namespace
 
 extern "C" {
+
+int abl_forward_is_fused(const abl_shape* s, int K, uint32_t flags) {
+  if (int e = check_shape(s)) return -e;
+  if (int e = check_k(K)) return -e;
+  if (flags & ~(uint32_t)(ABL_MATH_BF16 | ABL_NAIVE_FWD)) return -ABL_ERR_ARG;
+  return forward_fused_path(*s, geom_of(*s), K, (flags & ABL_MATH_BF16) != 0, (flags & ABL_NAIVE_FWD) != 0 && K != 32) != 0
+             ? 1
+             : 0;
+}
 
 int abl_forward(void* stream, const abl_shape* s, int K, uint32_t flags, const float* x, const float* W,
                 const float* gamma, const float* beta, const float* skip, void* scratch,
@@ -287,6 +306,14 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     DwSum dwsum;
     if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, tiles, dx, dgamma, dbeta,
+                                dwsum.copies > 0 ? &dwsum : nullptr);
+  }
+  // 1x1 layers with a long contraction: the register-resident kernel, one row of sums per row block
+  if (const int nrb = (K != 32 && !bf16) ? rows_f32_blocks(g, 1) : 0) {
+    if (int e = launch_rows_dgrad_reduce(st, g, K, dy, W, packed, stats, da3, static_cast<double*>(red))) return e;
+    DwSum dwsum;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, nrb, dx, dgamma, dbeta,
                                 dwsum.copies > 0 ? &dwsum : nullptr);
   }
   // 1x1 stride-1 layers: the same sums in the epilogue of the pointwise dgrad kernel
@@ -399,6 +426,11 @@ int abl_conv_dgrad_bn_reduce(void* stream, const abl_shape* s, int K, uint32_t f
     return ABL_ERR_ARG;
   const ConvGeom g = geom_of(*s);
   if (scratch_bytes < bn_partial_bytes(rows_of(*s), s->Cin)) return ABL_ERR_SCRATCH;
+  if (const int nrb = !(flags & ABL_MATH_BF16) ? rows_f32_blocks(g, 1) : 0) {   // 1x1, long contraction
+    *rows = nrb;
+    return launch_rows_dgrad_reduce((hipStream_t)stream, g, K, dy, W, packed, stats, da3,
+                                    static_cast<double*>(scratch));
+  }
   if (!halo_conv_supported(g) && pointwise_supported(g, 1)) {  // 1x1 stride 1: the pointwise kernel's epilogue
     int r = 0;
     if (int e = launch_pointwise_dgrad_reduce((hipStream_t)stream, g, K, (flags & ABL_MATH_BF16) != 0, dy, W, packed,

@@ -171,6 +171,16 @@ int image_wgrad_copies(const ConvGeom& g, int K);
 int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
                        const float* dy, float* copies);
 
+// 1x1 stride-1 convolutions (channel counts in multiples of 64) with the block's whole output tile in
+// accumulator registers and the operands loaded straight from global memory, for shapes that give
+// about one block per compute unit.  rows_f32_blocks: number of row blocks = rows of the sums
+// ([blocks][2][C] doubles: of y in mode 0, Eq. 6-7 in launch_rows_dgrad_reduce), 0 = not supported.
+int rows_f32_blocks(const ConvGeom& g, int mode);
+int launch_rows_f32(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
+                    float* out, double* sums);
+int launch_rows_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                             const void* packed, const void* stats, float* da3, double* partial);
+
 // ---- Eq. 9 / Eq. 10 for one value.  Callers must be compiled with floating-point contraction
 // off: the codes are compared bit for bit with an IEEE fp32 evaluation.
 // floor() limited to +-2^24 so that the integer conversion is defined for any input.

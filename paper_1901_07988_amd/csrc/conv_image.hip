@@ -580,6 +580,279 @@ int image_wgrad_splits(const ConvGeom& g) {
   return s < 1 ? 1 : s;
 }
 
+// ---- 1x1 stride-1 convolutions with everything but the weights' and activations' way in registers ----
+// Eq. 4 (mode 0) and the second half of Eq. 5 (mode 1, optionally with the Eq. 6-7 sums) of a 1x1 layer
+// are one matrix product of the [rows = N H W] x [Cg] activation with the weights.  One block takes up to
+// 208 rows (13 MFMA tiles) and keeps its whole output tile in accumulator registers, as the image-resident
+// kernels above do; with one filter tap no operand is used twice by a block, so nothing goes through LDS
+// in the main loop: a wave loads its activation fragments (the lane's row, four consecutive channels: 16
+// bytes) and weights straight from global memory into the registers the MFMAs read, a k-step (16 channels,
+// 16 x MT MFMAs per wave) ahead.  KSPLIT (long contractions, 64 output channels per block): the four waves
+// split the contraction and add their partial tiles through LDS at the end in a fixed order.  Otherwise
+// (256 output channels per block): each wave owns 64 output channels for the whole contraction and reads
+// every activation fragment itself (the four waves' reads of a line meet in the L1).  Per k-step MT + 16
+// (MT + 4 for the gradient) loads against 16 x MT MFMAs, no barrier, no vector-ALU work.
+template <int MODE, int MT, int EPI, bool KSPLIT>
+__global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __restrict__ in,
+                                                               const float* __restrict__ wgt, const float* skip,
+                                                               float* out, double* __restrict__ sums,
+                                                               const uint8_t* __restrict__ codes,
+                                                               const float* __restrict__ stats, ConvGeom g, int RB) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels (multiple of 64)
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;   // output channels
+  constexpr int NB = KSPLIT ? 64 : 256;        // output channels per block
+  const int64_t M = (int64_t)g.N * g.H * g.W;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD and its L2: the blocks of one row block (same input) run there
+  const int nblk = Ng / NB;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rb = (slot / nblk) * 8 + xcd;
+  const int n0 = (slot % nblk) * NB;
+  const int64_t row0 = (int64_t)rb * RB;
+  if (row0 >= M) return;
+  const int rows = M - row0 < RB ? (int)(M - row0) : RB;
+
+  // the lane's rows: byte offsets of (row, channels 4 lk ..) from the block's first row; rows past the
+  // block repeat its last row and are never stored
+  uint32_t a_lane[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = 16 * i + li;
+    a_lane[i] = 4u * (uint32_t)((m < rows ? m : rows - 1) * Cg + 4 * lk);
+  }
+  const char* const abase = reinterpret_cast<const char*>(in + row0 * Cg);
+  uint32_t w_lane[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    w_lane[t] = 4u * (MODE == 0 ? (uint32_t)((4 * lk + t) * g.Cout + li) : (uint32_t)(li * g.Cout + 4 * lk));
+  // acc[jj]: KSPLIT - the channel tile (wave + jj) % 4 of the block's 64 (a wave's own tile, the one it
+  // finishes, is acc[0]); otherwise tile jj of the wave's 64 channels
+  auto ntile = [&](int jj) __attribute__((always_inline)) {
+    return KSPLIT ? n0 + 16 * ((wave + jj) & 3) : n0 + 64 * wave + 16 * jj;
+  };
+  // k-steps of 16 channels; part p of 8 of a k-step's weights (forward: two rows of one channel tile;
+  // gradient: parts 0, 2, 4, 6 a whole tile) or, p < 0, all of them
+  auto load_w = [&](floatx4 (&dst)[4], int ks, int p) __attribute__((always_inline)) {
+    const int c0 = 16 * ks;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      if (p >= 0 && (p >> 1) != jj) continue;
+      const int nt = ntile(jj);
+      if (MODE == 0) {
+        const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)c0 * g.Cout + nt));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          if (p >= 0 && (t >> 1) != (p & 1)) continue;
+          // (opaque to the optimizer: the 32-bit offset stays a register operand of the load beside
+          // the scalar base instead of being widened to a 64-bit address outside the loop)
+          asm volatile("" : "+v"(w_lane[t]));
+          dst[jj][t] = *reinterpret_cast<const float*>(wb + w_lane[t]);
+        }
+      } else {
+        if (p >= 0 && (p & 1) != 0) continue;
+        const char* wb = reinterpret_cast<const char*>(wgt + ((size_t)nt * g.Cout + c0));
+        asm volatile("" : "+v"(w_lane[0]));
+        dst[jj] = *reinterpret_cast<const floatx4*>(wb + w_lane[0]);
+      }
+    }
+  };
+  auto load_a = [&](floatx4& dst, int i, int ks) __attribute__((always_inline)) {
+    const char* ab = abase + (size_t)ks * 64;
+    asm volatile("" : "+v"(a_lane[i]));
+    dst = *reinterpret_cast<const floatx4*>(ab + a_lane[i]);
+  };
+
+  floatx4 acc[4][MT];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[jj][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int nks = Cg / 16;
+  const int ks_begin = KSPLIT ? wave * nks / 4 : 0, ks_end = KSPLIT ? (wave + 1) * nks / 4 : nks;
+  floatx4 w0[4], w1[4], a[MT];
+  load_w(w0, ks_begin, -1);
+#pragma unroll
+  for (int i = 0; i < MT; ++i) load_a(a[i], i, ks_begin);
+  auto kstep = [&](const floatx4 (&wc)[4], floatx4 (&wn)[4], int ks) __attribute__((always_inline)) {
+    const int kn = ks + 1 < ks_end ? ks + 1 : ks;   // the last k-step asks for its own operands again: no branch
+    __builtin_amdgcn_sched_barrier(0);
+    // the order below is the schedule: a tile's 16 MFMAs (MFMA t contracts channels 4 lk + t), then
+    // the request for its next fragment and a part of the next k-step's weights
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc[jj][i]) : "v"(wc[jj][t]), "v"(a[i][t]));
+      load_a(a[i], i, kn);
+      constexpr int PP = (8 + MT - 1) / MT;   // parts per tile: all eight within the MT tiles
+#pragma unroll
+      for (int q = 0; q < PP; ++q)
+        if (i * PP + q < 8) load_w(wn, kn, i * PP + q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // (one k-step per iteration and a copy of the 16 weight registers: with two k-steps per iteration
+  // and the two sets taking turns the compiler keeps both iterations' fragments apart and spills)
+  for (int ks = ks_begin; ks < ks_end; ++ks) {
+    kstep(w0, w1, ks);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) w0[jj] = w1[jj];
+  }
+  // the last MFMAs' results are read below by instructions the compiler does not know to depend
+  // on a matrix-core result: more wait states than the longest such hazard (18)
+  asm volatile("s_nop 15\n\ts_nop 15");
+
+  // ---- epilogue of one 16-channel tile: shortcut, store, per-channel sums (row rb of [blocks][2][Ng])
+  auto finish = [&](floatx4 (&v)[MT], int nt) __attribute__((always_inline)) {
+    const int nch = nt + 4 * lk;
+    size_t o[MT];   // element offset of the lane's four channels; rows past the block: its last row's
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int m = 16 * i + li;
+      o[i] = (size_t)(row0 + (m < rows ? m : rows - 1)) * Ng + nch;
+    }
+    double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+    if (MODE == 0) {
+      if (skip != nullptr) {
+        floatx4 sv[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) sv[i] = *reinterpret_cast<const floatx4*>(skip + o[i]);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          v[i][0] += sv[i][0]; v[i][1] += sv[i][1]; v[i][2] += sv[i][2]; v[i][3] += sv[i][3];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        if (16 * i + li < rows) {
+          *reinterpret_cast<floatx4*>(out + o[i]) = v[i];
+          if (sums != nullptr) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              s1[r] += (double)v[i][r];
+              s2[r] += (double)v[i][r] * (double)v[i][r];
+            }
+          }
+        }
+      }
+    } else {
+      if constexpr (EPI != 0) {
+        uint32_t cw[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          cw[i] = EPI == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o[i] >> 1))
+                           : *reinterpret_cast<const uint32_t*>(codes + o[i]);
+        const floatx4 st4 = *reinterpret_cast<const floatx4*>(stats + P_STEP * Ng + nch);
+        const floatx4 bt4 = *reinterpret_cast<const floatx4*>(stats + P_BETA * Ng + nch);
+        const floatx4 gm4 = *reinterpret_cast<const floatx4*>(stats + P_GAMMA * Ng + nch);
+        const int4 fb4 = *reinterpret_cast<const int4*>(stats + P_FB * Ng + nch);
+        const int32_t fbv[4] = {fb4.x, fb4.y, fb4.z, fb4.w};
+        float ig[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ig[r] = 1.0f / gm4[r];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          if (16 * i + li < rows) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint32_t code = (cw[i] >> (EPI * r)) & ((1u << EPI) - 1u);
+              const int32_t j = (int32_t)code - (1 << (EPI - 1)) + fbv[r];
+              const float a2t = st4[r] * ((float)j + 0.5f);        // Eq. 10
+              const float da2 = a2t > 0.0f ? v[i][r] : 0.0f;       // Eq. 6
+              const float a1t = (a2t - bt4[r]) * ig[r];            // inverse of Eq. 2
+              s1[r] += (double)da2;
+              s2[r] += (double)a1t * (double)da2;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        if (16 * i + li < rows) *reinterpret_cast<floatx4*>(out + o[i]) = v[i];
+    }
+    if (sums != nullptr && (MODE == 0 || EPI != 0)) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+          s1[r] += __shfl_xor(s1[r], d, 64);
+          s2[r] += __shfl_xor(s2[r], d, 64);
+        }
+      }
+      if (li == 0) {
+        double* row = sums + (size_t)rb * 2 * Ng;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          row[nch + r] = s1[r];
+          row[Ng + nch + r] = s2[r];
+        }
+      }
+    }
+  };
+
+  if constexpr (KSPLIT) {
+    // the four partial tiles -> one: wave w sends acc[jj], jj = 1..3, to the owner (w + jj) % 4, which
+    // adds what it receives in the order jj = 1, 2, 3 of the senders
+#pragma unroll
+    for (int jj = 1; jj < 4; ++jj) {
+      const int owner = (wave + jj) & 3;
+      unsigned char* dst = smem + (size_t)((owner * 3 + (jj - 1)) * MT) * 1024 + lane * 16;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) *reinterpret_cast<floatx4*>(dst + i * 1024) = acc[jj][i];
+    }
+    __syncthreads();
+    floatx4 v[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      v[i] = acc[0][i];
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        const floatx4 t = *reinterpret_cast<const floatx4*>(smem + (size_t)((wave * 3 + q) * MT + i) * 1024 + lane * 16);
+        v[i][0] += t[0]; v[i][1] += t[1]; v[i][2] += t[2]; v[i][3] += t[3];
+      }
+    }
+    finish(v, n0 + 16 * wave);
+  } else {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) finish(acc[jj], n0 + 64 * wave + 16 * jj);
+  }
+}
+
+// rows per block and number of row blocks of the 1x1 kernel: whole images when one fits 13 tiles
+// and the batch then fills the chip better (64 images x 4 channel blocks = 256), else 208 rows
+struct RowsPlan {
+  int RB, nrb, mt;
+  bool ksplit;
+};
+bool rows_plan(const ConvGeom& g, int mode, RowsPlan& p) {
+  const int Cg = mode == 0 ? g.Cin : g.Cout, Ng = mode == 0 ? g.Cout : g.Cin;
+  if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
+  if (Cg % 64 != 0 || Ng % 64 != 0) return false;
+  const int64_t M = (int64_t)g.N * g.H * g.W;
+  const int64_t e_in = M * g.Cin, e_out = M * g.Cout;
+  if (e_in >= ((int64_t)1 << 30) || e_out >= ((int64_t)1 << 30)) return false;   // 32-bit byte offsets
+  // long contractions only (the waves split them); each wave reading every fragment itself for 256
+  // output channels per block (256 -> 1024 channels) measured no faster than the LDS-tiled kernel
+  p.ksplit = true;
+  if (Cg < 512) return false;
+  const int nb = 64;
+  const int HW = g.H * g.W;
+  p.mt = 13;
+  p.RB = HW <= 208 && HW > 104 ? HW : 208;
+  p.nrb = (int)((M + p.RB - 1) / p.RB);
+  if (p.nrb > kMaxPartialBlocks) return false;
+  // built for about one block per compute unit: with much fewer (or many more small ones) the tiled
+  // kernels are faster
+  const int64_t blocks = (int64_t)p.nrb * (Ng / nb);
+  return blocks >= 224 && blocks <= 2048;
+}
+
 int image_mt(const ConvGeom& g) {
   const int tiles = (g.H * g.W + 15) / 16;
   return tiles <= 4 ? 4 : tiles <= 8 ? 8 : tiles <= 13 ? 13 : 0;
@@ -660,6 +933,41 @@ int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* pac
   if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
   kern<<<grid, kThreads, lds, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
   return hip_status();
+}
+
+namespace {
+template <int MODE, int EPI>
+int launch_rows(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip, float* out,
+                double* sums, const uint8_t* codes, const float* stats) {
+  RowsPlan p;
+  if (!rows_plan(g, MODE, p)) return ABL_ERR_SHAPE;
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const unsigned grid = (unsigned)((p.nrb + 7) / 8 * 8 * (Ng / 64));
+  auto kern = rows_f32_kernel<MODE, 13, EPI, true>;
+  if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
+  kern<<<grid, kThreads, (size_t)12 * 13 * 1024, st>>>(in, w, skip, out, sums, codes, stats, g, p.RB);
+  return hip_status();
+}
+}  // namespace
+
+int rows_f32_blocks(const ConvGeom& g, int mode) {
+  RowsPlan p;
+  return rows_plan(g, mode, p) ? p.nrb : 0;
+}
+
+int launch_rows_f32(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
+                    float* out, double* sums) {
+  if (mode == 0) return launch_rows<0, 0>(st, g, in, w, skip, out, sums, nullptr, nullptr);
+  return launch_rows<1, 0>(st, g, in, w, nullptr, out, nullptr, nullptr, nullptr);
+}
+
+int launch_rows_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                             const void* packed, const void* stats, float* da3, double* partial) {
+  const uint8_t* codes = static_cast<const uint8_t*>(packed);
+  const float* sp = static_cast<const float*>(stats);
+  if (K == 4) return launch_rows<1, 4>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+  if (K == 8) return launch_rows<1, 8>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+  return ABL_ERR_SHAPE;
 }
 
 }  // namespace abl

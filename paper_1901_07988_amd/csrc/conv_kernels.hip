@@ -992,6 +992,13 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     if (want) *rows = tiles;
     return launch_halo_conv(st, g, 0, bf16, a3, w, skip, y, want ? sums : nullptr);
   }
+  // 1x1 layers that give about one block per compute unit: the output tile in registers, one row of sums
+  // per row block
+  if (const int nrb = !bf16 ? rows_f32_blocks(g, 0) : 0) {
+    const bool want = sums != nullptr && rows != nullptr;
+    if (want) *rows = nrb;
+    return launch_rows_f32(st, g, 0, a3, w, skip, y, want ? sums : nullptr);
+  }
   if (pointwise_supported(g, 0))
     return launch_pointwise_conv(st, g, 0, bf16, a3, w, skip, y, rows != nullptr ? sums : nullptr, rows);
   return launch_igemm<0, 0>(st, g, bf16, a3, w, skip, y, nullptr, nullptr);
@@ -1028,6 +1035,7 @@ int launch_conv_dgrad(hipStream_t st, const abl_shape& s, bool bf16, const float
   if (bf16 && bf16_gemm_supported(g, 1)) return launch_bf16_gemm(st, g, 1, dy, w, nullptr, da3);
   if (!bf16 && image_f32_supported(g, 1)) return launch_image_f32(st, g, 1, dy, w, nullptr, da3, nullptr);
   if (halo_conv_supported(g)) return launch_halo_conv(st, g, 1, bf16, dy, w, nullptr, da3);
+  if (!bf16 && rows_f32_blocks(g, 1) > 0) return launch_rows_f32(st, g, 1, dy, w, nullptr, da3, nullptr);
   if (pointwise_supported(g, 1)) return launch_pointwise_conv(st, g, 1, bf16, dy, w, nullptr, da3);
   return launch_igemm<1, 0>(st, g, bf16, dy, w, nullptr, da3, nullptr, nullptr);
 }

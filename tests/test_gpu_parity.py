@@ -797,7 +797,8 @@ def test_average_pool_folded_into_linear(G, oracle, s, pool):
 @pytest.mark.parametrize("N,H,W,Cin,Cout", [
     (1, 1, 1, 64, 16), (3, 5, 7, 128, 48), (2, 9, 9, 192, 96), (5, 6, 6, 256, 320), (1, 13, 11, 384, 64),
     (2, 8, 8, 512, 272), (7, 3, 3, 1024, 128), (1, 40, 40, 64, 64), (4, 17, 5, 640, 192), (2, 5, 5, 320, 64),
-    (1, 67, 126, 512, 256), (1, 67, 126, 256, 512)],
+    (1, 67, 126, 512, 256), (1, 67, 126, 256, 512),
+    (4, 77, 77, 512, 128), (3, 125, 125, 64, 512), (57, 14, 13, 512, 256), (2, 100, 60, 512, 512)],
     ids=lambda v: str(v))
 def test_pointwise_convolutions(G, oracle, N, H, W, Cin, Cout):
     """1x1 stride-1 layers through the kernel that loads activations straight into MFMA layout:
@@ -805,7 +806,10 @@ def test_pointwise_convolutions(G, oracle, N, H, W, Cin, Cout):
     128-channel chunks, one to four 16-channel tiles per wave, pixel counts that leave ragged
     tiles and idle blocks; the two largest cases have enough pixels (8442, not a multiple of 16)
     for the grid of whole rounds plus row groups split over the contraction, forward (512 -> 256)
-    and data gradient (256 -> 512)."""
+    and data gradient (256 -> 512).  The last four have contractions of 512 channels and at least 224
+    blocks of 208 rows (or whole images) x 64 output channels: the kernel that keeps the output tile
+    in registers - forward only, data gradient only (with its Eq. 6-7 sums in the layer call),
+    whole images per block, and both directions."""
     o = oracle
     s = LayerShape(N, H, W, Cin, Cout, 1, 1, 1, 0)
     print("case pointwise", s.as_tuple(), flush=True)
