@@ -122,3 +122,18 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_forward_path_query(B):
+    """abl_forward_is_fused answers from the shape alone (no launch): the 56x56 bottleneck layers take
+    the kernel with the Eq. 1-3 / Eq. 9 prologue, the 14x14 layers that the register-resident kernels
+    cover take the pack pass plus the plain contraction, exact storage never fuses."""
+    assert B.abl_forward_is_fused((64, 56, 56, 256, 64, 1, 1, 1, 0), 4) is True
+    assert B.abl_forward_is_fused((64, 56, 56, 64, 64, 3, 3, 1, 1), 4) is True
+    assert B.abl_forward_is_fused((64, 14, 14, 1024, 256, 1, 1, 1, 0), 4) is False
+    assert B.abl_forward_is_fused((64, 14, 14, 256, 256, 3, 3, 1, 1), 8) is False
+    assert B.abl_forward_is_fused((2, 14, 14, 256, 256, 3, 3, 1, 1), 4) is True      # too few blocks for them
+    assert B.abl_forward_is_fused((64, 56, 56, 64, 64, 3, 3, 1, 1), 32) is False
+    with pytest.raises(B.AblError) as e:
+        B.abl_forward_is_fused((64, 56, 56, 64, 64, 3, 3, 1, 1), 5)
+    assert e.value.code == B.ABL_ERR_ARG
