@@ -587,12 +587,11 @@ int image_wgrad_splits(const ConvGeom& g) {
 // kernels above do; with one filter tap no operand is used twice by a block, so nothing goes through LDS
 // in the main loop: a wave loads its activation fragments (the lane's row, four consecutive channels: 16
 // bytes) and weights straight from global memory into the registers the MFMAs read, a k-step (16 channels,
-// 16 x MT MFMAs per wave) ahead.  KSPLIT (long contractions, 64 output channels per block): the four waves
-// split the contraction and add their partial tiles through LDS at the end in a fixed order.  Otherwise
-// (256 output channels per block): each wave owns 64 output channels for the whole contraction and reads
-// every activation fragment itself (the four waves' reads of a line meet in the L1).  Per k-step MT + 16
-// (MT + 4 for the gradient) loads against 16 x MT MFMAs, no barrier, no vector-ALU work.
-template <int MODE, int MT, int EPI, bool KSPLIT>
+// 16 x MT MFMAs per wave) ahead.  The four waves split the contraction (which therefore has to be long:
+// 512 channels and more) and add their partial tiles through LDS at the end in a fixed order; a block
+// covers 64 output channels.  Per k-step MT + 16 (MT + 4 for the gradient) loads and a 16-register copy
+// against 16 x MT MFMAs, no barrier.
+template <int MODE, int MT, int EPI>
 __global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __restrict__ in,
                                                                const float* __restrict__ wgt, const float* skip,
                                                                float* out, double* __restrict__ sums,
@@ -601,7 +600,7 @@ __global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __re
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels (multiple of 64)
   const int Ng = MODE == 0 ? g.Cout : g.Cin;   // output channels
-  constexpr int NB = KSPLIT ? 64 : 256;        // output channels per block
+  constexpr int NB = 64;                       // output channels per block
   const int64_t M = (int64_t)g.N * g.H * g.W;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -628,11 +627,9 @@ __global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __re
 #pragma unroll
   for (int t = 0; t < 4; ++t)
     w_lane[t] = 4u * (MODE == 0 ? (uint32_t)((4 * lk + t) * g.Cout + li) : (uint32_t)(li * g.Cout + 4 * lk));
-  // acc[jj]: KSPLIT - the channel tile (wave + jj) % 4 of the block's 64 (a wave's own tile, the one it
-  // finishes, is acc[0]); otherwise tile jj of the wave's 64 channels
-  auto ntile = [&](int jj) __attribute__((always_inline)) {
-    return KSPLIT ? n0 + 16 * ((wave + jj) & 3) : n0 + 64 * wave + 16 * jj;
-  };
+  // acc[jj]: the channel tile (wave + jj) % 4 of the block's 64, so that a wave's own tile (the one it
+  // finishes) is acc[0] whatever the wave
+  auto ntile = [&](int jj) __attribute__((always_inline)) { return n0 + 16 * ((wave + jj) & 3); };
   // k-steps of 16 channels; part p of 8 of a k-step's weights (forward: two rows of one channel tile;
   // gradient: parts 0, 2, 4, 6 a whole tile) or, p < 0, all of them
   auto load_w = [&](floatx4 (&dst)[4], int ks, int p) __attribute__((always_inline)) {
@@ -672,7 +669,7 @@ __global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __re
     for (int i = 0; i < MT; ++i) acc[jj][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int nks = Cg / 16;
-  const int ks_begin = KSPLIT ? wave * nks / 4 : 0, ks_end = KSPLIT ? (wave + 1) * nks / 4 : nks;
+  const int ks_begin = wave * nks / 4, ks_end = (wave + 1) * nks / 4;
   floatx4 w0[4], w1[4], a[MT];
   load_w(w0, ks_begin, -1);
 #pragma unroll
@@ -796,39 +793,33 @@ __global__ __launch_bounds__(kThreads, 1) void rows_f32_kernel(const float* __re
     }
   };
 
-  if constexpr (KSPLIT) {
-    // the four partial tiles -> one: wave w sends acc[jj], jj = 1..3, to the owner (w + jj) % 4, which
-    // adds what it receives in the order jj = 1, 2, 3 of the senders
+  // the four partial tiles -> one: wave w sends acc[jj], jj = 1..3, to the owner (w + jj) % 4, which
+  // adds what it receives in the order jj = 1, 2, 3 of the senders
 #pragma unroll
-    for (int jj = 1; jj < 4; ++jj) {
-      const int owner = (wave + jj) & 3;
-      unsigned char* dst = smem + (size_t)((owner * 3 + (jj - 1)) * MT) * 1024 + lane * 16;
+  for (int jj = 1; jj < 4; ++jj) {
+    const int owner = (wave + jj) & 3;
+    unsigned char* dst = smem + (size_t)((owner * 3 + (jj - 1)) * MT) * 1024 + lane * 16;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) *reinterpret_cast<floatx4*>(dst + i * 1024) = acc[jj][i];
-    }
-    __syncthreads();
-    floatx4 v[MT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      v[i] = acc[0][i];
-#pragma unroll
-      for (int q = 0; q < 3; ++q) {
-        const floatx4 t = *reinterpret_cast<const floatx4*>(smem + (size_t)((wave * 3 + q) * MT + i) * 1024 + lane * 16);
-        v[i][0] += t[0]; v[i][1] += t[1]; v[i][2] += t[2]; v[i][3] += t[3];
-      }
-    }
-    finish(v, n0 + 16 * wave);
-  } else {
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) finish(acc[jj], n0 + 64 * wave + 16 * jj);
+    for (int i = 0; i < MT; ++i) *reinterpret_cast<floatx4*>(dst + i * 1024) = acc[jj][i];
   }
+  __syncthreads();
+  floatx4 v[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    v[i] = acc[0][i];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const floatx4 t = *reinterpret_cast<const floatx4*>(smem + (size_t)((wave * 3 + q) * MT + i) * 1024 + lane * 16);
+      v[i][0] += t[0]; v[i][1] += t[1]; v[i][2] += t[2]; v[i][3] += t[3];
+    }
+  }
+  finish(v, ntile(0));
 }
 
 // rows per block and number of row blocks of the 1x1 kernel: whole images when one fits 13 tiles
 // and the batch then fills the chip better (64 images x 4 channel blocks = 256), else 208 rows
 struct RowsPlan {
   int RB, nrb, mt;
-  bool ksplit;
 };
 bool rows_plan(const ConvGeom& g, int mode, RowsPlan& p) {
   const int Cg = mode == 0 ? g.Cin : g.Cout, Ng = mode == 0 ? g.Cout : g.Cin;
@@ -837,9 +828,9 @@ bool rows_plan(const ConvGeom& g, int mode, RowsPlan& p) {
   const int64_t M = (int64_t)g.N * g.H * g.W;
   const int64_t e_in = M * g.Cin, e_out = M * g.Cout;
   if (e_in >= ((int64_t)1 << 30) || e_out >= ((int64_t)1 << 30)) return false;   // 32-bit byte offsets
-  // long contractions only (the waves split them); each wave reading every fragment itself for 256
-  // output channels per block (256 -> 1024 channels) measured no faster than the LDS-tiled kernel
-  p.ksplit = true;
+  // long contractions only (the waves split them): for 256 channels neither each wave reading every
+  // fragment itself (256 output channels per block) nor a split in two (128 per block) measured
+  // faster than the LDS-tiled kernel
   if (Cg < 512) return false;
   const int nb = 64;
   const int HW = g.H * g.W;
@@ -943,7 +934,7 @@ int launch_rows(hipStream_t st, const ConvGeom& g, const float* in, const float*
   if (!rows_plan(g, MODE, p)) return ABL_ERR_SHAPE;
   const int Ng = MODE == 0 ? g.Cout : g.Cin;
   const unsigned grid = (unsigned)((p.nrb + 7) / 8 * 8 * (Ng / 64));
-  auto kern = rows_f32_kernel<MODE, 13, EPI, true>;
+  auto kern = rows_f32_kernel<MODE, 13, EPI>;
   if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
   kern<<<grid, kThreads, (size_t)12 * 13 * 1024, st>>>(in, w, skip, out, sums, codes, stats, g, p.RB);
   return hip_status();
