@@ -78,3 +78,50 @@ def test_random_stacks(G, oracle, seed):
         assert rel(run.output(), y_ref) < TOL
         # codes and gradients: every layer on the GPU's own tensors
         teacher_forced(G, o, wl, K, seed=seed, verbose=False)
+
+
+def _random_resident_layer(rng):
+    """A layer that one of the register-resident kernels takes in at least one direction: enough
+    images (or rows) for 224 blocks of 64 output channels."""
+    kind = int(rng.integers(0, 3))
+    if kind == 0:      # 3x3 'same' on a small image: image_f32_kernel forward and / or data gradient
+        H, W = int(rng.integers(2, 15)), int(rng.integers(2, 15))
+        while H * W > 208:
+            H -= 1
+        cin, cout = int(rng.choice([16, 32, 64, 128, 192])), int(rng.choice([64, 128, 256]))
+        N = -(-224 // (cout // 64)) + int(rng.integers(0, 5))
+        return LayerShape(N, H, W, cin, cout)
+    if kind == 1:      # 3x3 'same', 14 pixels wide: image_wgrad_kernel (32 x 64 channel tiles x shares of the images >= 224)
+        H = int(rng.choice([2, 4, 6, 10, 14]))
+        cin, cout = [(160, 320), (256, 128), (64, 512), (96, 320)][int(rng.integers(0, 4))]
+        return LayerShape(16 + int(rng.integers(0, 3)), H, 14, cin, cout)
+    # 1x1 with a long contraction: rows_f32_kernel forward (Cin >= 512) or data gradient (Cout >= 512)
+    big, small = int(rng.choice([512, 576, 1024])), int(rng.choice([64, 128]))
+    rows = -(-224 // (small // 64)) * 208 + int(rng.integers(1, 400))
+    H = int(rng.integers(20, 60))
+    Wd = -(-rows // H)
+    return LayerShape(1, H, Wd, big, small, 1, 1, 1, 0) if rng.random() < 0.5 else LayerShape(1, H, Wd, small, big, 1, 1, 1, 0)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_layers_on_the_register_resident_kernels(G, oracle, seed):
+    """Seeded random shapes large enough for the one-block-per-compute-unit kernels (whole image or
+    row block resident, output tile in accumulator registers): image sizes that leave ragged pixel
+    tiles, batches that are not multiples of eight, single-phase and multi-phase contractions."""
+    o = oracle
+    rng = np.random.default_rng(3000 + seed)
+    for _ in range(5):
+        s = _random_resident_layer(rng)
+        K = int(rng.choice([4, 8]))
+        print("case random resident layer", s.as_tuple(), K, flush=True)
+        x, w, gamma, beta, dy = synth.draw_layer(s, int(rng.integers(1 << 30)), "normal", "random")
+        skip = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32) if rng.random() < 0.3 else None
+        run = G.LayerRun(s, K)
+        y = run.forward(x, w, gamma, beta, skip=skip)
+        y_ref, saved = o.layer_forward(x, w, gamma, beta, K, oshape(o, s), skip=skip)
+        assert run.packed.cpu().numpy().tobytes() == saved.store.tobytes()
+        assert rel(y, y_ref) < TOL
+        dx, dw, dg, db = run.backward(dy, w)
+        dx_ref, dw_ref, dg_ref, db_ref = o.layer_backward(saved, dy, w)
+        assert rel(dx, dx_ref) < TOL and rel(dw, dw_ref) < TOL
+        assert rel(dg, dg_ref) < TOL and rel(db, db_ref) < TOL
