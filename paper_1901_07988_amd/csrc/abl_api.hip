@@ -298,6 +298,14 @@ int abl_backward(void* stream, const abl_shape* s, int K, uint32_t flags, const 
     return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, g.N, dx, dgamma, dbeta,
                                 dwsum.copies > 0 ? &dwsum : nullptr);
   }
+  // bf16 operands on the 32-deep matrix instruction: the same sums in the epilogue of its kernels
+  if (const int nr = (K != 32 && bf16_gemm) ? bf16_dgrad_reduce_rows(g) : 0) {
+    if (int e = launch_bf16_dgrad_reduce(st, g, K, dy, W, packed, stats, da3, static_cast<double*>(red))) return e;
+    DwSum dwsum;
+    if (int e = launch_conv_wgrad_packed(st, *s, K, bf16, packed, stats, dy, wpart, dW, false, &dwsum)) return e;
+    return launch_bn_bwd_finish(st, packed, stats, da3, M, s->Cin, K, accum, red, nr, dx, dgamma, dbeta,
+                                dwsum.copies > 0 ? &dwsum : nullptr);
+  }
   const int tiles = K != 32 && !bf16_gemm && halo_conv_supported(g) ? halo_tile_count(g, 1) : 0;
   if (tiles > 0 && tiles <= kMaxPartialBlocks) {
     if (int e = launch_halo_dgrad_reduce(st, g, K, bf16, dy, W, packed, stats, da3, static_cast<double*>(red)))

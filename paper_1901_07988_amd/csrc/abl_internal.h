@@ -141,8 +141,15 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
 // Forward (mode 0) / gradient to the input (mode 1) of any stride, filter and padding whose
 // contraction channels are a multiple of 32 and output channels a multiple of 64.
 bool bf16_gemm_supported(const ConvGeom& g, int mode);
+// sums / rows (nullable, mode 0): [*rows][2][Cout] doubles = per-block sum(y), sum(y^2) of the output;
+// *rows = 0 when the kernel leaves none (more blocks than kMaxPartialBlocks).
 int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
-                     float* out);
+                     float* out, double* sums = nullptr, int* rows = nullptr);
+// Gradient to the conv input with the Eq. 6-7 sums from the layer's codes (K = 4 / 8) in the epilogue of
+// whichever bf16 kernel takes the shape: partial = [rows][2][Cin] doubles; bf16_dgrad_reduce_rows = 0 if none does.
+int bf16_dgrad_reduce_rows(const ConvGeom& g);
+int launch_bf16_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                             const void* packed, const void* stats, float* da3, double* partial);
 // 3x3 'same' stride-1 convolutions whose whole image fits in LDS as bf16 (up to 208 pixels, e.g.
 // 14x14 with 256 channels): one block per image and 64 output channels.
 // sums (nullable, mode 0): [N][2][Cout] doubles = per-image sum(y), sum(y^2) of the output.

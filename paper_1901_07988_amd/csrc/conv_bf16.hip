@@ -41,10 +41,15 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int MODE, int BN>
+// EPI: 0 = none; 1 (forward) = per-block sums of y and y^2 per channel, the first pass of the next
+// layer's Eq. 1; 4 / 8 (gradient) = the Eq. 6-7 sums from the layer's K-bit codes, the first pass of
+// the BN backward.  Row m0 / BM of sums = [blocks][2][Ng] doubles.
+template <int MODE, int BN, int EPI>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const float* __restrict__ in,
                                                              const float* __restrict__ wgt, const float* skip,
-                                                             float* out, ConvGeom g) {
+                                                             float* out, ConvGeom g, double* __restrict__ sums,
+                                                             const uint8_t* __restrict__ codes,
+                                                             const float* __restrict__ stats) {
   constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
   constexpr int MT = WM / 16, NT = WN / 16;
   constexpr int A_PASSES = BM * (BK / 4) / kThreads;   // float4 of the A tile per thread: 4
@@ -215,24 +220,83 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const float* __rest
     __syncthreads();
   }
 
-  // epilogue: the lane holds channels n0 + wn0 + 16 j + 4 lk .. +3 of pixel m0 + wm0 + 16 i + li
+  // epilogue: the lane holds channels n0 + wn0 + 16 j + 4 lk .. +3 of pixel m0 + wm0 + 16 i + li.
+  // One 16-channel tile after the other, so that the sums of one tile only are live (all of them
+  // at once cost the kernel a resident block per SIMD).
+  double* red = reinterpret_cast<double*>(lds);   // [2][2][BN], free since the barrier that ended the main loop
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    const int64_t p = m0 + wm0 + 16 * i + li;
-    if (p >= Mg) continue;
+  for (int j = 0; j < NT; ++j) {
+    const int c = n0 + wn0 + 16 * j + 4 * lk;
+    double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+    floatx4 e_st, e_bt, e_ig;
+    int4 e_fb;
+    if constexpr (EPI > 1) {
+      e_st = *reinterpret_cast<const floatx4*>(stats + P_STEP * Ng + c);
+      e_bt = *reinterpret_cast<const floatx4*>(stats + P_BETA * Ng + c);
+      const floatx4 gm = *reinterpret_cast<const floatx4*>(stats + P_GAMMA * Ng + c);
+      e_ig = floatx4{1.0f / gm[0], 1.0f / gm[1], 1.0f / gm[2], 1.0f / gm[3]};
+      e_fb = *reinterpret_cast<const int4*>(stats + P_FB * Ng + c);
+    }
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int64_t o = p * Ng + n0 + wn0 + 16 * j + 4 * lk;
+    for (int i = 0; i < MT; ++i) {
+      const int64_t p = m0 + wm0 + 16 * i + li;
+      if (p >= Mg) continue;
+      const int64_t o = p * Ng + c;
       float4 v = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
       if (skip != nullptr) {
         const float4 sv = *reinterpret_cast<const float4*>(skip + o);
         v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
       }
       *reinterpret_cast<float4*>(out + o) = v;
+      if constexpr (EPI == 1) {
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          s1[r] += (double)vv[r];
+          s2[r] += (double)vv[r] * (double)vv[r];
+        }
+      } else if constexpr (EPI > 1) {
+        const uint32_t cw = EPI == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o >> 1))
+                                     : *reinterpret_cast<const uint32_t*>(codes + o);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        const int32_t fbv[4] = {e_fb.x, e_fb.y, e_fb.z, e_fb.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t code = (cw >> (EPI * r)) & ((1u << EPI) - 1u);
+          const int32_t q = (int32_t)code - (1 << (EPI - 1)) + fbv[r];
+          const float a2t = e_st[r] * ((float)q + 0.5f);            // Eq. 10
+          const float da2 = a2t > 0.0f ? vv[r] : 0.0f;              // Eq. 6
+          const float a1t = (a2t - e_bt[r]) * e_ig[r];              // inverse of Eq. 2
+          s1[r] += (double)da2;
+          s2[r] += (double)a1t * (double)da2;
+        }
+      }
+    }
+    if constexpr (EPI != 0) {
+      // fixed order: the 16 pixel lanes by a butterfly, then (below) the two waves that share the channels
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        double t1 = s1[r], t2 = s2[r];
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+          t1 += __shfl_xor(t1, d, 64);
+          t2 += __shfl_xor(t2, d, 64);
+        }
+        if (li == 0) {
+          red[(0 * 2 + (wave >> 1)) * BN + wn0 + 16 * j + 4 * lk + r] = t1;
+          red[(1 * 2 + (wave >> 1)) * BN + wn0 + 16 * j + 4 * lk + r] = t2;
+        }
+      }
+    }
+  }
+  if constexpr (EPI != 0) {
+    __syncthreads();
+    for (int c = tid; c < 2 * BN; c += kThreads) {
+      const int qv = c / BN, ch = c % BN;
+      sums[((m0 / BM) * 2 + qv) * Ng + n0 + ch] = red[(qv * 2 + 0) * BN + ch] + red[(qv * 2 + 1) * BN + ch];
     }
   }
 }
-
 
 // ---- 3x3 'same' stride-1 convolutions on small images: the whole image stays in LDS -------------
 // One block = one image x 64 output channels.  The image, rounded to bf16 once, sits in LDS with
@@ -248,11 +312,13 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const float* __rest
 // the next layer's Eq. 1 statistics.
 constexpr int IMG_NB = 64;       // output channels per block
 
-template <int MODE, int MT>
+template <int MODE, int MT, int EPI>
 __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __restrict__ in,
                                                                  const float* __restrict__ wgt,
                                                                  const float* skip, float* out,
-                                                                 double* __restrict__ sums, ConvGeom g) {
+                                                                 double* __restrict__ sums, ConvGeom g,
+                                                                 const uint8_t* __restrict__ codes,
+                                                                 const float* __restrict__ stats) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int H = g.H, W = g.W, HW = H * W, PW = W + 2;
   const int Cg = MODE == 0 ? g.Cin : g.Cout;   // contraction channels: a power of two, 32 .. 1024
@@ -448,6 +514,37 @@ __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __
     }
   }
   double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+  if constexpr (MODE == 1 && EPI != 0) {
+    // Eq. 6-7 from the layer's K-bit codes: the codes of the lane's four channels per pixel
+    uint32_t cw[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+      cw[i] = EPI == 4 ? (uint32_t) * reinterpret_cast<const uint16_t*>(codes + (o[i] >> 1))
+                       : *reinterpret_cast<const uint32_t*>(codes + o[i]);
+    const floatx4 st4 = *reinterpret_cast<const floatx4*>(stats + P_STEP * Ng + nch);
+    const floatx4 bt4 = *reinterpret_cast<const floatx4*>(stats + P_BETA * Ng + nch);
+    const floatx4 gm4 = *reinterpret_cast<const floatx4*>(stats + P_GAMMA * Ng + nch);
+    const int4 fb4 = *reinterpret_cast<const int4*>(stats + P_FB * Ng + nch);
+    const int32_t fbv[4] = {fb4.x, fb4.y, fb4.z, fb4.w};
+    float ig[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ig[r] = 1.0f / gm4[r];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if (16 * i + li < HW) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t code = (cw[i] >> (EPI * r)) & ((1u << EPI) - 1u);
+          const int32_t q = (int32_t)code - (1 << (EPI - 1)) + fbv[r];
+          const float a2t = st4[r] * ((float)q + 0.5f);        // Eq. 10
+          const float da2 = a2t > 0.0f ? v[i][r] : 0.0f;       // Eq. 6
+          const float a1t = (a2t - bt4[r]) * ig[r];            // inverse of Eq. 2
+          s1[r] += (double)da2;
+          s2[r] += (double)a1t * (double)da2;
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     if (16 * i + li < HW) {
@@ -461,8 +558,8 @@ __global__ __launch_bounds__(kThreads, 1) void image_bf16_kernel(const float* __
       }
     }
   }
-  if (MODE == 0 && sums != nullptr) {
-    // row `img` of [N][2][Ng]: sum(y), sum(y^2) over the image, added over the 16 pixel lanes
+  if (sums != nullptr && (MODE == 0 || EPI != 0)) {
+    // row `img` of [N][2][Ng]: the two sums over the image, added over the 16 pixel lanes
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -492,23 +589,61 @@ bool bf16_gemm_supported(const ConvGeom& g, int mode) {
   return e_in < ((int64_t)1 << 31) && e_out < ((int64_t)1 << 31);
 }
 
-int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
-                     float* out) {
-  if (!bf16_gemm_supported(g, mode)) return ABL_ERR_SHAPE;
-  const int Ng = mode == 0 ? g.Cout : g.Cin;
+int launch_image_bf16_epi(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w, float* da3,
+                          double* partial, const uint8_t* codes, const float* stats);
+
+namespace {
+// rows of sums the kernel leaves (one per block of 128 pixels), 0 if more than the partial buffers hold
+int gemm_sum_rows(const ConvGeom& g, int mode) {
   const int64_t Mg = mode == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
+  const int64_t nb = (Mg + BM - 1) / BM;
+  return nb <= kMaxPartialBlocks ? (int)nb : 0;
+}
+
+template <int MODE, int EPI>
+int launch_gemm(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip, float* out,
+                double* sums, const uint8_t* codes, const float* stats) {
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const int64_t Mg = MODE == 0 ? (int64_t)g.N * g.Ho * g.Wo : (int64_t)g.N * g.H * g.W;
   const int64_t mblk = ((Mg + BM - 1) / BM + 7) / 8 * 8;  // whole XCD rounds; blocks past the end return
   // 128 output channels per block when that still leaves two blocks per compute unit
-  const bool wide = Ng % 128 == 0 && mblk * (Ng / 128) >= 512;
+  // (not with the Eq. 6-7 epilogue: its registers would cost the wide tile a resident block per SIMD)
+  const bool wide = EPI <= 1 && Ng % 128 == 0 && mblk * (Ng / 128) >= 512;
   const unsigned grid = (unsigned)(mblk * (Ng / (wide ? 128 : 64)));
-  if (mode == 0) {
-    if (wide) gemm_bf16_kernel<0, 128><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
-    else gemm_bf16_kernel<0, 64><<<grid, kThreads, 0, st>>>(in, w, skip, out, g);
-  } else {
-    if (wide) gemm_bf16_kernel<1, 128><<<grid, kThreads, 0, st>>>(in, w, nullptr, out, g);
-    else gemm_bf16_kernel<1, 64><<<grid, kThreads, 0, st>>>(in, w, nullptr, out, g);
-  }
+  if (wide) gemm_bf16_kernel<MODE, 128, EPI><<<grid, kThreads, 0, st>>>(in, w, skip, out, g, sums, codes, stats);
+  else gemm_bf16_kernel<MODE, 64, EPI><<<grid, kThreads, 0, st>>>(in, w, skip, out, g, sums, codes, stats);
   return hip_status();
+}
+}  // namespace
+
+int launch_bf16_gemm(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w, const float* skip,
+                     float* out, double* sums, int* rows) {
+  if (!bf16_gemm_supported(g, mode)) return ABL_ERR_SHAPE;
+  if (rows != nullptr) *rows = 0;
+  if (mode == 0) {
+    const int nr = sums != nullptr && rows != nullptr ? gemm_sum_rows(g, 0) : 0;
+    if (nr > 0) {
+      *rows = nr;
+      return launch_gemm<0, 1>(st, g, in, w, skip, out, sums, nullptr, nullptr);
+    }
+    return launch_gemm<0, 0>(st, g, in, w, skip, out, nullptr, nullptr, nullptr);
+  }
+  return launch_gemm<1, 0>(st, g, in, w, nullptr, out, nullptr, nullptr, nullptr);
+}
+
+int bf16_dgrad_reduce_rows(const ConvGeom& g) {
+  if (image_bf16_supported(g, 1)) return g.N <= kMaxPartialBlocks ? g.N : 0;
+  return bf16_gemm_supported(g, 1) ? gemm_sum_rows(g, 1) : 0;
+}
+
+int launch_bf16_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w,
+                             const void* packed, const void* stats, float* da3, double* partial) {
+  if ((K != 4 && K != 8) || bf16_dgrad_reduce_rows(g) == 0) return ABL_ERR_SHAPE;
+  const uint8_t* codes = static_cast<const uint8_t*>(packed);
+  const float* sp = static_cast<const float*>(stats);
+  if (image_bf16_supported(g, 1)) return launch_image_bf16_epi(st, g, K, dy, w, da3, partial, codes, sp);
+  if (K == 4) return launch_gemm<1, 4>(st, g, dy, w, nullptr, da3, partial, codes, sp);
+  return launch_gemm<1, 8>(st, g, dy, w, nullptr, da3, partial, codes, sp);
 }
 
 namespace {
@@ -534,37 +669,56 @@ bool image_bf16_supported(const ConvGeom& g, int mode) {
   return e_in < ((int64_t)1 << 31) && e_out < ((int64_t)1 << 31);
 }
 
-int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
-                      const float* skip, float* out, double* sums) {
-  if (!image_bf16_supported(g, mode)) return ABL_ERR_SHAPE;
-  const int Ng = mode == 0 ? g.Cout : g.Cin;
-  const int mt = image_mt(g);
-  const size_t lds = image_lds_bytes(g, mode);
-  const unsigned grid = (unsigned)((g.N + 7) / 8 * 8 * (Ng / IMG_NB));
-  auto kern = mode == 0 ? (mt == 4 ? image_bf16_kernel<0, 4> : mt == 8 ? image_bf16_kernel<0, 8> : image_bf16_kernel<0, 13>)
-                        : (mt == 4 ? image_bf16_kernel<1, 4> : mt == 8 ? image_bf16_kernel<1, 8> : image_bf16_kernel<1, 13>);
-  // more than the default 64 KB of LDS per block has to be asked for, once per kernel and device
-  // (the full 160 KB, so that the answer does not depend on the first shape seen)
-  {
-    static std::mutex mu;
-    static std::set<std::pair<int, const void*>> done;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) {
+namespace {
+// more than the default 64 KB of LDS per block has to be asked for, once per kernel and device
+// (the full 160 KB, so that the answer does not depend on the first shape seen)
+int allow_full_lds_bf16(const void* kern) {
+  static std::mutex mu;
+  static std::set<std::pair<int, const void*>> done;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return ABL_ERR_HIP;
+  }
+  const std::pair<int, const void*> key(dev, kern);
+  std::lock_guard<std::mutex> lock(mu);
+  if (done.find(key) == done.end()) {
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
       (void)hipGetLastError();
       return ABL_ERR_HIP;
     }
-    const std::pair<int, const void*> key(dev, reinterpret_cast<const void*>(kern));
-    std::lock_guard<std::mutex> lock(mu);
-    if (done.find(key) == done.end()) {
-      if (hipFuncSetAttribute(key.second, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-        (void)hipGetLastError();
-        return ABL_ERR_HIP;
-      }
-      done.insert(key);
-    }
+    done.insert(key);
   }
-  kern<<<grid, kThreads, lds, st>>>(in, w, mode == 0 ? skip : nullptr, out, mode == 0 ? sums : nullptr, g);
+  return ABL_OK;
+}
+
+template <int MODE, int EPI>
+int launch_image(hipStream_t st, const ConvGeom& g, const float* in, const float* w, const float* skip, float* out,
+                 double* sums, const uint8_t* codes, const float* stats) {
+  const int Ng = MODE == 0 ? g.Cout : g.Cin;
+  const int mt = image_mt(g);
+  const size_t lds = image_lds_bytes(g, MODE);
+  const unsigned grid = (unsigned)((g.N + 7) / 8 * 8 * (Ng / IMG_NB));
+  auto kern = mt == 4 ? image_bf16_kernel<MODE, 4, EPI> : mt == 8 ? image_bf16_kernel<MODE, 8, EPI>
+                                                                   : image_bf16_kernel<MODE, 13, EPI>;
+  if (int e = allow_full_lds_bf16(reinterpret_cast<const void*>(kern))) return e;
+  kern<<<grid, kThreads, lds, st>>>(in, w, skip, out, sums, g, codes, stats);
   return hip_status();
+}
+}  // namespace
+
+int launch_image_bf16(hipStream_t st, const ConvGeom& g, int mode, const float* in, const float* w,
+                      const float* skip, float* out, double* sums) {
+  if (!image_bf16_supported(g, mode)) return ABL_ERR_SHAPE;
+  if (mode == 0) return launch_image<0, 0>(st, g, in, w, skip, out, sums, nullptr, nullptr);
+  return launch_image<1, 0>(st, g, in, w, nullptr, out, nullptr, nullptr, nullptr);
+}
+
+int launch_image_bf16_epi(hipStream_t st, const ConvGeom& g, int K, const float* dy, const float* w, float* da3,
+                          double* partial, const uint8_t* codes, const float* stats) {
+  if (!image_bf16_supported(g, 1)) return ABL_ERR_SHAPE;
+  if (K == 4) return launch_image<1, 4>(st, g, dy, w, nullptr, da3, partial, codes, stats);
+  return launch_image<1, 8>(st, g, dy, w, nullptr, da3, partial, codes, stats);
 }
 
 }  // namespace abl

@@ -979,7 +979,7 @@ int launch_conv_fwd(hipStream_t st, const abl_shape& s, bool bf16, const float* 
     if (want) *rows = g.N;
     return launch_image_bf16(st, g, 0, a3, w, skip, y, want ? sums : nullptr);
   }
-  if (bf16 && bf16_gemm_supported(g, 0)) return launch_bf16_gemm(st, g, 0, a3, w, skip, y);
+  if (bf16 && bf16_gemm_supported(g, 0)) return launch_bf16_gemm(st, g, 0, a3, w, skip, y, sums, rows);
   // small images: the whole image resident in LDS, one row of sums per image
   if (!bf16 && image_f32_supported(g, 0)) {
     const bool want = sums != nullptr && rows != nullptr;
