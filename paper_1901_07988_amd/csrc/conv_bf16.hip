@@ -223,6 +223,25 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const float* __rest
   // epilogue: the lane holds channels n0 + wn0 + 16 j + 4 lk .. +3 of pixel m0 + wm0 + 16 i + li.
   // One 16-channel tile after the other, so that the sums of one tile only are live (all of them
   // at once cost the kernel a resident block per SIMD).
+  if constexpr (EPI == 0) {
+    // no sums: one pixel after the other, so that a wave's stores to a pixel's channels follow each other
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int64_t p = m0 + wm0 + 16 * i + li;
+      if (p >= Mg) continue;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int64_t o = p * Ng + n0 + wn0 + 16 * j + 4 * lk;
+        float4 v = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
+        if (skip != nullptr) {
+          const float4 sv = *reinterpret_cast<const float4*>(skip + o);
+          v.x += sv.x; v.y += sv.y; v.z += sv.z; v.w += sv.w;
+        }
+        *reinterpret_cast<float4*>(out + o) = v;
+      }
+    }
+    return;
+  }
   double* red = reinterpret_cast<double*>(lds);   // [2][2][BN], free since the barrier that ended the main loop
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
