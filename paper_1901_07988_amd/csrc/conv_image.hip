@@ -27,6 +27,7 @@
 
 #include <mutex>
 #include <set>
+#include <type_traits>
 #include <utility>
 
 #include "abl_internal.h"
@@ -580,6 +581,196 @@ int image_wgrad_splits(const ConvGeom& g) {
   return s < 1 ? 1 : s;
 }
 
+// ---- weight gradient (first half of Eq. 5) of 1x1 stride-1 layers from the packed codes ------------
+// dW[ci][co] = sum over the N H W pixels of A3~[pixel][ci] * dy[pixel][co], A3~ = ReLU of Eq. 10: one matrix
+// product whose contraction index is the pixel (four per MFMA).  One block owns a 128 (ci) x 256 (co) tile
+// and a share of the pixels; each wave keeps 128 x 64 of it (32 accumulator tiles) in registers.
+// The rows and columns of an MFMA tile need not be neighbouring channels: lane li supplies, for its pixel,
+// EIGHT input channels (8 li .. 8 li + 7, two 16-byte LDS reads) and FOUR output channels (4 li .. 4 li + 3
+// of the wave's 64: one 16-byte load of dy straight from global memory, no LDS), and the 8 x 4 register
+// pairs are the 32 MFMAs of a 4-pixel step - 3 operand instructions for 32 MFMAs instead of one 4-byte
+// read per operand register.  Only the dequantized activation goes through LDS (shared by the four waves,
+// dequantized once per block): 16 pixels at a time in two buffers, one 32- or 64-bit code word per thread
+// and chunk, dequantized between the MFMAs of the chunk before.  The step of Eq. 10 is a factor per input
+// channel and is applied to the sums at the end (max(step * x, 0) = step * max(x, 0), step > 0), so a
+// dequantized element costs a convert, an add and a max.  Each share of the pixels leaves its own copy of
+// dW, summed in a fixed order by the caller's launch.
+constexpr int PW_CI = 128, PW_CO = 256, PW_PX = 16;
+
+template <int K>
+__global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* __restrict__ codes,
+                                                                 const float* __restrict__ stats,
+                                                                 const float* __restrict__ dy,
+                                                                 float* __restrict__ dst, ConvGeom g, int splits) {
+  __shared__ __attribute__((aligned(16))) float AL[2][PW_PX][PW_CI];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  // ids 8 apart share an XCD and its L2: the blocks that read the same dy (same co tile and share of
+  // the pixels, different ci tiles) run there
+  const int n_ci = g.Cin / PW_CI, n_co = g.Cout / PW_CO;
+  int ci_blk, pair;
+  if ((n_co * splits) % 8 == 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    pair = (slot / n_ci) * 8 + xcd;
+    ci_blk = slot % n_ci;
+  } else {
+    pair = blockIdx.x / n_ci;
+    ci_blk = blockIdx.x % n_ci;
+  }
+  const int co_blk = pair % n_co, split = pair / n_co;
+  const int ci0 = ci_blk * PW_CI, co0 = co_blk * PW_CO + 64 * wave;
+  const int chunks = (int)(((int64_t)g.N * g.H * g.W) / PW_PX);   // N H W is a multiple of 16
+  const int c_begin = (int)((int64_t)split * chunks / splits), c_end = (int)((int64_t)(split + 1) * chunks / splits);
+
+  // ---- staging role: the 8 channels ci0 + 8 cg .. of pixel px of a chunk.  Eq. 10 without its step:
+  // (code - 2^(K-1) + fb) + 0.5 = code + offh, exact in fp32 while |fb| < 2^22.
+  const int cg = tid & 15, px = tid >> 4;
+  float offh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    offh[e] = (float)(reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci0 + 8 * cg + e] - (1 << (K - 1))) + 0.5f;
+  uint32_t c_lane = (uint32_t)((px * g.Cin + ci0 + 8 * cg) * K / 8);
+  const size_t c_chunk = (size_t)PW_PX * g.Cin * K / 8;          // bytes of codes per chunk
+  uint32_t cw[2][K / 4];                                          // code words of the chunks of either parity
+  // (a chunk index past the tensor's last one asks for the last one again: never used)
+  auto load_codes = [&](uint32_t (&w)[K / 4], int c) __attribute__((always_inline)) {
+    const uint8_t* cb = codes + (size_t)(c < chunks ? c : chunks - 1) * c_chunk;
+    asm volatile("" : "+v"(c_lane));
+    if constexpr (K == 4) {
+      w[0] = *reinterpret_cast<const uint32_t*>(cb + c_lane);
+    } else {
+      const uint2 t = *reinterpret_cast<const uint2*>(cb + c_lane);
+      w[0] = t.x;
+      w[K / 4 - 1] = t.y;
+    }
+  };
+  float vals[8];
+  uint32_t by[2];   // K = 4: the even and the odd codes of the word, one per byte (a byte converts in one instruction)
+  auto dequant = [&](const uint32_t (&w)[K / 4], int e) __attribute__((always_inline)) {
+    uint32_t code;
+    if constexpr (K == 4) {
+      if (e == 0) {
+        by[0] = w[0] & 0x0F0F0F0Fu;
+        by[1] = (w[0] >> 4) & 0x0F0F0F0Fu;
+        asm volatile("" : "+v"(by[0]), "+v"(by[1]));   // (kept as they are: not folded back into a field extract per code)
+      }
+      code = (by[e & 1] >> (8 * (e >> 1))) & 0xFFu;
+    } else {
+      code = (w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+    }
+    vals[e] = fmaxf((float)code + offh[e], 0.0f);   // Eq. 10 over its step, then the ReLU
+  };
+  // LDS column of channel 8 m + e: 4 m + e for e < 4, 64 + 4 m + (e - 4) otherwise, so that the 16 lanes
+  // of a read or a write cover 256 consecutive bytes
+  auto store_vals = [&](int buf, int half) __attribute__((always_inline)) {
+    *reinterpret_cast<floatx4*>(&AL[buf][px][64 * half + 4 * cg]) =
+        floatx4{vals[4 * half], vals[4 * half + 1], vals[4 * half + 2], vals[4 * half + 3]};
+  };
+
+  // ---- operands of the MFMAs.  dy: the lane's pixel of step s is 4 s + lk, its channels co0 + 4 li ..
+  uint32_t d_lane[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) d_lane[s] = 4u * (uint32_t)((4 * s + lk) * g.Cout + co0 + 4 * li);
+  const size_t d_chunk = (size_t)PW_PX * g.Cout;                 // floats of dy per chunk
+  floatx4 dyr[8];                                                // ring: slot 4 (chunk parity) + s, two chunks ahead
+  auto load_dy = [&](int slot, int c, int s) __attribute__((always_inline)) {
+    const char* db = reinterpret_cast<const char*>(dy + (size_t)(c < chunks ? c : chunks - 1) * d_chunk);
+    asm volatile("" : "+v"(d_lane[s]));
+    dyr[slot] = *reinterpret_cast<const floatx4*>(db + d_lane[s]);
+  };
+  floatx4 af[2][2];                                              // [set][half]: channels 8 li .. + 3, 8 li + 4 .. + 7
+  auto read_a = [&](int set, int half, int buf, int s) __attribute__((always_inline)) {
+    af[set][half] = *reinterpret_cast<const floatx4*>(&AL[buf][4 * s + lk][64 * half + 4 * li]);
+  };
+
+  floatx4 acc[8][4];   // [e][j]: rows = input channels 8 (4 lk + r) + e, column = output channel 4 li + j
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[e][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // One chunk (four steps of 32 MFMAs) of parity PAR.  Between the MFMAs, one piece behind every group of
+  // four: the reads of the next step's activation fragments, the dequantization of the next chunk (code
+  // words in cw[PAR ^ 1], to buffer PAR ^ 1), the request for the code word of the chunk after that and,
+  // behind a step's last MFMA, the request for dy of the same step two chunks ahead into the slot just
+  // used.  The barrier sits behind step 2: the buffer written here was last read before the previous
+  // chunk's barrier, and step 3 already reads the next chunk's first fragments from it.
+  auto chunk = [&](auto par, int c) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par)::value;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int cur = s & 1, slot = 4 * PAR + s;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
+                       : "+a"(acc[e][j])
+                       : "v"(af[cur][e >> 2][e & 3]), "v"(dyr[slot][j]));
+        if (e < 2) {
+          if (s < 3) read_a(cur ^ 1, e, PAR, s + 1);
+          else read_a(cur ^ 1, e, PAR ^ 1, 0);
+        } else if (s == 0) {
+          if (e == 2) load_codes(cw[PAR], c + 2);
+          else if (e >= 4) dequant(cw[PAR ^ 1], e - 4);           // values 0..3
+        } else if (s == 1) {
+          if (e >= 4) dequant(cw[PAR ^ 1], e);                    // values 4..7
+        } else if (s == 2) {
+          if (e == 3) store_vals(PAR ^ 1, 0);
+          else if (e == 5) store_vals(PAR ^ 1, 1);
+        }
+        if (e == 7) load_dy(slot, c + 2, s);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (s == 2) __syncthreads();
+    }
+  };
+
+  if (c_begin < c_end) {
+    load_codes(cw[0], c_begin);
+    load_codes(cw[1], c_begin + 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_dy(s, c_begin, s);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_dy(4 + s, c_begin + 1, s);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dequant(cw[0], e);
+    store_vals(0, 0);
+    store_vals(0, 1);
+    __syncthreads();
+    read_a(0, 0, 0, 0);
+    read_a(0, 1, 0, 0);
+    const int n = c_end - c_begin;
+    for (int i = 0; i + 1 < n; i += 2) {
+      chunk(std::integral_constant<int, 0>{}, c_begin + i);
+      chunk(std::integral_constant<int, 1>{}, c_begin + i + 1);
+    }
+    if (n & 1) chunk(std::integral_constant<int, 0>{}, c_end - 1);
+  }
+  // the MFMAs' results are read below by instructions the compiler does not know to depend on a
+  // matrix-core result: more wait states than the longest such hazard
+  asm volatile("s_nop 15\n\ts_nop 15");
+  float* out = dst + (size_t)split * g.Cin * g.Cout;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int ci = ci0 + 8 * (4 * lk + r);
+    const floatx4 st0 = *reinterpret_cast<const floatx4*>(stats + P_STEP * g.Cin + ci);
+    const floatx4 st1 = *reinterpret_cast<const floatx4*>(stats + P_STEP * g.Cin + ci + 4);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float st = e < 4 ? st0[e & 3] : st1[e & 3];
+      *reinterpret_cast<floatx4*>(out + (size_t)(ci + e) * g.Cout + co0 + 4 * li) =
+          floatx4{st * acc[e][0][r], st * acc[e][1][r], st * acc[e][2][r], st * acc[e][3][r]};
+    }
+  }
+}
+
+int rows_wgrad_splits(const ConvGeom& g) {
+  const int tiles = (g.Cin / PW_CI) * (g.Cout / PW_CO);
+  return tiles <= 256 ? 256 / tiles : 0;
+}
+
 // ---- 1x1 stride-1 convolutions with everything but the weights' and activations' way in registers ----
 // Eq. 4 (mode 0) and the second half of Eq. 5 (mode 1, optionally with the Eq. 6-7 sums) of a 1x1 layer
 // are one matrix product of the [rows = N H W] x [Cg] activation with the weights.  One block takes up to
@@ -923,6 +1114,28 @@ int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* pac
   auto kern = K == 4 ? image_wgrad_kernel<4, 14> : image_wgrad_kernel<8, 14>;
   if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
   kern<<<grid, kThreads, lds, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
+  return hip_status();
+}
+
+int rows_wgrad_copies(const ConvGeom& g, int K) {
+  if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0 || (K != 4 && K != 8)) return 0;
+  if (g.Cin % PW_CI != 0 || g.Cout % PW_CO != 0) return 0;
+  const int64_t M = (int64_t)g.N * g.H * g.W;
+  if (M % PW_PX != 0) return 0;
+  const int s = rows_wgrad_splits(g);
+  if ((int64_t)s * (g.Cin / PW_CI) * (g.Cout / PW_CO) < 224) return 0;   // built for one block per compute unit
+  if (M / PW_PX < (int64_t)8 * s) return 0;                              // ... with a long share of the pixels each
+  if (M * g.Cin >= ((int64_t)1 << 30) || M * g.Cout >= ((int64_t)1 << 30)) return 0;   // 32-bit byte offsets
+  return s;
+}
+
+int launch_rows_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+                      const float* dy, float* copies) {
+  const int s = rows_wgrad_copies(g, K);
+  if (s == 0) return ABL_ERR_SHAPE;
+  const unsigned grid = (unsigned)(s * (g.Cin / PW_CI) * (g.Cout / PW_CO));
+  auto kern = K == 4 ? rows_wgrad_kernel<4> : rows_wgrad_kernel<8>;
+  kern<<<grid, kThreads, 0, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
   return hip_status();
 }
 

@@ -258,6 +258,38 @@ def test_conv_wgrad_from_packed(G, oracle, s, K):
     assert rel(dw, dw_ref) < TOL
 
 
+PW_WGRAD_CASES = [
+    LayerShape(16, 32, 32, 256, 256, 1, 1, 1, 0),      # 2 tiles x 128 shares of exactly 8 chunks
+    LayerShape(41, 40, 20, 128, 256, 1, 1, 1, 0),      # 1 tile x 256 shares of 8 or 9 chunks
+    LayerShape(9, 48, 48, 384, 256, 1, 1, 1, 0),       # 3 tiles x 85 shares (not a multiple of 8) of 15 or 16
+    LayerShape(64, 14, 14, 1024, 256, 1, 1, 1, 0),     # config 5: 8 tiles x 32 shares of 24 or 25
+    LayerShape(64, 14, 14, 256, 1024, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("s", PW_WGRAD_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_pointwise_wgrad_in_registers(G, oracle, s, K):
+    """Weight gradient of 1x1 layers with at least 128 x 256 channels and 8 chunks of 16 pixels per
+    block: the kernel that keeps a 128 x 256 tile of dW in registers and applies the step of Eq. 10
+    to the sums.  Even and odd chunk counts per block, block counts that do and do not fill the
+    eight-way block mapping, a folded bias that moves the ReLU threshold between codes."""
+    o = oracle
+    print("case pointwise wgrad", s.as_tuple(), K, flush=True)
+    rng = np.random.default_rng(sum(s.as_tuple()) + K)
+    gamma, beta = rand_affine(rng, s.Cin)
+    a2 = (gamma * rng.standard_normal((s.N, s.H, s.W, s.Cin)) + beta).astype(np.float32)
+    q = o.quantize(a2, gamma, beta, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    z = np.zeros(s.Cin, np.float32)
+    st = G.stats_from_arrays(z, z + 1, z + 1, gamma, beta, cq, step, fb)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    a3t = np.maximum(o.dequantize(q, gamma, beta, K), 0)
+    dw_ref = o.conv_wgrad(a3t, dy, oshape(o, s))
+    dw = G.run_conv_wgrad(s, K, o.pack_codes(q, K), st, dy)
+    assert rel(dw, dw_ref) < TOL
+
+
 LAYER_CASES = [
     (synth.config1().shapes[0], "normal", "unit"),             # BASELINE config 1 as is
     (LayerShape(4, 32, 32, 16, 16), "normal", "random"),
