@@ -178,8 +178,8 @@ int image_wgrad_copies(const ConvGeom& g, int K);
 int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
                        const float* dy, float* copies);
 
-// Weight gradient of a 1x1 stride-1 layer from its K-bit codes with the block's 128 x 256 tile of dW in
-// registers (fp32; Cin a multiple of 128, Cout of 256, N H W of 16).  Each share of the pixels
+// Weight gradient of a 1x1 stride-1 layer from its K-bit codes with the block's 64 x 256 tile of dW in
+// registers (fp32; Cin a multiple of 64, Cout of 256, N H W of 16).  Each share of the pixels
 // writes its own copy of dW in `copies` ([rows_wgrad_copies][Cin][Cout] floats) for the caller to sum.
 // rows_wgrad_copies returns 0 when the shape is not supported.
 int rows_wgrad_copies(const ConvGeom& g, int K);

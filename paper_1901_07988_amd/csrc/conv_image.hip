@@ -583,19 +583,21 @@ int image_wgrad_splits(const ConvGeom& g) {
 
 // ---- weight gradient (first half of Eq. 5) of 1x1 stride-1 layers from the packed codes ------------
 // dW[ci][co] = sum over the N H W pixels of A3~[pixel][ci] * dy[pixel][co], A3~ = ReLU of Eq. 10: one matrix
-// product whose contraction index is the pixel (four per MFMA).  One block owns a 128 (ci) x 256 (co) tile
-// and a share of the pixels; each wave keeps 128 x 64 of it (32 accumulator tiles) in registers.
+// product whose contraction index is the pixel (four per MFMA).  One block owns a 64 (ci) x 256 (co) tile
+// and a share of the pixels; each wave keeps 64 x 64 of it (16 accumulator tiles) in registers.
 // The rows and columns of an MFMA tile need not be neighbouring channels: lane li supplies, for its pixel,
-// EIGHT input channels (8 li .. 8 li + 7, two 16-byte LDS reads) and FOUR output channels (4 li .. 4 li + 3
-// of the wave's 64: one 16-byte load of dy straight from global memory, no LDS), and the 8 x 4 register
-// pairs are the 32 MFMAs of a 4-pixel step - 3 operand instructions for 32 MFMAs instead of one 4-byte
+// FOUR input channels (4 li .. 4 li + 3: one 16-byte LDS read) and FOUR output channels (4 li .. 4 li + 3
+// of the wave's 64: one 16-byte load of dy straight from global memory, no LDS), and the 4 x 4 register
+// pairs are the 16 MFMAs of a 4-pixel step - 2 operand instructions for 16 MFMAs instead of one 4-byte
 // read per operand register.  Only the dequantized activation goes through LDS (shared by the four waves,
-// dequantized once per block): 16 pixels at a time in two buffers, one 32- or 64-bit code word per thread
+// dequantized once per block): 16 pixels at a time in two buffers, one 16- or 32-bit code word per thread
 // and chunk, dequantized between the MFMAs of the chunk before.  The step of Eq. 10 is a factor per input
 // channel and is applied to the sums at the end (max(step * x, 0) = step * max(x, 0), step > 0), so a
 // dequantized element costs a convert, an add and a max.  Each share of the pixels leaves its own copy of
-// dW, summed in a fixed order by the caller's launch.
-constexpr int PW_CI = 128, PW_CO = 256, PW_PX = 16;
+// dW, summed in a fixed order by the caller's launch: the chip's accumulators are 16 copies of a 1024 x 256
+// dW.  (A 128 x 256 tile per block - eight input channels per lane, 32 MFMAs from 3 operand instructions,
+// twice the accumulators and copies - measured 2-5 us slower on every shape tried.)
+constexpr int PW_CI = 64, PW_CO = 256, PW_PX = 16;
 
 template <int K>
 __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* __restrict__ codes,
@@ -623,49 +625,41 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
   const int chunks = (int)(((int64_t)g.N * g.H * g.W) / PW_PX);   // N H W is a multiple of 16
   const int c_begin = (int)((int64_t)split * chunks / splits), c_end = (int)((int64_t)(split + 1) * chunks / splits);
 
-  // ---- staging role: the 8 channels ci0 + 8 cg .. of pixel px of a chunk.  Eq. 10 without its step:
+  // ---- staging role: the four channels ci0 + 4 cg .. of pixel px of a chunk.  Eq. 10 without its step:
   // (code - 2^(K-1) + fb) + 0.5 = code + offh, exact in fp32 while |fb| < 2^22.
   const int cg = tid & 15, px = tid >> 4;
-  float offh[8];
+  float offh[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e)
-    offh[e] = (float)(reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci0 + 8 * cg + e] - (1 << (K - 1))) + 0.5f;
-  uint32_t c_lane = (uint32_t)((px * g.Cin + ci0 + 8 * cg) * K / 8);
+  for (int e = 0; e < 4; ++e)
+    offh[e] = (float)(reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + ci0 + 4 * cg + e] - (1 << (K - 1))) + 0.5f;
+  uint32_t c_lane = (uint32_t)((px * g.Cin + ci0 + 4 * cg) * K / 8);
   const size_t c_chunk = (size_t)PW_PX * g.Cin * K / 8;          // bytes of codes per chunk
-  uint32_t cw[2][K / 4];                                          // code words of the chunks of either parity
+  uint32_t cw[2];                                                 // code words of the chunks of either parity
   // (a chunk index past the tensor's last one asks for the last one again: never used)
-  auto load_codes = [&](uint32_t (&w)[K / 4], int c) __attribute__((always_inline)) {
+  auto load_codes = [&](uint32_t& w, int c) __attribute__((always_inline)) {
     const uint8_t* cb = codes + (size_t)(c < chunks ? c : chunks - 1) * c_chunk;
     asm volatile("" : "+v"(c_lane));
-    if constexpr (K == 4) {
-      w[0] = *reinterpret_cast<const uint32_t*>(cb + c_lane);
-    } else {
-      const uint2 t = *reinterpret_cast<const uint2*>(cb + c_lane);
-      w[0] = t.x;
-      w[K / 4 - 1] = t.y;
-    }
+    if constexpr (K == 4) w = *reinterpret_cast<const uint16_t*>(cb + c_lane);
+    else w = *reinterpret_cast<const uint32_t*>(cb + c_lane);
   };
-  float vals[8];
+  float vals[4];
   uint32_t by[2];   // K = 4: the even and the odd codes of the word, one per byte (a byte converts in one instruction)
-  auto dequant = [&](const uint32_t (&w)[K / 4], int e) __attribute__((always_inline)) {
+  auto dequant = [&](uint32_t w, int e) __attribute__((always_inline)) {
     uint32_t code;
     if constexpr (K == 4) {
       if (e == 0) {
-        by[0] = w[0] & 0x0F0F0F0Fu;
-        by[1] = (w[0] >> 4) & 0x0F0F0F0Fu;
+        by[0] = w & 0x0F0Fu;
+        by[1] = (w >> 4) & 0x0F0Fu;
         asm volatile("" : "+v"(by[0]), "+v"(by[1]));   // (kept as they are: not folded back into a field extract per code)
       }
       code = (by[e & 1] >> (8 * (e >> 1))) & 0xFFu;
     } else {
-      code = (w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+      code = (w >> (8 * e)) & 0xFFu;
     }
     vals[e] = fmaxf((float)code + offh[e], 0.0f);   // Eq. 10 over its step, then the ReLU
   };
-  // LDS column of channel 8 m + e: 4 m + e for e < 4, 64 + 4 m + (e - 4) otherwise, so that the 16 lanes
-  // of a read or a write cover 256 consecutive bytes
-  auto store_vals = [&](int buf, int half) __attribute__((always_inline)) {
-    *reinterpret_cast<floatx4*>(&AL[buf][px][64 * half + 4 * cg]) =
-        floatx4{vals[4 * half], vals[4 * half + 1], vals[4 * half + 2], vals[4 * half + 3]};
+  auto store_vals = [&](int buf) __attribute__((always_inline)) {
+    *reinterpret_cast<floatx4*>(&AL[buf][px][4 * cg]) = floatx4{vals[0], vals[1], vals[2], vals[3]};
   };
 
   // ---- operands of the MFMAs.  dy: the lane's pixel of step s is 4 s + lk, its channels co0 + 4 li ..
@@ -679,18 +673,18 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
     asm volatile("" : "+v"(d_lane[s]));
     dyr[slot] = *reinterpret_cast<const floatx4*>(db + d_lane[s]);
   };
-  floatx4 af[2][2];                                              // [set][half]: channels 8 li .. + 3, 8 li + 4 .. + 7
-  auto read_a = [&](int set, int half, int buf, int s) __attribute__((always_inline)) {
-    af[set][half] = *reinterpret_cast<const floatx4*>(&AL[buf][4 * s + lk][64 * half + 4 * li]);
+  floatx4 af[2];                                                 // two sets taking turns: channels 4 li .. + 3
+  auto read_a = [&](int set, int buf, int s) __attribute__((always_inline)) {
+    af[set] = *reinterpret_cast<const floatx4*>(&AL[buf][4 * s + lk][4 * li]);
   };
 
-  floatx4 acc[8][4];   // [e][j]: rows = input channels 8 (4 lk + r) + e, column = output channel 4 li + j
+  floatx4 acc[4][4];   // [e][j]: rows = input channels 4 (4 lk + r) + e, column = output channel 4 li + j
 #pragma unroll
-  for (int e = 0; e < 8; ++e)
+  for (int e = 0; e < 4; ++e)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[e][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // One chunk (four steps of 32 MFMAs) of parity PAR.  Between the MFMAs, one piece behind every group of
+  // One chunk (four steps of 16 MFMAs) of parity PAR.  Between the MFMAs, one piece behind every group of
   // four: the reads of the next step's activation fragments, the dequantization of the next chunk (code
   // words in cw[PAR ^ 1], to buffer PAR ^ 1), the request for the code word of the chunk after that and,
   // behind a step's last MFMA, the request for dy of the same step two chunks ahead into the slot just
@@ -702,25 +696,24 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
     for (int s = 0; s < 4; ++s) {
       const int cur = s & 1, slot = 4 * PAR + s;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
+      for (int e = 0; e < 4; ++e) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
                        : "+a"(acc[e][j])
-                       : "v"(af[cur][e >> 2][e & 3]), "v"(dyr[slot][j]));
-        if (e < 2) {
-          if (s < 3) read_a(cur ^ 1, e, PAR, s + 1);
-          else read_a(cur ^ 1, e, PAR ^ 1, 0);
+                       : "v"(af[cur][e]), "v"(dyr[slot][j]));
+        if (e == 0) {
+          if (s < 3) read_a(cur ^ 1, PAR, s + 1);
+          else read_a(cur ^ 1, PAR ^ 1, 0);
         } else if (s == 0) {
-          if (e == 2) load_codes(cw[PAR], c + 2);
-          else if (e >= 4) dequant(cw[PAR ^ 1], e - 4);           // values 0..3
+          if (e == 1) load_codes(cw[PAR], c + 2);
+          else dequant(cw[PAR ^ 1], e - 2);           // values 0, 1
         } else if (s == 1) {
-          if (e >= 4) dequant(cw[PAR ^ 1], e);                    // values 4..7
+          if (e >= 2) dequant(cw[PAR ^ 1], e);        // values 2, 3
         } else if (s == 2) {
-          if (e == 3) store_vals(PAR ^ 1, 0);
-          else if (e == 5) store_vals(PAR ^ 1, 1);
+          if (e == 1) store_vals(PAR ^ 1);
         }
-        if (e == 7) load_dy(slot, c + 2, s);
+        if (e == 3) load_dy(slot, c + 2, s);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (s == 2) __syncthreads();
@@ -735,12 +728,10 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
 #pragma unroll
     for (int s = 0; s < 4; ++s) load_dy(4 + s, c_begin + 1, s);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dequant(cw[0], e);
-    store_vals(0, 0);
-    store_vals(0, 1);
+    for (int e = 0; e < 4; ++e) dequant(cw[0], e);
+    store_vals(0);
     __syncthreads();
-    read_a(0, 0, 0, 0);
-    read_a(0, 1, 0, 0);
+    read_a(0, 0, 0);
     const int n = c_end - c_begin;
     for (int i = 0; i + 1 < n; i += 2) {
       chunk(std::integral_constant<int, 0>{}, c_begin + i);
@@ -754,12 +745,11 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
   float* out = dst + (size_t)split * g.Cin * g.Cout;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int ci = ci0 + 8 * (4 * lk + r);
-    const floatx4 st0 = *reinterpret_cast<const floatx4*>(stats + P_STEP * g.Cin + ci);
-    const floatx4 st1 = *reinterpret_cast<const floatx4*>(stats + P_STEP * g.Cin + ci + 4);
+    const int ci = ci0 + 4 * (4 * lk + r);
+    const floatx4 st4 = *reinterpret_cast<const floatx4*>(stats + P_STEP * g.Cin + ci);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float st = e < 4 ? st0[e & 3] : st1[e & 3];
+    for (int e = 0; e < 4; ++e) {
+      const float st = st4[e];
       *reinterpret_cast<floatx4*>(out + (size_t)(ci + e) * g.Cout + co0 + 4 * li) =
           floatx4{st * acc[e][0][r], st * acc[e][1][r], st * acc[e][2][r], st * acc[e][3][r]};
     }
@@ -1124,7 +1114,7 @@ int rows_wgrad_copies(const ConvGeom& g, int K) {
   if (M % PW_PX != 0) return 0;
   const int s = rows_wgrad_splits(g);
   if ((int64_t)s * (g.Cin / PW_CI) * (g.Cout / PW_CO) < 224) return 0;   // built for one block per compute unit
-  if (M / PW_PX < (int64_t)8 * s) return 0;                              // ... with a long share of the pixels each
+  if (M / PW_PX < (int64_t)16 * s) return 0;                             // ... with a long share of the pixels each
   if (M * g.Cin >= ((int64_t)1 << 30) || M * g.Cout >= ((int64_t)1 << 30)) return 0;   // 32-bit byte offsets
   return s;
 }

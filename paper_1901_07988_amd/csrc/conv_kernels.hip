@@ -1082,7 +1082,7 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
     }
     return hip_status();
   }
-  // 1x1 layers with 128 x 256 channels and more: the kernel that keeps its tile of dW in registers
+  // 1x1 layers with 64 x 256 channels and more: the kernel that keeps its tile of dW in registers
   if (const int copies = (!bf16 && !relu32) ? rows_wgrad_copies(g, K) : 0) {
     float* dst = copies == 1 ? dw : static_cast<float*>(scratch);
     if (int e = launch_rows_wgrad(st, g, K, packed, sp, dy, dst)) return e;

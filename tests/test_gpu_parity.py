@@ -259,10 +259,10 @@ def test_conv_wgrad_from_packed(G, oracle, s, K):
 
 
 PW_WGRAD_CASES = [
-    LayerShape(16, 32, 32, 256, 256, 1, 1, 1, 0),      # 2 tiles x 128 shares of exactly 8 chunks
-    LayerShape(41, 40, 20, 128, 256, 1, 1, 1, 0),      # 1 tile x 256 shares of 8 or 9 chunks
-    LayerShape(9, 48, 48, 384, 256, 1, 1, 1, 0),       # 3 tiles x 85 shares (not a multiple of 8) of 15 or 16
-    LayerShape(64, 14, 14, 1024, 256, 1, 1, 1, 0),     # config 5: 8 tiles x 32 shares of 24 or 25
+    LayerShape(16, 32, 32, 256, 256, 1, 1, 1, 0),      # 4 tiles x 64 shares of exactly 16 chunks
+    LayerShape(41, 40, 20, 128, 256, 1, 1, 1, 0),      # 2 tiles x 128 shares of 16 or 17 chunks
+    LayerShape(9, 48, 48, 384, 256, 1, 1, 1, 0),       # 6 tiles x 42 shares (not a multiple of 8) of 30 or 31
+    LayerShape(64, 14, 14, 1024, 256, 1, 1, 1, 0),     # config 5: 16 tiles x 16 shares of 49
     LayerShape(64, 14, 14, 256, 1024, 1, 1, 1, 0),
 ]
 
@@ -270,8 +270,8 @@ PW_WGRAD_CASES = [
 @pytest.mark.parametrize("s", PW_WGRAD_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
 @pytest.mark.parametrize("K", [4, 8])
 def test_pointwise_wgrad_in_registers(G, oracle, s, K):
-    """Weight gradient of 1x1 layers with at least 128 x 256 channels and 8 chunks of 16 pixels per
-    block: the kernel that keeps a 128 x 256 tile of dW in registers and applies the step of Eq. 10
+    """Weight gradient of 1x1 layers with at least 64 x 256 channels and 16 chunks of 16 pixels per
+    block: the kernel that keeps a 64 x 256 tile of dW in registers and applies the step of Eq. 10
     to the sums.  Even and odd chunk counts per block, block counts that do and do not fill the
     eight-way block mapping, a folded bias that moves the ReLU threshold between codes."""
     o = oracle
