@@ -182,8 +182,9 @@ int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* pac
 // registers (fp32; Cin a multiple of 64, Cout of 256, N H W of 16).  Each share of the pixels
 // writes its own copy of dW in `copies` ([rows_wgrad_copies][Cin][Cout] floats) for the caller to sum.
 // rows_wgrad_copies returns 0 when the shape is not supported.
-int rows_wgrad_copies(const ConvGeom& g, int K);
-int launch_rows_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+// bf16: operands rounded to bf16 and contracted 32 pixels per MFMA (N H W a multiple of 32).
+int rows_wgrad_copies(const ConvGeom& g, int K, bool bf16);
+int launch_rows_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                       const float* dy, float* copies);
 
 // 1x1 stride-1 convolutions (channel counts in multiples of 64) with the block's whole output tile in

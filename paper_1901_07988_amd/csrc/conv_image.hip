@@ -756,6 +756,180 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
   }
 }
 
+// The same weight gradient with bf16 operands (v_mfma_f32_16x16x32_bf16: 32 pixels per MFMA, a lane
+// supplies eight of them per operand register set).  The tile, the shares and the copies are those of the
+// fp32 kernel; a chunk is 32 pixels = one step of 16 MFMAs.  Both operands are rounded to bf16 by the
+// hardware's packed convert, which takes its two inputs from any two registers - so the regrouping from
+// "four channels of one pixel" (what a 16-byte load delivers) to "eight pixels of one channel" (what
+// the MFMA wants) costs nothing beyond the conversion itself: dy goes from eight 16-byte global loads
+// (the lane's eight pixels) through 16 converts into the four operand sets; the activation is
+// dequantized (Eq. 10 with its step, ReLU: the rounded value is that of the tiled bf16 kernel),
+// converted in pairs of neighbouring pixels and written to LDS as [pixel group][e][li][8 pixels], from
+// where a lane's operand set e is one 16-byte read.  dy runs four chunks ahead in a ring of 128 registers.
+constexpr int PB_PX = 32;
+
+template <int K>
+__global__ __launch_bounds__(kThreads, 1) void rows_wgrad_bf16_kernel(const uint8_t* __restrict__ codes,
+                                                                      const float* __restrict__ stats,
+                                                                      const float* __restrict__ dy,
+                                                                      float* __restrict__ dst, ConvGeom g,
+                                                                      int splits) {
+  __shared__ __attribute__((aligned(16))) uint32_t AL[2][4][4][16][4];   // [buffer][pixel group][e][li][4 pixel pairs]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lk = lane >> 4;
+  const int n_ci = g.Cin / PW_CI, n_co = g.Cout / PW_CO;
+  int ci_blk, pair;
+  if ((n_co * splits) % 8 == 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    pair = (slot / n_ci) * 8 + xcd;
+    ci_blk = slot % n_ci;
+  } else {
+    pair = blockIdx.x / n_ci;
+    ci_blk = blockIdx.x % n_ci;
+  }
+  const int co_blk = pair % n_co, split = pair / n_co;
+  const int ci0 = ci_blk * PW_CI, co0 = co_blk * PW_CO + 64 * wave;
+  const int chunks = (int)(((int64_t)g.N * g.H * g.W) / PB_PX);   // N H W is a multiple of 32
+  const int c_begin = (int)((int64_t)split * chunks / splits), c_end = (int)((int64_t)(split + 1) * chunks / splits);
+
+  // ---- staging role: channels ci0 + 4 cg .., pixels 2 q and 2 q + 1 of a chunk (q = 4 wave + lk: wave w
+  // stages pixel group w).  Eq. 10 as one add and one multiply: step * (code + offh), offh = fb - 2^(K-1) + 0.5.
+  const int cg = tid & 15, q = tid >> 4;
+  float stp[4], offh[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int c = ci0 + 4 * cg + e;
+    stp[e] = stats[P_STEP * g.Cin + c];
+    offh[e] = (float)(reinterpret_cast<const int32_t*>(stats)[P_FB * g.Cin + c] - (1 << (K - 1))) + 0.5f;
+  }
+  uint32_t c_lane = (uint32_t)((2 * q * g.Cin + ci0 + 4 * cg) * K / 8);
+  const size_t c_chunk = (size_t)PB_PX * g.Cin * K / 8;          // bytes of codes per chunk
+  const size_t c_pixel = (size_t)g.Cin * K / 8;                   // ... per pixel
+  // the four codes of a pixel are 16 or 32 bits; kept in a word of their own size until they are
+  // taken apart (widened on arrival they would have to be waited for at the top of the loop)
+  using code_t = typename std::conditional<K == 4, uint16_t, uint32_t>::type;
+  code_t cw[4][2];                                                // ring of four chunks: [slot][pixel]
+  // (a chunk index past the tensor's last one asks for the last one again: never used)
+  auto load_codes = [&](code_t (&w)[2], int c) __attribute__((always_inline)) {
+    const uint8_t* cb = codes + (size_t)(c < chunks ? c : chunks - 1) * c_chunk;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      asm volatile("" : "+v"(c_lane));
+      w[p] = *reinterpret_cast<const code_t*>(cb + p * c_pixel + c_lane);
+    }
+  };
+  auto stage = [&](const code_t (&w)[2], int buf) __attribute__((always_inline)) {
+    float v[2][4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t code = ((uint32_t)w[p] >> (K * e)) & ((1u << K) - 1u);
+        v[p][e] = fmaxf(stp[e] * ((float)code + offh[e]), 0.0f);   // Eq. 10, then the ReLU
+      }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const __bf16 lo = (__bf16)v[0][e], hi = (__bf16)v[1][e];
+      AL[buf][q >> 2][e][cg][q & 3] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+    }
+  };
+
+  // ---- operands.  dy: the lane's pixels are 8 lk .. 8 lk + 7 of the chunk, its channels co0 + 4 li ..
+  uint32_t d_lane = 4u * (uint32_t)(8 * lk * g.Cout + co0 + 4 * li);
+  const size_t d_chunk = (size_t)PB_PX * g.Cout;                 // floats of dy per chunk
+  floatx4 dyr[4][8];                                             // ring of four chunks: [slot][pixel]
+  auto load_dy = [&](int slot, int c) __attribute__((always_inline)) {
+    const float* db = dy + (size_t)(c < chunks ? c : chunks - 1) * d_chunk;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      asm volatile("" : "+v"(d_lane));
+      dyr[slot][i] = *reinterpret_cast<const floatx4*>(reinterpret_cast<const char*>(db + (size_t)i * g.Cout) + d_lane);
+    }
+  };
+  // (one set: the next chunk's fragments are read after this chunk's MFMAs have been issued)
+  bf16x8_t af[4];                                                // [e]: eight pixels of channel 4 li + e
+  auto read_a = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) af[e] = *reinterpret_cast<const bf16x8_t*>(&AL[buf][lk][e][li][0]);
+  };
+
+  floatx4 acc[4][4];   // [e][j]: rows = input channels 4 (4 lk + r) + e, column = output channel 4 li + j
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[e][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // One chunk, ring slot SLOT (= chunk index mod 4 from the block's first): convert its dy, contract,
+  // ask for dy of the chunk four ahead into the slot, dequantize the next chunk into the other buffer
+  // and ask for the codes of the chunk four after that one.  One barrier per chunk: the buffer written here was
+  // last read in the previous chunk, before that chunk's barrier.
+  auto chunk = [&](auto slot_c, int c) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_c)::value, PAR = SLOT & 1;
+    // (the fences keep the phases in this order: left alone, the scheduler starts on the code words of
+    // later chunks at the top of the loop and waits for every load in flight to get at them)
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      d[j] = bf16x8_t{(__bf16)dyr[SLOT][0][j], (__bf16)dyr[SLOT][1][j], (__bf16)dyr[SLOT][2][j], (__bf16)dyr[SLOT][3][j],
+                      (__bf16)dyr[SLOT][4][j], (__bf16)dyr[SLOT][5][j], (__bf16)dyr[SLOT][6][j], (__bf16)dyr[SLOT][7][j]};
+    // (the converted operands exist before the slot is asked for again: otherwise the conversions sink
+    // below the loads and the old contents of the slot are copied out of their way first)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(d[j]));
+    __builtin_amdgcn_sched_barrier(0);
+    load_dy(SLOT, c + 4);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[e][j]) : "v"(af[e]), "v"(d[j]));
+    __builtin_amdgcn_sched_barrier(0);
+    stage(cw[(SLOT + 1) & 3], PAR ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_codes(cw[(SLOT + 1) & 3], c + 5);
+    __syncthreads();
+    read_a(PAR ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (c_begin < c_end) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) load_codes(cw[t], c_begin + t);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) load_dy(t, c_begin + t);
+    stage(cw[0], 0);
+    load_codes(cw[0], c_begin + 4);
+    __syncthreads();
+    read_a(0);
+    const int n = c_end - c_begin;
+    int i = 0;
+    for (; i + 3 < n; i += 4) {
+      chunk(std::integral_constant<int, 0>{}, c_begin + i);
+      chunk(std::integral_constant<int, 1>{}, c_begin + i + 1);
+      chunk(std::integral_constant<int, 2>{}, c_begin + i + 2);
+      chunk(std::integral_constant<int, 3>{}, c_begin + i + 3);
+    }
+    if (i < n) chunk(std::integral_constant<int, 0>{}, c_begin + i);
+    if (i + 1 < n) chunk(std::integral_constant<int, 1>{}, c_begin + i + 1);
+    if (i + 2 < n) chunk(std::integral_constant<int, 2>{}, c_begin + i + 2);
+  }
+  // the MFMAs' results are read below by instructions the compiler does not know to depend on a
+  // matrix-core result: more wait states than the longest such hazard
+  asm volatile("s_nop 15\n\ts_nop 15");
+  float* out = dst + (size_t)split * g.Cin * g.Cout;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int ci = ci0 + 4 * (4 * lk + r);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      *reinterpret_cast<floatx4*>(out + (size_t)(ci + e) * g.Cout + co0 + 4 * li) =
+          floatx4{acc[e][0][r], acc[e][1][r], acc[e][2][r], acc[e][3][r]};
+  }
+}
+
 int rows_wgrad_splits(const ConvGeom& g) {
   const int tiles = (g.Cin / PW_CI) * (g.Cout / PW_CO);
   return tiles <= 256 ? 256 / tiles : 0;
@@ -1107,11 +1281,11 @@ int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* pac
   return hip_status();
 }
 
-int rows_wgrad_copies(const ConvGeom& g, int K) {
+int rows_wgrad_copies(const ConvGeom& g, int K, bool bf16) {
   if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0 || (K != 4 && K != 8)) return 0;
   if (g.Cin % PW_CI != 0 || g.Cout % PW_CO != 0) return 0;
   const int64_t M = (int64_t)g.N * g.H * g.W;
-  if (M % PW_PX != 0) return 0;
+  if (M % (bf16 ? PB_PX : PW_PX) != 0) return 0;
   const int s = rows_wgrad_splits(g);
   if ((int64_t)s * (g.Cin / PW_CI) * (g.Cout / PW_CO) < 224) return 0;   // built for one block per compute unit
   if (M / PW_PX < (int64_t)16 * s) return 0;                             // ... with a long share of the pixels each
@@ -1119,12 +1293,13 @@ int rows_wgrad_copies(const ConvGeom& g, int K) {
   return s;
 }
 
-int launch_rows_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+int launch_rows_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                       const float* dy, float* copies) {
-  const int s = rows_wgrad_copies(g, K);
+  const int s = rows_wgrad_copies(g, K, bf16);
   if (s == 0) return ABL_ERR_SHAPE;
   const unsigned grid = (unsigned)(s * (g.Cin / PW_CI) * (g.Cout / PW_CO));
-  auto kern = K == 4 ? rows_wgrad_kernel<4> : rows_wgrad_kernel<8>;
+  auto kern = bf16 ? (K == 4 ? rows_wgrad_bf16_kernel<4> : rows_wgrad_bf16_kernel<8>)
+                   : (K == 4 ? rows_wgrad_kernel<4> : rows_wgrad_kernel<8>);
   kern<<<grid, kThreads, 0, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
   return hip_status();
 }

@@ -961,7 +961,7 @@ size_t wgrad_partial_bytes(const abl_shape& s) {
   const WgradPlan p = wgrad_plan(g);
   const size_t n = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
   int img = image_wgrad_copies(g, 4);   // the register-resident kernels' copies (same count for K = 8)
-  const int pw = rows_wgrad_copies(g, 4);
+  const int pw = rows_wgrad_copies(g, 4, false);
   if (pw > img) img = pw;
   return ((size_t)(p.split > img ? p.split : img) * n + 255) / 256 * 256;
 }
@@ -1083,9 +1083,9 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
     return hip_status();
   }
   // 1x1 layers with 64 x 256 channels and more: the kernel that keeps its tile of dW in registers
-  if (const int copies = (!bf16 && !relu32) ? rows_wgrad_copies(g, K) : 0) {
+  if (const int copies = !relu32 ? rows_wgrad_copies(g, K, bf16) : 0) {
     float* dst = copies == 1 ? dw : static_cast<float*>(scratch);
-    if (int e = launch_rows_wgrad(st, g, K, packed, sp, dy, dst)) return e;
+    if (int e = launch_rows_wgrad(st, g, K, bf16, packed, sp, dy, dst)) return e;
     const int64_t n = (int64_t)g.Cin * g.Cout;
     if (copies > 1 && defer != nullptr) {
       *defer = DwSum{dst, copies, n, dw};

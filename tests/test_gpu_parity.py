@@ -290,6 +290,29 @@ def test_pointwise_wgrad_in_registers(G, oracle, s, K):
     assert rel(dw, dw_ref) < TOL
 
 
+@pytest.mark.parametrize("s", PW_WGRAD_CASES, ids=lambda s: "x".join(map(str, s.as_tuple())))
+@pytest.mark.parametrize("K", [4, 8])
+def test_pointwise_wgrad_in_registers_bf16(G, oracle, s, K):
+    """The same shapes with ABL_MATH_BF16: operands rounded to bf16 (the dequantized activation with its
+    step, as in the tiled kernel) and contracted 32 pixels per MFMA.  Against the oracle on operands
+    rounded the same way the difference is the order of the fp32 accumulation only."""
+    from paper_1901_07988_amd import binding as B
+    o = oracle
+    print("case pointwise wgrad bf16", s.as_tuple(), K, flush=True)
+    rng = np.random.default_rng(sum(s.as_tuple()) + K + 1)
+    gamma, beta = rand_affine(rng, s.Cin)
+    a2 = (gamma * rng.standard_normal((s.N, s.H, s.W, s.Cin)) + beta).astype(np.float32)
+    q = o.quantize(a2, gamma, beta, K)
+    cq, step, fb = o.quant_consts(gamma, beta, K)
+    z = np.zeros(s.Cin, np.float32)
+    st = G.stats_from_arrays(z, z + 1, z + 1, gamma, beta, cq, step, fb)
+    dy = rng.standard_normal((s.N, s.Ho, s.Wo, s.Cout)).astype(np.float32)
+    a3t = np.maximum(o.dequantize(q, gamma, beta, K), np.float32(0))
+    dw = G.run_conv_wgrad(s, K, o.pack_codes(q, K), st, dy, flags=B.ABL_MATH_BF16)
+    assert rel(dw, o.conv_wgrad(a3t, dy, oshape(o, s))) < TOL_BF16
+    assert rel(dw, o.conv_wgrad(to_bf16(a3t), to_bf16(dy), oshape(o, s))) < TOL
+
+
 LAYER_CASES = [
     (synth.config1().shapes[0], "normal", "unit"),             # BASELINE config 1 as is
     (LayerShape(4, 32, 32, 16, 16), "normal", "random"),
