@@ -83,7 +83,11 @@ def test_random_stacks(G, oracle, seed):
 def _random_resident_layer(rng):
     """A layer that one of the register-resident kernels takes in at least one direction: enough
     images (or rows) for 224 blocks of 64 output channels."""
-    kind = int(rng.integers(0, 3))
+    kind = int(rng.integers(0, 4))
+    if kind == 3:      # 1x1 with 64 x 256 channel tiles: rows_wgrad_kernel (tiles x shares of the pixels >= 224, >= 16 chunks each)
+        cin, cout = int(rng.choice([64, 128, 192, 320])), int(rng.choice([256, 512]))
+        shares = 256 // ((cin // 64) * (cout // 256))
+        return LayerShape(1, 16, 16 * shares + int(rng.integers(0, 40)), cin, cout, 1, 1, 1, 0)
     if kind == 0:      # 3x3 'same' on a small image: image_f32_kernel forward and / or data gradient
         H, W = int(rng.integers(2, 15)), int(rng.integers(2, 15))
         while H * W > 208:
@@ -106,8 +110,9 @@ def _random_resident_layer(rng):
 @pytest.mark.parametrize("seed", range(3))
 def test_random_layers_on_the_register_resident_kernels(G, oracle, seed):
     """Seeded random shapes large enough for the one-block-per-compute-unit kernels (whole image or
-    row block resident, output tile in accumulator registers): image sizes that leave ragged pixel
-    tiles, batches that are not multiples of eight, single-phase and multi-phase contractions."""
+    row block resident, output tile or a tile of dW in accumulator registers): image sizes that leave
+    ragged pixel tiles, batches that are not multiples of eight, single-phase and multi-phase
+    contractions, tile counts that do not divide the 256 blocks."""
     o = oracle
     rng = np.random.default_rng(3000 + seed)
     for _ in range(5):
