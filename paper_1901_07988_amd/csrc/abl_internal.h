@@ -173,9 +173,10 @@ int launch_image_dgrad_reduce(hipStream_t st, const ConvGeom& g, int K, const fl
 // Weight gradient of the same layers (14-pixel-wide images) from the K-bit codes (K = 4 / 8): one
 // block per 32 x 64 tile of (input, output) channels and share of the images, each share leaving
 // its own copy of dW in `copies` ([image_wgrad_copies][R][S][Cin][Cout] floats) for the caller to
-// sum.  image_wgrad_copies returns 0 when the shape is not supported.
+// sum.  image_wgrad_copies returns 0 when the shape is not supported.  bf16: operands rounded to bf16,
+// 16 pixels per MFMA.
 int image_wgrad_copies(const ConvGeom& g, int K);
-int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                        const float* dy, float* copies);
 
 // Weight gradient of a 1x1 stride-1 layer from its K-bit codes with the block's 64 x 256 tile of dW in

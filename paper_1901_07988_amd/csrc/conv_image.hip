@@ -372,7 +372,14 @@ constexpr int WG_CI = 32, WG_CO = 64;
 constexpr int WG_AP = 4 * WG_CI + 64;   // bytes per patch position: the four pixel groups of a read hit
 constexpr int WG_DP = 4 * WG_CO + 64;   // ... different quarters of the banks (48 resp. 80 words apart)
 
-template <int K, int IW>
+// BF16: operands rounded to bf16 on their way from LDS to the registers and contracted 16 at a time
+// (v_mfma_f32_16x16x16_bf16); the tiles and the copies are the same.  Here the contraction runs over the
+// positions of the PADDED rows (image width + 2 = 16 = one MFMA step per image row): dy is staged in the
+// same 16-wide rows with zeros in the two border columns, so the patch address of every tap is the
+// step's base plus a constant (no row wrap to track, 0 address instructions per read) and the two
+// products with the border columns vanish.  The patch has one position of margin before and after it
+// for the corner taps of the border columns.
+template <int K, int IW, bool BF16 = false>
 __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t* __restrict__ codes,
                                                                   const float* __restrict__ stats,
                                                                   const float* __restrict__ dy,
@@ -380,8 +387,8 @@ __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t*
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int PW = IW + 2;
   const int H = g.H, HW = H * IW;             // HW a multiple of 4
-  unsigned char* const AL = smem;                                 // [(H+2) * PW][WG_AP]
-  unsigned char* const DL = smem + (H + 2) * PW * WG_AP;          // [HW][WG_DP]
+  unsigned char* const AL = smem + (BF16 ? WG_AP : 0);            // [(H+2) * PW][WG_AP] (BF16: a position of margin on either side)
+  unsigned char* const DL = AL + ((H + 2) * PW + (BF16 ? 1 : 0)) * WG_AP;   // [HW][WG_DP]; BF16: [H * PW][WG_DP]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, lk = lane >> 4;
@@ -413,6 +420,16 @@ __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t*
       else if (bp < 2 * PW) pos = (H + 1) * PW + (bp - PW);
       else pos = (((bp - 2 * PW) >> 1) + 1) * PW + (((bp - 2 * PW) & 1) ? PW - 1 : 0);
       *reinterpret_cast<uint4*>(AL + pos * WG_AP + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+    if constexpr (BF16) {
+      // the two margin positions of the patch and the border columns of dy
+      if (tid < 2 * per)
+        *reinterpret_cast<uint4*>(AL + (tid < per ? -1 : (H + 2) * PW) * WG_AP + (tid % per) * 16) = make_uint4(0u, 0u, 0u, 0u);
+      constexpr int perd = WG_DP / 16;
+      for (int it = tid; it < 2 * H * perd; it += kThreads) {
+        const int bp = it / perd, piece = it - bp * perd;
+        *reinterpret_cast<uint4*>(DL + ((bp >> 1) * PW + ((bp & 1) ? PW - 1 : 0)) * WG_DP + piece * 16) = make_uint4(0u, 0u, 0u, 0u);
+      }
     }
   }
 
@@ -459,7 +476,12 @@ __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t*
     for (int u = 0; u < DU; ++u) {
       const int f = tid + kThreads * u;
       const int fi = f < ndy ? f : ndy - 1;
-      *reinterpret_cast<floatx4*>(DL + (fi >> 4) * WG_DP + (fi & 15) * 16) = dyv[u];
+      int row = fi >> 4;                       // pixel h * IW + w
+      if constexpr (BF16) {                    // ... to position h * PW + w + 1 of the padded rows
+        const int h = (row * (65536 / IW + 1)) >> 16;   // row / IW for row < 4096
+        row += h * (PW - IW) + 1;
+      }
+      *reinterpret_cast<floatx4*>(DL + row * WG_DP + (fi & 15) * 16) = dyv[u];
     }
 #pragma unroll
     for (int q = 0; q < CQ; ++q) {
@@ -531,6 +553,64 @@ __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t*
     __syncthreads();
     if (img + 1 < img_end) stage_load(img + 1);
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (BF16) {
+      // step j = image row j; the lane's positions are 4 i + lk of the padded row (element i of its operand:
+      // any assignment of the step's 16 positions to the MFMA's 16 k will do, and with this one the four lane
+      // groups of a read are at neighbouring positions - different banks, as in the fp32 loop).  Output
+      // position P of row j reads the patch at P + (tap row) * PW + (tap column) - 1.
+      static_assert(!BF16 || IW + 2 == 16, "one padded row per 16-deep MFMA");
+      struct FragB {
+        shortx4 d[2];   // four positions of dy[.][co0 + 16 (2 wo + o) + li]
+        shortx4 a[9];   // four positions of patch[. + tap][ci0 + 16 wc + li]
+      };
+      auto pack4 = [](float x0, float x1, float x2, float x3) __attribute__((always_inline)) {
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        const bf16x2_t lo = {(__bf16)x0, (__bf16)x1}, hi = {(__bf16)x2, (__bf16)x3};
+        const uint2 u = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+        return __builtin_bit_cast(shortx4, u);
+      };
+      auto read_frag = [&](FragB& f, int abase, int dbase) __attribute__((always_inline)) {
+#pragma unroll
+        for (int o = 0; o < 2; ++o)
+          f.d[o] = pack4(*reinterpret_cast<const float*>(DL + dbase + o * 64),
+                         *reinterpret_cast<const float*>(DL + dbase + 4 * WG_DP + o * 64),
+                         *reinterpret_cast<const float*>(DL + dbase + 8 * WG_DP + o * 64),
+                         *reinterpret_cast<const float*>(DL + dbase + 12 * WG_DP + o * 64));
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const int off = ((t / 3) * PW + (t % 3)) * WG_AP;
+          f.a[t] = pack4(*reinterpret_cast<const float*>(AL + abase + off),
+                         *reinterpret_cast<const float*>(AL + abase + 4 * WG_AP + off),
+                         *reinterpret_cast<const float*>(AL + abase + 8 * WG_AP + off),
+                         *reinterpret_cast<const float*>(AL + abase + 12 * WG_AP + off));
+        }
+      };
+      auto mma16 = [&](const FragB& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+          for (int o = 0; o < 2; ++o)
+            acc[t][o] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.d[o], f.a[t], acc[t][o], 0, 0, 0);
+      };
+      int abase = (lk - 1) * WG_AP + (16 * wc + li) * 4;
+      int dbase = lk * WG_DP + (32 * wo + li) * 4;
+      FragB f0, f1;
+      read_frag(f0, abase, dbase);
+      for (int j = 0; j + 1 < H; j += 2) {
+        abase += PW * WG_AP;
+        dbase += PW * WG_DP;
+        read_frag(f1, abase, dbase);
+        mma16(f0);
+        // (the last pair of an even count asks for one row past the image: the first row again, never used)
+        const bool more = j + 2 < H;
+        abase = more ? abase + PW * WG_AP : (lk - 1) * WG_AP + (16 * wc + li) * 4;
+        dbase = more ? dbase + PW * WG_DP : lk * WG_DP + (32 * wo + li) * 4;
+        read_frag(f0, abase, dbase);
+        mma16(f1);
+      }
+      if (H & 1) mma16(f0);
+      continue;
+    }
     // lane's pixel of step 0: lk (row 0, column lk); steps advance it by four
     int w = lk;
     int abase = lk * WG_AP + (16 * wc + li) * 4;
@@ -1269,13 +1349,15 @@ int image_wgrad_copies(const ConvGeom& g, int K) {
   return s;
 }
 
-int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, const void* packed, const float* stats,
+int launch_image_wgrad(hipStream_t st, const ConvGeom& g, int K, bool bf16, const void* packed, const float* stats,
                        const float* dy, float* copies) {
   const int s = image_wgrad_copies(g, K);
   if (s == 0) return ABL_ERR_SHAPE;
-  const size_t lds = (size_t)(g.H + 2) * (g.W + 2) * WG_AP + (size_t)g.H * g.W * WG_DP;
+  const size_t lds = bf16 ? (size_t)((g.H + 2) * (g.W + 2) + 2) * WG_AP + (size_t)g.H * (g.W + 2) * WG_DP
+                          : (size_t)(g.H + 2) * (g.W + 2) * WG_AP + (size_t)g.H * g.W * WG_DP;
   const unsigned grid = (unsigned)(s * (g.Cin / WG_CI) * (g.Cout / WG_CO));
-  auto kern = K == 4 ? image_wgrad_kernel<4, 14> : image_wgrad_kernel<8, 14>;
+  auto kern = bf16 ? (K == 4 ? image_wgrad_kernel<4, 14, true> : image_wgrad_kernel<8, 14, true>)
+                   : (K == 4 ? image_wgrad_kernel<4, 14> : image_wgrad_kernel<8, 14>);
   if (int e = allow_full_lds(reinterpret_cast<const void*>(kern))) return e;
   kern<<<grid, kThreads, lds, st>>>(static_cast<const uint8_t*>(packed), stats, dy, copies, g, s);
   return hip_status();

@@ -1071,9 +1071,9 @@ int launch_conv_wgrad_packed(hipStream_t st, const abl_shape& s, int K, bool bf1
   }
   if (K != 32 && use_halo_wgrad(g)) return launch_halo_wgrad(st, g, K, bf16, packed, sp, dy, scratch, dw);
   // 3x3 layers on 14-pixel-wide images: the image-resident kernel, one copy of dW per share of the images
-  if (const int copies = (!bf16 && !relu32) ? image_wgrad_copies(g, K) : 0) {
+  if (const int copies = !relu32 ? image_wgrad_copies(g, K) : 0) {
     float* dst = copies == 1 ? dw : static_cast<float*>(scratch);
-    if (int e = launch_image_wgrad(st, g, K, packed, sp, dy, dst)) return e;
+    if (int e = launch_image_wgrad(st, g, K, bf16, packed, sp, dy, dst)) return e;
     const int64_t n = (int64_t)g.R * g.S * g.Cin * g.Cout;
     if (copies > 1 && defer != nullptr) {
       *defer = DwSum{dst, copies, n, dw};
