@@ -521,13 +521,17 @@ __global__ __launch_bounds__(kFinThreads) void bwd_finalize_dwsum_kernel(const d
                                                                       float* __restrict__ dw, int straight) {
   __shared__ double sm[32][32];
   if ((int)blockIdx.x >= nfin && straight != 0) {
-    // large weight tensors in few copies: one output per thread, the copies added in order
-    const int64_t i = (int64_t)(blockIdx.x - nfin) * kFinThreads + threadIdx.x;
+    // large weight tensors in few copies: four consecutive outputs per thread (n is a multiple of 4
+    // in this mode), the copies added in order
+    const int64_t i = 4 * ((int64_t)(blockIdx.x - nfin) * kFinThreads + threadIdx.x);
     if (i >= n) return;
-    float a = wpartial[i];
+    float4 a = *reinterpret_cast<const float4*>(wpartial + i);
 #pragma unroll 8
-    for (int k = 1; k < ncopies; ++k) a += wpartial[(int64_t)k * n + i];
-    dw[i] = a;
+    for (int k = 1; k < ncopies; ++k) {
+      const float4 b = *reinterpret_cast<const float4*>(wpartial + (int64_t)k * n + i);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *reinterpret_cast<float4*>(dw + i) = a;
     return;
   }
   if ((int)blockIdx.x < nfin) {
@@ -922,8 +926,8 @@ int launch_bn_bwd_finish(hipStream_t st, const void* packed, const void* stats, 
   if (dwsum != nullptr) {
     // many small copies (one per pixel tile): 16 interleaved parts per output and a tree;
     // few large ones (split contraction): one thread per output
-    const bool straight = dwsum->copies <= 32 && dwsum->n >= 131072;
-    const unsigned wblocks = straight ? (unsigned)((dwsum->n + kFinThreads - 1) / kFinThreads)
+    const bool straight = dwsum->copies <= 32 && dwsum->n >= 131072 && dwsum->n % 4 == 0;
+    const unsigned wblocks = straight ? (unsigned)((dwsum->n / 4 + kFinThreads - 1) / kFinThreads)
                                       : (unsigned)((dwsum->n + 63) / 64);
     bwd_finalize_dwsum_kernel<<<nfin + wblocks, kFinThreads, 0, st>>>(partial, nb, M, C, sp, dgamma, dbeta, means, nfin,
                                                                       dwsum->partial, dwsum->copies, dwsum->n,
