@@ -20,6 +20,12 @@
 // and takes the per-channel sums (of y for the next layer's Eq. 1, or Eq. 6-7 from the layer's
 // codes).
 //
+// The file also holds the other kernels built for one block per compute unit with their results in
+// accumulator registers, each described where it is defined: the weight gradient of the same 3x3 layers
+// from the packed codes (image_wgrad_kernel, fp32 or bf16 operands), the 1x1 convolutions with long
+// contractions (rows_f32_kernel) and the weight gradient of 1x1 layers (rows_wgrad_kernel,
+// rows_wgrad_bf16_kernel).
+//
 // The MFMAs are written as inline assembly with the accumulator tied to the result: left to the
 // register allocator, some tiles get a result register of their own and are copied back every
 // k-step.  The compiler does not know these are matrix-core results, so the wait states they need
