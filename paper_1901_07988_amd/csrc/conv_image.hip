@@ -617,35 +617,52 @@ __global__ __launch_bounds__(kThreads, 1) void image_wgrad_kernel(const uint8_t*
       if (H & 1) mma16(f0);
       continue;
     }
-    // lane's pixel of step 0: lk (row 0, column lk); steps advance it by four
-    int w = lk;
-    int abase = lk * WG_AP + (16 * wc + li) * 4;
-    int dbase = lk * WG_DP + (32 * wo + li) * 4;
-    auto advance = [&]() __attribute__((always_inline)) {
-      w += 4;
-      const bool wrap = w >= IW;
-      w = wrap ? w - IW : w;
-      abase += (wrap ? 4 + (PW - IW) : 4) * WG_AP;
-      dbase += 4 * WG_DP;
-    };
+    // The lane's pixel of step j is 4 j + lk.  Seven steps are 28 pixels = two image rows, so within such a
+    // group the lane's patch positions are seven constants (the row wrap included) and from group to
+    // group everything moves by two rows: one address add per step instead of tracking the column (six
+    // vector instructions per step, each as dear as a third of an MFMA here).  H is even: H / 2 groups.
+    static_assert(BF16 || (2 * IW) % 4 == 0, "two rows are a whole number of steps");
+    constexpr int GS = 2 * IW / 4;   // steps per group: 7
+    int off7[GS];
+#pragma unroll
+    for (int j = 0; j < GS; ++j) {
+      const int p = lk + 4 * j, hh = p >= IW ? 1 : 0;
+      off7[j] = (hh * PW + p - hh * IW) * WG_AP + (16 * wc + li) * 4;
+    }
+    int ag = 0;                                        // the group's first patch row, in bytes
+    int dg = lk * WG_DP + (32 * wo + li) * 4;          // the lane's dy of the group's step 0
     Frag f0, f1;
 #pragma unroll
-    for (int t = 0; t < 9; ++t) read_a(f0, t, abase);
+    for (int t = 0; t < 9; ++t) read_a(f0, t, off7[0]);
 #pragma unroll
-    for (int o = 0; o < 2; ++o) read_d(f0, o, dbase);
-    const int steps = HW / 4;
-    for (int j = 0; j + 1 < steps; j += 2) {
-      advance();
-      __builtin_amdgcn_sched_barrier(0);
-      step(f0, f1, abase, dbase);
-      advance();
-      // (the last pair of an even count asks for one step past the image's pixels: address 0 - never used)
-      const bool more = j + 2 < steps;
-      const int ab = more ? abase : 0, db = more ? dbase : 0;
-      __builtin_amdgcn_sched_barrier(0);
-      step(f1, f0, ab, db);
+    for (int o = 0; o < 2; ++o) read_d(f0, o, dg);
+    // one group: fa holds the fragments of its step 0, the steps take fa, fb, fa, ... and leave the next
+    // group's first fragments in fb (the image's last step asks for address 0 - never used)
+    auto group = [&](Frag& fa, Frag& fb, bool last) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < GS; ++j) {
+        int an, dn;
+        if (j + 1 < GS) {
+          an = ag + off7[j + 1];
+          dn = dg + (j + 1) * 4 * WG_DP;
+        } else {
+          an = last ? 0 : ag + 2 * PW * WG_AP + off7[0];
+          dn = last ? 0 : dg + 2 * IW * WG_DP;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (j & 1) step(fb, fa, an, dn);
+        else step(fa, fb, an, dn);
+      }
+      ag += 2 * PW * WG_AP;
+      dg += 2 * IW * WG_DP;
+    };
+    static_assert(BF16 || GS % 2 == 1, "an odd number of steps: the two fragment sets swap roles from group to group");
+    const int groups = H / 2;
+    for (int grp = 0; grp + 1 < groups; grp += 2) {
+      group(f0, f1, false);
+      group(f1, f0, grp + 2 >= groups);
     }
-    if (steps & 1) mma(f0);
+    if (groups & 1) group(f0, f1, true);
   }
   // the MFMAs' results are read below by instructions the compiler does not know to depend on a
   // matrix-core result: more wait states than the longest such hazard
