@@ -840,11 +840,14 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_kernel(const uint8_t* 
       chunk(std::integral_constant<int, 0>{}, c_begin + i);
       chunk(std::integral_constant<int, 1>{}, c_begin + i + 1);
     }
+    // The MFMAs' results are read by instructions the compiler does not know to depend on a matrix-core
+    // result - here already where it copies the accumulators around the conditional last chunk: more wait
+    // states than the longest such hazard, tied to the accumulator written last (every other one is at
+    // least one MFMA, 32 cycles, older), so that no read of it is placed above the wait.
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[3][3]));
     if (n & 1) chunk(std::integral_constant<int, 0>{}, c_end - 1);
   }
-  // the MFMAs' results are read below by instructions the compiler does not know to depend on a
-  // matrix-core result: more wait states than the longest such hazard
-  asm volatile("s_nop 15\n\ts_nop 15");
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[3][3]));
   float* out = dst + (size_t)split * g.Cin * g.Cout;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -1020,8 +1023,8 @@ __global__ __launch_bounds__(kThreads, 1) void rows_wgrad_bf16_kernel(const uint
     if (i + 2 < n) chunk(std::integral_constant<int, 2>{}, c_begin + i + 2);
   }
   // the MFMAs' results are read below by instructions the compiler does not know to depend on a
-  // matrix-core result: more wait states than the longest such hazard
-  asm volatile("s_nop 15\n\ts_nop 15");
+  // matrix-core result: more wait states than the longest such hazard, tied to the accumulator written last
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[3][3]));
   float* out = dst + (size_t)split * g.Cin * g.Cout;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
